@@ -1,0 +1,125 @@
+/*
+ * libtvg - fused conv2d and depthwise conv2d operators for one AMD MI355X (gfx950).
+ *
+ * These are hand-written versions of the fused tensor operators that the TVM
+ * paper (arXiv 1802.04799) generates: a convolution with the element-wise
+ * operators that follow it applied to its output inside the same kernel
+ * (Section 3, "Operator Fusion": conv2d is "complex-out-fusable"), for the
+ * operator shapes of Table 2 (conv2d C1..C12 of ResNet-18, depthwise conv2d
+ * D1..D9 of MobileNet) and any other shape within the stated limits.
+ *
+ * Conventions common to every entry point
+ *   - Plain C ABI.  Every data pointer is a DEVICE pointer owned by the caller;
+ *     the descriptor and the size_t outputs are HOST pointers.
+ *   - The library never allocates, frees or synchronises.  Work is enqueued on
+ *     `hip_stream` (a hipStream_t passed as void*; NULL = the default stream) and
+ *     the call returns at once.
+ *   - Tensors are dense and contiguous: activations NCHW, dense weights OIHW
+ *     [k][c][r][s], depthwise weights [c][1][r][s].  x, w, residual and y share
+ *     `dtype`; scale, shift and bias are fp32 [k] whatever the dtype.
+ *   - Cross-correlation (no kernel flip), symmetric zero padding, dilation 1.
+ *     Output extent OH = floor((H + 2*pad_h - R) / stride_h) + 1 (must be >= 1).
+ *   - Fused tail applied to the fp32 accumulator, in this order:
+ *       t = acc + bias[k] (if bias); t = t*scale[k] + shift[k];
+ *       t += residual[n,k,oh,ow] (if residual); t = max(t, 0) (if TVG_RELU);
+ *       y = t rounded to dtype (bf16: round to nearest, ties to even).
+ *   - y must not overlap x or w.  y may be the same buffer as residual (each
+ *     element is read and then written by the same lane).
+ *   - All arguments are validated on the host before any device call, so error
+ *     paths can be exercised on a machine without a GPU.  Errors are return
+ *     codes; nothing is thrown, logged or aborted.  On error nothing is launched.
+ *   - Results are deterministic run to run (no floating-point atomics).
+ *   - Limits: every tensor must hold fewer than 2^31 elements; R, S <= 16;
+ *     strides 1..8; pad < kernel extent.
+ */
+#ifndef TVG_H
+#define TVG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    TVG_OK = 0,
+    TVG_ERR_NULL = 1,          /* a required pointer is NULL */
+    TVG_ERR_BAD_SHAPE = 2,     /* non-positive extent, empty output, stride/pad out of range */
+    TVG_ERR_UNSUPPORTED = 3,   /* unknown dtype or flag, tensor too large, kernel size not built */
+    TVG_ERR_WORKSPACE = 4,     /* workspace NULL or smaller than the query says */
+    TVG_ERR_LAUNCH = 5         /* the HIP runtime refused the launch */
+} tvg_status;
+
+typedef enum { TVG_F32 = 0, TVG_BF16 = 1 } tvg_dtype;
+
+enum { TVG_RELU = 1u };        /* bits of tvg_conv_desc.flags */
+
+typedef struct {
+    int32_t n, c, h, w;        /* input N, C (= IC), H, W                                   */
+    int32_t k, r, s;           /* output channels, kernel height, kernel width              */
+    int32_t stride_h, stride_w, pad_h, pad_w;
+    int32_t dtype;             /* tvg_dtype of x, w, residual, y                            */
+    uint32_t flags;            /* TVG_RELU or 0                                             */
+} tvg_conv_desc;               /* depthwise: k == c, r == s == 3                            */
+
+/*
+ * Bytes of scratch that tvg_conv2d_fused needs for this problem (0 when the
+ * problem is not split along the reduction axis).  Pure host computation.
+ * `bytes` is a host pointer.  Returns TVG_OK or the same validation error the
+ * operator itself would return.
+ */
+tvg_status tvg_conv2d_workspace_size(const tvg_conv_desc *desc, size_t *bytes);
+
+/* Always 0 bytes; present so both operators are driven the same way. */
+tvg_status tvg_dwconv2d_workspace_size(const tvg_conv_desc *desc, size_t *bytes);
+
+/*
+ * Dense fused conv2d (Table 2, rows C; fused tail per Section 3).  Implicit
+ * GEMM on the matrix cores: rows = output channels, columns = output pixels
+ * (n, oh, ow), reduction = (c, r, s); fp32 accumulate for both dtypes.
+ *   x        device, [n][c][h][w], dtype
+ *   w        device, [k][c][r][s], dtype
+ *   scale    device, fp32 [k]  (required; pass ones for a bare convolution)
+ *   shift    device, fp32 [k]  (required; pass zeros for a bare convolution)
+ *   bias     device, fp32 [k], or NULL
+ *   residual device, [n][k][oh][ow], dtype, or NULL
+ *   y        device, [n][k][oh][ow], dtype, written completely
+ *   workspace device, at least tvg_conv2d_workspace_size() bytes, 256-byte
+ *            aligned; may be NULL when that size is 0.  Contents are scratch.
+ */
+tvg_status tvg_conv2d_fused(const tvg_conv_desc *desc, const void *x, const void *w,
+                            const float *scale, const float *shift, const float *bias,
+                            const void *residual, void *y,
+                            void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Depthwise fused 3x3 conv2d, channel multiplier 1 (Table 2, rows D; same fused
+ * tail).  Bandwidth kernel on the vector ALUs, no matrix cores.  Arguments as
+ * above with w = [c][1][3][3]; desc->k must equal desc->c and r == s == 3;
+ * stride_h == stride_w in {1, 2}.  The workspace arguments are ignored.
+ */
+tvg_status tvg_dwconv2d_fused(const tvg_conv_desc *desc, const void *x, const void *w,
+                              const float *scale, const float *shift, const float *bias,
+                              const void *residual, void *y,
+                              void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * 3x3 stride-2 pad-1 max-pool, NCHW, padded taps ignored.  Support operator
+ * for running the ResNet-18 body (the stem's 112x112 output must become the
+ * 56x56 input of Table 2's C2).  x [n][c][h][w] -> y [n][c][oh][ow] with
+ * oh = floor((h - 1) / 2) + 1.  dtype as in tvg_dtype.
+ */
+tvg_status tvg_maxpool2d_3x3s2(int32_t n, int32_t c, int32_t h, int32_t w, int32_t dtype,
+                               const void *x, void *y, void *hip_stream);
+
+/* Static, NUL-terminated description of a status code (never NULL). */
+const char *tvg_status_string(tvg_status status);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int tvg_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TVG_H */

@@ -1,0 +1,225 @@
+"""ctypes binding of libtvg.so.  Names and argument order follow include/tvg.h."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(HERE, "libtvg.so")
+
+TVG_F32, TVG_BF16 = 0, 1
+TVG_RELU = 1
+TVG_OK = 0
+
+
+class TvgError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+class ConvDesc(ctypes.Structure):
+    """Mirror of tvg_conv_desc."""
+    _fields_ = [("n", ctypes.c_int32), ("c", ctypes.c_int32), ("h", ctypes.c_int32),
+                ("w", ctypes.c_int32), ("k", ctypes.c_int32), ("r", ctypes.c_int32),
+                ("s", ctypes.c_int32), ("stride_h", ctypes.c_int32), ("stride_w", ctypes.c_int32),
+                ("pad_h", ctypes.c_int32), ("pad_w", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("flags", ctypes.c_uint32)]
+
+    @property
+    def oh(self) -> int:
+        return (self.h + 2 * self.pad_h - self.r) // self.stride_h + 1
+
+    @property
+    def ow(self) -> int:
+        return (self.w + 2 * self.pad_w - self.s) // self.stride_w + 1
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load() -> ctypes.CDLL:
+    """Load libtvg.so (built in-tree by ``paper_1802_04799_amd.build``).
+
+    torch is imported first so that the library binds to the HIP runtime torch
+    already loaded; device pointers and streams are only valid within one runtime.
+    """
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: run `python -m paper_1802_04799_amd.build` "
+                          "(there is no fallback implementation)")
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
+    lib = ctypes.CDLL(_LIB_PATH, mode=ctypes.RTLD_GLOBAL)
+    vp, sz = ctypes.c_void_p, ctypes.c_size_t
+    dp = ctypes.POINTER(ConvDesc)
+    lib.tvg_conv2d_workspace_size.restype = ctypes.c_int
+    lib.tvg_conv2d_workspace_size.argtypes = [dp, ctypes.POINTER(sz)]
+    lib.tvg_dwconv2d_workspace_size.restype = ctypes.c_int
+    lib.tvg_dwconv2d_workspace_size.argtypes = [dp, ctypes.POINTER(sz)]
+    for f in (lib.tvg_conv2d_fused, lib.tvg_dwconv2d_fused):
+        f.restype = ctypes.c_int
+        f.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.tvg_maxpool2d_3x3s2.restype = ctypes.c_int
+    lib.tvg_maxpool2d_3x3s2.argtypes = [ctypes.c_int32] * 5 + [vp, vp, vp]
+    lib.tvg_status_string.restype = ctypes.c_char_p
+    lib.tvg_status_string.argtypes = [ctypes.c_int]
+    lib.tvg_version.restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load().tvg_status_string(int(status)).decode()
+
+
+def tvg_version() -> int:
+    return int(load().tvg_version())
+
+
+# ---------------------------------------------------------------------------------------
+# raw entry points: torch tensors (or None / int addresses) in, status code out
+# ---------------------------------------------------------------------------------------
+
+def _addr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def tvg_conv2d_workspace_size(desc: ConvDesc) -> int:
+    out = ctypes.c_size_t(0)
+    st = load().tvg_conv2d_workspace_size(ctypes.byref(desc), ctypes.byref(out))
+    if st != TVG_OK:
+        raise TvgError(st, "tvg_conv2d_workspace_size")
+    return int(out.value)
+
+
+def tvg_dwconv2d_workspace_size(desc: ConvDesc) -> int:
+    out = ctypes.c_size_t(0)
+    st = load().tvg_dwconv2d_workspace_size(ctypes.byref(desc), ctypes.byref(out))
+    if st != TVG_OK:
+        raise TvgError(st, "tvg_dwconv2d_workspace_size")
+    return int(out.value)
+
+
+def tvg_conv2d_fused(desc, x, w, scale, shift, bias, residual, y, workspace=None,
+                     workspace_bytes=0, stream=None) -> int:
+    return int(load().tvg_conv2d_fused(ctypes.byref(desc), _addr(x), _addr(w), _addr(scale),
+                                       _addr(shift), _addr(bias), _addr(residual), _addr(y),
+                                       _addr(workspace), workspace_bytes, _stream(stream)))
+
+
+def tvg_dwconv2d_fused(desc, x, w, scale, shift, bias, residual, y, workspace=None,
+                       workspace_bytes=0, stream=None) -> int:
+    return int(load().tvg_dwconv2d_fused(ctypes.byref(desc), _addr(x), _addr(w), _addr(scale),
+                                         _addr(shift), _addr(bias), _addr(residual), _addr(y),
+                                         _addr(workspace), workspace_bytes, _stream(stream)))
+
+
+def tvg_maxpool2d_3x3s2(n, c, h, w, dtype, x, y, stream=None) -> int:
+    return int(load().tvg_maxpool2d_3x3s2(n, c, h, w, dtype, _addr(x), _addr(y), _stream(stream)))
+
+
+# ---------------------------------------------------------------------------------------
+# conveniences: build the descriptor from tensors, allocate y and workspace with torch
+# ---------------------------------------------------------------------------------------
+
+def _dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.float32:
+        return TVG_F32
+    if t.dtype == torch.bfloat16:
+        return TVG_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _check(x, w, scale, shift, bias, residual):
+    for name, t in (("x", x), ("w", w), ("scale", scale), ("shift", shift), ("bias", bias),
+                    ("residual", residual)):
+        if t is None:
+            continue
+        if not t.is_cuda:
+            raise ValueError(f"{name} must be a device tensor")
+        if not t.is_contiguous():
+            raise ValueError(f"{name} must be contiguous")
+    import torch
+    for name, t in (("scale", scale), ("shift", shift), ("bias", bias)):
+        if t is not None and t.dtype != torch.float32:
+            raise TypeError(f"{name} must be float32")
+    if w.dtype != x.dtype or (residual is not None and residual.dtype != x.dtype):
+        raise TypeError("x, w and residual must share one dtype")
+
+
+def make_desc(x, w, stride, pad, relu, depthwise=False) -> ConvDesc:
+    n, c, h, wd = x.shape
+    k, _, r, s = w.shape
+    sh, sw = (stride, stride) if isinstance(stride, int) else stride
+    ph, pw = (pad, pad) if isinstance(pad, int) else pad
+    return ConvDesc(n, c, h, wd, k, r, s, sh, sw, ph, pw, _dtype_code(x), TVG_RELU if relu else 0)
+
+
+def conv2d_fused(x, w, scale, shift, bias=None, residual=None, *, stride=1, pad=0, relu=False,
+                 out=None, workspace=None, stream=None):
+    """y = tail(conv2d(x, w)); allocates y (and the workspace when needed) with torch."""
+    import torch
+    _check(x, w, scale, shift, bias, residual)
+    desc = make_desc(x, w, stride, pad, relu)
+    if w.shape[1] != x.shape[1]:
+        raise ValueError("weight input channels do not match x")
+    need = tvg_conv2d_workspace_size(desc)
+    if out is None:
+        out = torch.empty((desc.n, desc.k, desc.oh, desc.ow), dtype=x.dtype, device=x.device)
+    if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = tvg_conv2d_fused(desc, x, w, scale, shift, bias, residual, out, workspace, ws_bytes, stream)
+    if st != TVG_OK:
+        raise TvgError(st, "tvg_conv2d_fused")
+    return out
+
+
+def dwconv2d_fused(x, w, scale, shift, bias=None, residual=None, *, stride=1, pad=1, relu=False,
+                   out=None, stream=None):
+    import torch
+    _check(x, w, scale, shift, bias, residual)
+    desc = make_desc(x, w, stride, pad, relu, depthwise=True)
+    if out is None:
+        out = torch.empty((desc.n, desc.k, desc.oh, desc.ow), dtype=x.dtype, device=x.device)
+    st = tvg_dwconv2d_fused(desc, x, w, scale, shift, bias, residual, out, None, 0, stream)
+    if st != TVG_OK:
+        raise TvgError(st, "tvg_dwconv2d_fused")
+    return out
+
+
+def maxpool2d_3x3s2(x, out=None, stream=None):
+    import torch
+    if not x.is_cuda or not x.is_contiguous():
+        raise ValueError("x must be a contiguous device tensor")
+    n, c, h, w = x.shape
+    if out is None:
+        out = torch.empty((n, c, (h - 1) // 2 + 1, (w - 1) // 2 + 1), dtype=x.dtype, device=x.device)
+    st = tvg_maxpool2d_3x3s2(n, c, h, w, _dtype_code(x), x, out, stream)
+    if st != TVG_OK:
+        raise TvgError(st, "tvg_maxpool2d_3x3s2")
+    return out

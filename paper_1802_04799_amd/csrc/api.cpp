@@ -1,0 +1,126 @@
+// C ABI of libtvg: argument validation (host only, before any device call),
+// planning and dispatch to the kernel launchers.
+#include "tvg_internal.h"
+
+namespace {
+
+using tvg::ConvProblem;
+
+const int64_t kMaxElems = (int64_t)1 << 31;
+
+tvg_status make_problem(const tvg_conv_desc *d, bool depthwise, ConvProblem *out)
+{
+    if (!d) return TVG_ERR_NULL;
+    if (d->n < 1 || d->c < 1 || d->h < 1 || d->w < 1 || d->k < 1 || d->r < 1 || d->s < 1)
+        return TVG_ERR_BAD_SHAPE;
+    if (d->stride_h < 1 || d->stride_w < 1 || d->stride_h > 8 || d->stride_w > 8)
+        return TVG_ERR_BAD_SHAPE;
+    if (d->pad_h < 0 || d->pad_w < 0 || d->pad_h >= d->r || d->pad_w >= d->s)
+        return TVG_ERR_BAD_SHAPE;
+    if (d->h + 2 * d->pad_h < d->r || d->w + 2 * d->pad_w < d->s) return TVG_ERR_BAD_SHAPE;
+    if (d->dtype != TVG_F32 && d->dtype != TVG_BF16) return TVG_ERR_UNSUPPORTED;
+    if (d->flags & ~(uint32_t)TVG_RELU) return TVG_ERR_UNSUPPORTED;
+    if (d->r > 16 || d->s > 16) return TVG_ERR_UNSUPPORTED;
+    if (depthwise) {
+        if (d->k != d->c) return TVG_ERR_BAD_SHAPE;
+        if (d->r != 3 || d->s != 3) return TVG_ERR_UNSUPPORTED;
+        if (d->stride_h != d->stride_w || d->stride_h > 2) return TVG_ERR_UNSUPPORTED;
+    }
+    ConvProblem p;
+    p.N = d->n; p.IC = d->c; p.H = d->h; p.W = d->w; p.OC = d->k; p.R = d->r; p.S = d->s;
+    p.sh = d->stride_h; p.sw = d->stride_w; p.ph = d->pad_h; p.pw = d->pad_w;
+    p.OH = (d->h + 2 * d->pad_h - d->r) / d->stride_h + 1;
+    p.OW = (d->w + 2 * d->pad_w - d->s) / d->stride_w + 1;
+    const int64_t nx = (int64_t)d->n * d->c * d->h * d->w;
+    const int64_t ny = (int64_t)d->n * d->k * p.OH * p.OW;
+    const int64_t nw = (int64_t)d->k * (depthwise ? 1 : d->c) * d->r * d->s;
+    if (nx >= kMaxElems || ny >= kMaxElems || nw >= kMaxElems) return TVG_ERR_UNSUPPORTED;
+    p.K = (depthwise ? 1 : d->c) * d->r * d->s;
+    p.npix = d->n * p.OH * p.OW;
+    p.dtype = d->dtype;
+    p.relu = (d->flags & TVG_RELU) ? 1 : 0;
+    *out = p;
+    return TVG_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+tvg_status tvg_conv2d_workspace_size(const tvg_conv_desc *desc, size_t *bytes)
+{
+    if (!bytes) return TVG_ERR_NULL;
+    ConvProblem p;
+    tvg_status st = make_problem(desc, false, &p);
+    if (st != TVG_OK) return st;
+    *bytes = tvg::plan_conv(p).workspace_bytes;
+    return TVG_OK;
+}
+
+tvg_status tvg_dwconv2d_workspace_size(const tvg_conv_desc *desc, size_t *bytes)
+{
+    if (!bytes) return TVG_ERR_NULL;
+    ConvProblem p;
+    tvg_status st = make_problem(desc, true, &p);
+    if (st != TVG_OK) return st;
+    *bytes = 0;
+    return TVG_OK;
+}
+
+tvg_status tvg_conv2d_fused(const tvg_conv_desc *desc, const void *x, const void *w,
+                            const float *scale, const float *shift, const float *bias,
+                            const void *residual, void *y, void *workspace,
+                            size_t workspace_bytes, void *hip_stream)
+{
+    ConvProblem p;
+    tvg_status st = make_problem(desc, false, &p);
+    if (st != TVG_OK) return st;
+    if (!x || !w || !scale || !shift || !y) return TVG_ERR_NULL;
+    const tvg::ConvPlan plan = tvg::plan_conv(p);
+    if (plan.workspace_bytes > 0 && (!workspace || workspace_bytes < plan.workspace_bytes))
+        return TVG_ERR_WORKSPACE;
+    tvg::ConvPointers ptr{x, w, scale, shift, bias, residual, y, static_cast<float *>(workspace)};
+    return tvg::launch_conv_igemm(p, plan, ptr, static_cast<hipStream_t>(hip_stream));
+}
+
+tvg_status tvg_dwconv2d_fused(const tvg_conv_desc *desc, const void *x, const void *w,
+                              const float *scale, const float *shift, const float *bias,
+                              const void *residual, void *y, void *workspace,
+                              size_t workspace_bytes, void *hip_stream)
+{
+    (void)workspace;
+    (void)workspace_bytes;
+    ConvProblem p;
+    tvg_status st = make_problem(desc, true, &p);
+    if (st != TVG_OK) return st;
+    if (!x || !w || !scale || !shift || !y) return TVG_ERR_NULL;
+    tvg::ConvPointers ptr{x, w, scale, shift, bias, residual, y, nullptr};
+    return tvg::launch_dwconv3x3(p, ptr, static_cast<hipStream_t>(hip_stream));
+}
+
+tvg_status tvg_maxpool2d_3x3s2(int32_t n, int32_t c, int32_t h, int32_t w, int32_t dtype,
+                               const void *x, void *y, void *hip_stream)
+{
+    if (n < 1 || c < 1 || h < 1 || w < 1) return TVG_ERR_BAD_SHAPE;
+    if (dtype != TVG_F32 && dtype != TVG_BF16) return TVG_ERR_UNSUPPORTED;
+    if ((int64_t)n * c * h * w >= kMaxElems) return TVG_ERR_UNSUPPORTED;
+    if (!x || !y) return TVG_ERR_NULL;
+    return tvg::launch_maxpool3x3s2(n, c, h, w, dtype, x, y, static_cast<hipStream_t>(hip_stream));
+}
+
+const char *tvg_status_string(tvg_status status)
+{
+    switch (status) {
+    case TVG_OK: return "ok";
+    case TVG_ERR_NULL: return "a required pointer is NULL";
+    case TVG_ERR_BAD_SHAPE: return "bad shape, stride or padding";
+    case TVG_ERR_UNSUPPORTED: return "unsupported dtype, flag, size or kernel extent";
+    case TVG_ERR_WORKSPACE: return "workspace missing or too small";
+    case TVG_ERR_LAUNCH: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+int tvg_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,52 @@
+// Internal declarations shared by the translation units of libtvg (not installed).
+#ifndef TVG_INTERNAL_H
+#define TVG_INTERNAL_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tvg.h"
+
+namespace tvg {
+
+// Number of compute units the launch heuristics are tuned for (MI355X).  A
+// constant, not a device query, so that workspace sizes are a pure function of
+// the descriptor.
+constexpr int kComputeUnits = 256;
+
+struct ConvProblem {
+    int N, IC, H, W, OC, R, S, sh, sw, ph, pw, OH, OW;
+    int K;          // IC * R * S, the reduction length of the implicit GEMM
+    int npix;       // N * OH * OW, the number of GEMM columns
+    int dtype;      // tvg_dtype
+    int relu;
+};
+
+struct ConvPointers {
+    const void *x, *w;
+    const float *scale, *shift, *bias;
+    const void *residual;
+    void *y;
+    float *workspace;
+};
+
+// How the dense kernel is launched for a problem; a pure function of the problem.
+struct ConvPlan {
+    int mt;             // rows (output channels) per workgroup tile: 64 or 128
+    int nt;             // columns (pixels) per workgroup tile: 128
+    int splits;         // partitions of the reduction axis (1 = none)
+    int k_per_split;    // reduction elements per partition, a multiple of the K chunk
+    size_t workspace_bytes;
+};
+
+ConvPlan plan_conv(const ConvProblem &p);
+
+tvg_status launch_conv_igemm(const ConvProblem &p, const ConvPlan &plan, const ConvPointers &ptr,
+                             hipStream_t stream);
+tvg_status launch_dwconv3x3(const ConvProblem &p, const ConvPointers &ptr, hipStream_t stream);
+tvg_status launch_maxpool3x3s2(int N, int C, int H, int W, int dtype, const void *x, void *y,
+                               hipStream_t stream);
+
+}  // namespace tvg
+
+#endif
