@@ -1,0 +1,303 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused conv2d / depthwise conv2d hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--skip-extras] [--skip-cpu]
+
+One step = one pass over the 12 ResNet-18 conv2d shapes (TVM paper, Table 2, C1..C12) at
+batch 64 with bf16 inputs/outputs, fp32 accumulate and the fused scale/shift + ReLU tail:
+12 launches of tvg_conv2d_fused through the C ABI, inputs already resident in HBM.
+Prints ONE JSON line.  ``value`` is the whole step's throughput in TFLOP/s (2*MACs of the
+direct method over the step time).  ``roofline`` describes the layer (= kernel launch)
+that takes the most time inside the timed region; ``layers`` lists all twelve.  The
+depthwise layers (D1..D9), the fp32 batch-1 shapes and the ResNet-18 body are measured
+after the timed region and reported under their own keys.  ``cpu_baseline`` times the fp64
+CPU oracle on a bounded sample of the same workload on this machine's host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6      # dense bf16 MFMA, 256 CU x 4096 FLOP/clk x 2.4 GHz
+PEAK_FP32_TFLOPS = 157.3       # fp32 MFMA / vector
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--skip-extras", action="store_true",
+                    help="only the timed region (for profiler runs)")
+    ap.add_argument("--skip-cpu", action="store_true", help="do not time the CPU oracle")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only; --gpus must be 1 "
+                 "(the path shards along the batch axis with no exchange, see DESIGN.md)")
+    import numpy as np
+    import torch
+    import tvg_inputs as ti
+    import paper_1802_04799_amd as tvg
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    torch.cuda.set_device(0)
+    tvg.load()
+    dev = torch.device("cuda:0")
+
+    def to_dev(a, bf16):
+        t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32))
+        return (t.to(torch.bfloat16) if bf16 else t).to(dev)
+
+    class Layer:
+        """One fused conv launch with everything preallocated."""
+        def __init__(self, sh, seed, dtype, depthwise=False, copies=1):
+            self.sh, self.dtype, self.depthwise = sh, dtype, depthwise
+            bf = dtype == "bf16"
+            inp = ti.make_inputs(sh, seed, dtype)
+            self.host = inp
+            self.x = [to_dev(inp["x"], bf)]
+            self.w = [to_dev(inp["w"], bf)]
+            self.scale = to_dev(inp["scale"], False)
+            self.shift = to_dev(inp["shift"], False)
+            tdt = torch.bfloat16 if bf else torch.float32
+            self.y = [torch.empty(sh.y_shape(), dtype=tdt, device=dev)]
+            for _ in range(copies - 1):       # disjoint buffer sets for cold-cache timing
+                self.x.append(self.x[0].clone())
+                self.w.append(self.w[0].clone())
+                self.y.append(torch.empty_like(self.y[0]))
+            self.desc = tvg.ConvDesc(sh.n, sh.ic, sh.h, sh.w, sh.oc, sh.r, sh.s, sh.stride,
+                                     sh.stride, sh.pad, sh.pad,
+                                     tvg.TVG_BF16 if bf else tvg.TVG_F32, tvg.TVG_RELU)
+            self.ws_bytes = 0 if depthwise else tvg.tvg_conv2d_workspace_size(self.desc)
+            self.ws = torch.empty(max(self.ws_bytes, 1), dtype=torch.uint8, device=dev)
+            self.fn = tvg.tvg_dwconv2d_fused if depthwise else tvg.tvg_conv2d_fused
+            self.bytes = sh.algorithmic_bytes(2 if bf else 4)
+
+        def launch(self, i=0):
+            st = self.fn(self.desc, self.x[i], self.w[i], self.scale, self.shift, None, None,
+                         self.y[i], self.ws, self.ws_bytes, None)
+            if st != 0:
+                raise RuntimeError(f"{self.sh.name}: {tvg.status_string(st)}")
+
+    def time_loop(fn, iters, warmup=3):
+        """Mean milliseconds per call of fn over back-to-back calls on the current stream."""
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+    # ---------------------------------------------------------------- the timed region
+    shapes = ti.resnet18_convs(64)
+    layers = [Layer(sh, ti.layer_seed(4, i), "bf16") for i, sh in enumerate(shapes)]
+    step_flops = sum(l.sh.flops for l in layers)
+    step_bytes = sum(l.bytes for l in layers)
+
+    def step():
+        for l in layers:
+            l.launch()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    K = args.steps
+    # one event before every launch and one after the last: per-launch durations measured
+    # inside the timed region, on the stream the kernels run on
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(layers) + 1)] for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(K):
+        for i, l in enumerate(layers):
+            ev[k][i].record()
+            l.launch()
+        ev[k][len(layers)].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / K
+    value = step_flops / (wall / K) / 1e12
+
+    per_layer_ms = [sum(ev[k][i].elapsed_time(ev[k][i + 1]) for k in range(K)) / K
+                    for i in range(len(layers))]
+    layer_rows = []
+    for l, ms in zip(layers, per_layer_ms):
+        tf = l.sh.flops / (ms * 1e-3) / 1e12
+        gbs = l.bytes / (ms * 1e-3) / 1e9
+        ai = l.sh.flops / l.bytes
+        attainable = min(PEAK_BF16_TFLOPS, ai * PEAK_HBM_GBS / 1e3)
+        layer_rows.append({"name": l.sh.name, "us": round(ms * 1e3, 2), "tflops": round(tf, 1),
+                           "gbs": round(gbs, 1), "frac_mfma_peak": round(tf / PEAK_BF16_TFLOPS, 4),
+                           "frac_attainable": round(tf / attainable, 4),
+                           "bound": "mfma" if ai > PEAK_BF16_TFLOPS * 1e3 / PEAK_HBM_GBS else "hbm"})
+    dom = max(range(len(layers)), key=lambda i: per_layer_ms[i])
+    dl = layers[dom]
+    dom_tf = dl.sh.flops / (per_layer_ms[dom] * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": "conv_igemm_kernel<bf16> on " + dl.sh.name,
+                "achieved": round(dom_tf, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(dom_tf / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "flops_per_launch": dl.sh.flops, "avg_launch_us": round(per_layer_ms[dom] * 1e3, 2)}
+
+    out = {
+        "metric": "fused conv2d TFLOP/s (% MFMA peak); depthwise conv GB/s (% HBM peak)",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": K,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "configs[3]: the 12 ResNet-18 conv2d shapes of Table 2 (C1..C12), "
+                               "batch 64, bf16 in/out, fp32 accumulate, fused scale/shift+ReLU; "
+                               "one step = 12 launches",
+                   "step_gflop": round(step_flops / 1e9, 2), "step_mbytes": round(step_bytes / 1e6, 1),
+                   "frac_mfma_peak": round(value / PEAK_BF16_TFLOPS, 4)},
+        "roofline": roofline,
+        "layers": layer_rows,
+    }
+
+    # ------------------------------------------------------------ extras (not in `value`)
+    if not args.skip_extras:
+        del ev
+        # depthwise D1..D9, fp32, batch 1: warm (same buffers) and cold (rotating > 512 MB)
+        dw_rows = []
+        for i, sh in enumerate(ti.mobilenet_depthwise(1)):
+            nbytes = sh.algorithmic_bytes(4)
+            copies = min(1500, max(2, int(640e6 // nbytes) + 1))
+            l = Layer(sh, ti.layer_seed(3, i), "f32", depthwise=True, copies=copies)
+            warm = time_loop(lambda: l.launch(0), 200)
+            state = {"i": 0}
+
+            def cold_call():
+                l.launch(state["i"] % copies)
+                state["i"] += 1
+            cold = time_loop(cold_call, 2 * copies, warmup=copies)
+            dw_rows.append({"name": sh.name, "kbytes": round(nbytes / 1e3, 1),
+                            "warm_us": round(warm * 1e3, 2), "cold_us": round(cold * 1e3, 2),
+                            "warm_gbs": round(nbytes / (warm * 1e-3) / 1e9, 1),
+                            "cold_gbs": round(nbytes / (cold * 1e-3) / 1e9, 1)})
+            del l
+        # the same kernel at batch 64: HBM-sized traffic
+        dw64_rows = []
+        for i, sh in enumerate(ti.mobilenet_depthwise(64)):
+            l = Layer(sh, ti.layer_seed(3, 100 + i), "f32", depthwise=True, copies=2)
+            state = {"i": 0}
+
+            def call():
+                l.launch(state["i"] & 1)
+                state["i"] += 1
+            ms = time_loop(call, 50)
+            dw64_rows.append({"name": sh.name, "mbytes": round(l.bytes / 1e6, 1),
+                              "us": round(ms * 1e3, 2),
+                              "gbs": round(l.bytes / (ms * 1e-3) / 1e9, 1),
+                              "frac_hbm_peak": round(l.bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)})
+            del l
+        tot_b = sum(r["mbytes"] for r in dw64_rows) * 1e6
+        tot_t = sum(r["us"] for r in dw64_rows) * 1e-6
+        out["depthwise"] = {
+            "config3_batch1_fp32": dw_rows,
+            "batch64_fp32": dw64_rows,
+            "batch64_total_gbs": round(tot_b / tot_t / 1e9, 1),
+            "batch64_frac_hbm_peak": round(tot_b / tot_t / 1e9 / PEAK_HBM_GBS, 4),
+            "note": "algorithmic bytes (x, w, y, scale, shift moved once) / event time; batch-1 "
+                    "layers are 0.45-4 MB and launch-bound; cold = rotating disjoint buffers",
+        }
+        # fp32, batch 1 (configs[1]): launch/occupancy-bound, reported for completeness
+        rows = []
+        for i, sh in enumerate(ti.resnet18_convs(1)):
+            l = Layer(sh, ti.layer_seed(2, i), "f32")
+            ms = time_loop(lambda: l.launch(0), 200)
+            rows.append({"name": sh.name, "us": round(ms * 1e3, 2),
+                         "tflops": round(sh.flops / (ms * 1e-3) / 1e12, 2),
+                         "splits_ws_bytes": l.ws_bytes})
+            del l
+        tot = sum(r["us"] for r in rows) * 1e-6
+        fl = sum(s.flops for s in ti.resnet18_convs(1))
+        out["fp32_batch1"] = {"layers": rows, "total_us": round(tot * 1e6, 1),
+                              "tflops": round(fl / tot / 1e12, 2),
+                              "frac_fp32_peak": round(fl / tot / 1e12 / PEAK_FP32_TFLOPS, 4)}
+        # ResNet-18 body, batch 32, bf16 (configs[4]): 20 convs + 1 max-pool, 21 launches
+        out["resnet18_body"] = bench_body(tvg, ti, torch, np, dev, to_dev, time_loop)
+
+    if not args.skip_cpu:
+        out["cpu_baseline"] = cpu_baseline(ti, np)
+
+    print(json.dumps(out))
+
+
+def bench_body(tvg, ti, torch, np, dev, to_dev, time_loop):
+    n = 32
+    steps = ti.resnet18_body(n)
+    weights = {s.layer_index: ti.make_weights(s.shape, ti.layer_seed(5, s.layer_index), "bf16")
+               for s in steps if s.op == "conv"}
+    dw = {k: {"w": to_dev(p["w"], True), "scale": to_dev(p["scale"], False),
+              "shift": to_dev(p["shift"], False)} for k, p in weights.items()}
+    images = to_dev(ti.body_images(n, ti.layer_seed(5, 901)), True)
+    tensors = {0: images}
+    calls = []
+    for st in steps:
+        src = tensors[st.src]
+        if st.op == "conv":
+            sh = st.shape
+            desc = tvg.ConvDesc(sh.n, sh.ic, sh.h, sh.w, sh.oc, sh.r, sh.s, sh.stride, sh.stride,
+                                sh.pad, sh.pad, tvg.TVG_BF16, tvg.TVG_RELU if st.relu else 0)
+            y = torch.empty(sh.y_shape(), dtype=torch.bfloat16, device=dev)
+            need = tvg.tvg_conv2d_workspace_size(desc)
+            ws = torch.empty(max(need, 1), dtype=torch.uint8, device=dev)
+            p = dw[st.layer_index]
+            res = None if st.residual is None else tensors[st.residual]
+            calls.append((tvg.tvg_conv2d_fused, (desc, src, p["w"], p["scale"], p["shift"], None,
+                                                 res, y, ws, need, None)))
+        else:
+            nn, c, h, w = src.shape
+            y = torch.empty((nn, c, (h - 1) // 2 + 1, (w - 1) // 2 + 1), dtype=torch.bfloat16,
+                            device=dev)
+            calls.append((tvg.tvg_maxpool2d_3x3s2, (nn, c, h, w, tvg.TVG_BF16, src, y, None)))
+        tensors[st.dst] = y
+
+    def forward():
+        for fn, a in calls:
+            st = fn(*a)
+            if st != 0:
+                raise RuntimeError(tvg.status_string(st))
+
+    ms = time_loop(forward, 10)
+    flops = sum(s.shape.flops for s in steps if s.op == "conv")
+    return {"batch": n, "launches": len(calls), "ms": round(ms, 4),
+            "tflops": round(flops / (ms * 1e-3) / 1e12, 1),
+            "images_per_s": round(n / (ms * 1e-3), 1),
+            "frac_mfma_peak": round(flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}
+
+
+def cpu_baseline(ti, np):
+    """The fp64 oracle, as it stands, on a bounded sample of the timed workload."""
+    import oracle
+    batch = 16
+    shapes = ti.resnet18_convs(batch)
+    flops, secs = 0, 0.0
+    for i, sh in enumerate(shapes):
+        inp = ti.make_inputs(sh, ti.layer_seed(4, i), "bf16")
+        t = time.perf_counter()
+        oracle.conv2d_fused(inp["x"], inp["w"], inp["scale"], inp["shift"],
+                            stride=(sh.stride,) * 2, pad=(sh.pad,) * 2, relu=True)
+        secs += time.perf_counter() - t
+        flops += sh.flops
+    return {"value": round(flops / secs / 1e12, 6), "unit": "TFLOP/s",
+            "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"the same 12 shapes at batch {batch} of 64 ({flops / 1e9:.1f} GFLOP, "
+                      f"{secs:.1f} s), fp64 seven-loop direct convolution + fused tail",
+            "seconds": round(secs, 2)}
+
+
+if __name__ == "__main__":
+    main()

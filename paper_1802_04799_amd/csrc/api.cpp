@@ -53,7 +53,8 @@ tvg_status tvg_conv2d_workspace_size(const tvg_conv_desc *desc, size_t *bytes)
     ConvProblem p;
     tvg_status st = make_problem(desc, false, &p);
     if (st != TVG_OK) return st;
-    *bytes = tvg::plan_conv(p).workspace_bytes;
+    tvg::Patch3x3Plan patch;
+    *bytes = tvg::plan_conv3x3_patch(p, &patch) ? 0 : tvg::plan_conv(p).workspace_bytes;
     return TVG_OK;
 }
 
@@ -76,11 +77,18 @@ tvg_status tvg_conv2d_fused(const tvg_conv_desc *desc, const void *x, const void
     tvg_status st = make_problem(desc, false, &p);
     if (st != TVG_OK) return st;
     if (!x || !w || !scale || !shift || !y) return TVG_ERR_NULL;
-    const tvg::ConvPlan plan = tvg::plan_conv(p);
+    tvg::ConvPointers ptr{x, w, scale, shift, bias, residual, y, static_cast<float *>(workspace)};
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    tvg::Patch3x3Plan patch;
+    const bool patch_shape = tvg::plan_conv3x3_patch(p, &patch);
+    if (patch_shape && tvg::conv3x3_patch_pointers_ok(ptr))
+        return tvg::launch_conv3x3_patch(p, patch, ptr, stream);
+    // A patch-shaped problem reported a zero workspace; if its pointers rule the patch
+    // kernel out, the generic kernel runs it in a single pass over the reduction.
+    const tvg::ConvPlan plan = tvg::plan_conv(p, !patch_shape);
     if (plan.workspace_bytes > 0 && (!workspace || workspace_bytes < plan.workspace_bytes))
         return TVG_ERR_WORKSPACE;
-    tvg::ConvPointers ptr{x, w, scale, shift, bias, residual, y, static_cast<float *>(workspace)};
-    return tvg::launch_conv_igemm(p, plan, ptr, static_cast<hipStream_t>(hip_stream));
+    return tvg::launch_conv_igemm(p, plan, ptr, stream);
 }
 
 tvg_status tvg_dwconv2d_fused(const tvg_conv_desc *desc, const void *x, const void *w,

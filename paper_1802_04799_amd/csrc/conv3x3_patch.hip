@@ -1,0 +1,353 @@
+// bf16 3x3 (pad 1, stride 1 or 2) fused conv2d: implicit GEMM on MFMA with the
+// input staged ONCE per input-channel chunk as a zero-padded spatial patch in LDS
+// and re-read from there by all nine filter taps.
+//
+// Why a second dense kernel: the generic implicit-GEMM kernel gathers every
+// (pixel, k) operand from global memory, i.e. each input value is fetched nine
+// times for a 3x3 filter, one 2-byte load each, and the address arithmetic of
+// those loads outweighs the MFMA work.  Here a workgroup's NT consecutive output
+// pixels (n, oh, ow flattened) need a contiguous range of input rows; those
+// rows are fetched once per chunk of 16 input channels (cooperative fetch into
+// the shared scope, TVM paper Section 4.2), transposed on the way so that the 8
+// channels an MFMA lane consumes are one 16-byte LDS word, and every tap reads
+// the same patch at a shifted address.  Weights for the chunk (all nine taps)
+// are fetched as contiguous 144-byte runs of the OIHW tensor and transposed in
+// registers to tap-major.  The reduction order is (ic chunk, tap, ic in chunk).
+//
+// Patch geometry.  "Virtual rows": image n owns rows n*(H+2) .. n*(H+2)+H+1,
+// the first and last being zero padding, so a pixel (n, oh, ow) and tap (r, s)
+// read virtual row n*(H+2) + oh*stride + r, column ow*stride + s of a
+// (W+2)-wide padded row.  A pixel tile therefore needs one contiguous range of
+// virtual rows even when it straddles images.
+//
+// Pipeline per chunk: global loads of chunk c+1 are issued into registers, the
+// 9 taps x MFMA phase of chunk c runs from LDS, then (barrier) the registers are
+// written to LDS (barrier).  Two workgroups per CU overlap each other's phases
+// (Section 4.4: hide memory latency behind compute).
+#include <stdio.h>
+#include <stdlib.h>
+
+#include "tvg_device.h"
+#include "tvg_internal.h"
+
+namespace tvg {
+
+namespace {
+
+struct PatchArgs {
+    const bf16_t *x, *w;
+    const float *scale, *shift, *bias;
+    const bf16_t *residual;
+    bf16_t *y;
+    int N, IC, H, W, OC, OH, OW, npix, relu, mtiles;
+};
+
+constexpr int kPosBytes = 48;    // 16 channels (32 B) + 16 B padding: conflict-free 16-byte reads
+constexpr int kChunk = 16;       // input channels per chunk = K of one 32x32x16 MFMA
+
+__device__ __forceinline__ int xcd_remap(int bid, int nb)
+{
+    const int q = nb >> 3, rem = nb & 7;
+    const int xcd = bid & 7, local = bid >> 3;
+    return xcd < rem ? xcd * (q + 1) + local : rem * (q + 1) + (xcd - rem) * q + local;
+}
+
+__device__ __forceinline__ uint32_t half_of(uint32_t d, int hi) { return hi ? d >> 16 : d & 0xFFFFu; }
+
+// MT x NT output tile per workgroup of 256 threads; PT = patch load tasks per thread.
+template <int MT, int NT, int STRIDE, int PT>
+__global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a)
+{
+    constexpr int WTM = MT / 2, WTN = NT / 2;
+    constexpr int MI = WTM / 32, NJ = WTN / 32;
+    constexpr int ABYTES = 9 * MT * kPosBytes;
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    unsigned char *As = smem;              // [tap][oc][48 B]
+    unsigned char *Ps = smem + ABYTES;     // [virtual row][W + 2][48 B]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave & 1, wn = wave >> 1;
+    const int lrow = lane & 31, lhalf = lane >> 5;
+
+    const int tile = xcd_remap(blockIdx.x, gridDim.x);
+    const int m0 = (tile % a.mtiles) * MT;
+    const int n0 = (tile / a.mtiles) * NT;
+
+    const int H = a.H, W = a.W, HW = H * W, OHW = a.OH * a.OW;
+    const int VH = H + 2, PW = W + 2;
+
+    // ---- tile geometry (uniform) ---------------------------------------------------------
+    const int p_last = min(n0 + NT, a.npix) - 1;
+    const int na = n0 / OHW, oha = (n0 - na * OHW) / a.OW;
+    const int nb = p_last / OHW, ohb = (p_last - nb * OHW) / a.OW;
+    const int vr_lo = na * VH + oha * STRIDE;
+    const int nrows = nb * VH + ohb * STRIDE + 2 - vr_lo + 1;
+    const int npos = nrows * PW;
+
+    // ---- zero the patch once: padding rows and columns are never written again ------------
+    for (int i = tid; i < npos * (kPosBytes / 16); i += 256)
+        reinterpret_cast<uint4v *>(Ps)[i] = uint4v{0u, 0u, 0u, 0u};
+
+    // ---- per-thread patch load tasks: (virtual row, iw, channel octet), fixed for all chunks
+    int goff[PT], loff[PT];
+    {
+        const int per_octet = nrows * W;
+#pragma unroll
+        for (int j = 0; j < PT; ++j) {
+            const int t = tid + j * 256;
+            goff[j] = 0;
+            loff[j] = -1;
+            if (t < 2 * per_octet) {
+                const int octet = t >= per_octet;
+                const int rem = t - octet * per_octet;
+                const int vrow = rem / W, iw = rem - vrow * W;
+                const int v = vr_lo + vrow;
+                const int n = v / VH, ih = v - n * VH - 1;
+                if (ih >= 0 && ih < H && n < a.N) {
+                    goff[j] = (n * a.IC + octet * 8) * HW + ih * W + iw;
+                    loff[j] = (vrow * PW + iw + 1) * kPosBytes + octet * 16;
+                }
+            }
+        }
+    }
+
+    // ---- per-lane LDS offsets of this lane's pixels (MFMA B operand) -----------------------
+    int pb[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        const int p = n0 + wn * WTN + j * 32 + lrow;
+        pb[j] = lhalf * 16;
+        if (p < a.npix) {
+            const int n = p / OHW, rem = p - n * OHW;
+            const int oh = rem / a.OW, ow = rem - oh * a.OW;
+            pb[j] += ((n * VH + oh * STRIDE - vr_lo) * PW + ow * STRIDE) * kPosBytes;
+        }
+    }
+
+    // ---- weight task: one output channel, one octet of input channels, all nine taps -------
+    const bool wtask = tid < MT * 2;
+    const int w_ocl = tid >> 1, w_oct = tid & 1;
+    const bool wvalid = wtask && (m0 + w_ocl) < a.OC;
+    const bf16_t *wsrc = a.w + ((size_t)(wvalid ? m0 + w_ocl : 0) * a.IC + w_oct * 8) * 9;
+
+    uint4v preg[PT];
+    uint4v wreg[9];
+
+    auto load_chunk = [&](int c) {
+        const bf16_t *xc = a.x + (size_t)c * kChunk * HW;
+#pragma unroll
+        for (int j = 0; j < PT; ++j) {
+            const bf16_t *src = xc + goff[j];
+            uint32_t v[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t lo = src[(2 * q) * HW], hi = src[(2 * q + 1) * HW];
+                v[q] = lo | (hi << 16);
+            }
+            preg[j] = uint4v{v[0], v[1], v[2], v[3]};
+        }
+        if (wtask) {
+            const uint4v *ws = reinterpret_cast<const uint4v *>(wsrc + (size_t)c * kChunk * 9);
+#pragma unroll
+            for (int i = 0; i < 9; ++i) wreg[i] = ws[i];
+        }
+    };
+
+    auto store_chunk = [&]() {
+#pragma unroll
+        for (int j = 0; j < PT; ++j)
+            if (loff[j] >= 0) *reinterpret_cast<uint4v *>(Ps + loff[j]) = preg[j];
+        if (wtask) {
+            // wreg holds 8 channels x 9 taps, tap fastest; emit one 8-channel vector per tap
+            uint32_t d[36];
+#pragma unroll
+            for (int i = 0; i < 9; ++i)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) d[i * 4 + q] = wvalid ? wreg[i][q] : 0u;
+#pragma unroll
+            for (int tap = 0; tap < 9; ++tap) {
+                uint32_t o[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int e0 = (2 * q) * 9 + tap, e1 = (2 * q + 1) * 9 + tap;
+                    o[q] = half_of(d[e0 >> 1], e0 & 1) | (half_of(d[e1 >> 1], e1 & 1) << 16);
+                }
+                *reinterpret_cast<uint4v *>(As + (tap * MT + w_ocl) * kPosBytes + w_oct * 16) =
+                    uint4v{o[0], o[1], o[2], o[3]};
+            }
+        }
+    };
+
+    float16v acc[MI][NJ];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    const int nchunks = a.IC / kChunk;
+    load_chunk(0);
+    __syncthreads();          // patch zeroing complete before the first real data lands
+    store_chunk();
+    __syncthreads();
+
+    const unsigned char *Abase = As + (wm * WTM + lrow) * kPosBytes + lhalf * 16;
+    for (int c = 0; c < nchunks; ++c) {
+        if (c + 1 < nchunks) load_chunk(c + 1);
+
+#pragma unroll
+        for (int tap = 0; tap < 9; ++tap) {
+            const int r = tap / 3, s = tap - r * 3;
+            const int toff = (r * PW + s) * kPosBytes;
+            uint4v af[MI], bf[NJ];
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+                af[i] = *reinterpret_cast<const uint4v *>(Abase + (tap * MT + i * 32) * kPosBytes);
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+                bf[j] = *reinterpret_cast<const uint4v *>(Ps + pb[j] + toff);
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        __builtin_bit_cast(bf16x8v, af[i]), __builtin_bit_cast(bf16x8v, bf[j]),
+                        acc[i][j], 0, 0, 0);
+        }
+
+        if (c + 1 < nchunks) {
+            __syncthreads();
+            store_chunk();
+            __syncthreads();
+        }
+    }
+
+    // ---- fused tail on the accumulators -------------------------------------------------
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        const int p = n0 + wn * WTN + j * 32 + lrow;
+        if (p >= a.npix) continue;
+        const int n = p / OHW, rem = p - n * OHW;
+        const int obase = n * a.OC * OHW + rem;
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int oc = m0 + wm * WTM + i * 32 + 8 * (v >> 2) + 4 * lhalf + (v & 3);
+                if (oc >= a.OC) continue;
+                fused_tail_store<bf16_t>(acc[i][j][v], a.scale[oc], a.shift[oc],
+                                         a.bias ? a.bias[oc] : 0.0f, a.residual, a.y,
+                                         obase + oc * OHW, a.relu != 0);
+            }
+        }
+    }
+}
+
+// Largest number of virtual rows any pixel tile of NT pixels needs.
+int max_patch_rows(const ConvProblem &p, int nt)
+{
+    const int OHW = p.OH * p.OW, VH = p.H + 2;
+    int best = 0;
+    for (long n0 = 0; n0 < p.npix; n0 += nt) {
+        const long last = (n0 + nt < p.npix ? n0 + nt : p.npix) - 1;
+        const int na = (int)(n0 / OHW), oha = (int)((n0 - (long)na * OHW) / p.OW);
+        const int nb = (int)(last / OHW), ohb = (int)((last - (long)nb * OHW) / p.OW);
+        const int rows = nb * VH + ohb * p.sh + 2 - (na * VH + oha * p.sh) + 1;
+        if (rows > best) best = rows;
+    }
+    return best;
+}
+
+template <int MT, int NT, int STRIDE, int PT>
+tvg_status launch_instance(const PatchArgs &a, int ntiles, size_t lds, hipStream_t stream)
+{
+    auto kernel = conv3x3_patch_kernel<MT, NT, STRIDE, PT>;
+    static bool configured = false;      // opt in to > 64 KB of dynamic LDS once per instance
+    if (!configured) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+            return TVG_ERR_LAUNCH;
+        configured = true;
+    }
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(a.mtiles * ntiles)), dim3(256), lds, stream, a);
+    return hipGetLastError() == hipSuccess ? TVG_OK : TVG_ERR_LAUNCH;
+}
+
+template <int MT, int NT, int STRIDE>
+tvg_status launch_pt(const PatchArgs &a, int ntiles, size_t lds, int pt, hipStream_t stream)
+{
+    if (pt <= 2) return launch_instance<MT, NT, STRIDE, 2>(a, ntiles, lds, stream);
+    if (pt <= 4) return launch_instance<MT, NT, STRIDE, 4>(a, ntiles, lds, stream);
+    return launch_instance<MT, NT, STRIDE, 8>(a, ntiles, lds, stream);
+}
+
+template <int MT, int NT>
+tvg_status launch_stride(const PatchArgs &a, int stride, int ntiles, size_t lds, int pt,
+                         hipStream_t stream)
+{
+    return stride == 1 ? launch_pt<MT, NT, 1>(a, ntiles, lds, pt, stream)
+                       : launch_pt<MT, NT, 2>(a, ntiles, lds, pt, stream);
+}
+
+}  // namespace
+
+bool conv3x3_patch_pointers_ok(const ConvPointers &ptr)
+{
+    return reinterpret_cast<uintptr_t>(ptr.w) % 16 == 0;   // weights are read as 16-byte vectors
+}
+
+bool plan_conv3x3_patch(const ConvProblem &p, Patch3x3Plan *plan)
+{
+    if (p.dtype != TVG_BF16 || p.R != 3 || p.S != 3 || p.ph != 1 || p.pw != 1) return false;
+    if (p.sh != p.sw || (p.sh != 1 && p.sh != 2)) return false;
+    if (p.IC % kChunk != 0) return false;
+    int force_mt = 0, force_nt = 0;
+    if (const char *e = getenv("TVG_FORCE_TILE")) sscanf(e, "%d,%d", &force_mt, &force_nt);
+    // Tile choice: fill 256 CUs twice over when the problem allows; prefer the largest tile.
+    const int mts[] = {128, 64}, nts[] = {128, 64};
+    Patch3x3Plan best{};
+    bool found = false;
+    for (int mt : mts) {
+        if (mt == 128 && p.OC <= 64) continue;
+        if (force_mt && mt != force_mt) continue;
+        for (int nt : nts) {
+            if (force_nt && nt != force_nt) continue;
+            const int rows = max_patch_rows(p, nt);
+            const int pt = (2 * rows * p.W + 255) / 256;
+            const size_t lds = (size_t)9 * mt * kPosBytes + (size_t)rows * (p.W + 2) * kPosBytes;
+            if (pt > 8 || lds > 80 * 1024) continue;
+            const long tiles = (long)((p.OC + mt - 1) / mt) * ((p.npix + nt - 1) / nt);
+            Patch3x3Plan cand{mt, nt, pt, rows, lds, tiles};
+            if (!found) { best = cand; found = true; }
+            // take a smaller tile only while the larger one leaves CUs idle
+            else if (best.tiles < 2 * kComputeUnits && tiles > best.tiles) best = cand;
+        }
+    }
+    if (!found) return false;
+    *plan = best;
+    return true;
+}
+
+tvg_status launch_conv3x3_patch(const ConvProblem &p, const Patch3x3Plan &plan,
+                                const ConvPointers &ptr, hipStream_t stream)
+{
+    PatchArgs a;
+    a.x = static_cast<const bf16_t *>(ptr.x); a.w = static_cast<const bf16_t *>(ptr.w);
+    a.scale = ptr.scale; a.shift = ptr.shift; a.bias = ptr.bias;
+    a.residual = static_cast<const bf16_t *>(ptr.residual); a.y = static_cast<bf16_t *>(ptr.y);
+    a.N = p.N; a.IC = p.IC; a.H = p.H; a.W = p.W; a.OC = p.OC; a.OH = p.OH; a.OW = p.OW;
+    a.npix = p.npix; a.relu = p.relu;
+    a.mtiles = (p.OC + plan.mt - 1) / plan.mt;
+    const int ntiles = (p.npix + plan.nt - 1) / plan.nt;
+    if (plan.mt == 128 && plan.nt == 128)
+        return launch_stride<128, 128>(a, p.sh, ntiles, plan.lds_bytes, plan.pt, stream);
+    if (plan.mt == 128)
+        return launch_stride<128, 64>(a, p.sh, ntiles, plan.lds_bytes, plan.pt, stream);
+    if (plan.nt == 128)
+        return launch_stride<64, 128>(a, p.sh, ntiles, plan.lds_bytes, plan.pt, stream);
+    return launch_stride<64, 64>(a, p.sh, ntiles, plan.lds_bytes, plan.pt, stream);
+}
+
+}  // namespace tvg

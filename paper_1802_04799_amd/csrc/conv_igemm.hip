@@ -302,7 +302,7 @@ tvg_status launch_typed(const IgemmArgs &a, int mt, hipStream_t stream)
 
 }  // namespace
 
-ConvPlan plan_conv(const ConvProblem &p)
+ConvPlan plan_conv(const ConvProblem &p, bool allow_split)
 {
     ConvPlan plan;
     const int kt = p.dtype == TVG_BF16 ? 32 : 16;
@@ -311,7 +311,7 @@ ConvPlan plan_conv(const ConvProblem &p)
     const long tiles = (long)((p.OC + plan.mt - 1) / plan.mt) * ((p.npix + kNT - 1) / kNT);
     const int chunks = (p.K + kt - 1) / kt;
     int splits = 1;
-    if (tiles < kComputeUnits) {
+    if (allow_split && tiles < kComputeUnits) {
         const int want = (int)((2 * kComputeUnits + tiles - 1) / tiles);
         splits = want < chunks / 4 ? want : chunks / 4;   // keep at least 4 chunks per partition
         if (splits > 32) splits = 32;

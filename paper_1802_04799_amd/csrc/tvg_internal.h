@@ -39,7 +39,24 @@ struct ConvPlan {
     size_t workspace_bytes;
 };
 
-ConvPlan plan_conv(const ConvProblem &p);
+// `allow_split` = false plans a single pass over the reduction (no workspace).
+ConvPlan plan_conv(const ConvProblem &p, bool allow_split = true);
+
+// Launch shape of the bf16 3x3 patch kernel; a pure function of the problem.
+struct Patch3x3Plan {
+    int mt, nt;         // output channels x pixels per workgroup
+    int pt;             // patch load tasks per thread
+    int rows;           // virtual input rows staged per tile (maximum over tiles)
+    size_t lds_bytes;
+    long tiles;
+};
+
+// True when the problem is one the patch kernel is built for (bf16, 3x3, pad 1,
+// stride 1 or 2, IC a multiple of 16).  Pointer alignment is checked at launch.
+bool plan_conv3x3_patch(const ConvProblem &p, Patch3x3Plan *plan);
+bool conv3x3_patch_pointers_ok(const ConvPointers &ptr);
+tvg_status launch_conv3x3_patch(const ConvProblem &p, const Patch3x3Plan &plan,
+                                const ConvPointers &ptr, hipStream_t stream);
 
 tvg_status launch_conv_igemm(const ConvProblem &p, const ConvPlan &plan, const ConvPointers &ptr,
                              hipStream_t stream);

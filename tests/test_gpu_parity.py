@@ -125,6 +125,30 @@ def test_dense_ragged_shapes_full_tail(tvg, dtype, cfg):
     assert rel_err(to_host(y), oracle_dense(sh, inp)) <= TOL[dtype]
 
 
+PATCH_RAGGED = [
+    # bf16 3x3 pad-1 problems with IC % 16 == 0: n, ic, h, w, oc, stride
+    (3, 16, 9, 11, 40, 1), (2, 32, 10, 13, 70, 2), (5, 48, 7, 7, 130, 1), (4, 16, 5, 6, 8, 2),
+    (1, 64, 1, 1, 64, 1), (2, 16, 2, 3, 16, 2), (1, 16, 30, 70, 16, 1), (1, 16, 33, 120, 200, 2),
+    (7, 32, 7, 7, 64, 2), (2, 16, 14, 14, 256, 1), (3, 16, 56, 56, 64, 1), (2, 16, 57, 55, 32, 2),
+]
+
+
+@pytest.mark.parametrize("tile", ["", "128,128", "128,64", "64,128", "64,64"])
+@pytest.mark.parametrize("cfg", PATCH_RAGGED)
+def test_bf16_3x3_patch_kernel_ragged_shapes_all_tiles(tvg, monkeypatch, cfg, tile):
+    """The LDS-patch 3x3 kernel under every workgroup tile shape it is built with (the
+    library reads TVG_FORCE_TILE on every call; an unusable choice falls back by itself)."""
+    n, ic, h, w, oc, stride = cfg
+    if tile:
+        monkeypatch.setenv("TVG_FORCE_TILE", tile)
+    else:
+        monkeypatch.delenv("TVG_FORCE_TILE", raising=False)
+    sh = ti.ConvShape("p", n, ic, h, w, oc, 3, 3, stride, 1)
+    inp = ti.make_inputs(sh, 4000 + sum(cfg), "bf16", residual=True, bias=True)
+    y = run_dense(tvg, sh, inp, "bf16")
+    assert rel_err(to_host(y), oracle_dense(sh, inp)) <= TOL["bf16"]
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_rectangular_filter_and_strides(tvg, dtype):
     import torch
