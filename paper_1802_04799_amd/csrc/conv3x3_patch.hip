@@ -40,10 +40,13 @@ struct PatchArgs {
     const bf16_t *residual;
     bf16_t *y;
     int N, IC, H, W, OC, OH, OW, npix, relu, mtiles;
+    int vmode;        // pixels per vector store in the epilogue (8, 4 or 1)
+    uint32_t x_bytes, w_bytes;
 };
 
 constexpr int kPosBytes = 48;    // 16 channels (32 B) + 16 B padding: conflict-free 16-byte reads
 constexpr int kChunk = 16;       // input channels per chunk = K of one 32x32x16 MFMA
+constexpr int kRsrcFlags = 0x00020000;   // raw buffer descriptor word 3 on gfx9-family targets
 
 __device__ __forceinline__ int xcd_remap(int bid, int nb)
 {
@@ -90,7 +93,8 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
         reinterpret_cast<uint4v *>(Ps)[i] = uint4v{0u, 0u, 0u, 0u};
 
     // ---- per-thread patch load tasks: (virtual row, iw, channel octet), fixed for all chunks
-    int goff[PT], loff[PT];
+    uint32_t goff[PT];      // byte offset of the task's first channel within a chunk of x
+    int loff[PT];           // byte offset of its 16-byte slot in the patch, -1 = nothing to do
     {
         const int per_octet = nrows * W;
 #pragma unroll
@@ -105,7 +109,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
                 const int v = vr_lo + vrow;
                 const int n = v / VH, ih = v - n * VH - 1;
                 if (ih >= 0 && ih < H && n < a.N) {
-                    goff[j] = (n * a.IC + octet * 8) * HW + ih * W + iw;
+                    goff[j] = 2u * (uint32_t)((n * a.IC + octet * 8) * HW + ih * W + iw);
                     loff[j] = (vrow * PW + iw + 1) * kPosBytes + octet * 16;
                 }
             }
@@ -128,43 +132,53 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
     // ---- weight task: one output channel, one octet of input channels, all nine taps -------
     const bool wtask = tid < MT * 2;
     const int w_ocl = tid >> 1, w_oct = tid & 1;
+    // rows past OC read row 0: their products land in accumulators that are never stored
     const bool wvalid = wtask && (m0 + w_ocl) < a.OC;
-    const bf16_t *wsrc = a.w + ((size_t)(wvalid ? m0 + w_ocl : 0) * a.IC + w_oct * 8) * 9;
+    const uint32_t woff = 2u * (uint32_t)(((wvalid ? m0 + w_ocl : 0) * a.IC + w_oct * 8) * 9);
 
-    uint4v preg[PT];
+    // Loaded values stay unpacked until store_chunk so that nothing waits on the loads
+    // before the MFMA phase of the current chunk.
+    uint32_t praw[PT][8];
     uint4v wreg[9];
 
+    // Buffer loads: a uniform descriptor + per-lane 32-bit byte offset + scalar offset, so
+    // the loads of a chunk cost no vector address arithmetic at all.
+    const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t *>(a.x), 0, a.x_bytes, kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t *>(a.w), 0, a.w_bytes, kRsrcFlags);
+
     auto load_chunk = [&](int c) {
-        const bf16_t *xc = a.x + (size_t)c * kChunk * HW;
 #pragma unroll
-        for (int j = 0; j < PT; ++j) {
-            const bf16_t *src = xc + goff[j];
-            uint32_t v[4];
+        for (int q = 0; q < 8; ++q) {
+            const int soff = (c * kChunk + q) * HW * 2;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const uint32_t lo = src[(2 * q) * HW], hi = src[(2 * q + 1) * HW];
-                v[q] = lo | (hi << 16);
-            }
-            preg[j] = uint4v{v[0], v[1], v[2], v[3]};
+            for (int j = 0; j < PT; ++j)
+                praw[j][q] = __builtin_amdgcn_raw_buffer_load_b16(xrsrc, goff[j], soff, 0);
         }
         if (wtask) {
-            const uint4v *ws = reinterpret_cast<const uint4v *>(wsrc + (size_t)c * kChunk * 9);
+            const int soff = c * kChunk * 9 * 2;
 #pragma unroll
-            for (int i = 0; i < 9; ++i) wreg[i] = ws[i];
+            for (int i = 0; i < 9; ++i)
+                wreg[i] = __builtin_bit_cast(
+                    uint4v, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, woff + i * 16, soff, 0));
         }
     };
 
     auto store_chunk = [&]() {
 #pragma unroll
         for (int j = 0; j < PT; ++j)
-            if (loff[j] >= 0) *reinterpret_cast<uint4v *>(Ps + loff[j]) = preg[j];
+            if (loff[j] >= 0)
+                *reinterpret_cast<uint4v *>(Ps + loff[j]) =
+                    uint4v{praw[j][0] | (praw[j][1] << 16), praw[j][2] | (praw[j][3] << 16),
+                           praw[j][4] | (praw[j][5] << 16), praw[j][6] | (praw[j][7] << 16)};
         if (wtask) {
             // wreg holds 8 channels x 9 taps, tap fastest; emit one 8-channel vector per tap
             uint32_t d[36];
 #pragma unroll
             for (int i = 0; i < 9; ++i)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) d[i * 4 + q] = wvalid ? wreg[i][q] : 0u;
+                for (int q = 0; q < 4; ++q) d[i * 4 + q] = wreg[i][q];
 #pragma unroll
             for (int tap = 0; tap < 9; ++tap) {
                 uint32_t o[4];
@@ -197,24 +211,31 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
     for (int c = 0; c < nchunks; ++c) {
         if (c + 1 < nchunks) load_chunk(c + 1);
 
-#pragma unroll
-        for (int tap = 0; tap < 9; ++tap) {
+        // operands of tap t+1 are requested from LDS before the MFMAs of tap t issue
+        uint4v af[2][MI], bf[2][NJ];
+        auto fetch = [&](int tap, int slot) {
             const int r = tap / 3, s = tap - r * 3;
             const int toff = (r * PW + s) * kPosBytes;
-            uint4v af[MI], bf[NJ];
 #pragma unroll
             for (int i = 0; i < MI; ++i)
-                af[i] = *reinterpret_cast<const uint4v *>(Abase + (tap * MT + i * 32) * kPosBytes);
+                af[slot][i] =
+                    *reinterpret_cast<const uint4v *>(Abase + (tap * MT + i * 32) * kPosBytes);
 #pragma unroll
             for (int j = 0; j < NJ; ++j)
-                bf[j] = *reinterpret_cast<const uint4v *>(Ps + pb[j] + toff);
+                bf[slot][j] = *reinterpret_cast<const uint4v *>(Ps + pb[j] + toff);
+        };
+        fetch(0, 0);
+#pragma unroll
+        for (int tap = 0; tap < 9; ++tap) {
+            const int cur = tap & 1;
+            if (tap + 1 < 9) fetch(tap + 1, cur ^ 1);
 #pragma unroll
             for (int i = 0; i < MI; ++i)
 #pragma unroll
                 for (int j = 0; j < NJ; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        __builtin_bit_cast(bf16x8v, af[i]), __builtin_bit_cast(bf16x8v, bf[j]),
-                        acc[i][j], 0, 0, 0);
+                        __builtin_bit_cast(bf16x8v, af[cur][i]),
+                        __builtin_bit_cast(bf16x8v, bf[cur][j]), acc[i][j], 0, 0, 0);
         }
 
         if (c + 1 < nchunks) {
@@ -224,25 +245,16 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
         }
     }
 
-    // ---- fused tail on the accumulators -------------------------------------------------
+    // ---- fused tail: transpose each 32x32 tile through LDS, vector stores -----------------
+    __syncthreads();                       // every wave is done reading the operand tiles
+    float *stage = reinterpret_cast<float *>(smem) + wave * kStageFloats;
+    const TailArgs tail{a.scale, a.shift, a.bias, a.residual, a.y, a.OC, OHW, a.npix, a.relu};
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) {
-        const int p = n0 + wn * WTN + j * 32 + lrow;
-        if (p >= a.npix) continue;
-        const int n = p / OHW, rem = p - n * OHW;
-        const int obase = n * a.OC * OHW + rem;
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int i = 0; i < MI; ++i) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int oc = m0 + wm * WTM + i * 32 + 8 * (v >> 2) + 4 * lhalf + (v & 3);
-                if (oc >= a.OC) continue;
-                fused_tail_store<bf16_t>(acc[i][j][v], a.scale[oc], a.shift[oc],
-                                         a.bias ? a.bias[oc] : 0.0f, a.residual, a.y,
-                                         obase + oc * OHW, a.relu != 0);
-            }
-        }
-    }
+        for (int j = 0; j < NJ; ++j)
+            store_tile<bf16_t>(acc[i][j], stage, lane, m0 + wm * WTM + i * 32,
+                               n0 + wn * WTN + j * 32, tail, a.vmode);
 }
 
 // Largest number of virtual rows any pixel tile of NT pixels needs.
@@ -340,6 +352,9 @@ tvg_status launch_conv3x3_patch(const ConvProblem &p, const Patch3x3Plan &plan,
     a.N = p.N; a.IC = p.IC; a.H = p.H; a.W = p.W; a.OC = p.OC; a.OH = p.OH; a.OW = p.OW;
     a.npix = p.npix; a.relu = p.relu;
     a.mtiles = (p.OC + plan.mt - 1) / plan.mt;
+    a.vmode = pick_store_vmode(p.dtype, p.OH * p.OW, ptr.y, ptr.residual);
+    a.x_bytes = (uint32_t)((size_t)p.N * p.IC * p.H * p.W * 2);
+    a.w_bytes = (uint32_t)((size_t)p.OC * p.IC * 9 * 2);
     const int ntiles = (p.npix + plan.nt - 1) / plan.nt;
     if (plan.mt == 128 && plan.nt == 128)
         return launch_stride<128, 128>(a, p.sh, ntiles, plan.lds_bytes, plan.pt, stream);

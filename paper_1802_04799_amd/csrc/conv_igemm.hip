@@ -34,6 +34,7 @@ struct IgemmArgs {
     int K, npix, relu;
     int mtiles, splits, k_per_split;
     int w_vec_ok;      // weight rows may be read as aligned 16-byte vectors
+    int vmode;         // pixels per vector store in the epilogue (8, 4 or 1)
 };
 
 constexpr int kThreads = 256;
@@ -224,10 +225,20 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(const IgemmArgs a)
         __syncthreads();
     }
 
-    // ---- fused tail on the accumulators ----------------------------------------------
+    // ---- fused tail on the accumulators (or raw partials when the reduction is split) -----
+    if (a.splits == 1) {
+        // the loop ended on a barrier: the operand buffers are free to stage the transposes
+        float *stage = reinterpret_cast<float *>(lds) + wave * kStageFloats;
+        const TailArgs tail{a.scale, a.shift, a.bias, a.residual, a.y, a.OC, OHW, a.npix, a.relu};
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+                store_tile<T>(acc[i][j], stage, lane, m0 + wm * WTM + i * 32,
+                              n0 + wn * 64 + j * 32, tail, a.vmode);
+        return;
+    }
     // Accumulator v of lane l in a 32x32 tile: row 8*(v/4) + 4*(l/32) + v%4, column l%32.
-    const T *res = static_cast<const T *>(a.residual);
-    T *yg = static_cast<T *>(a.y);
     const size_t total = (size_t)a.npix * a.OC;
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
@@ -241,13 +252,7 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(const IgemmArgs a)
             for (int v = 0; v < 16; ++v) {
                 const int oc = m0 + wm * WTM + i * 32 + 8 * (v >> 2) + 4 * lhalf + (v & 3);
                 if (oc >= a.OC) continue;
-                const int o = obase + oc * OHW;
-                if (a.splits == 1) {
-                    fused_tail_store<T>(acc[i][j][v], a.scale[oc], a.shift[oc],
-                                        a.bias ? a.bias[oc] : 0.0f, res, yg, o, a.relu != 0);
-                } else {
-                    a.ws[(size_t)split * total + o] = acc[i][j][v];
-                }
+                a.ws[(size_t)split * total + obase + oc * OHW] = acc[i][j][v];
             }
         }
     }
@@ -339,6 +344,7 @@ tvg_status launch_conv_igemm(const ConvProblem &p, const ConvPlan &plan, const C
     a.k_per_split = plan.k_per_split;
     const int ve = p.dtype == TVG_BF16 ? 8 : 4;
     a.w_vec_ok = (p.K % ve == 0) && (reinterpret_cast<uintptr_t>(ptr.w) % 16 == 0);
+    a.vmode = pick_store_vmode(p.dtype, p.OH * p.OW, ptr.y, ptr.residual);
     return p.dtype == TVG_BF16 ? launch_typed<bf16_t>(a, plan.mt, stream)
                                : launch_typed<float>(a, plan.mt, stream);
 }

@@ -6,6 +6,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "tvg.h"
+
 namespace tvg {
 
 typedef uint16_t bf16_t;   // raw bfloat16 bits
@@ -46,6 +48,163 @@ __device__ __forceinline__ void fused_tail_store(float acc, float scale, float s
     if (residual) t += Elem<T>::load(residual, out_index);
     if (relu) t = fmaxf(t, 0.0f);
     Elem<T>::store(y, out_index, t);
+}
+
+// ---------------------------------------------------------------------------------------
+// Tile epilogue shared by the MFMA kernels.
+//
+// A 32x32 fp32 accumulator tile (rows = output channels, columns = consecutive
+// output pixels) leaves the MFMA with one pixel per lane, which would mean one
+// 2- or 4-byte store per value.  Instead the wave transposes the tile through a
+// private 32 x 36 float staging area in LDS so that each lane owns V consecutive
+// pixels of one channel, applies the fused tail to them and moves residual and y
+// as 8- or 16-byte vectors (64 contiguous bytes or more per channel row).
+// V consecutive pixels starting at a multiple of V lie in one image and are
+// contiguous and aligned in NCHW exactly when OH*OW is a multiple of V; the
+// caller selects V accordingly (V = 1: no staging, direct stores).
+// ---------------------------------------------------------------------------------------
+struct TailArgs {
+    const float *scale, *shift, *bias;
+    const void *residual;
+    void *y;
+    int OC, OHW, npix, relu;
+};
+
+constexpr int kStageStride = 36;                       // floats per staged row (32 + 4 padding)
+constexpr int kStageFloats = 32 * kStageStride;        // per wave
+
+template <typename T, int V> struct VecIO;
+template <> struct VecIO<bf16_t, 8> {
+    typedef uint4v vec;
+    static __device__ __forceinline__ void unpack(const vec &r, float *f)
+    {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            f[2 * q] = __uint_as_float(r[q] << 16);
+            f[2 * q + 1] = __uint_as_float(r[q] & 0xFFFF0000u);
+        }
+    }
+    static __device__ __forceinline__ vec pack(const float *f)
+    {
+        vec r;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            r[q] = (uint32_t)f32_to_bf16(f[2 * q]) | ((uint32_t)f32_to_bf16(f[2 * q + 1]) << 16);
+        return r;
+    }
+};
+template <> struct VecIO<bf16_t, 4> {
+    typedef uint32_t vec __attribute__((ext_vector_type(2)));
+    static __device__ __forceinline__ void unpack(const vec &r, float *f)
+    {
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            f[2 * q] = __uint_as_float(r[q] << 16);
+            f[2 * q + 1] = __uint_as_float(r[q] & 0xFFFF0000u);
+        }
+    }
+    static __device__ __forceinline__ vec pack(const float *f)
+    {
+        vec r;
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+            r[q] = (uint32_t)f32_to_bf16(f[2 * q]) | ((uint32_t)f32_to_bf16(f[2 * q + 1]) << 16);
+        return r;
+    }
+};
+template <> struct VecIO<float, 4> {
+    typedef float4v vec;
+    static __device__ __forceinline__ void unpack(const vec &r, float *f)
+    {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) f[q] = r[q];
+    }
+    static __device__ __forceinline__ vec pack(const float *f) { return vec{f[0], f[1], f[2], f[3]}; }
+};
+
+// acc: one 32x32 MFMA accumulator tile (value v of lane l = row 8*(v/4) + 4*(l/32) + v%4,
+// column l%32).  oc0 / p0: output channel of row 0 / flattened pixel of column 0.
+template <typename T, int V>
+__device__ __forceinline__ void store_tile_staged(const float16v &acc, float *stage, int lane,
+                                                  int oc0, int p0, const TailArgs &t)
+{
+    typedef typename VecIO<T, V>::vec vec;
+    const int lrow = lane & 31, lhalf = lane >> 5;
+#pragma unroll
+    for (int v = 0; v < 16; ++v)
+        stage[(8 * (v >> 2) + 4 * lhalf + (v & 3)) * kStageStride + lrow] = acc[v];
+    __builtin_amdgcn_wave_barrier();
+    constexpr int G = 32 / V;                      // lane groups per row
+#pragma unroll
+    for (int it = 0; it < 32 * G / 64; ++it) {
+        const int task = it * 64 + lane;
+        const int row = task / G, g = task - row * G;
+        const int oc = oc0 + row, p = p0 + g * V;
+        if (oc < t.OC && p < t.npix) {
+            const int n = p / t.OHW, rem = p - n * t.OHW;
+            const size_t idx = (size_t)(n * t.OC + oc) * t.OHW + rem;
+            const float sc = t.scale[oc], sf = t.shift[oc], bs = t.bias ? t.bias[oc] : 0.0f;
+            float f[V], r[V];
+#pragma unroll
+            for (int q = 0; q < V; ++q) f[q] = stage[row * kStageStride + g * V + q];
+            if (t.residual)
+                VecIO<T, V>::unpack(*reinterpret_cast<const vec *>(static_cast<const T *>(t.residual) + idx), r);
+#pragma unroll
+            for (int q = 0; q < V; ++q) {
+                float o = (f[q] + bs) * sc + sf;
+                if (t.residual) o += r[q];
+                if (t.relu) o = fmaxf(o, 0.0f);
+                f[q] = o;
+            }
+            *reinterpret_cast<vec *>(static_cast<T *>(t.y) + idx) = VecIO<T, V>::pack(f);
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+}
+
+// Direct (unstaged) stores of one accumulator tile: any OH*OW, any alignment.
+template <typename T>
+__device__ __forceinline__ void store_tile_direct(const float16v &acc, int lane, int oc0, int p0,
+                                                  const TailArgs &t)
+{
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    const int p = p0 + lrow;
+    if (p >= t.npix) return;
+    const int n = p / t.OHW, rem = p - n * t.OHW;
+    const int obase = n * t.OC * t.OHW + rem;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int oc = oc0 + 8 * (v >> 2) + 4 * lhalf + (v & 3);
+        if (oc >= t.OC) continue;
+        fused_tail_store<T>(acc[v], t.scale[oc], t.shift[oc], t.bias ? t.bias[oc] : 0.0f,
+                            static_cast<const T *>(t.residual), static_cast<T *>(t.y),
+                            obase + oc * t.OHW, t.relu != 0);
+    }
+}
+
+// vmode: pixels per vector store (8, 4) or 1 for direct stores; chosen on the host.
+template <typename T>
+__device__ __forceinline__ void store_tile(const float16v &acc, float *stage, int lane, int oc0,
+                                           int p0, const TailArgs &t, int vmode)
+{
+    if constexpr (sizeof(T) == 2) {
+        if (vmode == 8) return store_tile_staged<bf16_t, 8>(acc, stage, lane, oc0, p0, t);
+        if (vmode == 4) return store_tile_staged<bf16_t, 4>(acc, stage, lane, oc0, p0, t);
+    } else {
+        if (vmode == 4) return store_tile_staged<float, 4>(acc, stage, lane, oc0, p0, t);
+    }
+    store_tile_direct<T>(acc, lane, oc0, p0, t);
+}
+
+// Host side: widest staged store the problem allows.
+inline int pick_store_vmode(int dtype, int OHW, const void *y, const void *residual)
+{
+    const bool aligned = reinterpret_cast<uintptr_t>(y) % 16 == 0 &&
+                         reinterpret_cast<uintptr_t>(residual) % 16 == 0;
+    if (!aligned) return 1;
+    if (dtype == TVG_BF16 && OHW % 8 == 0) return 8;
+    if (OHW % 4 == 0) return 4;
+    return 1;
 }
 
 }  // namespace tvg
