@@ -54,7 +54,9 @@ tvg_status tvg_conv2d_workspace_size(const tvg_conv_desc *desc, size_t *bytes)
     tvg_status st = make_problem(desc, false, &p);
     if (st != TVG_OK) return st;
     tvg::Patch3x3Plan patch;
-    *bytes = tvg::plan_conv3x3_patch(p, &patch) ? 0 : tvg::plan_conv(p).workspace_bytes;
+    tvg::StemPlan stem;
+    const bool single_pass = tvg::plan_conv3x3_patch(p, &patch) || tvg::plan_conv7x7s2_stem(p, &stem);
+    *bytes = single_pass ? 0 : tvg::plan_conv(p).workspace_bytes;
     return TVG_OK;
 }
 
@@ -83,9 +85,13 @@ tvg_status tvg_conv2d_fused(const tvg_conv_desc *desc, const void *x, const void
     const bool patch_shape = tvg::plan_conv3x3_patch(p, &patch);
     if (patch_shape && tvg::conv3x3_patch_pointers_ok(ptr))
         return tvg::launch_conv3x3_patch(p, patch, ptr, stream);
-    // A patch-shaped problem reported a zero workspace; if its pointers rule the patch
-    // kernel out, the generic kernel runs it in a single pass over the reduction.
-    const tvg::ConvPlan plan = tvg::plan_conv(p, !patch_shape);
+    tvg::StemPlan stem;
+    const bool stem_shape = tvg::plan_conv7x7s2_stem(p, &stem);
+    if (stem_shape && tvg::conv7x7s2_stem_pointers_ok(ptr))
+        return tvg::launch_conv7x7s2_stem(p, stem, ptr, stream);
+    // A problem shaped for a specialised kernel reported a zero workspace; if its pointers
+    // rule that kernel out, the generic kernel runs it in a single pass over the reduction.
+    const tvg::ConvPlan plan = tvg::plan_conv(p, !(patch_shape || stem_shape));
     if (plan.workspace_bytes > 0 && (!workspace || workspace_bytes < plan.workspace_bytes))
         return TVG_ERR_WORKSPACE;
     return tvg::launch_conv_igemm(p, plan, ptr, stream);

@@ -42,6 +42,7 @@ struct PatchArgs {
     int N, IC, H, W, OC, OH, OW, npix, relu, mtiles;
     int vmode;        // pixels per vector store in the epilogue (8, 4 or 1)
     uint32_t x_bytes, w_bytes;
+    int ss_offset;    // byte offset in LDS of the staged (scale, offset) pairs
 };
 
 constexpr int kPosBytes = 48;    // 16 channels (32 B) + 16 B padding: conflict-free 16-byte reads
@@ -87,6 +88,9 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
     const int vr_lo = na * VH + oha * STRIDE;
     const int nrows = nb * VH + ohb * STRIDE + 2 - vr_lo + 1;
     const int npos = nrows * PW;
+
+    float *ss_lds = reinterpret_cast<float *>(smem + a.ss_offset);
+    stage_scale_shift(ss_lds, m0, MT, a.scale, a.shift, a.bias, a.OC, tid, 256);
 
     // ---- zero the patch once: padding rows and columns are never written again ------------
     for (int i = tid; i < npos * (kPosBytes / 16); i += 256)
@@ -254,7 +258,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
 #pragma unroll
         for (int j = 0; j < NJ; ++j)
             store_tile<bf16_t>(acc[i][j], stage, lane, m0 + wm * WTM + i * 32,
-                               n0 + wn * WTN + j * 32, tail, a.vmode);
+                               n0 + wn * WTN + j * 32, tail, a.vmode, ss_lds, wm * WTM + i * 32);
 }
 
 // Largest number of virtual rows any pixel tile of NT pixels needs.
@@ -317,24 +321,31 @@ bool plan_conv3x3_patch(const ConvProblem &p, Patch3x3Plan *plan)
     if (p.IC % kChunk != 0) return false;
     int force_mt = 0, force_nt = 0;
     if (const char *e = getenv("TVG_FORCE_TILE")) sscanf(e, "%d,%d", &force_mt, &force_nt);
-    // Tile choice: fill 256 CUs twice over when the problem allows; prefer the largest tile.
-    const int mts[] = {128, 64}, nts[] = {128, 64};
+    // Tile choice (measured on MI355X at batch 64): take the largest tile that still gives at
+    // least 1.5 workgroups per CU, wider in pixels on a tie; if none does, the tile shape with
+    // the most workgroups.  A 128-channel tile with more than 4 patch tasks per thread (wide
+    // stride-2 patches) runs out of registers and is skipped.
+    const int cands[4][2] = {{128, 128}, {64, 128}, {128, 64}, {64, 64}};
     Patch3x3Plan best{};
-    bool found = false;
-    for (int mt : mts) {
+    bool found = false, best_fills = false;
+    for (const auto &c : cands) {
+        const int mt = c[0], nt = c[1];
         if (mt == 128 && p.OC <= 64) continue;
         if (force_mt && mt != force_mt) continue;
-        for (int nt : nts) {
-            if (force_nt && nt != force_nt) continue;
-            const int rows = max_patch_rows(p, nt);
-            const int pt = (2 * rows * p.W + 255) / 256;
-            const size_t lds = (size_t)9 * mt * kPosBytes + (size_t)rows * (p.W + 2) * kPosBytes;
-            if (pt > 8 || lds > 80 * 1024) continue;
-            const long tiles = (long)((p.OC + mt - 1) / mt) * ((p.npix + nt - 1) / nt);
-            Patch3x3Plan cand{mt, nt, pt, rows, lds, tiles};
-            if (!found) { best = cand; found = true; }
-            // take a smaller tile only while the larger one leaves CUs idle
-            else if (best.tiles < 2 * kComputeUnits && tiles > best.tiles) best = cand;
+        if (force_nt && nt != force_nt) continue;
+        const int rows = max_patch_rows(p, nt);
+        const int pt = (2 * rows * p.W + 255) / 256;
+        const size_t lds = (size_t)9 * mt * kPosBytes + (size_t)rows * (p.W + 2) * kPosBytes +
+                           (size_t)mt * 8;      // operands + (scale, offset) pairs
+        if (pt > 8 || lds > 80 * 1024) continue;
+        if (mt == 128 && pt > 4 && !force_mt) continue;
+        const long tiles = (long)((p.OC + mt - 1) / mt) * ((p.npix + nt - 1) / nt);
+        const bool fills = 2 * tiles >= 3 * kComputeUnits;
+        const Patch3x3Plan cand{mt, nt, pt, rows, lds, tiles};
+        if (!found || (!best_fills && (fills || tiles > best.tiles))) {
+            best = cand;
+            best_fills = fills;
+            found = true;
         }
     }
     if (!found) return false;
@@ -353,6 +364,7 @@ tvg_status launch_conv3x3_patch(const ConvProblem &p, const Patch3x3Plan &plan,
     a.npix = p.npix; a.relu = p.relu;
     a.mtiles = (p.OC + plan.mt - 1) / plan.mt;
     a.vmode = pick_store_vmode(p.dtype, p.OH * p.OW, ptr.y, ptr.residual);
+    a.ss_offset = (int)(plan.lds_bytes - (size_t)plan.mt * 8);
     a.x_bytes = (uint32_t)((size_t)p.N * p.IC * p.H * p.W * 2);
     a.w_bytes = (uint32_t)((size_t)p.OC * p.IC * 9 * 2);
     const int ntiles = (p.npix + plan.nt - 1) / plan.nt;

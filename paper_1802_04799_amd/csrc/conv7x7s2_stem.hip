@@ -1,0 +1,293 @@
+// bf16 7x7 stride-2 pad-3 fused conv2d for very few input channels (the ResNet
+// stem, Table 2's C1: 3 -> 64 channels on 224x224), on MFMA.
+//
+// With IC = 3 the reduction (147) is too short and too ragged for the channel-
+// chunked kernels, and at batch 64 the layer is bound by writing its output
+// (103 MB against 19 MB of input), so this kernel is built around three ideas:
+//
+//  * Reduction order (ic, r, s') with the filter row padded to 8 taps on the LEFT
+//    (s' = 0 is a zero weight, s' = 1..7 are the real taps).  One MFMA lane then
+//    consumes 8 horizontally adjacent input values of one (ic, r) pair, which are
+//    contiguous in the NCHW input: the input patch is staged in LDS in its
+//    natural layout with plain 16-byte copies, no transposition, and the operand
+//    of pixel (oh, ow) for pair (ic, r) starts at column 2*ow of the staged row
+//    (the staged row begins 4 columns left of the image).  K per MFMA = 2 pairs,
+//    ceil(7*IC/2) MFMAs cover the whole reduction: there is no K loop.
+//  * The weights (OC tile x 7*IC pairs x 8) are staged once per workgroup and
+//    re-used for every pixel tile the workgroup walks over (persistent
+//    workgroups), so the per-tile work is: copy a few input rows, 11 x 4 MFMAs
+//    per wave, store 64 x 256 outputs.
+//  * Rows that fall outside the image are fetched through a buffer descriptor at
+//    an out-of-range offset, which returns zeros: no branches in the copy.
+//
+// The next tile's rows are requested before the current tile's MFMAs and are
+// written to the other LDS buffer afterwards (one barrier per tile).
+#include "tvg_device.h"
+#include "tvg_internal.h"
+
+namespace tvg {
+
+namespace {
+
+struct StemArgs {
+    const bf16_t *x, *w;
+    const float *scale, *shift, *bias;
+    const bf16_t *residual;
+    bf16_t *y;
+    int N, IC, H, W, OC, OH, OW, npix, relu, vmode;
+    int nrows;          // staged virtual rows per tile (maximum over tiles)
+    int ntiles, mtiles, wg_per_mtile;
+    uint32_t x_bytes;
+};
+
+constexpr int kNT = 256;                 // pixels per tile
+constexpr int kMT = 64;                  // output channels per tile
+constexpr int kRsrcFlags = 0x00020000;   // raw buffer descriptor word 3 on gfx9-family targets
+constexpr uint32_t kOutOfRange = 0xFFFFFFF0u;
+
+// IC = input channels (compile time, so the reduction loop unrolls completely and the LDS
+// reads of one MFMA step overlap the previous step's MFMAs); LT = 16-byte copy tasks per
+// thread per tile.
+template <int IC, int LT>
+__global__ __launch_bounds__(256, 2) void conv7x7s2_stem_kernel(const StemArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    constexpr int npairs = IC * 7;
+    constexpr int NM = (npairs + 1) / 2;                 // MFMAs over the reduction
+    const int H = a.H, W = a.W, OHW = a.OH * a.OW;
+    const int VH = H + 6;                                // virtual rows per image (3 + H + 3)
+    const int pitch = (W + 8) * 2;                       // bytes per staged row
+    const int nrows = a.nrows;
+    const int a_bytes = 2 * NM * kMT * 16;
+    const int patch_bytes = IC * nrows * pitch;
+    unsigned char *As = smem;                            // [pair][oc][8 taps]
+    unsigned char *Ps = smem + a_bytes;                  // 2 x [ic][row][W + 8]
+    float *stage = reinterpret_cast<float *>(smem + a_bytes + 2 * patch_bytes) +
+                   (threadIdx.x >> 6) * kStageFloats;
+    float *ss_lds = reinterpret_cast<float *>(smem + a_bytes + 2 * patch_bytes) + 4 * kStageFloats;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    const int mtile = blockIdx.x % a.mtiles, wg = blockIdx.x / a.mtiles;
+    const int m0 = mtile * kMT;
+
+    stage_scale_shift(ss_lds, m0, kMT, a.scale, a.shift, a.bias, a.OC, tid, 256);
+
+    // ---- zero both patch buffers (their padding columns stay zero), stage the weights ----
+    for (int i = tid; i < 2 * patch_bytes / 16; i += 256)
+        reinterpret_cast<uint4v *>(Ps)[i] = uint4v{0u, 0u, 0u, 0u};
+    for (int e = tid; e < 2 * NM * kMT * 8; e += 256) {
+        const int sp = e & 7, ocl = (e >> 3) & (kMT - 1), pair = e >> 9;
+        const int ic = pair / 7, r = pair - ic * 7;
+        bf16_t v = 0;
+        if (pair < npairs && sp >= 1 && m0 + ocl < a.OC)
+            v = a.w[((size_t)(m0 + ocl) * IC + ic) * 49 + r * 7 + sp - 1];
+        reinterpret_cast<bf16_t *>(As)[e] = v;
+    }
+
+    // ---- per-thread copy tasks: (ic, row slot, 16-byte column group), fixed for all tiles --
+    const int VPR = W / 8;
+    const int ntasks = IC * nrows * VPR;
+    uint32_t cgoff[LT];
+    int rslot[LT], ldst[LT];
+#pragma unroll
+    for (int j = 0; j < LT; ++j) {
+        const int t = tid + j * 256;
+        const int pr = t / VPR, v = t - pr * VPR;
+        const int ic = pr / nrows, rs = pr - ic * nrows;
+        cgoff[j] = (uint32_t)(ic * H * W * 2 + v * 16);
+        rslot[j] = t < ntasks ? rs : -1;
+        ldst[j] = (ic * nrows + rs) * pitch + 8 + v * 16;
+    }
+
+    const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t *>(a.x), 0, a.x_bytes, kRsrcFlags);
+    const TailArgs tail{a.scale, a.shift, a.bias, a.residual, a.y, a.OC, OHW, a.npix, a.relu};
+
+    uint4v lreg[LT];
+    auto first_vrow = [&](int tile) {
+        const int p0 = tile * kNT;
+        const int n = p0 / OHW, oh = (p0 - n * OHW) / a.OW;
+        return n * VH + oh * 2;
+    };
+    auto load_tile = [&](int tile) {
+        const int vr_lo = first_vrow(tile);
+        const int n_lo = vr_lo / VH, vi_lo = vr_lo - n_lo * VH;
+#pragma unroll
+        for (int j = 0; j < LT; ++j) {
+            int vi = vi_lo + rslot[j], n = n_lo;
+            if (vi >= VH) { vi -= VH; n += 1; }
+            const int ih = vi - 3;
+            const bool ok = rslot[j] >= 0 && ih >= 0 && ih < H && n < a.N;
+            const uint32_t voff = ok ? cgoff[j] + (uint32_t)((n * IC * H + ih) * W) * 2u : kOutOfRange;
+            lreg[j] = __builtin_bit_cast(uint4v, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, voff, 0, 0));
+        }
+    };
+    auto store_tile_rows = [&](int buf) {
+        unsigned char *P = Ps + buf * patch_bytes;
+#pragma unroll
+        for (int j = 0; j < LT; ++j)
+            if (rslot[j] >= 0) {
+                typedef uint32_t u2 __attribute__((ext_vector_type(2)));
+                *reinterpret_cast<u2 *>(P + ldst[j]) = u2{lreg[j][0], lreg[j][1]};
+                *reinterpret_cast<u2 *>(P + ldst[j] + 8) = u2{lreg[j][2], lreg[j][3]};
+            }
+    };
+
+    int tile = wg;
+    if (tile < a.ntiles) load_tile(tile);
+    __syncthreads();
+    if (tile < a.ntiles) store_tile_rows(0);
+    __syncthreads();
+
+    for (int it = 0; tile < a.ntiles; tile += a.wg_per_mtile, ++it) {
+        const int next = tile + a.wg_per_mtile;
+        if (next < a.ntiles) load_tile(next);
+
+        const unsigned char *P = Ps + (it & 1) * patch_bytes;
+        const int p0 = tile * kNT;
+        const int vr_lo = first_vrow(tile);
+        int pb[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int p = p0 + wave * 64 + j * 32 + lrow;
+            pb[j] = 0;
+            if (p < a.npix) {
+                const int n = p / OHW, rem = p - n * OHW;
+                const int oh = rem / a.OW, ow = rem - oh * a.OW;
+                pb[j] = (n * VH + oh * 2 - vr_lo) * pitch + ow * 4;
+            }
+        }
+        float16v acc[2][2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+#pragma unroll
+        for (int m = 0; m < NM; ++m) {
+            // the two half-waves hold pairs 2m and 2m+1; both offsets are uniform values
+            const int pa = 2 * m, pq = 2 * m + 1 < npairs ? 2 * m + 1 : 0;
+            const int offa = ((pa / 7) * nrows + pa % 7) * pitch;
+            const int offq = ((pq / 7) * nrows + pq % 7) * pitch;
+            const int poff = lhalf ? offq : offa;
+            uint4v af[2], bf[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+                af[i] = *reinterpret_cast<const uint4v *>(As + ((2 * m + lhalf) * kMT + i * 32 + lrow) * 16);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const uint32_t *src = reinterpret_cast<const uint32_t *>(P + pb[j] + poff);
+                bf[j] = uint4v{src[0], src[1], src[2], src[3]};
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        __builtin_bit_cast(bf16x8v, af[i]), __builtin_bit_cast(bf16x8v, bf[j]),
+                        acc[i][j], 0, 0, 0);
+        }
+
+        // The next tile's rows have arrived during the MFMAs: put them into the other buffer
+        // now, so that waiting for those loads does not also wait for this tile's stores.
+        if (next < a.ntiles) store_tile_rows((it + 1) & 1);
+
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                store_tile<bf16_t>(acc[i][j], stage, lane, m0 + i * 32, p0 + wave * 64 + j * 32,
+                                   tail, a.vmode, ss_lds, i * 32);
+        __syncthreads();
+    }
+}
+
+int max_stem_rows(const ConvProblem &p)
+{
+    const int OHW = p.OH * p.OW, VH = p.H + 6;
+    int best = 0;
+    for (long p0 = 0; p0 < p.npix; p0 += kNT) {
+        const long last = (p0 + kNT < p.npix ? p0 + kNT : p.npix) - 1;
+        const int na = (int)(p0 / OHW), oha = (int)((p0 - (long)na * OHW) / p.OW);
+        const int nb = (int)(last / OHW), ohb = (int)((last - (long)nb * OHW) / p.OW);
+        const int rows = nb * VH + ohb * 2 + 6 - (na * VH + oha * 2) + 1;
+        if (rows > best) best = rows;
+    }
+    return best;
+}
+
+template <int IC, int LT>
+tvg_status launch_lt(const StemArgs &a, unsigned grid, size_t lds, hipStream_t stream)
+{
+    auto kernel = conv7x7s2_stem_kernel<IC, LT>;
+    static bool configured = false;
+    if (!configured) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+            return TVG_ERR_LAUNCH;
+        configured = true;
+    }
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), lds, stream, a);
+    return hipGetLastError() == hipSuccess ? TVG_OK : TVG_ERR_LAUNCH;
+}
+
+}  // namespace
+
+bool plan_conv7x7s2_stem(const ConvProblem &p, StemPlan *plan)
+{
+    if (p.dtype != TVG_BF16 || p.R != 7 || p.S != 7 || p.sh != 2 || p.sw != 2 || p.ph != 3 ||
+        p.pw != 3)
+        return false;
+    if (p.IC > 4 || p.W % 8 != 0) return false;
+    if ((size_t)p.N * p.IC * p.H * p.W * 2 > (size_t)kOutOfRange) return false;
+    const int rows = max_stem_rows(p);
+    if (rows > p.H + 6) return false;                   // a tile may wrap into the next image once
+    const int nm = (p.IC * 7 + 1) / 2;
+    const size_t lds = (size_t)2 * nm * kMT * 16 + (size_t)2 * p.IC * rows * (p.W + 8) * 2 +
+                       (size_t)4 * kStageFloats * sizeof(float) + (size_t)kMT * 8;
+    const int lt = (p.IC * rows * (p.W / 8) + 255) / 256;
+    if (lds > 80 * 1024 || lt > 8) return false;
+    plan->rows = rows;
+    plan->lt = lt;
+    plan->lds_bytes = lds;
+    return true;
+}
+
+bool conv7x7s2_stem_pointers_ok(const ConvPointers &ptr)
+{
+    return reinterpret_cast<uintptr_t>(ptr.x) % 16 == 0;   // input rows are copied as 16-byte vectors
+}
+
+tvg_status launch_conv7x7s2_stem(const ConvProblem &p, const StemPlan &plan, const ConvPointers &ptr,
+                                 hipStream_t stream)
+{
+    StemArgs a;
+    a.x = static_cast<const bf16_t *>(ptr.x); a.w = static_cast<const bf16_t *>(ptr.w);
+    a.scale = ptr.scale; a.shift = ptr.shift; a.bias = ptr.bias;
+    a.residual = static_cast<const bf16_t *>(ptr.residual); a.y = static_cast<bf16_t *>(ptr.y);
+    a.N = p.N; a.IC = p.IC; a.H = p.H; a.W = p.W; a.OC = p.OC; a.OH = p.OH; a.OW = p.OW;
+    a.npix = p.npix; a.relu = p.relu;
+    a.vmode = pick_store_vmode(p.dtype, p.OH * p.OW, ptr.y, ptr.residual);
+    a.nrows = plan.rows;
+    a.ntiles = (p.npix + kNT - 1) / kNT;
+    a.mtiles = (p.OC + kMT - 1) / kMT;
+    // persistent workgroups: two per CU, shared between the output-channel tiles
+    int per = 2 * kComputeUnits / a.mtiles;
+    if (per < 1) per = 1;
+    if (per > a.ntiles) per = a.ntiles;
+    a.wg_per_mtile = per;
+    a.x_bytes = (uint32_t)((size_t)p.N * p.IC * p.H * p.W * 2);
+    const unsigned grid = (unsigned)(per * a.mtiles);
+    if (p.IC == 3 && plan.lt <= 5) return launch_lt<3, 5>(a, grid, plan.lds_bytes, stream);
+    switch (p.IC) {
+    case 1: return launch_lt<1, 8>(a, grid, plan.lds_bytes, stream);
+    case 2: return launch_lt<2, 8>(a, grid, plan.lds_bytes, stream);
+    case 3: return launch_lt<3, 8>(a, grid, plan.lds_bytes, stream);
+    default: return launch_lt<4, 8>(a, grid, plan.lds_bytes, stream);
+    }
+}
+
+}  // namespace tvg

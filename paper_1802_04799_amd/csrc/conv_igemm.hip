@@ -86,6 +86,7 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(const IgemmArgs a)
     constexpr int BUF = (MT + kNT) * kLdsRow;
 
     __shared__ __attribute__((aligned(16))) unsigned char lds[2 * BUF];
+    __shared__ float ss_lds[2 * MT];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -191,6 +192,8 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(const IgemmArgs a)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
+    if (a.splits == 1)
+        stage_scale_shift(ss_lds, m0, MT, a.scale, a.shift, a.bias, a.OC, tid, kThreads);
     if (nchunks > 0) {
         load_chunk(0);
         store_chunk(0);
@@ -235,7 +238,7 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(const IgemmArgs a)
 #pragma unroll
             for (int j = 0; j < NJ; ++j)
                 store_tile<T>(acc[i][j], stage, lane, m0 + wm * WTM + i * 32,
-                              n0 + wn * 64 + j * 32, tail, a.vmode);
+                              n0 + wn * 64 + j * 32, tail, a.vmode, ss_lds, wm * WTM + i * 32);
         return;
     }
     // Accumulator v of lane l in a 32x32 tile: row 8*(v/4) + 4*(l/32) + v%4, column l%32.

@@ -19,12 +19,18 @@ typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(uint32_t(b) << 16); }
 
-// fp32 -> bf16, round to nearest, ties to even (finite inputs).
+// fp32 -> bf16, round to nearest, ties to even: the hardware conversion of gfx950
+// (v_cvt_pk_bf16_f32), one instruction per pair of values.
 __device__ __forceinline__ bf16_t f32_to_bf16(float f)
 {
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return bf16_t(u >> 16);
+    return __builtin_bit_cast(bf16_t, static_cast<__bf16>(f));
+}
+
+__device__ __forceinline__ uint32_t f32x2_to_bf16x2(float lo, float hi)
+{
+    typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+    typedef float f2 __attribute__((ext_vector_type(2)));
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f2{lo, hi}, bf2));
 }
 
 template <typename T> struct Elem;
@@ -73,6 +79,26 @@ struct TailArgs {
 constexpr int kStageStride = 36;                       // floats per staged row (32 + 4 padding)
 constexpr int kStageFloats = 32 * kStageStride;        // per wave
 
+// Puts the per-channel multiplier and offset of a tile's `rows` output channels into LDS as
+// (scale, bias*scale + shift) pairs, so the epilogue reads them with LDS latency instead of
+// issuing dependent global loads per store.  (acc + bias)*scale + shift == acc*scale + that
+// offset.  Call before a barrier that precedes the first staged store.
+__device__ __forceinline__ void stage_scale_shift(float *ss, int m0, int rows, const float *scale,
+                                                  const float *shift, const float *bias, int OC,
+                                                  int tid, int nthreads)
+{
+    for (int r = tid; r < rows; r += nthreads) {
+        const int oc = m0 + r;
+        float sc = 0.0f, sf = 0.0f;
+        if (oc < OC) {
+            sc = scale[oc];
+            sf = bias ? fmaf(bias[oc], sc, shift[oc]) : shift[oc];
+        }
+        ss[2 * r] = sc;
+        ss[2 * r + 1] = sf;
+    }
+}
+
 template <typename T, int V> struct VecIO;
 template <> struct VecIO<bf16_t, 8> {
     typedef uint4v vec;
@@ -89,7 +115,7 @@ template <> struct VecIO<bf16_t, 8> {
         vec r;
 #pragma unroll
         for (int q = 0; q < 4; ++q)
-            r[q] = (uint32_t)f32_to_bf16(f[2 * q]) | ((uint32_t)f32_to_bf16(f[2 * q + 1]) << 16);
+            r[q] = f32x2_to_bf16x2(f[2 * q], f[2 * q + 1]);
         return r;
     }
 };
@@ -108,7 +134,7 @@ template <> struct VecIO<bf16_t, 4> {
         vec r;
 #pragma unroll
         for (int q = 0; q < 2; ++q)
-            r[q] = (uint32_t)f32_to_bf16(f[2 * q]) | ((uint32_t)f32_to_bf16(f[2 * q + 1]) << 16);
+            r[q] = f32x2_to_bf16x2(f[2 * q], f[2 * q + 1]);
         return r;
     }
 };
@@ -124,9 +150,11 @@ template <> struct VecIO<float, 4> {
 
 // acc: one 32x32 MFMA accumulator tile (value v of lane l = row 8*(v/4) + 4*(l/32) + v%4,
 // column l%32).  oc0 / p0: output channel of row 0 / flattened pixel of column 0.
+// ss: staged (scale, offset) pairs of the workgroup tile, row0: row of oc0 inside that tile.
 template <typename T, int V>
 __device__ __forceinline__ void store_tile_staged(const float16v &acc, float *stage, int lane,
-                                                  int oc0, int p0, const TailArgs &t)
+                                                  int oc0, int p0, const TailArgs &t,
+                                                  const float *ss, int row0)
 {
     typedef typename VecIO<T, V>::vec vec;
     const int lrow = lane & 31, lhalf = lane >> 5;
@@ -135,15 +163,20 @@ __device__ __forceinline__ void store_tile_staged(const float16v &acc, float *st
         stage[(8 * (v >> 2) + 4 * lhalf + (v & 3)) * kStageStride + lrow] = acc[v];
     __builtin_amdgcn_wave_barrier();
     constexpr int G = 32 / V;                      // lane groups per row
+    // image index of the tile's first pixel: uniform, so one scalar division; a tile of 32
+    // pixels crosses into later images by repeated subtraction (at most once for OH*OW >= 32)
+    const int p0u = __builtin_amdgcn_readfirstlane(p0);
+    const int n0 = p0u / t.OHW, rem0 = p0u - n0 * t.OHW;
 #pragma unroll
     for (int it = 0; it < 32 * G / 64; ++it) {
         const int task = it * 64 + lane;
         const int row = task / G, g = task - row * G;
         const int oc = oc0 + row, p = p0 + g * V;
         if (oc < t.OC && p < t.npix) {
-            const int n = p / t.OHW, rem = p - n * t.OHW;
+            int n = n0, rem = rem0 + g * V;
+            while (rem >= t.OHW) { rem -= t.OHW; ++n; }
             const size_t idx = (size_t)(n * t.OC + oc) * t.OHW + rem;
-            const float sc = t.scale[oc], sf = t.shift[oc], bs = t.bias ? t.bias[oc] : 0.0f;
+            const float sc = ss[2 * (row0 + row)], sf = ss[2 * (row0 + row) + 1];
             float f[V], r[V];
 #pragma unroll
             for (int q = 0; q < V; ++q) f[q] = stage[row * kStageStride + g * V + q];
@@ -151,7 +184,7 @@ __device__ __forceinline__ void store_tile_staged(const float16v &acc, float *st
                 VecIO<T, V>::unpack(*reinterpret_cast<const vec *>(static_cast<const T *>(t.residual) + idx), r);
 #pragma unroll
             for (int q = 0; q < V; ++q) {
-                float o = (f[q] + bs) * sc + sf;
+                float o = fmaf(f[q], sc, sf);
                 if (t.residual) o += r[q];
                 if (t.relu) o = fmaxf(o, 0.0f);
                 f[q] = o;
@@ -185,13 +218,14 @@ __device__ __forceinline__ void store_tile_direct(const float16v &acc, int lane,
 // vmode: pixels per vector store (8, 4) or 1 for direct stores; chosen on the host.
 template <typename T>
 __device__ __forceinline__ void store_tile(const float16v &acc, float *stage, int lane, int oc0,
-                                           int p0, const TailArgs &t, int vmode)
+                                           int p0, const TailArgs &t, int vmode, const float *ss,
+                                           int row0)
 {
     if constexpr (sizeof(T) == 2) {
-        if (vmode == 8) return store_tile_staged<bf16_t, 8>(acc, stage, lane, oc0, p0, t);
-        if (vmode == 4) return store_tile_staged<bf16_t, 4>(acc, stage, lane, oc0, p0, t);
+        if (vmode == 8) return store_tile_staged<bf16_t, 8>(acc, stage, lane, oc0, p0, t, ss, row0);
+        if (vmode == 4) return store_tile_staged<bf16_t, 4>(acc, stage, lane, oc0, p0, t, ss, row0);
     } else {
-        if (vmode == 4) return store_tile_staged<float, 4>(acc, stage, lane, oc0, p0, t);
+        if (vmode == 4) return store_tile_staged<float, 4>(acc, stage, lane, oc0, p0, t, ss, row0);
     }
     store_tile_direct<T>(acc, lane, oc0, p0, t);
 }

@@ -58,6 +58,17 @@ bool conv3x3_patch_pointers_ok(const ConvPointers &ptr);
 tvg_status launch_conv3x3_patch(const ConvProblem &p, const Patch3x3Plan &plan,
                                 const ConvPointers &ptr, hipStream_t stream);
 
+// bf16 7x7 stride-2 pad-3 kernel for IC <= 4 (the ResNet stem).
+struct StemPlan {
+    int rows;           // virtual input rows staged per tile
+    int lt;             // 16-byte copy tasks per thread per tile
+    size_t lds_bytes;
+};
+bool plan_conv7x7s2_stem(const ConvProblem &p, StemPlan *plan);
+bool conv7x7s2_stem_pointers_ok(const ConvPointers &ptr);
+tvg_status launch_conv7x7s2_stem(const ConvProblem &p, const StemPlan &plan,
+                                 const ConvPointers &ptr, hipStream_t stream);
+
 tvg_status launch_conv_igemm(const ConvProblem &p, const ConvPlan &plan, const ConvPointers &ptr,
                              hipStream_t stream);
 tvg_status launch_dwconv3x3(const ConvProblem &p, const ConvPointers &ptr, hipStream_t stream);

@@ -149,6 +149,23 @@ def test_bf16_3x3_patch_kernel_ragged_shapes_all_tiles(tvg, monkeypatch, cfg, ti
     assert rel_err(to_host(y), oracle_dense(sh, inp)) <= TOL["bf16"]
 
 
+STEM_SHAPES = [
+    # bf16 7x7 stride-2 pad-3 problems with few input channels: n, ic, h, w, oc
+    (2, 3, 32, 32, 64), (3, 3, 40, 24, 70), (1, 4, 16, 16, 8), (5, 3, 18, 8, 64),
+    (2, 1, 64, 64, 16), (1, 3, 224, 224, 64), (2, 2, 50, 48, 100), (3, 3, 31, 40, 33),
+]
+
+
+@pytest.mark.parametrize("cfg", STEM_SHAPES)
+def test_bf16_7x7_stem_kernel_shapes(tvg, cfg):
+    """The stem kernel (and, for shapes it declines, its fallback) with the full fused tail."""
+    n, ic, h, w, oc = cfg
+    sh = ti.ConvShape("stem", n, ic, h, w, oc, 7, 7, 2, 3)
+    inp = ti.make_inputs(sh, 6000 + sum(cfg), "bf16", residual=True, bias=True)
+    y = run_dense(tvg, sh, inp, "bf16")
+    assert rel_err(to_host(y), oracle_dense(sh, inp)) <= TOL["bf16"]
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_rectangular_filter_and_strides(tvg, dtype):
     import torch
