@@ -55,7 +55,9 @@ tvg_status tvg_conv2d_workspace_size(const tvg_conv_desc *desc, size_t *bytes)
     if (st != TVG_OK) return st;
     tvg::Patch3x3Plan patch;
     tvg::StemPlan stem;
-    const bool single_pass = tvg::plan_conv3x3_patch(p, &patch) || tvg::plan_conv7x7s2_stem(p, &stem);
+    tvg::Pw1x1Plan pw;
+    const bool single_pass = tvg::plan_conv3x3_patch(p, &patch) ||
+                             tvg::plan_conv7x7s2_stem(p, &stem) || tvg::plan_conv1x1(p, &pw);
     *bytes = single_pass ? 0 : tvg::plan_conv(p).workspace_bytes;
     return TVG_OK;
 }
@@ -89,9 +91,12 @@ tvg_status tvg_conv2d_fused(const tvg_conv_desc *desc, const void *x, const void
     const bool stem_shape = tvg::plan_conv7x7s2_stem(p, &stem);
     if (stem_shape && tvg::conv7x7s2_stem_pointers_ok(ptr))
         return tvg::launch_conv7x7s2_stem(p, stem, ptr, stream);
+    tvg::Pw1x1Plan pw;
+    const bool pw_shape = tvg::plan_conv1x1(p, &pw);
+    if (pw_shape && tvg::conv1x1_pointers_ok(ptr)) return tvg::launch_conv1x1(p, pw, ptr, stream);
     // A problem shaped for a specialised kernel reported a zero workspace; if its pointers
     // rule that kernel out, the generic kernel runs it in a single pass over the reduction.
-    const tvg::ConvPlan plan = tvg::plan_conv(p, !(patch_shape || stem_shape));
+    const tvg::ConvPlan plan = tvg::plan_conv(p, !(patch_shape || stem_shape || pw_shape));
     if (plan.workspace_bytes > 0 && (!workspace || workspace_bytes < plan.workspace_bytes))
         return TVG_ERR_WORKSPACE;
     return tvg::launch_conv_igemm(p, plan, ptr, stream);

@@ -1,0 +1,253 @@
+// bf16 1x1 (pointwise) fused conv2d, stride 1 or 2, on MFMA: y[oc, p] = sum_ic w[oc, ic] *
+// x[ic, pixel p], a GEMM whose K axis (ic) is the slowest axis of the NCHW input.
+//
+// These layers (Table 2's C3, C5, C8, C11) have 20-80 FLOP per byte at batch 64, far
+// below the bf16 ridge of the chip, so the kernel is organised around the memory side:
+// no filter taps, no halo and no bounds masks; every thread owns fixed (pixel, channel
+// octet) slots whose byte offsets are computed once, and per K chunk of 32 channels it
+// issues its loads through a buffer descriptor (uniform base + per-lane offset + scalar
+// channel offset, i.e. no vector address arithmetic), packs 8 channels of one pixel into
+// a 16-byte LDS word (the transposition NCHW -> K-innermost happens in registers) and the
+// wave tiles run 32x32x16 MFMAs from LDS.  Weight rows are contiguous in ic and are copied
+// as 16-byte vectors.  Loads of chunk c+1 are in flight during the MFMAs of chunk c
+// (cooperative fetch + latency hiding, TVM paper Sections 4.2 and 4.4); the fused tail
+// (Section 3) runs on the accumulators with vector stores.
+#include "tvg_device.h"
+#include "tvg_internal.h"
+
+namespace tvg {
+
+namespace {
+
+struct PwArgs {
+    const bf16_t *x, *w;
+    const float *scale, *shift, *bias;
+    const bf16_t *residual;
+    bf16_t *y;
+    int N, IC, H, W, OC, OH, OW, stride, npix, relu, mtiles, vmode;
+    uint32_t x_bytes, w_bytes;
+};
+
+constexpr int kRow = 80;                 // bytes per LDS row: 32 channels (64 B) + 16 B padding
+constexpr int kKC = 32;                  // channels per K chunk
+constexpr int kRsrcFlags = 0x00020000;   // raw buffer descriptor word 3 on gfx9-family targets
+constexpr uint32_t kOutOfRange = 0xFFFFFFF0u;
+
+__device__ __forceinline__ int xcd_remap(int bid, int nb)
+{
+    const int q = nb >> 3, rem = nb & 7;
+    const int xcd = bid & 7, local = bid >> 3;
+    return xcd < rem ? xcd * (q + 1) + local : rem * (q + 1) + (xcd - rem) * q + local;
+}
+
+template <int MT, int NT>
+__global__ __launch_bounds__(256) void conv1x1_kernel(const PwArgs a)
+{
+    constexpr int WTM = MT / 2, WTN = NT / 2;
+    constexpr int MI = WTM / 32, NJ = WTN / 32;
+    constexpr int BT = NT * 4 / 256;          // (pixel, octet) slots per thread
+    constexpr int AT = (MT * 4 + 255) / 256;  // weight vectors per thread
+    constexpr int OPER = (MT + NT) * kRow;
+    constexpr int STAGE = 4 * kStageFloats * 4;
+    __shared__ __attribute__((aligned(16))) unsigned char lds[OPER > STAGE ? OPER : STAGE];
+    __shared__ float ss_lds[2 * MT];
+    unsigned char *As = lds, *Bs = lds + MT * kRow;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave & 1, wn = wave >> 1;
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    const int tile = xcd_remap(blockIdx.x, gridDim.x);
+    const int m0 = (tile % a.mtiles) * MT;
+    const int n0 = (tile / a.mtiles) * NT;
+    const int HW = a.H * a.W, OHW = a.OH * a.OW;
+
+    stage_scale_shift(ss_lds, m0, MT, a.scale, a.shift, a.bias, a.OC, tid, 256);
+
+    // ---- fixed load slots ------------------------------------------------------------------
+    uint32_t boff[BT];          // byte offset of (pixel, channel 8*octet) in x, or out of range
+    int bdst[BT], boct[BT];
+#pragma unroll
+    for (int j = 0; j < BT; ++j) {
+        const int t = tid + j * 256;
+        const int pl = t % NT, octet = t / NT;      // lanes run over pixels: coalesced loads
+        const int p = n0 + pl;
+        boct[j] = octet;
+        bdst[j] = pl * kRow + octet * 16;
+        boff[j] = 0;       // pixels past the end read pixel 0; their columns are never stored
+        if (p < a.npix) {
+            const int n = p / OHW, rem = p - n * OHW;
+            const int oh = rem / a.OW, ow = rem - oh * a.OW;
+            boff[j] = 2u * (uint32_t)((n * a.IC + octet * 8) * HW + oh * a.stride * a.W +
+                                      ow * a.stride);
+        }
+    }
+    uint32_t aoff[AT];
+    int adst[AT], akv[AT];
+#pragma unroll
+    for (int i = 0; i < AT; ++i) {
+        const int v = tid + i * 256;
+        const int row = v >> 2, kv = v & 3;
+        akv[i] = kv;
+        adst[i] = v < MT * 4 ? row * kRow + kv * 16 : -1;
+        // rows past OC read row 0; their accumulators are never stored
+        aoff[i] = 2u * (uint32_t)(((v < MT * 4 && m0 + row < a.OC) ? m0 + row : 0) * a.IC + kv * 8);
+    }
+
+    const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t *>(a.x), 0, a.x_bytes, kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t *>(a.w), 0, a.w_bytes, kRsrcFlags);
+
+    uint32_t braw[BT][8];
+    uint4v areg[AT];
+    // Full chunks (all 32 channels below IC) use the scalar offset operand for the channel
+    // term; a ragged last chunk builds complete per-lane offsets so that channels past IC
+    // are unambiguously out of range of the descriptor and read as zeros.
+    auto load_chunk = [&](int c) {
+        const int c0 = c * kKC;
+        if (c0 + kKC <= a.IC) {
+#pragma unroll
+            for (int j = 0; j < BT; ++j)
+#pragma unroll
+                for (int q = 0; q < 8; ++q)
+                    braw[j][q] =
+                        __builtin_amdgcn_raw_buffer_load_b16(xrsrc, boff[j], (c0 + q) * HW * 2, 0);
+#pragma unroll
+            for (int i = 0; i < AT; ++i)
+                areg[i] = __builtin_bit_cast(
+                    uint4v, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, aoff[i], c0 * 2, 0));
+        } else {
+#pragma unroll
+            for (int j = 0; j < BT; ++j) {
+                const bool ok = c0 + boct[j] * 8 < a.IC;
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    const uint32_t off = ok ? boff[j] + (uint32_t)((c0 + q) * HW * 2) : kOutOfRange;
+                    braw[j][q] = __builtin_amdgcn_raw_buffer_load_b16(xrsrc, off, 0, 0);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < AT; ++i) {
+                const uint32_t off = (c0 + akv[i] * 8 < a.IC) ? aoff[i] + (uint32_t)(c0 * 2) : kOutOfRange;
+                areg[i] = __builtin_bit_cast(uint4v,
+                                             __builtin_amdgcn_raw_buffer_load_b128(wrsrc, off, 0, 0));
+            }
+        }
+    };
+    auto store_chunk = [&]() {
+#pragma unroll
+        for (int j = 0; j < BT; ++j)
+            *reinterpret_cast<uint4v *>(Bs + bdst[j]) =
+                uint4v{braw[j][0] | (braw[j][1] << 16), braw[j][2] | (braw[j][3] << 16),
+                       braw[j][4] | (braw[j][5] << 16), braw[j][6] | (braw[j][7] << 16)};
+#pragma unroll
+        for (int i = 0; i < AT; ++i)
+            if (adst[i] >= 0) *reinterpret_cast<uint4v *>(As + adst[i]) = areg[i];
+    };
+
+    float16v acc[MI][NJ];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    const int nchunks = (a.IC + kKC - 1) / kKC;
+    load_chunk(0);
+    store_chunk();
+    __syncthreads();
+
+    for (int c = 0; c < nchunks; ++c) {
+        if (c + 1 < nchunks) load_chunk(c + 1);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            uint4v af[MI], bf[NJ];
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+                af[i] = *reinterpret_cast<const uint4v *>(
+                    As + (wm * WTM + i * 32 + lrow) * kRow + ks * 32 + lhalf * 16);
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+                bf[j] = *reinterpret_cast<const uint4v *>(
+                    Bs + (wn * WTN + j * 32 + lrow) * kRow + ks * 32 + lhalf * 16);
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        __builtin_bit_cast(bf16x8v, af[i]), __builtin_bit_cast(bf16x8v, bf[j]),
+                        acc[i][j], 0, 0, 0);
+        }
+        __syncthreads();
+        if (c + 1 < nchunks) {
+            store_chunk();
+            __syncthreads();
+        }
+    }
+
+    float *stage = reinterpret_cast<float *>(lds) + wave * kStageFloats;
+    const TailArgs tail{a.scale, a.shift, a.bias, a.residual, a.y, a.OC, OHW, a.npix, a.relu};
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+            store_tile<bf16_t>(acc[i][j], stage, lane, m0 + wm * WTM + i * 32,
+                               n0 + wn * WTN + j * 32, tail, a.vmode, ss_lds, wm * WTM + i * 32);
+}
+
+}  // namespace
+
+bool plan_conv1x1(const ConvProblem &p, Pw1x1Plan *plan)
+{
+    if (p.dtype != TVG_BF16 || p.R != 1 || p.S != 1 || p.ph != 0 || p.pw != 0) return false;
+    if (p.sh != p.sw || (p.sh != 1 && p.sh != 2)) return false;
+    if (p.IC % 8 != 0) return false;
+    if ((size_t)p.N * p.IC * p.H * p.W * 2 > (size_t)kOutOfRange) return false;
+    const int cands[4][2] = {{128, 128}, {64, 128}, {128, 64}, {64, 64}};
+    bool found = false, fills_best = false;
+    for (const auto &c : cands) {
+        const int mt = c[0], nt = c[1];
+        if (mt == 128 && p.OC <= 64) continue;
+        const long tiles = (long)((p.OC + mt - 1) / mt) * ((p.npix + nt - 1) / nt);
+        const bool fills = 2 * tiles >= 3 * kComputeUnits;
+        if (!found || (!fills_best && (fills || tiles > plan->tiles))) {
+            plan->mt = mt; plan->nt = nt; plan->tiles = tiles;
+            fills_best = fills;
+            found = true;
+        }
+    }
+    return found;
+}
+
+bool conv1x1_pointers_ok(const ConvPointers &ptr)
+{
+    return reinterpret_cast<uintptr_t>(ptr.w) % 16 == 0 && reinterpret_cast<uintptr_t>(ptr.x) % 2 == 0;
+}
+
+tvg_status launch_conv1x1(const ConvProblem &p, const Pw1x1Plan &plan, const ConvPointers &ptr,
+                          hipStream_t stream)
+{
+    PwArgs a;
+    a.x = static_cast<const bf16_t *>(ptr.x); a.w = static_cast<const bf16_t *>(ptr.w);
+    a.scale = ptr.scale; a.shift = ptr.shift; a.bias = ptr.bias;
+    a.residual = static_cast<const bf16_t *>(ptr.residual); a.y = static_cast<bf16_t *>(ptr.y);
+    a.N = p.N; a.IC = p.IC; a.H = p.H; a.W = p.W; a.OC = p.OC; a.OH = p.OH; a.OW = p.OW;
+    a.stride = p.sh; a.npix = p.npix; a.relu = p.relu;
+    a.mtiles = (p.OC + plan.mt - 1) / plan.mt;
+    a.vmode = pick_store_vmode(p.dtype, p.OH * p.OW, ptr.y, ptr.residual);
+    a.x_bytes = (uint32_t)((size_t)p.N * p.IC * p.H * p.W * 2);
+    a.w_bytes = (uint32_t)((size_t)p.OC * p.IC * 2);
+    const unsigned grid = (unsigned)plan.tiles;
+    if (plan.mt == 128 && plan.nt == 128)
+        hipLaunchKernelGGL((conv1x1_kernel<128, 128>), dim3(grid), dim3(256), 0, stream, a);
+    else if (plan.mt == 128)
+        hipLaunchKernelGGL((conv1x1_kernel<128, 64>), dim3(grid), dim3(256), 0, stream, a);
+    else if (plan.nt == 128)
+        hipLaunchKernelGGL((conv1x1_kernel<64, 128>), dim3(grid), dim3(256), 0, stream, a);
+    else
+        hipLaunchKernelGGL((conv1x1_kernel<64, 64>), dim3(grid), dim3(256), 0, stream, a);
+    return hipGetLastError() == hipSuccess ? TVG_OK : TVG_ERR_LAUNCH;
+}
+
+}  // namespace tvg

@@ -81,6 +81,11 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
     const int H = a.H, W = a.W, HW = H * W, OHW = a.OH * a.OW;
     const int VH = H + 2, PW = W + 2;
 
+    // Index arithmetic below divides by OH*OW, OW, W and H+2 only; the host admits this
+    // kernel when every dividend stays below 2^22, where fast_div is exact.
+    const float inv_ohw = 1.0f / (float)OHW, inv_ow = 1.0f / (float)a.OW;
+    const float inv_w = 1.0f / (float)W, inv_vh = 1.0f / (float)VH;
+
     // ---- tile geometry (uniform) ---------------------------------------------------------
     const int p_last = min(n0 + NT, a.npix) - 1;
     const int na = n0 / OHW, oha = (n0 - na * OHW) / a.OW;
@@ -109,9 +114,10 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
             if (t < 2 * per_octet) {
                 const int octet = t >= per_octet;
                 const int rem = t - octet * per_octet;
-                const int vrow = rem / W, iw = rem - vrow * W;
-                const int v = vr_lo + vrow;
-                const int n = v / VH, ih = v - n * VH - 1;
+                int iw, vi;
+                const int vrow = fast_div(rem, W, inv_w, &iw);
+                const int n = fast_div(vr_lo + vrow, VH, inv_vh, &vi);
+                const int ih = vi - 1;
                 if (ih >= 0 && ih < H && n < a.N) {
                     goff[j] = 2u * (uint32_t)((n * a.IC + octet * 8) * HW + ih * W + iw);
                     loff[j] = (vrow * PW + iw + 1) * kPosBytes + octet * 16;
@@ -127,8 +133,9 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
         const int p = n0 + wn * WTN + j * 32 + lrow;
         pb[j] = lhalf * 16;
         if (p < a.npix) {
-            const int n = p / OHW, rem = p - n * OHW;
-            const int oh = rem / a.OW, ow = rem - oh * a.OW;
+            int rem, ow;
+            const int n = fast_div(p, OHW, inv_ohw, &rem);
+            const int oh = fast_div(rem, a.OW, inv_ow, &ow);
             pb[j] += ((n * VH + oh * STRIDE - vr_lo) * PW + ow * STRIDE) * kPosBytes;
         }
     }
@@ -240,6 +247,9 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                         __builtin_bit_cast(bf16x8v, af[cur][i]),
                         __builtin_bit_cast(bf16x8v, bf[cur][j]), acc[i][j], 0, 0, 0);
+            // keep the order written here: next tap's LDS reads first, then this tap's MFMAs
+            if (tap + 1 < 9) __builtin_amdgcn_sched_group_barrier(0x100, MI + NJ, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, MI * NJ, 0);
         }
 
         if (c + 1 < nchunks) {
@@ -319,6 +329,7 @@ bool plan_conv3x3_patch(const ConvProblem &p, Patch3x3Plan *plan)
     if (p.dtype != TVG_BF16 || p.R != 3 || p.S != 3 || p.ph != 1 || p.pw != 1) return false;
     if (p.sh != p.sw || (p.sh != 1 && p.sh != 2)) return false;
     if (p.IC % kChunk != 0) return false;
+    if (p.npix >= (1 << 22) || (long)p.N * (p.H + 2) >= (1 << 22)) return false;   // fast_div range
     int force_mt = 0, force_nt = 0;
     if (const char *e = getenv("TVG_FORCE_TILE")) sscanf(e, "%d,%d", &force_mt, &force_nt);
     // Tile choice (measured on MI355X at batch 64): take the largest tile that still gives at

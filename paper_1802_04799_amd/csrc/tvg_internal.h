@@ -69,6 +69,16 @@ bool conv7x7s2_stem_pointers_ok(const ConvPointers &ptr);
 tvg_status launch_conv7x7s2_stem(const ConvProblem &p, const StemPlan &plan,
                                  const ConvPointers &ptr, hipStream_t stream);
 
+// bf16 1x1 (pointwise) kernel, stride 1 or 2, IC a multiple of 8.
+struct Pw1x1Plan {
+    int mt, nt;
+    long tiles;
+};
+bool plan_conv1x1(const ConvProblem &p, Pw1x1Plan *plan);
+bool conv1x1_pointers_ok(const ConvPointers &ptr);
+tvg_status launch_conv1x1(const ConvProblem &p, const Pw1x1Plan &plan, const ConvPointers &ptr,
+                          hipStream_t stream);
+
 tvg_status launch_conv_igemm(const ConvProblem &p, const ConvPlan &plan, const ConvPointers &ptr,
                              hipStream_t stream);
 tvg_status launch_dwconv3x3(const ConvProblem &p, const ConvPointers &ptr, hipStream_t stream);

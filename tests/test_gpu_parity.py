@@ -166,6 +166,22 @@ def test_bf16_7x7_stem_kernel_shapes(tvg, cfg):
     assert rel_err(to_host(y), oracle_dense(sh, inp)) <= TOL["bf16"]
 
 
+PW_SHAPES = [
+    # bf16 1x1 problems with IC % 8 == 0: n, ic, h, w, oc, stride
+    (2, 8, 9, 9, 33, 1), (3, 40, 15, 13, 70, 2), (1, 64, 56, 56, 64, 1), (2, 72, 7, 7, 130, 1),
+    (5, 16, 6, 10, 8, 2), (1, 264, 3, 5, 200, 1), (4, 32, 28, 28, 256, 2), (1, 8, 1, 1, 1, 1),
+]
+
+
+@pytest.mark.parametrize("cfg", PW_SHAPES)
+def test_bf16_1x1_kernel_shapes(tvg, cfg):
+    n, ic, h, w, oc, stride = cfg
+    sh = ti.ConvShape("pw", n, ic, h, w, oc, 1, 1, stride, 0)
+    inp = ti.make_inputs(sh, 8000 + sum(cfg), "bf16", residual=True, bias=True)
+    y = run_dense(tvg, sh, inp, "bf16")
+    assert rel_err(to_host(y), oracle_dense(sh, inp)) <= TOL["bf16"]
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_rectangular_filter_and_strides(tvg, dtype):
     import torch
