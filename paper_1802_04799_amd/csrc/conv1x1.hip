@@ -188,12 +188,8 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const PwArgs a)
 
     float *stage = reinterpret_cast<float *>(lds) + wave * kStageFloats;
     const TailArgs tail{a.scale, a.shift, a.bias, a.residual, a.y, a.OC, OHW, a.npix, a.relu};
-#pragma unroll
-    for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < NJ; ++j)
-            store_tile<bf16_t>(acc[i][j], stage, lane, m0 + wm * WTM + i * 32,
-                               n0 + wn * WTN + j * 32, tail, a.vmode, ss_lds, wm * WTM + i * 32);
+    store_acc_tiles<bf16_t, MI, NJ>(acc, stage, lane, m0 + wm * WTM, n0 + wn * WTN, tail, a.vmode,
+                                    ss_lds, wm * WTM);
 }
 
 }  // namespace

@@ -263,12 +263,8 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
     __syncthreads();                       // every wave is done reading the operand tiles
     float *stage = reinterpret_cast<float *>(smem) + wave * kStageFloats;
     const TailArgs tail{a.scale, a.shift, a.bias, a.residual, a.y, a.OC, OHW, a.npix, a.relu};
-#pragma unroll
-    for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < NJ; ++j)
-            store_tile<bf16_t>(acc[i][j], stage, lane, m0 + wm * WTM + i * 32,
-                               n0 + wn * WTN + j * 32, tail, a.vmode, ss_lds, wm * WTM + i * 32);
+    store_acc_tiles<bf16_t, MI, NJ>(acc, stage, lane, m0 + wm * WTM, n0 + wn * WTN, tail, a.vmode,
+                                    ss_lds, wm * WTM);
 }
 
 // Largest number of virtual rows any pixel tile of NT pixels needs.

@@ -195,12 +195,7 @@ __global__ __launch_bounds__(256, 2) void conv7x7s2_stem_kernel(const StemArgs a
         // now, so that waiting for those loads does not also wait for this tile's stores.
         if (next < a.ntiles) store_tile_rows((it + 1) & 1);
 
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-                store_tile<bf16_t>(acc[i][j], stage, lane, m0 + i * 32, p0 + wave * 64 + j * 32,
-                                   tail, a.vmode, ss_lds, i * 32);
+        store_acc_tiles<bf16_t, 2, 2>(acc, stage, lane, m0, p0 + wave * 64, tail, a.vmode, ss_lds, 0);
         __syncthreads();
     }
 }

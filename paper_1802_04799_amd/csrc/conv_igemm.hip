@@ -233,12 +233,8 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(const IgemmArgs a)
         // the loop ended on a barrier: the operand buffers are free to stage the transposes
         float *stage = reinterpret_cast<float *>(lds) + wave * kStageFloats;
         const TailArgs tail{a.scale, a.shift, a.bias, a.residual, a.y, a.OC, OHW, a.npix, a.relu};
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
-#pragma unroll
-            for (int j = 0; j < NJ; ++j)
-                store_tile<T>(acc[i][j], stage, lane, m0 + wm * WTM + i * 32,
-                              n0 + wn * 64 + j * 32, tail, a.vmode, ss_lds, wm * WTM + i * 32);
+        store_acc_tiles<T, MI, NJ>(acc, stage, lane, m0 + wm * WTM, n0 + wn * 64, tail, a.vmode,
+                                   ss_lds, wm * WTM);
         return;
     }
     // Accumulator v of lane l in a 32x32 tile: row 8*(v/4) + 4*(l/32) + v%4, column l%32.

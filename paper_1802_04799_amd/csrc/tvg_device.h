@@ -245,6 +245,30 @@ __device__ __forceinline__ void store_tile(const float16v &acc, float *stage, in
     store_tile_direct<T>(acc, lane, oc0, p0, t);
 }
 
+// All MI x NJ accumulator tiles of a wave, one after the other through ONE copy of the
+// store code: the loop is kept rolled and the tile is picked by uniform selects, because
+// inlining the epilogue per tile multiplies the code size and the kernels' hot loops then
+// no longer fit the instruction cache.
+template <typename T, int MI, int NJ>
+__device__ __forceinline__ void store_acc_tiles(const float16v (&acc)[MI][NJ], float *stage,
+                                                int lane, int oc_base, int p_base,
+                                                const TailArgs &t, int vmode, const float *ss,
+                                                int row_base)
+{
+#pragma unroll 1
+    for (int k = 0; k < MI * NJ; ++k) {
+        float16v cur = acc[0][0];
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+                if (i * NJ + j == k) cur = acc[i][j];
+        const int i = k / NJ, j = k - i * NJ;
+        store_tile<T>(cur, stage, lane, oc_base + i * 32, p_base + j * 32, t, vmode, ss,
+                      row_base + i * 32);
+    }
+}
+
 // Host side: widest staged store the problem allows.
 inline int pick_store_vmode(int dtype, int OHW, const void *y, const void *residual)
 {

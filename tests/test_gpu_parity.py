@@ -149,6 +149,30 @@ def test_bf16_3x3_patch_kernel_ragged_shapes_all_tiles(tvg, monkeypatch, cfg, ti
     assert rel_err(to_host(y), oracle_dense(sh, inp)) <= TOL["bf16"]
 
 
+PATCH_WIDE = [
+    # bf16 3x3 pad-1 problems with 64 or more input channels: n, ic, h, w, oc, stride
+    (2, 64, 9, 11, 40, 1), (3, 64, 10, 13, 70, 2), (5, 96, 7, 7, 130, 1), (2, 128, 14, 14, 256, 1),
+    (1, 64, 30, 70, 16, 1), (2, 64, 33, 40, 200, 2), (7, 64, 7, 7, 64, 2), (1, 64, 1, 1, 64, 1),
+    (3, 80, 5, 6, 8, 2), (40, 64, 7, 7, 64, 1), (2, 64, 56, 56, 64, 1), (9, 128, 28, 28, 128, 1),
+]
+
+
+@pytest.mark.parametrize("tile", ["", "128,128", "64,128", "64,64"])
+@pytest.mark.parametrize("cfg", PATCH_WIDE)
+def test_bf16_3x3_patch_kernel_many_chunks(tvg, monkeypatch, cfg, tile):
+    """The 3x3 patch kernel with several channel chunks per tile: tiles that straddle images,
+    ragged channel and pixel tails, every tile shape."""
+    n, ic, h, w, oc, stride = cfg
+    if tile:
+        monkeypatch.setenv("TVG_FORCE_TILE", tile)
+    else:
+        monkeypatch.delenv("TVG_FORCE_TILE", raising=False)
+    sh = ti.ConvShape("pw3", n, ic, h, w, oc, 3, 3, stride, 1)
+    inp = ti.make_inputs(sh, 9000 + sum(cfg), "bf16", residual=True, bias=True)
+    y = run_dense(tvg, sh, inp, "bf16")
+    assert rel_err(to_host(y), oracle_dense(sh, inp)) <= TOL["bf16"]
+
+
 STEM_SHAPES = [
     # bf16 7x7 stride-2 pad-3 problems with few input channels: n, ic, h, w, oc
     (2, 3, 32, 32, 64), (3, 3, 40, 24, 70), (1, 4, 16, 16, 8), (5, 3, 18, 8, 64),
