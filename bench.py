@@ -36,6 +36,11 @@ def parse():
     ap.add_argument("--skip-extras", action="store_true",
                     help="only the timed region (for profiler runs)")
     ap.add_argument("--skip-cpu", action="store_true", help="do not time the CPU oracle")
+    ap.add_argument("--only", default="", help="comma-separated layer names (C1..C12): restrict "
+                    "the step to these layers (for profiler runs)")
+    ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
+                    help="only run a plain device copy of this many MiB --steps times "
+                         "(reference for scaling FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
 
 
@@ -43,7 +48,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only; --gpus must be 1 "
-                 "(the path shards along the batch axis with no exchange, see DESIGN.md)")
+                 "(the path would shard along the batch axis with no exchange)")
     import numpy as np
     import torch
     import tvg_inputs as ti
@@ -104,8 +109,20 @@ def main():
         return e0.elapsed_time(e1) / iters
 
     # ---------------------------------------------------------------- the timed region
+    if args.copy_probe:
+        return copy_probe(torch, args)
     shapes = ti.resnet18_convs(64)
     layers = [Layer(sh, ti.layer_seed(4, i), "bf16") for i, sh in enumerate(shapes)]
+    if args.only:
+        keep = set(args.only.split(","))
+        layers = [l for l in layers if l.sh.name in keep]
+    # The twelve layers are independent; they are launched with the seven 3x3 layers (one
+    # kernel: conv3x3_patch_kernel, the largest share of the step) last and back to back, so
+    # that two events per step bracket exactly that kernel's launches.
+    is_dom = lambda l: l.sh.r == 3
+    layers = [l for l in layers if not is_dom(l)] + [l for l in layers if is_dom(l)]
+    n_dom = sum(1 for l in layers if is_dom(l))
+    first_dom = len(layers) - n_dom
     step_flops = sum(l.sh.flops for l in layers)
     step_bytes = sum(l.bytes for l in layers)
 
@@ -116,24 +133,38 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    K = args.steps
-    # one event before every launch and one after the last: per-launch durations measured
-    # inside the timed region, on the stream the kernels run on
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(layers) + 1)] for _ in range(K)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(K):
+
+    # per-layer durations: a calibration pass with an event before every launch, outside the
+    # timed region (the extra events cost about 4 us per launch)
+    cal = 5
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(layers) + 1)] for _ in range(cal)]
+    for k in range(cal):
         for i, l in enumerate(layers):
             ev[k][i].record()
             l.launch()
         ev[k][len(layers)].record()
     torch.cuda.synchronize()
+    per_layer_ms = [sum(ev[k][i].elapsed_time(ev[k][i + 1]) for k in range(cal)) / cal
+                    for i in range(len(layers))]
+    del ev
+
+    K = args.steps
+    d0 = [torch.cuda.Event(enable_timing=True) for _ in range(K)]
+    d1 = [torch.cuda.Event(enable_timing=True) for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(K):
+        for i, l in enumerate(layers):
+            if i == first_dom and n_dom:
+                d0[k].record()
+            l.launch()
+        if n_dom:
+            d1[k].record()
+    torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / K
     value = step_flops / (wall / K) / 1e12
 
-    per_layer_ms = [sum(ev[k][i].elapsed_time(ev[k][i + 1]) for k in range(K)) / K
-                    for i in range(len(layers))]
     layer_rows = []
     for l, ms in zip(layers, per_layer_ms):
         tf = l.sh.flops / (ms * 1e-3) / 1e12
@@ -144,13 +175,24 @@ def main():
                            "gbs": round(gbs, 1), "frac_mfma_peak": round(tf / PEAK_BF16_TFLOPS, 4),
                            "frac_attainable": round(tf / attainable, 4),
                            "bound": "mfma" if ai > PEAK_BF16_TFLOPS * 1e3 / PEAK_HBM_GBS else "hbm"})
-    dom = max(range(len(layers)), key=lambda i: per_layer_ms[i])
-    dl = layers[dom]
-    dom_tf = dl.sh.flops / (per_layer_ms[dom] * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "conv_igemm_kernel<bf16> on " + dl.sh.name,
-                "achieved": round(dom_tf, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(dom_tf / PEAK_BF16_TFLOPS, 4), "traffic": None,
-                "flops_per_launch": dl.sh.flops, "avg_launch_us": round(per_layer_ms[dom] * 1e3, 2)}
+    roofline = None
+    if n_dom:
+        dom_ms = sum(d0[k].elapsed_time(d1[k]) for k in range(K)) / K      # all n_dom launches
+        dom_flops = sum(l.sh.flops for l in layers if is_dom(l))
+        dom_bytes = sum(l.bytes for l in layers if is_dom(l))
+        dom_tf = dom_flops / (dom_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": round(dom_tf, 2), "peak": PEAK_BF16_TFLOPS,
+                    "unit": "TFLOP/s", "frac": round(dom_tf / PEAK_BF16_TFLOPS, 4),
+                    "traffic": measured_traffic("conv3x3_patch_kernel"),
+                    "kernel": "conv3x3_patch_kernel<bf16>",
+                    "launches_per_step": n_dom,
+                    "layers": [l.sh.name for l in layers if is_dom(l)],
+                    "flops_per_launch": dom_flops / n_dom,
+                    "algorithmic_bytes_per_launch": dom_bytes / n_dom,
+                    "avg_launch_us": round(dom_ms * 1e3 / n_dom, 2),
+                    "share_of_step_time": round(dom_ms / ms_per_step, 3),
+                    "timing": "two HIP events per step around the kernel's back-to-back launches, "
+                              "inside the timed region, on the launch stream"}
 
     out = {
         "metric": "fused conv2d TFLOP/s (% MFMA peak); depthwise conv GB/s (% HBM peak)",
@@ -159,16 +201,17 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "configs[3]: the 12 ResNet-18 conv2d shapes of Table 2 (C1..C12), "
                                "batch 64, bf16 in/out, fp32 accumulate, fused scale/shift+ReLU; "
-                               "one step = 12 launches",
+                               "one step = 12 launches" + (f" (restricted to {args.only})" if args.only else ""),
                    "step_gflop": round(step_flops / 1e9, 2), "step_mbytes": round(step_bytes / 1e6, 1),
                    "frac_mfma_peak": round(value / PEAK_BF16_TFLOPS, 4)},
         "roofline": roofline,
         "layers": layer_rows,
+        "layers_note": "per-launch durations from a calibration pass with an event before every "
+                       "launch (adds about 4 us per launch); not part of the timed region",
     }
 
     # ------------------------------------------------------------ extras (not in `value`)
     if not args.skip_extras:
-        del ev
         # depthwise D1..D9, fp32, batch 1: warm (same buffers) and cold (rotating > 512 MB)
         dw_rows = []
         for i, sh in enumerate(ti.mobilenet_depthwise(1)):
@@ -235,6 +278,28 @@ def main():
     print(json.dumps(out))
 
 
+def copy_probe(torch, args):
+    n = args.copy_probe * 1024 * 1024 // 4
+    x = torch.ones(n, dtype=torch.float32, device="cuda")
+    y = torch.empty_like(x)
+    torch.cuda.synchronize()
+    for _ in range(args.steps):
+        y.copy_(x)
+    torch.cuda.synchronize()
+    print(json.dumps({"copy_probe_mib": args.copy_probe, "copies": args.steps}))
+
+
+def measured_traffic(kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary
+    (profiles/hbm_traffic.json, written from two --pmc runs), or None when there is none."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(kernel, {}).get("bytes_per_launch")
+    except (OSError, ValueError):
+        return None
+
+
 def bench_body(tvg, ti, torch, np, dev, to_dev, time_loop):
     n = 32
     steps = ti.resnet18_body(n)
@@ -282,7 +347,7 @@ def bench_body(tvg, ti, torch, np, dev, to_dev, time_loop):
 def cpu_baseline(ti, np):
     """The fp64 oracle, as it stands, on a bounded sample of the timed workload."""
     import oracle
-    batch = 16
+    batch = 64
     shapes = ti.resnet18_convs(batch)
     flops, secs = 0, 0.0
     for i, sh in enumerate(shapes):
@@ -294,7 +359,7 @@ def cpu_baseline(ti, np):
         flops += sh.flops
     return {"value": round(flops / secs / 1e12, 6), "unit": "TFLOP/s",
             "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": f"the same 12 shapes at batch {batch} of 64 ({flops / 1e9:.1f} GFLOP, "
+            "sample": f"one whole step: the same 12 shapes at batch {batch} ({flops / 1e9:.1f} GFLOP, "
                       f"{secs:.1f} s), fp64 seven-loop direct convolution + fused tail",
             "seconds": round(secs, 2)}
 

@@ -26,6 +26,7 @@ struct PwArgs {
     bf16_t *y;
     int N, IC, H, W, OC, OH, OW, stride, npix, relu, mtiles, vmode;
     uint32_t x_bytes, w_bytes;
+    int ntiles, m_major;
 };
 
 constexpr int kRow = 80;                 // bytes per LDS row: 32 channels (64 B) + 16 B padding
@@ -57,8 +58,11 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const PwArgs a)
     const int wm = wave & 1, wn = wave >> 1;
     const int lrow = lane & 31, lhalf = lane >> 5;
     const int tile = xcd_remap(blockIdx.x, gridDim.x);
-    const int m0 = (tile % a.mtiles) * MT;
-    const int n0 = (tile / a.mtiles) * NT;
+    // Consecutive tiles (which share an XCD's L2) share the larger operand: the same pixel
+    // tile under all channel tiles, or - when the weights outweigh the input - the same
+    // channel tile over consecutive pixel tiles.
+    const int m0 = (a.m_major ? tile / a.ntiles : tile % a.mtiles) * MT;
+    const int n0 = (a.m_major ? tile % a.ntiles : tile / a.mtiles) * NT;
     const int HW = a.H * a.W, OHW = a.OH * a.OW;
 
     stage_scale_shift(ss_lds, m0, MT, a.scale, a.shift, a.bias, a.OC, tid, 256);
@@ -231,6 +235,8 @@ tvg_status launch_conv1x1(const ConvProblem &p, const Pw1x1Plan &plan, const Con
     a.N = p.N; a.IC = p.IC; a.H = p.H; a.W = p.W; a.OC = p.OC; a.OH = p.OH; a.OW = p.OW;
     a.stride = p.sh; a.npix = p.npix; a.relu = p.relu;
     a.mtiles = (p.OC + plan.mt - 1) / plan.mt;
+    a.ntiles = (p.npix + plan.nt - 1) / plan.nt;
+    a.m_major = (size_t)p.OC * p.IC > (size_t)p.N * p.IC * p.H * p.W;
     a.vmode = pick_store_vmode(p.dtype, p.OH * p.OW, ptr.y, ptr.residual);
     a.x_bytes = (uint32_t)((size_t)p.N * p.IC * p.H * p.W * 2);
     a.w_bytes = (uint32_t)((size_t)p.OC * p.IC * 2);

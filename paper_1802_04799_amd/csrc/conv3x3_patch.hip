@@ -43,6 +43,7 @@ struct PatchArgs {
     int vmode;        // pixels per vector store in the epilogue (8, 4 or 1)
     uint32_t x_bytes, w_bytes;
     int ss_offset;    // byte offset in LDS of the staged (scale, offset) pairs
+    int ntiles, m_major;
 };
 
 constexpr int kPosBytes = 48;    // 16 channels (32 B) + 16 B padding: conflict-free 16-byte reads
@@ -75,8 +76,11 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
     const int lrow = lane & 31, lhalf = lane >> 5;
 
     const int tile = xcd_remap(blockIdx.x, gridDim.x);
-    const int m0 = (tile % a.mtiles) * MT;
-    const int n0 = (tile / a.mtiles) * NT;
+    // Consecutive tiles (which share an XCD's L2) share the larger operand: the same pixel
+    // tile under all channel tiles, or - when the weights outweigh the input - the same
+    // channel tile over consecutive pixel tiles.
+    const int m0 = (a.m_major ? tile / a.ntiles : tile % a.mtiles) * MT;
+    const int n0 = (a.m_major ? tile % a.ntiles : tile / a.mtiles) * NT;
 
     const int H = a.H, W = a.W, HW = H * W, OHW = a.OH * a.OW;
     const int VH = H + 2, PW = W + 2;
@@ -375,6 +379,8 @@ tvg_status launch_conv3x3_patch(const ConvProblem &p, const Patch3x3Plan &plan,
     a.x_bytes = (uint32_t)((size_t)p.N * p.IC * p.H * p.W * 2);
     a.w_bytes = (uint32_t)((size_t)p.OC * p.IC * 9 * 2);
     const int ntiles = (p.npix + plan.nt - 1) / plan.nt;
+    a.ntiles = ntiles;
+    a.m_major = (size_t)p.OC * p.IC * 9 > (size_t)p.N * p.IC * p.H * p.W;
     if (plan.mt == 128 && plan.nt == 128)
         return launch_stride<128, 128>(a, p.sh, ntiles, plan.lds_bytes, plan.pt, stream);
     if (plan.mt == 128)
