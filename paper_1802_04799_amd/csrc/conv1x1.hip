@@ -49,7 +49,7 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const PwArgs a)
     constexpr int BT = NT * 4 / 256;          // (pixel, octet) slots per thread
     constexpr int AT = (MT * 4 + 255) / 256;  // weight vectors per thread
     constexpr int OPER = (MT + NT) * kRow;
-    constexpr int STAGE = 4 * kStageFloats * 4;
+    constexpr int STAGE = 4 * kStageBytes;
     __shared__ __attribute__((aligned(16))) unsigned char lds[OPER > STAGE ? OPER : STAGE];
     __shared__ float ss_lds[2 * MT];
     unsigned char *As = lds, *Bs = lds + MT * kRow;
@@ -179,8 +179,9 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const PwArgs a)
             for (int i = 0; i < MI; ++i)
 #pragma unroll
                 for (int j = 0; j < NJ; ++j)
+                    // pixel operand first: the accumulator tile is D[pixel][channel]
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        __builtin_bit_cast(bf16x8v, af[i]), __builtin_bit_cast(bf16x8v, bf[j]),
+                        __builtin_bit_cast(bf16x8v, bf[j]), __builtin_bit_cast(bf16x8v, af[i]),
                         acc[i][j], 0, 0, 0);
         }
         __syncthreads();
@@ -190,7 +191,7 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const PwArgs a)
         }
     }
 
-    float *stage = reinterpret_cast<float *>(lds) + wave * kStageFloats;
+    unsigned char *stage = lds + wave * kStageBytes;
     const TailArgs tail{a.scale, a.shift, a.bias, a.residual, a.y, a.OC, OHW, a.npix, a.relu};
     store_acc_tiles<bf16_t, MI, NJ>(acc, stage, lane, m0 + wm * WTM, n0 + wn * WTN, tail, a.vmode,
                                     ss_lds, wm * WTM);

@@ -248,9 +248,10 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
             for (int i = 0; i < MI; ++i)
 #pragma unroll
                 for (int j = 0; j < NJ; ++j)
+                    // pixel operand first: the accumulator tile is D[pixel][channel]
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        __builtin_bit_cast(bf16x8v, af[cur][i]),
-                        __builtin_bit_cast(bf16x8v, bf[cur][j]), acc[i][j], 0, 0, 0);
+                        __builtin_bit_cast(bf16x8v, bf[cur][j]),
+                        __builtin_bit_cast(bf16x8v, af[cur][i]), acc[i][j], 0, 0, 0);
             // keep the order written here: next tap's LDS reads first, then this tap's MFMAs
             if (tap + 1 < 9) __builtin_amdgcn_sched_group_barrier(0x100, MI + NJ, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, MI * NJ, 0);
@@ -265,7 +266,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
 
     // ---- fused tail: transpose each 32x32 tile through LDS, vector stores -----------------
     __syncthreads();                       // every wave is done reading the operand tiles
-    float *stage = reinterpret_cast<float *>(smem) + wave * kStageFloats;
+    unsigned char *stage = smem + wave * kStageBytes;
     const TailArgs tail{a.scale, a.shift, a.bias, a.residual, a.y, a.OC, OHW, a.npix, a.relu};
     store_acc_tiles<bf16_t, MI, NJ>(acc, stage, lane, m0 + wm * WTM, n0 + wn * WTN, tail, a.vmode,
                                     ss_lds, wm * WTM);

@@ -62,8 +62,7 @@ __global__ __launch_bounds__(256, 2) void conv7x7s2_stem_kernel(const StemArgs a
     const int patch_bytes = IC * nrows * pitch;
     unsigned char *As = smem;                            // [pair][oc][8 taps]
     unsigned char *Ps = smem + a_bytes;                  // 2 x [ic][row][W + 8]
-    float *stage = reinterpret_cast<float *>(smem + a_bytes + 2 * patch_bytes) +
-                   (threadIdx.x >> 6) * kStageFloats;
+    unsigned char *stage = smem + a_bytes + 2 * patch_bytes + (threadIdx.x >> 6) * kStageBytes;
     float *ss_lds = reinterpret_cast<float *>(smem + a_bytes + 2 * patch_bytes) + 4 * kStageFloats;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -186,8 +185,9 @@ __global__ __launch_bounds__(256, 2) void conv7x7s2_stem_kernel(const StemArgs a
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j)
+                    // pixel operand first: the accumulator tile is D[pixel][channel]
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        __builtin_bit_cast(bf16x8v, af[i]), __builtin_bit_cast(bf16x8v, bf[j]),
+                        __builtin_bit_cast(bf16x8v, bf[j]), __builtin_bit_cast(bf16x8v, af[i]),
                         acc[i][j], 0, 0, 0);
         }
 
@@ -242,7 +242,7 @@ bool plan_conv7x7s2_stem(const ConvProblem &p, StemPlan *plan)
     if (rows > p.H + 6) return false;                   // a tile may wrap into the next image once
     const int nm = (p.IC * 7 + 1) / 2;
     const size_t lds = (size_t)2 * nm * kMT * 16 + (size_t)2 * p.IC * rows * (p.W + 8) * 2 +
-                       (size_t)4 * kStageFloats * sizeof(float) + (size_t)kMT * 8;
+                       (size_t)4 * kStageBytes + (size_t)kMT * 8;
     const int lt = (p.IC * rows * (p.W / 8) + 255) / 256;
     if (lds > 80 * 1024 || lt > 8) return false;
     plan->rows = rows;

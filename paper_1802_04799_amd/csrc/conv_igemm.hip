@@ -221,7 +221,8 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(const IgemmArgs a)
 #pragma unroll
             for (int i = 0; i < MI; ++i)
 #pragma unroll
-                for (int j = 0; j < NJ; ++j) Mma<T>::run(acc[i][j], af[i], bf[j]);
+                // pixel operand first: the accumulator tile is D[pixel][channel]
+                for (int j = 0; j < NJ; ++j) Mma<T>::run(acc[i][j], bf[j], af[i]);
         }
 
         if (c + 1 < nchunks) store_chunk(buf ^ 1);
@@ -231,27 +232,26 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(const IgemmArgs a)
     // ---- fused tail on the accumulators (or raw partials when the reduction is split) -----
     if (a.splits == 1) {
         // the loop ended on a barrier: the operand buffers are free to stage the transposes
-        float *stage = reinterpret_cast<float *>(lds) + wave * kStageFloats;
+        unsigned char *stage = lds + wave * kStageBytes;
         const TailArgs tail{a.scale, a.shift, a.bias, a.residual, a.y, a.OC, OHW, a.npix, a.relu};
         store_acc_tiles<T, MI, NJ>(acc, stage, lane, m0 + wm * WTM, n0 + wn * 64, tail, a.vmode,
                                    ss_lds, wm * WTM);
         return;
     }
-    // Accumulator v of lane l in a 32x32 tile: row 8*(v/4) + 4*(l/32) + v%4, column l%32.
+    // Accumulator v of lane l in a 32x32 tile: pixel 8*(v/4) + 4*(l/32) + v%4, channel l%32.
     const size_t total = (size_t)a.npix * a.OC;
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) {
-        const int p = n0 + wn * 64 + j * 32 + lrow;
-        if (p >= a.npix) continue;
-        const int n = p / OHW, rem = p - n * OHW;
-        const int obase = n * a.OC * OHW + rem;
+    for (int i = 0; i < MI; ++i) {
+        const int oc = m0 + wm * WTM + i * 32 + lrow;
+        if (oc >= a.OC) continue;
 #pragma unroll
-        for (int i = 0; i < MI; ++i) {
+        for (int j = 0; j < NJ; ++j) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int oc = m0 + wm * WTM + i * 32 + 8 * (v >> 2) + 4 * lhalf + (v & 3);
-                if (oc >= a.OC) continue;
-                a.ws[(size_t)split * total + obase + oc * OHW] = acc[i][j][v];
+                const int p = n0 + wn * 64 + j * 32 + 8 * (v >> 2) + 4 * lhalf + (v & 3);
+                if (p >= a.npix) continue;
+                const int n = p / OHW, rem = p - n * OHW;
+                a.ws[(size_t)split * total + (size_t)(n * a.OC + oc) * OHW + rem] = acc[i][j][v];
             }
         }
     }

@@ -73,15 +73,21 @@ __device__ __forceinline__ void fused_tail_store(float acc, float scale, float s
 // ---------------------------------------------------------------------------------------
 // Tile epilogue shared by the MFMA kernels.
 //
-// A 32x32 fp32 accumulator tile (rows = output channels, columns = consecutive
-// output pixels) leaves the MFMA with one pixel per lane, which would mean one
-// 2- or 4-byte store per value.  Instead the wave transposes the tile through a
-// private 32 x 36 float staging area in LDS so that each lane owns V consecutive
-// pixels of one channel, applies the fused tail to them and moves residual and y
-// as 8- or 16-byte vectors (64 contiguous bytes or more per channel row).
-// V consecutive pixels starting at a multiple of V lie in one image and are
-// contiguous and aligned in NCHW exactly when OH*OW is a multiple of V; the
-// caller selects V accordingly (V = 1: no staging, direct stores).
+// The kernels feed the MFMA with the pixel operand first and the weight operand second, so
+// a 32x32 accumulator tile comes out as D[pixel][channel]: value v of lane l belongs to
+// channel l%32 and pixel 8*(v/4) + 4*(l/32) + v%4, i.e. a lane holds four groups of four
+// CONSECUTIVE pixels of ONE output channel.  The fused tail (one FMA with the channel's
+// scale and offset, residual add, ReLU clamp, rounding) is therefore applied in place, with
+// one (scale, offset) pair per lane, and a group packs into one 8-byte (bf16) or 16-byte
+// (fp32) piece of an NCHW row without any data exchange.  Three store modes, chosen on the
+// host from OH*OW and the pointers' alignment:
+//   8  (bf16, OH*OW % 8 == 0)  the packed groups go through a wave-private LDS area
+//      (32 channel rows x 64 B, row stride 80 B) and leave as 16-byte stores, four lanes per
+//      channel row = 64 contiguous bytes;
+//   4  (OH*OW % 4 == 0)        each group is stored directly (8 or 16 bytes per lane);
+//   1  (anything else)         element-wise stores with a per-pixel index.
+// Four consecutive pixels starting at a multiple of four lie in one image and are contiguous
+// and aligned in NCHW exactly when OH*OW is a multiple of four.
 // ---------------------------------------------------------------------------------------
 struct TailArgs {
     const float *scale, *shift, *bias;
@@ -90,13 +96,14 @@ struct TailArgs {
     int OC, OHW, npix, relu;
 };
 
-constexpr int kStageStride = 36;                       // floats per staged row (32 + 4 padding)
-constexpr int kStageFloats = 32 * kStageStride;        // per wave
+constexpr int kStageRow = 80;                          // bytes per staged channel row
+constexpr int kStageBytes = 32 * kStageRow;            // per wave
+constexpr int kStageFloats = kStageBytes / 4;
 
 // Puts the per-channel multiplier and offset of a tile's `rows` output channels into LDS as
 // (scale, bias*scale + shift) pairs, so the epilogue reads them with LDS latency instead of
-// issuing dependent global loads per store.  (acc + bias)*scale + shift == acc*scale + that
-// offset.  Call before a barrier that precedes the first staged store.
+// issuing dependent global loads.  (acc + bias)*scale + shift == acc*scale + that offset.
+// Call before a barrier that precedes the first store_tile.
 __device__ __forceinline__ void stage_scale_shift(float *ss, int m0, int rows, const float *scale,
                                                   const float *shift, const float *bias, int OC,
                                                   int tid, int nthreads)
@@ -113,163 +120,126 @@ __device__ __forceinline__ void stage_scale_shift(float *ss, int m0, int rows, c
     }
 }
 
-template <typename T, int V> struct VecIO;
-template <> struct VecIO<bf16_t, 8> {
-    typedef uint4v vec;
-    static __device__ __forceinline__ void unpack(const vec &r, float *f)
-    {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            f[2 * q] = __uint_as_float(r[q] << 16);
-            f[2 * q + 1] = __uint_as_float(r[q] & 0xFFFF0000u);
-        }
-    }
+typedef uint32_t uint2v __attribute__((ext_vector_type(2)));
+
+// Four fp32 values -> the dtype's packed group, and a packed group -> four fp32 values.
+template <typename T> struct Group4;
+template <> struct Group4<bf16_t> {
+    typedef uint2v vec;
     static __device__ __forceinline__ vec pack(const float *f)
     {
-        vec r;
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-            r[q] = f32x2_to_bf16x2(f[2 * q], f[2 * q + 1]);
-        return r;
+        return vec{f32x2_to_bf16x2(f[0], f[1]), f32x2_to_bf16x2(f[2], f[3])};
     }
-};
-template <> struct VecIO<bf16_t, 4> {
-    typedef uint32_t vec __attribute__((ext_vector_type(2)));
     static __device__ __forceinline__ void unpack(const vec &r, float *f)
     {
-#pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            f[2 * q] = __uint_as_float(r[q] << 16);
-            f[2 * q + 1] = __uint_as_float(r[q] & 0xFFFF0000u);
-        }
-    }
-    static __device__ __forceinline__ vec pack(const float *f)
-    {
-        vec r;
-#pragma unroll
-        for (int q = 0; q < 2; ++q)
-            r[q] = f32x2_to_bf16x2(f[2 * q], f[2 * q + 1]);
-        return r;
+        f[0] = __uint_as_float(r[0] << 16); f[1] = __uint_as_float(r[0] & 0xFFFF0000u);
+        f[2] = __uint_as_float(r[1] << 16); f[3] = __uint_as_float(r[1] & 0xFFFF0000u);
     }
 };
-template <> struct VecIO<float, 4> {
+template <> struct Group4<float> {
     typedef float4v vec;
+    static __device__ __forceinline__ vec pack(const float *f) { return vec{f[0], f[1], f[2], f[3]}; }
     static __device__ __forceinline__ void unpack(const vec &r, float *f)
     {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) f[q] = r[q];
+        f[0] = r[0]; f[1] = r[1]; f[2] = r[2]; f[3] = r[3];
     }
-    static __device__ __forceinline__ vec pack(const float *f) { return vec{f[0], f[1], f[2], f[3]}; }
 };
 
-// acc: one 32x32 MFMA accumulator tile (value v of lane l = row 8*(v/4) + 4*(l/32) + v%4,
-// column l%32).  oc0 / p0: output channel of row 0 / flattened pixel of column 0.
-// ss: staged (scale, offset) pairs of the workgroup tile, row0: row of oc0 inside that tile.
-template <typename T, int V>
-__device__ __forceinline__ void store_tile_staged(const float16v &acc, float *stage, int lane,
-                                                  int oc0, int p0, const TailArgs &t,
-                                                  const float *ss, int row0)
+// acc: one 32x32 accumulator tile in the D[pixel][channel] orientation described above.
+// oc0 / p0: output channel of column 0 / flattened pixel of row 0 (a multiple of 32).
+// ss: staged (scale, offset) pairs of the workgroup tile, row0: index of oc0 in that tile.
+// stage: kStageBytes of wave-private LDS (mode 8 only).
+template <typename T>
+__device__ __forceinline__ void store_tile(const float16v &acc, unsigned char *stage, int lane,
+                                           int oc0, int p0, const TailArgs &t, int vmode,
+                                           const float *ss, int row0)
 {
-    typedef typename VecIO<T, V>::vec vec;
+    typedef typename Group4<T>::vec gvec;
     const int lrow = lane & 31, lhalf = lane >> 5;
-#pragma unroll
-    for (int v = 0; v < 16; ++v)
-        stage[(8 * (v >> 2) + 4 * lhalf + (v & 3)) * kStageStride + lrow] = acc[v];
-    __builtin_amdgcn_wave_barrier();
-    constexpr int G = 32 / V;                      // lane groups per row
-    // image index of the tile's first pixel: uniform, so one scalar division; a tile of 32
-    // pixels crosses into later images by repeated subtraction (at most once for OH*OW >= 32)
+    const int oc = oc0 + lrow;
+    const float sc = ss[2 * (row0 + lrow)], sf = ss[2 * (row0 + lrow) + 1];
+    const float floor_v = t.relu ? 0.0f : -INFINITY;     // no ReLU = clamp at minus infinity
+    const T *res = static_cast<const T *>(t.residual);
+    T *y = static_cast<T *>(t.y);
+    // image index of the tile's first pixel: uniform, one scalar division; later pixels
+    // reach later images by repeated subtraction (at most once when OH*OW >= 32)
     const int p0u = __builtin_amdgcn_readfirstlane(p0);
     const int n0 = p0u / t.OHW, rem0 = p0u - n0 * t.OHW;
+
+    if (vmode == 1) {
 #pragma unroll
-    for (int it = 0; it < 32 * G / 64; ++it) {
-        const int task = it * 64 + lane;
-        const int row = task / G, g = task - row * G;
-        const int oc = oc0 + row, p = p0 + g * V;
-        if (oc < t.OC && p < t.npix) {
-            int n = n0, rem = rem0 + g * V;
-            while (rem >= t.OHW) { rem -= t.OHW; ++n; }
-            const size_t idx = (size_t)(n * t.OC + oc) * t.OHW + rem;
-            const float sc = ss[2 * (row0 + row)], sf = ss[2 * (row0 + row) + 1];
-            float f[V], r[V];
-#pragma unroll
-            for (int q = 0; q < V; ++q) {
-                f[q] = stage[row * kStageStride + g * V + q];
-                r[q] = 0.0f;
+        for (int v = 0; v < 16; ++v) {
+            const int pl = 8 * (v >> 2) + 4 * lhalf + (v & 3);
+            if (oc < t.OC && p0 + pl < t.npix) {
+                int n = n0, rem = rem0 + pl;
+                while (rem >= t.OHW) { rem -= t.OHW; ++n; }
+                const int idx = (n * t.OC + oc) * t.OHW + rem;
+                float o = fmaf(acc[v], sc, sf);
+                if (res) o += Elem<T>::load(res, idx);
+                Elem<T>::store(y, idx, fmaxf(o, floor_v));
             }
-            if (t.residual)
-                VecIO<T, V>::unpack(*reinterpret_cast<const vec *>(static_cast<const T *>(t.residual) + idx), r);
-            // no per-element selects: a missing residual adds zeros, a missing ReLU clamps
-            // at minus infinity
-            const float floor_v = t.relu ? 0.0f : -INFINITY;
+        }
+        return;
+    }
+
 #pragma unroll
-            for (int q = 0; q < V; ++q) f[q] = fmaxf(fmaf(f[q], sc, sf) + r[q], floor_v);
-            *reinterpret_cast<vec *>(static_cast<T *>(t.y) + idx) = VecIO<T, V>::pack(f);
+    for (int gq = 0; gq < 4; ++gq) {
+        const int pl = 8 * gq + 4 * lhalf;
+        const bool ok = oc < t.OC && p0 + pl < t.npix;      // npix % 4 == 0: whole group or none
+        int n = n0, rem = rem0 + pl;
+        while (rem >= t.OHW) { rem -= t.OHW; ++n; }
+        const int idx = ok ? (n * t.OC + oc) * t.OHW + rem : 0;
+        float f[4], r[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (res && ok) Group4<T>::unpack(*reinterpret_cast<const gvec *>(res + idx), r);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) f[q] = fmaxf(fmaf(acc[4 * gq + q], sc, sf) + r[q], floor_v);
+        const gvec packed = Group4<T>::pack(f);
+        if constexpr (sizeof(T) == 2) {
+            if (vmode == 8) {
+                *reinterpret_cast<gvec *>(stage + lrow * kStageRow + pl * 2) = packed;
+                continue;
+            }
+        }
+        if (ok) *reinterpret_cast<gvec *>(y + idx) = packed;
+    }
+
+    if constexpr (sizeof(T) == 2) {
+        if (vmode == 8) {
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int it = 0; it < 2; ++it) {
+                const int task = it * 64 + lane;
+                const int row = task >> 2, g = task & 3;
+                const int c = oc0 + row, p = p0 + 8 * g;
+                if (c < t.OC && p < t.npix) {
+                    int n = n0, rem = rem0 + 8 * g;
+                    while (rem >= t.OHW) { rem -= t.OHW; ++n; }
+                    const int idx = (n * t.OC + c) * t.OHW + rem;
+                    *reinterpret_cast<uint4v *>(y + idx) =
+                        *reinterpret_cast<const uint4v *>(stage + row * kStageRow + g * 16);
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
         }
     }
-    __builtin_amdgcn_wave_barrier();
 }
 
-// Direct (unstaged) stores of one accumulator tile: any OH*OW, any alignment.
-template <typename T>
-__device__ __forceinline__ void store_tile_direct(const float16v &acc, int lane, int oc0, int p0,
-                                                  const TailArgs &t)
-{
-    const int lrow = lane & 31, lhalf = lane >> 5;
-    const int p = p0 + lrow;
-    if (p >= t.npix) return;
-    const int n = p / t.OHW, rem = p - n * t.OHW;
-    const int obase = n * t.OC * t.OHW + rem;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        const int oc = oc0 + 8 * (v >> 2) + 4 * lhalf + (v & 3);
-        if (oc >= t.OC) continue;
-        fused_tail_store<T>(acc[v], t.scale[oc], t.shift[oc], t.bias ? t.bias[oc] : 0.0f,
-                            static_cast<const T *>(t.residual), static_cast<T *>(t.y),
-                            obase + oc * t.OHW, t.relu != 0);
-    }
-}
-
-// vmode: pixels per vector store (8, 4) or 1 for direct stores; chosen on the host.
-template <typename T>
-__device__ __forceinline__ void store_tile(const float16v &acc, float *stage, int lane, int oc0,
-                                           int p0, const TailArgs &t, int vmode, const float *ss,
-                                           int row0)
-{
-    if constexpr (sizeof(T) == 2) {
-        if (vmode == 8) return store_tile_staged<bf16_t, 8>(acc, stage, lane, oc0, p0, t, ss, row0);
-        if (vmode == 4) return store_tile_staged<bf16_t, 4>(acc, stage, lane, oc0, p0, t, ss, row0);
-    } else {
-        if (vmode == 4) return store_tile_staged<float, 4>(acc, stage, lane, oc0, p0, t, ss, row0);
-    }
-    store_tile_direct<T>(acc, lane, oc0, p0, t);
-}
-
-// All MI x NJ accumulator tiles of a wave, one after the other through ONE copy of the
-// store code: the loop is kept rolled and the tile is picked by uniform selects, because
-// inlining the epilogue per tile multiplies the code size and the kernels' hot loops then
-// no longer fit the instruction cache.
+// All MI x NJ accumulator tiles of a wave (acc[i][j]: channel block i, pixel block j).
 template <typename T, int MI, int NJ>
-__device__ __forceinline__ void store_acc_tiles(const float16v (&acc)[MI][NJ], float *stage,
+__device__ __forceinline__ void store_acc_tiles(const float16v (&acc)[MI][NJ], unsigned char *stage,
                                                 int lane, int oc_base, int p_base,
                                                 const TailArgs &t, int vmode, const float *ss,
                                                 int row_base)
 {
-#pragma unroll 1
-    for (int k = 0; k < MI * NJ; ++k) {
-        float16v cur = acc[0][0];
 #pragma unroll
-        for (int i = 0; i < MI; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
-            for (int j = 0; j < NJ; ++j)
-                if (i * NJ + j == k) cur = acc[i][j];
-        const int i = k / NJ, j = k - i * NJ;
-        store_tile<T>(cur, stage, lane, oc_base + i * 32, p_base + j * 32, t, vmode, ss,
-                      row_base + i * 32);
-    }
+        for (int j = 0; j < NJ; ++j)
+            store_tile<T>(acc[i][j], stage, lane, oc_base + i * 32, p_base + j * 32, t, vmode, ss,
+                          row_base + i * 32);
 }
 
-// Host side: widest staged store the problem allows.
+// Host side: the store mode the problem allows (see store_tile).
 inline int pick_store_vmode(int dtype, int OHW, const void *y, const void *residual)
 {
     const bool aligned = reinterpret_cast<uintptr_t>(y) % 16 == 0 &&
