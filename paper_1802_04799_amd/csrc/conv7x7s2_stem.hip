@@ -104,14 +104,18 @@ __global__ __launch_bounds__(256, 2) void conv7x7s2_stem_kernel(const StemArgs a
     const TailArgs tail{a.scale, a.shift, a.bias, a.residual, a.y, a.OC, OHW, a.npix, a.relu};
 
     uint4v lreg[LT];
+    // index arithmetic through the float reciprocal (exact below 2^22, checked on the host)
+    const float inv_ohw = 1.0f / (float)OHW, inv_ow = 1.0f / (float)a.OW, inv_vh = 1.0f / (float)VH;
     auto first_vrow = [&](int tile) {
-        const int p0 = tile * kNT;
-        const int n = p0 / OHW, oh = (p0 - n * OHW) / a.OW;
+        int rem, ow;
+        const int n = fast_div(tile * kNT, OHW, inv_ohw, &rem);
+        const int oh = fast_div(rem, a.OW, inv_ow, &ow);
         return n * VH + oh * 2;
     };
     auto load_tile = [&](int tile) {
         const int vr_lo = first_vrow(tile);
-        const int n_lo = vr_lo / VH, vi_lo = vr_lo - n_lo * VH;
+        int vi_lo;
+        const int n_lo = fast_div(vr_lo, VH, inv_vh, &vi_lo);
 #pragma unroll
         for (int j = 0; j < LT; ++j) {
             int vi = vi_lo + rslot[j], n = n_lo;
@@ -152,8 +156,9 @@ __global__ __launch_bounds__(256, 2) void conv7x7s2_stem_kernel(const StemArgs a
             const int p = p0 + wave * 64 + j * 32 + lrow;
             pb[j] = 0;
             if (p < a.npix) {
-                const int n = p / OHW, rem = p - n * OHW;
-                const int oh = rem / a.OW, ow = rem - oh * a.OW;
+                int rem, ow;
+                const int n = fast_div(p, OHW, inv_ohw, &rem);
+                const int oh = fast_div(rem, a.OW, inv_ow, &ow);
                 pb[j] = (n * VH + oh * 2 - vr_lo) * pitch + ow * 4;
             }
         }
@@ -237,6 +242,7 @@ bool plan_conv7x7s2_stem(const ConvProblem &p, StemPlan *plan)
         p.pw != 3)
         return false;
     if (p.IC > 4 || p.W % 8 != 0) return false;
+    if (p.npix >= (1 << 22) || (long)p.N * (p.H + 6) >= (1 << 22)) return false;   // fast_div range
     if ((size_t)p.N * p.IC * p.H * p.W * 2 > (size_t)kOutOfRange) return false;
     const int rows = max_stem_rows(p);
     if (rows > p.H + 6) return false;                   // a tile may wrap into the next image once

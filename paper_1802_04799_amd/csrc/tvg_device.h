@@ -166,6 +166,38 @@ __device__ __forceinline__ void store_tile(const float16v &acc, unsigned char *s
     const int p0u = __builtin_amdgcn_readfirstlane(p0);
     const int n0 = p0u / t.OHW, rem0 = p0u - n0 * t.OHW;
 
+    // Fast path (uniform test): the tile's 32 pixels lie in one image and neither the pixel
+    // nor the channel range is ragged, so every index is base + constant and nothing is
+    // masked.  This is the case for all but the boundary tiles.
+    if (vmode != 1 && rem0 + 32 <= t.OHW && p0u + 32 <= t.npix &&
+        __builtin_amdgcn_readfirstlane(oc0) + 32 <= t.OC) {
+        const int base = (n0 * t.OC + oc) * t.OHW + rem0 + 4 * lhalf;     // lane's group 0
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+            float f[4], r[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (res) Group4<T>::unpack(*reinterpret_cast<const gvec *>(res + base + 8 * gq), r);
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                f[q] = fmaxf(fmaf(acc[4 * gq + q], sc, sf) + r[q], floor_v);
+            const gvec packed = Group4<T>::pack(f);
+            if (sizeof(T) == 2 && vmode == 8)
+                *reinterpret_cast<gvec *>(stage + lrow * kStageRow + (8 * gq + 4 * lhalf) * 2) = packed;
+            else
+                *reinterpret_cast<gvec *>(y + base + 8 * gq) = packed;
+        }
+        if (sizeof(T) == 2 && vmode == 8) {
+            __builtin_amdgcn_wave_barrier();
+            const int row = lane >> 2, g = lane & 3;
+            const int b2 = (n0 * t.OC + oc0 + row) * t.OHW + rem0 + 8 * g;
+#pragma unroll
+            for (int it = 0; it < 2; ++it)
+                *reinterpret_cast<uint4v *>(y + b2 + it * 16 * t.OHW) =
+                    *reinterpret_cast<const uint4v *>(stage + (row + 16 * it) * kStageRow + g * 16);
+            __builtin_amdgcn_wave_barrier();
+        }
+        return;
+    }
+
     if (vmode == 1) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
