@@ -59,8 +59,11 @@ __device__ __forceinline__ int xcd_remap(int bid, int nb)
 
 __device__ __forceinline__ uint32_t half_of(uint32_t d, int hi) { return hi ? d >> 16 : d & 0xFFFFu; }
 
-// MT x NT output tile per workgroup of 256 threads; PT = patch load tasks per thread.
-template <int MT, int NT, int STRIDE, int PT>
+// MT x NT output tile per workgroup of 256 threads; PT = patch load tasks per thread; PX =
+// horizontally adjacent pixels fetched per load (2 or 4 need W to be a multiple: 32- or
+// 64-bit loads, a half or a quarter of the vector memory instructions, whose issue rate is
+// what limits the staging).
+template <int MT, int NT, int STRIDE, int PT, int PX>
 __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a)
 {
     constexpr int WTM = MT / 2, WTN = NT / 2;
@@ -99,17 +102,14 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
     const int npos = nrows * PW;
 
     float *ss_lds = reinterpret_cast<float *>(smem + a.ss_offset);
-    stage_scale_shift(ss_lds, m0, MT, a.scale, a.shift, a.bias, a.OC, tid, 256);
-
-    // ---- zero the patch once: padding rows and columns are never written again ------------
-    for (int i = tid; i < npos * (kPosBytes / 16); i += 256)
-        reinterpret_cast<uint4v *>(Ps)[i] = uint4v{0u, 0u, 0u, 0u};
 
     // ---- per-thread patch load tasks: (virtual row, iw, channel octet), fixed for all chunks
     uint32_t goff[PT];      // byte offset of the task's first channel within a chunk of x
     int loff[PT];           // byte offset of its 16-byte slot in the patch, -1 = nothing to do
     {
-        const int per_octet = nrows * W;
+        const int WPX = W / PX;
+        const float inv_wpx = 1.0f / (float)WPX;
+        const int per_octet = nrows * WPX;
 #pragma unroll
         for (int j = 0; j < PT; ++j) {
             const int t = tid + j * 256;
@@ -119,7 +119,8 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
                 const int octet = t >= per_octet;
                 const int rem = t - octet * per_octet;
                 int iw, vi;
-                const int vrow = fast_div(rem, W, inv_w, &iw);
+                const int vrow = fast_div(rem, WPX, inv_wpx, &iw);
+                iw *= PX;
                 const int n = fast_div(vr_lo + vrow, VH, inv_vh, &vi);
                 const int ih = vi - 1;
                 if (ih >= 0 && ih < H && n < a.N) {
@@ -153,7 +154,8 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
 
     // Loaded values stay unpacked until store_chunk so that nothing waits on the loads
     // before the MFMA phase of the current chunk.
-    uint32_t praw[PT][8];
+    constexpr int W32 = PX == 4 ? 2 : 1;       // registers per load
+    uint32_t praw[PT][8][W32];
     uint4v wreg[9];
 
     // Buffer loads: a uniform descriptor + per-lane 32-bit byte offset + scalar offset, so
@@ -169,7 +171,16 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
             const int soff = (c * kChunk + q) * HW * 2;
 #pragma unroll
             for (int j = 0; j < PT; ++j)
-                praw[j][q] = __builtin_amdgcn_raw_buffer_load_b16(xrsrc, goff[j], soff, 0);
+                if constexpr (PX == 4) {
+                    const uint2v t2 = __builtin_bit_cast(
+                        uint2v, __builtin_amdgcn_raw_buffer_load_b64(xrsrc, goff[j], soff, 0));
+                    praw[j][q][0] = t2[0];
+                    praw[j][q][1] = t2[1];
+                } else if constexpr (PX == 2) {
+                    praw[j][q][0] = __builtin_amdgcn_raw_buffer_load_b32(xrsrc, goff[j], soff, 0);
+                } else {
+                    praw[j][q][0] = __builtin_amdgcn_raw_buffer_load_b16(xrsrc, goff[j], soff, 0);
+                }
         }
         if (wtask) {
             const int soff = c * kChunk * 9 * 2;
@@ -183,10 +194,19 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
     auto store_chunk = [&]() {
 #pragma unroll
         for (int j = 0; j < PT; ++j)
-            if (loff[j] >= 0)
-                *reinterpret_cast<uint4v *>(Ps + loff[j]) =
-                    uint4v{praw[j][0] | (praw[j][1] << 16), praw[j][2] | (praw[j][3] << 16),
-                           praw[j][4] | (praw[j][5] << 16), praw[j][6] | (praw[j][7] << 16)};
+            if (loff[j] >= 0) {
+                // pixel k of the task sits in half (k & 1) of register k >> 1 of each channel
+#pragma unroll
+                for (int k = 0; k < PX; ++k) {
+                    uint32_t o[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        o[q] = half_of(praw[j][2 * q][k >> 1], k & 1) |
+                               (half_of(praw[j][2 * q + 1][k >> 1], k & 1) << 16);
+                    *reinterpret_cast<uint4v *>(Ps + loff[j] + k * kPosBytes) =
+                        uint4v{o[0], o[1], o[2], o[3]};
+                }
+            }
         if (wtask) {
             // wreg holds 8 channels x 9 taps, tap fastest; emit one 8-channel vector per tap
             uint32_t d[36];
@@ -217,13 +237,21 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
     const int nchunks = a.IC / kChunk;
+    // The first chunk's loads go out before the rest of the set-up, which then runs under
+    // their latency: zero the patch once (padding rows and columns are never written
+    // again) and stage the tile's (scale, offset) pairs.
     load_chunk(0);
+    for (int i = tid; i < npos * (kPosBytes / 16); i += 256)
+        reinterpret_cast<uint4v *>(Ps)[i] = uint4v{0u, 0u, 0u, 0u};
+    stage_scale_shift(ss_lds, m0, MT, a.scale, a.shift, a.bias, a.OC, tid, 256);
     __syncthreads();          // patch zeroing complete before the first real data lands
     store_chunk();
     __syncthreads();
 
     const unsigned char *Abase = As + (wm * WTM + lrow) * kPosBytes + lhalf * 16;
     for (int c = 0; c < nchunks; ++c) {
+        // All of the next chunk's loads are issued before this chunk's MFMAs: measured, issuing
+        // them in slices between the taps leaves them too little time to arrive.
         if (c + 1 < nchunks) load_chunk(c + 1);
 
         // operands of tap t+1 are requested from LDS before the MFMAs of tap t issue
@@ -287,10 +315,10 @@ int max_patch_rows(const ConvProblem &p, int nt)
     return best;
 }
 
-template <int MT, int NT, int STRIDE, int PT>
+template <int MT, int NT, int STRIDE, int PT, int PX>
 tvg_status launch_instance(const PatchArgs &a, int ntiles, size_t lds, hipStream_t stream)
 {
-    auto kernel = conv3x3_patch_kernel<MT, NT, STRIDE, PT>;
+    auto kernel = conv3x3_patch_kernel<MT, NT, STRIDE, PT, PX>;
     static bool configured = false;      // opt in to > 64 KB of dynamic LDS once per instance
     if (!configured) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
@@ -303,26 +331,31 @@ tvg_status launch_instance(const PatchArgs &a, int ntiles, size_t lds, hipStream
 }
 
 template <int MT, int NT, int STRIDE>
-tvg_status launch_pt(const PatchArgs &a, int ntiles, size_t lds, int pt, hipStream_t stream)
+tvg_status launch_pt(const PatchArgs &a, int ntiles, size_t lds, int pt, int px, hipStream_t stream)
 {
-    if (pt <= 2) return launch_instance<MT, NT, STRIDE, 2>(a, ntiles, lds, stream);
-    if (pt <= 4) return launch_instance<MT, NT, STRIDE, 4>(a, ntiles, lds, stream);
-    return launch_instance<MT, NT, STRIDE, 8>(a, ntiles, lds, stream);
+    if (px == 2) {
+        if (pt <= 2) return launch_instance<MT, NT, STRIDE, 2, 2>(a, ntiles, lds, stream);
+        return launch_instance<MT, NT, STRIDE, 4, 2>(a, ntiles, lds, stream);
+    }
+    if (pt <= 2) return launch_instance<MT, NT, STRIDE, 2, 1>(a, ntiles, lds, stream);
+    if (pt <= 4) return launch_instance<MT, NT, STRIDE, 4, 1>(a, ntiles, lds, stream);
+    return launch_instance<MT, NT, STRIDE, 8, 1>(a, ntiles, lds, stream);
 }
 
 template <int MT, int NT>
-tvg_status launch_stride(const PatchArgs &a, int stride, int ntiles, size_t lds, int pt,
+tvg_status launch_stride(const PatchArgs &a, int stride, int ntiles, size_t lds, int pt, int px,
                          hipStream_t stream)
 {
-    return stride == 1 ? launch_pt<MT, NT, 1>(a, ntiles, lds, pt, stream)
-                       : launch_pt<MT, NT, 2>(a, ntiles, lds, pt, stream);
+    return stride == 1 ? launch_pt<MT, NT, 1>(a, ntiles, lds, pt, px, stream)
+                       : launch_pt<MT, NT, 2>(a, ntiles, lds, pt, px, stream);
 }
 
 }  // namespace
 
 bool conv3x3_patch_pointers_ok(const ConvPointers &ptr)
 {
-    return reinterpret_cast<uintptr_t>(ptr.w) % 16 == 0;   // weights are read as 16-byte vectors
+    // weights are read as 16-byte vectors, input pixels as up to 64-bit groups
+    return reinterpret_cast<uintptr_t>(ptr.w) % 16 == 0 && reinterpret_cast<uintptr_t>(ptr.x) % 8 == 0;
 }
 
 bool plan_conv3x3_patch(const ConvProblem &p, Patch3x3Plan *plan)
@@ -346,14 +379,19 @@ bool plan_conv3x3_patch(const ConvProblem &p, Patch3x3Plan *plan)
         if (force_mt && mt != force_mt) continue;
         if (force_nt && nt != force_nt) continue;
         const int rows = max_patch_rows(p, nt);
-        const int pt = (2 * rows * p.W + 255) / 256;
+        // two pixels per load when the rows are even (32-bit aligned pairs) and that keeps the
+        // task count within the instances built for it
+        // (four pixels per load were measured too: no gain over two, so no instance is built)
+        int px = p.W % 2 == 0 ? 2 : 1;
+        int pt = (2 * rows * (p.W / px) + 255) / 256;
+        if (px == 2 && pt > 4) { px = 1; pt = (2 * rows * p.W + 255) / 256; }
         const size_t lds = (size_t)9 * mt * kPosBytes + (size_t)rows * (p.W + 2) * kPosBytes +
                            (size_t)mt * 8;      // operands + (scale, offset) pairs
         if (pt > 8 || lds > 80 * 1024) continue;
         if (mt == 128 && pt > 4 && !force_mt) continue;
         const long tiles = (long)((p.OC + mt - 1) / mt) * ((p.npix + nt - 1) / nt);
         const bool fills = 2 * tiles >= 3 * kComputeUnits;
-        const Patch3x3Plan cand{mt, nt, pt, rows, lds, tiles};
+        const Patch3x3Plan cand{mt, nt, pt, px, rows, lds, tiles};
         if (!found || (!best_fills && (fills || tiles > best.tiles))) {
             best = cand;
             best_fills = fills;
@@ -383,12 +421,12 @@ tvg_status launch_conv3x3_patch(const ConvProblem &p, const Patch3x3Plan &plan,
     a.ntiles = ntiles;
     a.m_major = (size_t)p.OC * p.IC * 9 > (size_t)p.N * p.IC * p.H * p.W;
     if (plan.mt == 128 && plan.nt == 128)
-        return launch_stride<128, 128>(a, p.sh, ntiles, plan.lds_bytes, plan.pt, stream);
+        return launch_stride<128, 128>(a, p.sh, ntiles, plan.lds_bytes, plan.pt, plan.px, stream);
     if (plan.mt == 128)
-        return launch_stride<128, 64>(a, p.sh, ntiles, plan.lds_bytes, plan.pt, stream);
+        return launch_stride<128, 64>(a, p.sh, ntiles, plan.lds_bytes, plan.pt, plan.px, stream);
     if (plan.nt == 128)
-        return launch_stride<64, 128>(a, p.sh, ntiles, plan.lds_bytes, plan.pt, stream);
-    return launch_stride<64, 64>(a, p.sh, ntiles, plan.lds_bytes, plan.pt, stream);
+        return launch_stride<64, 128>(a, p.sh, ntiles, plan.lds_bytes, plan.pt, plan.px, stream);
+    return launch_stride<64, 64>(a, p.sh, ntiles, plan.lds_bytes, plan.pt, plan.px, stream);
 }
 
 }  // namespace tvg

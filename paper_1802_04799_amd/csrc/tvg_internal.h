@@ -46,6 +46,7 @@ ConvPlan plan_conv(const ConvProblem &p, bool allow_split = true);
 struct Patch3x3Plan {
     int mt, nt;         // output channels x pixels per workgroup
     int pt;             // patch load tasks per thread
+    int px;             // pixels per load (1, 2 or 4)
     int rows;           // virtual input rows staged per tile (maximum over tiles)
     size_t lds_bytes;
     long tiles;
