@@ -66,7 +66,11 @@ __device__ __forceinline__ uint32_t half_of(uint32_t d, int hi) { return hi ? d 
 template <int MT, int NT, int STRIDE, int PT, int PX>
 __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a)
 {
-    constexpr int WTM = MT / 2, WTN = NT / 2;
+    // four waves as 2 x 2, or 1 x 4 for the wide 64 x 256 tile (the weights of a chunk weigh
+    // about six times the input patch per tile side, so a wide pixel tile moves the fewest
+    // operand bytes per MFMA through the vector memory path)
+    constexpr int WM = NT == 256 ? 1 : 2, WN = 4 / WM;
+    constexpr int WTM = MT / WM, WTN = NT / WN;
     constexpr int MI = WTM / 32, NJ = WTN / 32;
     constexpr int ABYTES = 9 * MT * kPosBytes;
 
@@ -75,7 +79,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
     unsigned char *Ps = smem + ABYTES;     // [virtual row][W + 2][48 B]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave & 1, wn = wave >> 1;
+    const int wm = wave % WM, wn = wave / WM;
     const int lrow = lane & 31, lhalf = lane >> 5;
 
     const int tile = xcd_remap(blockIdx.x, gridDim.x);
@@ -91,7 +95,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
     // Index arithmetic below divides by OH*OW, OW, W and H+2 only; the host admits this
     // kernel when every dividend stays below 2^22, where fast_div is exact.
     const float inv_ohw = 1.0f / (float)OHW, inv_ow = 1.0f / (float)a.OW;
-    const float inv_w = 1.0f / (float)W, inv_vh = 1.0f / (float)VH;
+    const float inv_vh = 1.0f / (float)VH;
 
     // ---- tile geometry (uniform) ---------------------------------------------------------
     const int p_last = min(n0 + NT, a.npix) - 1;
@@ -370,7 +374,7 @@ bool plan_conv3x3_patch(const ConvProblem &p, Patch3x3Plan *plan)
     // least 1.5 workgroups per CU, wider in pixels on a tie; if none does, the tile shape with
     // the most workgroups.  A 128-channel tile with more than 4 patch tasks per thread (wide
     // stride-2 patches) runs out of registers and is skipped.
-    const int cands[4][2] = {{128, 128}, {64, 128}, {128, 64}, {64, 64}};
+    const int cands[5][2] = {{64, 256}, {128, 128}, {64, 128}, {128, 64}, {64, 64}};
     Patch3x3Plan best{};
     bool found = false, best_fills = false;
     for (const auto &c : cands) {
@@ -420,6 +424,8 @@ tvg_status launch_conv3x3_patch(const ConvProblem &p, const Patch3x3Plan &plan,
     const int ntiles = (p.npix + plan.nt - 1) / plan.nt;
     a.ntiles = ntiles;
     a.m_major = (size_t)p.OC * p.IC * 9 > (size_t)p.N * p.IC * p.H * p.W;
+    if (plan.nt == 256)
+        return launch_stride<64, 256>(a, p.sh, ntiles, plan.lds_bytes, plan.pt, plan.px, stream);
     if (plan.mt == 128 && plan.nt == 128)
         return launch_stride<128, 128>(a, p.sh, ntiles, plan.lds_bytes, plan.pt, plan.px, stream);
     if (plan.mt == 128)

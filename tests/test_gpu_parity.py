@@ -133,7 +133,7 @@ PATCH_RAGGED = [
 ]
 
 
-@pytest.mark.parametrize("tile", ["", "128,128", "128,64", "64,128", "64,64"])
+@pytest.mark.parametrize("tile", ["", "64,256", "128,128", "128,64", "64,128", "64,64"])
 @pytest.mark.parametrize("cfg", PATCH_RAGGED)
 def test_bf16_3x3_patch_kernel_ragged_shapes_all_tiles(tvg, monkeypatch, cfg, tile):
     """The LDS-patch 3x3 kernel under every workgroup tile shape it is built with (the
@@ -157,7 +157,7 @@ PATCH_WIDE = [
 ]
 
 
-@pytest.mark.parametrize("tile", ["", "128,128", "64,128", "64,64"])
+@pytest.mark.parametrize("tile", ["", "64,256", "128,128", "64,128", "64,64"])
 @pytest.mark.parametrize("cfg", PATCH_WIDE)
 def test_bf16_3x3_patch_kernel_many_chunks(tvg, monkeypatch, cfg, tile):
     """The 3x3 patch kernel with several channel chunks per tile: tiles that straddle images,
