@@ -133,6 +133,171 @@ __global__ __launch_bounds__(256) void dwconv3x3_kernel(const DwArgs a)
     }
 }
 
+// Register-blocked variant for fp32 planes whose rows are multiples of four: no LDS.
+// A lane computes a block of 4 output rows x 4 output columns of one plane; every input
+// row of the block is read as 16-byte vectors plus the halo scalars, re-used in registers
+// by the (up to three) output rows that need it, and each output row leaves as one 16-byte
+// store.  Neighbouring lanes read neighbouring vectors of the same row; the overlap
+// between blocks (halo rows and columns) is served by the caches.
+struct DwDirectArgs {
+    const float *x, *w;
+    const float *scale, *shift, *bias;
+    const float *residual;
+    float *y;
+    int C, H, W, OH, OW;
+    int CB;            // 4-column blocks per output row
+    int tpp;           // lane tasks per plane: row blocks x CB
+    int total;         // tasks in total
+    float inv_cb;
+    int relu;
+};
+
+constexpr int kRB = 4;        // output rows per lane
+
+template <int STRIDE>
+__global__ __launch_bounds__(256) void dwconv3x3_direct_kernel(const DwDirectArgs a)
+{
+    const int g = blockIdx.x * 256 + threadIdx.x;
+    if (g >= a.total) return;
+    const int plane = g / a.tpp;
+    int cb;
+    const int rb = fast_div(g - plane * a.tpp, a.CB, a.inv_cb, &cb);
+    const int c = plane % a.C;
+    const int oh0 = rb * kRB, ow0 = cb * 4;
+    const int H = a.H, W = a.W;
+    const float *__restrict__ xp = a.x + (size_t)plane * H * W;
+
+    float wt[9];
+#pragma unroll
+    for (int e = 0; e < 9; ++e) wt[e] = a.w[c * 9 + e];
+    const float sc = a.scale[c];
+    const float sf = a.bias ? fmaf(a.bias[c], sc, a.shift[c]) : a.shift[c];
+
+    constexpr int IR = (kRB - 1) * STRIDE + 3;        // input rows of the block
+    constexpr int NV = 3 * STRIDE + 3;                // input columns of the block
+    float acc[kRB][4];
+#pragma unroll
+    for (int o = 0; o < kRB; ++o)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc[o][q] = 0.0f;
+
+    const int iw0 = ow0 * STRIDE;                     // first in-image column of the vectors
+#pragma unroll
+    for (int rr = 0; rr < IR; ++rr) {
+        const int ih = oh0 * STRIDE - 1 + rr;
+        if (ih < 0 || ih >= H) continue;              // a padding row contributes nothing
+        const float *row = xp + ih * W + iw0;
+        float v[NV];                                  // columns iw0 - 1 .. iw0 + NV - 2
+        v[0] = iw0 > 0 ? row[-1] : 0.0f;
+        const float4v m0 = *reinterpret_cast<const float4v *>(row);
+        v[1] = m0[0]; v[2] = m0[1]; v[3] = m0[2]; v[4] = m0[3];
+        if (STRIDE == 1) {
+            v[5] = iw0 + 4 < W ? row[4] : 0.0f;
+        } else {
+            const float4v m1 = *reinterpret_cast<const float4v *>(row + 4);
+            v[5] = m1[0]; v[6] = m1[1]; v[7] = m1[2]; v[8] = m1[3];
+        }
+#pragma unroll
+        for (int o = 0; o < kRB; ++o) {
+            const int r = rr - o * STRIDE;
+            if (r < 0 || r > 2) continue;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                acc[o][q] += v[q * STRIDE] * wt[r * 3] + v[q * STRIDE + 1] * wt[r * 3 + 1] +
+                             v[q * STRIDE + 2] * wt[r * 3 + 2];
+        }
+    }
+
+    const float floor_v = a.relu ? 0.0f : -INFINITY;
+#pragma unroll
+    for (int o = 0; o < kRB; ++o) {
+        const int oh = oh0 + o;
+        if (oh >= a.OH) continue;
+        const size_t idx = ((size_t)plane * a.OH + oh) * a.OW + ow0;
+        float4v r = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (a.residual) r = *reinterpret_cast<const float4v *>(a.residual + idx);
+        float4v out;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) out[q] = fmaxf(fmaf(acc[o][q], sc, sf) + r[q], floor_v);
+        *reinterpret_cast<float4v *>(a.y + idx) = out;
+    }
+}
+
+// Variant for small fp32 planes (at most 256 outputs per plane: 14x14 and 7x7 maps).  A
+// workgroup copies PG whole planes, which are one contiguous run of memory, into LDS with
+// 16-byte loads and no per-element index arithmetic; every lane then keeps ONE output
+// position (oh, ow) for the whole kernel, with its nine tap offsets and in-image mask
+// computed once, and walks over the planes of the group.
+struct DwSmallArgs {
+    const float *x, *w;
+    const float *scale, *shift, *bias;
+    const float *residual;
+    float *y;
+    int planes, C, H, W, OH, OW, PG, relu;
+};
+
+template <int STRIDE>
+__global__ __launch_bounds__(256) void dwconv3x3_smallplane_kernel(const DwSmallArgs a)
+{
+    extern __shared__ float smem[];
+    const int HW = a.H * a.W, OHW = a.OH * a.OW;
+    float *tile = smem;                   // [PG][H*W]
+    float *prm = smem + a.PG * HW;        // [PG][12]: 9 taps, scale, offset, unused
+    const int tid = threadIdx.x;
+    const int p0 = blockIdx.x * a.PG;
+    const int np = min(a.PG, a.planes - p0);
+
+    // ---- copy the planes: contiguous, 16-byte aligned start (PG is a multiple of 4) --------
+    const float *src = a.x + (size_t)p0 * HW;
+    const int nflt = np * HW, nvec = nflt >> 2;
+    for (int i = tid; i < nvec; i += 256)
+        reinterpret_cast<float4v *>(tile)[i] = reinterpret_cast<const float4v *>(src)[i];
+    for (int i = (nvec << 2) + tid; i < nflt; i += 256) tile[i] = src[i];
+    for (int l = tid; l < np * 12; l += 256) {
+        const int p = l / 12, e = l - p * 12;
+        const int c = (p0 + p) % a.C;
+        float v = 0.0f;
+        if (e < 9) v = a.w[c * 9 + e];
+        else if (e == 9) v = a.scale[c];
+        else if (e == 10) v = a.bias ? fmaf(a.bias[c], a.scale[c], a.shift[c]) : a.shift[c];
+        prm[l] = v;
+    }
+
+    // ---- this lane's output position and taps, fixed for the kernel -------------------------
+    const int G = 256 / OHW;              // planes handled per pass of the workgroup
+    const int sub = tid / OHW, r0 = tid - sub * OHW;
+    const int oh = r0 / a.OW, ow = r0 - oh * a.OW;
+    int toff[9];
+    uint32_t mask = 0;
+#pragma unroll
+    for (int r = 0; r < 3; ++r)
+#pragma unroll
+        for (int s = 0; s < 3; ++s) {
+            const int ih = oh * STRIDE - 1 + r, iw = ow * STRIDE - 1 + s;
+            const bool ok = ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
+            toff[r * 3 + s] = ok ? ih * a.W + iw : 0;
+            mask |= (uint32_t)ok << (r * 3 + s);
+        }
+    __syncthreads();
+    if (sub >= G) return;
+
+    const float floor_v = a.relu ? 0.0f : -INFINITY;
+    for (int p = sub; p < np; p += G) {
+        const float *pl = tile + p * HW;
+        const float *pp = prm + p * 12;
+        float acc = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 9; ++e) {
+            const float v = pl[toff[e]];
+            acc += ((mask >> e) & 1u) ? v * pp[e] : 0.0f;
+        }
+        const size_t idx = (size_t)(p0 + p) * OHW + r0;
+        float o = fmaf(acc, pp[9], pp[10]);
+        if (a.residual) o += a.residual[idx];
+        a.y[idx] = fmaxf(o, floor_v);
+    }
+}
+
 int ceil_log2(int v)
 {
     int l = 0;
@@ -144,6 +309,59 @@ int ceil_log2(int v)
 
 tvg_status launch_dwconv3x3(const ConvProblem &p, const ConvPointers &ptr, hipStream_t stream)
 {
+    const int stride0 = p.sh;
+    const bool ptr16 = reinterpret_cast<uintptr_t>(ptr.x) % 16 == 0 &&
+                       reinterpret_cast<uintptr_t>(ptr.y) % 16 == 0 &&
+                       reinterpret_cast<uintptr_t>(ptr.residual) % 16 == 0;
+    const long tasks = (long)p.N * p.IC * ((p.OH + kRB - 1) / kRB) * (p.OW / 4);
+    if (p.dtype == TVG_F32 && ptr16 && p.W % 4 == 0 && p.OW % 4 == 0 && p.W >= 8 &&
+        tasks < (1L << 31) && (p.OH + kRB - 1) / kRB * (p.OW / 4) < (1 << 22)) {
+        DwDirectArgs d;
+        d.x = static_cast<const float *>(ptr.x); d.w = static_cast<const float *>(ptr.w);
+        d.scale = ptr.scale; d.shift = ptr.shift; d.bias = ptr.bias;
+        d.residual = static_cast<const float *>(ptr.residual); d.y = static_cast<float *>(ptr.y);
+        d.C = p.IC; d.H = p.H; d.W = p.W; d.OH = p.OH; d.OW = p.OW;
+        d.CB = p.OW / 4;
+        d.tpp = (p.OH + kRB - 1) / kRB * d.CB;
+        d.total = (int)tasks;
+        d.inv_cb = 1.0f / (float)d.CB;
+        d.relu = p.relu;
+        const unsigned blocks = (unsigned)((tasks + 255) / 256);
+        if (stride0 == 1)
+            hipLaunchKernelGGL((dwconv3x3_direct_kernel<1>), dim3(blocks), dim3(256), 0, stream, d);
+        else
+            hipLaunchKernelGGL((dwconv3x3_direct_kernel<2>), dim3(blocks), dim3(256), 0, stream, d);
+        return hipGetLastError() == hipSuccess ? TVG_OK : TVG_ERR_LAUNCH;
+    }
+
+    if (p.dtype == TVG_F32 && p.OH * p.OW <= 256 && reinterpret_cast<uintptr_t>(ptr.x) % 16 == 0) {
+        DwSmallArgs d;
+        d.x = static_cast<const float *>(ptr.x); d.w = static_cast<const float *>(ptr.w);
+        d.scale = ptr.scale; d.shift = ptr.shift; d.bias = ptr.bias;
+        d.residual = static_cast<const float *>(ptr.residual); d.y = static_cast<float *>(ptr.y);
+        d.planes = p.N * p.IC; d.C = p.IC; d.H = p.H; d.W = p.W; d.OH = p.OH; d.OW = p.OW;
+        d.relu = p.relu;
+        // planes per workgroup: a multiple of 4, about 2048 outputs, at most 40 KB of LDS,
+        // and no larger than leaves about four workgroups per CU
+        const int hw = p.H * p.W, ohw = p.OH * p.OW;
+        int pg = 2048 / ohw;
+        const int cap_lds = (40 * 1024 / 4) / (hw + 12);
+        if (pg > cap_lds) pg = cap_lds;
+        const int cap_fill = d.planes / (4 * kComputeUnits);
+        if (cap_fill >= 4 && pg > cap_fill) pg = cap_fill;
+        pg = pg / 4 * 4;
+        if (pg >= 4) {
+            d.PG = pg;
+            const size_t lds = (size_t)pg * (hw + 12) * sizeof(float);
+            const unsigned blocks = (unsigned)((d.planes + pg - 1) / pg);
+            if (stride0 == 1)
+                hipLaunchKernelGGL((dwconv3x3_smallplane_kernel<1>), dim3(blocks), dim3(256), lds, stream, d);
+            else
+                hipLaunchKernelGGL((dwconv3x3_smallplane_kernel<2>), dim3(blocks), dim3(256), lds, stream, d);
+            return hipGetLastError() == hipSuccess ? TVG_OK : TVG_ERR_LAUNCH;
+        }
+    }
+
     DwArgs a;
     a.x = ptr.x; a.w = ptr.w; a.scale = ptr.scale; a.shift = ptr.shift; a.bias = ptr.bias;
     a.residual = ptr.residual; a.y = ptr.y;

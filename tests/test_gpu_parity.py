@@ -50,7 +50,12 @@ def test_config3_depthwise_fp32_batch1(tvg, i):
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("n,c,h,w,stride", [(3, 5, 9, 11, 1), (2, 7, 10, 13, 2), (1, 3, 1, 1, 1),
                                               (2, 70, 33, 65, 2), (1, 2, 130, 131, 1),
-                                              (4, 300, 7, 7, 1), (1, 1, 2, 3, 2)])
+                                              (4, 300, 7, 7, 1), (1, 1, 2, 3, 2),
+                                              # rows that are multiples of four (fp32: the
+                                              # register-blocked kernel), ragged row blocks
+                                              (2, 5, 12, 16, 1), (3, 7, 16, 24, 2), (1, 3, 8, 8, 1),
+                                              (2, 4, 21, 32, 2), (1, 2, 9, 12, 1), (1, 3, 7, 8, 2),
+                                              (2, 6, 30, 120, 1)])
 def test_depthwise_ragged_shapes_full_tail(tvg, dtype, n, c, h, w, stride):
     import torch
     sh = ti.ConvShape("dw", n, c, h, w, c, 3, 3, stride, 1, depthwise=True)
