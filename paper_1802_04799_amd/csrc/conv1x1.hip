@@ -49,7 +49,7 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const PwArgs a)
     constexpr int BT = NT * 4 / 256;          // (pixel, octet) slots per thread
     constexpr int AT = (MT * 4 + 255) / 256;  // weight vectors per thread
     constexpr int OPER = (MT + NT) * kRow;
-    constexpr int STAGE = 4 * kStageBytes;
+    constexpr int STAGE = 4 * MI * NJ * kStageBytes;    // the epilogue stages all of a wave's tiles
     __shared__ __attribute__((aligned(16))) unsigned char lds[OPER > STAGE ? OPER : STAGE];
     __shared__ float ss_lds[2 * MT];
     unsigned char *As = lds, *Bs = lds + MT * kRow;
@@ -191,9 +191,9 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const PwArgs a)
         }
     }
 
-    unsigned char *stage = lds + wave * kStageBytes;
+    unsigned char *stage = lds + wave * (MI * NJ * kStageBytes);
     const TailArgs tail{a.scale, a.shift, a.bias, a.residual, a.y, a.OC, OHW, a.npix, a.relu};
-    store_acc_tiles<bf16_t, MI, NJ>(acc, stage, lane, m0 + wm * WTM, n0 + wn * WTN, tail, a.vmode,
+    store_acc_tiles_batched<MI, NJ>(acc, stage, lane, m0 + wm * WTM, n0 + wn * WTN, tail, a.vmode,
                                     ss_lds, wm * WTM);
 }
 

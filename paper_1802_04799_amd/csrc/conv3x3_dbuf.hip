@@ -1,0 +1,433 @@
+// bf16 3x3 (pad 1, stride 1 or 2) fused conv2d, software-pipelined variant of the patch
+// kernel: the operand tiles of an input-channel chunk live in one of TWO LDS stages, so the
+// registers holding chunk c+1 are transposed and written to the idle stage BETWEEN the MFMAs
+// of chunk c, and one barrier per chunk is all the synchronisation left.  The global loads of
+// chunk c+2 are issued as soon as those registers are free.  (TVM paper Section 4.2:
+// cooperative fetch into the shared scope; Section 4.4: memory latency hidden behind compute -
+// here inside one workgroup instead of by switching between workgroups.)
+//
+// Tile: 64 output channels x NT pixels (NT = 256, 128 or 64), 256 threads.
+//
+// LDS layout of a stage.  An MFMA lane consumes 8 channels (16 bytes) of one pixel or one
+// filter row; the two channel octets of a chunk are kept in two separate PLANES, each a dense
+// array of 16-byte words indexed by position, so that 16 consecutive lanes (which read the same
+// octet of 16 consecutive positions) touch 256 consecutive bytes: conflict-free without
+// padding, and the byte offset of a tap is one constant for all lanes.
+//   A planes: [octet][tap][oc]      16 B each (+128 B between the planes: spreads the writes)
+//   P planes: [octet][virtual row][column]   16 B each
+// Virtual rows are those of the patch kernel: image n owns rows n*(H+2) .. n*(H+2)+H+1, first
+// and last being zero padding.  For stride 2 a row is stored even columns first, then odd
+// columns, so that the pixels of consecutive lanes (two columns apart) are again consecutive
+// 16-byte words.
+#include <stdio.h>
+#include <stdlib.h>
+
+#include <type_traits>
+
+#include "tvg_device.h"
+#include "tvg_internal.h"
+
+namespace tvg {
+
+namespace {
+
+struct DbufArgs {
+    const bf16_t *x, *w;
+    const float *scale, *shift, *bias;
+    const bf16_t *residual;
+    bf16_t *y;
+    int N, IC, H, W, OC, OH, OW, npix, relu, mtiles;
+    int vmode;        // pixels per vector store in the epilogue (8, 4 or 1)
+    uint32_t x_bytes, w_bytes;
+    int pplane;       // bytes of one channel-octet plane of the patch
+    int stage_bytes;  // weight planes + patch planes + dump area
+    int ss_offset;    // byte offset in LDS of the staged (scale, offset) pairs
+    int ntiles, m_major;
+    // reciprocals for fast_div (host-computed 1.0f / x): of the tile-order divisor, OH*OW, OW,
+    // H + 2 and W / PX
+    float inv_tdiv, inv_ohw, inv_ow, inv_vh, inv_wpx;
+};
+
+constexpr int kMT = 64;
+constexpr int kChunk = 16;                       // input channels per chunk = K of one MFMA
+constexpr int kAPlane = 9 * kMT * 16 + 128;      // bytes of one weight plane
+constexpr int kRsrcFlags = 0x00020000;           // raw buffer descriptor word 3 on gfx9-family targets
+
+__device__ __forceinline__ int xcd_remap(int bid, int nb)
+{
+    const int q = nb >> 3, rem = nb & 7;
+    const int xcd = bid & 7, local = bid >> 3;
+    return xcd < rem ? xcd * (q + 1) + local : rem * (q + 1) + (xcd - rem) * q + local;
+}
+
+// 16-bit half `ha` of a in the low half of the result, half `hb` of b in the high half.
+__device__ __forceinline__ uint32_t pack_halves(uint32_t a, int ha, uint32_t b, int hb)
+{
+    // v_perm_b32 selects bytes 0..3 from its second source and 4..7 from its first
+    const uint32_t sel = (ha ? 0x0302u : 0x0100u) | (hb ? 0x07060000u : 0x05040000u);
+    return __builtin_amdgcn_perm(b, a, sel);
+}
+
+// PT = patch load tasks per thread; PX = horizontally adjacent pixels per load (2 needs an
+// even W: 32-bit loads).
+template <int NT, int STRIDE, int PT, int PX>
+__global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
+{
+    constexpr int MT = kMT;
+    constexpr int WM = NT == 256 ? 1 : 2, WN = 4 / WM;
+    constexpr int WTM = MT / WM, WTN = NT / WN;
+    constexpr int MI = WTM / 32, NJ = WTN / 32;
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave % WM, wn = wave / WM;
+    const int lrow = lane & 31, lhalf = lane >> 5;
+
+    const int H = a.H, W = a.W, HW = H * W, OHW = a.OH * a.OW;
+    const int VH = H + 2;
+    // 16-byte words per patch row, and where the odd columns start (stride 2 only)
+    const int PWH = (W + 3) >> 1;
+    const int PWS = STRIDE == 2 ? 2 * PWH : W + 2;
+    const int stage_bytes = a.stage_bytes;
+
+    // All index arithmetic divides through host-computed float reciprocals; the host admits
+    // this kernel when every dividend stays below 2^22, where fast_div is exact.
+    int m0, n0;
+    {
+        const int tile = xcd_remap(blockIdx.x, gridDim.x);
+        int r;
+        const int q = fast_div(tile, a.m_major ? a.ntiles : a.mtiles, a.inv_tdiv, &r);
+        m0 = (a.m_major ? q : r) * MT;
+        n0 = (a.m_major ? r : q) * NT;
+    }
+
+    // ---- weight task: one output channel, four input channels, all nine taps ----------------
+    const int w_ocl = tid >> 2, w_quad = tid & 3;
+    // rows past OC read row 0: their products land in accumulators that are never stored
+    const uint32_t woff =
+        2u * (uint32_t)((((m0 + w_ocl) < a.OC ? m0 + w_ocl : 0) * a.IC + w_quad * 4) * 9);
+    const int wdst = (w_quad >> 1) * kAPlane + w_ocl * 16 + (w_quad & 1) * 8;
+
+    uint32_t goff[PT];      // byte offset of a patch task's first channel within a chunk of x
+    int loff[PT];           // byte offset of its first 16-byte word in a stage
+    // second pixel of a pair: the next word, or for stride 2 (first pixel in an odd padded
+    // column) the following even column
+    const int pair_step = STRIDE == 2 ? 16 - PWH * 16 : 16;
+    uint32_t praw[PT][8];
+    uint32_t wraw[18];
+
+    const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t *>(a.x), 0, a.x_bytes, kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t *>(a.w), 0, a.w_bytes, kRsrcFlags);
+
+    // The staging work of a chunk as a list of small items, so that it can be dealt out between
+    // the MFMAs of the previous chunk.  A register is reloaded (chunk c+2) right after the item
+    // that consumed it (chunk c+1), so the loads are in flight for almost a whole chunk:
+    //   0..8    transpose filter tap i of the weights into the stage
+    //   9..17   load 8 bytes of the weight row
+    //   then per patch task: PX transposes (one pixel each), 8 loads (one channel each)
+    constexpr int kItems = 18 + PT * (PX + 8);
+    auto work_item = [&](int it, bool do_pack, bool do_load, unsigned char *dst, int c) {
+        if (it < 9) {
+            if (!do_pack) return;
+            const int tap = it;
+            uint32_t o[2];
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const int e0 = (2 * q) * 9 + tap, e1 = (2 * q + 1) * 9 + tap;
+                o[q] = pack_halves(wraw[e0 >> 1], e0 & 1, wraw[e1 >> 1], e1 & 1);
+            }
+            *reinterpret_cast<uint2v *>(dst + wdst + tap * MT * 16) = uint2v{o[0], o[1]};
+        } else if (it < 18) {
+            if (!do_load) return;
+            const int i = it - 9;
+            const uint2v t2 = __builtin_bit_cast(
+                uint2v, __builtin_amdgcn_raw_buffer_load_b64(wrsrc, woff + i * 8, c * kChunk * 9 * 2, 0));
+            wraw[2 * i] = t2[0];
+            wraw[2 * i + 1] = t2[1];
+        } else {
+            const int j = (it - 18) / (PX + 8), r = (it - 18) % (PX + 8);
+            if (r < PX) {
+                if (!do_pack) return;
+                const int k = r;
+                uint32_t o[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    o[q] = pack_halves(praw[j][2 * q], k, praw[j][2 * q + 1], k);
+                *reinterpret_cast<uint4v *>(dst + loff[j] + k * pair_step) =
+                    uint4v{o[0], o[1], o[2], o[3]};
+            } else {
+                if (!do_load) return;
+                const int q = r - PX;
+                const int soff = (c * kChunk + q) * HW * 2;
+                if constexpr (PX == 2)
+                    praw[j][q] = __builtin_amdgcn_raw_buffer_load_b32(xrsrc, goff[j], soff, 0);
+                else
+                    praw[j][q] = __builtin_amdgcn_raw_buffer_load_b16(xrsrc, goff[j], soff, 0);
+            }
+        }
+    };
+
+    // The first chunk's loads go out as early as their addresses are known - the weights
+    // first, they need no geometry - and the rest of the set-up runs under their latency.
+#pragma unroll
+    for (int it = 9; it < 18; ++it) work_item(it, false, true, smem, 0);
+
+    // ---- tile geometry (uniform values) ----------------------------------------------------
+    int vr_lo, nrows;
+    {
+        const int p_last = min(n0 + NT, a.npix) - 1;
+        int ra, rb, t;
+        const int na = fast_div(n0, OHW, a.inv_ohw, &ra), oha = fast_div(ra, a.OW, a.inv_ow, &t);
+        const int nb = fast_div(p_last, OHW, a.inv_ohw, &rb), ohb = fast_div(rb, a.OW, a.inv_ow, &t);
+        vr_lo = na * VH + oha * STRIDE;
+        nrows = nb * VH + ohb * STRIDE + 2 - vr_lo + 1;
+    }
+
+    // ---- per-thread patch load tasks: (virtual row, iw, channel octet), fixed for all chunks
+    {
+        const int WPX = W / PX;
+        const int per_octet = nrows * WPX;
+#pragma unroll
+        for (int j = 0; j < PT; ++j) {
+            const int t = tid + j * 256;
+            const int octet = t >= per_octet;
+            const int rem = t - (octet ? per_octet : 0);
+            int iw, vi;
+            const int vrow = fast_div(rem, WPX, a.inv_wpx, &iw);
+            iw *= PX;
+            const int n = fast_div(vr_lo + vrow, VH, a.inv_vh, &vi);
+            const int ih = vi - 1;
+            const bool live = t < 2 * per_octet && ih >= 0 && ih < H && n < a.N;
+            const int col = iw + 1;
+            const int word = STRIDE == 2 ? (col & 1) * PWH + (col >> 1) : col;
+            // tasks with nothing to fetch (padding rows, past the tile) load element 0 and
+            // write it to a dump area behind the planes, so that no store needs a predicate
+            goff[j] = live ? 2u * (uint32_t)((n * a.IC + octet * 8) * HW + ih * W + iw) : 0u;
+            loff[j] = live ? 2 * kAPlane + octet * a.pplane + (vrow * PWS + word) * 16
+                           : 2 * kAPlane + 2 * a.pplane + (tid & 15) * 32 +
+                                 (STRIDE == 2 ? 16 - pair_step : 0);
+        }
+    }
+#pragma unroll
+    for (int it = 18; it < kItems; ++it) work_item(it, false, true, smem, 0);
+
+    // ---- per-lane stage offsets of this lane's pixels (MFMA pixel operand) ------------------
+    int pb[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        const int p = n0 + wn * WTN + j * 32 + lrow;
+        int rem, ow;
+        const int n = fast_div(p, OHW, a.inv_ohw, &rem);
+        const int oh = fast_div(rem, a.OW, a.inv_ow, &ow);
+        pb[j] = 2 * kAPlane + lhalf * a.pplane +
+                (p < a.npix ? ((n * VH + oh * STRIDE - vr_lo) * PWS + ow) * 16 : 0);
+    }
+    const int ab = lhalf * kAPlane + (wm * WTM + lrow) * 16;
+
+    float *ss_lds = reinterpret_cast<float *>(smem + a.ss_offset);
+
+    float16v acc[MI][NJ];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    const int nchunks = a.IC / kChunk;
+    // zero the patch planes of both stages once (padding rows and columns are never written
+    // again) and stage the tile's (scale, offset) pairs
+    {
+        const int words = 2 * a.pplane / 16;
+        for (int s = 0; s < 2; ++s) {
+            uint4v *pz = reinterpret_cast<uint4v *>(smem + s * stage_bytes + 2 * kAPlane);
+            for (int i = tid; i < words; i += 256) pz[i] = uint4v{0u, 0u, 0u, 0u};
+        }
+    }
+    stage_scale_shift(ss_lds, m0, MT, a.scale, a.shift, a.bias, a.OC, tid, 256);
+    __syncthreads();          // zeroing complete before the first real data lands
+    if (nchunks > 1) {
+#pragma unroll
+        for (int it = 0; it < kItems; ++it) work_item(it, true, true, smem, 1);
+    } else {
+#pragma unroll
+        for (int it = 0; it < kItems; ++it) work_item(it, true, false, smem, 0);
+    }
+    __syncthreads();
+
+    // MFMA operands are requested from LDS kDepth taps (at least four MFMAs) ahead of their use
+    constexpr int kDepth = 1, kSlots = kDepth + 1;
+    uint4v af[kSlots][MI], bf[kSlots][NJ];
+    // pws16 = bytes per patch row in a plane.  The caller hides it (and the stage pointers)
+    // from loop-invariant code motion: precomputed per-tap addresses for both stages would
+    // cost some 60 registers, one scalar and one vector add per read cost nothing.
+    auto fetch = [&](const unsigned char *st, int pws16, int tap, int slot) {
+        const int r = tap / 3, s = tap - r * 3;
+        const int toff = r * pws16 + (STRIDE == 2 ? (s & 1) * (pws16 >> 1) + (s >> 1) * 16 : s * 16);
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+            af[slot][i] = *reinterpret_cast<const uint4v *>(st + ab + (tap * MT + i * 32) * 16);
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+            bf[slot][j] = *reinterpret_cast<const uint4v *>(st + pb[j] + toff);
+    };
+    // One filter tap of chunk c: request the next tap's operands from LDS, then this tap's
+    // MFMAs, each followed by its share of the staging items of chunks c+1 (transposes into the
+    // idle stage) and c+2 (loads): a few byte permutes, an LDS store or a few loads, which issue
+    // while the MFMA runs.  The order written here is kept: the fences stop the compiler from
+    // regrouping it.  MODE 2 = transposes and loads, 1 = transposes only, 0 = neither.
+    auto tap_step = [&](auto tapc, auto modec, const unsigned char *cur_stage,
+                        unsigned char *next_stage, int pws16, int cl) {
+        constexpr int tap = decltype(tapc)::value;
+        constexpr int mode = decltype(modec)::value;
+        constexpr int cur = tap % kSlots, nm = MI * NJ;
+        if constexpr (tap + kDepth < 9) fetch(cur_stage, pws16, tap + kDepth, (tap + kDepth) % kSlots);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+                // pixel operand first: the accumulator tile is D[pixel][channel]
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    __builtin_bit_cast(bf16x8v, bf[cur][j]), __builtin_bit_cast(bf16x8v, af[cur][i]),
+                    acc[i][j], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (mode > 0) {
+                    const int g = tap * nm + i * NJ + j;
+#pragma unroll
+                    for (int it = g * kItems / (9 * nm); it < (g + 1) * kItems / (9 * nm); ++it)
+                        work_item(it, true, mode == 2, next_stage, cl);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+    };
+    auto chunk_taps = [&](auto modec, const unsigned char *cur_stage, unsigned char *next_stage,
+                          int pws16, int cl) {
+#pragma unroll
+        for (int t = 0; t < kDepth; ++t) fetch(cur_stage, pws16, t, t);
+        tap_step(std::integral_constant<int, 0>{}, modec, cur_stage, next_stage, pws16, cl);
+        tap_step(std::integral_constant<int, 1>{}, modec, cur_stage, next_stage, pws16, cl);
+        tap_step(std::integral_constant<int, 2>{}, modec, cur_stage, next_stage, pws16, cl);
+        tap_step(std::integral_constant<int, 3>{}, modec, cur_stage, next_stage, pws16, cl);
+        tap_step(std::integral_constant<int, 4>{}, modec, cur_stage, next_stage, pws16, cl);
+        tap_step(std::integral_constant<int, 5>{}, modec, cur_stage, next_stage, pws16, cl);
+        tap_step(std::integral_constant<int, 6>{}, modec, cur_stage, next_stage, pws16, cl);
+        tap_step(std::integral_constant<int, 7>{}, modec, cur_stage, next_stage, pws16, cl);
+        tap_step(std::integral_constant<int, 8>{}, modec, cur_stage, next_stage, pws16, cl);
+    };
+
+    auto chunk = [&](auto modec, int c) {
+        int so = (c & 1) * stage_bytes, pws16 = PWS * 16;
+        asm volatile("" : "+s"(so), "+s"(pws16));
+        chunk_taps(modec, smem + so, smem + (stage_bytes - so), pws16, c + 2);
+        if constexpr (decltype(modec)::value > 0) __syncthreads();
+    };
+    // steady state, then the last two chunks, which have less and nothing left to stage
+    for (int c = 0; c + 2 < nchunks; ++c) chunk(std::integral_constant<int, 2>{}, c);
+    if (nchunks > 1) chunk(std::integral_constant<int, 1>{}, nchunks - 2);
+    chunk(std::integral_constant<int, 0>{}, nchunks - 1);
+
+    // ---- fused tail: per-wave staging in LDS, vector stores --------------------------------
+    __syncthreads();                       // every wave is done reading the operand tiles
+    unsigned char *stage = smem + wave * (MI * NJ * kStageBytes);   // <= 40 KB < two stages
+    const TailArgs tail{a.scale, a.shift, a.bias, a.residual, a.y, a.OC, OHW, a.npix, a.relu};
+    store_acc_tiles_batched<MI, NJ>(acc, stage, lane, m0 + wm * WTM, n0 + wn * WTN, tail, a.vmode,
+                                    ss_lds, wm * WTM);
+}
+
+template <int NT, int STRIDE, int PT, int PX>
+tvg_status launch_instance(const DbufArgs &a, size_t lds, hipStream_t stream)
+{
+    auto kernel = conv3x3_dbuf_kernel<NT, STRIDE, PT, PX>;
+    static bool configured = false;      // opt in to > 64 KB of dynamic LDS once per instance
+    if (!configured) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+            return TVG_ERR_LAUNCH;
+        configured = true;
+    }
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(a.mtiles * a.ntiles)), dim3(256), lds, stream, a);
+    return hipGetLastError() == hipSuccess ? TVG_OK : TVG_ERR_LAUNCH;
+}
+
+template <int NT, int STRIDE>
+tvg_status launch_pt(const DbufArgs &a, size_t lds, int pt, int px, hipStream_t stream)
+{
+    if (px == 2) {
+        if (pt <= 2) return launch_instance<NT, STRIDE, 2, 2>(a, lds, stream);
+        return launch_instance<NT, STRIDE, 4, 2>(a, lds, stream);
+    }
+    if (pt <= 2) return launch_instance<NT, STRIDE, 2, 1>(a, lds, stream);
+    return launch_instance<NT, STRIDE, 4, 1>(a, lds, stream);
+}
+
+template <int NT>
+tvg_status launch_stride(const DbufArgs &a, int stride, size_t lds, int pt, int px, hipStream_t stream)
+{
+    return stride == 1 ? launch_pt<NT, 1>(a, lds, pt, px, stream)
+                       : launch_pt<NT, 2>(a, lds, pt, px, stream);
+}
+
+}  // namespace
+
+// Fills the double-buffered fields of a plan whose mt/nt/rows are set; false if the two
+// stages do not fit or the tile shape has no instance.
+bool plan_conv3x3_dbuf(const ConvProblem &p, Patch3x3Plan *plan)
+{
+    if (plan->mt != kMT) return false;
+    const int pwh = (p.W + 3) / 2;
+    const int pws = p.sh == 2 ? 2 * pwh : p.W + 2;
+    const int pplane = plan->rows * pws * 16;
+    int px = p.W % 2 == 0 ? 2 : 1;
+    int pt = (2 * plan->rows * (p.W / px) + 255) / 256;
+    if (px == 2 && pt > 4) { px = 1; pt = (2 * plan->rows * p.W + 255) / 256; }
+    if (pt > 4) return false;
+    // behind the planes of a stage: 32 bytes for each of 16 lanes, where idle patch tasks store
+    // (a stride-2 pair stores its two pixels pwh - 1 words apart)
+    const int dump = 512 + (p.sh == 2 ? pwh * 16 : 0);
+    const int stage = 2 * kAPlane + 2 * pplane + dump;
+    const size_t lds = 2 * (size_t)stage + (size_t)kMT * 8;
+    // two workgroups per CU, or one per CU when the whole grid is resident at once anyway
+    if (lds > 80 * 1024 && !(lds <= 160 * 1024 && plan->tiles <= kComputeUnits)) return false;
+    if (plan->tiles >= (1 << 22)) return false;      // fast_div range of the tile index
+    plan->dbuf = 1;
+    plan->pt = pt;
+    plan->px = px;
+    plan->pplane = pplane;
+    plan->stage_bytes = stage;
+    plan->lds_bytes = lds;
+    return true;
+}
+
+tvg_status launch_conv3x3_dbuf(const ConvProblem &p, const Patch3x3Plan &plan,
+                               const ConvPointers &ptr, hipStream_t stream)
+{
+    DbufArgs a;
+    a.x = static_cast<const bf16_t *>(ptr.x); a.w = static_cast<const bf16_t *>(ptr.w);
+    a.scale = ptr.scale; a.shift = ptr.shift; a.bias = ptr.bias;
+    a.residual = static_cast<const bf16_t *>(ptr.residual); a.y = static_cast<bf16_t *>(ptr.y);
+    a.N = p.N; a.IC = p.IC; a.H = p.H; a.W = p.W; a.OC = p.OC; a.OH = p.OH; a.OW = p.OW;
+    a.npix = p.npix; a.relu = p.relu;
+    a.mtiles = (p.OC + kMT - 1) / kMT;
+    a.vmode = pick_store_vmode(p.dtype, p.OH * p.OW, ptr.y, ptr.residual);
+    a.pplane = plan.pplane;
+    a.stage_bytes = plan.stage_bytes;
+    a.ss_offset = (int)(plan.lds_bytes - (size_t)kMT * 8);
+    a.x_bytes = (uint32_t)((size_t)p.N * p.IC * p.H * p.W * 2);
+    a.w_bytes = (uint32_t)((size_t)p.OC * p.IC * 9 * 2);
+    a.ntiles = (p.npix + plan.nt - 1) / plan.nt;
+    a.m_major = (size_t)p.OC * p.IC * 9 > (size_t)p.N * p.IC * p.H * p.W;
+    a.inv_tdiv = 1.0f / (float)(a.m_major ? a.ntiles : a.mtiles);
+    a.inv_ohw = 1.0f / (float)(p.OH * p.OW);
+    a.inv_ow = 1.0f / (float)p.OW;
+    a.inv_vh = 1.0f / (float)(p.H + 2);
+    a.inv_wpx = 1.0f / (float)(p.W / plan.px);
+    if (plan.nt == 256) return launch_stride<256>(a, p.sh, plan.lds_bytes, plan.pt, plan.px, stream);
+    if (plan.nt == 128) return launch_stride<128>(a, p.sh, plan.lds_bytes, plan.pt, plan.px, stream);
+    return launch_stride<64>(a, p.sh, plan.lds_bytes, plan.pt, plan.px, stream);
+}
+
+}  // namespace tvg

@@ -298,10 +298,12 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
 
     // ---- fused tail: transpose each 32x32 tile through LDS, vector stores -----------------
     __syncthreads();                       // every wave is done reading the operand tiles
-    unsigned char *stage = smem + wave * kStageBytes;
+    // up to two tiles per wave are staged at a time: 20 KB, less than any instance's operands
+    constexpr int BT = MI * NJ >= 2 ? 2 : 1;
+    unsigned char *stage = smem + wave * (BT * kStageBytes);
     const TailArgs tail{a.scale, a.shift, a.bias, a.residual, a.y, a.OC, OHW, a.npix, a.relu};
-    store_acc_tiles<bf16_t, MI, NJ>(acc, stage, lane, m0 + wm * WTM, n0 + wn * WTN, tail, a.vmode,
-                                    ss_lds, wm * WTM);
+    store_acc_tiles_batched<MI, NJ, BT>(acc, stage, lane, m0 + wm * WTM, n0 + wn * WTN, tail,
+                                        a.vmode, ss_lds, wm * WTM);
 }
 
 // Largest number of virtual rows any pixel tile of NT pixels needs.
@@ -370,6 +372,8 @@ bool plan_conv3x3_patch(const ConvProblem &p, Patch3x3Plan *plan)
     if (p.npix >= (1 << 22) || (long)p.N * (p.H + 2) >= (1 << 22)) return false;   // fast_div range
     int force_mt = 0, force_nt = 0;
     if (const char *e = getenv("TVG_FORCE_TILE")) sscanf(e, "%d,%d", &force_mt, &force_nt);
+    bool use_dbuf = true;
+    if (const char *e = getenv("TVG_DBUF")) use_dbuf = atoi(e) != 0;
     // Tile choice (measured on MI355X at batch 64): take the largest tile that still gives at
     // least 1.5 workgroups per CU, wider in pixels on a tie; if none does, the tile shape with
     // the most workgroups.  A 128-channel tile with more than 4 patch tasks per thread (wide
@@ -391,11 +395,15 @@ bool plan_conv3x3_patch(const ConvProblem &p, Patch3x3Plan *plan)
         if (px == 2 && pt > 4) { px = 1; pt = (2 * rows * p.W + 255) / 256; }
         const size_t lds = (size_t)9 * mt * kPosBytes + (size_t)rows * (p.W + 2) * kPosBytes +
                            (size_t)mt * 8;      // operands + (scale, offset) pairs
-        if (pt > 8 || lds > 80 * 1024) continue;
-        if (mt == 128 && pt > 4 && !force_mt) continue;
         const long tiles = (long)((p.OC + mt - 1) / mt) * ((p.npix + nt - 1) / nt);
-        const bool fills = 2 * tiles >= 3 * kComputeUnits;
-        const Patch3x3Plan cand{mt, nt, pt, px, rows, lds, tiles};
+        Patch3x3Plan cand{mt, nt, pt, px, rows, lds, tiles, 0, 0, 0};
+        if (!(use_dbuf && plan_conv3x3_dbuf(p, &cand))) {
+            if (pt > 8 || lds > 80 * 1024) continue;
+            if (mt == 128 && pt > 4 && !force_mt) continue;
+        }
+        // the pipelined kernel keeps a CU busy with one workgroup: three quarters of the CUs
+        // covered is enough for it; the single-stage kernel wants 1.5 workgroups per CU
+        const bool fills = cand.dbuf ? 4 * tiles >= 3 * kComputeUnits : 2 * tiles >= 3 * kComputeUnits;
         if (!found || (!best_fills && (fills || tiles > best.tiles))) {
             best = cand;
             best_fills = fills;
@@ -410,6 +418,7 @@ bool plan_conv3x3_patch(const ConvProblem &p, Patch3x3Plan *plan)
 tvg_status launch_conv3x3_patch(const ConvProblem &p, const Patch3x3Plan &plan,
                                 const ConvPointers &ptr, hipStream_t stream)
 {
+    if (plan.dbuf) return launch_conv3x3_dbuf(p, plan, ptr, stream);
     PatchArgs a;
     a.x = static_cast<const bf16_t *>(ptr.x); a.w = static_cast<const bf16_t *>(ptr.w);
     a.scale = ptr.scale; a.shift = ptr.shift; a.bias = ptr.bias;

@@ -62,8 +62,9 @@ __global__ __launch_bounds__(256, 2) void conv7x7s2_stem_kernel(const StemArgs a
     const int patch_bytes = IC * nrows * pitch;
     unsigned char *As = smem;                            // [pair][oc][8 taps]
     unsigned char *Ps = smem + a_bytes;                  // 2 x [ic][row][W + 8]
-    unsigned char *stage = smem + a_bytes + 2 * patch_bytes + (threadIdx.x >> 6) * kStageBytes;
-    float *ss_lds = reinterpret_cast<float *>(smem + a_bytes + 2 * patch_bytes) + 4 * kStageFloats;
+    // per wave: staging for two accumulator tiles at a time
+    unsigned char *stage = smem + a_bytes + 2 * patch_bytes + (threadIdx.x >> 6) * 2 * kStageBytes;
+    float *ss_lds = reinterpret_cast<float *>(smem + a_bytes + 2 * patch_bytes) + 8 * kStageFloats;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lrow = lane & 31, lhalf = lane >> 5;
@@ -200,7 +201,7 @@ __global__ __launch_bounds__(256, 2) void conv7x7s2_stem_kernel(const StemArgs a
         // now, so that waiting for those loads does not also wait for this tile's stores.
         if (next < a.ntiles) store_tile_rows((it + 1) & 1);
 
-        store_acc_tiles<bf16_t, 2, 2>(acc, stage, lane, m0, p0 + wave * 64, tail, a.vmode, ss_lds, 0);
+        store_acc_tiles_batched<2, 2, 2>(acc, stage, lane, m0, p0 + wave * 64, tail, a.vmode, ss_lds, 0);
         __syncthreads();
     }
 }
@@ -248,7 +249,7 @@ bool plan_conv7x7s2_stem(const ConvProblem &p, StemPlan *plan)
     if (rows > p.H + 6) return false;                   // a tile may wrap into the next image once
     const int nm = (p.IC * 7 + 1) / 2;
     const size_t lds = (size_t)2 * nm * kMT * 16 + (size_t)2 * p.IC * rows * (p.W + 8) * 2 +
-                       (size_t)4 * kStageBytes + (size_t)kMT * 8;
+                       (size_t)8 * kStageBytes + (size_t)kMT * 8;
     const int lt = (p.IC * rows * (p.W / 8) + 255) / 256;
     if (lds > 80 * 1024 || lt > 8) return false;
     plan->rows = rows;

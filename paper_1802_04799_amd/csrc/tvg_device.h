@@ -271,6 +271,95 @@ __device__ __forceinline__ void store_acc_tiles(const float16v (&acc)[MI][NJ], u
                           row_base + i * 32);
 }
 
+// The fast-path body of store_acc_tiles_batched: tile (i, j) starts at channel ocu + 32 i and
+// at pixel rem0[j] of image n0[j]; everything is in range.  BT tiles share one LDS round trip.
+template <int MI, int NJ, int BT, bool HAS_RES>
+__device__ __forceinline__ void store_fast_tiles(const float16v (&acc)[MI][NJ], unsigned char *stage,
+                                                 int lane, int ocu, const int (&n0)[NJ],
+                                                 const int (&rem0)[NJ], const TailArgs &t,
+                                                 const float *ss, int row_base)
+{
+    static_assert((MI * NJ) % BT == 0, "tiles per batch must divide the tile count");
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    const float floor_v = t.relu ? 0.0f : -INFINITY;
+    const bf16_t *res = static_cast<const bf16_t *>(t.residual);
+    bf16_t *y = static_cast<bf16_t *>(t.y);
+    const int row = lane >> 2, g = lane & 3;
+#pragma unroll
+    for (int b0 = 0; b0 < MI * NJ; b0 += BT) {
+#pragma unroll
+        for (int k = 0; k < BT; ++k) {
+            const int i = (b0 + k) / NJ, j = (b0 + k) % NJ;
+            const float sc = ss[2 * (row_base + i * 32 + lrow)];
+            const float sf = ss[2 * (row_base + i * 32 + lrow) + 1];
+            unsigned char *st = stage + k * kStageBytes;
+            const int base = (n0[j] * t.OC + ocu + i * 32 + lrow) * t.OHW + rem0[j] + 4 * lhalf;
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                float f[4], r[4];
+                if (HAS_RES)
+                    Group4<bf16_t>::unpack(*reinterpret_cast<const uint2v *>(res + base + 8 * gq), r);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    float v = fmaf(acc[i][j][4 * gq + q], sc, sf);
+                    if (HAS_RES) v += r[q];
+                    f[q] = fmaxf(v, floor_v);
+                }
+                *reinterpret_cast<uint2v *>(st + lrow * kStageRow + (8 * gq + 4 * lhalf) * 2) =
+                    Group4<bf16_t>::pack(f);
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int k = 0; k < BT; ++k) {
+            const int i = (b0 + k) / NJ, j = (b0 + k) % NJ;
+            const unsigned char *st = stage + k * kStageBytes;
+            const int b2 = (n0[j] * t.OC + ocu + i * 32 + row) * t.OHW + rem0[j] + 8 * g;
+#pragma unroll
+            for (int it = 0; it < 2; ++it)
+                *reinterpret_cast<uint4v *>(y + b2 + it * 16 * t.OHW) =
+                    *reinterpret_cast<const uint4v *>(st + (row + 16 * it) * kStageRow + g * 16);
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+// store_acc_tiles for bf16 with BT*kStageBytes of wave-private LDS at `stage`: when every tile
+// of the wave is on store_tile's fast path (mode 8, nothing ragged, each tile within one
+// image) BT tiles at a time are converted and staged first and stored afterwards, so the LDS
+// round trip and the store issue are paid once per batch instead of once per tile.
+template <int MI, int NJ, int BT = MI * NJ>
+__device__ __forceinline__ void store_acc_tiles_batched(const float16v (&acc)[MI][NJ],
+                                                        unsigned char *stage, int lane, int oc_base,
+                                                        int p_base, const TailArgs &t, int vmode,
+                                                        const float *ss, int row_base)
+{
+    const int pbu = __builtin_amdgcn_readfirstlane(p_base);
+    const int ocu = __builtin_amdgcn_readfirstlane(oc_base);
+    bool fast = vmode == 8 && ocu + MI * 32 <= t.OC && pbu + NJ * 32 <= t.npix;
+    int n0[NJ], rem0[NJ];
+    n0[0] = pbu / t.OHW;
+    rem0[0] = pbu - n0[0] * t.OHW;
+    fast = fast && rem0[0] + 32 <= t.OHW;
+#pragma unroll
+    for (int j = 1; j < NJ; ++j) {
+        // the previous tile ended inside its image, so this one starts at most at its end
+        const bool wrap = rem0[j - 1] + 32 >= t.OHW;
+        n0[j] = n0[j - 1] + (wrap ? 1 : 0);
+        rem0[j] = wrap ? 0 : rem0[j - 1] + 32;
+        fast = fast && rem0[j] + 32 <= t.OHW;
+    }
+    if (!fast) {
+        store_acc_tiles<bf16_t, MI, NJ>(acc, stage, lane, oc_base, p_base, t, vmode, ss, row_base);
+        return;
+    }
+    // the residual test is hoisted out: a branch per group would fence the tiles from each other
+    if (t.residual)
+        store_fast_tiles<MI, NJ, BT, true>(acc, stage, lane, ocu, n0, rem0, t, ss, row_base);
+    else
+        store_fast_tiles<MI, NJ, BT, false>(acc, stage, lane, ocu, n0, rem0, t, ss, row_base);
+}
+
 // Host side: the store mode the problem allows (see store_tile).
 inline int pick_store_vmode(int dtype, int OHW, const void *y, const void *residual)
 {

@@ -50,6 +50,9 @@ struct Patch3x3Plan {
     int rows;           // virtual input rows staged per tile (maximum over tiles)
     size_t lds_bytes;
     long tiles;
+    int dbuf;           // 1 = the software-pipelined kernel with two LDS stages runs the tile
+    int pplane;         // its bytes per channel-octet plane of the patch
+    int stage_bytes;    // its bytes per LDS stage
 };
 
 // True when the problem is one the patch kernel is built for (bf16, 3x3, pad 1,
@@ -58,6 +61,10 @@ bool plan_conv3x3_patch(const ConvProblem &p, Patch3x3Plan *plan);
 bool conv3x3_patch_pointers_ok(const ConvPointers &ptr);
 tvg_status launch_conv3x3_patch(const ConvProblem &p, const Patch3x3Plan &plan,
                                 const ConvPointers &ptr, hipStream_t stream);
+// Two-stage variant (64-channel tiles): completes a plan whose mt, nt and rows are set.
+bool plan_conv3x3_dbuf(const ConvProblem &p, Patch3x3Plan *plan);
+tvg_status launch_conv3x3_dbuf(const ConvProblem &p, const Patch3x3Plan &plan,
+                               const ConvPointers &ptr, hipStream_t stream);
 
 // bf16 7x7 stride-2 pad-3 kernel for IC <= 4 (the ResNet stem).
 struct StemPlan {
