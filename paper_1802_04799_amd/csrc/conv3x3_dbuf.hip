@@ -40,6 +40,8 @@ struct DbufArgs {
     int vmode;        // pixels per vector store in the epilogue (8, 4 or 1)
     uint32_t x_bytes, w_bytes;
     int pplane;       // bytes of one channel-octet plane of the patch
+    int pws;          // 16-byte words per patch row in a plane
+    int xp16;         // extra bytes between the rows of consecutive images in a plane
     int stage_bytes;  // weight planes + patch planes + dump area
     int ss_offset;    // byte offset in LDS of the staged (scale, offset) pairs
     int ntiles, m_major;
@@ -68,13 +70,20 @@ __device__ __forceinline__ uint32_t pack_halves(uint32_t a, int ha, uint32_t b, 
     return __builtin_amdgcn_perm(b, a, sel);
 }
 
-// PT = patch load tasks per thread; PX = horizontally adjacent pixels per load (2 needs an
-// even W: 32-bit loads).
-template <int NT, int STRIDE, int PT, int PX>
-__global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
+// PT = patch load tasks per staging thread; PX = horizontally adjacent pixels per load (W must
+// be a multiple: 16- to 128-bit loads; the vector memory path is what the staging saturates,
+// and its cost is per instruction, so the widest load the row length admits is used);
+// NW = waves per workgroup.
+// NW = 4: every thread stages weights and patch; two workgroups share a CU and fill each
+// other's gaps.  NW = 8 is for grids of at most one workgroup per CU: two waves per SIMD of the
+// same workgroup fill each other's gaps instead, waves 0-3 stage the weights and waves 4-7 the
+// patch (256 threads each, as for NW = 4), and all eight run MFMAs on a quarter-size wave tile.
+template <int NT, int STRIDE, int PT, int PX, int NW>
+__global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void conv3x3_dbuf_kernel(const DbufArgs a)
 {
     constexpr int MT = kMT;
-    constexpr int WM = NT == 256 ? 1 : 2, WN = 4 / WM;
+    constexpr int kThreads = NW * 64;
+    constexpr int WM = NW == 8 ? 2 : (NT == 256 ? 1 : 2), WN = NW / WM;
     constexpr int WTM = MT / WM, WTN = NT / WN;
     constexpr int MI = WTM / 32, NJ = WTN / 32;
 
@@ -83,12 +92,12 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WM, wn = wave / WM;
     const int lrow = lane & 31, lhalf = lane >> 5;
+    const int stid = tid & 255;            // index among the 256 threads of a staging role
 
     const int H = a.H, W = a.W, HW = H * W, OHW = a.OH * a.OW;
     const int VH = H + 2;
     // 16-byte words per patch row, and where the odd columns start (stride 2 only)
-    const int PWH = (W + 3) >> 1;
-    const int PWS = STRIDE == 2 ? 2 * PWH : W + 2;
+    const int PWS = a.pws, PWH = PWS >> 1;
     const int stage_bytes = a.stage_bytes;
 
     // All index arithmetic divides through host-computed float reciprocals; the host admits
@@ -103,7 +112,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
     }
 
     // ---- weight task: one output channel, four input channels, all nine taps ----------------
-    const int w_ocl = tid >> 2, w_quad = tid & 3;
+    const int w_ocl = stid >> 2, w_quad = stid & 3;
     // rows past OC read row 0: their products land in accumulators that are never stored
     const uint32_t woff =
         2u * (uint32_t)((((m0 + w_ocl) < a.OC ? m0 + w_ocl : 0) * a.IC + w_quad * 4) * 9);
@@ -114,8 +123,14 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
     // second pixel of a pair: the next word, or for stride 2 (first pixel in an odd padded
     // column) the following even column
     const int pair_step = STRIDE == 2 ? 16 - PWH * 16 : 16;
-    uint32_t praw[PT][8];
-    uint32_t wraw[18];
+    // byte offset of pixel k of a task from its first: consecutive words, or for stride 2
+    // alternating between the odd-column and the even-column half of the row
+    auto pixel_step = [&](int k) { return STRIDE == 2 ? (k & 1) * pair_step + (k >> 1) * 16 : k * 16; };
+    // two register sets: while one is transposed into LDS (chunk c+1) the other is still in
+    // flight (chunk c+2), so a load has two chunks of MFMA time to arrive
+    constexpr int PW32 = PX >= 2 ? PX / 2 : 1;        // registers per patch load
+    uint32_t praw[2][PT][8][PW32];
+    uint32_t wraw[2][18];
 
     const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<bf16_t *>(a.x), 0, a.x_bytes, kRsrcFlags);
@@ -124,12 +139,13 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
 
     // The staging work of a chunk as a list of small items, so that it can be dealt out between
     // the MFMAs of the previous chunk.  A register is reloaded (chunk c+2) right after the item
-    // that consumed it (chunk c+1), so the loads are in flight for almost a whole chunk:
+    // that consumed it (chunk c+1) - with chunk c+3, the other set holding chunk c+2:
     //   0..8    transpose filter tap i of the weights into the stage
     //   9..17   load 8 bytes of the weight row
     //   then per patch task: PX transposes (one pixel each), 8 loads (one channel each)
+    // `set` = which of the two register sets the item works on.
     constexpr int kItems = 18 + PT * (PX + 8);
-    auto work_item = [&](int it, bool do_pack, bool do_load, unsigned char *dst, int c) {
+    auto work_item = [&](int it, int set, bool do_pack, bool do_load, unsigned char *dst, int c) {
         if (it < 9) {
             if (!do_pack) return;
             const int tap = it;
@@ -137,7 +153,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
 #pragma unroll
             for (int q = 0; q < 2; ++q) {
                 const int e0 = (2 * q) * 9 + tap, e1 = (2 * q + 1) * 9 + tap;
-                o[q] = pack_halves(wraw[e0 >> 1], e0 & 1, wraw[e1 >> 1], e1 & 1);
+                o[q] = pack_halves(wraw[set][e0 >> 1], e0 & 1, wraw[set][e1 >> 1], e1 & 1);
             }
             *reinterpret_cast<uint2v *>(dst + wdst + tap * MT * 16) = uint2v{o[0], o[1]};
         } else if (it < 18) {
@@ -145,8 +161,8 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
             const int i = it - 9;
             const uint2v t2 = __builtin_bit_cast(
                 uint2v, __builtin_amdgcn_raw_buffer_load_b64(wrsrc, woff + i * 8, c * kChunk * 9 * 2, 0));
-            wraw[2 * i] = t2[0];
-            wraw[2 * i + 1] = t2[1];
+            wraw[set][2 * i] = t2[0];
+            wraw[set][2 * i + 1] = t2[1];
         } else {
             const int j = (it - 18) / (PX + 8), r = (it - 18) % (PX + 8);
             if (r < PX) {
@@ -155,32 +171,57 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
                 uint32_t o[4];
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
-                    o[q] = pack_halves(praw[j][2 * q], k, praw[j][2 * q + 1], k);
-                *reinterpret_cast<uint4v *>(dst + loff[j] + k * pair_step) =
+                    o[q] = pack_halves(praw[set][j][2 * q][k >> 1], k & 1,
+                                       praw[set][j][2 * q + 1][k >> 1], k & 1);
+                *reinterpret_cast<uint4v *>(dst + loff[j] + pixel_step(k)) =
                     uint4v{o[0], o[1], o[2], o[3]};
             } else {
                 if (!do_load) return;
                 const int q = r - PX;
                 const int soff = (c * kChunk + q) * HW * 2;
-                if constexpr (PX == 2)
-                    praw[j][q] = __builtin_amdgcn_raw_buffer_load_b32(xrsrc, goff[j], soff, 0);
-                else
-                    praw[j][q] = __builtin_amdgcn_raw_buffer_load_b16(xrsrc, goff[j], soff, 0);
+                if constexpr (PX == 8) {
+                    const uint4v t4 = __builtin_bit_cast(
+                        uint4v, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, goff[j], soff, 0));
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) praw[set][j][q][d] = t4[d];
+                } else if constexpr (PX == 4) {
+                    const uint2v t2 = __builtin_bit_cast(
+                        uint2v, __builtin_amdgcn_raw_buffer_load_b64(xrsrc, goff[j], soff, 0));
+                    praw[set][j][q][0] = t2[0];
+                    praw[set][j][q][1] = t2[1];
+                } else if constexpr (PX == 2) {
+                    praw[set][j][q][0] = __builtin_amdgcn_raw_buffer_load_b32(xrsrc, goff[j], soff, 0);
+                } else {
+                    praw[set][j][q][0] = __builtin_amdgcn_raw_buffer_load_b16(xrsrc, goff[j], soff, 0);
+                }
             }
         }
     };
 
+    // Staging roles: 0 = weights (items 0..17), 1 = patch (the rest), 2 = both.
+    const bool w_role = NW == 4 || wave < 4, p_role = NW == 4 || wave >= 4;
+    auto weight_items = [&](int set, bool do_pack, bool do_load, unsigned char *dst, int c) {
+        if (!w_role) return;
+#pragma unroll
+        for (int it = 0; it < 18; ++it) work_item(it, set, do_pack, do_load, dst, c);
+    };
+    auto patch_items = [&](int set, bool do_pack, bool do_load, unsigned char *dst, int c) {
+        if (!p_role) return;
+#pragma unroll
+        for (int it = 18; it < kItems; ++it) work_item(it, set, do_pack, do_load, dst, c);
+    };
+
     // The first chunk's loads go out as early as their addresses are known - the weights
     // first, they need no geometry - and the rest of the set-up runs under their latency.
-#pragma unroll
-    for (int it = 9; it < 18; ++it) work_item(it, false, true, smem, 0);
+    weight_items(0, false, true, smem, 0);
 
     // ---- tile geometry (uniform values) ----------------------------------------------------
-    int vr_lo, nrows;
+    int vr_lo, nrows, na;
     {
         const int p_last = min(n0 + NT, a.npix) - 1;
         int ra, rb, t;
-        const int na = fast_div(n0, OHW, a.inv_ohw, &ra), oha = fast_div(ra, a.OW, a.inv_ow, &t);
+        na = fast_div(n0, OHW, a.inv_ohw, &ra);
+        const int oha = fast_div(ra, a.OW, a.inv_ow, &t);
         const int nb = fast_div(p_last, OHW, a.inv_ohw, &rb), ohb = fast_div(rb, a.OW, a.inv_ow, &t);
         vr_lo = na * VH + oha * STRIDE;
         nrows = nb * VH + ohb * STRIDE + 2 - vr_lo + 1;
@@ -192,7 +233,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
         const int per_octet = nrows * WPX;
 #pragma unroll
         for (int j = 0; j < PT; ++j) {
-            const int t = tid + j * 256;
+            const int t = stid + j * 256;
             const int octet = t >= per_octet;
             const int rem = t - (octet ? per_octet : 0);
             int iw, vi;
@@ -206,13 +247,15 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
             // tasks with nothing to fetch (padding rows, past the tile) load element 0 and
             // write it to a dump area behind the planes, so that no store needs a predicate
             goff[j] = live ? 2u * (uint32_t)((n * a.IC + octet * 8) * HW + ih * W + iw) : 0u;
-            loff[j] = live ? 2 * kAPlane + octet * a.pplane + (vrow * PWS + word) * 16
-                           : 2 * kAPlane + 2 * a.pplane + (tid & 15) * 32 +
-                                 (STRIDE == 2 ? 16 - pair_step : 0);
+            loff[j] = live ? 2 * kAPlane + octet * a.pplane + (vrow * PWS + word) * 16 + (n - na) * a.xp16
+                           : 2 * kAPlane + 2 * a.pplane + (stid & 15) * (PX > 1 ? PX * 16 : 32) +
+                                 (STRIDE == 2 && PX > 1 ? 16 - pair_step : 0);
         }
     }
-#pragma unroll
-    for (int it = 18; it < kItems; ++it) work_item(it, false, true, smem, 0);
+    patch_items(0, false, true, smem, 0);
+    // the second chunk into the other register set (the channel count is a multiple of 32)
+    weight_items(1, false, true, smem, 1);
+    patch_items(1, false, true, smem, 1);
 
     // ---- per-lane stage offsets of this lane's pixels (MFMA pixel operand) ------------------
     int pb[NJ];
@@ -223,7 +266,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
         const int n = fast_div(p, OHW, a.inv_ohw, &rem);
         const int oh = fast_div(rem, a.OW, a.inv_ow, &ow);
         pb[j] = 2 * kAPlane + lhalf * a.pplane +
-                (p < a.npix ? ((n * VH + oh * STRIDE - vr_lo) * PWS + ow) * 16 : 0);
+                (p < a.npix ? ((n * VH + oh * STRIDE - vr_lo) * PWS + ow) * 16 + (n - na) * a.xp16 : 0);
     }
     const int ab = lhalf * kAPlane + (wm * WTM + lrow) * 16;
 
@@ -244,18 +287,13 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
         const int words = 2 * a.pplane / 16;
         for (int s = 0; s < 2; ++s) {
             uint4v *pz = reinterpret_cast<uint4v *>(smem + s * stage_bytes + 2 * kAPlane);
-            for (int i = tid; i < words; i += 256) pz[i] = uint4v{0u, 0u, 0u, 0u};
+            for (int i = tid; i < words; i += kThreads) pz[i] = uint4v{0u, 0u, 0u, 0u};
         }
     }
-    stage_scale_shift(ss_lds, m0, MT, a.scale, a.shift, a.bias, a.OC, tid, 256);
+    stage_scale_shift(ss_lds, m0, MT, a.scale, a.shift, a.bias, a.OC, tid, kThreads);
     __syncthreads();          // zeroing complete before the first real data lands
-    if (nchunks > 1) {
-#pragma unroll
-        for (int it = 0; it < kItems; ++it) work_item(it, true, true, smem, 1);
-    } else {
-#pragma unroll
-        for (int it = 0; it < kItems; ++it) work_item(it, true, false, smem, 0);
-    }
+    weight_items(0, true, nchunks > 2, smem, 2);
+    patch_items(0, true, nchunks > 2, smem, 2);
     __syncthreads();
 
     // MFMA operands are requested from LDS kDepth taps (at least four MFMAs) ahead of their use
@@ -276,10 +314,10 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
     };
     // One filter tap of chunk c: request the next tap's operands from LDS, then this tap's
     // MFMAs, each followed by its share of the staging items of chunks c+1 (transposes into the
-    // idle stage) and c+2 (loads): a few byte permutes, an LDS store or a few loads, which issue
+    // idle stage) and c+3 (loads into the registers just transposed): a few byte permutes, an LDS store or a few loads, which issue
     // while the MFMA runs.  The order written here is kept: the fences stop the compiler from
     // regrouping it.  MODE 2 = transposes and loads, 1 = transposes only, 0 = neither.
-    auto tap_step = [&](auto tapc, auto modec, const unsigned char *cur_stage,
+    auto tap_step = [&](auto tapc, auto modec, auto setc, auto rolec, const unsigned char *cur_stage,
                         unsigned char *next_stage, int pws16, int cl) {
         constexpr int tap = decltype(tapc)::value;
         constexpr int mode = decltype(modec)::value;
@@ -296,39 +334,68 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
                     acc[i][j], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
                 if (mode > 0) {
+                    constexpr int role = decltype(rolec)::value;
+                    constexpr int first = role == 1 ? 18 : 0, count = (role == 0 ? 18 : kItems) - first;
                     const int g = tap * nm + i * NJ + j;
 #pragma unroll
-                    for (int it = g * kItems / (9 * nm); it < (g + 1) * kItems / (9 * nm); ++it)
-                        work_item(it, true, mode == 2, next_stage, cl);
+                    for (int it = first + g * count / (9 * nm); it < first + (g + 1) * count / (9 * nm); ++it)
+                        work_item(it, decltype(setc)::value, true, mode == 2, next_stage, cl);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
     };
-    auto chunk_taps = [&](auto modec, const unsigned char *cur_stage, unsigned char *next_stage,
-                          int pws16, int cl) {
+    auto chunk_taps = [&](auto modec, auto setc, auto rolec, const unsigned char *cur_stage,
+                          unsigned char *next_stage, int pws16, int cl) {
 #pragma unroll
         for (int t = 0; t < kDepth; ++t) fetch(cur_stage, pws16, t, t);
-        tap_step(std::integral_constant<int, 0>{}, modec, cur_stage, next_stage, pws16, cl);
-        tap_step(std::integral_constant<int, 1>{}, modec, cur_stage, next_stage, pws16, cl);
-        tap_step(std::integral_constant<int, 2>{}, modec, cur_stage, next_stage, pws16, cl);
-        tap_step(std::integral_constant<int, 3>{}, modec, cur_stage, next_stage, pws16, cl);
-        tap_step(std::integral_constant<int, 4>{}, modec, cur_stage, next_stage, pws16, cl);
-        tap_step(std::integral_constant<int, 5>{}, modec, cur_stage, next_stage, pws16, cl);
-        tap_step(std::integral_constant<int, 6>{}, modec, cur_stage, next_stage, pws16, cl);
-        tap_step(std::integral_constant<int, 7>{}, modec, cur_stage, next_stage, pws16, cl);
-        tap_step(std::integral_constant<int, 8>{}, modec, cur_stage, next_stage, pws16, cl);
+        tap_step(std::integral_constant<int, 0>{}, modec, setc, rolec, cur_stage, next_stage, pws16, cl);
+        tap_step(std::integral_constant<int, 1>{}, modec, setc, rolec, cur_stage, next_stage, pws16, cl);
+        tap_step(std::integral_constant<int, 2>{}, modec, setc, rolec, cur_stage, next_stage, pws16, cl);
+        tap_step(std::integral_constant<int, 3>{}, modec, setc, rolec, cur_stage, next_stage, pws16, cl);
+        tap_step(std::integral_constant<int, 4>{}, modec, setc, rolec, cur_stage, next_stage, pws16, cl);
+        tap_step(std::integral_constant<int, 5>{}, modec, setc, rolec, cur_stage, next_stage, pws16, cl);
+        tap_step(std::integral_constant<int, 6>{}, modec, setc, rolec, cur_stage, next_stage, pws16, cl);
+        tap_step(std::integral_constant<int, 7>{}, modec, setc, rolec, cur_stage, next_stage, pws16, cl);
+        tap_step(std::integral_constant<int, 8>{}, modec, setc, rolec, cur_stage, next_stage, pws16, cl);
     };
 
-    auto chunk = [&](auto modec, int c) {
-        int so = (c & 1) * stage_bytes, pws16 = PWS * 16;
+    // Chunk c of parity PAR reads stage PAR, transposes register set PAR^1 (chunk c+1) into
+    // stage PAR^1 and reloads that set with chunk c+3.
+    auto chunk = [&](auto parc, auto modec, int c) {
+        constexpr int par = decltype(parc)::value;
+        int so = par * stage_bytes, pws16 = PWS * 16;
         asm volatile("" : "+s"(so), "+s"(pws16));
-        chunk_taps(modec, smem + so, smem + (stage_bytes - so), pws16, c + 2);
+        using Set = std::integral_constant<int, par ^ 1>;
+        if constexpr (NW == 4)
+            chunk_taps(modec, Set{}, std::integral_constant<int, 2>{}, smem + so,
+                       smem + (stage_bytes - so), pws16, c + 3);
+        else if (wave < 4)
+            chunk_taps(modec, Set{}, std::integral_constant<int, 0>{}, smem + so,
+                       smem + (stage_bytes - so), pws16, c + 3);
+        else
+            chunk_taps(modec, Set{}, std::integral_constant<int, 1>{}, smem + so,
+                       smem + (stage_bytes - so), pws16, c + 3);
         if constexpr (decltype(modec)::value > 0) __syncthreads();
     };
-    // steady state, then the last two chunks, which have less and nothing left to stage
-    for (int c = 0; c + 2 < nchunks; ++c) chunk(std::integral_constant<int, 2>{}, c);
-    if (nchunks > 1) chunk(std::integral_constant<int, 1>{}, nchunks - 2);
-    chunk(std::integral_constant<int, 0>{}, nchunks - 1);
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    using M0 = std::integral_constant<int, 0>;
+    using M1 = std::integral_constant<int, 1>;
+    using M2 = std::integral_constant<int, 2>;
+    // steady state in pairs (the chunk count is even), then the last four or two chunks, which
+    // have less and finally nothing left to stage
+    int c = 0;
+    for (; c + 4 < nchunks; c += 2) {
+        chunk(P0{}, M2{}, c);
+        chunk(P1{}, M2{}, c + 1);
+    }
+    if (c + 4 == nchunks) {
+        chunk(P0{}, M2{}, c);
+        chunk(P1{}, M1{}, c + 1);
+        c += 2;
+    }
+    chunk(P0{}, M1{}, c);
+    chunk(P1{}, M0{}, c + 1);
 
     // ---- fused tail: per-wave staging in LDS, vector stores --------------------------------
     __syncthreads();                       // every wave is done reading the operand tiles
@@ -338,10 +405,10 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
                                     ss_lds, wm * WTM);
 }
 
-template <int NT, int STRIDE, int PT, int PX>
+template <int NT, int STRIDE, int PT, int PX, int NW>
 tvg_status launch_instance(const DbufArgs &a, size_t lds, hipStream_t stream)
 {
-    auto kernel = conv3x3_dbuf_kernel<NT, STRIDE, PT, PX>;
+    auto kernel = conv3x3_dbuf_kernel<NT, STRIDE, PT, PX, NW>;
     static bool configured = false;      // opt in to > 64 KB of dynamic LDS once per instance
     if (!configured) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
@@ -349,19 +416,25 @@ tvg_status launch_instance(const DbufArgs &a, size_t lds, hipStream_t stream)
             return TVG_ERR_LAUNCH;
         configured = true;
     }
-    hipLaunchKernelGGL(kernel, dim3((unsigned)(a.mtiles * a.ntiles)), dim3(256), lds, stream, a);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(a.mtiles * a.ntiles)), dim3(NW * 64), lds, stream, a);
     return hipGetLastError() == hipSuccess ? TVG_OK : TVG_ERR_LAUNCH;
 }
 
 template <int NT, int STRIDE>
 tvg_status launch_pt(const DbufArgs &a, size_t lds, int pt, int px, hipStream_t stream)
 {
-    if (px == 2) {
-        if (pt <= 2) return launch_instance<NT, STRIDE, 2, 2>(a, lds, stream);
-        return launch_instance<NT, STRIDE, 4, 2>(a, lds, stream);
+    switch (px) {
+    case 8: return launch_instance<NT, STRIDE, 1, 8, 4>(a, lds, stream);
+    case 4:
+        if (pt <= 1) return launch_instance<NT, STRIDE, 1, 4, 4>(a, lds, stream);
+        return launch_instance<NT, STRIDE, 2, 4, 4>(a, lds, stream);
+    case 2:
+        if (pt <= 2) return launch_instance<NT, STRIDE, 2, 2, 4>(a, lds, stream);
+        return launch_instance<NT, STRIDE, 4, 2, 4>(a, lds, stream);
+    default:
+        if (pt <= 2) return launch_instance<NT, STRIDE, 2, 1, 4>(a, lds, stream);
+        return launch_instance<NT, STRIDE, 4, 1, 4>(a, lds, stream);
     }
-    if (pt <= 2) return launch_instance<NT, STRIDE, 2, 1>(a, lds, stream);
-    return launch_instance<NT, STRIDE, 4, 1>(a, lds, stream);
 }
 
 template <int NT>
@@ -378,25 +451,38 @@ tvg_status launch_stride(const DbufArgs &a, int stride, size_t lds, int pt, int 
 bool plan_conv3x3_dbuf(const ConvProblem &p, Patch3x3Plan *plan)
 {
     if (plan->mt != kMT) return false;
+    if (p.IC % (2 * kChunk) != 0) return false;      // the chunk loop runs in pairs
+    // Row pitch of the patch planes.  The 16 lanes of one LDS access read the words of 16
+    // consecutive pixels; they are conflict-free when those words are consecutive modulo 16,
+    // also across the end of an image row and of an image.  Stride 1: a pitch of W + 16 words
+    // makes the step at a row end 1 (mod 16), and xp extra words between images do the same
+    // for the step from an image's last pixel to the next image's first.  Stride 2 keeps the
+    // plain pitch (even columns, then odd columns).
     const int pwh = (p.W + 3) / 2;
-    const int pws = p.sh == 2 ? 2 * pwh : p.W + 2;
-    const int pplane = plan->rows * pws * 16;
-    int px = p.W % 2 == 0 ? 2 : 1;
-    int pt = (2 * plan->rows * (p.W / px) + 255) / 256;
-    if (px == 2 && pt > 4) { px = 1; pt = (2 * plan->rows * p.W + 255) / 256; }
-    if (pt > 4) return false;
+    const int pws = p.sh == 2 ? 2 * pwh : p.W + 16;
+    const int xp = p.sh == 2 ? 0 : ((p.H * p.W - (p.H + 2) * pws) % 16 + 16) % 16;
+    const int images = (plan->nt - 1) / (p.OH * p.OW) + 1;     // image ends a tile can span
+    const int pplane = (plan->rows * pws + images * xp) * 16;
+    // the widest load that divides a row (and an image plane: every row then starts aligned)
+    const int px = p.W % 8 == 0 ? 8 : p.W % 4 == 0 ? 4 : p.W % 2 == 0 ? 2 : 1;
+    const int pt = (2 * plan->rows * (p.W / px) + 255) / 256;
+    if (pt * (px >= 2 ? px / 2 : 1) > 4) return false;       // registers of a task's loads
     // behind the planes of a stage: 32 bytes for each of 16 lanes, where idle patch tasks store
     // (a stride-2 pair stores its two pixels pwh - 1 words apart)
-    const int dump = 512 + (p.sh == 2 ? pwh * 16 : 0);
+    const int dump = 16 * (px > 1 ? px * 16 : 32) + (p.sh == 2 ? pwh * 16 : 0);
     const int stage = 2 * kAPlane + 2 * pplane + dump;
     const size_t lds = 2 * (size_t)stage + (size_t)kMT * 8;
     // two workgroups per CU, or one per CU when the whole grid is resident at once anyway
     if (lds > 80 * 1024 && !(lds <= 160 * 1024 && plan->tiles <= kComputeUnits)) return false;
     if (plan->tiles >= (1 << 22)) return false;      // fast_div range of the tile index
     plan->dbuf = 1;
+    // (eight waves per workgroup were measured for grids of one workgroup per CU: no gain)
+    plan->nw = 4;
     plan->pt = pt;
     plan->px = px;
     plan->pplane = pplane;
+    plan->pws = pws;
+    plan->xp16 = xp * 16;
     plan->stage_bytes = stage;
     plan->lds_bytes = lds;
     return true;
@@ -414,6 +500,8 @@ tvg_status launch_conv3x3_dbuf(const ConvProblem &p, const Patch3x3Plan &plan,
     a.mtiles = (p.OC + kMT - 1) / kMT;
     a.vmode = pick_store_vmode(p.dtype, p.OH * p.OW, ptr.y, ptr.residual);
     a.pplane = plan.pplane;
+    a.pws = plan.pws;
+    a.xp16 = plan.xp16;
     a.stage_bytes = plan.stage_bytes;
     a.ss_offset = (int)(plan.lds_bytes - (size_t)kMT * 8);
     a.x_bytes = (uint32_t)((size_t)p.N * p.IC * p.H * p.W * 2);
@@ -425,8 +513,10 @@ tvg_status launch_conv3x3_dbuf(const ConvProblem &p, const Patch3x3Plan &plan,
     a.inv_ow = 1.0f / (float)p.OW;
     a.inv_vh = 1.0f / (float)(p.H + 2);
     a.inv_wpx = 1.0f / (float)(p.W / plan.px);
-    if (plan.nt == 256) return launch_stride<256>(a, p.sh, plan.lds_bytes, plan.pt, plan.px, stream);
-    if (plan.nt == 128) return launch_stride<128>(a, p.sh, plan.lds_bytes, plan.pt, plan.px, stream);
+    if (plan.nt == 256)
+        return launch_stride<256>(a, p.sh, plan.lds_bytes, plan.pt, plan.px, stream);
+    if (plan.nt == 128)
+        return launch_stride<128>(a, p.sh, plan.lds_bytes, plan.pt, plan.px, stream);
     return launch_stride<64>(a, p.sh, plan.lds_bytes, plan.pt, plan.px, stream);
 }
 
