@@ -70,29 +70,36 @@ __device__ __forceinline__ uint32_t pack_halves(uint32_t a, int ha, uint32_t b, 
     return __builtin_amdgcn_perm(b, a, sel);
 }
 
-// PT = patch load tasks per staging thread; PX = horizontally adjacent pixels per load (W must
-// be a multiple: 16- to 128-bit loads; the vector memory path is what the staging saturates,
-// and its cost is per instruction, so the widest load the row length admits is used);
-// NW = waves per workgroup.
-// NW = 4: every thread stages weights and patch; two workgroups share a CU and fill each
-// other's gaps.  NW = 8 is for grids of at most one workgroup per CU: two waves per SIMD of the
-// same workgroup fill each other's gaps instead, waves 0-3 stage the weights and waves 4-7 the
-// patch (256 threads each, as for NW = 4), and all eight run MFMAs on a quarter-size wave tile.
-template <int NT, int STRIDE, int PT, int PX, int NW>
-__global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void conv3x3_dbuf_kernel(const DbufArgs a)
+// s_waitcnt immediate for "at most vm vector-memory and lgkm LDS/scalar operations pending"
+// (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8; 63 / 15 = no wait).
+constexpr int waitcnt_imm(int vm, int lgkm)
+{
+    return (vm & 0xF) | ((vm >> 4) << 14) | (7 << 4) | (lgkm << 8);
+}
+
+// PT = patch load tasks per thread; PX = horizontally adjacent pixels per load (W must be a
+// multiple: 16- to 128-bit loads).
+//
+// What limits this kernel is the number of instructions a SIMD has to issue per MFMA, so the
+// loop body is kept to the bone: every LDS address is a register computed once per stage plus
+// an immediate, one explicit wait covers all loads of a register set, and
+// the widest load the row length admits is used.
+template <int NT, int STRIDE, int PT, int PX>
+__global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
 {
     constexpr int MT = kMT;
-    constexpr int kThreads = NW * 64;
-    constexpr int WM = NW == 8 ? 2 : (NT == 256 ? 1 : 2), WN = NW / WM;
+    constexpr int WM = NT == 256 ? 1 : 2, WN = 4 / WM;
     constexpr int WTM = MT / WM, WTN = NT / WN;
     constexpr int MI = WTM / 32, NJ = WTN / 32;
+    constexpr int PW32 = PX >= 2 ? PX / 2 : 1;        // registers per patch load
+    constexpr int kLoads = 9 + 8 * PT;                // vector memory loads per thread and chunk
+    constexpr int SB = STRIDE == 2 ? 2 : 1;           // column halves of a patch row
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WM, wn = wave / WM;
     const int lrow = lane & 31, lhalf = lane >> 5;
-    const int stid = tid & 255;            // index among the 256 threads of a staging role
 
     const int H = a.H, W = a.W, HW = H * W, OHW = a.OH * a.OW;
     const int VH = H + 2;
@@ -112,23 +119,20 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void conv3x3_dbuf_kernel(
     }
 
     // ---- weight task: one output channel, four input channels, all nine taps ----------------
-    const int w_ocl = stid >> 2, w_quad = stid & 3;
+    const int w_ocl = tid >> 2, w_quad = tid & 3;
     // rows past OC read row 0: their products land in accumulators that are never stored
     const uint32_t woff =
         2u * (uint32_t)((((m0 + w_ocl) < a.OC ? m0 + w_ocl : 0) * a.IC + w_quad * 4) * 9);
-    const int wdst = (w_quad >> 1) * kAPlane + w_ocl * 16 + (w_quad & 1) * 8;
+    // LDS byte addresses are kept per stage (index 0 / 1), so that the loop adds nothing to them
+    int wbase[2];           // where tap 0 of the weight task goes
+    wbase[0] = (w_quad >> 1) * kAPlane + w_ocl * 16 + (w_quad & 1) * 8;
+    wbase[1] = wbase[0] + stage_bytes;
 
     uint32_t goff[PT];      // byte offset of a patch task's first channel within a chunk of x
-    int loff[PT];           // byte offset of its first 16-byte word in a stage
-    // second pixel of a pair: the next word, or for stride 2 (first pixel in an odd padded
-    // column) the following even column
-    const int pair_step = STRIDE == 2 ? 16 - PWH * 16 : 16;
-    // byte offset of pixel k of a task from its first: consecutive words, or for stride 2
-    // alternating between the odd-column and the even-column half of the row
-    auto pixel_step = [&](int k) { return STRIDE == 2 ? (k & 1) * pair_step + (k >> 1) * 16 : k * 16; };
+    int pwbase[2][PT];      // where the first pixel of a patch task goes
+    int pwbase2[2][PT];     // stride 2: its second pixel (the even-column half of the row)
     // two register sets: while one is transposed into LDS (chunk c+1) the other is still in
     // flight (chunk c+2), so a load has two chunks of MFMA time to arrive
-    constexpr int PW32 = PX >= 2 ? PX / 2 : 1;        // registers per patch load
     uint32_t praw[2][PT][8][PW32];
     uint32_t wraw[2][18];
 
@@ -136,16 +140,18 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void conv3x3_dbuf_kernel(
         const_cast<bf16_t *>(a.x), 0, a.x_bytes, kRsrcFlags);
     const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<bf16_t *>(a.w), 0, a.w_bytes, kRsrcFlags);
+    const int hw2 = HW * 2;
 
     // The staging work of a chunk as a list of small items, so that it can be dealt out between
-    // the MFMAs of the previous chunk.  A register is reloaded (chunk c+2) right after the item
-    // that consumed it (chunk c+1) - with chunk c+3, the other set holding chunk c+2:
+    // the MFMAs of an earlier chunk.  A register is reloaded right after the item that consumed
+    // it (chunk c+1) - with chunk c+3, the other set holding chunk c+2:
     //   0..8    transpose filter tap i of the weights into the stage
     //   9..17   load 8 bytes of the weight row
     //   then per patch task: PX transposes (one pixel each), 8 loads (one channel each)
-    // `set` = which of the two register sets the item works on.
+    // `set` = which register set the item works on = which stage a transpose writes to;
+    // cbase = byte offset of the chunk to load within an image of x.
     constexpr int kItems = 18 + PT * (PX + 8);
-    auto work_item = [&](int it, int set, bool do_pack, bool do_load, unsigned char *dst, int c) {
+    auto work_item = [&](int it, int set, bool do_pack, bool do_load, int c, int cbase) {
         if (it < 9) {
             if (!do_pack) return;
             const int tap = it;
@@ -155,7 +161,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void conv3x3_dbuf_kernel(
                 const int e0 = (2 * q) * 9 + tap, e1 = (2 * q + 1) * 9 + tap;
                 o[q] = pack_halves(wraw[set][e0 >> 1], e0 & 1, wraw[set][e1 >> 1], e1 & 1);
             }
-            *reinterpret_cast<uint2v *>(dst + wdst + tap * MT * 16) = uint2v{o[0], o[1]};
+            *reinterpret_cast<uint2v *>(smem + wbase[set] + tap * MT * 16) = uint2v{o[0], o[1]};
         } else if (it < 18) {
             if (!do_load) return;
             const int i = it - 9;
@@ -173,12 +179,14 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void conv3x3_dbuf_kernel(
                 for (int q = 0; q < 4; ++q)
                     o[q] = pack_halves(praw[set][j][2 * q][k >> 1], k & 1,
                                        praw[set][j][2 * q + 1][k >> 1], k & 1);
-                *reinterpret_cast<uint4v *>(dst + loff[j] + pixel_step(k)) =
-                    uint4v{o[0], o[1], o[2], o[3]};
+                // consecutive words; for stride 2 alternately the odd- and the even-column half
+                unsigned char *dst = STRIDE == 2 ? smem + ((k & 1) ? pwbase2[set][j] : pwbase[set][j]) + (k >> 1) * 16
+                                                 : smem + pwbase[set][j] + k * 16;
+                *reinterpret_cast<uint4v *>(dst) = uint4v{o[0], o[1], o[2], o[3]};
             } else {
                 if (!do_load) return;
                 const int q = r - PX;
-                const int soff = (c * kChunk + q) * HW * 2;
+                const int soff = cbase + q * hw2;
                 if constexpr (PX == 8) {
                     const uint4v t4 = __builtin_bit_cast(
                         uint4v, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, goff[j], soff, 0));
@@ -197,23 +205,22 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void conv3x3_dbuf_kernel(
             }
         }
     };
-
-    // Staging roles: 0 = weights (items 0..17), 1 = patch (the rest), 2 = both.
-    const bool w_role = NW == 4 || wave < 4, p_role = NW == 4 || wave >= 4;
-    auto weight_items = [&](int set, bool do_pack, bool do_load, unsigned char *dst, int c) {
-        if (!w_role) return;
+    auto all_items = [&](int first, int last, int set, bool do_pack, bool do_load, int c) {
+        const int cbase = c * kChunk * hw2;
 #pragma unroll
-        for (int it = 0; it < 18; ++it) work_item(it, set, do_pack, do_load, dst, c);
-    };
-    auto patch_items = [&](int set, bool do_pack, bool do_load, unsigned char *dst, int c) {
-        if (!p_role) return;
-#pragma unroll
-        for (int it = 18; it < kItems; ++it) work_item(it, set, do_pack, do_load, dst, c);
+        for (int it = first; it < last; ++it) work_item(it, set, do_pack, do_load, c, cbase);
     };
 
     // The first chunk's loads go out as early as their addresses are known - the weights
     // first, they need no geometry - and the rest of the set-up runs under their latency.
-    weight_items(0, false, true, smem, 0);
+    all_items(9, 18, 0, false, true, 0);
+    // likewise the tile's per-channel multiplier and offset, needed only by the fused tail
+    float ss_scale = 0.0f, ss_shift = 0.0f, ss_bias = 0.0f;
+    if (tid < MT && m0 + tid < a.OC) {
+        ss_scale = a.scale[m0 + tid];
+        ss_shift = a.shift[m0 + tid];
+        if (a.bias) ss_bias = a.bias[m0 + tid];
+    }
 
     // ---- tile geometry (uniform values) ----------------------------------------------------
     int vr_lo, nrows, na;
@@ -231,9 +238,12 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void conv3x3_dbuf_kernel(
     {
         const int WPX = W / PX;
         const int per_octet = nrows * WPX;
+        // second pixel of a stride-2 task: first pixel in an odd padded column, the second in
+        // the following even column
+        const int pair_step = 16 - PWH * 16;
 #pragma unroll
         for (int j = 0; j < PT; ++j) {
-            const int t = stid + j * 256;
+            const int t = tid + j * 256;
             const int octet = t >= per_octet;
             const int rem = t - (octet ? per_octet : 0);
             int iw, vi;
@@ -247,28 +257,50 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void conv3x3_dbuf_kernel(
             // tasks with nothing to fetch (padding rows, past the tile) load element 0 and
             // write it to a dump area behind the planes, so that no store needs a predicate
             goff[j] = live ? 2u * (uint32_t)((n * a.IC + octet * 8) * HW + ih * W + iw) : 0u;
-            loff[j] = live ? 2 * kAPlane + octet * a.pplane + (vrow * PWS + word) * 16 + (n - na) * a.xp16
-                           : 2 * kAPlane + 2 * a.pplane + (stid & 15) * (PX > 1 ? PX * 16 : 32) +
-                                 (STRIDE == 2 && PX > 1 ? 16 - pair_step : 0);
+            pwbase[0][j] = live ? 2 * kAPlane + octet * a.pplane + (vrow * PWS + word) * 16 + (n - na) * a.xp16
+                                : 2 * kAPlane + 2 * a.pplane + (tid & 15) * (PX > 1 ? PX * 16 : 32) +
+                                      (STRIDE == 2 && PX > 1 ? 16 - pair_step : 0);
+            pwbase[1][j] = pwbase[0][j] + stage_bytes;
+            pwbase2[0][j] = pwbase[0][j] + pair_step;
+            pwbase2[1][j] = pwbase[1][j] + pair_step;
         }
     }
-    patch_items(0, false, true, smem, 0);
-    // the second chunk into the other register set (the channel count is a multiple of 32)
-    weight_items(1, false, true, smem, 1);
-    patch_items(1, false, true, smem, 1);
+    all_items(18, kItems, 0, false, true, 0);
+    // The second chunk goes into the other register set (the channel count is a multiple of
+    // 32).  A vector memory instruction takes the address unit some 60 cycles, and a wave issues
+    // in order: its loads are dealt out between the pieces of set-up arithmetic that follow,
+    // which would otherwise wait behind them.
+    constexpr int kSecond = kItems - 9;            // items 9 .. kItems-1 (transposes are skipped)
+    auto second_chunk_loads = [&](int part, int parts) {
+        __builtin_amdgcn_sched_barrier(0);
+        all_items(9 + part * kSecond / parts, 9 + (part + 1) * kSecond / parts, 1, false, true, 1);
+        __builtin_amdgcn_sched_barrier(0);
+    };
 
-    // ---- per-lane stage offsets of this lane's pixels (MFMA pixel operand) ------------------
-    int pb[NJ];
+    // ---- per-lane addresses of the MFMA operands, per stage ---------------------------------
+    // pixel operand: [stage][filter row][column half][pixel block]; a tap adds an immediate
+    int bbase[2][3][SB][NJ];
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
+        second_chunk_loads(j, NJ + 2);
         const int p = n0 + wn * WTN + j * 32 + lrow;
         int rem, ow;
         const int n = fast_div(p, OHW, a.inv_ohw, &rem);
         const int oh = fast_div(rem, a.OW, a.inv_ow, &ow);
-        pb[j] = 2 * kAPlane + lhalf * a.pplane +
-                (p < a.npix ? ((n * VH + oh * STRIDE - vr_lo) * PWS + ow) * 16 + (n - na) * a.xp16 : 0);
+        const int pb = 2 * kAPlane + lhalf * a.pplane +
+                       (p < a.npix ? ((n * VH + oh * STRIDE - vr_lo) * PWS + ow) * 16 + (n - na) * a.xp16 : 0);
+#pragma unroll
+        for (int r = 0; r < 3; ++r)
+#pragma unroll
+            for (int h = 0; h < SB; ++h) {
+                bbase[0][r][h][j] = pb + (r * PWS + h * PWH) * 16;
+                bbase[1][r][h][j] = bbase[0][r][h][j] + stage_bytes;
+            }
     }
-    const int ab = lhalf * kAPlane + (wm * WTM + lrow) * 16;
+    int abase[2];
+    abase[0] = lhalf * kAPlane + (wm * WTM + lrow) * 16;
+    abase[1] = abase[0] + stage_bytes;
+    second_chunk_loads(NJ, NJ + 2);
 
     float *ss_lds = reinterpret_cast<float *>(smem + a.ss_offset);
 
@@ -279,6 +311,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void conv3x3_dbuf_kernel(
         for (int j = 0; j < NJ; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+    second_chunk_loads(NJ + 1, NJ + 2);
 
     const int nchunks = a.IC / kChunk;
     // zero the patch planes of both stages once (padding rows and columns are never written
@@ -287,42 +320,45 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void conv3x3_dbuf_kernel(
         const int words = 2 * a.pplane / 16;
         for (int s = 0; s < 2; ++s) {
             uint4v *pz = reinterpret_cast<uint4v *>(smem + s * stage_bytes + 2 * kAPlane);
-            for (int i = tid; i < words; i += kThreads) pz[i] = uint4v{0u, 0u, 0u, 0u};
+            for (int i = tid; i < words; i += 256) pz[i] = uint4v{0u, 0u, 0u, 0u};
         }
     }
-    stage_scale_shift(ss_lds, m0, MT, a.scale, a.shift, a.bias, a.OC, tid, kThreads);
+    if (tid < MT) {
+        // (acc + bias)*scale + shift == acc*scale + (bias*scale + shift)
+        ss_lds[2 * tid] = ss_scale;
+        ss_lds[2 * tid + 1] = fmaf(ss_bias, ss_scale, ss_shift);
+    }
     __syncthreads();          // zeroing complete before the first real data lands
-    weight_items(0, true, nchunks > 2, smem, 2);
-    patch_items(0, true, nchunks > 2, smem, 2);
+    all_items(0, kItems, 0, true, nchunks > 2, 2);
     __syncthreads();
 
-    // MFMA operands are requested from LDS kDepth taps (at least four MFMAs) ahead of their use
-    constexpr int kDepth = 1, kSlots = kDepth + 1;
+    // MFMA operands are requested from LDS kDepth taps ahead of their use: measured on a lone
+    // workgroup, a tap costs an LDS round trip (some 150 cycles) unless at least that much MFMA
+    // work lies between request and use
+    constexpr int kDepth = MI * NJ >= 4 ? 2 : MI * NJ == 2 ? 3 : 4, kSlots = kDepth + 1;
     uint4v af[kSlots][MI], bf[kSlots][NJ];
-    // pws16 = bytes per patch row in a plane.  The caller hides it (and the stage pointers)
-    // from loop-invariant code motion: precomputed per-tap addresses for both stages would
-    // cost some 60 registers, one scalar and one vector add per read cost nothing.
-    auto fetch = [&](const unsigned char *st, int pws16, int tap, int slot) {
+    auto fetch = [&](int st, int tap, int slot) {
         const int r = tap / 3, s = tap - r * 3;
-        const int toff = r * pws16 + (STRIDE == 2 ? (s & 1) * (pws16 >> 1) + (s >> 1) * 16 : s * 16);
 #pragma unroll
         for (int i = 0; i < MI; ++i)
-            af[slot][i] = *reinterpret_cast<const uint4v *>(st + ab + (tap * MT + i * 32) * 16);
+            af[slot][i] = *reinterpret_cast<const uint4v *>(smem + abase[st] + (tap * MT + i * 32) * 16);
 #pragma unroll
         for (int j = 0; j < NJ; ++j)
-            bf[slot][j] = *reinterpret_cast<const uint4v *>(st + pb[j] + toff);
+            bf[slot][j] = *reinterpret_cast<const uint4v *>(
+                smem + bbase[st][r][STRIDE == 2 ? (s & 1) : 0][j] + (STRIDE == 2 ? (s >> 1) : s) * 16);
     };
-    // One filter tap of chunk c: request the next tap's operands from LDS, then this tap's
-    // MFMAs, each followed by its share of the staging items of chunks c+1 (transposes into the
-    // idle stage) and c+3 (loads into the registers just transposed): a few byte permutes, an LDS store or a few loads, which issue
-    // while the MFMA runs.  The order written here is kept: the fences stop the compiler from
-    // regrouping it.  MODE 2 = transposes and loads, 1 = transposes only, 0 = neither.
-    auto tap_step = [&](auto tapc, auto modec, auto setc, auto rolec, const unsigned char *cur_stage,
-                        unsigned char *next_stage, int pws16, int cl) {
+    // One filter tap of chunk c (stage PAR): request the operands of a later tap, then this
+    // tap's MFMAs, each followed by its share of the staging items of chunks c+1
+    // (transposes into the other stage) and c+3 (loads into the registers just transposed): a
+    // few byte permutes and an LDS store, or a few loads, which issue while the MFMA runs.  The
+    // order written here is kept: the fences stop the compiler from regrouping it.
+    // MODE 2 = transposes and loads, 1 = transposes only, 0 = neither.
+    auto tap_step = [&](auto tapc, auto modec, auto parc, int cl, int cbase) {
         constexpr int tap = decltype(tapc)::value;
         constexpr int mode = decltype(modec)::value;
+        constexpr int par = decltype(parc)::value;
         constexpr int cur = tap % kSlots, nm = MI * NJ;
-        if constexpr (tap + kDepth < 9) fetch(cur_stage, pws16, tap + kDepth, (tap + kDepth) % kSlots);
+        if constexpr (tap + kDepth < 9) fetch(par, tap + kDepth, (tap + kDepth) % kSlots);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < MI; ++i)
@@ -334,48 +370,36 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void conv3x3_dbuf_kernel(
                     acc[i][j], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
                 if (mode > 0) {
-                    constexpr int role = decltype(rolec)::value;
-                    constexpr int first = role == 1 ? 18 : 0, count = (role == 0 ? 18 : kItems) - first;
                     const int g = tap * nm + i * NJ + j;
 #pragma unroll
-                    for (int it = first + g * count / (9 * nm); it < first + (g + 1) * count / (9 * nm); ++it)
-                        work_item(it, decltype(setc)::value, true, mode == 2, next_stage, cl);
+                    for (int it = g * kItems / (9 * nm); it < (g + 1) * kItems / (9 * nm); ++it)
+                        work_item(it, par ^ 1, true, mode == 2, cl, cbase);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
     };
-    auto chunk_taps = [&](auto modec, auto setc, auto rolec, const unsigned char *cur_stage,
-                          unsigned char *next_stage, int pws16, int cl) {
-#pragma unroll
-        for (int t = 0; t < kDepth; ++t) fetch(cur_stage, pws16, t, t);
-        tap_step(std::integral_constant<int, 0>{}, modec, setc, rolec, cur_stage, next_stage, pws16, cl);
-        tap_step(std::integral_constant<int, 1>{}, modec, setc, rolec, cur_stage, next_stage, pws16, cl);
-        tap_step(std::integral_constant<int, 2>{}, modec, setc, rolec, cur_stage, next_stage, pws16, cl);
-        tap_step(std::integral_constant<int, 3>{}, modec, setc, rolec, cur_stage, next_stage, pws16, cl);
-        tap_step(std::integral_constant<int, 4>{}, modec, setc, rolec, cur_stage, next_stage, pws16, cl);
-        tap_step(std::integral_constant<int, 5>{}, modec, setc, rolec, cur_stage, next_stage, pws16, cl);
-        tap_step(std::integral_constant<int, 6>{}, modec, setc, rolec, cur_stage, next_stage, pws16, cl);
-        tap_step(std::integral_constant<int, 7>{}, modec, setc, rolec, cur_stage, next_stage, pws16, cl);
-        tap_step(std::integral_constant<int, 8>{}, modec, setc, rolec, cur_stage, next_stage, pws16, cl);
-    };
-
     // Chunk c of parity PAR reads stage PAR, transposes register set PAR^1 (chunk c+1) into
     // stage PAR^1 and reloads that set with chunk c+3.
     auto chunk = [&](auto parc, auto modec, int c) {
         constexpr int par = decltype(parc)::value;
-        int so = par * stage_bytes, pws16 = PWS * 16;
-        asm volatile("" : "+s"(so), "+s"(pws16));
-        using Set = std::integral_constant<int, par ^ 1>;
-        if constexpr (NW == 4)
-            chunk_taps(modec, Set{}, std::integral_constant<int, 2>{}, smem + so,
-                       smem + (stage_bytes - so), pws16, c + 3);
-        else if (wave < 4)
-            chunk_taps(modec, Set{}, std::integral_constant<int, 0>{}, smem + so,
-                       smem + (stage_bytes - so), pws16, c + 3);
-        else
-            chunk_taps(modec, Set{}, std::integral_constant<int, 1>{}, smem + so,
-                       smem + (stage_bytes - so), pws16, c + 3);
-        if constexpr (decltype(modec)::value > 0) __syncthreads();
+        constexpr int mode = decltype(modec)::value;
+        const int cbase = (c + 3) * kChunk * hw2;
+#pragma unroll
+        for (int t = 0; t < kDepth; ++t) fetch(par, t, t);
+        // The set to transpose was loaded two chunks ago; only the other set's loads (issued
+        // during the previous chunk) may still be in flight.  One wait instead of one per
+        // register.  (Where fewer loads are pending, the compiler's own waits take over.)
+        if constexpr (mode > 0) __builtin_amdgcn_s_waitcnt(waitcnt_imm(kLoads, 15));
+        tap_step(std::integral_constant<int, 0>{}, modec, parc, c + 3, cbase);
+        tap_step(std::integral_constant<int, 1>{}, modec, parc, c + 3, cbase);
+        tap_step(std::integral_constant<int, 2>{}, modec, parc, c + 3, cbase);
+        tap_step(std::integral_constant<int, 3>{}, modec, parc, c + 3, cbase);
+        tap_step(std::integral_constant<int, 4>{}, modec, parc, c + 3, cbase);
+        tap_step(std::integral_constant<int, 5>{}, modec, parc, c + 3, cbase);
+        tap_step(std::integral_constant<int, 6>{}, modec, parc, c + 3, cbase);
+        tap_step(std::integral_constant<int, 7>{}, modec, parc, c + 3, cbase);
+        tap_step(std::integral_constant<int, 8>{}, modec, parc, c + 3, cbase);
+        if constexpr (mode > 0) __syncthreads();
     };
     using P0 = std::integral_constant<int, 0>;
     using P1 = std::integral_constant<int, 1>;
@@ -405,10 +429,10 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 1 : 2) void conv3x3_dbuf_kernel(
                                     ss_lds, wm * WTM);
 }
 
-template <int NT, int STRIDE, int PT, int PX, int NW>
+template <int NT, int STRIDE, int PT, int PX>
 tvg_status launch_instance(const DbufArgs &a, size_t lds, hipStream_t stream)
 {
-    auto kernel = conv3x3_dbuf_kernel<NT, STRIDE, PT, PX, NW>;
+    auto kernel = conv3x3_dbuf_kernel<NT, STRIDE, PT, PX>;
     static bool configured = false;      // opt in to > 64 KB of dynamic LDS once per instance
     if (!configured) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
@@ -416,7 +440,7 @@ tvg_status launch_instance(const DbufArgs &a, size_t lds, hipStream_t stream)
             return TVG_ERR_LAUNCH;
         configured = true;
     }
-    hipLaunchKernelGGL(kernel, dim3((unsigned)(a.mtiles * a.ntiles)), dim3(NW * 64), lds, stream, a);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(a.mtiles * a.ntiles)), dim3(256), lds, stream, a);
     return hipGetLastError() == hipSuccess ? TVG_OK : TVG_ERR_LAUNCH;
 }
 
@@ -424,16 +448,16 @@ template <int NT, int STRIDE>
 tvg_status launch_pt(const DbufArgs &a, size_t lds, int pt, int px, hipStream_t stream)
 {
     switch (px) {
-    case 8: return launch_instance<NT, STRIDE, 1, 8, 4>(a, lds, stream);
+    case 8: return launch_instance<NT, STRIDE, 1, 8>(a, lds, stream);
     case 4:
-        if (pt <= 1) return launch_instance<NT, STRIDE, 1, 4, 4>(a, lds, stream);
-        return launch_instance<NT, STRIDE, 2, 4, 4>(a, lds, stream);
+        if (pt <= 1) return launch_instance<NT, STRIDE, 1, 4>(a, lds, stream);
+        return launch_instance<NT, STRIDE, 2, 4>(a, lds, stream);
     case 2:
-        if (pt <= 2) return launch_instance<NT, STRIDE, 2, 2, 4>(a, lds, stream);
-        return launch_instance<NT, STRIDE, 4, 2, 4>(a, lds, stream);
+        if (pt <= 2) return launch_instance<NT, STRIDE, 2, 2>(a, lds, stream);
+        return launch_instance<NT, STRIDE, 4, 2>(a, lds, stream);
     default:
-        if (pt <= 2) return launch_instance<NT, STRIDE, 2, 1, 4>(a, lds, stream);
-        return launch_instance<NT, STRIDE, 4, 1, 4>(a, lds, stream);
+        if (pt <= 2) return launch_instance<NT, STRIDE, 2, 1>(a, lds, stream);
+        return launch_instance<NT, STRIDE, 4, 1>(a, lds, stream);
     }
 }
 
@@ -452,17 +476,22 @@ bool plan_conv3x3_dbuf(const ConvProblem &p, Patch3x3Plan *plan)
 {
     if (plan->mt != kMT) return false;
     if (p.IC % (2 * kChunk) != 0) return false;      // the chunk loop runs in pairs
+    // Measured at batch 64: with fewer than eight chunks the deeper pipeline's longer start-up
+    // (three chunks in flight before the first MFMA) costs more than the loop gains, and
+    // stride-2 patches are too large for two stages to pay.
+    if (p.sh != 1 || p.IC < 8 * kChunk) return false;
     // Row pitch of the patch planes.  The 16 lanes of one LDS access read the words of 16
     // consecutive pixels; they are conflict-free when those words are consecutive modulo 16,
     // also across the end of an image row and of an image.  Stride 1: a pitch of W + 16 words
     // makes the step at a row end 1 (mod 16), and xp extra words between images do the same
     // for the step from an image's last pixel to the next image's first.  Stride 2 keeps the
-    // plain pitch (even columns, then odd columns).
+    // plain pitch (even columns, then odd columns); so does stride 1 when the padded planes
+    // would cost the second workgroup per CU.
     const int pwh = (p.W + 3) / 2;
-    const int pws = p.sh == 2 ? 2 * pwh : p.W + 16;
-    const int xp = p.sh == 2 ? 0 : ((p.H * p.W - (p.H + 2) * pws) % 16 + 16) % 16;
     const int images = (plan->nt - 1) / (p.OH * p.OW) + 1;     // image ends a tile can span
-    const int pplane = (plan->rows * pws + images * xp) * 16;
+    int pws = p.sh == 2 ? 2 * pwh : p.W + 16;
+    int xp = p.sh == 2 ? 0 : ((p.H * p.W - (p.H + 2) * pws) % 16 + 16) % 16;
+    int pplane = (plan->rows * pws + images * xp) * 16;
     // the widest load that divides a row (and an image plane: every row then starts aligned)
     const int px = p.W % 8 == 0 ? 8 : p.W % 4 == 0 ? 4 : p.W % 2 == 0 ? 2 : 1;
     const int pt = (2 * plan->rows * (p.W / px) + 255) / 256;
@@ -470,14 +499,19 @@ bool plan_conv3x3_dbuf(const ConvProblem &p, Patch3x3Plan *plan)
     // behind the planes of a stage: 32 bytes for each of 16 lanes, where idle patch tasks store
     // (a stride-2 pair stores its two pixels pwh - 1 words apart)
     const int dump = 16 * (px > 1 ? px * 16 : 32) + (p.sh == 2 ? pwh * 16 : 0);
-    const int stage = 2 * kAPlane + 2 * pplane + dump;
-    const size_t lds = 2 * (size_t)stage + (size_t)kMT * 8;
+    int stage = 2 * kAPlane + 2 * pplane + dump;
+    size_t lds = 2 * (size_t)stage + (size_t)kMT * 8;
+    if (lds > 80 * 1024 && p.sh == 1) {
+        pws = p.W + 2;
+        xp = 0;
+        pplane = plan->rows * pws * 16;
+        stage = 2 * kAPlane + 2 * pplane + dump;
+        lds = 2 * (size_t)stage + (size_t)kMT * 8;
+    }
     // two workgroups per CU, or one per CU when the whole grid is resident at once anyway
     if (lds > 80 * 1024 && !(lds <= 160 * 1024 && plan->tiles <= kComputeUnits)) return false;
     if (plan->tiles >= (1 << 22)) return false;      // fast_div range of the tile index
     plan->dbuf = 1;
-    // (eight waves per workgroup were measured for grids of one workgroup per CU: no gain)
-    plan->nw = 4;
     plan->pt = pt;
     plan->px = px;
     plan->pplane = pplane;

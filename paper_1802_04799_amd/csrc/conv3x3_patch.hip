@@ -396,7 +396,7 @@ bool plan_conv3x3_patch(const ConvProblem &p, Patch3x3Plan *plan)
         const size_t lds = (size_t)9 * mt * kPosBytes + (size_t)rows * (p.W + 2) * kPosBytes +
                            (size_t)mt * 8;      // operands + (scale, offset) pairs
         const long tiles = (long)((p.OC + mt - 1) / mt) * ((p.npix + nt - 1) / nt);
-        Patch3x3Plan cand{mt, nt, pt, px, rows, lds, tiles, 0, 0, 0, 0, 0, 4};
+        Patch3x3Plan cand{mt, nt, pt, px, rows, lds, tiles, 0, 0, 0, 0, 0};
         if (!(use_dbuf && plan_conv3x3_dbuf(p, &cand))) {
             if (pt > 8 || lds > 80 * 1024) continue;
             if (mt == 128 && pt > 4 && !force_mt) continue;

@@ -54,7 +54,6 @@ struct Patch3x3Plan {
     int pplane;         // its bytes per channel-octet plane of the patch
     int stage_bytes;    // its bytes per LDS stage
     int pws, xp16;      // its patch row pitch (16-byte words) and extra bytes between images
-    int nw;             // its waves per workgroup (4 or 8)
 };
 
 // True when the problem is one the patch kernel is built for (bf16, 3x3, pad 1,
