@@ -38,6 +38,9 @@ def parse():
     ap.add_argument("--skip-cpu", action="store_true", help="do not time the CPU oracle")
     ap.add_argument("--only", default="", help="comma-separated layer names (C1..C12): restrict "
                     "the step to these layers (for profiler runs)")
+    ap.add_argument("--depthwise-probe", action="store_true",
+                    help="only launch the depthwise layers D1..D9 at batch 64 --steps times each "
+                         "(for profiler runs)")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
                     help="only run a plain device copy of this many MiB --steps times "
                          "(reference for scaling FETCH_SIZE / WRITE_SIZE counters)")
@@ -111,14 +114,24 @@ def main():
     # ---------------------------------------------------------------- the timed region
     if args.copy_probe:
         return copy_probe(torch, args)
+    if args.depthwise_probe:
+        for i, sh in enumerate(ti.mobilenet_depthwise(64)):
+            l = Layer(sh, ti.layer_seed(3, 100 + i), "f32", depthwise=True, copies=2)
+            for k in range(args.warmup + args.steps):
+                l.launch(k & 1)
+            torch.cuda.synchronize()
+            del l
+        print(json.dumps({"depthwise_probe": "D1..D9 batch 64 fp32", "launches_each": args.warmup + args.steps}))
+        return
     shapes = ti.resnet18_convs(64)
     layers = [Layer(sh, ti.layer_seed(4, i), "bf16") for i, sh in enumerate(shapes)]
     if args.only:
         keep = set(args.only.split(","))
         layers = [l for l in layers if l.sh.name in keep]
-    # The twelve layers are independent; they are launched with the seven 3x3 layers (one
-    # kernel: conv3x3_patch_kernel, the largest share of the step) last and back to back, so
-    # that two events per step bracket exactly that kernel's launches.
+    # The twelve layers are independent; they are launched with the seven 3x3 layers (the
+    # LDS-patch implicit-GEMM kernels conv3x3_patch_kernel and conv3x3_dbuf_kernel, together the
+    # largest share of the step) last and back to back, so that two events per step bracket
+    # exactly those launches.
     is_dom = lambda l: l.sh.r == 3
     layers = [l for l in layers if not is_dom(l)] + [l for l in layers if is_dom(l)]
     n_dom = sum(1 for l in layers if is_dom(l))
@@ -183,8 +196,8 @@ def main():
         dom_tf = dom_flops / (dom_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": round(dom_tf, 2), "peak": PEAK_BF16_TFLOPS,
                     "unit": "TFLOP/s", "frac": round(dom_tf / PEAK_BF16_TFLOPS, 4),
-                    "traffic": measured_traffic("conv3x3_patch_kernel"),
-                    "kernel": "conv3x3_patch_kernel<bf16>",
+                    "traffic": measured_traffic("conv3x3_kernels"),
+                    "kernel": "conv3x3_patch_kernel + conv3x3_dbuf_kernel (bf16 3x3 implicit GEMM)",
                     "launches_per_step": n_dom,
                     "layers": [l.sh.name for l in layers if is_dom(l)],
                     "flops_per_launch": dom_flops / n_dom,
