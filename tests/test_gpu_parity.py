@@ -154,6 +154,45 @@ def test_bf16_3x3_patch_kernel_ragged_shapes_all_tiles(tvg, monkeypatch, cfg, ti
     assert rel_err(to_host(y), oracle_dense(sh, inp)) <= TOL["bf16"]
 
 
+DBUF_SHAPES = [
+    # bf16 3x3 pad-1 stride-1 problems with IC % 32 == 0 and IC >= 128 (the software-pipelined
+    # kernel): n, ic, h, w, oc.  Row lengths that are multiples of 8, 4, 2 and odd (16- to
+    # 2-byte loads), images smaller than a tile, ragged channel and pixel tails, one-pixel rows.
+    (1, 128, 1, 1, 64), (3, 128, 7, 7, 130), (2, 160, 9, 11, 40), (1, 128, 30, 70, 16),
+    (2, 128, 8, 8, 64), (5, 192, 12, 12, 96), (1, 256, 33, 40, 72), (40, 128, 7, 7, 64),
+    (2, 128, 3, 1, 64), (1, 128, 2, 64, 200), (3, 128, 5, 6, 8), (1, 512, 7, 7, 64),
+    (2, 128, 56, 56, 64), (70, 128, 3, 3, 64),
+]
+
+
+@pytest.mark.parametrize("tile", ["", "64,256", "64,128", "64,64"])
+@pytest.mark.parametrize("cfg", DBUF_SHAPES)
+def test_bf16_3x3_pipelined_kernel_shapes_all_tiles(tvg, monkeypatch, cfg, tile):
+    """The two-stage 3x3 kernel under every pixel-tile width, with bias, residual and ReLU."""
+    n, ic, h, w, oc = cfg
+    if tile:
+        monkeypatch.setenv("TVG_FORCE_TILE", tile)
+    else:
+        monkeypatch.delenv("TVG_FORCE_TILE", raising=False)
+    sh = ti.ConvShape("db3", n, ic, h, w, oc, 3, 3, 1, 1)
+    inp = ti.make_inputs(sh, 12000 + sum(cfg), "bf16", residual=True, bias=True)
+    y = run_dense(tvg, sh, inp, "bf16")
+    assert rel_err(to_host(y), oracle_dense(sh, inp)) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("cfg", [(2, 128, 8, 8, 64), (3, 128, 7, 7, 130), (1, 256, 33, 40, 72)])
+def test_bf16_3x3_pipelined_kernel_plain_tail_and_determinism(tvg, cfg):
+    """No bias, no residual, no ReLU (negative outputs survive), and bit-identical reruns."""
+    n, ic, h, w, oc = cfg
+    sh = ti.ConvShape("db3", n, ic, h, w, oc, 3, 3, 1, 1)
+    inp = ti.make_inputs(sh, 13000 + sum(cfg), "bf16", residual=False, bias=False)
+    y1 = to_host(run_dense(tvg, sh, inp, "bf16", relu=False))
+    y2 = to_host(run_dense(tvg, sh, inp, "bf16", relu=False))
+    assert np.array_equal(y1, y2)
+    assert rel_err(y1, oracle_dense(sh, inp, relu=False)) <= TOL["bf16"]
+    assert (y1 < 0).any()
+
+
 PATCH_WIDE = [
     # bf16 3x3 pad-1 problems with 64 or more input channels: n, ic, h, w, oc, stride
     (2, 64, 9, 11, 40, 1), (3, 64, 10, 13, 70, 2), (5, 96, 7, 7, 130, 1), (2, 128, 14, 14, 256, 1),
