@@ -84,13 +84,18 @@ constexpr int waitcnt_imm(int vm, int lgkm)
 // loop body is kept to the bone: every LDS address is a register computed once per stage plus
 // an immediate, one explicit wait covers all loads of a register set, and
 // the widest load the row length admits is used.
-template <int NT, int STRIDE, int PT, int PX>
+//
+// WM = waves along the 64 output channels (1 or 2), NJ = 32-pixel blocks per wave: the tile is
+// 64 x NT with NT = (4 / WM) * NJ * 32.  (Tiles of 448 and 832 pixels - one workgroup per CU with
+// 112 or 208 accumulator registers per lane - were measured: slower, a single wave per SIMD
+// issues an MFMA plus its LDS operand read in 27 ns against 16 ns for two waves.)
+template <int WM, int NJ, int STRIDE, int PT, int PX>
 __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
 {
     constexpr int MT = kMT;
-    constexpr int WM = NT == 256 ? 1 : 2, WN = 4 / WM;
-    constexpr int WTM = MT / WM, WTN = NT / WN;
-    constexpr int MI = WTM / 32, NJ = WTN / 32;
+    constexpr int WN = 4 / WM;
+    constexpr int WTM = MT / WM, WTN = NJ * 32, NT = WN * WTN;
+    constexpr int MI = WTM / 32;
     constexpr int PW32 = PX >= 2 ? PX / 2 : 1;        // registers per patch load
     constexpr int kLoads = 9 + 8 * PT;                // vector memory loads per thread and chunk
     constexpr int SB = STRIDE == 2 ? 2 : 1;           // column halves of a patch row
@@ -151,7 +156,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
     // `set` = which register set the item works on = which stage a transpose writes to;
     // cbase = byte offset of the chunk to load within an image of x.
     constexpr int kItems = 18 + PT * (PX + 8);
-    auto work_item = [&](int it, int set, bool do_pack, bool do_load, int c, int cbase) {
+    auto work_item = [&](int it, int set, bool do_pack, bool do_load, int c, int cbase) __attribute__((always_inline)) {
         if (it < 9) {
             if (!do_pack) return;
             const int tap = it;
@@ -205,7 +210,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
             }
         }
     };
-    auto all_items = [&](int first, int last, int set, bool do_pack, bool do_load, int c) {
+    auto all_items = [&](int first, int last, int set, bool do_pack, bool do_load, int c) __attribute__((always_inline)) {
         const int cbase = c * kChunk * hw2;
 #pragma unroll
         for (int it = first; it < last; ++it) work_item(it, set, do_pack, do_load, c, cbase);
@@ -271,36 +276,31 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
     // in order: its loads are dealt out between the pieces of set-up arithmetic that follow,
     // which would otherwise wait behind them.
     constexpr int kSecond = kItems - 9;            // items 9 .. kItems-1 (transposes are skipped)
-    auto second_chunk_loads = [&](int part, int parts) {
+    auto second_chunk_loads = [&](int part, int parts) __attribute__((always_inline)) {
         __builtin_amdgcn_sched_barrier(0);
         all_items(9 + part * kSecond / parts, 9 + (part + 1) * kSecond / parts, 1, false, true, 1);
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    // ---- per-lane addresses of the MFMA operands, per stage ---------------------------------
-    // pixel operand: [stage][filter row][column half][pixel block]; a tap adds an immediate
-    int bbase[2][3][SB][NJ];
+    // ---- per-lane addresses of the MFMA operands --------------------------------------------
+    // pixel operand: the word of filter row 0, column 0 of pixel block j in this lane's octet
+    // plane of stage 0; stage, filter row (uniform values) and column (an immediate) are added
+    // at the read - one vector add per read is free, a register per combination is not
+    int bpix[NJ];
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
-        second_chunk_loads(j, NJ + 2);
+        if (j < 4) second_chunk_loads(j, NJ < 4 ? NJ + 2 : 6);
         const int p = n0 + wn * WTN + j * 32 + lrow;
         int rem, ow;
         const int n = fast_div(p, OHW, a.inv_ohw, &rem);
         const int oh = fast_div(rem, a.OW, a.inv_ow, &ow);
-        const int pb = 2 * kAPlane + lhalf * a.pplane +
-                       (p < a.npix ? ((n * VH + oh * STRIDE - vr_lo) * PWS + ow) * 16 + (n - na) * a.xp16 : 0);
-#pragma unroll
-        for (int r = 0; r < 3; ++r)
-#pragma unroll
-            for (int h = 0; h < SB; ++h) {
-                bbase[0][r][h][j] = pb + (r * PWS + h * PWH) * 16;
-                bbase[1][r][h][j] = bbase[0][r][h][j] + stage_bytes;
-            }
+        bpix[j] = 2 * kAPlane + lhalf * a.pplane +
+                  (p < a.npix ? ((n * VH + oh * STRIDE - vr_lo) * PWS + ow) * 16 + (n - na) * a.xp16 : 0);
     }
     int abase[2];
     abase[0] = lhalf * kAPlane + (wm * WTM + lrow) * 16;
     abase[1] = abase[0] + stage_bytes;
-    second_chunk_loads(NJ, NJ + 2);
+    second_chunk_loads(NJ < 4 ? NJ : 4, NJ < 4 ? NJ + 2 : 6);
 
     float *ss_lds = reinterpret_cast<float *>(smem + a.ss_offset);
 
@@ -311,7 +311,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
         for (int j = 0; j < NJ; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-    second_chunk_loads(NJ + 1, NJ + 2);
+    second_chunk_loads(NJ < 4 ? NJ + 1 : 5, NJ < 4 ? NJ + 2 : 6);
 
     const int nchunks = a.IC / kChunk;
     // zero the patch planes of both stages once (padding rows and columns are never written
@@ -332,73 +332,83 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
     all_items(0, kItems, 0, true, nchunks > 2, 2);
     __syncthreads();
 
-    // MFMA operands are requested from LDS kDepth taps ahead of their use: measured on a lone
-    // workgroup, a tap costs an LDS round trip (some 150 cycles) unless at least that much MFMA
-    // work lies between request and use
-    constexpr int kDepth = MI * NJ >= 4 ? 2 : MI * NJ == 2 ? 3 : 4, kSlots = kDepth + 1;
-    uint4v af[kSlots][MI], bf[kSlots][NJ];
-    auto fetch = [&](int st, int tap, int slot) {
-        const int r = tap / 3, s = tap - r * 3;
+    // MFMA operands are requested from LDS ahead of their use: the weight operands of tap t+1
+    // before the MFMAs of tap t, the pixel operands (one per 32-pixel block and tap, in the
+    // order of use) kAhead operands ahead through a ring of registers.
+    constexpr int kAhead = 4, kRing = kAhead + 1, kSeq = 9 * NJ;
+    uint4v af[2][MI], bfr[kRing];
+    auto fetch_a = [&](int st, int tap, int slot) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < MI; ++i)
             af[slot][i] = *reinterpret_cast<const uint4v *>(smem + abase[st] + (tap * MT + i * 32) * 16);
-#pragma unroll
-        for (int j = 0; j < NJ; ++j)
-            bf[slot][j] = *reinterpret_cast<const uint4v *>(
-                smem + bbase[st][r][STRIDE == 2 ? (s & 1) : 0][j] + (STRIDE == 2 ? (s >> 1) : s) * 16);
     };
-    // One filter tap of chunk c (stage PAR): request the operands of a later tap, then this
-    // tap's MFMAs, each followed by its share of the staging items of chunks c+1
-    // (transposes into the other stage) and c+3 (loads into the registers just transposed): a
-    // few byte permutes and an LDS store, or a few loads, which issue while the MFMA runs.  The
-    // order written here is kept: the fences stop the compiler from regrouping it.
+    // q = tap * NJ + block; rowoff[r] = stage offset + filter row r (uniform)
+    auto fetch_b = [&](const int (&rowoff)[3], int q) __attribute__((always_inline)) {
+        const int tap = q / NJ, j = q % NJ, r = tap / 3, s = tap - r * 3;
+        bfr[q % kRing] = *reinterpret_cast<const uint4v *>(
+            smem + bpix[j] + rowoff[r] + (STRIDE == 2 ? (s & 1) * PWH * 16 + (s >> 1) * 16 : s * 16));
+    };
+    // One filter tap of chunk c (stage PAR): request later operands, then this tap's MFMAs, each
+    // followed by its share of the staging items of chunks c+1 (transposes into the other
+    // stage) and c+3 (loads into the registers just transposed): a few byte permutes and an LDS
+    // store, or a few loads, which issue while the MFMA runs.  The order written here is kept:
+    // the fences stop the compiler from regrouping it.
     // MODE 2 = transposes and loads, 1 = transposes only, 0 = neither.
-    auto tap_step = [&](auto tapc, auto modec, auto parc, int cl, int cbase) {
+    auto tap_step = [&](auto tapc, auto modec, auto parc, const int (&rowoff)[3], int cl, int cbase) __attribute__((always_inline)) {
         constexpr int tap = decltype(tapc)::value;
         constexpr int mode = decltype(modec)::value;
         constexpr int par = decltype(parc)::value;
-        constexpr int cur = tap % kSlots, nm = MI * NJ;
-        if constexpr (tap + kDepth < 9) fetch(par, tap + kDepth, (tap + kDepth) % kSlots);
-        __builtin_amdgcn_sched_barrier(0);
+        constexpr int nm = MI * NJ;
+        if constexpr (tap + 1 < 9) fetch_a(par, tap + 1, (tap + 1) & 1);
 #pragma unroll
-        for (int i = 0; i < MI; ++i)
+        for (int j = 0; j < NJ; ++j) {
+            const int q = tap * NJ + j;
+            if (q + kAhead < kSeq) fetch_b(rowoff, q + kAhead);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int j = 0; j < NJ; ++j) {
+            for (int i = 0; i < MI; ++i) {
                 // pixel operand first: the accumulator tile is D[pixel][channel]
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                    __builtin_bit_cast(bf16x8v, bf[cur][j]), __builtin_bit_cast(bf16x8v, af[cur][i]),
-                    acc[i][j], 0, 0, 0);
+                    __builtin_bit_cast(bf16x8v, bfr[q % kRing]),
+                    __builtin_bit_cast(bf16x8v, af[tap & 1][i]), acc[i][j], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
                 if (mode > 0) {
-                    const int g = tap * nm + i * NJ + j;
+                    const int g = tap * nm + j * MI + i;
 #pragma unroll
                     for (int it = g * kItems / (9 * nm); it < (g + 1) * kItems / (9 * nm); ++it)
                         work_item(it, par ^ 1, true, mode == 2, cl, cbase);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
+        }
     };
     // Chunk c of parity PAR reads stage PAR, transposes register set PAR^1 (chunk c+1) into
     // stage PAR^1 and reloads that set with chunk c+3.
-    auto chunk = [&](auto parc, auto modec, int c) {
+    auto chunk = [&](auto parc, auto modec, int c) __attribute__((always_inline)) {
         constexpr int par = decltype(parc)::value;
         constexpr int mode = decltype(modec)::value;
         const int cbase = (c + 3) * kChunk * hw2;
+        // (hidden from loop-invariant code motion, which would spend a register per
+        // combination of stage, filter row and pixel block on precomputed addresses)
+        int so = par * stage_bytes;
+        asm volatile("" : "+s"(so));
+        const int rowoff[3] = {so, so + PWS * 16, so + 2 * PWS * 16};
+        fetch_a(par, 0, 0);
 #pragma unroll
-        for (int t = 0; t < kDepth; ++t) fetch(par, t, t);
+        for (int q = 0; q < kAhead && q < kSeq; ++q) fetch_b(rowoff, q);
         // The set to transpose was loaded two chunks ago; only the other set's loads (issued
         // during the previous chunk) may still be in flight.  One wait instead of one per
         // register.  (Where fewer loads are pending, the compiler's own waits take over.)
         if constexpr (mode > 0) __builtin_amdgcn_s_waitcnt(waitcnt_imm(kLoads, 15));
-        tap_step(std::integral_constant<int, 0>{}, modec, parc, c + 3, cbase);
-        tap_step(std::integral_constant<int, 1>{}, modec, parc, c + 3, cbase);
-        tap_step(std::integral_constant<int, 2>{}, modec, parc, c + 3, cbase);
-        tap_step(std::integral_constant<int, 3>{}, modec, parc, c + 3, cbase);
-        tap_step(std::integral_constant<int, 4>{}, modec, parc, c + 3, cbase);
-        tap_step(std::integral_constant<int, 5>{}, modec, parc, c + 3, cbase);
-        tap_step(std::integral_constant<int, 6>{}, modec, parc, c + 3, cbase);
-        tap_step(std::integral_constant<int, 7>{}, modec, parc, c + 3, cbase);
-        tap_step(std::integral_constant<int, 8>{}, modec, parc, c + 3, cbase);
+        tap_step(std::integral_constant<int, 0>{}, modec, parc, rowoff, c + 3, cbase);
+        tap_step(std::integral_constant<int, 1>{}, modec, parc, rowoff, c + 3, cbase);
+        tap_step(std::integral_constant<int, 2>{}, modec, parc, rowoff, c + 3, cbase);
+        tap_step(std::integral_constant<int, 3>{}, modec, parc, rowoff, c + 3, cbase);
+        tap_step(std::integral_constant<int, 4>{}, modec, parc, rowoff, c + 3, cbase);
+        tap_step(std::integral_constant<int, 5>{}, modec, parc, rowoff, c + 3, cbase);
+        tap_step(std::integral_constant<int, 6>{}, modec, parc, rowoff, c + 3, cbase);
+        tap_step(std::integral_constant<int, 7>{}, modec, parc, rowoff, c + 3, cbase);
+        tap_step(std::integral_constant<int, 8>{}, modec, parc, rowoff, c + 3, cbase);
         if constexpr (mode > 0) __syncthreads();
     };
     using P0 = std::integral_constant<int, 0>;
@@ -423,16 +433,17 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
 
     // ---- fused tail: per-wave staging in LDS, vector stores --------------------------------
     __syncthreads();                       // every wave is done reading the operand tiles
-    unsigned char *stage = smem + wave * (MI * NJ * kStageBytes);   // <= 40 KB < two stages
+    constexpr int BT = MI * NJ < 4 ? MI * NJ : 4;                 // tiles staged at a time
+    unsigned char *stage = smem + wave * (BT * kStageBytes);      // <= 40 KB < two stages
     const TailArgs tail{a.scale, a.shift, a.bias, a.residual, a.y, a.OC, OHW, a.npix, a.relu};
-    store_acc_tiles_batched<MI, NJ>(acc, stage, lane, m0 + wm * WTM, n0 + wn * WTN, tail, a.vmode,
-                                    ss_lds, wm * WTM);
+    store_acc_tiles_batched<MI, NJ, BT>(acc, stage, lane, m0 + wm * WTM, n0 + wn * WTN, tail,
+                                        a.vmode, ss_lds, wm * WTM);
 }
 
-template <int NT, int STRIDE, int PT, int PX>
+template <int WM, int NJ, int PT, int PX>
 tvg_status launch_instance(const DbufArgs &a, size_t lds, hipStream_t stream)
 {
-    auto kernel = conv3x3_dbuf_kernel<NT, STRIDE, PT, PX>;
+    auto kernel = conv3x3_dbuf_kernel<WM, NJ, 1, PT, PX>;
     static bool configured = false;      // opt in to > 64 KB of dynamic LDS once per instance
     if (!configured) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
@@ -444,28 +455,21 @@ tvg_status launch_instance(const DbufArgs &a, size_t lds, hipStream_t stream)
     return hipGetLastError() == hipSuccess ? TVG_OK : TVG_ERR_LAUNCH;
 }
 
-template <int NT, int STRIDE>
+template <int WM, int NJ>
 tvg_status launch_pt(const DbufArgs &a, size_t lds, int pt, int px, hipStream_t stream)
 {
     switch (px) {
-    case 8: return launch_instance<NT, STRIDE, 1, 8>(a, lds, stream);
+    case 8: return launch_instance<WM, NJ, 1, 8>(a, lds, stream);
     case 4:
-        if (pt <= 1) return launch_instance<NT, STRIDE, 1, 4>(a, lds, stream);
-        return launch_instance<NT, STRIDE, 2, 4>(a, lds, stream);
+        if (pt <= 1) return launch_instance<WM, NJ, 1, 4>(a, lds, stream);
+        return launch_instance<WM, NJ, 2, 4>(a, lds, stream);
     case 2:
-        if (pt <= 2) return launch_instance<NT, STRIDE, 2, 2>(a, lds, stream);
-        return launch_instance<NT, STRIDE, 4, 2>(a, lds, stream);
+        if (pt <= 2) return launch_instance<WM, NJ, 2, 2>(a, lds, stream);
+        return launch_instance<WM, NJ, 4, 2>(a, lds, stream);
     default:
-        if (pt <= 2) return launch_instance<NT, STRIDE, 2, 1>(a, lds, stream);
-        return launch_instance<NT, STRIDE, 4, 1>(a, lds, stream);
+        if (pt <= 2) return launch_instance<WM, NJ, 2, 1>(a, lds, stream);
+        return launch_instance<WM, NJ, 4, 1>(a, lds, stream);
     }
-}
-
-template <int NT>
-tvg_status launch_stride(const DbufArgs &a, int stride, size_t lds, int pt, int px, hipStream_t stream)
-{
-    return stride == 1 ? launch_pt<NT, 1>(a, lds, pt, px, stream)
-                       : launch_pt<NT, 2>(a, lds, pt, px, stream);
 }
 
 }  // namespace
@@ -476,10 +480,10 @@ bool plan_conv3x3_dbuf(const ConvProblem &p, Patch3x3Plan *plan)
 {
     if (plan->mt != kMT) return false;
     if (p.IC % (2 * kChunk) != 0) return false;      // the chunk loop runs in pairs
-    // Measured at batch 64: with fewer than eight chunks the deeper pipeline's longer start-up
-    // (three chunks in flight before the first MFMA) costs more than the loop gains, and
-    // stride-2 patches are too large for two stages to pay.
-    if (p.sh != 1 || p.IC < 8 * kChunk) return false;
+    // Measured at batch 64: stride-2 patches are too large for two stages to pay, and with
+    // fewer than eight chunks the deeper pipeline's longer start-up (three chunks in flight
+    // before the first MFMA) costs more than the loop gains.
+    if (p.sh != 1 || p.IC < 8 * kChunk || plan->nt > 256) return false;
     // Row pitch of the patch planes.  The 16 lanes of one LDS access read the words of 16
     // consecutive pixels; they are conflict-free when those words are consecutive modulo 16,
     // also across the end of an image row and of an image.  Stride 1: a pitch of W + 16 words
@@ -547,11 +551,11 @@ tvg_status launch_conv3x3_dbuf(const ConvProblem &p, const Patch3x3Plan &plan,
     a.inv_ow = 1.0f / (float)p.OW;
     a.inv_vh = 1.0f / (float)(p.H + 2);
     a.inv_wpx = 1.0f / (float)(p.W / plan.px);
-    if (plan.nt == 256)
-        return launch_stride<256>(a, p.sh, plan.lds_bytes, plan.pt, plan.px, stream);
-    if (plan.nt == 128)
-        return launch_stride<128>(a, p.sh, plan.lds_bytes, plan.pt, plan.px, stream);
-    return launch_stride<64>(a, p.sh, plan.lds_bytes, plan.pt, plan.px, stream);
+    switch (plan.nt) {
+    case 256: return launch_pt<1, 2>(a, plan.lds_bytes, plan.pt, plan.px, stream);
+    case 128: return launch_pt<2, 2>(a, plan.lds_bytes, plan.pt, plan.px, stream);
+    default: return launch_pt<2, 1>(a, plan.lds_bytes, plan.pt, plan.px, stream);
+    }
 }
 
 }  // namespace tvg

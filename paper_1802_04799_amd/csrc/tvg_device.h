@@ -279,46 +279,53 @@ __device__ __forceinline__ void store_fast_tiles(const float16v (&acc)[MI][NJ], 
                                                  const int (&rem0)[NJ], const TailArgs &t,
                                                  const float *ss, int row_base)
 {
-    static_assert((MI * NJ) % BT == 0, "tiles per batch must divide the tile count");
+    constexpr int T = MI * NJ;
     const int lrow = lane & 31, lhalf = lane >> 5;
     const float floor_v = t.relu ? 0.0f : -INFINITY;
     const bf16_t *res = static_cast<const bf16_t *>(t.residual);
     bf16_t *y = static_cast<bf16_t *>(t.y);
     const int row = lane >> 2, g = lane & 3;
 #pragma unroll
-    for (int b0 = 0; b0 < MI * NJ; b0 += BT) {
+    for (int b0 = 0; b0 < T; b0 += BT) {
 #pragma unroll
         for (int k = 0; k < BT; ++k) {
-            const int i = (b0 + k) / NJ, j = (b0 + k) % NJ;
-            const float sc = ss[2 * (row_base + i * 32 + lrow)];
-            const float sf = ss[2 * (row_base + i * 32 + lrow) + 1];
-            unsigned char *st = stage + k * kStageBytes;
-            const int base = (n0[j] * t.OC + ocu + i * 32 + lrow) * t.OHW + rem0[j] + 4 * lhalf;
+            // (the last batch may be short; clamped indices keep every subscript a constant)
+            const int tix = b0 + k < T ? b0 + k : T - 1;
+            const int i = tix / NJ, j = tix % NJ;
+            if (b0 + k < T) {
+                const float sc = ss[2 * (row_base + i * 32 + lrow)];
+                const float sf = ss[2 * (row_base + i * 32 + lrow) + 1];
+                unsigned char *st = stage + k * kStageBytes;
+                const int base = (n0[j] * t.OC + ocu + i * 32 + lrow) * t.OHW + rem0[j] + 4 * lhalf;
 #pragma unroll
-            for (int gq = 0; gq < 4; ++gq) {
-                float f[4], r[4];
-                if (HAS_RES)
-                    Group4<bf16_t>::unpack(*reinterpret_cast<const uint2v *>(res + base + 8 * gq), r);
+                for (int gq = 0; gq < 4; ++gq) {
+                    float f[4], r[4];
+                    if (HAS_RES)
+                        Group4<bf16_t>::unpack(*reinterpret_cast<const uint2v *>(res + base + 8 * gq), r);
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    float v = fmaf(acc[i][j][4 * gq + q], sc, sf);
-                    if (HAS_RES) v += r[q];
-                    f[q] = fmaxf(v, floor_v);
+                    for (int q = 0; q < 4; ++q) {
+                        float v = fmaf(acc[i][j][4 * gq + q], sc, sf);
+                        if (HAS_RES) v += r[q];
+                        f[q] = fmaxf(v, floor_v);
+                    }
+                    *reinterpret_cast<uint2v *>(st + lrow * kStageRow + (8 * gq + 4 * lhalf) * 2) =
+                        Group4<bf16_t>::pack(f);
                 }
-                *reinterpret_cast<uint2v *>(st + lrow * kStageRow + (8 * gq + 4 * lhalf) * 2) =
-                    Group4<bf16_t>::pack(f);
             }
         }
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int k = 0; k < BT; ++k) {
-            const int i = (b0 + k) / NJ, j = (b0 + k) % NJ;
-            const unsigned char *st = stage + k * kStageBytes;
-            const int b2 = (n0[j] * t.OC + ocu + i * 32 + row) * t.OHW + rem0[j] + 8 * g;
+            const int tix = b0 + k < T ? b0 + k : T - 1;
+            const int i = tix / NJ, j = tix % NJ;
+            if (b0 + k < T) {
+                const unsigned char *st = stage + k * kStageBytes;
+                const int b2 = (n0[j] * t.OC + ocu + i * 32 + row) * t.OHW + rem0[j] + 8 * g;
 #pragma unroll
-            for (int it = 0; it < 2; ++it)
-                *reinterpret_cast<uint4v *>(y + b2 + it * 16 * t.OHW) =
-                    *reinterpret_cast<const uint4v *>(st + (row + 16 * it) * kStageRow + g * 16);
+                for (int it = 0; it < 2; ++it)
+                    *reinterpret_cast<uint4v *>(y + b2 + it * 16 * t.OHW) =
+                        *reinterpret_cast<const uint4v *>(st + (row + 16 * it) * kStageRow + g * 16);
+            }
         }
         __builtin_amdgcn_wave_barrier();
     }
