@@ -238,6 +238,9 @@ PW_SHAPES = [
     # bf16 1x1 problems with IC % 8 == 0: n, ic, h, w, oc, stride
     (2, 8, 9, 9, 33, 1), (3, 40, 15, 13, 70, 2), (1, 64, 56, 56, 64, 1), (2, 72, 7, 7, 130, 1),
     (5, 16, 6, 10, 8, 2), (1, 264, 3, 5, 200, 1), (4, 32, 28, 28, 256, 2), (1, 8, 1, 1, 1, 1),
+    # exactly 2 and 8 chunks of 32 channels (all chunks fetched up front), ragged tiles
+    (3, 256, 14, 14, 130, 2), (2, 256, 9, 11, 70, 1), (20, 256, 14, 14, 512, 2), (3, 64, 13, 9, 40, 2),
+    (2, 128, 10, 10, 96, 1),
 ]
 
 
