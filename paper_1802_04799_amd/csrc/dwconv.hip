@@ -219,7 +219,7 @@ __global__ __launch_bounds__(256) void dwconv3x3_direct_kernel(const DwDirectArg
         float4v out;
 #pragma unroll
         for (int q = 0; q < 4; ++q) out[q] = fmaxf(fmaf(acc[o][q], sc, sf) + r[q], floor_v);
-        *reinterpret_cast<float4v *>(a.y + idx) = out;
+        stream_store(reinterpret_cast<float4v *>(a.y + idx), out);
     }
 }
 
@@ -294,7 +294,7 @@ __global__ __launch_bounds__(256) void dwconv3x3_smallplane_kernel(const DwSmall
         const size_t idx = (size_t)(p0 + p) * OHW + r0;
         float o = fmaf(acc, pp[9], pp[10]);
         if (a.residual) o += a.residual[idx];
-        a.y[idx] = fmaxf(o, floor_v);
+        stream_store(a.y + idx, fmaxf(o, floor_v));     // a wave's lanes write one contiguous run
     }
 }
 
