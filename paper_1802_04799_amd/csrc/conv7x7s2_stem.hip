@@ -37,7 +37,7 @@ struct StemArgs {
     int N, IC, H, W, OC, OH, OW, npix, relu, vmode;
     int nrows;          // staged virtual rows per tile (maximum over tiles)
     int ntiles, mtiles, wg_per_mtile;
-    uint32_t x_bytes;
+    uint32_t x_bytes, w_bytes;
 };
 
 constexpr int kNT = 256;                 // pixels per tile
@@ -73,16 +73,42 @@ __global__ __launch_bounds__(256, 2) void conv7x7s2_stem_kernel(const StemArgs a
 
     stage_scale_shift(ss_lds, m0, kMT, a.scale, a.shift, a.bias, a.OC, tid, 256);
 
-    // ---- zero both patch buffers (their padding columns stay zero), stage the weights ----
+    // ---- zero both patch buffers (their padding columns stay zero) and the weight area ----
     for (int i = tid; i < 2 * patch_bytes / 16; i += 256)
         reinterpret_cast<uint4v *>(Ps)[i] = uint4v{0u, 0u, 0u, 0u};
-    for (int e = tid; e < 2 * NM * kMT * 8; e += 256) {
-        const int sp = e & 7, ocl = (e >> 3) & (kMT - 1), pair = e >> 9;
-        const int ic = pair / 7, r = pair - ic * 7;
-        bf16_t v = 0;
-        if (pair < npairs && sp >= 1 && m0 + ocl < a.OC)
-            v = a.w[((size_t)(m0 + ocl) * IC + ic) * 49 + r * 7 + sp - 1];
-        reinterpret_cast<bf16_t *>(As)[e] = v;
+    for (int i = tid; i < a_bytes / 16; i += 256)
+        reinterpret_cast<uint4v *>(As)[i] = uint4v{0u, 0u, 0u, 0u};
+    // ---- stage the weights: the tile's channels are one contiguous run of [oc][ic][r][s], read
+    // as 16-byte vectors that are all in flight together, then scattered element by element
+    // into [pair = (ic, r)][oc][slot = s + 1] (slot 0, the odd pair and absent channels stay 0)
+    {
+        constexpr int KW = IC * 49;                      // weights per output channel
+        constexpr int WV = (kMT * KW + 7) / 8;           // vectors per full tile
+        constexpr int WT = (WV + 255) / 256;             // vectors per thread
+        const int count = min(kMT, a.OC - m0) * KW;
+        const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<bf16_t *>(a.w), 0, a.w_bytes, kRsrcFlags);
+        const uint32_t wbase = (uint32_t)m0 * KW * 2u;
+        uint4v wv[WT];
+#pragma unroll
+        for (int j = 0; j < WT; ++j) {
+            const int v = tid + j * 256;
+            const uint32_t voff = v * 8 < count ? wbase + (uint32_t)v * 16u : kOutOfRange;
+            wv[j] = __builtin_bit_cast(uint4v, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, voff, 0, 0));
+        }
+        __syncthreads();                                 // the zeros are in place
+#pragma unroll
+        for (int j = 0; j < WT; ++j) {
+            const int f0 = (tid + j * 256) * 8;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int f = f0 + k;
+                const int ocl = f / KW, rem = f - ocl * KW;
+                const int pair = rem / 7, sp = rem - pair * 7 + 1;
+                const bf16_t v = (bf16_t)(k & 1 ? wv[j][k >> 1] >> 16 : wv[j][k >> 1] & 0xffffu);
+                if (f < count) reinterpret_cast<bf16_t *>(As)[(pair * kMT + ocl) * 8 + sp] = v;
+            }
+        }
     }
 
     // ---- per-thread copy tasks: (ic, row slot, 16-byte column group), fixed for all tiles --
@@ -260,7 +286,8 @@ bool plan_conv7x7s2_stem(const ConvProblem &p, StemPlan *plan)
 
 bool conv7x7s2_stem_pointers_ok(const ConvPointers &ptr)
 {
-    return reinterpret_cast<uintptr_t>(ptr.x) % 16 == 0;   // input rows are copied as 16-byte vectors
+    // input rows and the weights are read as 16-byte vectors
+    return reinterpret_cast<uintptr_t>(ptr.x) % 16 == 0 && reinterpret_cast<uintptr_t>(ptr.w) % 16 == 0;
 }
 
 tvg_status launch_conv7x7s2_stem(const ConvProblem &p, const StemPlan &plan, const ConvPointers &ptr,
@@ -282,6 +309,7 @@ tvg_status launch_conv7x7s2_stem(const ConvProblem &p, const StemPlan &plan, con
     if (per > a.ntiles) per = a.ntiles;
     a.wg_per_mtile = per;
     a.x_bytes = (uint32_t)((size_t)p.N * p.IC * p.H * p.W * 2);
+    a.w_bytes = (uint32_t)((size_t)p.OC * p.IC * 49 * 2);
     const unsigned grid = (unsigned)(per * a.mtiles);
     if (p.IC == 3 && plan.lt <= 5) return launch_lt<3, 5>(a, grid, plan.lds_bytes, stream);
     switch (p.IC) {
