@@ -27,6 +27,7 @@
 #include <stdio.h>
 #include <stdlib.h>
 
+#include <numeric>
 #include "tvg_device.h"
 #include "tvg_internal.h"
 
@@ -311,7 +312,10 @@ int max_patch_rows(const ConvProblem &p, int nt)
 {
     const int OHW = p.OH * p.OW, VH = p.H + 2;
     int best = 0;
-    for (long n0 = 0; n0 < p.npix; n0 += nt) {
+    // the row count of a tile depends only on where in an image it starts, which repeats after
+    // OHW / gcd(OHW, nt) tiles: one period covers every case (this runs on every call)
+    const long period = (long)nt * (OHW / std::gcd(OHW, nt));
+    for (long n0 = 0; n0 < p.npix && n0 < period; n0 += nt) {
         const long last = (n0 + nt < p.npix ? n0 + nt : p.npix) - 1;
         const int na = (int)(n0 / OHW), oha = (int)((n0 - (long)na * OHW) / p.OW);
         const int nb = (int)(last / OHW), ohb = (int)((last - (long)nb * OHW) / p.OW);

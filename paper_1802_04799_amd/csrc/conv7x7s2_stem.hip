@@ -22,6 +22,7 @@
 //
 // The next tile's rows are requested before the current tile's MFMAs and are
 // written to the other LDS buffer afterwards (one barrier per tile).
+#include <numeric>
 #include "tvg_device.h"
 #include "tvg_internal.h"
 
@@ -236,7 +237,10 @@ int max_stem_rows(const ConvProblem &p)
 {
     const int OHW = p.OH * p.OW, VH = p.H + 6;
     int best = 0;
-    for (long p0 = 0; p0 < p.npix; p0 += kNT) {
+    // the row count of a tile depends only on where in an image it starts, which repeats after
+    // OHW / gcd(OHW, kNT) tiles: one period covers every case (this runs on every call)
+    const long period = (long)kNT * (OHW / std::gcd(OHW, kNT));
+    for (long p0 = 0; p0 < p.npix && p0 < period; p0 += kNT) {
         const long last = (p0 + kNT < p.npix ? p0 + kNT : p.npix) - 1;
         const int na = (int)(p0 / OHW), oha = (int)((p0 - (long)na * OHW) / p.OW);
         const int nb = (int)(last / OHW), ohb = (int)((last - (long)nb * OHW) / p.OW);
