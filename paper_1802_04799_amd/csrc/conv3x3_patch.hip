@@ -18,7 +18,9 @@
 // the first and last being zero padding, so a pixel (n, oh, ow) and tap (r, s)
 // read virtual row n*(H+2) + oh*stride + r, column ow*stride + s of a
 // (W+2)-wide padded row.  A pixel tile therefore needs one contiguous range of
-// virtual rows even when it straddles images.
+// virtual rows even when it straddles images.  For stride 2 a row is stored even
+// columns first, odd columns after them, so that the pixels of consecutive lanes
+// (two columns apart) are adjacent positions again.
 //
 // Pipeline per chunk: global loads of chunk c+1 are issued into registers, the
 // 9 taps x MFMA phase of chunk c runs from LDS, then (barrier) the registers are
@@ -61,9 +63,8 @@ __device__ __forceinline__ int xcd_remap(int bid, int nb)
 __device__ __forceinline__ uint32_t half_of(uint32_t d, int hi) { return hi ? d >> 16 : d & 0xFFFFu; }
 
 // MT x NT output tile per workgroup of 256 threads; PT = patch load tasks per thread; PX =
-// horizontally adjacent pixels fetched per load (2 or 4 need W to be a multiple: 32- or
-// 64-bit loads, a half or a quarter of the vector memory instructions, whose issue rate is
-// what limits the staging).
+// horizontally adjacent pixels fetched per load (2, 4 or 8 need W to be a multiple: 32-, 64- or
+// 128-bit loads, a half to an eighth of the vector memory instructions).
 template <int MT, int NT, int STRIDE, int PT, int PX>
 __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a)
 {
@@ -92,6 +93,11 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
 
     const int H = a.H, W = a.W, HW = H * W, OHW = a.OH * a.OW;
     const int VH = H + 2, PW = W + 2;
+    // Stride 2: a patch row holds its even columns first and its odd columns from position
+    // HALF on, so that the 32 pixels of an MFMA operand (input columns two apart) are 32
+    // adjacent positions, which 16-byte reads cover without bank conflicts; interleaved, they
+    // would be 96 bytes apart and collide in pairs.
+    const int HALF = (PW + 1) / 2;
 
     // Index arithmetic below divides by OH*OW, OW, W and H+2 only; the host admits this
     // kernel when every dividend stays below 2^22, where fast_div is exact.
@@ -130,7 +136,9 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
                 const int ih = vi - 1;
                 if (ih >= 0 && ih < H && n < a.N) {
                     goff[j] = 2u * (uint32_t)((n * a.IC + octet * 8) * HW + ih * W + iw);
-                    loff[j] = (vrow * PW + iw + 1) * kPosBytes + octet * 16;
+                    const int col = iw + 1;       // patch column (0 = left padding)
+                    const int pos = STRIDE == 2 ? ((col & 1) ? HALF + (col >> 1) : (col >> 1)) : col;
+                    loff[j] = (vrow * PW + pos) * kPosBytes + octet * 16;
                 }
             }
         }
@@ -146,7 +154,8 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
             int rem, ow;
             const int n = fast_div(p, OHW, inv_ohw, &rem);
             const int oh = fast_div(rem, a.OW, inv_ow, &ow);
-            pb[j] += ((n * VH + oh * STRIDE - vr_lo) * PW + ow * STRIDE) * kPosBytes;
+            // (stride 2: column 2*ow is even, at position ow of its row)
+            pb[j] += ((n * VH + oh * STRIDE - vr_lo) * PW + ow) * kPosBytes;
         }
     }
 
@@ -159,7 +168,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
 
     // Loaded values stay unpacked until store_chunk so that nothing waits on the loads
     // before the MFMA phase of the current chunk.
-    constexpr int W32 = PX == 4 ? 2 : 1;       // registers per load
+    constexpr int W32 = PX >= 2 ? PX / 2 : 1;  // registers per load
     uint32_t praw[PT][8][W32];
     uint4v wreg[9];
 
@@ -176,7 +185,12 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
             const int soff = (c * kChunk + q) * HW * 2;
 #pragma unroll
             for (int j = 0; j < PT; ++j)
-                if constexpr (PX == 4) {
+                if constexpr (PX == 8) {
+                    const uint4v t4 = __builtin_bit_cast(
+                        uint4v, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, goff[j], soff, 0));
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) praw[j][q][d] = t4[d];
+                } else if constexpr (PX == 4) {
                     const uint2v t2 = __builtin_bit_cast(
                         uint2v, __builtin_amdgcn_raw_buffer_load_b64(xrsrc, goff[j], soff, 0));
                     praw[j][q][0] = t2[0];
@@ -208,8 +222,11 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
                     for (int q = 0; q < 4; ++q)
                         o[q] = half_of(praw[j][2 * q][k >> 1], k & 1) |
                                (half_of(praw[j][2 * q + 1][k >> 1], k & 1) << 16);
-                    *reinterpret_cast<uint4v *>(Ps + loff[j] + k * kPosBytes) =
-                        uint4v{o[0], o[1], o[2], o[3]};
+                    // stride 2 (PX > 1: the task starts on an odd patch column): pixels
+                    // alternate between the odd and the even half of the row
+                    const int koff = STRIDE == 2 ? ((k & 1) ? (1 - HALF) * kPosBytes : 0) + (k >> 1) * kPosBytes
+                                                 : k * kPosBytes;
+                    *reinterpret_cast<uint4v *>(Ps + loff[j] + koff) = uint4v{o[0], o[1], o[2], o[3]};
                 }
             }
         if (wtask) {
@@ -263,7 +280,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
         uint4v af[2][MI], bf[2][NJ];
         auto fetch = [&](int tap, int slot) {
             const int r = tap / 3, s = tap - r * 3;
-            const int toff = (r * PW + s) * kPosBytes;
+            const int toff = (r * PW + (STRIDE == 2 ? (s == 1 ? HALF : (s >> 1)) : s)) * kPosBytes;
 #pragma unroll
             for (int i = 0; i < MI; ++i)
                 af[slot][i] =
@@ -343,6 +360,18 @@ tvg_status launch_instance(const PatchArgs &a, int ntiles, size_t lds, hipStream
 template <int MT, int NT, int STRIDE>
 tvg_status launch_pt(const PatchArgs &a, int ntiles, size_t lds, int pt, int px, hipStream_t stream)
 {
+    if constexpr (STRIDE == 2) {
+        // stride-2 patches are four times the output tile: wide loads keep the count down
+        if (px == 8) {
+            if (pt <= 1) return launch_instance<MT, NT, STRIDE, 1, 8>(a, ntiles, lds, stream);
+            return launch_instance<MT, NT, STRIDE, 2, 8>(a, ntiles, lds, stream);
+        }
+        if (px == 4) {
+            if (pt <= 1) return launch_instance<MT, NT, STRIDE, 1, 4>(a, ntiles, lds, stream);
+            if (pt <= 2) return launch_instance<MT, NT, STRIDE, 2, 4>(a, ntiles, lds, stream);
+            return launch_instance<MT, NT, STRIDE, 4, 4>(a, ntiles, lds, stream);
+        }
+    }
     if (px == 2) {
         if (pt <= 2) return launch_instance<MT, NT, STRIDE, 2, 2>(a, ntiles, lds, stream);
         return launch_instance<MT, NT, STRIDE, 4, 2>(a, ntiles, lds, stream);
@@ -393,8 +422,15 @@ bool plan_conv3x3_patch(const ConvProblem &p, Patch3x3Plan *plan)
         const int rows = max_patch_rows(p, nt);
         // two pixels per load when the rows are even (32-bit aligned pairs) and that keeps the
         // task count within the instances built for it
-        // (four pixels per load were measured too: no gain over two, so no instance is built)
+        // (stride 1: four pixels per load were measured too, no gain over two)
         int px = p.W % 2 == 0 ? 2 : 1;
+        if (p.sh == 2) {
+            // a stride-2 patch is four times the output tile: 16- or 8-byte loads where the
+            // rows allow them (x is 16-byte aligned, and so is every row when W % 8 == 0)
+            // (measured at batch 64, with the split rows: C4 26.0 -> 24.2 us; C7 unchanged)
+            if (p.W % 8 == 0 && (2 * rows * (p.W / 8) + 255) / 256 <= 2) px = 8;
+            else if (p.W % 4 == 0 && (2 * rows * (p.W / 4) + 255) / 256 <= 4) px = 4;
+        }
         int pt = (2 * rows * (p.W / px) + 255) / 256;
         if (px == 2 && pt > 4) { px = 1; pt = (2 * rows * p.W + 255) / 256; }
         const size_t lds = (size_t)9 * mt * kPosBytes + (size_t)rows * (p.W + 2) * kPosBytes +
