@@ -36,6 +36,8 @@ def parse():
     ap.add_argument("--skip-extras", action="store_true",
                     help="only the timed region (for profiler runs)")
     ap.add_argument("--skip-cpu", action="store_true", help="do not time the CPU oracle")
+    ap.add_argument("--no-stream-hint", action="store_true",
+                    help="operator layers without the TVG_STREAM_OUT store hint")
     ap.add_argument("--only", default="", help="comma-separated layer names (C1..C12): restrict "
                     "the step to these layers (for profiler runs)")
     ap.add_argument("--depthwise-probe", action="store_true",
@@ -67,6 +69,10 @@ def main():
         t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32))
         return (t.to(torch.bfloat16) if bf16 else t).to(dev)
 
+    # The operator benchmark runs unrelated layers: nothing reads an output again, which is what
+    # the library's TVG_STREAM_OUT hint is for.  The ResNet-18 chain below runs without it.
+    hint = 0 if args.no_stream_hint else tvg.TVG_STREAM_OUT
+
     class Layer:
         """One fused conv launch with everything preallocated."""
         def __init__(self, sh, seed, dtype, depthwise=False, copies=1):
@@ -86,7 +92,7 @@ def main():
                 self.y.append(torch.empty_like(self.y[0]))
             self.desc = tvg.ConvDesc(sh.n, sh.ic, sh.h, sh.w, sh.oc, sh.r, sh.s, sh.stride,
                                      sh.stride, sh.pad, sh.pad,
-                                     tvg.TVG_BF16 if bf else tvg.TVG_F32, tvg.TVG_RELU)
+                                     tvg.TVG_BF16 if bf else tvg.TVG_F32, tvg.TVG_RELU | hint)
             self.ws_bytes = 0 if depthwise else tvg.tvg_conv2d_workspace_size(self.desc)
             self.ws = torch.empty(max(self.ws_bytes, 1), dtype=torch.uint8, device=dev)
             self.fn = tvg.tvg_dwconv2d_fused if depthwise else tvg.tvg_conv2d_fused
@@ -216,7 +222,8 @@ def main():
                                "batch 64, bf16 in/out, fp32 accumulate, fused scale/shift+ReLU; "
                                "one step = 12 launches" + (f" (restricted to {args.only})" if args.only else ""),
                    "step_gflop": round(step_flops / 1e9, 2), "step_mbytes": round(step_bytes / 1e6, 1),
-                   "frac_mfma_peak": round(value / PEAK_BF16_TFLOPS, 4)},
+                   "frac_mfma_peak": round(value / PEAK_BF16_TFLOPS, 4),
+                   "stream_out_hint": not args.no_stream_hint},
         "roofline": roofline,
         "layers": layer_rows,
         "layers_note": "per-launch durations from a calibration pass with an event before every "
@@ -350,8 +357,14 @@ def bench_body(tvg, ti, torch, np, dev, to_dev, time_loop):
                 raise RuntimeError(tvg.status_string(st))
 
     ms = time_loop(forward, 10)
+    # The same 21 launches captured once into a HIP graph and replayed: the library neither
+    # allocates nor synchronises, so the chain records as it stands.
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=torch.cuda.Stream()):
+        forward()
+    graph_ms = time_loop(graph.replay, 10)
     flops = sum(s.shape.flops for s in steps if s.op == "conv")
-    return {"batch": n, "launches": len(calls), "ms": round(ms, 4),
+    return {"batch": n, "launches": len(calls), "ms": round(ms, 4), "graph_replay_ms": round(graph_ms, 4),
             "tflops": round(flops / (ms * 1e-3) / 1e12, 1),
             "images_per_s": round(n / (ms * 1e-3), 1),
             "frac_mfma_peak": round(flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}

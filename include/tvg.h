@@ -53,14 +53,23 @@ typedef enum {
 
 typedef enum { TVG_F32 = 0, TVG_BF16 = 1 } tvg_dtype;
 
-enum { TVG_RELU = 1u };        /* bits of tvg_conv_desc.flags */
+/* Bits of tvg_conv_desc.flags.
+ * TVG_RELU        clamp the output at zero (last step of the fused tail).
+ * TVG_STREAM_OUT  a hint, results are identical with and without it: y is stored with the
+ *                 non-temporal cache hint.  Right when nothing reads y soon (an operator run
+ *                 on its own, an output larger than the caches): the kernel and its successor
+ *                 then run faster, since y neither displaces the operands in L2 nor waits
+ *                 there to be written back.  Wrong between the layers of a network whose
+ *                 activations fit the memory-side cache: the next layer would fetch from
+ *                 HBM what it could have found there.  Off by default. */
+enum { TVG_RELU = 1u, TVG_STREAM_OUT = 2u };
 
 typedef struct {
     int32_t n, c, h, w;        /* input N, C (= IC), H, W                                   */
     int32_t k, r, s;           /* output channels, kernel height, kernel width              */
     int32_t stride_h, stride_w, pad_h, pad_w;
     int32_t dtype;             /* tvg_dtype of x, w, residual, y                            */
-    uint32_t flags;            /* TVG_RELU or 0                                             */
+    uint32_t flags;            /* TVG_RELU | TVG_STREAM_OUT, or 0                           */
 } tvg_conv_desc;               /* depthwise: k == c, r == s == 3                            */
 
 /*

@@ -10,6 +10,7 @@ _LIB_PATH = os.path.join(HERE, "libtvg.so")
 
 TVG_F32, TVG_BF16 = 0, 1
 TVG_RELU = 1
+TVG_STREAM_OUT = 2      # hint: nothing reads y soon, store it past the caches
 TVG_OK = 0
 
 
@@ -171,20 +172,21 @@ def _check(x, w, scale, shift, bias, residual):
         raise TypeError("x, w and residual must share one dtype")
 
 
-def make_desc(x, w, stride, pad, relu, depthwise=False) -> ConvDesc:
+def make_desc(x, w, stride, pad, relu, depthwise=False, stream_out=False) -> ConvDesc:
     n, c, h, wd = x.shape
     k, _, r, s = w.shape
     sh, sw = (stride, stride) if isinstance(stride, int) else stride
     ph, pw = (pad, pad) if isinstance(pad, int) else pad
-    return ConvDesc(n, c, h, wd, k, r, s, sh, sw, ph, pw, _dtype_code(x), TVG_RELU if relu else 0)
+    flags = (TVG_RELU if relu else 0) | (TVG_STREAM_OUT if stream_out else 0)
+    return ConvDesc(n, c, h, wd, k, r, s, sh, sw, ph, pw, _dtype_code(x), flags)
 
 
 def conv2d_fused(x, w, scale, shift, bias=None, residual=None, *, stride=1, pad=0, relu=False,
-                 out=None, workspace=None, stream=None):
+                 out=None, workspace=None, stream=None, stream_out=False):
     """y = tail(conv2d(x, w)); allocates y (and the workspace when needed) with torch."""
     import torch
     _check(x, w, scale, shift, bias, residual)
-    desc = make_desc(x, w, stride, pad, relu)
+    desc = make_desc(x, w, stride, pad, relu, stream_out=stream_out)
     if w.shape[1] != x.shape[1]:
         raise ValueError("weight input channels do not match x")
     need = tvg_conv2d_workspace_size(desc)
@@ -200,10 +202,10 @@ def conv2d_fused(x, w, scale, shift, bias=None, residual=None, *, stride=1, pad=
 
 
 def dwconv2d_fused(x, w, scale, shift, bias=None, residual=None, *, stride=1, pad=1, relu=False,
-                   out=None, stream=None):
+                   out=None, stream=None, stream_out=False):
     import torch
     _check(x, w, scale, shift, bias, residual)
-    desc = make_desc(x, w, stride, pad, relu, depthwise=True)
+    desc = make_desc(x, w, stride, pad, relu, depthwise=True, stream_out=stream_out)
     if out is None:
         out = torch.empty((desc.n, desc.k, desc.oh, desc.ow), dtype=x.dtype, device=x.device)
     st = tvg_dwconv2d_fused(desc, x, w, scale, shift, bias, residual, out, None, 0, stream)

@@ -1,5 +1,6 @@
 // C ABI of libtvg: argument validation (host only, before any device call),
 // planning and dispatch to the kernel launchers.
+#include <stdlib.h>
 #include "tvg_internal.h"
 
 namespace {
@@ -19,7 +20,7 @@ tvg_status make_problem(const tvg_conv_desc *d, bool depthwise, ConvProblem *out
         return TVG_ERR_BAD_SHAPE;
     if (d->h + 2 * d->pad_h < d->r || d->w + 2 * d->pad_w < d->s) return TVG_ERR_BAD_SHAPE;
     if (d->dtype != TVG_F32 && d->dtype != TVG_BF16) return TVG_ERR_UNSUPPORTED;
-    if (d->flags & ~(uint32_t)TVG_RELU) return TVG_ERR_UNSUPPORTED;
+    if (d->flags & ~(uint32_t)(TVG_RELU | TVG_STREAM_OUT)) return TVG_ERR_UNSUPPORTED;
     if (d->r > 16 || d->s > 16) return TVG_ERR_UNSUPPORTED;
     if (depthwise) {
         if (d->k != d->c) return TVG_ERR_BAD_SHAPE;
@@ -39,6 +40,7 @@ tvg_status make_problem(const tvg_conv_desc *d, bool depthwise, ConvProblem *out
     p.npix = d->n * p.OH * p.OW;
     p.dtype = d->dtype;
     p.relu = (d->flags & TVG_RELU) ? 1 : 0;
+    p.stream_out = (d->flags & TVG_STREAM_OUT) ? 1 : 0;
     *out = p;
     return TVG_OK;
 }

@@ -268,7 +268,7 @@ tvg_status launch_conv1x1(const ConvProblem &p, const Pw1x1Plan &plan, const Con
     a.scale = ptr.scale; a.shift = ptr.shift; a.bias = ptr.bias;
     a.residual = static_cast<const bf16_t *>(ptr.residual); a.y = static_cast<bf16_t *>(ptr.y);
     a.N = p.N; a.IC = p.IC; a.H = p.H; a.W = p.W; a.OC = p.OC; a.OH = p.OH; a.OW = p.OW;
-    a.stride = p.sh; a.npix = p.npix; a.relu = p.relu;
+    a.stride = p.sh; a.npix = p.npix; a.relu = p.relu | (p.stream_out << 1);
     a.mtiles = (p.OC + plan.mt - 1) / plan.mt;
     a.ntiles = (p.npix + plan.nt - 1) / plan.nt;
     a.m_major = (size_t)p.OC * p.IC > (size_t)p.N * p.IC * p.H * p.W;

@@ -518,7 +518,7 @@ tvg_status launch_conv3x3_dbuf(const ConvProblem &p, const Patch3x3Plan &plan,
     a.scale = ptr.scale; a.shift = ptr.shift; a.bias = ptr.bias;
     a.residual = static_cast<const bf16_t *>(ptr.residual); a.y = static_cast<bf16_t *>(ptr.y);
     a.N = p.N; a.IC = p.IC; a.H = p.H; a.W = p.W; a.OC = p.OC; a.OH = p.OH; a.OW = p.OW;
-    a.npix = p.npix; a.relu = p.relu;
+    a.npix = p.npix; a.relu = p.relu | (p.stream_out << 1);
     a.mtiles = (p.OC + kMT - 1) / kMT;
     a.vmode = pick_store_vmode(p.dtype, p.OH * p.OW, ptr.y, ptr.residual);
     a.pplane = plan.pplane;

@@ -302,7 +302,7 @@ tvg_status launch_conv7x7s2_stem(const ConvProblem &p, const StemPlan &plan, con
     a.scale = ptr.scale; a.shift = ptr.shift; a.bias = ptr.bias;
     a.residual = static_cast<const bf16_t *>(ptr.residual); a.y = static_cast<bf16_t *>(ptr.y);
     a.N = p.N; a.IC = p.IC; a.H = p.H; a.W = p.W; a.OC = p.OC; a.OH = p.OH; a.OW = p.OW;
-    a.npix = p.npix; a.relu = p.relu;
+    a.npix = p.npix; a.relu = p.relu | (p.stream_out << 1);
     a.vmode = pick_store_vmode(p.dtype, p.OH * p.OW, ptr.y, ptr.residual);
     a.nrows = plan.rows;
     a.ntiles = (p.npix + kNT - 1) / kNT;

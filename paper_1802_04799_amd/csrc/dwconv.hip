@@ -154,7 +154,7 @@ struct DwDirectArgs {
 
 constexpr int kRB = 4;        // output rows per lane
 
-template <int STRIDE>
+template <int STRIDE, bool NT>
 __global__ __launch_bounds__(256) void dwconv3x3_direct_kernel(const DwDirectArgs a)
 {
     const int g = blockIdx.x * 256 + threadIdx.x;
@@ -219,7 +219,7 @@ __global__ __launch_bounds__(256) void dwconv3x3_direct_kernel(const DwDirectArg
         float4v out;
 #pragma unroll
         for (int q = 0; q < 4; ++q) out[q] = fmaxf(fmaf(acc[o][q], sc, sf) + r[q], floor_v);
-        stream_store(reinterpret_cast<float4v *>(a.y + idx), out);
+        stream_store<NT>(reinterpret_cast<float4v *>(a.y + idx), out);
     }
 }
 
@@ -236,7 +236,7 @@ struct DwSmallArgs {
     int planes, C, H, W, OH, OW, PG, relu;
 };
 
-template <int STRIDE>
+template <int STRIDE, bool NT>
 __global__ __launch_bounds__(256) void dwconv3x3_smallplane_kernel(const DwSmallArgs a)
 {
     extern __shared__ float smem[];
@@ -294,7 +294,7 @@ __global__ __launch_bounds__(256) void dwconv3x3_smallplane_kernel(const DwSmall
         const size_t idx = (size_t)(p0 + p) * OHW + r0;
         float o = fmaf(acc, pp[9], pp[10]);
         if (a.residual) o += a.residual[idx];
-        stream_store(a.y + idx, fmaxf(o, floor_v));     // a wave's lanes write one contiguous run
+        stream_store<NT>(a.y + idx, fmaxf(o, floor_v));     // a wave's lanes write one contiguous run
     }
 }
 
@@ -327,10 +327,14 @@ tvg_status launch_dwconv3x3(const ConvProblem &p, const ConvPointers &ptr, hipSt
         d.inv_cb = 1.0f / (float)d.CB;
         d.relu = p.relu;
         const unsigned blocks = (unsigned)((tasks + 255) / 256);
-        if (stride0 == 1)
-            hipLaunchKernelGGL((dwconv3x3_direct_kernel<1>), dim3(blocks), dim3(256), 0, stream, d);
+        if (stride0 == 1 && p.stream_out)
+            hipLaunchKernelGGL((dwconv3x3_direct_kernel<1, true>), dim3(blocks), dim3(256), 0, stream, d);
+        else if (stride0 == 1)
+            hipLaunchKernelGGL((dwconv3x3_direct_kernel<1, false>), dim3(blocks), dim3(256), 0, stream, d);
+        else if (p.stream_out)
+            hipLaunchKernelGGL((dwconv3x3_direct_kernel<2, true>), dim3(blocks), dim3(256), 0, stream, d);
         else
-            hipLaunchKernelGGL((dwconv3x3_direct_kernel<2>), dim3(blocks), dim3(256), 0, stream, d);
+            hipLaunchKernelGGL((dwconv3x3_direct_kernel<2, false>), dim3(blocks), dim3(256), 0, stream, d);
         return hipGetLastError() == hipSuccess ? TVG_OK : TVG_ERR_LAUNCH;
     }
 
@@ -354,10 +358,14 @@ tvg_status launch_dwconv3x3(const ConvProblem &p, const ConvPointers &ptr, hipSt
             d.PG = pg;
             const size_t lds = (size_t)pg * (hw + 12) * sizeof(float);
             const unsigned blocks = (unsigned)((d.planes + pg - 1) / pg);
-            if (stride0 == 1)
-                hipLaunchKernelGGL((dwconv3x3_smallplane_kernel<1>), dim3(blocks), dim3(256), lds, stream, d);
+            if (stride0 == 1 && p.stream_out)
+                hipLaunchKernelGGL((dwconv3x3_smallplane_kernel<1, true>), dim3(blocks), dim3(256), lds, stream, d);
+            else if (stride0 == 1)
+                hipLaunchKernelGGL((dwconv3x3_smallplane_kernel<1, false>), dim3(blocks), dim3(256), lds, stream, d);
+            else if (p.stream_out)
+                hipLaunchKernelGGL((dwconv3x3_smallplane_kernel<2, true>), dim3(blocks), dim3(256), lds, stream, d);
             else
-                hipLaunchKernelGGL((dwconv3x3_smallplane_kernel<2>), dim3(blocks), dim3(256), lds, stream, d);
+                hipLaunchKernelGGL((dwconv3x3_smallplane_kernel<2, false>), dim3(blocks), dim3(256), lds, stream, d);
             return hipGetLastError() == hipSuccess ? TVG_OK : TVG_ERR_LAUNCH;
         }
     }

@@ -33,14 +33,19 @@ __device__ __forceinline__ uint32_t f32x2_to_bf16x2(float lo, float hi)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(f2{lo, hi}, bf2));
 }
 
-// The 16-byte output stores of the staged tail (each row of a tile leaves as 64 contiguous
-// bytes) carry the non-temporal hint: y is written once and not read again by the kernel, and
-// left as ordinary dirty lines it occupies L2 until the end of the kernel, where the write-back
-// then delays the next launch (measured on the twelve-layer step: 333 us with plain stores,
-// 299 us with these).  Narrow stores stay plain: with the hint the element-wise tail of the
-// 7x7 layers was 30-60 % slower.
-template <typename V>
-__device__ __forceinline__ void stream_store(V *p, V v) { __builtin_nontemporal_store(v, p); }
+// Output store with or without the non-temporal hint (the TVG_STREAM_OUT flag of the call), a
+// compile-time choice: the wide stores of the staged tail and of the depthwise kernels take
+// it.  With the hint y neither displaces the operands in L2 nor waits there, dirty, for the
+// write-back at the end of the kernel (measured on twelve unrelated layers in a row: 333 us
+// plain, 299 us hinted); without it the next kernel finds y in the memory-side cache (measured
+// on the 21-launch ResNet-18 chain at batch 32: 0.437 ms plain, 0.450 ms hinted).  Narrow
+// stores are always plain: hinted, the element-wise tail of 7x7 maps was 30-60 % slower.
+template <bool NT, typename V>
+__device__ __forceinline__ void stream_store(V *p, V v)
+{
+    if constexpr (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
 
 // Exact floor division of small non-negative integers through the float reciprocal:
 // a and b below 2^22, inv_b = 1.0f / b.  The float quotient is within one of the true
@@ -102,7 +107,7 @@ struct TailArgs {
     const float *scale, *shift, *bias;
     const void *residual;
     void *y;
-    int OC, OHW, npix, relu;
+    int OC, OHW, npix, relu;      // relu: bit 0 = ReLU, bit 1 = hinted stores on the staged fast path
 };
 
 constexpr int kStageRow = 80;                          // bytes per staged channel row
@@ -167,7 +172,7 @@ __device__ __forceinline__ void store_tile(const float16v &acc, unsigned char *s
     const int lrow = lane & 31, lhalf = lane >> 5;
     const int oc = oc0 + lrow;
     const float sc = ss[2 * (row0 + lrow)], sf = ss[2 * (row0 + lrow) + 1];
-    const float floor_v = t.relu ? 0.0f : -INFINITY;     // no ReLU = clamp at minus infinity
+    const float floor_v = (t.relu & 1) ? 0.0f : -INFINITY;     // no ReLU = clamp at minus infinity
     const T *res = static_cast<const T *>(t.residual);
     T *y = static_cast<T *>(t.y);
     // image index of the tile's first pixel: uniform, one scalar division; later pixels
@@ -200,8 +205,8 @@ __device__ __forceinline__ void store_tile(const float16v &acc, unsigned char *s
             const int b2 = (n0 * t.OC + oc0 + row) * t.OHW + rem0 + 8 * g;
 #pragma unroll
             for (int it = 0; it < 2; ++it)
-                stream_store(reinterpret_cast<uint4v *>(y + b2 + it * 16 * t.OHW),
-                             *reinterpret_cast<const uint4v *>(stage + (row + 16 * it) * kStageRow + g * 16));
+                *reinterpret_cast<uint4v *>(y + b2 + it * 16 * t.OHW) =
+                    *reinterpret_cast<const uint4v *>(stage + (row + 16 * it) * kStageRow + g * 16);
             __builtin_amdgcn_wave_barrier();
         }
         return;
@@ -256,8 +261,8 @@ __device__ __forceinline__ void store_tile(const float16v &acc, unsigned char *s
                     int n = n0, rem = rem0 + 8 * g;
                     while (rem >= t.OHW) { rem -= t.OHW; ++n; }
                     const int idx = (n * t.OC + c) * t.OHW + rem;
-                    stream_store(reinterpret_cast<uint4v *>(y + idx),
-                                 *reinterpret_cast<const uint4v *>(stage + row * kStageRow + g * 16));
+                    *reinterpret_cast<uint4v *>(y + idx) =
+                        *reinterpret_cast<const uint4v *>(stage + row * kStageRow + g * 16);
                 }
             }
             __builtin_amdgcn_wave_barrier();
@@ -282,7 +287,7 @@ __device__ __forceinline__ void store_acc_tiles(const float16v (&acc)[MI][NJ], u
 
 // The fast-path body of store_acc_tiles_batched: tile (i, j) starts at channel ocu + 32 i and
 // at pixel rem0[j] of image n0[j]; everything is in range.  BT tiles share one LDS round trip.
-template <int MI, int NJ, int BT, bool HAS_RES>
+template <int MI, int NJ, int BT, bool HAS_RES, bool NT>
 __device__ __forceinline__ void store_fast_tiles(const float16v (&acc)[MI][NJ], unsigned char *stage,
                                                  int lane, int ocu, const int (&n0)[NJ],
                                                  const int (&rem0)[NJ], const TailArgs &t,
@@ -290,7 +295,7 @@ __device__ __forceinline__ void store_fast_tiles(const float16v (&acc)[MI][NJ], 
 {
     constexpr int T = MI * NJ;
     const int lrow = lane & 31, lhalf = lane >> 5;
-    const float floor_v = t.relu ? 0.0f : -INFINITY;
+    const float floor_v = (t.relu & 1) ? 0.0f : -INFINITY;
     const bf16_t *res = static_cast<const bf16_t *>(t.residual);
     bf16_t *y = static_cast<bf16_t *>(t.y);
     const int row = lane >> 2, g = lane & 3;
@@ -332,8 +337,8 @@ __device__ __forceinline__ void store_fast_tiles(const float16v (&acc)[MI][NJ], 
                 const int b2 = (n0[j] * t.OC + ocu + i * 32 + row) * t.OHW + rem0[j] + 8 * g;
 #pragma unroll
                 for (int it = 0; it < 2; ++it)
-                    stream_store(reinterpret_cast<uint4v *>(y + b2 + it * 16 * t.OHW),
-                                 *reinterpret_cast<const uint4v *>(st + (row + 16 * it) * kStageRow + g * 16));
+                    stream_store<NT>(reinterpret_cast<uint4v *>(y + b2 + it * 16 * t.OHW),
+                                     *reinterpret_cast<const uint4v *>(st + (row + 16 * it) * kStageRow + g * 16));
             }
         }
         __builtin_amdgcn_wave_barrier();
@@ -370,10 +375,15 @@ __device__ __forceinline__ void store_acc_tiles_batched(const float16v (&acc)[MI
         return;
     }
     // the residual test is hoisted out: a branch per group would fence the tiles from each other
-    if (t.residual)
-        store_fast_tiles<MI, NJ, BT, true>(acc, stage, lane, ocu, n0, rem0, t, ss, row_base);
-    else
-        store_fast_tiles<MI, NJ, BT, false>(acc, stage, lane, ocu, n0, rem0, t, ss, row_base);
+    // (so is the store hint, a compile-time property of the store instruction)
+    const bool nt = (t.relu & 2) != 0;
+    if (t.residual) {
+        if (nt) store_fast_tiles<MI, NJ, BT, true, true>(acc, stage, lane, ocu, n0, rem0, t, ss, row_base);
+        else store_fast_tiles<MI, NJ, BT, true, false>(acc, stage, lane, ocu, n0, rem0, t, ss, row_base);
+    } else {
+        if (nt) store_fast_tiles<MI, NJ, BT, false, true>(acc, stage, lane, ocu, n0, rem0, t, ss, row_base);
+        else store_fast_tiles<MI, NJ, BT, false, false>(acc, stage, lane, ocu, n0, rem0, t, ss, row_base);
+    }
 }
 
 // Host side: the store mode the problem allows (see store_tile).

@@ -20,6 +20,7 @@ struct ConvProblem {
     int npix;       // N * OH * OW, the number of GEMM columns
     int dtype;      // tvg_dtype
     int relu;
+    int stream_out; // TVG_STREAM_OUT: y is stored with the non-temporal hint
 };
 
 struct ConvPointers {

@@ -42,7 +42,7 @@ def test_struct_layout_matches_header():
     (dict(n=0), 2), (dict(c=-1), 2), (dict(h=0), 2), (dict(k=0), 2), (dict(r=0), 2),
     (dict(stride_h=0), 2), (dict(stride_w=9), 2), (dict(pad_h=-1), 2), (dict(pad_h=3), 2),
     (dict(h=1, w=1, r=5, s=5, pad_h=1, pad_w=1), 2),          # empty output
-    (dict(dtype=2), 3), (dict(flags=2), 3), (dict(r=17, s=17, pad_h=8, pad_w=8, h=40, w=40), 3),
+    (dict(dtype=2), 3), (dict(flags=4), 3), (dict(flags=8 | 1), 3), (dict(r=17, s=17, pad_h=8, pad_w=8, h=40, w=40), 3),
     (dict(n=64, c=4096, h=256, w=256), 3),                    # 2^34 input elements
 ])
 def test_conv_rejects_bad_descriptors_on_the_host(kw, status):

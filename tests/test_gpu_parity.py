@@ -11,11 +11,11 @@ from _util import TOL, dev_inputs, rel_err, to_dev, to_host
 pytestmark = pytest.mark.gpu
 
 
-def run_dense(tvg, sh, inp, dtype, relu=True):
+def run_dense(tvg, sh, inp, dtype, relu=True, stream_out=False):
     import torch
     d = dev_inputs(inp, dtype)
     y = tvg.conv2d_fused(d["x"], d["w"], d["scale"], d["shift"], d["bias"], d["residual"],
-                         stride=sh.stride, pad=sh.pad, relu=relu)
+                         stride=sh.stride, pad=sh.pad, relu=relu, stream_out=stream_out)
     torch.cuda.synchronize()
     return y
 
@@ -40,7 +40,10 @@ def test_config3_depthwise_fp32_batch1(tvg, i):
     inp = ti.make_inputs(sh, ti.layer_seed(3, i), "f32")
     d = dev_inputs(inp, "f32")
     y = tvg.dwconv2d_fused(d["x"], d["w"], d["scale"], d["shift"], stride=sh.stride, pad=1, relu=True)
+    hinted = tvg.dwconv2d_fused(d["x"], d["w"], d["scale"], d["shift"], stride=sh.stride, pad=1,
+                                relu=True, stream_out=True)
     torch.cuda.synchronize()
+    assert torch.equal(y, hinted)                 # the store hint changes no value
     want = oracle.dwconv2d_fused(inp["x"], inp["w"], inp["scale"], inp["shift"],
                                  stride=(sh.stride,) * 2, pad=(1, 1), relu=True)
     assert tuple(y.shape) == sh.y_shape()
@@ -76,8 +79,11 @@ def test_depthwise_batch64_sampled(tvg):
     sh = ti.mobilenet_depthwise(64)[2]
     inp = ti.make_inputs(sh, ti.layer_seed(3, 102), "f32")
     d = dev_inputs(inp, "f32")
-    y = tvg.dwconv2d_fused(d["x"], d["w"], d["scale"], d["shift"], stride=1, pad=1, relu=True)
+    y = tvg.dwconv2d_fused(d["x"], d["w"], d["scale"], d["shift"], stride=1, pad=1, relu=True,
+                           stream_out=True)       # as bench.py launches it
+    plain = tvg.dwconv2d_fused(d["x"], d["w"], d["scale"], d["shift"], stride=1, pad=1, relu=True)
     torch.cuda.synchronize()
+    assert torch.equal(y, plain)                  # the store hint changes no value
     got = to_host(y)
     for n in (0, 63):
         want = oracle.dwconv2d_fused(inp["x"][n:n + 1], inp["w"], inp["scale"], inp["shift"],
@@ -321,9 +327,12 @@ def test_output_may_alias_residual(tvg):
 def test_config4_resnet18_shapes_bf16_batch64_sampled(tvg, i):
     """Full-size launch (the configuration bench.py times); the oracle evaluates a sample of
     outputs one by one: the first and last tile plus random positions."""
+    import torch
     sh = ti.resnet18_convs(64)[i]
     inp = ti.make_inputs(sh, ti.layer_seed(4, i), "bf16")
-    y = run_dense(tvg, sh, inp, "bf16")
+    y = run_dense(tvg, sh, inp, "bf16", stream_out=True)      # as bench.py launches it
+    # the store hint changes no value: bit-identical to the plain launch
+    assert torch.equal(y.view(torch.int16), run_dense(tvg, sh, inp, "bf16").view(torch.int16))
     got = to_host(y).reshape(-1)
     rng = np.random.default_rng(i)
     total = got.size
@@ -414,6 +423,61 @@ def test_config5_resnet18_body_bf16_small_batch_full(tvg):
     rho = float(np.sqrt(np.mean(r * r)))
     assert float(np.sqrt(np.mean((g - r) ** 2))) / rho <= 2e-2
     assert rel_err(g, r) <= 8e-2
+
+
+def test_config5_resnet18_body_hip_graph_replays_match_eager(tvg):
+    """The 21-launch chain recorded once into a HIP graph: the library allocates nothing and
+    never synchronises, so it records as it stands.  Three replays, each on new images written
+    into the captured input buffer, with eager launches and synchronisations between them;
+    every tensor of every replay is bit-identical to the eager chain on the same images."""
+    import torch
+    steps = ti.resnet18_body(2)
+    weights = body_weights(steps)
+    dev_w = {k: {n: to_dev(v, "bf16" if n == "w" else "f32") for n, v in p.items()}
+             for k, p in weights.items()}
+    images = to_dev(ti.body_images(2, ti.layer_seed(5, 900)), "bf16")
+    tensors, calls = {0: images}, []
+    for st in steps:
+        src = tensors[st.src]
+        if st.op == "conv":
+            sh, p = st.shape, dev_w[st.layer_index]
+            desc = tvg.ConvDesc(sh.n, sh.ic, sh.h, sh.w, sh.oc, sh.r, sh.s, sh.stride, sh.stride,
+                                sh.pad, sh.pad, tvg.TVG_BF16, tvg.TVG_RELU if st.relu else 0)
+            y = torch.empty(sh.y_shape(), dtype=torch.bfloat16, device="cuda:0")
+            need = tvg.tvg_conv2d_workspace_size(desc)
+            ws = torch.empty(max(need, 1), dtype=torch.uint8, device="cuda:0")
+            res = None if st.residual is None else tensors[st.residual]
+            calls.append((tvg.tvg_conv2d_fused, (desc, src, p["w"], p["scale"], p["shift"], None,
+                                                 res, y, ws, need, None)))
+        else:
+            n, c, h, w = src.shape
+            y = torch.empty((n, c, (h - 1) // 2 + 1, (w - 1) // 2 + 1), dtype=torch.bfloat16,
+                            device="cuda:0")
+            calls.append((tvg.tvg_maxpool2d_3x3s2, (n, c, h, w, tvg.TVG_BF16, src, y, None)))
+        tensors[st.dst] = y
+
+    def forward():          # stream=None: the binding launches on torch's current stream
+        for fn, a in calls:
+            assert fn(*a) == 0
+
+    forward()               # one-time kernel attributes are set outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=torch.cuda.Stream()):
+        forward()
+    for rep in range(3):
+        images.copy_(to_dev(ti.body_images(2, ti.layer_seed(5, 910 + rep)), "bf16"))
+        forward()
+        torch.cuda.synchronize()
+        want = {k: t.clone() for k, t in tensors.items()}
+        for k, t in tensors.items():
+            if k != 0:
+                t.fill_(float("nan"))       # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k, t in tensors.items():
+            assert torch.equal(t.view(torch.int16), want[k].view(torch.int16)), (rep, k)
 
 
 def test_config5_resnet18_body_bf16_batch32_teacher_forced(tvg):
