@@ -162,7 +162,7 @@ template <> struct Group4<float> {
 // acc: one 32x32 accumulator tile in the D[pixel][channel] orientation described above.
 // oc0 / p0: output channel of column 0 / flattened pixel of row 0 (a multiple of 32).
 // ss: staged (scale, offset) pairs of the workgroup tile, row0: index of oc0 in that tile.
-// stage: kStageBytes of wave-private LDS (mode 8 only).
+// stage: kStageBytes of wave-private LDS (used by bf16 modes 8 and 1).
 template <typename T>
 __device__ __forceinline__ void store_tile(const float16v &acc, unsigned char *stage, int lane,
                                            int oc0, int p0, const TailArgs &t, int vmode,
@@ -210,6 +210,51 @@ __device__ __forceinline__ void store_tile(const float16v &acc, unsigned char *s
             __builtin_amdgcn_wave_barrier();
         }
         return;
+    }
+
+    if constexpr (sizeof(T) == 2) {
+        if (vmode == 1) {
+            // Odd-sized maps (7x7 = 49 pixels): nothing is aligned, every element is stored on
+            // its own.  In the accumulator layout a store instruction would scatter its 64
+            // two-byte elements over 64 cache lines (measured: 2-4 us of tail on the 7x7
+            // layers, the address unit taking a line per cycle); transposed through the
+            // stage, its lanes write two channel rows of 32 adjacent pixels.  The residual
+            // comes in the same way.
+            const int px = lane & 31, rsel = lane >> 5;
+            int n = n0, rem = rem0 + px;
+            while (rem >= t.OHW) { rem -= t.OHW; ++n; }
+            const bool pok = p0 + px < t.npix;
+            const int rbase = (n * t.OC + oc0) * t.OHW + rem;        // (row 0, this lane's pixel)
+            if (res) {
+#pragma unroll
+                for (int it = 0; it < 16; ++it) {
+                    const int row = 2 * it + rsel;
+                    T v = 0;
+                    if (pok && oc0 + row < t.OC) v = res[rbase + row * t.OHW];
+                    *reinterpret_cast<T *>(stage + row * kStageRow + px * 2) = v;
+                }
+                __builtin_amdgcn_wave_barrier();
+            }
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                gvec *slot = reinterpret_cast<gvec *>(stage + lrow * kStageRow + (8 * gq + 4 * lhalf) * 2);
+                float f[4], r[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+                if (res) Group4<T>::unpack(*slot, r);
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    f[q] = fmaxf(fmaf(acc[4 * gq + q], sc, sf) + r[q], floor_v);
+                *slot = Group4<T>::pack(f);
+            }
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int it = 0; it < 16; ++it) {
+                const int row = 2 * it + rsel;
+                if (pok && oc0 + row < t.OC)
+                    y[rbase + row * t.OHW] = *reinterpret_cast<const T *>(stage + row * kStageRow + px * 2);
+            }
+            __builtin_amdgcn_wave_barrier();
+            return;
+        }
     }
 
     if (vmode == 1) {
