@@ -141,6 +141,10 @@ PATCH_RAGGED = [
     (3, 16, 9, 11, 40, 1), (2, 32, 10, 13, 70, 2), (5, 48, 7, 7, 130, 1), (4, 16, 5, 6, 8, 2),
     (1, 64, 1, 1, 64, 1), (2, 16, 2, 3, 16, 2), (1, 16, 30, 70, 16, 1), (1, 16, 33, 120, 200, 2),
     (7, 32, 7, 7, 64, 2), (2, 16, 14, 14, 256, 1), (3, 16, 56, 56, 64, 1), (2, 16, 57, 55, 32, 2),
+    # stride 2 with rows that take 8-byte and 16-byte loads (W % 4 == 0, W % 8 == 0): even and
+    # odd columns are stored apart, several images per tile, ragged tails
+    (2, 32, 28, 28, 96, 2), (3, 16, 12, 12, 40, 2), (1, 48, 20, 36, 64, 2), (2, 16, 16, 24, 64, 2),
+    (5, 16, 9, 8, 33, 2), (9, 32, 4, 4, 64, 2),
 ]
 
 
