@@ -95,7 +95,9 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
     constexpr int WTM = MT / WM, WTN = NJ * 32, NT = WN * WTN;
     constexpr int MI = WTM / 32;
     constexpr int PW32 = PX >= 2 ? PX / 2 : 1;        // registers per patch load
-    constexpr int kLoads = 9 + 8 * PT;                // vector memory loads per thread and chunk
+    constexpr int kWLoads = 5;                        // a weight task's 72 bytes: 4 x 16 + 8
+    constexpr int kLoads = kWLoads + 8 * PT;          // vector memory loads per thread and chunk
+    constexpr int kP0 = 9 + kWLoads;                  // first patch item
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
@@ -147,11 +149,11 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
     // the MFMAs of an earlier chunk.  A register is reloaded right after the item that consumed
     // it (chunk c+1) - with chunk c+3, the other set holding chunk c+2:
     //   0..8    transpose filter tap i of the weights into the stage
-    //   9..17   load 8 bytes of the weight row
+    //   9..13   load the weight task's 72-byte run (4 x 16 bytes + 8 bytes)
     //   then per patch task: PX transposes (one pixel each), 8 loads (one channel each)
     // `set` = which register set the item works on = which stage a transpose writes to;
     // cbase = byte offset of the chunk to load within an image of x.
-    constexpr int kItems = 18 + PT * (PX + 8);
+    constexpr int kItems = kP0 + PT * (PX + 8);
     auto work_item = [&](int it, int set, bool do_pack, bool do_load, int c, int cbase) __attribute__((always_inline)) {
         if (it < 9) {
             if (!do_pack) return;
@@ -163,15 +165,23 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
                 o[q] = pack_halves(wraw[set][e0 >> 1], e0 & 1, wraw[set][e1 >> 1], e1 & 1);
             }
             *reinterpret_cast<uint2v *>(smem + wbase[set] + tap * MT * 16) = uint2v{o[0], o[1]};
-        } else if (it < 18) {
+        } else if (it < kP0) {
             if (!do_load) return;
+            // the task's run of 72 bytes starts 8-byte aligned: 16-byte loads need 4
             const int i = it - 9;
-            const uint2v t2 = __builtin_bit_cast(
-                uint2v, __builtin_amdgcn_raw_buffer_load_b64(wrsrc, woff + i * 8, c * kChunk * 9 * 2, 0));
-            wraw[set][2 * i] = t2[0];
-            wraw[set][2 * i + 1] = t2[1];
+            if (i < 4) {
+                const uint4v t4 = __builtin_bit_cast(
+                    uint4v, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, woff + i * 16, c * kChunk * 9 * 2, 0));
+#pragma unroll
+                for (int d = 0; d < 4; ++d) wraw[set][4 * i + d] = t4[d];
+            } else {
+                const uint2v t2 = __builtin_bit_cast(
+                    uint2v, __builtin_amdgcn_raw_buffer_load_b64(wrsrc, woff + 64, c * kChunk * 9 * 2, 0));
+                wraw[set][16] = t2[0];
+                wraw[set][17] = t2[1];
+            }
         } else {
-            const int j = (it - 18) / (PX + 8), r = (it - 18) % (PX + 8);
+            const int j = (it - kP0) / (PX + 8), r = (it - kP0) % (PX + 8);
             if (r < PX) {
                 if (!do_pack) return;
                 const int k = r;
@@ -212,7 +222,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
 
     // The first chunk's loads go out as early as their addresses are known - the weights
     // first, they need no geometry - and the rest of the set-up runs under their latency.
-    all_items(9, 18, 0, false, true, 0);
+    all_items(9, kP0, 0, false, true, 0);
     // likewise the tile's per-channel multiplier and offset, needed only by the fused tail
     float ss_scale = 0.0f, ss_shift = 0.0f, ss_bias = 0.0f;
     if (tid < MT && m0 + tid < a.OC) {
@@ -256,7 +266,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
             pwbase[1][j] = pwbase[0][j] + stage_bytes;
         }
     }
-    all_items(18, kItems, 0, false, true, 0);
+    all_items(kP0, kItems, 0, false, true, 0);
     // The second chunk goes into the other register set (the channel count is a multiple of
     // 32).  A vector memory instruction takes the address unit some 60 cycles, and a wave issues
     // in order: its loads are dealt out between the pieces of set-up arithmetic that follow,
