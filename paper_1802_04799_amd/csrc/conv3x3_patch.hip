@@ -360,8 +360,8 @@ tvg_status launch_instance(const PatchArgs &a, int ntiles, size_t lds, hipStream
 template <int MT, int NT, int STRIDE>
 tvg_status launch_pt(const PatchArgs &a, int ntiles, size_t lds, int pt, int px, hipStream_t stream)
 {
-    if constexpr (STRIDE == 2) {
-        // stride-2 patches are four times the output tile: wide loads keep the count down
+    {
+        // wide loads keep the number of vector memory instructions down
         if (px == 8) {
             if (pt <= 1) return launch_instance<MT, NT, STRIDE, 1, 8>(a, ntiles, lds, stream);
             return launch_instance<MT, NT, STRIDE, 2, 8>(a, ntiles, lds, stream);
@@ -422,12 +422,13 @@ bool plan_conv3x3_patch(const ConvProblem &p, Patch3x3Plan *plan)
         const int rows = max_patch_rows(p, nt);
         // two pixels per load when the rows are even (32-bit aligned pairs) and that keeps the
         // task count within the instances built for it
-        // (stride 1: four pixels per load were measured too, no gain over two)
         int px = p.W % 2 == 0 ? 2 : 1;
-        if (p.sh == 2) {
-            // a stride-2 patch is four times the output tile: 16- or 8-byte loads where the
-            // rows allow them (x is 16-byte aligned, and so is every row when W % 8 == 0)
-            // (measured at batch 64, with the split rows: C4 26.0 -> 24.2 us; C7 unchanged)
+        // 16- or 8-byte loads where the rows allow them (x is 16-byte aligned, and so is every
+        // row when W % 8 == 0): a stride-2 patch is four times the output tile (measured at
+        // batch 64 with the split rows: C4 26.0 -> 24.2 us, C7 unchanged); at stride 1 they pay
+        // under the 256-pixel tile only (C2 30.5 -> 28.9 us; under 64x128 31.4 -> 32.9: the wider
+        // a task, the more of its lanes' 16-byte LDS stores fall on the same banks)
+        if (p.sh == 2 || nt == 256) {
             if (p.W % 8 == 0 && (2 * rows * (p.W / 8) + 255) / 256 <= 2) px = 8;
             else if (p.W % 4 == 0 && (2 * rows * (p.W / 4) + 255) / 256 <= 4) px = 4;
         }
