@@ -116,16 +116,20 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
 
     // ---- per-thread patch load tasks: (virtual row, iw, channel octet), fixed for all chunks
     uint32_t goff[PT];      // byte offset of the task's first channel within a chunk of x
-    int loff[PT];           // byte offset of its 16-byte slot in the patch, -1 = nothing to do
+    int loff[PT];           // byte offset of its 16-byte slot in the patch
+    int nvalid[PT];         // pixels of the task to store: 0 = nothing to do, < PX = the row's ragged end
     {
-        const int WPX = W / PX;
+        // a row that is not a multiple of PX ends in a task with fewer pixels; its load reads on
+        // into the next row (or, at the very end of x, past the buffer: zeros), 4-byte aligned
+        const int WPX = (W + PX - 1) / PX;
         const float inv_wpx = 1.0f / (float)WPX;
         const int per_octet = nrows * WPX;
 #pragma unroll
         for (int j = 0; j < PT; ++j) {
             const int t = tid + j * 256;
             goff[j] = 0;
-            loff[j] = -1;
+            loff[j] = 0;
+            nvalid[j] = 0;
             if (t < 2 * per_octet) {
                 const int octet = t >= per_octet;
                 const int rem = t - octet * per_octet;
@@ -139,6 +143,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
                     const int col = iw + 1;       // patch column (0 = left padding)
                     const int pos = STRIDE == 2 ? ((col & 1) ? HALF + (col >> 1) : (col >> 1)) : col;
                     loff[j] = (vrow * PW + pos) * kPosBytes + octet * 16;
+                    nvalid[j] = min(PX, W - iw);
                 }
             }
         }
@@ -212,23 +217,29 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
 
     auto store_chunk = [&]() {
 #pragma unroll
-        for (int j = 0; j < PT; ++j)
-            if (loff[j] >= 0) {
-                // pixel k of the task sits in half (k & 1) of register k >> 1 of each channel
+        for (int j = 0; j < PT; ++j) {
+            // pixel k of the task sits in half (k & 1) of register k >> 1 of each channel;
+            // rows are even when PX > 1, so a ragged task ends on a pixel pair
+            constexpr int STEP = PX > 1 ? 2 : 1;
 #pragma unroll
-                for (int k = 0; k < PX; ++k) {
-                    uint32_t o[4];
+            for (int k0 = 0; k0 < PX; k0 += STEP) {
+                if (k0 < nvalid[j]) {
 #pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        o[q] = half_of(praw[j][2 * q][k >> 1], k & 1) |
-                               (half_of(praw[j][2 * q + 1][k >> 1], k & 1) << 16);
-                    // stride 2 (PX > 1: the task starts on an odd patch column): pixels
-                    // alternate between the odd and the even half of the row
-                    const int koff = STRIDE == 2 ? ((k & 1) ? (1 - HALF) * kPosBytes : 0) + (k >> 1) * kPosBytes
-                                                 : k * kPosBytes;
-                    *reinterpret_cast<uint4v *>(Ps + loff[j] + koff) = uint4v{o[0], o[1], o[2], o[3]};
+                    for (int k = k0; k < k0 + STEP; ++k) {
+                        uint32_t o[4];
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            o[q] = half_of(praw[j][2 * q][k >> 1], k & 1) |
+                                   (half_of(praw[j][2 * q + 1][k >> 1], k & 1) << 16);
+                        // stride 2 (PX > 1: the task starts on an odd patch column): pixels
+                        // alternate between the odd and the even half of the row
+                        const int koff = STRIDE == 2 ? ((k & 1) ? (1 - HALF) * kPosBytes : 0) + (k >> 1) * kPosBytes
+                                                     : k * kPosBytes;
+                        *reinterpret_cast<uint4v *>(Ps + loff[j] + koff) = uint4v{o[0], o[1], o[2], o[3]};
+                    }
                 }
             }
+        }
         if (wtask) {
             // wreg holds 8 channels x 9 taps, tap fastest; emit one 8-channel vector per tap
             uint32_t d[36];
@@ -428,11 +439,13 @@ bool plan_conv3x3_patch(const ConvProblem &p, Patch3x3Plan *plan)
         // batch 64 with the split rows: C4 26.0 -> 24.2 us, C7 unchanged); at stride 1 they pay
         // under the 256-pixel tile only (C2 30.5 -> 28.9 us; under 64x128 31.4 -> 32.9: the wider
         // a task, the more of its lanes' 16-byte LDS stores fall on the same banks)
-        if (p.sh == 2 || nt == 256) {
-            if (p.W % 8 == 0 && (2 * rows * (p.W / 8) + 255) / 256 <= 2) px = 8;
-            else if (p.W % 4 == 0 && (2 * rows * (p.W / 4) + 255) / 256 <= 4) px = 4;
+        if ((p.sh == 2 || nt == 256) && p.W % 2 == 0) {
+            // (a row that is no multiple of the load ends in a shorter task, loads 4-byte aligned)
+            const auto tasks = [&](int q) { return (2 * rows * ((p.W + q - 1) / q) + 255) / 256; };
+            if (p.W >= 8 && tasks(8) <= 2 && (p.W % 8 == 0 || tasks(8) < tasks(4))) px = 8;
+            else if (p.W >= 4 && tasks(4) <= 4) px = 4;
         }
-        int pt = (2 * rows * (p.W / px) + 255) / 256;
+        int pt = (2 * rows * ((p.W + px - 1) / px) + 255) / 256;
         if (px == 2 && pt > 4) { px = 1; pt = (2 * rows * p.W + 255) / 256; }
         const size_t lds = (size_t)9 * mt * kPosBytes + (size_t)rows * (p.W + 2) * kPosBytes +
                            (size_t)mt * 8;      // operands + (scale, offset) pairs

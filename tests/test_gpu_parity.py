@@ -145,6 +145,10 @@ PATCH_RAGGED = [
     # odd columns are stored apart, several images per tile, ragged tails
     (2, 32, 28, 28, 96, 2), (3, 16, 12, 12, 40, 2), (1, 48, 20, 36, 64, 2), (2, 16, 16, 24, 64, 2),
     (5, 16, 9, 8, 33, 2), (9, 32, 4, 4, 64, 2),
+    # rows that are even but no multiple of the load: the last task of a row is short, and the
+    # last load of the tensor reaches past its end
+    (3, 32, 14, 14, 64, 2), (2, 16, 10, 10, 40, 2), (1, 16, 9, 18, 64, 2), (2, 16, 6, 22, 33, 2),
+    (1, 16, 3, 6, 8, 1), (64, 32, 14, 14, 64, 2),
 ]
 
 
