@@ -373,10 +373,30 @@ __device__ __forceinline__ void store_fast_tiles(const float16v (&acc)[MI][NJ], 
             }
         }
         __builtin_amdgcn_wave_barrier();
+        // Two staged tiles that are neighbours along the pixels (same channels, the next 32
+        // pixels of the same image) leave together: eight lanes write the 128 contiguous bytes
+        // of a channel row - a whole cache line when the map size is a multiple of 64 -
+        // instead of two instructions writing half of it each.
+        constexpr bool kPairs = BT % 2 == 0 && NJ % 2 == 0;
 #pragma unroll
         for (int k = 0; k < BT; ++k) {
             const int tix = b0 + k < T ? b0 + k : T - 1;
             const int i = tix / NJ, j = tix % NJ;
+            if constexpr (kPairs) {
+                // (b0 and NJ even: tiles k, k + 1 of an even k share their channel block)
+                const int jn = j + 1 < NJ ? j + 1 : j;
+                if (k % 2 == 0 && n0[jn] == n0[j]) {
+                    const int row8 = lane >> 3, g8 = lane & 7;
+                    const unsigned char *st = stage + (k + (g8 >> 2)) * kStageBytes;
+                    const int b2 = (n0[j] * t.OC + ocu + i * 32 + row8) * t.OHW + rem0[j] + 8 * g8;
+#pragma unroll
+                    for (int it = 0; it < 4; ++it)
+                        stream_store<NT>(reinterpret_cast<uint4v *>(y + b2 + it * 8 * t.OHW),
+                                         *reinterpret_cast<const uint4v *>(st + (row8 + 8 * it) * kStageRow + (g8 & 3) * 16));
+                    continue;
+                }
+                if (k % 2 == 1 && n0[j] == n0[j - (j > 0 ? 1 : 0)]) continue;   // left with its neighbour
+            }
             if (b0 + k < T) {
                 const unsigned char *st = stage + k * kStageBytes;
                 const int b2 = (n0[j] * t.OC + ocu + i * 32 + row) * t.OHW + rem0[j] + 8 * g;
