@@ -1,8 +1,9 @@
-// bf16 3x3 (pad 1, stride 1) fused conv2d, software-pipelined variant of the patch kernel: the
-// operand tiles of an input-channel chunk live in one of TWO LDS stages, so the registers
-// holding chunk c+1 are transposed and written to the idle stage BETWEEN the MFMAs of chunk c,
-// and one barrier per chunk is all the synchronisation left.  The global loads of chunk c+3
-// are issued as soon as those registers are free (two register sets).  (TVM paper Section 4.2:
+// bf16 3x3 (pad 1, stride 1 or 2) fused conv2d, software-pipelined variant of the patch
+// kernel: the operand tiles of an input-channel chunk live in one of TWO LDS stages, so the
+// registers holding chunk c+1 are transposed and written to the idle stage BETWEEN the MFMAs
+// of chunk c, and one barrier per chunk is all the synchronisation left.  The global loads of
+// chunk c+3 are issued as soon as those registers are free (two register sets).  (TVM paper
+// Section 4.2:
 // cooperative fetch into the shared scope; Section 4.4: memory latency hidden behind compute -
 // here inside one workgroup instead of by switching between workgroups.)
 //
@@ -16,7 +17,9 @@
 //   A planes: [octet][tap][oc]      16 B each (+128 B between the planes: spreads the writes)
 //   P planes: [octet][virtual row][column]   16 B each
 // Virtual rows are those of the patch kernel: image n owns rows n*(H+2) .. n*(H+2)+H+1, first
-// and last being zero padding.
+// and last being zero padding.  For stride 2 a row is stored even columns first, then odd
+// columns, so that the pixels of consecutive lanes (two columns apart) are again consecutive
+// 16-byte words.
 #include <stdio.h>
 #include <stdlib.h>
 
@@ -87,7 +90,7 @@ constexpr int waitcnt_imm(int vm, int lgkm)
 // 64 x NT with NT = (4 / WM) * NJ * 32.  (Tiles of 448 and 832 pixels - one workgroup per CU with
 // 112 or 208 accumulator registers per lane - were measured: slower, a single wave per SIMD
 // issues an MFMA plus its LDS operand read in 27 ns against 16 ns for two waves.)
-template <int WM, int NJ, int PT, int PX>
+template <int WM, int NJ, int STRIDE, int PT, int PX>
 __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
 {
     constexpr int MT = kMT;
@@ -108,7 +111,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
     const int H = a.H, W = a.W, HW = H * W, OHW = a.OH * a.OW;
     const int VH = H + 2;
     // 16-byte words per patch row, and where the odd columns start (stride 2 only)
-    const int PWS = a.pws;
+    const int PWS = a.pws, PWH = PWS >> 1;
     const int stage_bytes = a.stage_bytes;
 
     // All index arithmetic divides through host-computed float reciprocals; the host admits
@@ -134,6 +137,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
 
     uint32_t goff[PT];      // byte offset of a patch task's first channel within a chunk of x
     int pwbase[2][PT];      // where the first pixel of a patch task goes
+    int pwbase2[2][PT];     // stride 2: its second pixel (the even-column half of the row)
     // two register sets: while one is transposed into LDS (chunk c+1) the other is still in
     // flight (chunk c+2), so a load has two chunks of MFMA time to arrive
     uint32_t praw[2][PT][8][PW32];
@@ -190,8 +194,10 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
                 for (int q = 0; q < 4; ++q)
                     o[q] = pack_halves(praw[set][j][2 * q][k >> 1], k & 1,
                                        praw[set][j][2 * q + 1][k >> 1], k & 1);
-                *reinterpret_cast<uint4v *>(smem + pwbase[set][j] + k * 16) =
-                    uint4v{o[0], o[1], o[2], o[3]};
+                // consecutive words; for stride 2 alternately the odd- and the even-column half
+                unsigned char *dst = STRIDE == 2 ? smem + ((k & 1) ? pwbase2[set][j] : pwbase[set][j]) + (k >> 1) * 16
+                                                 : smem + pwbase[set][j] + k * 16;
+                *reinterpret_cast<uint4v *>(dst) = uint4v{o[0], o[1], o[2], o[3]};
             } else {
                 if (!do_load) return;
                 const int q = r - PX;
@@ -239,14 +245,17 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
         na = fast_div(n0, OHW, a.inv_ohw, &ra);
         const int oha = fast_div(ra, a.OW, a.inv_ow, &t);
         const int nb = fast_div(p_last, OHW, a.inv_ohw, &rb), ohb = fast_div(rb, a.OW, a.inv_ow, &t);
-        vr_lo = na * VH + oha;
-        nrows = nb * VH + ohb + 2 - vr_lo + 1;
+        vr_lo = na * VH + oha * STRIDE;
+        nrows = nb * VH + ohb * STRIDE + 2 - vr_lo + 1;
     }
 
     // ---- per-thread patch load tasks: (virtual row, iw, channel octet), fixed for all chunks
     {
         const int WPX = W / PX;
         const int per_octet = nrows * WPX;
+        // second pixel of a stride-2 task: first pixel in an odd padded column, the second in
+        // the following even column
+        const int pair_step = 16 - PWH * 16;
 #pragma unroll
         for (int j = 0; j < PT; ++j) {
             const int t = tid + j * 256;
@@ -258,12 +267,17 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
             const int n = fast_div(vr_lo + vrow, VH, a.inv_vh, &vi);
             const int ih = vi - 1;
             const bool live = t < 2 * per_octet && ih >= 0 && ih < H && n < a.N;
+            const int col = iw + 1;
+            const int word = STRIDE == 2 ? (col & 1) * PWH + (col >> 1) : col;
             // tasks with nothing to fetch (padding rows, past the tile) load element 0 and
             // write it to a dump area behind the planes, so that no store needs a predicate
             goff[j] = live ? 2u * (uint32_t)((n * a.IC + octet * 8) * HW + ih * W + iw) : 0u;
-            pwbase[0][j] = live ? 2 * kAPlane + octet * a.pplane + (vrow * PWS + iw + 1) * 16 + (n - na) * a.xp16
-                                : 2 * kAPlane + 2 * a.pplane + (tid & 15) * (PX > 1 ? PX * 16 : 32);
+            pwbase[0][j] = live ? 2 * kAPlane + octet * a.pplane + (vrow * PWS + word) * 16 + (n - na) * a.xp16
+                                : 2 * kAPlane + 2 * a.pplane + (tid & 15) * (PX > 1 ? PX * 16 : 32) +
+                                      (STRIDE == 2 && PX > 1 ? 16 - pair_step : 0);
             pwbase[1][j] = pwbase[0][j] + stage_bytes;
+            pwbase2[0][j] = pwbase[0][j] + pair_step;
+            pwbase2[1][j] = pwbase[1][j] + pair_step;
         }
     }
     all_items(kP0, kItems, 0, false, true, 0);
@@ -291,7 +305,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
         const int n = fast_div(p, OHW, a.inv_ohw, &rem);
         const int oh = fast_div(rem, a.OW, a.inv_ow, &ow);
         bpix[j] = 2 * kAPlane + lhalf * a.pplane +
-                  (p < a.npix ? ((n * VH + oh - vr_lo) * PWS + ow) * 16 + (n - na) * a.xp16 : 0);
+                  (p < a.npix ? ((n * VH + oh * STRIDE - vr_lo) * PWS + ow) * 16 + (n - na) * a.xp16 : 0);
     }
     int abase[2];
     abase[0] = lhalf * kAPlane + (wm * WTM + lrow) * 16;
@@ -342,7 +356,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
     auto fetch_b = [&](const int (&rowoff)[3], int q) __attribute__((always_inline)) {
         const int tap = q / NJ, j = q % NJ, r = tap / 3, s = tap - r * 3;
         bfr[q % kRing] = *reinterpret_cast<const uint4v *>(
-            smem + bpix[j] + rowoff[r] + s * 16);
+            smem + bpix[j] + rowoff[r] + (STRIDE == 2 ? (s & 1) * PWH * 16 + (s >> 1) * 16 : s * 16));
     };
     // One filter tap of chunk c (stage PAR): request later operands, then this tap's MFMAs, each
     // followed by its share of the staging items of chunks c+1 (transposes into the other
@@ -436,10 +450,10 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
                                         a.vmode, ss_lds, wm * WTM);
 }
 
-template <int WM, int NJ, int PT, int PX>
+template <int WM, int NJ, int STRIDE, int PT, int PX>
 tvg_status launch_instance(const DbufArgs &a, size_t lds, hipStream_t stream)
 {
-    auto kernel = conv3x3_dbuf_kernel<WM, NJ, PT, PX>;
+    auto kernel = conv3x3_dbuf_kernel<WM, NJ, STRIDE, PT, PX>;
     static bool configured = false;      // opt in to > 64 KB of dynamic LDS once per instance
     if (!configured) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
@@ -452,19 +466,34 @@ tvg_status launch_instance(const DbufArgs &a, size_t lds, hipStream_t stream)
 }
 
 template <int WM, int NJ>
-tvg_status launch_pt(const DbufArgs &a, size_t lds, int pt, int px, hipStream_t stream)
+tvg_status launch_pt(const DbufArgs &a, size_t lds, int stride, int pt, int px, hipStream_t stream)
 {
+    if (stride == 2) {
+        // instances exist for the 128- and 256-pixel tiles and even rows (see the plan)
+        if constexpr (NJ == 2) {
+            if (px == 8) return launch_instance<WM, NJ, 2, 1, 8>(a, lds, stream);
+            if (px == 4) {
+                if (pt <= 1) return launch_instance<WM, NJ, 2, 1, 4>(a, lds, stream);
+                return launch_instance<WM, NJ, 2, 2, 4>(a, lds, stream);
+            }
+            if (px == 2) {
+                if (pt <= 2) return launch_instance<WM, NJ, 2, 2, 2>(a, lds, stream);
+                return launch_instance<WM, NJ, 2, 4, 2>(a, lds, stream);
+            }
+        }
+        return TVG_ERR_UNSUPPORTED;
+    }
     switch (px) {
-    case 8: return launch_instance<WM, NJ, 1, 8>(a, lds, stream);
+    case 8: return launch_instance<WM, NJ, 1, 1, 8>(a, lds, stream);
     case 4:
-        if (pt <= 1) return launch_instance<WM, NJ, 1, 4>(a, lds, stream);
-        return launch_instance<WM, NJ, 2, 4>(a, lds, stream);
+        if (pt <= 1) return launch_instance<WM, NJ, 1, 1, 4>(a, lds, stream);
+        return launch_instance<WM, NJ, 1, 2, 4>(a, lds, stream);
     case 2:
-        if (pt <= 2) return launch_instance<WM, NJ, 2, 2>(a, lds, stream);
-        return launch_instance<WM, NJ, 4, 2>(a, lds, stream);
+        if (pt <= 2) return launch_instance<WM, NJ, 1, 2, 2>(a, lds, stream);
+        return launch_instance<WM, NJ, 1, 4, 2>(a, lds, stream);
     default:
-        if (pt <= 2) return launch_instance<WM, NJ, 2, 1>(a, lds, stream);
-        return launch_instance<WM, NJ, 4, 1>(a, lds, stream);
+        if (pt <= 2) return launch_instance<WM, NJ, 1, 2, 1>(a, lds, stream);
+        return launch_instance<WM, NJ, 1, 4, 1>(a, lds, stream);
     }
 }
 
@@ -476,30 +505,35 @@ bool plan_conv3x3_dbuf(const ConvProblem &p, Patch3x3Plan *plan)
 {
     if (plan->mt != kMT) return false;
     if (p.IC % (2 * kChunk) != 0) return false;      // the chunk loop runs in pairs
-    // Measured at batch 64: stride-2 patches are too large for two stages to pay, and with
-    // fewer than eight chunks the deeper pipeline's longer start-up (three chunks in flight
-    // before the first MFMA) costs more than the loop gains.
-    if (p.sh != 1 || p.IC < 8 * kChunk || plan->nt > 256) return false;
+    // Measured at batch 64: with fewer than eight chunks the deeper pipeline's longer start-up
+    // (three chunks in flight before the first MFMA) costs more than the loop gains.
+    if (p.IC < 8 * kChunk || plan->nt > 256) return false;
+    // Stride 2: a patch is four times the output tile, so its two stages fill the LDS of a CU
+    // and the kernel pays only where one workgroup per CU covers the problem (instances: the
+    // 128- and 256-pixel tiles, even rows).
+    if (p.sh == 2 && (plan->nt < 128 || p.W % 2 != 0 || plan->tiles > kComputeUnits)) return false;
     // Row pitch of the patch planes.  The 16 lanes of one LDS access read the words of 16
     // consecutive pixels; they are conflict-free when those words are consecutive modulo 16,
-    // also across the end of an image row and of an image.  A pitch of W + 16 words makes the
-    // step at a row end 1 (mod 16), and xp extra words between images do the same for the step
-    // from an image's last pixel to the next image's first.  The plain pitch W + 2 is used
-    // instead when the padded planes would cost the second workgroup per CU.
+    // also across the end of an image row and of an image.  Stride 1: a pitch of W + 16 words
+    // makes the step at a row end 1 (mod 16), and xp extra words between images do the same
+    // for the step from an image's last pixel to the next image's first.  Stride 2 keeps the
+    // plain pitch (even columns, then odd columns); so does stride 1 when the padded planes
+    // would cost the second workgroup per CU.
+    const int pwh = (p.W + 3) / 2;
     const int images = (plan->nt - 1) / (p.OH * p.OW) + 1;     // image ends a tile can span
-    int pws = p.W + 16;
-    int xp = ((p.H * p.W - (p.H + 2) * pws) % 16 + 16) % 16;
+    int pws = p.sh == 2 ? 2 * pwh : p.W + 16;
+    int xp = p.sh == 2 ? 0 : ((p.H * p.W - (p.H + 2) * pws) % 16 + 16) % 16;
     int pplane = (plan->rows * pws + images * xp) * 16;
     // the widest load that divides a row (and an image plane: every row then starts aligned)
     const int px = p.W % 8 == 0 ? 8 : p.W % 4 == 0 ? 4 : p.W % 2 == 0 ? 2 : 1;
     const int pt = (2 * plan->rows * (p.W / px) + 255) / 256;
     if (pt * (px >= 2 ? px / 2 : 1) > 4) return false;       // registers of a task's loads
-    // behind the planes of a stage: room for the pixels of one task for each of 16 lanes, where
-    // idle patch tasks store
-    const int dump = 16 * (px > 1 ? px * 16 : 32);
+    // behind the planes of a stage: 32 bytes for each of 16 lanes, where idle patch tasks store
+    // (a stride-2 pair stores its two pixels pwh - 1 words apart)
+    const int dump = 16 * (px > 1 ? px * 16 : 32) + (p.sh == 2 ? pwh * 16 : 0);
     int stage = 2 * kAPlane + 2 * pplane + dump;
     size_t lds = 2 * (size_t)stage + (size_t)kMT * 8;
-    if (lds > 80 * 1024) {
+    if (lds > 80 * 1024 && p.sh == 1) {
         pws = p.W + 2;
         xp = 0;
         pplane = plan->rows * pws * 16;
@@ -546,9 +580,9 @@ tvg_status launch_conv3x3_dbuf(const ConvProblem &p, const Patch3x3Plan &plan,
     a.inv_vh = 1.0f / (float)(p.H + 2);
     a.inv_wpx = 1.0f / (float)(p.W / plan.px);
     switch (plan.nt) {
-    case 256: return launch_pt<1, 2>(a, plan.lds_bytes, plan.pt, plan.px, stream);
-    case 128: return launch_pt<2, 2>(a, plan.lds_bytes, plan.pt, plan.px, stream);
-    default: return launch_pt<2, 1>(a, plan.lds_bytes, plan.pt, plan.px, stream);
+    case 256: return launch_pt<1, 2>(a, plan.lds_bytes, p.sh, plan.pt, plan.px, stream);
+    case 128: return launch_pt<2, 2>(a, plan.lds_bytes, p.sh, plan.pt, plan.px, stream);
+    default: return launch_pt<2, 1>(a, plan.lds_bytes, p.sh, plan.pt, plan.px, stream);
     }
 }
 

@@ -194,6 +194,28 @@ def test_bf16_3x3_pipelined_kernel_shapes_all_tiles(tvg, monkeypatch, cfg, tile)
     assert rel_err(to_host(y), oracle_dense(sh, inp)) <= TOL["bf16"]
 
 
+DBUF_STRIDE2 = [
+    # stride 2 under the pipelined kernel (IC % 32 == 0, IC >= 128, at most one workgroup per
+    # CU): rows that take 4-, 8- and 16-byte loads, several images per tile, ragged tails
+    (2, 128, 14, 14, 64), (3, 128, 9, 10, 130), (1, 256, 28, 28, 72), (2, 128, 16, 16, 64),
+    (5, 160, 7, 8, 40), (1, 128, 2, 2, 64), (4, 128, 6, 12, 64), (64, 256, 14, 14, 64),
+]
+
+
+@pytest.mark.parametrize("tile", ["", "64,256", "64,128"])
+@pytest.mark.parametrize("cfg", DBUF_STRIDE2)
+def test_bf16_3x3_pipelined_kernel_stride2(tvg, monkeypatch, cfg, tile):
+    n, ic, h, w, oc = cfg
+    if tile:
+        monkeypatch.setenv("TVG_FORCE_TILE", tile)
+    else:
+        monkeypatch.delenv("TVG_FORCE_TILE", raising=False)
+    sh = ti.ConvShape("db2", n, ic, h, w, oc, 3, 3, 2, 1)
+    inp = ti.make_inputs(sh, 7100 + sum(cfg), "bf16", residual=True, bias=True)
+    y = run_dense(tvg, sh, inp, "bf16")
+    assert rel_err(to_host(y), oracle_dense(sh, inp)) <= TOL["bf16"]
+
+
 @pytest.mark.parametrize("cfg", [(2, 128, 8, 8, 64), (3, 128, 7, 7, 130), (1, 256, 33, 40, 72)])
 def test_bf16_3x3_pipelined_kernel_plain_tail_and_determinism(tvg, cfg):
     """No bias, no residual, no ReLU (negative outputs survive), and bit-identical reruns."""
