@@ -138,6 +138,9 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
     uint32_t goff[PT];      // byte offset of a patch task's first channel within a chunk of x
     int pwbase[2][PT];      // where the first pixel of a patch task goes
     int pwbase2[2][PT];     // stride 2: its second pixel (the even-column half of the row)
+    // PX = 4: where pixels 2 and 3 go - behind the first pair, or, for the short last task of a
+    // row of 4m + 2 pixels, to the dump area (its load then reads on into the next row)
+    int pwtail[2][PX == 4 ? PT : 1], pwtail2[2][PX == 4 && STRIDE == 2 ? PT : 1];
     // two register sets: while one is transposed into LDS (chunk c+1) the other is still in
     // flight (chunk c+2), so a load has two chunks of MFMA time to arrive
     uint32_t praw[2][PT][8][PW32];
@@ -197,6 +200,11 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
                 // consecutive words; for stride 2 alternately the odd- and the even-column half
                 unsigned char *dst = STRIDE == 2 ? smem + ((k & 1) ? pwbase2[set][j] : pwbase[set][j]) + (k >> 1) * 16
                                                  : smem + pwbase[set][j] + k * 16;
+                if constexpr (PX == 4) {
+                    if (k >= 2)
+                        dst = STRIDE == 2 ? smem + (k == 3 ? pwtail2[set][j] : pwtail[set][j])
+                                          : smem + pwtail[set][j] + (k - 2) * 16;
+                }
                 *reinterpret_cast<uint4v *>(dst) = uint4v{o[0], o[1], o[2], o[3]};
             } else {
                 if (!do_load) return;
@@ -251,7 +259,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
 
     // ---- per-thread patch load tasks: (virtual row, iw, channel octet), fixed for all chunks
     {
-        const int WPX = W / PX;
+        const int WPX = (W + PX - 1) / PX;       // (PX = 4 also serves rows of 4m + 2 pixels)
         const int per_octet = nrows * WPX;
         // second pixel of a stride-2 task: first pixel in an odd padded column, the second in
         // the following even column
@@ -278,6 +286,16 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
             pwbase[1][j] = pwbase[0][j] + stage_bytes;
             pwbase2[0][j] = pwbase[0][j] + pair_step;
             pwbase2[1][j] = pwbase[1][j] + pair_step;
+            if constexpr (PX == 4) {
+                const bool whole = !live || iw + 4 <= W;
+                const int dump = 2 * kAPlane + 2 * a.pplane + (tid & 15) * 64;
+                pwtail[0][j] = whole ? pwbase[0][j] + (STRIDE == 2 ? 16 : 32) : dump + 32;
+                pwtail[1][j] = pwtail[0][j] + stage_bytes;
+                if constexpr (STRIDE == 2) {
+                    pwtail2[0][j] = whole ? pwbase2[0][j] + 16 : dump + 48;
+                    pwtail2[1][j] = pwtail2[0][j] + stage_bytes;
+                }
+            }
         }
     }
     all_items(kP0, kItems, 0, false, true, 0);
@@ -525,8 +543,9 @@ bool plan_conv3x3_dbuf(const ConvProblem &p, Patch3x3Plan *plan)
     int xp = p.sh == 2 ? 0 : ((p.H * p.W - (p.H + 2) * pws) % 16 + 16) % 16;
     int pplane = (plan->rows * pws + images * xp) * 16;
     // the widest load that divides a row (and an image plane: every row then starts aligned)
-    const int px = p.W % 8 == 0 ? 8 : p.W % 4 == 0 ? 4 : p.W % 2 == 0 ? 2 : 1;
-    const int pt = (2 * plan->rows * (p.W / px) + 255) / 256;
+    // (rows of 4m + 2 pixels take 8-byte loads too, 4-byte aligned, the last one of a row short)
+    const int px = p.W % 8 == 0 ? 8 : p.W % 4 == 0 ? 4 : p.W % 2 != 0 ? 1 : p.W >= 6 ? 4 : 2;
+    const int pt = (2 * plan->rows * ((p.W + px - 1) / px) + 255) / 256;
     if (pt * (px >= 2 ? px / 2 : 1) > 4) return false;       // registers of a task's loads
     // behind the planes of a stage: 32 bytes for each of 16 lanes, where idle patch tasks store
     // (a stride-2 pair stores its two pixels pwh - 1 words apart)
@@ -578,7 +597,7 @@ tvg_status launch_conv3x3_dbuf(const ConvProblem &p, const Patch3x3Plan &plan,
     a.inv_ohw = 1.0f / (float)(p.OH * p.OW);
     a.inv_ow = 1.0f / (float)p.OW;
     a.inv_vh = 1.0f / (float)(p.H + 2);
-    a.inv_wpx = 1.0f / (float)(p.W / plan.px);
+    a.inv_wpx = 1.0f / (float)((p.W + plan.px - 1) / plan.px);
     switch (plan.nt) {
     case 256: return launch_pt<1, 2>(a, plan.lds_bytes, p.sh, plan.pt, plan.px, stream);
     case 128: return launch_pt<2, 2>(a, plan.lds_bytes, p.sh, plan.pt, plan.px, stream);

@@ -176,6 +176,8 @@ DBUF_SHAPES = [
     (2, 128, 8, 8, 64), (5, 192, 12, 12, 96), (1, 256, 33, 40, 72), (40, 128, 7, 7, 64),
     (2, 128, 3, 1, 64), (1, 128, 2, 64, 200), (3, 128, 5, 6, 8), (1, 512, 7, 7, 64),
     (2, 128, 56, 56, 64), (70, 128, 3, 3, 64),
+    # rows of 4m + 2 pixels: 8-byte loads whose last task of a row is short
+    (2, 128, 14, 14, 64), (3, 128, 10, 10, 96), (1, 256, 9, 22, 72),
 ]
 
 
