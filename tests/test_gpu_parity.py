@@ -381,7 +381,8 @@ def test_config4_resnet18_shapes_bf16_batch64_sampled(tvg, i):
 # ------------------------------------------------------------------------------------------
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("shape", [(2, 3, 8, 8), (1, 5, 7, 9), (2, 64, 112, 112), (1, 2, 1, 1)])
+@pytest.mark.parametrize("shape", [(2, 3, 8, 8), (1, 5, 7, 9), (2, 64, 112, 112), (1, 2, 1, 1),
+                                   (3, 5, 9, 16), (1, 4, 2, 8), (2, 7, 13, 40), (1, 3, 1, 24)])
 def test_maxpool_is_exact(tvg, dtype, shape):
     import torch
     rng = np.random.default_rng(sum(shape))
