@@ -47,7 +47,7 @@ typedef enum {
     TVG_ERR_NULL = 1,          /* a required pointer is NULL */
     TVG_ERR_BAD_SHAPE = 2,     /* non-positive extent, empty output, stride/pad out of range */
     TVG_ERR_UNSUPPORTED = 3,   /* unknown dtype or flag, tensor too large, kernel size not built */
-    TVG_ERR_WORKSPACE = 4,     /* workspace NULL or smaller than the query says */
+    TVG_ERR_WORKSPACE = 4,     /* workspace NULL, smaller than the query says or misaligned */
     TVG_ERR_LAUNCH = 5         /* the HIP runtime refused the launch */
 } tvg_status;
 

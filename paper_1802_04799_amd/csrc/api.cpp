@@ -99,7 +99,8 @@ tvg_status tvg_conv2d_fused(const tvg_conv_desc *desc, const void *x, const void
     // A problem shaped for a specialised kernel reported a zero workspace; if its pointers
     // rule that kernel out, the generic kernel runs it in a single pass over the reduction.
     const tvg::ConvPlan plan = tvg::plan_conv(p, !(patch_shape || stem_shape || pw_shape));
-    if (plan.workspace_bytes > 0 && (!workspace || workspace_bytes < plan.workspace_bytes))
+    if (plan.workspace_bytes > 0 && (!workspace || workspace_bytes < plan.workspace_bytes ||
+                                     reinterpret_cast<uintptr_t>(workspace) % 256 != 0))
         return TVG_ERR_WORKSPACE;
     return tvg::launch_conv_igemm(p, plan, ptr, stream);
 }

@@ -92,6 +92,9 @@ def test_workspace_query_and_too_small_workspace():
     assert tvg.tvg_conv2d_fused(small, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, None, 0, 0) == 4
     assert tvg.tvg_conv2d_fused(small, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, FAKE,
                                 need - 1, 0) == 4
+    # the workspace must be 256-byte aligned
+    assert tvg.tvg_conv2d_fused(small, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, FAKE + 64,
+                                need, 0) == 4
     assert tvg.tvg_dwconv2d_workspace_size(desc(k=8, c=8)) == 0
 
 
