@@ -279,6 +279,10 @@ PW_SHAPES = [
     # exactly 2 and 8 chunks of 32 channels (all chunks fetched up front), ragged tiles
     (3, 256, 14, 14, 130, 2), (2, 256, 9, 11, 70, 1), (20, 256, 14, 14, 512, 2), (3, 64, 13, 9, 40, 2),
     (2, 128, 10, 10, 96, 1),
+    # map sizes and row lengths that are multiples of 8, 4 and 2, one and several chunks, ragged
+    # channel tails
+    (2, 64, 16, 16, 96, 2), (1, 96, 8, 24, 64, 2), (1, 40, 5, 6, 33, 1), (3, 200, 4, 8, 130, 1),
+    (2, 64, 12, 28, 64, 2), (5, 32, 2, 4, 16, 2), (1, 256, 8, 8, 200, 1),
 ]
 
 
@@ -289,6 +293,23 @@ def test_bf16_1x1_kernel_shapes(tvg, cfg):
     inp = ti.make_inputs(sh, 8000 + sum(cfg), "bf16", residual=True, bias=True)
     y = run_dense(tvg, sh, inp, "bf16")
     assert rel_err(to_host(y), oracle_dense(sh, inp)) <= TOL["bf16"]
+
+
+def test_bf16_1x1_kernel_unaligned_input(tvg):
+    """x at an 8-byte and at a 2-byte offset from an aligned address (the kernel needs 2-byte
+    alignment only)."""
+    import torch
+    sh = ti.ConvShape("pwa", 2, 64, 8, 8, 64, 1, 1, 1, 0)
+    inp = ti.make_inputs(sh, 8123, "bf16")
+    d = dev_inputs(inp, "bf16")
+    want = oracle_dense(sh, inp)
+    for off in (4, 1):
+        store = torch.empty(d["x"].numel() + 16, dtype=torch.bfloat16, device="cuda:0")
+        x = store[off:off + d["x"].numel()].view(d["x"].shape)
+        x.copy_(d["x"])
+        y = tvg.conv2d_fused(x, d["w"], d["scale"], d["shift"], stride=1, pad=0, relu=True)
+        torch.cuda.synchronize()
+        assert rel_err(to_host(y), want) <= TOL["bf16"], off
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
