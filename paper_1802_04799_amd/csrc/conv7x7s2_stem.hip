@@ -313,7 +313,10 @@ tvg_status launch_conv7x7s2_stem(const ConvProblem &p, const StemPlan &plan, con
     if (per > a.ntiles) per = a.ntiles;
     a.wg_per_mtile = per;
     a.x_bytes = (uint32_t)((size_t)p.N * p.IC * p.H * p.W * 2);
-    a.w_bytes = (uint32_t)((size_t)p.OC * p.IC * 49 * 2);
+    // Buffer loads are range-checked per 4-byte word: an odd number of weights (odd OC x IC)
+    // would leave the last one unreadable, so the size is rounded up to whole words (the two
+    // bytes past the tensor lie in the same aligned word as its last element).
+    a.w_bytes = ((uint32_t)((size_t)p.OC * p.IC * 49 * 2) + 3u) & ~3u;
     const unsigned grid = (unsigned)(per * a.mtiles);
     if (p.IC == 3 && plan.lt <= 5) return launch_lt<3, 5>(a, grid, plan.lds_bytes, stream);
     switch (p.IC) {

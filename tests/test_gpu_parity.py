@@ -259,6 +259,8 @@ STEM_SHAPES = [
     # bf16 7x7 stride-2 pad-3 problems with few input channels: n, ic, h, w, oc
     (2, 3, 32, 32, 64), (3, 3, 40, 24, 70), (1, 4, 16, 16, 8), (5, 3, 18, 8, 64),
     (2, 1, 64, 64, 16), (1, 3, 224, 224, 64), (2, 2, 50, 48, 100), (3, 3, 31, 40, 33),
+    # an odd number of weights: the tensor ends in the middle of a 4-byte word
+    (1, 1, 12, 48, 33), (3, 1, 34, 40, 33), (2, 3, 9, 16, 1),
 ]
 
 
