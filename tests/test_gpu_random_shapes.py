@@ -1,0 +1,111 @@
+"""Seeded random problem shapes through the C ABI against the oracle, full outputs.
+
+The shape lists of test_gpu_parity.py are written by hand around the cases each kernel is known
+to have; this sweep draws shapes, tails and tile overrides at random (fixed seeds, so every run
+sees the same cases) to reach the combinations nobody thought of.  It found the stem kernel's
+unreadable last weight when OC x IC is odd.
+"""
+import random
+
+import numpy as np
+import pytest
+
+import oracle
+import tvg_inputs as ti
+from _util import TOL, dev_inputs, rel_err, to_host
+
+pytestmark = pytest.mark.gpu
+
+TILES = ["", "", "64,256", "64,128", "128,64", "64,64", "128,128"]
+
+
+def draw_dense(rng):
+    kind = rng.choice(["3x3", "3x3", "3x3deep", "3x3deep_s2", "1x1", "7x7", "odd"])
+    if kind == "3x3":
+        ic, r, stride, pad = 16 * rng.randint(1, 6), 3, rng.choice([1, 2]), 1
+    elif kind == "3x3deep":
+        ic, r, stride, pad = 32 * rng.randint(4, 8), 3, 1, 1
+    elif kind == "3x3deep_s2":
+        ic, r, stride, pad = 32 * rng.randint(4, 8), 3, 2, 1
+    elif kind == "1x1":
+        ic, r, stride, pad = 8 * rng.randint(1, 40), 1, rng.choice([1, 2]), 0
+    elif kind == "7x7":
+        ic, r, stride, pad = rng.randint(1, 4), 7, 2, 3
+    else:                                   # shapes no specialised kernel takes
+        r = rng.choice([1, 2, 3, 5])
+        ic, stride, pad = rng.randint(1, 20), rng.choice([1, 2, 3]), rng.randint(0, r - 1)   # pad < r
+    n = rng.choice([1, 2, 3, 5, 8])
+    lo = 4 if r == 7 else max(1, r - 2 * pad)
+    h, w = rng.randint(lo, 30), rng.randint(lo, 30)
+    if kind == "7x7":
+        w = 8 * rng.randint(1, 5)
+    elif rng.random() < 0.5:
+        w += w & 1                          # favour even rows (wide loads)
+    oc = rng.choice([1, 8, 33, 64, 70, 128, 130, 200])
+    return ti.ConvShape("r", n, ic, h, w, oc, r, r, stride, pad)
+
+
+def cases(seed, count):
+    rng = random.Random(seed)
+    out = []
+    while len(out) < count:
+        sh = draw_dense(rng)
+        if sh.flops > 4e8:
+            continue
+        out.append((len(out), sh, rng.choice(TILES), rng.random() < 0.7, rng.random() < 0.5,
+                    rng.random() < 0.5, rng.random() < 0.5))
+    return out
+
+
+@pytest.mark.parametrize("case", cases(20260, 300), ids=lambda c: f"{c[0]}")
+def test_random_dense_bf16(tvg, monkeypatch, case):
+    i, sh, tile, relu, hint, res, bias = case
+    if tile:
+        monkeypatch.setenv("TVG_FORCE_TILE", tile)
+    else:
+        monkeypatch.delenv("TVG_FORCE_TILE", raising=False)
+    inp = ti.make_inputs(sh, 52000 + i, "bf16", residual=res, bias=bias)
+    d = dev_inputs(inp, "bf16")
+    y = tvg.conv2d_fused(d["x"], d["w"], d["scale"], d["shift"], d["bias"], d["residual"],
+                         stride=sh.stride, pad=sh.pad, relu=relu, stream_out=hint)
+    want = oracle.conv2d_fused(inp["x"], inp["w"], inp["scale"], inp["shift"], inp["bias"],
+                               inp["residual"], stride=(sh.stride,) * 2, pad=(sh.pad,) * 2, relu=relu)
+    assert rel_err(to_host(y), want) <= TOL["bf16"], sh
+
+
+@pytest.mark.parametrize("case", cases(20261, 100), ids=lambda c: f"{c[0]}")
+def test_random_dense_fp32(tvg, case):
+    i, sh, _, relu, hint, res, bias = case
+    inp = ti.make_inputs(sh, 53000 + i, "f32", residual=res, bias=bias)
+    d = dev_inputs(inp, "f32")
+    y = tvg.conv2d_fused(d["x"], d["w"], d["scale"], d["shift"], d["bias"], d["residual"],
+                         stride=sh.stride, pad=sh.pad, relu=relu, stream_out=hint)
+    want = oracle.conv2d_fused(inp["x"], inp["w"], inp["scale"], inp["shift"], inp["bias"],
+                               inp["residual"], stride=(sh.stride,) * 2, pad=(sh.pad,) * 2, relu=relu)
+    assert rel_err(to_host(y), want) <= TOL["f32"], sh
+
+
+def dw_cases(seed, count):
+    rng = random.Random(seed)
+    out = []
+    for i in range(count):
+        n, c = rng.choice([1, 2, 5]), rng.choice([1, 3, 8, 32, 100])
+        h, w = rng.randint(1, 40), rng.randint(1, 40)
+        if rng.random() < 0.5:
+            w = 4 * rng.randint(1, 10)
+        out.append((i, n, c, h, w, rng.choice([1, 2]), rng.choice(["f32", "f32", "bf16"]),
+                    rng.random() < 0.7, rng.random() < 0.5, rng.random() < 0.5))
+    return out
+
+
+@pytest.mark.parametrize("case", dw_cases(20262, 120), ids=lambda c: f"{c[0]}")
+def test_random_depthwise(tvg, case):
+    i, n, c, h, w, stride, dtype, relu, hint, res = case
+    sh = ti.ConvShape("rd", n, c, h, w, c, 3, 3, stride, 1, depthwise=True)
+    inp = ti.make_inputs(sh, 54000 + i, dtype, residual=res, bias=True)
+    d = dev_inputs(inp, dtype)
+    y = tvg.dwconv2d_fused(d["x"], d["w"], d["scale"], d["shift"], d["bias"], d["residual"],
+                           stride=stride, pad=1, relu=relu, stream_out=hint)
+    want = oracle.dwconv2d_fused(inp["x"], inp["w"], inp["scale"], inp["shift"], inp["bias"],
+                                 inp["residual"], stride=(stride,) * 2, pad=(1, 1), relu=relu)
+    assert rel_err(to_host(y), want) <= TOL[dtype], sh
