@@ -31,11 +31,16 @@ PEAK_HBM_GBS = 8000.0
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=200,
+                    help="untimed steps first: the GPU needs some 50 ms of work to reach its steady "
+                         "state (3 steps: 0.273 ms per step, 300 steps: 0.260)")
     ap.add_argument("--skip-extras", action="store_true",
                     help="only the timed region (for profiler runs)")
     ap.add_argument("--skip-cpu", action="store_true", help="do not time the CPU oracle")
+    ap.add_argument("--tune", action="store_true",
+                    help="before the timed region, time every tile shape of every layer and fix "
+                         "the fastest (paper_1802_04799_amd.tune); the choices are reported")
     ap.add_argument("--no-stream-hint", action="store_true",
                     help="operator layers without the TVG_STREAM_OUT store hint")
     ap.add_argument("--only", default="", help="comma-separated layer names (C1..C12): restrict "
@@ -149,6 +154,13 @@ def main():
         for l in layers:
             l.launch()
 
+    tuning = None
+    if args.tune:       # a measured per-shape choice of the tile knob, outside the timed region
+        from paper_1802_04799_amd import tune
+        tuning = [dict(tune.tune_conv2d(l.desc, l.x[0], l.w[0], l.scale, l.shift, l.y[0],
+                                        workspace=l.ws if l.ws_bytes else None), layer=l.sh.name)
+                  for l in layers]
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -226,6 +238,7 @@ def main():
                    "stream_out_hint": not args.no_stream_hint},
         "roofline": roofline,
         "layers": layer_rows,
+        "tuning": tuning,
         "layers_note": "per-launch durations from a calibration pass with an event before every "
                        "launch (adds about 4 us per launch); not part of the timed region",
     }

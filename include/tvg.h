@@ -122,6 +122,30 @@ tvg_status tvg_dwconv2d_fused(const tvg_conv_desc *desc, const void *x, const vo
 tvg_status tvg_maxpool2d_3x3s2(int32_t n, int32_t c, int32_t h, int32_t w, int32_t dtype,
                                const void *x, void *y, void *hip_stream);
 
+/*
+ * Tuning (TVM paper Section 5: the schedule of an operator is chosen per shape by measurement).
+ * The tile shape of a kernel - output channels x pixels per workgroup - is its main knob; the
+ * library picks one by a measured rule, and a caller that has timed the alternatives on its own
+ * problem can fix the choice.  Host-only calls, safe to use from several threads.
+ *
+ * tvg_conv2d_set_tile: from now on plan this exact problem (every descriptor field but flags)
+ * with tiles of mt x nt, one of 64x256, 128x128, 64x128, 128x64, 64x64 (anything else:
+ * TVG_ERR_UNSUPPORTED); mt = nt = 0 forgets the problem.  A tile shape that the problem's kernel
+ * cannot use makes the call fall back to the generic kernel, which is correct but slow: time
+ * before you fix.  At most 1024 problems are remembered.
+ * tvg_conv2d_get_plan: which kernel and tile shape a call with this descriptor would use now
+ * (alignment of the pointers aside).  kernel, mt, nt are host pointers.
+ */
+typedef enum {
+    TVG_KERNEL_GENERIC = 0,        /* implicit GEMM with gathered operands, any shape      */
+    TVG_KERNEL_3X3 = 1,            /* bf16 3x3, input patch in LDS, one stage              */
+    TVG_KERNEL_3X3_PIPELINED = 2,  /* bf16 3x3, two LDS stages, software-pipelined         */
+    TVG_KERNEL_STEM = 3,           /* bf16 7x7 stride 2, few input channels                */
+    TVG_KERNEL_1X1 = 4             /* bf16 1x1                                             */
+} tvg_kernel;
+tvg_status tvg_conv2d_set_tile(const tvg_conv_desc *desc, int32_t mt, int32_t nt);
+tvg_status tvg_conv2d_get_plan(const tvg_conv_desc *desc, int32_t *kernel, int32_t *mt, int32_t *nt);
+
 /* Static, NUL-terminated description of a status code (never NULL). */
 const char *tvg_status_string(tvg_status status);
 

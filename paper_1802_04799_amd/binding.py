@@ -75,6 +75,11 @@ def load() -> ctypes.CDLL:
     lib.tvg_status_string.restype = ctypes.c_char_p
     lib.tvg_status_string.argtypes = [ctypes.c_int]
     lib.tvg_version.restype = ctypes.c_int
+    lib.tvg_conv2d_set_tile.restype = ctypes.c_int
+    lib.tvg_conv2d_set_tile.argtypes = [dp, ctypes.c_int32, ctypes.c_int32]
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    lib.tvg_conv2d_get_plan.restype = ctypes.c_int
+    lib.tvg_conv2d_get_plan.argtypes = [dp, i32p, i32p, i32p]
     _lib = lib
     return lib
 
@@ -85,6 +90,23 @@ def status_string(status: int) -> str:
 
 def tvg_version() -> int:
     return int(load().tvg_version())
+
+
+KERNEL_NAMES = {0: "generic", 1: "3x3", 2: "3x3-pipelined", 3: "stem", 4: "1x1"}
+
+
+def tvg_conv2d_set_tile(desc: "ConvDesc", mt: int, nt: int) -> int:
+    """Fix (or, with 0, 0, forget) the tile shape this exact problem is planned with."""
+    return int(load().tvg_conv2d_set_tile(ctypes.byref(desc), int(mt), int(nt)))
+
+
+def tvg_conv2d_get_plan(desc: "ConvDesc"):
+    """(kernel id, mt, nt) a call with this descriptor would use now."""
+    k, mt, nt = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+    st = load().tvg_conv2d_get_plan(ctypes.byref(desc), ctypes.byref(k), ctypes.byref(mt), ctypes.byref(nt))
+    if st != TVG_OK:
+        raise TvgError(st, "tvg_conv2d_get_plan")
+    return k.value, mt.value, nt.value
 
 
 # ---------------------------------------------------------------------------------------

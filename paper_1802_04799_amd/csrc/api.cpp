@@ -1,6 +1,11 @@
 // C ABI of libtvg: argument validation (host only, before any device call),
 // planning and dispatch to the kernel launchers.
+#include <stdio.h>
 #include <stdlib.h>
+#include <string.h>
+
+#include <mutex>
+#include <vector>
 #include "tvg_internal.h"
 
 namespace {
@@ -45,9 +50,106 @@ tvg_status make_problem(const tvg_conv_desc *d, bool depthwise, ConvProblem *out
     return TVG_OK;
 }
 
+// Problems whose tile shape a caller has fixed (tvg_conv2d_set_tile): a short list under a
+// mutex - planning reads it on every call, a tuner writes it a few times per shape.
+struct TileEntry {
+    int key[12];
+    int mt, nt;
+};
+std::mutex g_tile_mutex;
+std::vector<TileEntry> g_tiles;
+constexpr size_t kMaxTileEntries = 1024;
+
+void tile_key(const ConvProblem &p, int (&key)[12])
+{
+    const int k[12] = {p.N, p.IC, p.H, p.W, p.OC, p.R, p.S, p.sh, p.sw, p.ph, p.pw, p.dtype};
+    memcpy(key, k, sizeof(k));
+}
+
 }  // namespace
 
+namespace tvg {
+
+bool forced_tile(const ConvProblem &p, int *mt, int *nt)
+{
+    int key[12];
+    tile_key(p, key);
+    {
+        std::lock_guard<std::mutex> lock(g_tile_mutex);
+        for (const TileEntry &e : g_tiles)
+            if (memcmp(e.key, key, sizeof(key)) == 0) {
+                *mt = e.mt;
+                *nt = e.nt;
+                return true;
+            }
+    }
+    if (const char *e = getenv("TVG_FORCE_TILE"))
+        if (sscanf(e, "%d,%d", mt, nt) == 2 && *mt > 0 && *nt > 0) return true;
+    return false;
+}
+
+}  // namespace tvg
+
 extern "C" {
+
+tvg_status tvg_conv2d_set_tile(const tvg_conv_desc *desc, int32_t mt, int32_t nt)
+{
+    ConvProblem p;
+    tvg_status st = make_problem(desc, false, &p);
+    if (st != TVG_OK) return st;
+    const bool clear = mt == 0 && nt == 0;
+    const bool known = (mt == 64 && (nt == 256 || nt == 128 || nt == 64)) ||
+                       (mt == 128 && (nt == 128 || nt == 64));
+    if (!clear && !known) return TVG_ERR_UNSUPPORTED;
+    int key[12];
+    tile_key(p, key);
+    std::lock_guard<std::mutex> lock(g_tile_mutex);
+    for (size_t i = 0; i < g_tiles.size(); ++i)
+        if (memcmp(g_tiles[i].key, key, sizeof(key)) == 0) {
+            if (clear) g_tiles.erase(g_tiles.begin() + (long)i);
+            else { g_tiles[i].mt = mt; g_tiles[i].nt = nt; }
+            return TVG_OK;
+        }
+    if (clear) return TVG_OK;
+    if (g_tiles.size() >= kMaxTileEntries) return TVG_ERR_UNSUPPORTED;
+    TileEntry e;
+    memcpy(e.key, key, sizeof(key));
+    e.mt = mt;
+    e.nt = nt;
+    g_tiles.push_back(e);
+    return TVG_OK;
+}
+
+tvg_status tvg_conv2d_get_plan(const tvg_conv_desc *desc, int32_t *kernel, int32_t *mt, int32_t *nt)
+{
+    if (!kernel || !mt || !nt) return TVG_ERR_NULL;
+    ConvProblem p;
+    tvg_status st = make_problem(desc, false, &p);
+    if (st != TVG_OK) return st;
+    tvg::Patch3x3Plan patch;
+    tvg::StemPlan stem;
+    tvg::Pw1x1Plan pw;
+    if (tvg::plan_conv3x3_patch(p, &patch)) {
+        *kernel = patch.dbuf ? TVG_KERNEL_3X3_PIPELINED : TVG_KERNEL_3X3;
+        *mt = patch.mt;
+        *nt = patch.nt;
+    } else if (tvg::plan_conv7x7s2_stem(p, &stem)) {
+        *kernel = TVG_KERNEL_STEM;
+        *mt = 64;
+        *nt = 256;
+    } else if (tvg::plan_conv1x1(p, &pw)) {
+        *kernel = TVG_KERNEL_1X1;
+        *mt = pw.mt;
+        *nt = pw.nt;
+    } else {
+        const tvg::ConvPlan plan = tvg::plan_conv(p);
+        *kernel = TVG_KERNEL_GENERIC;
+        *mt = plan.mt;
+        *nt = plan.nt;
+    }
+    return TVG_OK;
+}
+
 
 tvg_status tvg_conv2d_workspace_size(const tvg_conv_desc *desc, size_t *bytes)
 {

@@ -239,7 +239,7 @@ bool plan_conv1x1(const ConvProblem &p, Pw1x1Plan *plan)
     const auto &cands = (p.OC <= 64 && p.IC < 64) ? shallow : deep;
     bool found = false, fills_best = false;
     int force_mt = 0, force_nt = 0;       // tuning override, as for the 3x3 kernels
-    if (const char *e = getenv("TVG_FORCE_TILE")) sscanf(e, "%d,%d", &force_mt, &force_nt);
+    if (!forced_tile(p, &force_mt, &force_nt)) force_mt = force_nt = 0;
     for (const auto &c : cands) {
         const int mt = c[0], nt = c[1];
         if (mt == 128 && p.OC <= 64) continue;

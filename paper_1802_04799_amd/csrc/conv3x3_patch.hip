@@ -415,7 +415,7 @@ bool plan_conv3x3_patch(const ConvProblem &p, Patch3x3Plan *plan)
     if (p.IC % kChunk != 0) return false;
     if (p.npix >= (1 << 22) || (long)p.N * (p.H + 2) >= (1 << 22)) return false;   // fast_div range
     int force_mt = 0, force_nt = 0;
-    if (const char *e = getenv("TVG_FORCE_TILE")) sscanf(e, "%d,%d", &force_mt, &force_nt);
+    if (!forced_tile(p, &force_mt, &force_nt)) force_mt = force_nt = 0;
     bool use_dbuf = true;
     if (const char *e = getenv("TVG_DBUF")) use_dbuf = atoi(e) != 0;
     // Tile choice (measured on MI355X at batch 64): take the largest tile that still gives at

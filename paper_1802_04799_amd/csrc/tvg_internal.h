@@ -40,6 +40,11 @@ struct ConvPlan {
     size_t workspace_bytes;
 };
 
+// Tile shape fixed for this exact problem by tvg_conv2d_set_tile, or by the TVG_FORCE_TILE
+// environment variable ("mt,nt", for sweeps); false when neither names one.  The planners of
+// the 3x3 and 1x1 kernels then consider that tile shape only.
+bool forced_tile(const ConvProblem &p, int *mt, int *nt);
+
 // `allow_split` = false plans a single pass over the reduction (no workspace).
 ConvPlan plan_conv(const ConvProblem &p, bool allow_split = true);
 

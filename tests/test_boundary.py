@@ -26,7 +26,7 @@ def test_every_declared_symbol_is_exported():
     names = set(re.findall(r"\b(tvg_[a-z0-9_]+)\s*\(", header))
     assert {"tvg_conv2d_fused", "tvg_dwconv2d_fused", "tvg_conv2d_workspace_size",
             "tvg_dwconv2d_workspace_size", "tvg_maxpool2d_3x3s2", "tvg_status_string",
-            "tvg_version"} <= names
+            "tvg_version", "tvg_conv2d_set_tile", "tvg_conv2d_get_plan"} <= names
     lib = tvg.load()
     for n in names:
         assert hasattr(lib, n), n
@@ -96,6 +96,35 @@ def test_workspace_query_and_too_small_workspace():
     assert tvg.tvg_conv2d_fused(small, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, FAKE + 64,
                                 need, 0) == 4
     assert tvg.tvg_dwconv2d_workspace_size(desc(k=8, c=8)) == 0
+
+
+def test_tile_table_sets_overrides_and_forgets():
+    """tvg_conv2d_set_tile / tvg_conv2d_get_plan are host-only: the planners' choice, a fixed
+    tile, its removal, and what is rejected."""
+    c6 = desc(n=64, c=128, h=28, w=28, k=128, dtype=tvg.TVG_BF16, flags=tvg.TVG_RELU)
+    assert tvg.tvg_conv2d_get_plan(c6) == (2, 64, 256)               # pipelined 3x3, 64 x 256
+    assert tvg.tvg_conv2d_set_tile(c6, 64, 128) == 0
+    plain = desc(n=64, c=128, h=28, w=28, k=128, dtype=tvg.TVG_BF16, flags=0)
+    assert tvg.tvg_conv2d_get_plan(plain)[1:] == (64, 128)           # flags are not part of the key
+    other = desc(n=32, c=128, h=28, w=28, k=128, dtype=tvg.TVG_BF16)
+    assert tvg.tvg_conv2d_get_plan(other)[1:] != (64, 128) or tvg.tvg_conv2d_get_plan(other)[0] != 2
+    assert tvg.tvg_conv2d_set_tile(c6, 128, 64) == 0                 # replaces the entry
+    assert tvg.tvg_conv2d_get_plan(c6)[1:] == (128, 64)
+    assert tvg.tvg_conv2d_set_tile(c6, 0, 0) == 0
+    assert tvg.tvg_conv2d_get_plan(c6) == (2, 64, 256)
+    assert tvg.tvg_conv2d_set_tile(c6, 0, 0) == 0                    # forgetting twice is fine
+    for mt, nt in [(64, 100), (256, 64), (128, 256), (-64, 64), (64, 0)]:
+        assert tvg.tvg_conv2d_set_tile(c6, mt, nt) == 3
+    assert tvg.tvg_conv2d_set_tile(desc(n=0), 64, 64) == 2
+    lib = tvg.load()
+    assert lib.tvg_conv2d_set_tile(None, 64, 64) == 1
+    assert lib.tvg_conv2d_get_plan(ctypes.byref(c6), None, None, None) == 1
+    # kernels by problem: stem, 1x1, generic (fp32)
+    assert tvg.tvg_conv2d_get_plan(desc(n=64, c=3, h=224, w=224, k=64, r=7, s=7, stride_h=2,
+                                        stride_w=2, pad_h=3, pad_w=3, dtype=tvg.TVG_BF16))[0] == 3
+    assert tvg.tvg_conv2d_get_plan(desc(n=64, c=128, h=28, w=28, k=256, r=1, s=1, stride_h=2,
+                                        stride_w=2, pad_h=0, pad_w=0, dtype=tvg.TVG_BF16)) == (4, 128, 64)
+    assert tvg.tvg_conv2d_get_plan(desc(n=1, c=64, h=56, w=56, k=64))[0] == 0
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):

@@ -481,6 +481,37 @@ def test_config5_resnet18_body_bf16_small_batch_full(tvg):
     assert rel_err(g, r) <= 8e-2
 
 
+def test_tuner_fixes_a_tile_and_results_stay_right(tvg, tmp_path):
+    """tune.tune_conv2d times the tile shapes of a problem through the C ABI and fixes the
+    fastest; whatever it picks, the result still matches the oracle, and the choice survives
+    a save / load round trip."""
+    import torch
+    from paper_1802_04799_amd import tune
+    sh = ti.ConvShape("tn", 8, 64, 28, 28, 128, 3, 3, 1, 1)
+    inp = ti.make_inputs(sh, 9911, "bf16")
+    d = dev_inputs(inp, "bf16")
+    desc = tvg.ConvDesc(sh.n, sh.ic, sh.h, sh.w, sh.oc, 3, 3, 1, 1, 1, 1, tvg.TVG_BF16, tvg.TVG_RELU)
+    y = torch.empty(sh.y_shape(), dtype=torch.bfloat16, device="cuda:0")
+    try:
+        rep = tune.tune_conv2d(desc, d["x"], d["w"], d["scale"], d["shift"], y, iters=10, repeats=2,
+                               min_gain=0.0)
+        assert rep["kernel"] == "3x3" and len(rep["candidates"]) >= 3
+        assert rep["tuned_us"] <= rep["default_us"]
+        plan = tvg.tvg_conv2d_get_plan(desc)
+        if rep["chosen"]:
+            assert list(plan[1:]) == rep["chosen"]
+        out = tvg.conv2d_fused(d["x"], d["w"], d["scale"], d["shift"], stride=1, pad=1, relu=True)
+        torch.cuda.synchronize()
+        assert rel_err(to_host(out), oracle_dense(sh, inp)) <= TOL["bf16"]
+        path = str(tmp_path / "tiles.json")
+        tune.save(path)
+        tvg.tvg_conv2d_set_tile(desc, 0, 0)
+        assert tune.load(path) == (1 if rep["chosen"] else 0)
+        assert tvg.tvg_conv2d_get_plan(desc) == plan
+    finally:
+        tvg.tvg_conv2d_set_tile(desc, 0, 0)
+
+
 def test_config5_resnet18_body_hip_graph_replays_match_eager(tvg):
     """The 21-launch chain recorded once into a HIP graph: the library allocates nothing and
     never synchronises, so it records as it stands.  Three replays, each on new images written
