@@ -304,6 +304,8 @@ def main():
                               "frac_fp32_peak": round(fl / tot / 1e12 / PEAK_FP32_TFLOPS, 4)}
         # ResNet-18 body, batch 32, bf16 (configs[4]): 20 convs + 1 max-pool, 21 launches
         out["resnet18_body"] = bench_body(tvg, ti, torch, np, dev, to_dev, time_loop)
+        # MobileNet body, batch 32, bf16: stem + 13 x (depthwise 3x3, 1x1), 27 launches
+        out["mobilenet_body"] = bench_body(tvg, ti, torch, np, dev, to_dev, time_loop, "mobilenet")
 
     if not args.skip_cpu:
         out["cpu_baseline"] = cpu_baseline(ti, np)
@@ -333,19 +335,28 @@ def measured_traffic(kernel):
         return None
 
 
-def bench_body(tvg, ti, torch, np, dev, to_dev, time_loop):
+def bench_body(tvg, ti, torch, np, dev, to_dev, time_loop, network="resnet18"):
     n = 32
-    steps = ti.resnet18_body(n)
-    weights = {s.layer_index: ti.make_weights(s.shape, ti.layer_seed(5, s.layer_index), "bf16")
-               for s in steps if s.op == "conv"}
+    config = 5 if network == "resnet18" else 6
+    steps = ti.resnet18_body(n) if network == "resnet18" else ti.mobilenet_body(n)
+    weights = {s.layer_index: ti.make_weights(s.shape, ti.layer_seed(config, s.layer_index), "bf16")
+               for s in steps if s.op != "maxpool"}
     dw = {k: {"w": to_dev(p["w"], True), "scale": to_dev(p["scale"], False),
               "shift": to_dev(p["shift"], False)} for k, p in weights.items()}
-    images = to_dev(ti.body_images(n, ti.layer_seed(5, 901)), True)
+    images = to_dev(ti.body_images(n, ti.layer_seed(config, 901)), True)
     tensors = {0: images}
     calls = []
     for st in steps:
         src = tensors[st.src]
-        if st.op == "conv":
+        if st.op == "dwconv":
+            sh = st.shape
+            desc = tvg.ConvDesc(sh.n, sh.ic, sh.h, sh.w, sh.oc, 3, 3, sh.stride, sh.stride, 1, 1,
+                                tvg.TVG_BF16, tvg.TVG_RELU if st.relu else 0)
+            y = torch.empty(sh.y_shape(), dtype=torch.bfloat16, device=dev)
+            p = dw[st.layer_index]
+            calls.append((tvg.tvg_dwconv2d_fused, (desc, src, p["w"], p["scale"], p["shift"], None,
+                                                   None, y, None, 0, None)))
+        elif st.op == "conv":
             sh = st.shape
             desc = tvg.ConvDesc(sh.n, sh.ic, sh.h, sh.w, sh.oc, sh.r, sh.s, sh.stride, sh.stride,
                                 sh.pad, sh.pad, tvg.TVG_BF16, tvg.TVG_RELU if st.relu else 0)
@@ -376,7 +387,7 @@ def bench_body(tvg, ti, torch, np, dev, to_dev, time_loop):
     with torch.cuda.graph(graph, stream=torch.cuda.Stream()):
         forward()
     graph_ms = time_loop(graph.replay, 10)
-    flops = sum(s.shape.flops for s in steps if s.op == "conv")
+    flops = sum(s.shape.flops for s in steps if s.op != "maxpool")
     return {"batch": n, "launches": len(calls), "ms": round(ms, 4), "graph_replay_ms": round(graph_ms, 4),
             "tflops": round(flops / (ms * 1e-3) / 1e12, 1),
             "images_per_s": round(n / (ms * 1e-3), 1),

@@ -106,7 +106,8 @@ tvg_status tvg_conv2d_fused(const tvg_conv_desc *desc, const void *x, const void
  * Depthwise fused 3x3 conv2d, channel multiplier 1 (Table 2, rows D; same fused
  * tail).  Bandwidth kernel on the vector ALUs, no matrix cores.  Arguments as
  * above with w = [c][1][3][3]; desc->k must equal desc->c and r == s == 3;
- * stride_h == stride_w in {1, 2}.  The workspace arguments are ignored.
+ * stride_h == stride_w in {1, 2}; pad_h == pad_w == 1 (Table 2's "SAME" padding; anything
+ * else is TVG_ERR_UNSUPPORTED).  The workspace arguments are ignored.
  */
 tvg_status tvg_dwconv2d_fused(const tvg_conv_desc *desc, const void *x, const void *w,
                               const float *scale, const float *shift, const float *bias,

@@ -1,4 +1,4 @@
-"""Oracle run of a chained network (the ResNet-18 convolutional body workload).
+"""Oracle run of a chained network (the ResNet-18 and MobileNet convolutional bodies).
 
 TEST INFRASTRUCTURE ONLY.  Each layer is evaluated by the fp64 oracle from the
 previous layers' stored outputs.  Because the workload stores every activation
@@ -12,7 +12,7 @@ from typing import Callable, Dict, List, Optional
 
 import numpy as np
 
-from . import conv2d_fused, maxpool2d, round_to_bf16
+from . import conv2d_fused, dwconv2d_fused, maxpool2d, round_to_bf16
 
 
 def run_steps(steps, images: np.ndarray, weights: Dict[int, dict], store_bf16: bool = True,
@@ -31,6 +31,11 @@ def run_steps(steps, images: np.ndarray, weights: Dict[int, dict], store_bf16: b
             res = None if st.residual is None else tensors[st.residual]
             y64 = conv2d_fused(src, p["w"], p["scale"], p["shift"], None, res,
                                stride=(sh.stride, sh.stride), pad=(sh.pad, sh.pad), relu=st.relu)
+        elif st.op == "dwconv":
+            p = weights[st.layer_index]
+            sh = st.shape
+            y64 = dwconv2d_fused(src, p["w"], p["scale"], p["shift"], None, None,
+                                 stride=(sh.stride, sh.stride), pad=(sh.pad, sh.pad), relu=st.relu)
         elif st.op == "maxpool":
             y64 = maxpool2d(src, k=3, stride=2, pad=1)
         else:

@@ -31,6 +31,7 @@ tvg_status make_problem(const tvg_conv_desc *d, bool depthwise, ConvProblem *out
         if (d->k != d->c) return TVG_ERR_BAD_SHAPE;
         if (d->r != 3 || d->s != 3) return TVG_ERR_UNSUPPORTED;
         if (d->stride_h != d->stride_w || d->stride_h > 2) return TVG_ERR_UNSUPPORTED;
+        if (d->pad_h != 1 || d->pad_w != 1) return TVG_ERR_UNSUPPORTED;
     }
     ConvProblem p;
     p.N = d->n; p.IC = d->c; p.H = d->h; p.W = d->w; p.OC = d->k; p.R = d->r; p.S = d->s;

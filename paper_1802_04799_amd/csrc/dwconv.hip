@@ -223,20 +223,137 @@ __global__ __launch_bounds__(256) void dwconv3x3_direct_kernel(const DwDirectArg
     }
 }
 
-// Variant for small fp32 planes (at most 256 outputs per plane: 14x14 and 7x7 maps).  A
-// workgroup copies PG whole planes, which are one contiguous run of memory, into LDS with
-// 16-byte loads and no per-element index arithmetic; every lane then keeps ONE output
-// position (oh, ow) for the whole kernel, with its nine tap offsets and in-image mask
-// computed once, and walks over the planes of the group.
-struct DwSmallArgs {
-    const float *x, *w;
+// The same register blocking for bf16 planes: a lane computes 4 output rows x CW output
+// columns (CW = 8 or 4, the output row must be a multiple of it).  An input row of the block
+// is CW * STRIDE pixels in one or two vector loads of 8 or 16 bytes plus the halo pixel(s);
+// an output row leaves as one 16- or 8-byte store.  Sums are fp32, as everywhere.
+struct DwDirectBf16Args {
+    const bf16_t *x, *w;
     const float *scale, *shift, *bias;
-    const float *residual;
-    float *y;
+    const bf16_t *residual;
+    bf16_t *y;
+    int C, H, W, OH, OW;
+    int CB;            // column blocks per output row
+    int tpp;           // lane tasks per plane: row blocks x CB
+    int total;         // tasks in total
+    float inv_cb;
+    int relu;
+};
+
+template <int STRIDE, int CW, bool NT>
+__global__ __launch_bounds__(256) void dwconv3x3_direct_bf16_kernel(const DwDirectBf16Args a)
+{
+    const int g = blockIdx.x * 256 + threadIdx.x;
+    if (g >= a.total) return;
+    const int plane = g / a.tpp;
+    int cb;
+    const int rb = fast_div(g - plane * a.tpp, a.CB, a.inv_cb, &cb);
+    const int c = plane % a.C;
+    const int oh0 = rb * kRB, ow0 = cb * CW;
+    const int H = a.H, W = a.W;
+    const bf16_t *__restrict__ xp = a.x + (size_t)plane * H * W;
+
+    float wt[9];
+#pragma unroll
+    for (int e = 0; e < 9; ++e) wt[e] = bf16_to_f32(a.w[c * 9 + e]);
+    const float sc = a.scale[c];
+    const float sf = a.bias ? fmaf(a.bias[c], sc, a.shift[c]) : a.shift[c];
+
+    constexpr int IR = (kRB - 1) * STRIDE + 3;        // input rows of the block
+    constexpr int NIN = CW * STRIDE;                  // input pixels fetched as vectors
+    constexpr int NW = NIN / 2;                       // ... in 4-byte words
+    constexpr int NV = NIN + 2;                       // columns iw0 - 1 .. iw0 + NIN
+    float acc[kRB][CW];
+#pragma unroll
+    for (int o = 0; o < kRB; ++o)
+#pragma unroll
+        for (int q = 0; q < CW; ++q) acc[o][q] = 0.0f;
+
+    const int iw0 = ow0 * STRIDE;
+#pragma unroll
+    for (int rr = 0; rr < IR; ++rr) {
+        const int ih = oh0 * STRIDE - 1 + rr;
+        if (ih < 0 || ih >= H) continue;              // a padding row contributes nothing
+        const bf16_t *row = xp + ih * W + iw0;
+        uint32_t wd[NW];
+        if (NW == 2) {
+            const uint2v m = *reinterpret_cast<const uint2v *>(row);
+            wd[0] = m[0]; wd[1] = m[1];
+        } else {
+#pragma unroll
+            for (int k = 0; k < NW / 4; ++k) {
+                const uint4v m = reinterpret_cast<const uint4v *>(row)[k];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) wd[4 * k + e] = m[e];
+            }
+        }
+        float v[NV];
+        v[0] = iw0 > 0 ? bf16_to_f32(row[-1]) : 0.0f;
+#pragma unroll
+        for (int k = 0; k < NW; ++k) {
+            v[1 + 2 * k] = __uint_as_float(wd[k] << 16);
+            v[2 + 2 * k] = __uint_as_float(wd[k] & 0xFFFF0000u);
+        }
+        if (STRIDE == 1) v[NV - 1] = iw0 + NIN < W ? bf16_to_f32(row[NIN]) : 0.0f;
+#pragma unroll
+        for (int o = 0; o < kRB; ++o) {
+            const int r = rr - o * STRIDE;
+            if (r < 0 || r > 2) continue;
+#pragma unroll
+            for (int q = 0; q < CW; ++q)
+                acc[o][q] += v[q * STRIDE] * wt[r * 3] + v[q * STRIDE + 1] * wt[r * 3 + 1] +
+                             v[q * STRIDE + 2] * wt[r * 3 + 2];
+        }
+    }
+
+    typedef uint32_t outv __attribute__((ext_vector_type(CW / 2)));
+    const float floor_v = a.relu ? 0.0f : -INFINITY;
+#pragma unroll
+    for (int o = 0; o < kRB; ++o) {
+        const int oh = oh0 + o;
+        if (oh >= a.OH) continue;
+        const size_t idx = ((size_t)plane * a.OH + oh) * a.OW + ow0;
+        outv r;
+#pragma unroll
+        for (int k = 0; k < CW / 2; ++k) r[k] = 0u;
+        if (a.residual) r = *reinterpret_cast<const outv *>(a.residual + idx);
+        outv out;
+#pragma unroll
+        for (int k = 0; k < CW / 2; ++k) {
+            const float lo = fmaxf(fmaf(acc[o][2 * k], sc, sf) + __uint_as_float(r[k] << 16), floor_v);
+            const float hi = fmaxf(fmaf(acc[o][2 * k + 1], sc, sf) + __uint_as_float(r[k] & 0xFFFF0000u),
+                                   floor_v);
+            out[k] = f32x2_to_bf16x2(lo, hi);
+        }
+        stream_store<NT>(reinterpret_cast<outv *>(a.y + idx), out);
+    }
+}
+
+template <int STRIDE, int CW>
+void launch_direct_bf16(const DwDirectBf16Args &d, bool nt, unsigned blocks, hipStream_t stream)
+{
+    if (nt)
+        hipLaunchKernelGGL((dwconv3x3_direct_bf16_kernel<STRIDE, CW, true>), dim3(blocks), dim3(256), 0,
+                           stream, d);
+    else
+        hipLaunchKernelGGL((dwconv3x3_direct_bf16_kernel<STRIDE, CW, false>), dim3(blocks), dim3(256), 0,
+                           stream, d);
+}
+
+// Variant for small planes (at most 256 outputs per plane: 14x14 and 7x7 maps).  A
+// workgroup copies PG whole planes, which are one contiguous run of memory, into LDS (as
+// fp32) with 16-byte loads and no per-element index arithmetic; every lane then keeps ONE
+// output position (oh, ow) for the whole kernel, with its nine tap offsets and in-image
+// mask computed once, and walks over the planes of the group.
+struct DwSmallArgs {
+    const void *x, *w;
+    const float *scale, *shift, *bias;
+    const void *residual;
+    void *y;
     int planes, C, H, W, OH, OW, PG, relu;
 };
 
-template <int STRIDE, bool NT>
+template <typename T, int STRIDE, bool NT>
 __global__ __launch_bounds__(256) void dwconv3x3_smallplane_kernel(const DwSmallArgs a)
 {
     extern __shared__ float smem[];
@@ -246,18 +363,33 @@ __global__ __launch_bounds__(256) void dwconv3x3_smallplane_kernel(const DwSmall
     const int tid = threadIdx.x;
     const int p0 = blockIdx.x * a.PG;
     const int np = min(a.PG, a.planes - p0);
+    const T *__restrict__ wg = static_cast<const T *>(a.w);
 
-    // ---- copy the planes: contiguous, 16-byte aligned start (PG is a multiple of 4) --------
-    const float *src = a.x + (size_t)p0 * HW;
-    const int nflt = np * HW, nvec = nflt >> 2;
-    for (int i = tid; i < nvec; i += 256)
-        reinterpret_cast<float4v *>(tile)[i] = reinterpret_cast<const float4v *>(src)[i];
-    for (int i = (nvec << 2) + tid; i < nflt; i += 256) tile[i] = src[i];
+    // ---- copy the planes: contiguous, 16-byte aligned start (PG * sizeof(T) is a multiple of 16)
+    const T *src = static_cast<const T *>(a.x) + (size_t)p0 * HW;
+    const int nelem = np * HW;
+    constexpr int VE = 16 / sizeof(T);    // elements per 16-byte vector
+    const int nvec = nelem / VE;
+    for (int i = tid; i < nvec; i += 256) {
+        if (sizeof(T) == 4) {
+            reinterpret_cast<float4v *>(tile)[i] = reinterpret_cast<const float4v *>(src)[i];
+        } else {
+            const uint4v m = reinterpret_cast<const uint4v *>(src)[i];
+            float4v lo, hi;
+            lo[0] = __uint_as_float(m[0] << 16); lo[1] = __uint_as_float(m[0] & 0xFFFF0000u);
+            lo[2] = __uint_as_float(m[1] << 16); lo[3] = __uint_as_float(m[1] & 0xFFFF0000u);
+            hi[0] = __uint_as_float(m[2] << 16); hi[1] = __uint_as_float(m[2] & 0xFFFF0000u);
+            hi[2] = __uint_as_float(m[3] << 16); hi[3] = __uint_as_float(m[3] & 0xFFFF0000u);
+            reinterpret_cast<float4v *>(tile)[2 * i] = lo;
+            reinterpret_cast<float4v *>(tile)[2 * i + 1] = hi;
+        }
+    }
+    for (int i = nvec * VE + tid; i < nelem; i += 256) tile[i] = Elem<T>::load(src, i);
     for (int l = tid; l < np * 12; l += 256) {
         const int p = l / 12, e = l - p * 12;
         const int c = (p0 + p) % a.C;
         float v = 0.0f;
-        if (e < 9) v = a.w[c * 9 + e];
+        if (e < 9) v = Elem<T>::load(wg, c * 9 + e);
         else if (e == 9) v = a.scale[c];
         else if (e == 10) v = a.bias ? fmaf(a.bias[c], a.scale[c], a.shift[c]) : a.shift[c];
         prm[l] = v;
@@ -281,6 +413,8 @@ __global__ __launch_bounds__(256) void dwconv3x3_smallplane_kernel(const DwSmall
     __syncthreads();
     if (sub >= G) return;
 
+    const T *res = static_cast<const T *>(a.residual);
+    T *yg = static_cast<T *>(a.y);
     const float floor_v = a.relu ? 0.0f : -INFINITY;
     for (int p = sub; p < np; p += G) {
         const float *pl = tile + p * HW;
@@ -293,9 +427,23 @@ __global__ __launch_bounds__(256) void dwconv3x3_smallplane_kernel(const DwSmall
         }
         const size_t idx = (size_t)(p0 + p) * OHW + r0;
         float o = fmaf(acc, pp[9], pp[10]);
-        if (a.residual) o += a.residual[idx];
-        stream_store<NT>(a.y + idx, fmaxf(o, floor_v));     // a wave's lanes write one contiguous run
+        if (res) o += Elem<T>::load(res + idx, 0);
+        o = fmaxf(o, floor_v);
+        // a wave's lanes write one contiguous run; the hint pays on 4-byte elements only
+        if (sizeof(T) == 4) stream_store<NT>(reinterpret_cast<float *>(yg) + idx, o);
+        else Elem<T>::store(yg + idx, 0, o);
     }
+}
+
+template <typename T, int STRIDE>
+void launch_smallplane(const DwSmallArgs &d, bool nt, unsigned blocks, size_t lds, hipStream_t stream)
+{
+    if (nt && sizeof(T) == 4)
+        hipLaunchKernelGGL((dwconv3x3_smallplane_kernel<T, STRIDE, true>), dim3(blocks), dim3(256), lds,
+                           stream, d);
+    else
+        hipLaunchKernelGGL((dwconv3x3_smallplane_kernel<T, STRIDE, false>), dim3(blocks), dim3(256), lds,
+                           stream, d);
 }
 
 int ceil_log2(int v)
@@ -338,34 +486,62 @@ tvg_status launch_dwconv3x3(const ConvProblem &p, const ConvPointers &ptr, hipSt
         return hipGetLastError() == hipSuccess ? TVG_OK : TVG_ERR_LAUNCH;
     }
 
-    if (p.dtype == TVG_F32 && p.OH * p.OW <= 256 && reinterpret_cast<uintptr_t>(ptr.x) % 16 == 0) {
-        DwSmallArgs d;
-        d.x = static_cast<const float *>(ptr.x); d.w = static_cast<const float *>(ptr.w);
+    // bf16: 8 output columns per lane where the row allows, else 4; planes of at most 256
+    // outputs whose rows allow neither go to the small-plane kernel below
+    const int cw = p.OW % 8 == 0 ? 8 : p.OW % 4 == 0 ? 4 : 0;
+    const long btasks = cw ? (long)p.N * p.IC * ((p.OH + kRB - 1) / kRB) * (p.OW / cw) : 0;
+    if (p.dtype == TVG_BF16 && ptr16 && cw && (stride0 == 1 || p.W == 2 * p.OW) &&
+        reinterpret_cast<uintptr_t>(ptr.w) % 2 == 0 && btasks < (1L << 31) &&
+        (p.OH + kRB - 1) / kRB * (p.OW / cw) < (1 << 22)) {
+        DwDirectBf16Args d;
+        d.x = static_cast<const bf16_t *>(ptr.x); d.w = static_cast<const bf16_t *>(ptr.w);
         d.scale = ptr.scale; d.shift = ptr.shift; d.bias = ptr.bias;
-        d.residual = static_cast<const float *>(ptr.residual); d.y = static_cast<float *>(ptr.y);
+        d.residual = static_cast<const bf16_t *>(ptr.residual); d.y = static_cast<bf16_t *>(ptr.y);
+        d.C = p.IC; d.H = p.H; d.W = p.W; d.OH = p.OH; d.OW = p.OW;
+        d.CB = p.OW / cw;
+        d.tpp = (p.OH + kRB - 1) / kRB * d.CB;
+        d.total = (int)btasks;
+        d.inv_cb = 1.0f / (float)d.CB;
+        d.relu = p.relu;
+        const unsigned blocks = (unsigned)((btasks + 255) / 256);
+        const bool nt = p.stream_out != 0;
+        if (stride0 == 1 && cw == 8) launch_direct_bf16<1, 8>(d, nt, blocks, stream);
+        else if (stride0 == 1) launch_direct_bf16<1, 4>(d, nt, blocks, stream);
+        else if (cw == 8) launch_direct_bf16<2, 8>(d, nt, blocks, stream);
+        else launch_direct_bf16<2, 4>(d, nt, blocks, stream);
+        return hipGetLastError() == hipSuccess ? TVG_OK : TVG_ERR_LAUNCH;
+    }
+
+    if (p.OH * p.OW <= 256 && reinterpret_cast<uintptr_t>(ptr.x) % 16 == 0) {
+        DwSmallArgs d;
+        d.x = ptr.x; d.w = ptr.w;
+        d.scale = ptr.scale; d.shift = ptr.shift; d.bias = ptr.bias;
+        d.residual = ptr.residual; d.y = ptr.y;
         d.planes = p.N * p.IC; d.C = p.IC; d.H = p.H; d.W = p.W; d.OH = p.OH; d.OW = p.OW;
         d.relu = p.relu;
-        // planes per workgroup: a multiple of 4, about 2048 outputs, at most 40 KB of LDS,
-        // and no larger than leaves about four workgroups per CU
+        // planes per workgroup: a multiple of 4 (fp32) or 8 (bf16) so that every group starts
+        // on a 16-byte boundary, about 2048 outputs, at most 40 KB of LDS, and no larger than
+        // leaves about four workgroups per CU
+        const int unit = p.dtype == TVG_BF16 ? 8 : 4;
         const int hw = p.H * p.W, ohw = p.OH * p.OW;
         int pg = 2048 / ohw;
         const int cap_lds = (40 * 1024 / 4) / (hw + 12);
         if (pg > cap_lds) pg = cap_lds;
         const int cap_fill = d.planes / (4 * kComputeUnits);
-        if (cap_fill >= 4 && pg > cap_fill) pg = cap_fill;
-        pg = pg / 4 * 4;
-        if (pg >= 4) {
+        if (cap_fill >= unit && pg > cap_fill) pg = cap_fill;
+        pg = pg / unit * unit;
+        if (pg >= unit) {
             d.PG = pg;
             const size_t lds = (size_t)pg * (hw + 12) * sizeof(float);
             const unsigned blocks = (unsigned)((d.planes + pg - 1) / pg);
-            if (stride0 == 1 && p.stream_out)
-                hipLaunchKernelGGL((dwconv3x3_smallplane_kernel<1, true>), dim3(blocks), dim3(256), lds, stream, d);
-            else if (stride0 == 1)
-                hipLaunchKernelGGL((dwconv3x3_smallplane_kernel<1, false>), dim3(blocks), dim3(256), lds, stream, d);
-            else if (p.stream_out)
-                hipLaunchKernelGGL((dwconv3x3_smallplane_kernel<2, true>), dim3(blocks), dim3(256), lds, stream, d);
-            else
-                hipLaunchKernelGGL((dwconv3x3_smallplane_kernel<2, false>), dim3(blocks), dim3(256), lds, stream, d);
+            const bool nt = p.stream_out != 0;
+            if (p.dtype == TVG_BF16) {
+                if (stride0 == 1) launch_smallplane<bf16_t, 1>(d, nt, blocks, lds, stream);
+                else launch_smallplane<bf16_t, 2>(d, nt, blocks, lds, stream);
+            } else {
+                if (stride0 == 1) launch_smallplane<float, 1>(d, nt, blocks, lds, stream);
+                else launch_smallplane<float, 2>(d, nt, blocks, lds, stream);
+            }
             return hipGetLastError() == hipSuccess ? TVG_OK : TVG_ERR_LAUNCH;
         }
     }

@@ -72,7 +72,8 @@ def test_null_pointers_are_rejected():
 
 @pytest.mark.parametrize("kw,status", [
     (dict(k=16), 2), (dict(r=5, s=5, pad_h=2, pad_w=2), 3), (dict(stride_h=3, stride_w=3), 3),
-    (dict(stride_h=1, stride_w=2), 3),
+    (dict(stride_h=1, stride_w=2), 3), (dict(pad_h=0, pad_w=0), 3), (dict(pad_h=2, pad_w=2), 3),
+    (dict(pad_h=1, pad_w=0), 3),
 ])
 def test_depthwise_rejects_what_it_does_not_build(kw, status):
     d = desc(**kw)

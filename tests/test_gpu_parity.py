@@ -50,6 +50,25 @@ def test_config3_depthwise_fp32_batch1(tvg, i):
     assert rel_err(to_host(y), want) <= TOL["f32"]
 
 
+@pytest.mark.parametrize("i", range(9))
+def test_depthwise_bf16_table2_shapes_batch2(tvg, i):
+    """D1..D9 in bf16 with residual (the register-blocked bf16 kernel with 8 and 4 columns per
+    lane, the small-plane kernel), hinted and plain stores bit-identical."""
+    import torch
+    sh = ti.mobilenet_depthwise(2)[i]
+    inp = ti.make_inputs(sh, ti.layer_seed(3, 200 + i), "bf16", residual=True)
+    d = dev_inputs(inp, "bf16")
+    y = tvg.dwconv2d_fused(d["x"], d["w"], d["scale"], d["shift"], None, d["residual"],
+                           stride=sh.stride, pad=1, relu=True)
+    hinted = tvg.dwconv2d_fused(d["x"], d["w"], d["scale"], d["shift"], None, d["residual"],
+                                stride=sh.stride, pad=1, relu=True, stream_out=True)
+    torch.cuda.synchronize()
+    assert torch.equal(y.view(torch.int16), hinted.view(torch.int16))
+    want = oracle.dwconv2d_fused(inp["x"], inp["w"], inp["scale"], inp["shift"], None,
+                                 inp["residual"], stride=(sh.stride,) * 2, pad=(1, 1), relu=True)
+    assert rel_err(to_host(y), want) <= TOL["bf16"]
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("n,c,h,w,stride", [(3, 5, 9, 11, 1), (2, 7, 10, 13, 2), (1, 3, 1, 1, 1),
                                               (2, 70, 33, 65, 2), (1, 2, 130, 131, 1),
@@ -430,15 +449,20 @@ def run_body_gpu(tvg, steps, images, weights):
             tensors[st.dst] = tvg.conv2d_fused(src, p["w"], p["scale"], p["shift"], None, res,
                                                stride=st.shape.stride, pad=st.shape.pad,
                                                relu=st.relu)
+        elif st.op == "dwconv":
+            p = dev_w[st.layer_index]
+            tensors[st.dst] = tvg.dwconv2d_fused(src, p["w"], p["scale"], p["shift"], None, None,
+                                                 stride=st.shape.stride, pad=st.shape.pad,
+                                                 relu=st.relu)
         else:
             tensors[st.dst] = tvg.maxpool2d_3x3s2(src)
     torch.cuda.synchronize()
     return tensors
 
 
-def body_weights(steps):
-    return {s.layer_index: ti.make_weights(s.shape, ti.layer_seed(5, s.layer_index), "bf16")
-            for s in steps if s.op == "conv"}
+def body_weights(steps, config=5):
+    return {s.layer_index: ti.make_weights(s.shape, ti.layer_seed(config, s.layer_index), "bf16")
+            for s in steps if s.op in ("conv", "dwconv")}
 
 
 def test_config5_resnet18_body_bf16_small_batch_full(tvg):
@@ -593,4 +617,67 @@ def test_config5_resnet18_body_bf16_batch32_teacher_forced(tvg):
         # the sample's own RMS can be small; floor with the whole GPU tensor's RMS
         rho = float(np.sqrt(np.mean(out * out)))
         err = np.max(np.abs(out[idx] - want) / np.maximum(np.abs(want), rho))
+        assert err <= TOL["bf16"], (st.name, err)
+
+
+def oracle_layer(st, host, weights, idx=None):
+    p = weights[st.layer_index]
+    kw = dict(stride=(st.shape.stride,) * 2, pad=(st.shape.pad,) * 2, relu=st.relu)
+    if st.op == "dwconv":
+        y = oracle.dwconv2d_fused(host[st.src], p["w"], p["scale"], p["shift"], None, None, **kw)
+        return y if idx is None else y.reshape(-1)[idx]
+    if idx is None:
+        return oracle.conv2d_fused(host[st.src], p["w"], p["scale"], p["shift"], None, None, **kw)
+    return oracle.conv2d_fused_at(host[st.src], p["w"], p["scale"], p["shift"], None, None,
+                                  idx=idx, **kw)
+
+
+def test_mobilenet_body_bf16_small_batch_full(tvg):
+    """The 27-launch MobileNet body (stem, 13 x depthwise 3x3 + 1x1) at batch 2: every layer's
+    complete output against the oracle fed with the GPU's own input of that layer (2e-2), and
+    the last tensor against the oracle chain (fp64 per layer, stored as bf16) with the
+    end-to-end bounds of the ResNet-18 chain test scaled to 27 layers: rms 2.5e-2, worst
+    element 1e-1."""
+    from oracle.resnet_body import run_steps
+    steps = ti.mobilenet_body(2)
+    weights = body_weights(steps, config=6)
+    images = ti.body_images(2, ti.layer_seed(6, 900))
+    got = run_body_gpu(tvg, steps, images, weights)
+    host = {k: v.float().cpu().numpy() for k, v in got.items()}
+    for st in steps:
+        err = rel_err(host[st.dst], oracle_layer(st, host, weights))
+        assert err <= TOL["bf16"], (st.name, err)
+    want = run_steps(steps, images, weights)
+    final = steps[-1].dst
+    assert tuple(got[final].shape) == (2, 1024, 7, 7)
+    g, r = to_host(got[final]), want[final].astype(np.float64)
+    rho = float(np.sqrt(np.mean(r * r)))
+    assert float(np.sqrt(np.mean((g - r) ** 2))) / rho <= 2.5e-2
+    assert rel_err(g, r) <= 1e-1
+
+
+def test_mobilenet_body_bf16_batch32_teacher_forced(tvg):
+    """Batch 32, the launch configuration the benchmark times: sampled outputs of every layer
+    against the oracle fed with the GPU's own input of that layer (depthwise layers: the
+    first and the last image in full)."""
+    steps = ti.mobilenet_body(32)
+    weights = body_weights(steps, config=6)
+    images = ti.body_images(32, ti.layer_seed(6, 901))
+    got = run_body_gpu(tvg, steps, images, weights)
+    rng = np.random.default_rng(6)
+    for st in steps:
+        src = got[st.src].float().cpu().numpy()
+        out = got[st.dst].float().cpu().numpy().astype(np.float64)
+        rho = float(np.sqrt(np.mean(out * out)))
+        if st.op == "dwconv":
+            for img in (0, 31):
+                want = oracle_layer(st, {st.src: src[img:img + 1]}, weights)
+                err = np.max(np.abs(out[img:img + 1] - want) / np.maximum(np.abs(want), rho))
+                assert err <= TOL["bf16"], (st.name, img, err)
+            continue
+        flat = out.reshape(-1)
+        idx = np.unique(np.concatenate([np.arange(128), flat.size - 1 - np.arange(128),
+                                        rng.integers(0, flat.size, 1500)]))
+        want = oracle_layer(st, {st.src: src}, weights, idx)
+        err = np.max(np.abs(flat[idx] - want) / np.maximum(np.abs(want), rho))
         assert err <= TOL["bf16"], (st.name, err)

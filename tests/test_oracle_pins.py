@@ -332,3 +332,45 @@ def test_body_chain_small_runs_and_rounds():
     for t in out.values():
         assert np.array_equal(ti.quantize_bf16(t), t)
     assert out[steps[-1].dst].shape == (1, 64, 56, 56)
+
+
+def test_mobilenet_body_graph_has_the_expected_layers():
+    """13 depthwise + 13 pointwise + the stem; 567.7 M multiply-adds per image (the network's
+    published 569 M includes the 1.0 M of its classifier, which is not part of the body)."""
+    steps = ti.mobilenet_body(2)
+    from collections import Counter
+    assert Counter(s.op for s in steps) == {"conv": 14, "dwconv": 13}
+    cnt = Counter(s.shape.name for s in steps if s.op == "dwconv")
+    assert cnt == {"D1": 1, "D2": 1, "D3": 1, "D4": 1, "D5": 1, "D6": 1, "D7": 5, "D8": 1, "D9": 1}
+    assert sum(s.shape.flops for s in steps) // 2 == 2 * 567716352
+    prev = None
+    for s in steps:                                 # a plain chain: each layer reads the last one
+        if prev is not None:
+            assert s.src == prev.dst and s.shape.x_shape() == prev.shape.y_shape()
+        prev = s
+    assert steps[-1].shape.y_shape() == (2, 1024, 7, 7)
+    assert [s.layer_index for s in steps] == list(range(27))
+
+
+@pytest.mark.parametrize("stride", [1, 2])
+def test_chain_depthwise_then_pointwise_equals_the_factorised_dense_conv(stride):
+    """A depthwise 3x3 followed by a 1x1 conv (no tail in between) is the dense 3x3 conv with
+    weights pw[oc][c] * dw[c][r][s]: pins the chain's depthwise step and its wiring against
+    the dense operator."""
+    from oracle.resnet_body import run_steps
+    rng = np.random.default_rng(77 + stride)
+    n, c, h, w, oc = 2, 5, 9, 8, 7
+    d = ti.ConvShape("d", n, c, h, w, c, 3, 3, stride, 1, depthwise=True)
+    p = ti.ConvShape("p", n, c, d.oh, d.ow, oc, 1, 1, 1, 0)
+    steps = [ti.Step("dwconv", "dw", 0, 1, d, None, False, 0), ti.Step("conv", "pw", 1, 2, p, None, True, 1)]
+    wd, wp = rand(rng, c, 1, 3, 3), rand(rng, oc, c, 1, 1)
+    scale, shift = rand(rng, oc) + 2.0, rand(rng, oc)
+    weights = {0: {"w": wd, "scale": np.ones(c, np.float32), "shift": np.zeros(c, np.float32)},
+               1: {"w": wp, "scale": scale, "shift": shift}}
+    x = rand(rng, n, c, h, w)
+    got = run_steps(steps, x, weights, store_bf16=False)[2]
+    dense_w = (wp[:, :, 0, 0][:, :, None, None].astype(np.float64) * wd[:, 0][None].astype(np.float64))
+    want = oracle.conv2d_fused(x, dense_w.astype(np.float32), scale, shift, None, None,
+                               stride=(stride, stride), pad=(1, 1), relu=True)
+    assert got.shape == want.shape == (n, oc, d.oh, d.ow)
+    np.testing.assert_allclose(got, want, rtol=0, atol=2e-6)     # fp32 storage of the two stages

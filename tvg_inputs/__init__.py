@@ -183,8 +183,8 @@ def config1_shape() -> ConvShape:
 
 @dataclass(frozen=True)
 class Step:
-    """One launch of the ResNet-18 body: tensors are named by small integer ids."""
-    op: str                      # "conv" or "maxpool"
+    """One launch of a network body: tensors are named by small integer ids."""
+    op: str                      # "conv", "dwconv" or "maxpool"
     name: str
     src: int
     dst: int
@@ -235,6 +235,30 @@ def resnet18_body(n: int = 32) -> List[Step]:
     t = basic_block("s3b2", t, C["C9"], C["C9"])
     t = basic_block("s4b1", t, C["C10"], C["C12"], C["C11"])
     t = basic_block("s4b2", t, C["C12"], C["C12"])
+    return steps
+
+
+def mobilenet_body(n: int = 32) -> List[Step]:
+    """MobileNet (v1, width 1, 224 x 224) convolutional body as a flat launch list.
+
+    Stem: 3x3 stride-2 conv 3 -> 32, then 13 blocks of a depthwise 3x3 conv (Table 2's
+    D1..D9, D7 five times) followed by a 1x1 conv; every layer carries scale/shift + ReLU.
+    27 launches; tensor 0 = the images, the last tensor is [n][1024][7][7].
+    """
+    D = {s.name: s for s in mobilenet_depthwise(n)}
+    blocks = [("D1", 64), ("D2", 128), ("D3", 128), ("D4", 256), ("D5", 256), ("D6", 512),
+              ("D7", 512), ("D7", 512), ("D7", 512), ("D7", 512), ("D7", 512), ("D8", 1024),
+              ("D9", 1024)]
+    steps: List[Step] = [Step("conv", "stem", 0, 1, ConvShape("M0", n, 3, 224, 224, 32, 3, 3, 2, 1),
+                              None, True, 0)]
+    t, layer = 1, 1
+    for b, (dname, oc) in enumerate(blocks, start=1):
+        d = D[dname]
+        steps.append(Step("dwconv", f"b{b}.dw", t, t + 1, d, None, True, layer))
+        pw = ConvShape(f"P{b}", n, d.ic, d.oh, d.ow, oc, 1, 1, 1, 0)
+        steps.append(Step("conv", f"b{b}.pw", t + 1, t + 2, pw, None, True, layer + 1))
+        t += 2
+        layer += 2
     return steps
 
 
