@@ -163,6 +163,27 @@ def dwconv2d_fused(x, w, scale, shift, bias=None, residual=None, *, stride=(1, 1
     return y
 
 
+def dwpw_fused(x, w_dw, scale_dw, shift_dw, w_pw, scale_pw, shift_pw, bias_pw=None,
+               residual=None, *, stride=1, relu_dw=True, relu_pw=True, store="bf16") -> np.ndarray:
+    """Depthwise 3x3 (pad 1) + tail, then 1x1 conv + tail: the MobileNet block that the fused
+    GPU operator evaluates in one launch (Section 3, operator fusion; Table 2 rows D).
+
+    This is the definition, two oracle calls: the depthwise result is rounded to the storage
+    type between them (``store`` = "bf16": nearest bfloat16; "f32": nearest float32), because
+    the operator's second stage reads values of that type.  fp64 output.
+    """
+    t = dwconv2d_fused(x, w_dw, scale_dw, shift_dw, None, None, stride=(stride, stride),
+                       pad=(1, 1), relu=relu_dw)
+    if store == "bf16":
+        t = round_to_bf16(t)
+    elif store == "f32":
+        t = t.astype(np.float32)
+    else:
+        raise ValueError(store)
+    return conv2d_fused(t, w_pw, scale_pw, shift_pw, bias_pw, residual, stride=(1, 1), pad=(0, 0),
+                        relu=relu_pw)
+
+
 def maxpool2d(x, *, k=3, stride=2, pad=1) -> np.ndarray:
     """Max-pool with padded taps ignored, fp64 output."""
     lib = _load()

@@ -374,3 +374,36 @@ def test_chain_depthwise_then_pointwise_equals_the_factorised_dense_conv(stride)
                                stride=(stride, stride), pad=(1, 1), relu=True)
     assert got.shape == want.shape == (n, oc, d.oh, d.ow)
     np.testing.assert_allclose(got, want, rtol=0, atol=2e-6)     # fp32 storage of the two stages
+
+
+@pytest.mark.parametrize("stride", [1, 2])
+def test_dwpw_block_equals_the_factorised_dense_conv_and_a_matmul(stride):
+    """The MobileNet block oracle against two independent forms.  (1) Without a depthwise
+    tail it is the dense 3x3 conv with weights pw[k][c] * dw[c][r][s].  (2) With the tail,
+    the second stage is a plain matrix product over channels of the brute-force depthwise
+    result (scale/shift/ReLU applied, rounded to bf16 by the input module's bit routine)."""
+    rng = np.random.default_rng(910 + stride)
+    n, c, h, w, k = 2, 6, 7, 10, 5
+    x, wd, wp = rand(rng, n, c, h, w), rand(rng, c, 1, 3, 3), rand(rng, k, c, 1, 1)
+    sd, fd = rand(rng, c) + 2.0, rand(rng, c)
+    sp, fp, bp = rand(rng, k) + 2.0, rand(rng, k), rand(rng, k)
+    ones, zeros = np.ones(c, np.float32), np.zeros(c, np.float32)
+    got = oracle.dwpw_fused(x, wd, ones, zeros, wp, sp, fp, stride=stride, relu_dw=False,
+                            relu_pw=True, store="f32")
+    dense_w = wp[:, :, 0, 0][:, :, None, None].astype(np.float64) * wd[:, 0][None].astype(np.float64)
+    want = oracle.conv2d_fused(x, dense_w.astype(np.float32), sp, fp, None, None,
+                               stride=(stride, stride), pad=(1, 1), relu=True)
+    np.testing.assert_allclose(got, want, rtol=0, atol=2e-6)
+
+    t = brute_depthwise(x, wd, (stride, stride), (1, 1)) * sd.astype(np.float64)[None, :, None, None] \
+        + fd.astype(np.float64)[None, :, None, None]
+    t = ti.quantize_bf16(np.maximum(t, 0.0).astype(np.float32)).astype(np.float64)
+    oh, ow = t.shape[2:]
+    res = rand(rng, n, k, oh, ow)
+    z = np.einsum("kc,nchw->nkhw", wp[:, :, 0, 0].astype(np.float64), t)
+    z = (z + bp.astype(np.float64)[None, :, None, None]) * sp.astype(np.float64)[None, :, None, None] \
+        + fp.astype(np.float64)[None, :, None, None] + res
+    got = oracle.dwpw_fused(x, wd, sd, fd, wp, sp, fp, bp, res, stride=stride, relu_dw=True,
+                            relu_pw=False, store="bf16")
+    # the bf16 rounding of t can flip where the fp64 and float32 sums straddle a tie: none here
+    np.testing.assert_allclose(got, z, rtol=0, atol=1e-9)
