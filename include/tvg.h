@@ -115,6 +115,34 @@ tvg_status tvg_dwconv2d_fused(const tvg_conv_desc *desc, const void *x, const vo
                               void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * MobileNet block: depthwise 3x3 conv2d and the 1x1 conv2d that follows it, as one operator
+ * (Section 3, operator fusion, carried across the two operators of the block; Table 2 rows D
+ * are its first stage):
+ *   t = tail_dw(depthwise3x3(x, w_dw)), rounded to dtype     tail_dw: t*scale_dw[c] + shift_dw[c],
+ *                                                            max(t, 0) if dw_desc->flags has TVG_RELU
+ *   y = tail_pw(conv1x1(t, w_pw))                            the fused tail of tvg_conv2d_fused with
+ *                                                            scale_pw, shift_pw, bias_pw, residual,
+ *                                                            pw_flags (TVG_RELU, TVG_STREAM_OUT)
+ * dw_desc describes the depthwise stage as for tvg_dwconv2d_fused (k == c, 3x3, pad 1, stride 1
+ * or 2); pw_k is the number of output channels of the 1x1 stage.
+ *   x [n][c][h][w]; w_dw [c][1][3][3]; w_pw [pw_k][c][1][1]; scale_dw, shift_dw fp32 [c];
+ *   scale_pw, shift_pw fp32 [pw_k]; bias_pw fp32 [pw_k] or NULL; residual [n][pw_k][oh][ow] or
+ *   NULL; y [n][pw_k][oh][ow], written completely.  All device pointers; x, w_pw, residual and y
+ *   must be 16-byte aligned (TVG_ERR_UNSUPPORTED otherwise).
+ * bf16 problems whose maps are small enough (tvg_dwpw_workspace_size() == 0) run as ONE kernel:
+ * t is produced in LDS as the pixel operand of the 1x1 stage and never reaches memory.  Every
+ * other problem runs as the two kernels back to back with t in `workspace` (at least
+ * tvg_dwpw_workspace_size() bytes, 256-byte aligned; TVG_ERR_WORKSPACE otherwise); the results
+ * of both forms follow the definition above.
+ */
+tvg_status tvg_dwpw_workspace_size(const tvg_conv_desc *dw_desc, int32_t pw_k, size_t *bytes);
+tvg_status tvg_dwpw_fused(const tvg_conv_desc *dw_desc, int32_t pw_k, uint32_t pw_flags,
+                          const void *x, const void *w_dw, const float *scale_dw,
+                          const float *shift_dw, const void *w_pw, const float *scale_pw,
+                          const float *shift_pw, const float *bias_pw, const void *residual,
+                          void *y, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * 3x3 stride-2 pad-1 max-pool, NCHW, padded taps ignored.  Support operator
  * for running the ResNet-18 body (the stem's 112x112 output must become the
  * 56x56 input of Table 2's C2).  x [n][c][h][w] -> y [n][c][oh][ow] with

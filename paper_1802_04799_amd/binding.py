@@ -70,6 +70,10 @@ def load() -> ctypes.CDLL:
     for f in (lib.tvg_conv2d_fused, lib.tvg_dwconv2d_fused):
         f.restype = ctypes.c_int
         f.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.tvg_dwpw_workspace_size.restype = ctypes.c_int
+    lib.tvg_dwpw_workspace_size.argtypes = [dp, ctypes.c_int32, ctypes.POINTER(sz)]
+    lib.tvg_dwpw_fused.restype = ctypes.c_int
+    lib.tvg_dwpw_fused.argtypes = [dp, ctypes.c_int32, ctypes.c_uint32] + [vp] * 10 + [vp, sz, vp]
     lib.tvg_maxpool2d_3x3s2.restype = ctypes.c_int
     lib.tvg_maxpool2d_3x3s2.argtypes = [ctypes.c_int32] * 5 + [vp, vp, vp]
     lib.tvg_status_string.restype = ctypes.c_char_p
@@ -160,6 +164,23 @@ def tvg_dwconv2d_fused(desc, x, w, scale, shift, bias, residual, y, workspace=No
                                          _addr(workspace), workspace_bytes, _stream(stream)))
 
 
+def tvg_dwpw_workspace_size(dw_desc: ConvDesc, pw_k: int) -> int:
+    out = ctypes.c_size_t(0)
+    st = load().tvg_dwpw_workspace_size(ctypes.byref(dw_desc), int(pw_k), ctypes.byref(out))
+    if st != TVG_OK:
+        raise TvgError(st, "tvg_dwpw_workspace_size")
+    return int(out.value)
+
+
+def tvg_dwpw_fused(dw_desc, pw_k, pw_flags, x, w_dw, scale_dw, shift_dw, w_pw, scale_pw, shift_pw,
+                   bias_pw, residual, y, workspace=None, workspace_bytes=0, stream=None) -> int:
+    return int(load().tvg_dwpw_fused(ctypes.byref(dw_desc), int(pw_k), int(pw_flags), _addr(x),
+                                     _addr(w_dw), _addr(scale_dw), _addr(shift_dw), _addr(w_pw),
+                                     _addr(scale_pw), _addr(shift_pw), _addr(bias_pw),
+                                     _addr(residual), _addr(y), _addr(workspace), workspace_bytes,
+                                     _stream(stream)))
+
+
 def tvg_maxpool2d_3x3s2(n, c, h, w, dtype, x, y, stream=None) -> int:
     return int(load().tvg_maxpool2d_3x3s2(n, c, h, w, dtype, _addr(x), _addr(y), _stream(stream)))
 
@@ -233,6 +254,32 @@ def dwconv2d_fused(x, w, scale, shift, bias=None, residual=None, *, stride=1, pa
     st = tvg_dwconv2d_fused(desc, x, w, scale, shift, bias, residual, out, None, 0, stream)
     if st != TVG_OK:
         raise TvgError(st, "tvg_dwconv2d_fused")
+    return out
+
+
+def dwpw_fused(x, w_dw, scale_dw, shift_dw, w_pw, scale_pw, shift_pw, bias_pw=None, residual=None, *,
+               stride=1, relu_dw=True, relu_pw=True, out=None, workspace=None, stream=None,
+               stream_out=False):
+    """MobileNet block (depthwise 3x3 + tail, 1x1 conv + tail) through tvg_dwpw_fused;
+    allocates y (and the workspace when the problem runs as two kernels) with torch."""
+    import torch
+    _check(x, w_pw, scale_pw, shift_pw, bias_pw, residual)
+    _check(x, w_dw, scale_dw, shift_dw, None, None)
+    desc = make_desc(x, w_dw, stride, 1, relu_dw, depthwise=True)
+    k = w_pw.shape[0]
+    if w_pw.shape[1] != x.shape[1] or tuple(w_pw.shape[2:]) != (1, 1):
+        raise ValueError("w_pw must be [k][c][1][1]")
+    flags = (TVG_RELU if relu_pw else 0) | (TVG_STREAM_OUT if stream_out else 0)
+    need = tvg_dwpw_workspace_size(desc, k)
+    if out is None:
+        out = torch.empty((desc.n, k, desc.oh, desc.ow), dtype=x.dtype, device=x.device)
+    if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = tvg_dwpw_fused(desc, k, flags, x, w_dw, scale_dw, shift_dw, w_pw, scale_pw, shift_pw,
+                        bias_pw, residual, out, workspace, ws_bytes, stream)
+    if st != TVG_OK:
+        raise TvgError(st, "tvg_dwpw_fused")
     return out
 
 

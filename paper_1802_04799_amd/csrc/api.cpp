@@ -4,6 +4,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <initializer_list>
 #include <mutex>
 #include <vector>
 #include "tvg_internal.h"
@@ -221,6 +222,80 @@ tvg_status tvg_dwconv2d_fused(const tvg_conv_desc *desc, const void *x, const vo
     if (!x || !w || !scale || !shift || !y) return TVG_ERR_NULL;
     tvg::ConvPointers ptr{x, w, scale, shift, bias, residual, y, nullptr};
     return tvg::launch_dwconv3x3(p, ptr, static_cast<hipStream_t>(hip_stream));
+}
+
+// The 1x1 stage of the block as a problem of its own: reads the depthwise stage's output.
+static tvg_status make_pw_problem(const tvg_conv_desc *dw_desc, const ConvProblem &dw, int32_t pw_k,
+                                  uint32_t pw_flags, ConvProblem *pw)
+{
+    if (pw_k < 1) return TVG_ERR_BAD_SHAPE;
+    tvg_conv_desc d = *dw_desc;
+    d.h = dw.OH; d.w = dw.OW; d.k = pw_k; d.r = d.s = 1;
+    d.stride_h = d.stride_w = 1; d.pad_h = d.pad_w = 0;
+    d.flags = pw_flags;
+    return make_problem(&d, false, pw);
+}
+
+static size_t dwpw_workspace(const ConvProblem &dw, const ConvProblem &pw)
+{
+    tvg::DwPwPlan plan;
+    if (tvg::plan_dwpw(dw, pw.OC, &plan)) return 0;
+    const size_t elem = dw.dtype == TVG_BF16 ? 2 : 4;
+    size_t bytes = ((size_t)dw.N * dw.IC * dw.OH * dw.OW * elem + 255) & ~(size_t)255;
+    tvg::Pw1x1Plan p1;
+    if (!tvg::plan_conv1x1(pw, &p1)) bytes += tvg::plan_conv(pw).workspace_bytes;   // split-K scratch
+    return bytes;
+}
+
+tvg_status tvg_dwpw_workspace_size(const tvg_conv_desc *dw_desc, int32_t pw_k, size_t *bytes)
+{
+    if (!bytes) return TVG_ERR_NULL;
+    ConvProblem dw, pw;
+    tvg_status st = make_problem(dw_desc, true, &dw);
+    if (st != TVG_OK) return st;
+    st = make_pw_problem(dw_desc, dw, pw_k, 0, &pw);
+    if (st != TVG_OK) return st;
+    *bytes = dwpw_workspace(dw, pw);
+    return TVG_OK;
+}
+
+tvg_status tvg_dwpw_fused(const tvg_conv_desc *dw_desc, int32_t pw_k, uint32_t pw_flags,
+                          const void *x, const void *w_dw, const float *scale_dw,
+                          const float *shift_dw, const void *w_pw, const float *scale_pw,
+                          const float *shift_pw, const float *bias_pw, const void *residual,
+                          void *y, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    ConvProblem dw, pw;
+    tvg_status st = make_problem(dw_desc, true, &dw);
+    if (st != TVG_OK) return st;
+    st = make_pw_problem(dw_desc, dw, pw_k, pw_flags, &pw);
+    if (st != TVG_OK) return st;
+    if (!x || !w_dw || !scale_dw || !shift_dw || !w_pw || !scale_pw || !shift_pw || !y)
+        return TVG_ERR_NULL;
+    for (const void *q : {x, w_pw, residual, (const void *)y})
+        if (reinterpret_cast<uintptr_t>(q) % 16 != 0) return TVG_ERR_UNSUPPORTED;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    tvg::DwPwPlan plan;
+    if (tvg::plan_dwpw(dw, pw.OC, &plan)) {
+        const tvg::DwPwPointers ptr{x, w_dw, scale_dw, shift_dw, w_pw, scale_pw, shift_pw, bias_pw,
+                                    residual, y};
+        return tvg::launch_dwpw(dw, pw.OC, pw.relu, pw.stream_out, plan, ptr, stream);
+    }
+    const size_t need = dwpw_workspace(dw, pw);
+    if (!workspace || workspace_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 256 != 0)
+        return TVG_ERR_WORKSPACE;
+    const size_t elem = dw.dtype == TVG_BF16 ? 2 : 4;
+    const size_t t_bytes = ((size_t)dw.N * dw.IC * dw.OH * dw.OW * elem + 255) & ~(size_t)255;
+    dw.stream_out = 0;                       // t is read by the next launch
+    const tvg::ConvPointers dptr{x, w_dw, scale_dw, shift_dw, nullptr, nullptr, workspace, nullptr};
+    st = tvg::launch_dwconv3x3(dw, dptr, stream);
+    if (st != TVG_OK) return st;
+    const tvg::ConvPointers pptr{workspace, w_pw, scale_pw, shift_pw, bias_pw, residual, y,
+                                 reinterpret_cast<float *>(static_cast<char *>(workspace) + t_bytes)};
+    tvg::Pw1x1Plan p1;
+    if (tvg::plan_conv1x1(pw, &p1) && tvg::conv1x1_pointers_ok(pptr))
+        return tvg::launch_conv1x1(pw, p1, pptr, stream);
+    return tvg::launch_conv_igemm(pw, tvg::plan_conv(pw), pptr, stream);
 }
 
 tvg_status tvg_maxpool2d_3x3s2(int32_t n, int32_t c, int32_t h, int32_t w, int32_t dtype,

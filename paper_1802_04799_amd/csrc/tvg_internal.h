@@ -94,6 +94,24 @@ bool conv1x1_pointers_ok(const ConvPointers &ptr);
 tvg_status launch_conv1x1(const ConvProblem &p, const Pw1x1Plan &plan, const ConvPointers &ptr,
                           hipStream_t stream);
 
+// bf16 MobileNet block in one kernel: depthwise 3x3 (pad 1, stride 1) computed in LDS as the
+// pixel operand of the 1x1 stage.  `dw` is the depthwise problem, OC the 1x1 stage's channels.
+struct DwPwPlan {
+    int mt, lt;        // output channels per workgroup, patch dwords per loader thread
+    long tiles;
+};
+struct DwPwPointers {
+    const void *x, *w_dw;
+    const float *scale_dw, *shift_dw;
+    const void *w_pw;
+    const float *scale_pw, *shift_pw, *bias_pw;
+    const void *residual;
+    void *y;
+};
+bool plan_dwpw(const ConvProblem &dw, int OC, DwPwPlan *plan);
+tvg_status launch_dwpw(const ConvProblem &dw, int OC, int pw_relu, int pw_stream_out,
+                       const DwPwPlan &plan, const DwPwPointers &ptr, hipStream_t stream);
+
 tvg_status launch_conv_igemm(const ConvProblem &p, const ConvPlan &plan, const ConvPointers &ptr,
                              hipStream_t stream);
 tvg_status launch_dwconv3x3(const ConvProblem &p, const ConvPointers &ptr, hipStream_t stream);

@@ -26,7 +26,8 @@ def test_every_declared_symbol_is_exported():
     names = set(re.findall(r"\b(tvg_[a-z0-9_]+)\s*\(", header))
     assert {"tvg_conv2d_fused", "tvg_dwconv2d_fused", "tvg_conv2d_workspace_size",
             "tvg_dwconv2d_workspace_size", "tvg_maxpool2d_3x3s2", "tvg_status_string",
-            "tvg_version", "tvg_conv2d_set_tile", "tvg_conv2d_get_plan"} <= names
+            "tvg_version", "tvg_conv2d_set_tile", "tvg_conv2d_get_plan", "tvg_dwpw_fused",
+            "tvg_dwpw_workspace_size"} <= names
     lib = tvg.load()
     for n in names:
         assert hasattr(lib, n), n
@@ -126,6 +127,44 @@ def test_tile_table_sets_overrides_and_forgets():
     assert tvg.tvg_conv2d_get_plan(desc(n=64, c=128, h=28, w=28, k=256, r=1, s=1, stride_h=2,
                                         stride_w=2, pad_h=0, pad_w=0, dtype=tvg.TVG_BF16)) == (4, 128, 64)
     assert tvg.tvg_conv2d_get_plan(desc(n=1, c=64, h=56, w=56, k=64))[0] == 0
+
+
+def test_block_entry_point_validates_on_the_host():
+    """tvg_dwpw_fused / tvg_dwpw_workspace_size: which problems run as one kernel, and every
+    error path before a device call."""
+    small = desc(n=32, c=512, h=14, w=14, k=512, dtype=tvg.TVG_BF16, flags=tvg.TVG_RELU)
+    assert tvg.tvg_dwpw_workspace_size(small, 512) == 0                 # one kernel
+    assert tvg.tvg_dwpw_workspace_size(desc(n=32, c=1024, h=7, w=7, k=1024, dtype=tvg.TVG_BF16), 1024) == 0
+    wide = desc(n=2, c=32, h=112, w=112, k=32, dtype=tvg.TVG_BF16)
+    assert tvg.tvg_dwpw_workspace_size(wide, 64) == 2 * 32 * 112 * 112 * 2   # two kernels, t in between
+    s2 = desc(n=2, c=64, h=14, w=14, k=64, stride_h=2, stride_w=2, dtype=tvg.TVG_BF16)
+    assert tvg.tvg_dwpw_workspace_size(s2, 64) == 2 * 64 * 7 * 7 * 2
+    f32 = desc(n=1, c=32, h=14, w=14, k=32)
+    assert tvg.tvg_dwpw_workspace_size(f32, 8) >= 32 * 14 * 14 * 4
+    odd = desc(n=1, c=24, h=14, w=14, k=24, dtype=tvg.TVG_BF16)        # channels not a multiple of 32
+    assert tvg.tvg_dwpw_workspace_size(odd, 8) > 0
+    A = 0x10000
+    args = [A] * 7 + [None, None, A]        # x w_dw scale_dw shift_dw w_pw scale_pw shift_pw bias res y
+    assert tvg.tvg_dwpw_fused(small, 0, 0, *args, stream=0) == 2
+    assert tvg.tvg_dwpw_fused(small, 512, 4, *args, stream=0) == 3               # unknown flag
+    assert tvg.tvg_dwpw_fused(desc(k=16), 8, 0, *args, stream=0) == 2            # not depthwise
+    assert tvg.tvg_dwpw_fused(desc(k=8, c=8, pad_h=0, pad_w=0), 8, 0, *args, stream=0) == 3
+    for missing in (0, 1, 2, 3, 4, 5, 6, 9):
+        a2 = list(args)
+        a2[missing] = None
+        assert tvg.tvg_dwpw_fused(small, 512, 0, *a2, stream=0) == 1
+    for k in (0, 4, 8, 9):                                             # x, w_pw, residual, y alignment
+        a2 = list(args)
+        a2[k] = A + 8
+        assert tvg.tvg_dwpw_fused(small, 512, 0, *a2, stream=0) == 3
+    assert tvg.tvg_dwpw_fused(wide, 64, 0, *args, stream=0) == 4                 # needs a workspace
+    need = tvg.tvg_dwpw_workspace_size(wide, 64)
+    assert tvg.tvg_dwpw_fused(wide, 64, 0, *args, A, need - 1, 0) == 4
+    assert tvg.tvg_dwpw_fused(wide, 64, 0, *args, A + 64, need, 0) == 4
+    with pytest.raises(tvg.TvgError):
+        tvg.tvg_dwpw_workspace_size(desc(k=16), 8)
+    lib = tvg.load()
+    assert lib.tvg_dwpw_workspace_size(ctypes.byref(small), 8, None) == 1
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):

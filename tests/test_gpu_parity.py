@@ -681,3 +681,86 @@ def test_mobilenet_body_bf16_batch32_teacher_forced(tvg):
         want = oracle_layer(st, {st.src: src}, weights, idx)
         err = np.max(np.abs(flat[idx] - want) / np.maximum(np.abs(want), rho))
         assert err <= TOL["bf16"], (st.name, err)
+
+
+# ------------------------------------------------------------------------------------------
+# MobileNet block: depthwise 3x3 + 1x1 through tvg_dwpw_fused (one kernel where the map is
+# small, two kernels otherwise)
+# ------------------------------------------------------------------------------------------
+
+def block_inputs(n, c, h, w, k, stride, dtype, seed, residual, bias):
+    d = ti.ConvShape("bd", n, c, h, w, c, 3, 3, stride, 1, depthwise=True)
+    p = ti.ConvShape("bp", n, c, d.oh, d.ow, k, 1, 1, 1, 0)
+    a = ti.make_inputs(d, seed, dtype)
+    b = ti.make_inputs(p, seed + 1, dtype, residual=residual, bias=bias)
+    return d, p, a, b
+
+
+def run_block(tvg, d, a, b, dtype, stride, relu_dw, relu_pw, hint=False):
+    import torch
+    dev = lambda v, t=dtype: to_dev(v, t)
+    y = tvg.dwpw_fused(dev(a["x"]), dev(a["w"]), dev(a["scale"], "f32"), dev(a["shift"], "f32"),
+                       dev(b["w"]), dev(b["scale"], "f32"), dev(b["shift"], "f32"),
+                       dev(b["bias"], "f32"), dev(b["residual"]), stride=stride, relu_dw=relu_dw,
+                       relu_pw=relu_pw, stream_out=hint)
+    torch.cuda.synchronize()
+    return y
+
+
+def oracle_block(a, b, dtype, stride, relu_dw, relu_pw):
+    return oracle.dwpw_fused(a["x"], a["w"], a["scale"], a["shift"], b["w"], b["scale"], b["shift"],
+                             b["bias"], b["residual"], stride=stride, relu_dw=relu_dw,
+                             relu_pw=relu_pw, store=dtype)
+
+
+# (n, c, h, w, k): maps small enough for the one-kernel form (bf16, stride 1, c % 32 == 0)
+BLOCK_FUSED = [(2, 256, 28, 28, 256), (2, 512, 14, 14, 512), (2, 1024, 7, 7, 1024),   # MobileNet
+               (3, 64, 7, 7, 40), (1, 32, 6, 6, 8), (5, 96, 9, 5, 130), (2, 32, 28, 28, 64),
+               (1, 64, 16, 8, 200), (7, 32, 5, 7, 64), (2, 128, 3, 40, 96), (1, 32, 33, 1, 70),
+               (4, 160, 11, 13, 129), (1, 32, 8, 4, 1), (9, 64, 6, 6, 257), (1, 32, 56, 56, 64),
+               (2, 64, 20, 62, 32)]
+
+
+@pytest.mark.parametrize("cfg", BLOCK_FUSED, ids=lambda c: "x".join(map(str, c)))
+def test_block_one_kernel_form(tvg, cfg):
+    n, c, h, w, k = cfg
+    seed = 7100 + sum(cfg)
+    variant = seed % 4
+    residual, bias = variant in (1, 3), variant in (2, 3)
+    relu_dw, relu_pw = variant != 2, variant != 1
+    d, p, a, b = block_inputs(n, c, h, w, k, 1, "bf16", seed, residual, bias)
+    desc = tvg.ConvDesc(n, c, h, w, c, 3, 3, 1, 1, 1, 1, tvg.TVG_BF16, 0)
+    assert tvg.tvg_dwpw_workspace_size(desc, k) == 0
+    y = run_block(tvg, d, a, b, "bf16", 1, relu_dw, relu_pw)
+    assert tuple(y.shape) == p.y_shape()
+    assert rel_err(to_host(y), oracle_block(a, b, "bf16", 1, relu_dw, relu_pw)) <= TOL["bf16"]
+    hinted = run_block(tvg, d, a, b, "bf16", 1, relu_dw, relu_pw, hint=True)
+    import torch
+    assert torch.equal(y.view(torch.int16), hinted.view(torch.int16))
+
+
+@pytest.mark.parametrize("cfg", [(2, 64, 14, 14, 64, 2, "bf16"), (1, 32, 112, 112, 64, 1, "bf16"),
+                                 (1, 16, 9, 9, 8, 1, "f32"), (2, 24, 14, 14, 40, 1, "bf16"),
+                                 (1, 8, 12, 16, 24, 2, "f32"), (2, 32, 5, 5, 16, 1, "bf16")],
+                         ids=lambda c: "x".join(map(str, c)))
+def test_block_two_kernel_form(tvg, cfg):
+    n, c, h, w, k, stride, dtype = cfg
+    d, p, a, b = block_inputs(n, c, h, w, k, stride, dtype, 7300 + sum(cfg[:6]), True, True)
+    code = tvg.TVG_BF16 if dtype == "bf16" else tvg.TVG_F32
+    desc = tvg.ConvDesc(n, c, h, w, c, 3, 3, stride, stride, 1, 1, code, 0)
+    assert tvg.tvg_dwpw_workspace_size(desc, k) > 0
+    y = run_block(tvg, d, a, b, dtype, stride, True, True)
+    assert tuple(y.shape) == p.y_shape()
+    assert rel_err(to_host(y), oracle_block(a, b, dtype, stride, True, True)) <= TOL[dtype]
+
+
+def test_block_one_kernel_form_batch32_sampled(tvg):
+    """MobileNet's 14x14 block (512 -> 512) at batch 32, the benchmark's launch configuration:
+    one image in full and the last image's last channels against the oracle."""
+    n, c, hw, k = 32, 512, 14, 512
+    d, p, a, b = block_inputs(n, c, hw, hw, k, 1, "bf16", 7401, False, False)
+    y = to_host(run_block(tvg, d, a, b, "bf16", 1, True, True))
+    for img in (0, 17, 31):
+        a1 = dict(a, x=a["x"][img:img + 1])
+        want = oracle_block(a1, b, "bf16", 1, True, True)
+        assert rel_err(y[img:img + 1], want) <= TOL["bf16"], img
