@@ -129,13 +129,20 @@ tvg_status tvg_dwconv2d_fused(const tvg_conv_desc *desc, const void *x, const vo
  *   scale_pw, shift_pw fp32 [pw_k]; bias_pw fp32 [pw_k] or NULL; residual [n][pw_k][oh][ow] or
  *   NULL; y [n][pw_k][oh][ow], written completely.  All device pointers; x, w_pw, residual and y
  *   must be 16-byte aligned (TVG_ERR_UNSUPPORTED otherwise).
- * bf16 problems whose maps are small enough (tvg_dwpw_workspace_size() == 0) run as ONE kernel:
- * t is produced in LDS as the pixel operand of the 1x1 stage and never reaches memory.  Every
- * other problem runs as the two kernels back to back with t in `workspace` (at least
- * tvg_dwpw_workspace_size() bytes, 256-byte aligned; TVG_ERR_WORKSPACE otherwise); the results
- * of both forms follow the definition above.
+ * Two forms compute this, and the workspace argument selects between them:
+ *   - with a workspace of at least tvg_dwpw_workspace_size() bytes (256-byte aligned): the two
+ *     kernels back to back, t held in the workspace.  This is the faster form on every shape
+ *     measured so far and what a caller with memory to spare should use.
+ *   - with workspace == NULL: ONE kernel, for callers that cannot spare the intermediate; t is
+ *     produced in LDS as the pixel operand of the 1x1 stage and never reaches memory.  Exists
+ *     for bf16, stride 1, c a multiple of 32 and maps whose rows are short enough
+ *     (tvg_dwpw_one_kernel() says whether a problem qualifies); TVG_ERR_WORKSPACE otherwise.
+ * A workspace that is too small or misaligned is TVG_ERR_WORKSPACE.  Both forms follow the
+ * definition above (t rounded to dtype between the stages).
  */
 tvg_status tvg_dwpw_workspace_size(const tvg_conv_desc *dw_desc, int32_t pw_k, size_t *bytes);
+/* *available = 1 if the one-kernel form exists for this problem, else 0.  Host only. */
+tvg_status tvg_dwpw_one_kernel(const tvg_conv_desc *dw_desc, int32_t pw_k, int32_t *available);
 tvg_status tvg_dwpw_fused(const tvg_conv_desc *dw_desc, int32_t pw_k, uint32_t pw_flags,
                           const void *x, const void *w_dw, const float *scale_dw,
                           const float *shift_dw, const void *w_pw, const float *scale_pw,

@@ -72,6 +72,8 @@ def load() -> ctypes.CDLL:
         f.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.tvg_dwpw_workspace_size.restype = ctypes.c_int
     lib.tvg_dwpw_workspace_size.argtypes = [dp, ctypes.c_int32, ctypes.POINTER(sz)]
+    lib.tvg_dwpw_one_kernel.restype = ctypes.c_int
+    lib.tvg_dwpw_one_kernel.argtypes = [dp, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)]
     lib.tvg_dwpw_fused.restype = ctypes.c_int
     lib.tvg_dwpw_fused.argtypes = [dp, ctypes.c_int32, ctypes.c_uint32] + [vp] * 10 + [vp, sz, vp]
     lib.tvg_maxpool2d_3x3s2.restype = ctypes.c_int
@@ -172,6 +174,14 @@ def tvg_dwpw_workspace_size(dw_desc: ConvDesc, pw_k: int) -> int:
     return int(out.value)
 
 
+def tvg_dwpw_one_kernel(dw_desc: ConvDesc, pw_k: int) -> bool:
+    out = ctypes.c_int32(0)
+    st = load().tvg_dwpw_one_kernel(ctypes.byref(dw_desc), int(pw_k), ctypes.byref(out))
+    if st != TVG_OK:
+        raise TvgError(st, "tvg_dwpw_one_kernel")
+    return bool(out.value)
+
+
 def tvg_dwpw_fused(dw_desc, pw_k, pw_flags, x, w_dw, scale_dw, shift_dw, w_pw, scale_pw, shift_pw,
                    bias_pw, residual, y, workspace=None, workspace_bytes=0, stream=None) -> int:
     return int(load().tvg_dwpw_fused(ctypes.byref(dw_desc), int(pw_k), int(pw_flags), _addr(x),
@@ -259,9 +269,10 @@ def dwconv2d_fused(x, w, scale, shift, bias=None, residual=None, *, stride=1, pa
 
 def dwpw_fused(x, w_dw, scale_dw, shift_dw, w_pw, scale_pw, shift_pw, bias_pw=None, residual=None, *,
                stride=1, relu_dw=True, relu_pw=True, out=None, workspace=None, stream=None,
-               stream_out=False):
+               stream_out=False, one_kernel=False):
     """MobileNet block (depthwise 3x3 + tail, 1x1 conv + tail) through tvg_dwpw_fused;
-    allocates y (and the workspace when the problem runs as two kernels) with torch."""
+    allocates y with torch, and the workspace of the two-kernel form unless ``one_kernel``
+    asks for the form that needs none."""
     import torch
     _check(x, w_pw, scale_pw, shift_pw, bias_pw, residual)
     _check(x, w_dw, scale_dw, shift_dw, None, None)
@@ -270,11 +281,14 @@ def dwpw_fused(x, w_dw, scale_dw, shift_dw, w_pw, scale_pw, shift_pw, bias_pw=No
     if w_pw.shape[1] != x.shape[1] or tuple(w_pw.shape[2:]) != (1, 1):
         raise ValueError("w_pw must be [k][c][1][1]")
     flags = (TVG_RELU if relu_pw else 0) | (TVG_STREAM_OUT if stream_out else 0)
-    need = tvg_dwpw_workspace_size(desc, k)
     if out is None:
         out = torch.empty((desc.n, k, desc.oh, desc.ow), dtype=x.dtype, device=x.device)
-    if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
-        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    if one_kernel:
+        workspace = None
+    else:
+        need = tvg_dwpw_workspace_size(desc, k)
+        if workspace is None or workspace.numel() * workspace.element_size() < need:
+            workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     st = tvg_dwpw_fused(desc, k, flags, x, w_dw, scale_dw, shift_dw, w_pw, scale_pw, shift_pw,
                         bias_pw, residual, out, workspace, ws_bytes, stream)

@@ -238,8 +238,6 @@ static tvg_status make_pw_problem(const tvg_conv_desc *dw_desc, const ConvProble
 
 static size_t dwpw_workspace(const ConvProblem &dw, const ConvProblem &pw)
 {
-    tvg::DwPwPlan plan;
-    if (tvg::plan_dwpw(dw, pw.OC, &plan)) return 0;
     const size_t elem = dw.dtype == TVG_BF16 ? 2 : 4;
     size_t bytes = ((size_t)dw.N * dw.IC * dw.OH * dw.OW * elem + 255) & ~(size_t)255;
     tvg::Pw1x1Plan p1;
@@ -256,6 +254,19 @@ tvg_status tvg_dwpw_workspace_size(const tvg_conv_desc *dw_desc, int32_t pw_k, s
     st = make_pw_problem(dw_desc, dw, pw_k, 0, &pw);
     if (st != TVG_OK) return st;
     *bytes = dwpw_workspace(dw, pw);
+    return TVG_OK;
+}
+
+tvg_status tvg_dwpw_one_kernel(const tvg_conv_desc *dw_desc, int32_t pw_k, int32_t *available)
+{
+    if (!available) return TVG_ERR_NULL;
+    ConvProblem dw, pw;
+    tvg_status st = make_problem(dw_desc, true, &dw);
+    if (st != TVG_OK) return st;
+    st = make_pw_problem(dw_desc, dw, pw_k, 0, &pw);
+    if (st != TVG_OK) return st;
+    tvg::DwPwPlan plan;
+    *available = tvg::plan_dwpw(dw, pw.OC, &plan) ? 1 : 0;
     return TVG_OK;
 }
 
@@ -276,7 +287,8 @@ tvg_status tvg_dwpw_fused(const tvg_conv_desc *dw_desc, int32_t pw_k, uint32_t p
         if (reinterpret_cast<uintptr_t>(q) % 16 != 0) return TVG_ERR_UNSUPPORTED;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     tvg::DwPwPlan plan;
-    if (tvg::plan_dwpw(dw, pw.OC, &plan)) {
+    if (!workspace && workspace_bytes == 0) {          // the caller asks for the one-kernel form
+        if (!tvg::plan_dwpw(dw, pw.OC, &plan)) return TVG_ERR_WORKSPACE;
         const tvg::DwPwPointers ptr{x, w_dw, scale_dw, shift_dw, w_pw, scale_pw, shift_pw, bias_pw,
                                     residual, y};
         return tvg::launch_dwpw(dw, pw.OC, pw.relu, pw.stream_out, plan, ptr, stream);

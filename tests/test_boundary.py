@@ -27,7 +27,7 @@ def test_every_declared_symbol_is_exported():
     assert {"tvg_conv2d_fused", "tvg_dwconv2d_fused", "tvg_conv2d_workspace_size",
             "tvg_dwconv2d_workspace_size", "tvg_maxpool2d_3x3s2", "tvg_status_string",
             "tvg_version", "tvg_conv2d_set_tile", "tvg_conv2d_get_plan", "tvg_dwpw_fused",
-            "tvg_dwpw_workspace_size"} <= names
+            "tvg_dwpw_workspace_size", "tvg_dwpw_one_kernel"} <= names
     lib = tvg.load()
     for n in names:
         assert hasattr(lib, n), n
@@ -130,19 +130,24 @@ def test_tile_table_sets_overrides_and_forgets():
 
 
 def test_block_entry_point_validates_on_the_host():
-    """tvg_dwpw_fused / tvg_dwpw_workspace_size: which problems run as one kernel, and every
-    error path before a device call."""
+    """tvg_dwpw_fused / tvg_dwpw_workspace_size / tvg_dwpw_one_kernel: which problems have the
+    one-kernel form, the workspace of the two-kernel form, and every error path before a
+    device call."""
     small = desc(n=32, c=512, h=14, w=14, k=512, dtype=tvg.TVG_BF16, flags=tvg.TVG_RELU)
-    assert tvg.tvg_dwpw_workspace_size(small, 512) == 0                 # one kernel
-    assert tvg.tvg_dwpw_workspace_size(desc(n=32, c=1024, h=7, w=7, k=1024, dtype=tvg.TVG_BF16), 1024) == 0
+    assert tvg.tvg_dwpw_one_kernel(small, 512)
+    assert tvg.tvg_dwpw_one_kernel(desc(n=32, c=1024, h=7, w=7, k=1024, dtype=tvg.TVG_BF16), 1024)
+    assert tvg.tvg_dwpw_workspace_size(small, 512) == 32 * 512 * 14 * 14 * 2
     wide = desc(n=2, c=32, h=112, w=112, k=32, dtype=tvg.TVG_BF16)
-    assert tvg.tvg_dwpw_workspace_size(wide, 64) == 2 * 32 * 112 * 112 * 2   # two kernels, t in between
+    assert not tvg.tvg_dwpw_one_kernel(wide, 64)                        # rows too long
+    assert tvg.tvg_dwpw_workspace_size(wide, 64) == 2 * 32 * 112 * 112 * 2
     s2 = desc(n=2, c=64, h=14, w=14, k=64, stride_h=2, stride_w=2, dtype=tvg.TVG_BF16)
-    assert tvg.tvg_dwpw_workspace_size(s2, 64) == 2 * 64 * 7 * 7 * 2
+    assert not tvg.tvg_dwpw_one_kernel(s2, 64)
+    assert tvg.tvg_dwpw_workspace_size(s2, 64) == 2 * 64 * 7 * 7 * 2         # 12544 = 49 * 256
     f32 = desc(n=1, c=32, h=14, w=14, k=32)
+    assert not tvg.tvg_dwpw_one_kernel(f32, 8)
     assert tvg.tvg_dwpw_workspace_size(f32, 8) >= 32 * 14 * 14 * 4
     odd = desc(n=1, c=24, h=14, w=14, k=24, dtype=tvg.TVG_BF16)        # channels not a multiple of 32
-    assert tvg.tvg_dwpw_workspace_size(odd, 8) > 0
+    assert not tvg.tvg_dwpw_one_kernel(odd, 8)
     A = 0x10000
     args = [A] * 7 + [None, None, A]        # x w_dw scale_dw shift_dw w_pw scale_pw shift_pw bias res y
     assert tvg.tvg_dwpw_fused(small, 0, 0, *args, stream=0) == 2
@@ -157,14 +162,18 @@ def test_block_entry_point_validates_on_the_host():
         a2 = list(args)
         a2[k] = A + 8
         assert tvg.tvg_dwpw_fused(small, 512, 0, *a2, stream=0) == 3
-    assert tvg.tvg_dwpw_fused(wide, 64, 0, *args, stream=0) == 4                 # needs a workspace
+    assert tvg.tvg_dwpw_fused(wide, 64, 0, *args, stream=0) == 4       # no one-kernel form, no workspace
     need = tvg.tvg_dwpw_workspace_size(wide, 64)
     assert tvg.tvg_dwpw_fused(wide, 64, 0, *args, A, need - 1, 0) == 4
     assert tvg.tvg_dwpw_fused(wide, 64, 0, *args, A + 64, need, 0) == 4
+    assert tvg.tvg_dwpw_fused(small, 512, 0, *args, A, 16, 0) == 4     # a workspace, but too small
     with pytest.raises(tvg.TvgError):
         tvg.tvg_dwpw_workspace_size(desc(k=16), 8)
+    with pytest.raises(tvg.TvgError):
+        tvg.tvg_dwpw_one_kernel(desc(k=16), 8)
     lib = tvg.load()
     assert lib.tvg_dwpw_workspace_size(ctypes.byref(small), 8, None) == 1
+    assert lib.tvg_dwpw_one_kernel(ctypes.byref(small), 8, None) == 1
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):

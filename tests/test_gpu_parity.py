@@ -696,13 +696,13 @@ def block_inputs(n, c, h, w, k, stride, dtype, seed, residual, bias):
     return d, p, a, b
 
 
-def run_block(tvg, d, a, b, dtype, stride, relu_dw, relu_pw, hint=False):
+def run_block(tvg, d, a, b, dtype, stride, relu_dw, relu_pw, hint=False, one_kernel=False):
     import torch
     dev = lambda v, t=dtype: to_dev(v, t)
     y = tvg.dwpw_fused(dev(a["x"]), dev(a["w"]), dev(a["scale"], "f32"), dev(a["shift"], "f32"),
                        dev(b["w"]), dev(b["scale"], "f32"), dev(b["shift"], "f32"),
                        dev(b["bias"], "f32"), dev(b["residual"]), stride=stride, relu_dw=relu_dw,
-                       relu_pw=relu_pw, stream_out=hint)
+                       relu_pw=relu_pw, stream_out=hint, one_kernel=one_kernel)
     torch.cuda.synchronize()
     return y
 
@@ -730,13 +730,17 @@ def test_block_one_kernel_form(tvg, cfg):
     relu_dw, relu_pw = variant != 2, variant != 1
     d, p, a, b = block_inputs(n, c, h, w, k, 1, "bf16", seed, residual, bias)
     desc = tvg.ConvDesc(n, c, h, w, c, 3, 3, 1, 1, 1, 1, tvg.TVG_BF16, 0)
-    assert tvg.tvg_dwpw_workspace_size(desc, k) == 0
-    y = run_block(tvg, d, a, b, "bf16", 1, relu_dw, relu_pw)
+    assert tvg.tvg_dwpw_one_kernel(desc, k)
+    want = oracle_block(a, b, "bf16", 1, relu_dw, relu_pw)
+    y = run_block(tvg, d, a, b, "bf16", 1, relu_dw, relu_pw, one_kernel=True)
     assert tuple(y.shape) == p.y_shape()
-    assert rel_err(to_host(y), oracle_block(a, b, "bf16", 1, relu_dw, relu_pw)) <= TOL["bf16"]
-    hinted = run_block(tvg, d, a, b, "bf16", 1, relu_dw, relu_pw, hint=True)
+    assert rel_err(to_host(y), want) <= TOL["bf16"]
+    hinted = run_block(tvg, d, a, b, "bf16", 1, relu_dw, relu_pw, hint=True, one_kernel=True)
     import torch
     assert torch.equal(y.view(torch.int16), hinted.view(torch.int16))
+    # the same problem as two kernels (a workspace is passed)
+    two = run_block(tvg, d, a, b, "bf16", 1, relu_dw, relu_pw)
+    assert rel_err(to_host(two), want) <= TOL["bf16"]
 
 
 @pytest.mark.parametrize("cfg", [(2, 64, 14, 14, 64, 2, "bf16"), (1, 32, 112, 112, 64, 1, "bf16"),
@@ -748,7 +752,7 @@ def test_block_two_kernel_form(tvg, cfg):
     d, p, a, b = block_inputs(n, c, h, w, k, stride, dtype, 7300 + sum(cfg[:6]), True, True)
     code = tvg.TVG_BF16 if dtype == "bf16" else tvg.TVG_F32
     desc = tvg.ConvDesc(n, c, h, w, c, 3, 3, stride, stride, 1, 1, code, 0)
-    assert tvg.tvg_dwpw_workspace_size(desc, k) > 0
+    assert not tvg.tvg_dwpw_one_kernel(desc, k)
     y = run_block(tvg, d, a, b, dtype, stride, True, True)
     assert tuple(y.shape) == p.y_shape()
     assert rel_err(to_host(y), oracle_block(a, b, dtype, stride, True, True)) <= TOL[dtype]
@@ -759,7 +763,7 @@ def test_block_one_kernel_form_batch32_sampled(tvg):
     one image in full and the last image's last channels against the oracle."""
     n, c, hw, k = 32, 512, 14, 512
     d, p, a, b = block_inputs(n, c, hw, hw, k, 1, "bf16", 7401, False, False)
-    y = to_host(run_block(tvg, d, a, b, "bf16", 1, True, True))
+    y = to_host(run_block(tvg, d, a, b, "bf16", 1, True, True, one_kernel=True))
     for img in (0, 17, 31):
         a1 = dict(a, x=a["x"][img:img + 1])
         want = oracle_block(a1, b, "bf16", 1, True, True)
