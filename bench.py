@@ -48,6 +48,9 @@ def parse():
     ap.add_argument("--depthwise-probe", action="store_true",
                     help="only launch the depthwise layers D1..D9 at batch 64 --steps times each "
                          "(for profiler runs)")
+    ap.add_argument("--body-probe", default="", choices=["", "resnet18", "mobilenet"],
+                    help="only run this network body at batch 32 --warmup + --steps times "
+                         "(for profiler runs)")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
                     help="only run a plain device copy of this many MiB --steps times "
                          "(reference for scaling FETCH_SIZE / WRITE_SIZE counters)")
@@ -133,6 +136,11 @@ def main():
             torch.cuda.synchronize()
             del l
         print(json.dumps({"depthwise_probe": "D1..D9 batch 64 fp32", "launches_each": args.warmup + args.steps}))
+        return
+    if args.body_probe:
+        r = bench_body(tvg, ti, torch, np, dev, to_dev, time_loop, args.body_probe,
+                       iters=args.steps, warmup=args.warmup, graph=False)
+        print(json.dumps({"body_probe": args.body_probe, **r}))
         return
     shapes = ti.resnet18_convs(64)
     layers = [Layer(sh, ti.layer_seed(4, i), "bf16") for i, sh in enumerate(shapes)]
@@ -335,7 +343,8 @@ def measured_traffic(kernel):
         return None
 
 
-def bench_body(tvg, ti, torch, np, dev, to_dev, time_loop, network="resnet18"):
+def bench_body(tvg, ti, torch, np, dev, to_dev, time_loop, network="resnet18", iters=10, warmup=3,
+               graph=True):
     n = 32
     config = 5 if network == "resnet18" else 6
     steps = ti.resnet18_body(n) if network == "resnet18" else ti.mobilenet_body(n)
@@ -380,15 +389,17 @@ def bench_body(tvg, ti, torch, np, dev, to_dev, time_loop, network="resnet18"):
             if st != 0:
                 raise RuntimeError(tvg.status_string(st))
 
-    ms = time_loop(forward, 10)
-    # The same 21 launches captured once into a HIP graph and replayed: the library neither
-    # allocates nor synchronises, so the chain records as it stands.
-    graph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(graph, stream=torch.cuda.Stream()):
-        forward()
-    graph_ms = time_loop(graph.replay, 10)
+    ms = time_loop(forward, iters, warmup)
+    graph_ms = float("nan")
+    if graph:
+        # The same launches captured once into a HIP graph and replayed: the library neither
+        # allocates nor synchronises, so the chain records as it stands.
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=torch.cuda.Stream()):
+            forward()
+        graph_ms = time_loop(g.replay, 10)
     flops = sum(s.shape.flops for s in steps if s.op != "maxpool")
-    return {"batch": n, "launches": len(calls), "ms": round(ms, 4), "graph_replay_ms": round(graph_ms, 4),
+    return {"batch": n, "launches": len(calls), "ms": round(ms, 4), "graph_replay_ms": round(graph_ms, 4) if graph else None,
             "tflops": round(flops / (ms * 1e-3) / 1e12, 1),
             "images_per_s": round(n / (ms * 1e-3), 1),
             "frac_mfma_peak": round(flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}
