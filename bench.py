@@ -353,6 +353,19 @@ def bench_body(tvg, ti, torch, np, dev, to_dev, time_loop, network="resnet18", i
     dw = {k: {"w": to_dev(p["w"], True), "scale": to_dev(p["scale"], False),
               "shift": to_dev(p["shift"], False)} for k, p in weights.items()}
     images = to_dev(ti.body_images(n, ti.layer_seed(config, 901)), True)
+    # Static memory plan (paper Section 3): every intermediate tensor lives in one arena, at the
+    # offset tvg_plan_arena gives it; tensors that are never alive together share memory.  The
+    # images stay outside (the chain is replayed on them).
+    lives = ti.tensor_lives(steps)
+    ids = [t for t in lives if t != 0]
+    offsets, arena_bytes = tvg.tvg_plan_arena([lives[t] for t in ids])
+    arena = torch.empty(arena_bytes, dtype=torch.uint8, device=dev)
+    offset_of = dict(zip(ids, offsets))
+
+    def planned(t, shape):
+        nbytes = lives[t][0]
+        return arena[offset_of[t]:offset_of[t] + nbytes].view(torch.bfloat16).view(shape)
+
     tensors = {0: images}
     calls = []
     for st in steps:
@@ -361,7 +374,7 @@ def bench_body(tvg, ti, torch, np, dev, to_dev, time_loop, network="resnet18", i
             sh = st.shape
             desc = tvg.ConvDesc(sh.n, sh.ic, sh.h, sh.w, sh.oc, 3, 3, sh.stride, sh.stride, 1, 1,
                                 tvg.TVG_BF16, tvg.TVG_RELU if st.relu else 0)
-            y = torch.empty(sh.y_shape(), dtype=torch.bfloat16, device=dev)
+            y = planned(st.dst, sh.y_shape())
             p = dw[st.layer_index]
             calls.append((tvg.tvg_dwconv2d_fused, (desc, src, p["w"], p["scale"], p["shift"], None,
                                                    None, y, None, 0, None)))
@@ -369,7 +382,7 @@ def bench_body(tvg, ti, torch, np, dev, to_dev, time_loop, network="resnet18", i
             sh = st.shape
             desc = tvg.ConvDesc(sh.n, sh.ic, sh.h, sh.w, sh.oc, sh.r, sh.s, sh.stride, sh.stride,
                                 sh.pad, sh.pad, tvg.TVG_BF16, tvg.TVG_RELU if st.relu else 0)
-            y = torch.empty(sh.y_shape(), dtype=torch.bfloat16, device=dev)
+            y = planned(st.dst, sh.y_shape())
             need = tvg.tvg_conv2d_workspace_size(desc)
             ws = torch.empty(max(need, 1), dtype=torch.uint8, device=dev)
             p = dw[st.layer_index]
@@ -378,8 +391,7 @@ def bench_body(tvg, ti, torch, np, dev, to_dev, time_loop, network="resnet18", i
                                                  res, y, ws, need, None)))
         else:
             nn, c, h, w = src.shape
-            y = torch.empty((nn, c, (h - 1) // 2 + 1, (w - 1) // 2 + 1), dtype=torch.bfloat16,
-                            device=dev)
+            y = planned(st.dst, (nn, c, (h - 1) // 2 + 1, (w - 1) // 2 + 1))
             calls.append((tvg.tvg_maxpool2d_3x3s2, (nn, c, h, w, tvg.TVG_BF16, src, y, None)))
         tensors[st.dst] = y
 
@@ -399,7 +411,8 @@ def bench_body(tvg, ti, torch, np, dev, to_dev, time_loop, network="resnet18", i
             forward()
         graph_ms = time_loop(g.replay, 10)
     flops = sum(s.shape.flops for s in steps if s.op != "maxpool")
-    return {"batch": n, "launches": len(calls), "ms": round(ms, 4), "graph_replay_ms": round(graph_ms, 4) if graph else None,
+    return {"batch": n, "launches": len(calls), "arena_mb": round(arena_bytes / 1e6, 1),
+            "unplanned_mb": round(sum(lives[t][0] for t in ids) / 1e6, 1), "ms": round(ms, 4), "graph_replay_ms": round(graph_ms, 4) if graph else None,
             "tflops": round(flops / (ms * 1e-3) / 1e12, 1),
             "images_per_s": round(n / (ms * 1e-3), 1),
             "frac_mfma_peak": round(flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}

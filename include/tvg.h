@@ -159,6 +159,28 @@ tvg_status tvg_maxpool2d_3x3s2(int32_t n, int32_t c, int32_t h, int32_t w, int32
                                const void *x, void *y, void *hip_stream);
 
 /*
+ * Static memory plan (TVM paper Section 3: after fusion a static memory planning pass
+ * pre-allocates the memory of every intermediate tensor).  Host-only.  Given each tensor's size
+ * and the launches during which it must stay intact - from the launch that writes it
+ * (first_step) to the last launch that reads it (last_step), both inclusive - the call assigns
+ * byte offsets in one arena so that tensors whose intervals intersect never overlap (so an
+ * operator's output never overlaps its own inputs) while tensors that are never alive together
+ * share memory.  Offsets are multiples of 256.  Greedy: largest tensor first, lowest offset that
+ * is free over its whole interval; deterministic.
+ *   tensors  host, `count` entries (1 <= count <= 4096; bytes >= 1; 0 <= first_step <= last_step)
+ *   offsets  host, `count` entries, written
+ *   arena_bytes  host, written: the arena's size (a multiple of 256)
+ * Returns TVG_ERR_NULL, TVG_ERR_BAD_SHAPE (count or an entry out of range) or TVG_OK.
+ */
+typedef struct tvg_tensor_life {
+    uint64_t bytes;
+    int32_t first_step;
+    int32_t last_step;
+} tvg_tensor_life;
+tvg_status tvg_plan_arena(const tvg_tensor_life *tensors, int32_t count, uint64_t *offsets,
+                          uint64_t *arena_bytes);
+
+/*
  * Tuning (TVM paper Section 5: the schedule of an operator is chosen per shape by measurement).
  * The tile shape of a kernel - output channels x pixels per workgroup - is its main knob; the
  * library picks one by a measured rule, and a caller that has timed the alternatives on its own

@@ -37,6 +37,12 @@ class ConvDesc(ctypes.Structure):
         return (self.w + 2 * self.pad_w - self.s) // self.stride_w + 1
 
 
+class TensorLife(ctypes.Structure):
+    """Mirror of tvg_tensor_life."""
+    _fields_ = [("bytes", ctypes.c_uint64), ("first_step", ctypes.c_int32),
+                ("last_step", ctypes.c_int32)]
+
+
 _lib: Optional[ctypes.CDLL] = None
 
 
@@ -76,6 +82,9 @@ def load() -> ctypes.CDLL:
     lib.tvg_dwpw_one_kernel.argtypes = [dp, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)]
     lib.tvg_dwpw_fused.restype = ctypes.c_int
     lib.tvg_dwpw_fused.argtypes = [dp, ctypes.c_int32, ctypes.c_uint32] + [vp] * 10 + [vp, sz, vp]
+    lib.tvg_plan_arena.restype = ctypes.c_int
+    lib.tvg_plan_arena.argtypes = [ctypes.POINTER(TensorLife), ctypes.c_int32,
+                                   ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint64)]
     lib.tvg_maxpool2d_3x3s2.restype = ctypes.c_int
     lib.tvg_maxpool2d_3x3s2.argtypes = [ctypes.c_int32] * 5 + [vp, vp, vp]
     lib.tvg_status_string.restype = ctypes.c_char_p
@@ -189,6 +198,18 @@ def tvg_dwpw_fused(dw_desc, pw_k, pw_flags, x, w_dw, scale_dw, shift_dw, w_pw, s
                                      _addr(scale_pw), _addr(shift_pw), _addr(bias_pw),
                                      _addr(residual), _addr(y), _addr(workspace), workspace_bytes,
                                      _stream(stream)))
+
+
+def tvg_plan_arena(lives):
+    """lives: sequence of (bytes, first_step, last_step).  Returns (offsets, arena_bytes)."""
+    n = len(lives)
+    arr = (TensorLife * max(n, 1))(*[TensorLife(int(b), int(f), int(l)) for b, f, l in lives])
+    offs = (ctypes.c_uint64 * max(n, 1))()
+    total = ctypes.c_uint64(0)
+    st = load().tvg_plan_arena(arr, n, offs, ctypes.byref(total))
+    if st != TVG_OK:
+        raise TvgError(st, "tvg_plan_arena")
+    return [int(o) for o in offs[:n]], int(total.value)
 
 
 def tvg_maxpool2d_3x3s2(n, c, h, w, dtype, x, y, stream=None) -> int:

@@ -4,7 +4,9 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <algorithm>
 #include <initializer_list>
+#include <utility>
 #include <mutex>
 #include <vector>
 #include "tvg_internal.h"
@@ -308,6 +310,48 @@ tvg_status tvg_dwpw_fused(const tvg_conv_desc *dw_desc, int32_t pw_k, uint32_t p
     if (tvg::plan_conv1x1(pw, &p1) && tvg::conv1x1_pointers_ok(pptr))
         return tvg::launch_conv1x1(pw, p1, pptr, stream);
     return tvg::launch_conv_igemm(pw, tvg::plan_conv(pw), pptr, stream);
+}
+
+tvg_status tvg_plan_arena(const tvg_tensor_life *tensors, int32_t count, uint64_t *offsets,
+                          uint64_t *arena_bytes)
+{
+    if (!tensors || !offsets || !arena_bytes) return TVG_ERR_NULL;
+    if (count < 1 || count > 4096) return TVG_ERR_BAD_SHAPE;
+    for (int32_t i = 0; i < count; ++i)
+        if (tensors[i].bytes < 1 || tensors[i].bytes > ((uint64_t)1 << 48) ||
+            tensors[i].first_step < 0 || tensors[i].last_step < tensors[i].first_step)
+            return TVG_ERR_BAD_SHAPE;
+    const uint64_t kAlign = 256;
+    std::vector<int32_t> order(count);
+    for (int32_t i = 0; i < count; ++i) order[i] = i;
+    std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
+        return tensors[a].bytes > tensors[b].bytes;          // ties keep their index order
+    });
+    std::vector<char> placed(count, 0);
+    std::vector<std::pair<uint64_t, uint64_t>> busy;          // [begin, end) of conflicting tensors
+    uint64_t arena = 0;
+    for (int32_t oi = 0; oi < count; ++oi) {
+        const int32_t t = order[oi];
+        const uint64_t size = (tensors[t].bytes + kAlign - 1) / kAlign * kAlign;
+        busy.clear();
+        for (int32_t j = 0; j < count; ++j)
+            if (placed[j] && tensors[j].first_step <= tensors[t].last_step &&
+                tensors[t].first_step <= tensors[j].last_step) {
+                const uint64_t sz = (tensors[j].bytes + kAlign - 1) / kAlign * kAlign;
+                busy.emplace_back(offsets[j], offsets[j] + sz);
+            }
+        std::sort(busy.begin(), busy.end());
+        uint64_t at = 0;                                      // lowest gap that holds `size`
+        for (const auto &b : busy) {
+            if (b.first >= at + size) break;
+            if (b.second > at) at = b.second;
+        }
+        offsets[t] = at;
+        placed[t] = 1;
+        if (at + size > arena) arena = at + size;
+    }
+    *arena_bytes = arena;
+    return TVG_OK;
 }
 
 tvg_status tvg_maxpool2d_3x3s2(int32_t n, int32_t c, int32_t h, int32_t w, int32_t dtype,

@@ -768,3 +768,50 @@ def test_block_one_kernel_form_batch32_sampled(tvg):
         a1 = dict(a, x=a["x"][img:img + 1])
         want = oracle_block(a1, b, "bf16", 1, True, True)
         assert rel_err(y[img:img + 1], want) <= TOL["bf16"], img
+
+
+@pytest.mark.parametrize("network", ["resnet18", "mobilenet"])
+def test_body_in_a_planned_arena_matches_separate_tensors(tvg, network):
+    """Every intermediate tensor of the chain placed by tvg_plan_arena in one arena (tensors that
+    are never alive together share memory): the final output is bit-identical to the run with
+    one allocation per tensor, twice in a row (the second run starts from a dirty arena)."""
+    import torch
+    steps = ti.resnet18_body(2) if network == "resnet18" else ti.mobilenet_body(2)
+    config = 5 if network == "resnet18" else 6
+    weights = body_weights(steps, config=config)
+    images = ti.body_images(2, ti.layer_seed(config, 902))
+    want = run_body_gpu(tvg, steps, images, weights)[steps[-1].dst]
+
+    lives = ti.tensor_lives(steps)
+    ids = [t for t in lives if t != 0]
+    offsets, arena_bytes = tvg.tvg_plan_arena([lives[t] for t in ids])
+    assert arena_bytes < sum(lives[t][0] for t in ids)
+    arena = torch.full((arena_bytes,), 0x7F, dtype=torch.uint8, device="cuda")   # NaN patterns
+    off = dict(zip(ids, offsets))
+    dev_w = {k: {n: to_dev(v, "bf16" if n == "w" else "f32") for n, v in p.items()}
+             for k, p in weights.items()}
+    x0 = to_dev(images, "bf16")
+    for rep in range(2):
+        tensors = {0: x0}
+        for st in steps:
+            src = tensors[st.src]
+            if st.op == "maxpool":
+                n, c, h, w = src.shape
+                shape = (n, c, (h - 1) // 2 + 1, (w - 1) // 2 + 1)
+            else:
+                shape = st.shape.y_shape()
+            y = arena[off[st.dst]:off[st.dst] + lives[st.dst][0]].view(torch.bfloat16).view(shape)
+            p = dev_w.get(st.layer_index)
+            if st.op == "conv":
+                res = None if st.residual is None else tensors[st.residual]
+                tvg.conv2d_fused(src, p["w"], p["scale"], p["shift"], None, res, stride=st.shape.stride,
+                                 pad=st.shape.pad, relu=st.relu, out=y)
+            elif st.op == "dwconv":
+                tvg.dwconv2d_fused(src, p["w"], p["scale"], p["shift"], None, None,
+                                   stride=st.shape.stride, pad=1, relu=st.relu, out=y)
+            else:
+                tvg.maxpool2d_3x3s2(src, out=y)
+            tensors[st.dst] = y
+        torch.cuda.synchronize()
+        got = tensors[steps[-1].dst]
+        assert torch.equal(got.view(torch.int16), want.view(torch.int16)), rep

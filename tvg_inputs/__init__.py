@@ -262,6 +262,29 @@ def mobilenet_body(n: int = 32) -> List[Step]:
     return steps
 
 
+def tensor_lives(steps: List[Step], elem_bytes: int = 2):
+    """(bytes, first_step, last_step) per tensor id of a launch list, for a static memory plan.
+
+    A tensor must stay intact from the launch that writes it to the last launch that reads it
+    (as src or residual); tensor 0, the images, is there from launch 0, and the last tensor
+    stays until the end because the caller reads it.
+    """
+    shapes = {0: steps[0].shape.x_shape()}
+    first, last = {0: 0}, {0: 0}
+    for i, st in enumerate(steps):
+        if st.op == "maxpool":
+            n, c, h, w = shapes[st.src]
+            shapes[st.dst] = (n, c, (h - 1) // 2 + 1, (w - 1) // 2 + 1)
+        else:
+            shapes[st.dst] = st.shape.y_shape()
+        first[st.dst] = last[st.dst] = i
+        for t in (st.src, st.residual):
+            if t is not None:
+                last[t] = i
+    last[steps[-1].dst] = len(steps) - 1
+    return {t: (int(np.prod(shapes[t])) * elem_bytes, first[t], last[t]) for t in sorted(shapes)}
+
+
 def body_images(n: int, seed: int) -> np.ndarray:
     """U[-1, 1] images [n][3][224][224], bf16-representable float32."""
     rng = np.random.default_rng(seed)
