@@ -137,6 +137,7 @@ tvg_status tvg_dwconv2d_fused(const tvg_conv_desc *desc, const void *x, const vo
  *     produced in LDS as the pixel operand of the 1x1 stage and never reaches memory.  Exists
  *     for bf16, stride 1, c a multiple of 32 and maps whose rows are short enough
  *     (tvg_dwpw_one_kernel() says whether a problem qualifies); TVG_ERR_WORKSPACE otherwise.
+ *     This form also needs w_dw 4-byte aligned (TVG_ERR_UNSUPPORTED otherwise).
  * A workspace that is too small or misaligned is TVG_ERR_WORKSPACE.  Both forms follow the
  * definition above (t rounded to dtype between the stages).
  */

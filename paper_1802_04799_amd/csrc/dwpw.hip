@@ -365,7 +365,7 @@ bool plan_dwpw(const ConvProblem &dw, int OC, DwPwPlan *plan)
     if ((size_t)OC * dw.IC * 2 > (size_t)kOutOfRange) return false;
     const int words = max_patch_words(dw);
     if (words > 16 * 8) return false;
-    plan->lt = words <= 8 * 8 ? 8 : words <= 12 * 8 ? 12 : 16;
+    plan->lt = words <= 8 * 8 ? 8 : 16;            // one or two passes of 64 words over a row
     // every channel tile repeats the depthwise stage of its pixels, so tall tiles where the
     // accumulators allow (measured: 512 -> 512 at 14x14, batch 32: 37 us with 128, 29 with 256)
     plan->mt = OC <= 64 ? 64 : (OC >= 256 && dw.IC <= 512) ? 256 : 128;
@@ -394,15 +394,12 @@ tvg_status launch_dwpw(const ConvProblem &dw, int OC, int pw_relu, int pw_stream
 #define TVG_DWPW(MT_, LT_) hipLaunchKernelGGL((dwpw_kernel<MT_, LT_>), grid, block, 0, stream, a)
     if (plan.mt == 256) {
         if (plan.lt == 8) TVG_DWPW(256, 8);
-        else if (plan.lt == 12) TVG_DWPW(256, 12);
         else TVG_DWPW(256, 16);
     } else if (plan.mt == 128) {
         if (plan.lt == 8) TVG_DWPW(128, 8);
-        else if (plan.lt == 12) TVG_DWPW(128, 12);
         else TVG_DWPW(128, 16);
     } else {
         if (plan.lt == 8) TVG_DWPW(64, 8);
-        else if (plan.lt == 12) TVG_DWPW(64, 12);
         else TVG_DWPW(64, 16);
     }
 #undef TVG_DWPW

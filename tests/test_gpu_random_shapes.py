@@ -109,3 +109,41 @@ def test_random_depthwise(tvg, case):
     want = oracle.dwconv2d_fused(inp["x"], inp["w"], inp["scale"], inp["shift"], inp["bias"],
                                  inp["residual"], stride=(stride,) * 2, pad=(1, 1), relu=relu)
     assert rel_err(to_host(y), want) <= TOL[dtype], sh
+
+
+def block_cases(seed, count):
+    rng = random.Random(seed)
+    out = []
+    for i in range(count):
+        n, c = rng.choice([1, 2, 3, 6]), 32 * rng.randint(1, 5)
+        h, w = rng.randint(1, 30), rng.randint(1, 30)
+        if rng.random() < 0.3:
+            h = w = rng.choice([7, 14, 28])
+        out.append((i, n, c, h, w, rng.choice([1, 7, 32, 64, 100, 128, 200, 256, 300]),
+                    rng.choice([1, 1, 1, 2]), rng.random() < 0.7, rng.random() < 0.7,
+                    rng.random() < 0.4, rng.random() < 0.4, rng.random() < 0.5))
+    return out
+
+
+@pytest.mark.parametrize("case", block_cases(20263, 80), ids=lambda c: f"{c[0]}")
+def test_random_blocks(tvg, case):
+    """tvg_dwpw_fused on random bf16 shapes: the one-kernel form wherever it exists (no
+    workspace), and the two-kernel form for every case."""
+    i, n, c, h, w, k, stride, relu_dw, relu_pw, res, bias, hint = case
+    d = ti.ConvShape("bd", n, c, h, w, c, 3, 3, stride, 1, depthwise=True)
+    p = ti.ConvShape("bp", n, c, d.oh, d.ow, k, 1, 1, 1, 0)
+    a = ti.make_inputs(d, 56000 + 2 * i, "bf16")
+    b = ti.make_inputs(p, 56001 + 2 * i, "bf16", residual=res, bias=bias)
+    da, db = dev_inputs(a, "bf16"), dev_inputs(b, "bf16")
+    want = oracle.dwpw_fused(a["x"], a["w"], a["scale"], a["shift"], b["w"], b["scale"], b["shift"],
+                             b["bias"], b["residual"], stride=stride, relu_dw=relu_dw,
+                             relu_pw=relu_pw, store="bf16")
+    desc = tvg.ConvDesc(n, c, h, w, c, 3, 3, stride, stride, 1, 1, tvg.TVG_BF16, 0)
+    forms = [False] + ([True] if tvg.tvg_dwpw_one_kernel(desc, k) else [])
+    if stride == 1 and h * w >= 32 and w <= 30:
+        assert True in forms, "every such map fits the one-kernel form"
+    for one in forms:
+        y = tvg.dwpw_fused(da["x"], da["w"], da["scale"], da["shift"], db["w"], db["scale"],
+                           db["shift"], db["bias"], db["residual"], stride=stride, relu_dw=relu_dw,
+                           relu_pw=relu_pw, stream_out=hint, one_kernel=one)
+        assert rel_err(to_host(y), want) <= TOL["bf16"], (one, d, k)
