@@ -48,6 +48,8 @@ def parse():
     ap.add_argument("--depthwise-probe", action="store_true",
                     help="only launch the depthwise layers D1..D9 at batch 64 --steps times each "
                          "(for profiler runs)")
+    ap.add_argument("--no-arena", action="store_true",
+                    help="network bodies with one allocation per tensor instead of the planned arena")
     ap.add_argument("--body-probe", default="", choices=["", "resnet18", "mobilenet"],
                     help="only run this network body at batch 32 --warmup + --steps times "
                          "(for profiler runs)")
@@ -139,7 +141,8 @@ def main():
         return
     if args.body_probe:
         r = bench_body(tvg, ti, torch, np, dev, to_dev, time_loop, args.body_probe,
-                       iters=args.steps, warmup=args.warmup, graph=False)
+                       iters=args.steps, warmup=args.warmup, graph=False,
+                       use_arena=not args.no_arena)
         print(json.dumps({"body_probe": args.body_probe, **r}))
         return
     shapes = ti.resnet18_convs(64)
@@ -311,9 +314,19 @@ def main():
                               "tflops": round(fl / tot / 1e12, 2),
                               "frac_fp32_peak": round(fl / tot / 1e12 / PEAK_FP32_TFLOPS, 4)}
         # ResNet-18 body, batch 32, bf16 (configs[4]): 20 convs + 1 max-pool, 21 launches
-        out["resnet18_body"] = bench_body(tvg, ti, torch, np, dev, to_dev, time_loop)
+        out["resnet18_body"] = bench_body(tvg, ti, torch, np, dev, to_dev, time_loop, iters=50,
+                                          warmup=20, use_arena=not args.no_arena)
+        if not args.no_arena:      # the same chain with one allocation per tensor, for comparison
+            out["resnet18_body"]["ms_separate_tensors"] = bench_body(
+                tvg, ti, torch, np, dev, to_dev, time_loop, iters=50, warmup=20, graph=False,
+                use_arena=False)["ms"]
         # MobileNet body, batch 32, bf16: stem + 13 x (depthwise 3x3, 1x1), 27 launches
-        out["mobilenet_body"] = bench_body(tvg, ti, torch, np, dev, to_dev, time_loop, "mobilenet")
+        out["mobilenet_body"] = bench_body(tvg, ti, torch, np, dev, to_dev, time_loop, "mobilenet",
+                                           iters=50, warmup=20, use_arena=not args.no_arena)
+        if not args.no_arena:
+            out["mobilenet_body"]["ms_separate_tensors"] = bench_body(
+                tvg, ti, torch, np, dev, to_dev, time_loop, "mobilenet", iters=50, warmup=20,
+                graph=False, use_arena=False)["ms"]
 
     if not args.skip_cpu:
         out["cpu_baseline"] = cpu_baseline(ti, np)
@@ -344,7 +357,7 @@ def measured_traffic(kernel):
 
 
 def bench_body(tvg, ti, torch, np, dev, to_dev, time_loop, network="resnet18", iters=10, warmup=3,
-               graph=True):
+               graph=True, use_arena=True):
     n = 32
     config = 5 if network == "resnet18" else 6
     steps = ti.resnet18_body(n) if network == "resnet18" else ti.mobilenet_body(n)
@@ -364,6 +377,8 @@ def bench_body(tvg, ti, torch, np, dev, to_dev, time_loop, network="resnet18", i
 
     def planned(t, shape):
         nbytes = lives[t][0]
+        if not use_arena:
+            return torch.empty(shape, dtype=torch.bfloat16, device=dev)
         return arena[offset_of[t]:offset_of[t] + nbytes].view(torch.bfloat16).view(shape)
 
     tensors = {0: images}
@@ -411,7 +426,7 @@ def bench_body(tvg, ti, torch, np, dev, to_dev, time_loop, network="resnet18", i
             forward()
         graph_ms = time_loop(g.replay, 10)
     flops = sum(s.shape.flops for s in steps if s.op != "maxpool")
-    return {"batch": n, "launches": len(calls), "arena_mb": round(arena_bytes / 1e6, 1),
+    return {"batch": n, "launches": len(calls), "arena": use_arena, "arena_mb": round(arena_bytes / 1e6, 1),
             "unplanned_mb": round(sum(lives[t][0] for t in ids) / 1e6, 1), "ms": round(ms, 4), "graph_replay_ms": round(graph_ms, 4) if graph else None,
             "tflops": round(flops / (ms * 1e-3) / 1e12, 1),
             "images_per_s": round(n / (ms * 1e-3), 1),
