@@ -315,14 +315,16 @@ def main():
                               "frac_fp32_peak": round(fl / tot / 1e12 / PEAK_FP32_TFLOPS, 4)}
         # ResNet-18 body, batch 32, bf16 (configs[4]): 20 convs + 1 max-pool, 21 launches
         out["resnet18_body"] = bench_body(tvg, ti, torch, np, dev, to_dev, time_loop, iters=50,
-                                          warmup=20, use_arena=not args.no_arena)
+                                          warmup=20, use_arena=not args.no_arena,
+                                          tune_tiles=args.tune)
         if not args.no_arena:      # the same chain with one allocation per tensor, for comparison
             out["resnet18_body"]["ms_separate_tensors"] = bench_body(
                 tvg, ti, torch, np, dev, to_dev, time_loop, iters=50, warmup=20, graph=False,
                 use_arena=False)["ms"]
         # MobileNet body, batch 32, bf16: stem + 13 x (depthwise 3x3, 1x1), 27 launches
         out["mobilenet_body"] = bench_body(tvg, ti, torch, np, dev, to_dev, time_loop, "mobilenet",
-                                           iters=50, warmup=20, use_arena=not args.no_arena)
+                                           iters=50, warmup=20, use_arena=not args.no_arena,
+                                           tune_tiles=args.tune)
         if not args.no_arena:
             out["mobilenet_body"]["ms_separate_tensors"] = bench_body(
                 tvg, ti, torch, np, dev, to_dev, time_loop, "mobilenet", iters=50, warmup=20,
@@ -357,7 +359,7 @@ def measured_traffic(kernel):
 
 
 def bench_body(tvg, ti, torch, np, dev, to_dev, time_loop, network="resnet18", iters=10, warmup=3,
-               graph=True, use_arena=True):
+               graph=True, use_arena=True, tune_tiles=False):
     n = 32
     config = 5 if network == "resnet18" else 6
     steps = ti.resnet18_body(n) if network == "resnet18" else ti.mobilenet_body(n)
@@ -410,6 +412,15 @@ def bench_body(tvg, ti, torch, np, dev, to_dev, time_loop, network="resnet18", i
             calls.append((tvg.tvg_maxpool2d_3x3s2, (nn, c, h, w, tvg.TVG_BF16, src, y, None)))
         tensors[st.dst] = y
 
+    tuned = None
+    if tune_tiles:      # the measured tile search over this body's dense layers (batch-32 shapes)
+        from paper_1802_04799_amd import tune
+        tuned = 0
+        for fn, a in calls:
+            if fn is tvg.tvg_conv2d_fused:
+                desc, x_, w_, sc_, sf_, _, res_, y_ = a[:8]
+                tuned += tune.tune_conv2d(desc, x_, w_, sc_, sf_, y_, residual=res_)["chosen"] is not None
+
     def forward():
         for fn, a in calls:
             st = fn(*a)
@@ -426,7 +437,7 @@ def bench_body(tvg, ti, torch, np, dev, to_dev, time_loop, network="resnet18", i
             forward()
         graph_ms = time_loop(g.replay, 10)
     flops = sum(s.shape.flops for s in steps if s.op != "maxpool")
-    return {"batch": n, "launches": len(calls), "arena": use_arena, "arena_mb": round(arena_bytes / 1e6, 1),
+    return {"batch": n, "launches": len(calls), "tiles_changed_by_tuning": tuned, "arena": use_arena, "arena_mb": round(arena_bytes / 1e6, 1),
             "unplanned_mb": round(sum(lives[t][0] for t in ids) / 1e6, 1), "ms": round(ms, 4), "graph_replay_ms": round(graph_ms, 4) if graph else None,
             "tflops": round(flops / (ms * 1e-3) / 1e12, 1),
             "images_per_s": round(n / (ms * 1e-3), 1),
