@@ -30,7 +30,14 @@
  *     codes; nothing is thrown, logged or aborted.  On error nothing is launched.
  *   - Results are deterministic run to run (no floating-point atomics).
  *   - Limits: every tensor must hold fewer than 2^31 elements; R, S <= 16;
- *     strides 1..8; pad < kernel extent.
+ *     strides 1..8; pad < kernel extent.  Depthwise calls also need
+ *     (3*stride + 3) * (w + 2) <= 16372, i.e. w <= 2726 at stride 1 and w <= 1817 at stride 2
+ *     (one band of input rows is staged in 64 KB of LDS); the size query and the operator
+ *     both answer TVG_ERR_UNSUPPORTED beyond that.
+ *   - Which kernel runs a problem, its launch shape and its workspace size depend on the
+ *     descriptor (flags aside) and on what tvg_conv2d_set_tile has fixed, on nothing else: no
+ *     environment variable is read.  Plans are remembered per problem; a size query and the
+ *     call that follows it therefore agree unless tvg_conv2d_set_tile runs in between.
  */
 #ifndef TVG_H
 #define TVG_H
@@ -61,7 +68,9 @@ typedef enum { TVG_F32 = 0, TVG_BF16 = 1 } tvg_dtype;
  *                 then run faster, since y neither displaces the operands in L2 nor waits
  *                 there to be written back.  Wrong between the layers of a network whose
  *                 activations fit the memory-side cache: the next layer would fetch from
- *                 HBM what it could have found there.  Off by default. */
+ *                 HBM what it could have found there.  Off by default.  Kernels without wide
+ *                 stores (the generic kernel that takes fp32 and odd shapes, the element-wise
+ *                 tail of unaligned maps) ignore it. */
 enum { TVG_RELU = 1u, TVG_STREAM_OUT = 2u };
 
 typedef struct {

@@ -17,6 +17,18 @@ using tvg::ConvProblem;
 
 const int64_t kMaxElems = (int64_t)1 << 31;
 
+// Product of positive extents, saturating at kMaxElems (every factor is below 2^31, so a
+// partial product below 2^31 times the next factor stays inside 64 bits).
+int64_t count_elems(std::initializer_list<int64_t> extents)
+{
+    int64_t n = 1;
+    for (int64_t e : extents) {
+        n *= e;
+        if (n >= kMaxElems) return kMaxElems;
+    }
+    return n;
+}
+
 tvg_status make_problem(const tvg_conv_desc *d, bool depthwise, ConvProblem *out)
 {
     if (!d) return TVG_ERR_NULL;
@@ -24,27 +36,37 @@ tvg_status make_problem(const tvg_conv_desc *d, bool depthwise, ConvProblem *out
         return TVG_ERR_BAD_SHAPE;
     if (d->stride_h < 1 || d->stride_w < 1 || d->stride_h > 8 || d->stride_w > 8)
         return TVG_ERR_BAD_SHAPE;
+    // The filter extent is bounded before anything is computed from the padding: with r, s <= 16
+    // and pad < r every sum below stays far inside the int range (h, w < 2^31 - 32 is implied by
+    // the element-count limit, checked in 64 bits).
+    if (d->r > 16 || d->s > 16) return TVG_ERR_UNSUPPORTED;
     if (d->pad_h < 0 || d->pad_w < 0 || d->pad_h >= d->r || d->pad_w >= d->s)
         return TVG_ERR_BAD_SHAPE;
-    if (d->h + 2 * d->pad_h < d->r || d->w + 2 * d->pad_w < d->s) return TVG_ERR_BAD_SHAPE;
+    if ((int64_t)d->h + 2 * d->pad_h < d->r || (int64_t)d->w + 2 * d->pad_w < d->s)
+        return TVG_ERR_BAD_SHAPE;
     if (d->dtype != TVG_F32 && d->dtype != TVG_BF16) return TVG_ERR_UNSUPPORTED;
     if (d->flags & ~(uint32_t)(TVG_RELU | TVG_STREAM_OUT)) return TVG_ERR_UNSUPPORTED;
-    if (d->r > 16 || d->s > 16) return TVG_ERR_UNSUPPORTED;
+    if (count_elems({d->n, d->c, d->h, d->w}) >= kMaxElems) return TVG_ERR_UNSUPPORTED;
     if (depthwise) {
         if (d->k != d->c) return TVG_ERR_BAD_SHAPE;
         if (d->r != 3 || d->s != 3) return TVG_ERR_UNSUPPORTED;
         if (d->stride_h != d->stride_w || d->stride_h > 2) return TVG_ERR_UNSUPPORTED;
         if (d->pad_h != 1 || d->pad_w != 1) return TVG_ERR_UNSUPPORTED;
+        // one band of input rows (4 output rows) of one plane must fit 64 KB of LDS as fp32
+        if ((int64_t)(3 * d->stride_h + 3) * ((int64_t)d->w + 2) > tvg::kDwBandFloats)
+            return TVG_ERR_UNSUPPORTED;
     }
     ConvProblem p;
     p.N = d->n; p.IC = d->c; p.H = d->h; p.W = d->w; p.OC = d->k; p.R = d->r; p.S = d->s;
     p.sh = d->stride_h; p.sw = d->stride_w; p.ph = d->pad_h; p.pw = d->pad_w;
-    p.OH = (d->h + 2 * d->pad_h - d->r) / d->stride_h + 1;
-    p.OW = (d->w + 2 * d->pad_w - d->s) / d->stride_w + 1;
-    const int64_t nx = (int64_t)d->n * d->c * d->h * d->w;
-    const int64_t ny = (int64_t)d->n * d->k * p.OH * p.OW;
-    const int64_t nw = (int64_t)d->k * (depthwise ? 1 : d->c) * d->r * d->s;
-    if (nx >= kMaxElems || ny >= kMaxElems || nw >= kMaxElems) return TVG_ERR_UNSUPPORTED;
+    const int64_t oh = ((int64_t)d->h + 2 * d->pad_h - d->r) / d->stride_h + 1;
+    const int64_t ow = ((int64_t)d->w + 2 * d->pad_w - d->s) / d->stride_w + 1;
+    if (oh >= kMaxElems || ow >= kMaxElems) return TVG_ERR_UNSUPPORTED;
+    p.OH = (int)oh;
+    p.OW = (int)ow;
+    const int64_t ny = count_elems({d->n, d->k, p.OH, p.OW});
+    const int64_t nw = count_elems({d->k, depthwise ? 1 : d->c, d->r, d->s});
+    if (ny >= kMaxElems || nw >= kMaxElems) return TVG_ERR_UNSUPPORTED;
     p.K = (depthwise ? 1 : d->c) * d->r * d->s;
     p.npix = d->n * p.OH * p.OW;
     p.dtype = d->dtype;
@@ -70,6 +92,52 @@ void tile_key(const ConvProblem &p, int (&key)[12])
     memcpy(key, k, sizeof(k));
 }
 
+// Everything planning derives from a problem, computed once per distinct problem: which
+// kernel takes it and with what launch shape.  The descriptor's flags do not enter (no plan
+// depends on them).  A short list under a mutex, scanned linearly; tvg_conv2d_set_tile empties
+// it.  The launch-bound batch-1 layers spend 1-5 us per call in planning otherwise.
+struct Dispatch {
+    int key[12];
+    bool patch_shape, stem_shape, pw_shape;
+    tvg::Patch3x3Plan patch;
+    tvg::StemPlan stem;
+    tvg::Pw1x1Plan pw;
+    tvg::ConvPlan generic;          // the generic kernel's plan, reduction split allowed
+    tvg::ConvPlan generic_single;   // the same in a single pass (no workspace)
+};
+std::mutex g_dispatch_mutex;
+std::vector<Dispatch> g_dispatch;
+size_t g_dispatch_next = 0;
+constexpr size_t kMaxDispatchEntries = 256;
+
+Dispatch dispatch_for(const ConvProblem &p)
+{
+    int key[12];
+    tile_key(p, key);
+    {
+        std::lock_guard<std::mutex> lock(g_dispatch_mutex);
+        for (const Dispatch &d : g_dispatch)
+            if (memcmp(d.key, key, sizeof(key)) == 0) return d;
+    }
+    Dispatch d{};
+    memcpy(d.key, key, sizeof(key));
+    d.patch_shape = tvg::plan_conv3x3_patch(p, &d.patch);
+    d.stem_shape = !d.patch_shape && tvg::plan_conv7x7s2_stem(p, &d.stem);
+    d.pw_shape = !d.patch_shape && !d.stem_shape && tvg::plan_conv1x1(p, &d.pw);
+    d.generic = tvg::plan_conv(p, true);
+    d.generic_single = tvg::plan_conv(p, false);
+    std::lock_guard<std::mutex> lock(g_dispatch_mutex);
+    if (g_dispatch.size() < kMaxDispatchEntries) g_dispatch.push_back(d);
+    else g_dispatch[g_dispatch_next++ % kMaxDispatchEntries] = d;     // replace the oldest slot
+    return d;
+}
+
+void forget_dispatch()
+{
+    std::lock_guard<std::mutex> lock(g_dispatch_mutex);
+    g_dispatch.clear();
+}
+
 }  // namespace
 
 namespace tvg {
@@ -87,8 +155,6 @@ bool forced_tile(const ConvProblem &p, int *mt, int *nt)
                 return true;
             }
     }
-    if (const char *e = getenv("TVG_FORCE_TILE"))
-        if (sscanf(e, "%d,%d", mt, nt) == 2 && *mt > 0 && *nt > 0) return true;
     return false;
 }
 
@@ -107,6 +173,7 @@ tvg_status tvg_conv2d_set_tile(const tvg_conv_desc *desc, int32_t mt, int32_t nt
     if (!clear && !known) return TVG_ERR_UNSUPPORTED;
     int key[12];
     tile_key(p, key);
+    forget_dispatch();                     // plans made under the old table are stale
     std::lock_guard<std::mutex> lock(g_tile_mutex);
     for (size_t i = 0; i < g_tiles.size(); ++i)
         if (memcmp(g_tiles[i].key, key, sizeof(key)) == 0) {
@@ -130,26 +197,23 @@ tvg_status tvg_conv2d_get_plan(const tvg_conv_desc *desc, int32_t *kernel, int32
     ConvProblem p;
     tvg_status st = make_problem(desc, false, &p);
     if (st != TVG_OK) return st;
-    tvg::Patch3x3Plan patch;
-    tvg::StemPlan stem;
-    tvg::Pw1x1Plan pw;
-    if (tvg::plan_conv3x3_patch(p, &patch)) {
-        *kernel = patch.dbuf ? TVG_KERNEL_3X3_PIPELINED : TVG_KERNEL_3X3;
-        *mt = patch.mt;
-        *nt = patch.nt;
-    } else if (tvg::plan_conv7x7s2_stem(p, &stem)) {
+    const Dispatch d = dispatch_for(p);
+    if (d.patch_shape) {
+        *kernel = d.patch.dbuf ? TVG_KERNEL_3X3_PIPELINED : TVG_KERNEL_3X3;
+        *mt = d.patch.mt;
+        *nt = d.patch.nt;
+    } else if (d.stem_shape) {
         *kernel = TVG_KERNEL_STEM;
         *mt = 64;
         *nt = 256;
-    } else if (tvg::plan_conv1x1(p, &pw)) {
+    } else if (d.pw_shape) {
         *kernel = TVG_KERNEL_1X1;
-        *mt = pw.mt;
-        *nt = pw.nt;
+        *mt = d.pw.mt;
+        *nt = d.pw.nt;
     } else {
-        const tvg::ConvPlan plan = tvg::plan_conv(p);
         *kernel = TVG_KERNEL_GENERIC;
-        *mt = plan.mt;
-        *nt = plan.nt;
+        *mt = d.generic.mt;
+        *nt = d.generic.nt;
     }
     return TVG_OK;
 }
@@ -161,12 +225,9 @@ tvg_status tvg_conv2d_workspace_size(const tvg_conv_desc *desc, size_t *bytes)
     ConvProblem p;
     tvg_status st = make_problem(desc, false, &p);
     if (st != TVG_OK) return st;
-    tvg::Patch3x3Plan patch;
-    tvg::StemPlan stem;
-    tvg::Pw1x1Plan pw;
-    const bool single_pass = tvg::plan_conv3x3_patch(p, &patch) ||
-                             tvg::plan_conv7x7s2_stem(p, &stem) || tvg::plan_conv1x1(p, &pw);
-    *bytes = single_pass ? 0 : tvg::plan_conv(p).workspace_bytes;
+    const Dispatch d = dispatch_for(p);
+    const bool single_pass = d.patch_shape || d.stem_shape || d.pw_shape;
+    *bytes = single_pass ? 0 : d.generic.workspace_bytes;
     return TVG_OK;
 }
 
@@ -191,20 +252,16 @@ tvg_status tvg_conv2d_fused(const tvg_conv_desc *desc, const void *x, const void
     if (!x || !w || !scale || !shift || !y) return TVG_ERR_NULL;
     tvg::ConvPointers ptr{x, w, scale, shift, bias, residual, y, static_cast<float *>(workspace)};
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    tvg::Patch3x3Plan patch;
-    const bool patch_shape = tvg::plan_conv3x3_patch(p, &patch);
-    if (patch_shape && tvg::conv3x3_patch_pointers_ok(ptr))
-        return tvg::launch_conv3x3_patch(p, patch, ptr, stream);
-    tvg::StemPlan stem;
-    const bool stem_shape = tvg::plan_conv7x7s2_stem(p, &stem);
-    if (stem_shape && tvg::conv7x7s2_stem_pointers_ok(ptr))
-        return tvg::launch_conv7x7s2_stem(p, stem, ptr, stream);
-    tvg::Pw1x1Plan pw;
-    const bool pw_shape = tvg::plan_conv1x1(p, &pw);
-    if (pw_shape && tvg::conv1x1_pointers_ok(ptr)) return tvg::launch_conv1x1(p, pw, ptr, stream);
+    const Dispatch d = dispatch_for(p);
+    if (d.patch_shape && tvg::conv3x3_patch_pointers_ok(ptr))
+        return tvg::launch_conv3x3_patch(p, d.patch, ptr, stream);
+    if (d.stem_shape && tvg::conv7x7s2_stem_pointers_ok(ptr))
+        return tvg::launch_conv7x7s2_stem(p, d.stem, ptr, stream);
+    if (d.pw_shape && tvg::conv1x1_pointers_ok(ptr)) return tvg::launch_conv1x1(p, d.pw, ptr, stream);
     // A problem shaped for a specialised kernel reported a zero workspace; if its pointers
     // rule that kernel out, the generic kernel runs it in a single pass over the reduction.
-    const tvg::ConvPlan plan = tvg::plan_conv(p, !(patch_shape || stem_shape || pw_shape));
+    const tvg::ConvPlan &plan = (d.patch_shape || d.stem_shape || d.pw_shape) ? d.generic_single
+                                                                               : d.generic;
     if (plan.workspace_bytes > 0 && (!workspace || workspace_bytes < plan.workspace_bytes ||
                                      reinterpret_cast<uintptr_t>(workspace) % 256 != 0))
         return TVG_ERR_WORKSPACE;
@@ -359,7 +416,7 @@ tvg_status tvg_maxpool2d_3x3s2(int32_t n, int32_t c, int32_t h, int32_t w, int32
 {
     if (n < 1 || c < 1 || h < 1 || w < 1) return TVG_ERR_BAD_SHAPE;
     if (dtype != TVG_F32 && dtype != TVG_BF16) return TVG_ERR_UNSUPPORTED;
-    if ((int64_t)n * c * h * w >= kMaxElems) return TVG_ERR_UNSUPPORTED;
+    if (count_elems({n, c, h, w}) >= kMaxElems) return TVG_ERR_UNSUPPORTED;
     if (!x || !y) return TVG_ERR_NULL;
     return tvg::launch_maxpool3x3s2(n, c, h, w, dtype, x, y, static_cast<hipStream_t>(hip_stream));
 }

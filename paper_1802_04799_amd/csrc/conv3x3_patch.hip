@@ -416,8 +416,7 @@ bool plan_conv3x3_patch(const ConvProblem &p, Patch3x3Plan *plan)
     if (p.npix >= (1 << 22) || (long)p.N * (p.H + 2) >= (1 << 22)) return false;   // fast_div range
     int force_mt = 0, force_nt = 0;
     if (!forced_tile(p, &force_mt, &force_nt)) force_mt = force_nt = 0;
-    bool use_dbuf = true;
-    if (const char *e = getenv("TVG_DBUF")) use_dbuf = atoi(e) != 0;
+    const bool use_dbuf = true;
     // Tile choice (measured on MI355X at batch 64): take the largest tile that still gives at
     // least 1.5 workgroups per CU, wider in pixels on a tie; if none does, the tile shape with
     // the most workgroups.  A 128-channel tile with more than 4 patch tasks per thread (wide

@@ -569,7 +569,8 @@ tvg_status launch_dwconv3x3(const ConvProblem &p, const ConvPointers &ptr, hipSt
     const size_t lds_cap = 48 * 1024;
     while (pt > 1 && (size_t)pt * (ir * wp + kPrm) * sizeof(float) > lds_cap) --pt;
     const size_t lds_bytes = (size_t)pt * (ir * wp + kPrm) * sizeof(float);
-    if (lds_bytes > 64 * 1024) return TVG_ERR_UNSUPPORTED;   // a single row band does not fit
+    // (the host interface has already rejected rows whose narrowest band does not fit)
+    if (lds_bytes > 64 * 1024) return TVG_ERR_UNSUPPORTED;
 
     a.PT = pt; a.RT = rt;
     a.row_tiles = (p.OH + rt - 1) / rt;

@@ -339,6 +339,8 @@ __device__ __forceinline__ void store_fast_tiles(const float16v (&acc)[MI][NJ], 
                                                  const float *ss, int row_base)
 {
     constexpr int T = MI * NJ;
+    // a short last batch would let the pair store below pick up a stale staged tile
+    static_assert(T % BT == 0, "the batch size must divide the number of tiles of a wave");
     const int lrow = lane & 31, lhalf = lane >> 5;
     const float floor_v = (t.relu & 1) ? 0.0f : -INFINITY;
     const bf16_t *res = static_cast<const bf16_t *>(t.residual);

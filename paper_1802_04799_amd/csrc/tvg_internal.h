@@ -14,6 +14,11 @@ namespace tvg {
 // the descriptor.
 constexpr int kComputeUnits = 256;
 
+// Depthwise: floats of LDS that the narrowest row band of the general kernel may take (four
+// output rows = 3*stride + 3 input rows of W + 2 columns, plus 12 per-plane parameters, in
+// 64 KB).  The host rejects wider rows for every depthwise call, whichever kernel would run.
+constexpr int kDwBandFloats = 64 * 1024 / 4 - 12;
+
 struct ConvProblem {
     int N, IC, H, W, OC, R, S, sh, sw, ph, pw, OH, OW;
     int K;          // IC * R * S, the reduction length of the implicit GEMM
@@ -40,9 +45,8 @@ struct ConvPlan {
     size_t workspace_bytes;
 };
 
-// Tile shape fixed for this exact problem by tvg_conv2d_set_tile, or by the TVG_FORCE_TILE
-// environment variable ("mt,nt", for sweeps); false when neither names one.  The planners of
-// the 3x3 and 1x1 kernels then consider that tile shape only.
+// Tile shape fixed for this exact problem by tvg_conv2d_set_tile; false when there is none.
+// The planners of the 3x3 and 1x1 kernels then consider that tile shape only.
 bool forced_tile(const ConvProblem &p, int *mt, int *nt);
 
 // `allow_split` = false plans a single pass over the reduction (no workspace).

@@ -1,7 +1,18 @@
 """Shared helpers of the GPU parity tests (no arithmetic of the method itself)."""
+import contextlib
+
 import numpy as np
 
-TOL = {"f32": 1e-4, "bf16": 2e-2}
+TOL = {"f32": 1e-4, "bf16": 2e-2}          # the stated tolerances (max relative error)
+# What the arithmetic of ONE fused operator allows: bf16 outputs are the fp32 result rounded
+# once to 8 significant bits (at most 2^-8 = 3.9e-3 relative) plus fp32 accumulation (about
+# 1e-6 of rho); a dropped tap or channel of a K = 4608 reduction (1.5 % rms) lands far outside.
+# fp32 outputs carry the accumulation error only.
+TIGHT = {"f32": 5e-5, "bf16": 5e-3}
+# The MobileNet block rounds twice (the depthwise result to the storage type, then y): where the
+# fp32 and fp64 depthwise sums straddle a rounding boundary the intermediate differs by one ulp,
+# which with a single channel reaches y undiminished: 2 * 2^-8 = 7.8e-3 at worst.
+BLOCK_TIGHT = 1e-2
 
 
 def rel_err(got, want):
@@ -19,6 +30,32 @@ def rel_err(got, want):
     if rho == 0.0:
         return float(np.max(np.abs(g - r), initial=0.0)) / 1e-6 * 1e-4
     return float(np.max(np.abs(g - r) / np.maximum(np.abs(r), rho), initial=0.0))
+
+
+def check(got, want, dtype, what=None, tight=None):
+    """The parity gate of a single fused operator: the stated tolerance, and next to it the
+    tight bound the arithmetic gives (TIGHT, or `tight` for an operator with its own bound)."""
+    err = rel_err(got, want)
+    assert err <= TOL[dtype], (what, err)
+    assert err <= (TIGHT[dtype] if tight is None else tight), (what, err, "tight bound")
+    return err
+
+
+@contextlib.contextmanager
+def fixed_tile(tvg, sh, dtype, tile):
+    """Plan the dense problem `sh` with the workgroup tile "mt,nt" (through tvg_conv2d_set_tile)
+    for the duration of the block; "" leaves the library's own choice."""
+    if not tile:
+        yield
+        return
+    mt, nt = (int(v) for v in tile.split(","))
+    desc = tvg.ConvDesc(sh.n, sh.ic, sh.h, sh.w, sh.oc, sh.r, sh.s, sh.stride, sh.stride, sh.pad,
+                        sh.pad, tvg.TVG_BF16 if dtype == "bf16" else tvg.TVG_F32, 0)
+    assert tvg.tvg_conv2d_set_tile(desc, mt, nt) == 0
+    try:
+        yield
+    finally:
+        assert tvg.tvg_conv2d_set_tile(desc, 0, 0) == 0
 
 
 def to_dev(a, dtype):

@@ -83,6 +83,58 @@ def test_depthwise_rejects_what_it_does_not_build(kw, status):
         tvg.tvg_dwconv2d_workspace_size(d)
 
 
+@pytest.mark.parametrize("kw", [
+    dict(r=2**31 - 1, pad_h=2**31 - 2), dict(s=2**31 - 1, pad_w=2**31 - 2, w=3),
+    dict(h=2**31 - 1, w=2**31 - 1, pad_h=2, pad_w=2), dict(r=2**30, s=2**30, pad_h=2**30 - 1, pad_w=5),
+    dict(n=2**31 - 1, c=2**31 - 1, k=2**31 - 1),
+    dict(n=1, c=1, k=1, h=2**31 - 1, w=1, pad_h=2, pad_w=0, s=1),      # output rows: 2^31 + 1
+])
+def test_extreme_descriptors_are_rejected_without_arithmetic_on_them(kw):
+    """Extents near INT_MAX: the filter-size limit is checked before any sum involving the
+    padding, and element counts are formed in 64 bits, so every such descriptor is an error
+    code (bad shape or unsupported), from the query and from the operator alike."""
+    d = desc(**kw)
+    with pytest.raises(tvg.TvgError) as e:
+        tvg.tvg_conv2d_workspace_size(d)
+    assert e.value.status in (2, 3)
+    assert tvg.tvg_conv2d_fused(d, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, None, 0, 0) == e.value.status
+    assert tvg.tvg_maxpool2d_3x3s2(2**31 - 1, 2**31 - 1, 2**31 - 1, 2**31 - 1, 0, FAKE, FAKE, 0) == 3
+
+
+@pytest.mark.parametrize("w,stride,dtype,ok", [
+    (2726, 1, 0, True), (2727, 1, 0, False), (1817, 2, 1, True), (1818, 2, 1, False),
+    (5001, 1, 0, False), (3001, 1, 1, False), (3001, 2, 1, False)])
+def test_depthwise_row_width_limit_is_the_same_for_query_and_operator(w, stride, dtype, ok):
+    """The documented limit (3*stride + 3) * (w + 2) <= 16372: the size query and the operator
+    give the same answer on both sides of it (the operator is called with no pointers, so a
+    descriptor that passes fails on the NULL check instead of launching)."""
+    d = desc(n=1, c=8, k=8, h=8, w=w, stride_h=stride, stride_w=stride, dtype=dtype)
+    op = tvg.tvg_dwconv2d_fused(d, None, None, None, None, None, None, None, None, 0, 0)
+    if ok:
+        assert tvg.tvg_dwconv2d_workspace_size(d) == 0 and op == 1
+    else:
+        with pytest.raises(tvg.TvgError) as e:
+            tvg.tvg_dwconv2d_workspace_size(d)
+        assert e.value.status == 3 and op == 3
+
+
+def test_plans_do_not_depend_on_the_environment(monkeypatch):
+    """No environment variable reaches planning: the variables an earlier build read change
+    nothing, and the query agrees with itself across calls (plans are remembered)."""
+    c6 = desc(n=64, c=128, h=28, w=28, k=128, dtype=tvg.TVG_BF16)
+    c12 = desc(n=1, c=512, h=7, w=7, k=512)
+    before = (tvg.tvg_conv2d_get_plan(c6), tvg.tvg_conv2d_workspace_size(c12))
+    monkeypatch.setenv("TVG_FORCE_TILE", "64,64")
+    monkeypatch.setenv("TVG_DBUF", "0")
+    assert tvg.tvg_conv2d_set_tile(c6, 64, 128) == 0        # empties the remembered plans
+    assert tvg.tvg_conv2d_set_tile(c6, 0, 0) == 0
+    assert (tvg.tvg_conv2d_get_plan(c6), tvg.tvg_conv2d_workspace_size(c12)) == before
+    # more distinct problems than the plan memory holds: old entries are replaced, answers stay
+    for n in range(1, 300):
+        tvg.tvg_conv2d_get_plan(desc(n=n, c=16, h=9, w=9, k=16, dtype=tvg.TVG_BF16))
+    assert (tvg.tvg_conv2d_get_plan(c6), tvg.tvg_conv2d_workspace_size(c12)) == before
+
+
 def test_workspace_query_and_too_small_workspace():
     # a large-batch problem fills the chip without splitting the reduction
     big = desc(n=64, c=64, h=56, w=56, k=64, dtype=tvg.TVG_BF16)

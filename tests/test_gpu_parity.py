@@ -6,17 +6,18 @@ import pytest
 
 import oracle
 import tvg_inputs as ti
-from _util import TOL, dev_inputs, rel_err, to_dev, to_host
+from _util import BLOCK_TIGHT, TOL, check, dev_inputs, fixed_tile, rel_err, to_dev, to_host
 
 pytestmark = pytest.mark.gpu
 
 
-def run_dense(tvg, sh, inp, dtype, relu=True, stream_out=False):
+def run_dense(tvg, sh, inp, dtype, relu=True, stream_out=False, tile=""):
     import torch
     d = dev_inputs(inp, dtype)
-    y = tvg.conv2d_fused(d["x"], d["w"], d["scale"], d["shift"], d["bias"], d["residual"],
-                         stride=sh.stride, pad=sh.pad, relu=relu, stream_out=stream_out)
-    torch.cuda.synchronize()
+    with fixed_tile(tvg, sh, dtype, tile):
+        y = tvg.conv2d_fused(d["x"], d["w"], d["scale"], d["shift"], d["bias"], d["residual"],
+                             stride=sh.stride, pad=sh.pad, relu=relu, stream_out=stream_out)
+        torch.cuda.synchronize()
     return y
 
 
@@ -47,7 +48,7 @@ def test_config3_depthwise_fp32_batch1(tvg, i):
     want = oracle.dwconv2d_fused(inp["x"], inp["w"], inp["scale"], inp["shift"],
                                  stride=(sh.stride,) * 2, pad=(1, 1), relu=True)
     assert tuple(y.shape) == sh.y_shape()
-    assert rel_err(to_host(y), want) <= TOL["f32"]
+    check(to_host(y), want, "f32")
 
 
 @pytest.mark.parametrize("i", range(9))
@@ -66,7 +67,7 @@ def test_depthwise_bf16_table2_shapes_batch2(tvg, i):
     assert torch.equal(y.view(torch.int16), hinted.view(torch.int16))
     want = oracle.dwconv2d_fused(inp["x"], inp["w"], inp["scale"], inp["shift"], None,
                                  inp["residual"], stride=(sh.stride,) * 2, pad=(1, 1), relu=True)
-    assert rel_err(to_host(y), want) <= TOL["bf16"]
+    check(to_host(y), want, "bf16")
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -88,26 +89,26 @@ def test_depthwise_ragged_shapes_full_tail(tvg, dtype, n, c, h, w, stride):
     torch.cuda.synchronize()
     want = oracle.dwconv2d_fused(inp["x"], inp["w"], inp["scale"], inp["shift"], inp["bias"],
                                  inp["residual"], stride=(stride,) * 2, pad=(1, 1), relu=True)
-    assert rel_err(to_host(y), want) <= TOL[dtype]
+    check(to_host(y), want, dtype)
 
 
-def test_depthwise_batch64_sampled(tvg):
-    """D3 at batch 64 (HBM-sized traffic): the launch configuration of the supplementary
-    bandwidth measurement, checked on one full image and on the last planes."""
+@pytest.mark.parametrize("i", [0, 2, 3, 8])
+def test_depthwise_batch64_full(tvg, i):
+    """D1, D3, D4, D9 at batch 64 (HBM-sized traffic): the launch configuration of the
+    supplementary bandwidth measurement, every output against the oracle."""
     import torch
-    sh = ti.mobilenet_depthwise(64)[2]
-    inp = ti.make_inputs(sh, ti.layer_seed(3, 102), "f32")
+    sh = ti.mobilenet_depthwise(64)[i]
+    inp = ti.make_inputs(sh, ti.layer_seed(3, 100 + i), "f32")
     d = dev_inputs(inp, "f32")
-    y = tvg.dwconv2d_fused(d["x"], d["w"], d["scale"], d["shift"], stride=1, pad=1, relu=True,
-                           stream_out=True)       # as bench.py launches it
-    plain = tvg.dwconv2d_fused(d["x"], d["w"], d["scale"], d["shift"], stride=1, pad=1, relu=True)
+    y = tvg.dwconv2d_fused(d["x"], d["w"], d["scale"], d["shift"], stride=sh.stride, pad=1,
+                           relu=True, stream_out=True)       # as bench.py launches it
+    plain = tvg.dwconv2d_fused(d["x"], d["w"], d["scale"], d["shift"], stride=sh.stride, pad=1,
+                               relu=True)
     torch.cuda.synchronize()
     assert torch.equal(y, plain)                  # the store hint changes no value
-    got = to_host(y)
-    for n in (0, 63):
-        want = oracle.dwconv2d_fused(inp["x"][n:n + 1], inp["w"], inp["scale"], inp["shift"],
-                                     stride=(1, 1), pad=(1, 1), relu=True)
-        assert rel_err(got[n:n + 1], want) <= TOL["f32"]
+    want = oracle.dwconv2d_fused(inp["x"], inp["w"], inp["scale"], inp["shift"],
+                                 stride=(sh.stride,) * 2, pad=(1, 1), relu=True)
+    check(to_host(y), want, "f32", sh.name)
 
 
 # ------------------------------------------------------------------------------------------
@@ -118,7 +119,7 @@ def test_config1_single_conv_fp32(tvg):
     sh = ti.config1_shape()
     inp = ti.make_inputs(sh, ti.layer_seed(1, 0), "f32")
     y = run_dense(tvg, sh, inp, "f32")
-    assert rel_err(to_host(y), oracle_dense(sh, inp)) <= TOL["f32"]
+    check(to_host(y), oracle_dense(sh, inp), "f32")
 
 
 @pytest.mark.parametrize("i", range(12))
@@ -127,7 +128,7 @@ def test_config2_resnet18_shapes_fp32_batch1(tvg, i):
     inp = ti.make_inputs(sh, ti.layer_seed(2, i), "f32")
     y = run_dense(tvg, sh, inp, "f32")
     assert tuple(y.shape) == sh.y_shape()
-    assert rel_err(to_host(y), oracle_dense(sh, inp)) <= TOL["f32"]
+    check(to_host(y), oracle_dense(sh, inp), "f32")
 
 
 RAGGED = [
@@ -152,7 +153,7 @@ def test_dense_ragged_shapes_full_tail(tvg, dtype, cfg):
     sh = ti.ConvShape("x", n, ic, h, w, oc, r, s, stride, pad)
     inp = ti.make_inputs(sh, 777 + sum(cfg), dtype, residual=True, bias=True)
     y = run_dense(tvg, sh, inp, dtype)
-    assert rel_err(to_host(y), oracle_dense(sh, inp)) <= TOL[dtype]
+    check(to_host(y), oracle_dense(sh, inp), dtype)
 
 
 PATCH_RAGGED = [
@@ -173,18 +174,14 @@ PATCH_RAGGED = [
 
 @pytest.mark.parametrize("tile", ["", "64,256", "128,128", "128,64", "64,128", "64,64"])
 @pytest.mark.parametrize("cfg", PATCH_RAGGED)
-def test_bf16_3x3_patch_kernel_ragged_shapes_all_tiles(tvg, monkeypatch, cfg, tile):
-    """The LDS-patch 3x3 kernel under every workgroup tile shape it is built with (the
-    library reads TVG_FORCE_TILE on every call; an unusable choice falls back by itself)."""
+def test_bf16_3x3_patch_kernel_ragged_shapes_all_tiles(tvg, cfg, tile):
+    """The LDS-patch 3x3 kernel under every workgroup tile shape it is built with (fixed through
+    tvg_conv2d_set_tile; a shape the kernel cannot use falls back to the generic kernel)."""
     n, ic, h, w, oc, stride = cfg
-    if tile:
-        monkeypatch.setenv("TVG_FORCE_TILE", tile)
-    else:
-        monkeypatch.delenv("TVG_FORCE_TILE", raising=False)
     sh = ti.ConvShape("p", n, ic, h, w, oc, 3, 3, stride, 1)
     inp = ti.make_inputs(sh, 4000 + sum(cfg), "bf16", residual=True, bias=True)
-    y = run_dense(tvg, sh, inp, "bf16")
-    assert rel_err(to_host(y), oracle_dense(sh, inp)) <= TOL["bf16"]
+    y = run_dense(tvg, sh, inp, "bf16", tile=tile)
+    check(to_host(y), oracle_dense(sh, inp), "bf16")
 
 
 DBUF_SHAPES = [
@@ -202,17 +199,13 @@ DBUF_SHAPES = [
 
 @pytest.mark.parametrize("tile", ["", "64,256", "64,128", "64,64"])
 @pytest.mark.parametrize("cfg", DBUF_SHAPES)
-def test_bf16_3x3_pipelined_kernel_shapes_all_tiles(tvg, monkeypatch, cfg, tile):
+def test_bf16_3x3_pipelined_kernel_shapes_all_tiles(tvg, cfg, tile):
     """The two-stage 3x3 kernel under every pixel-tile width, with bias, residual and ReLU."""
     n, ic, h, w, oc = cfg
-    if tile:
-        monkeypatch.setenv("TVG_FORCE_TILE", tile)
-    else:
-        monkeypatch.delenv("TVG_FORCE_TILE", raising=False)
     sh = ti.ConvShape("db3", n, ic, h, w, oc, 3, 3, 1, 1)
     inp = ti.make_inputs(sh, 12000 + sum(cfg), "bf16", residual=True, bias=True)
-    y = run_dense(tvg, sh, inp, "bf16")
-    assert rel_err(to_host(y), oracle_dense(sh, inp)) <= TOL["bf16"]
+    y = run_dense(tvg, sh, inp, "bf16", tile=tile)
+    check(to_host(y), oracle_dense(sh, inp), "bf16")
 
 
 DBUF_STRIDE2 = [
@@ -225,16 +218,12 @@ DBUF_STRIDE2 = [
 
 @pytest.mark.parametrize("tile", ["", "64,256", "64,128"])
 @pytest.mark.parametrize("cfg", DBUF_STRIDE2)
-def test_bf16_3x3_pipelined_kernel_stride2(tvg, monkeypatch, cfg, tile):
+def test_bf16_3x3_pipelined_kernel_stride2(tvg, cfg, tile):
     n, ic, h, w, oc = cfg
-    if tile:
-        monkeypatch.setenv("TVG_FORCE_TILE", tile)
-    else:
-        monkeypatch.delenv("TVG_FORCE_TILE", raising=False)
     sh = ti.ConvShape("db2", n, ic, h, w, oc, 3, 3, 2, 1)
     inp = ti.make_inputs(sh, 7100 + sum(cfg), "bf16", residual=True, bias=True)
-    y = run_dense(tvg, sh, inp, "bf16")
-    assert rel_err(to_host(y), oracle_dense(sh, inp)) <= TOL["bf16"]
+    y = run_dense(tvg, sh, inp, "bf16", tile=tile)
+    check(to_host(y), oracle_dense(sh, inp), "bf16")
 
 
 @pytest.mark.parametrize("cfg", [(2, 128, 8, 8, 64), (3, 128, 7, 7, 130), (1, 256, 33, 40, 72)])
@@ -246,7 +235,7 @@ def test_bf16_3x3_pipelined_kernel_plain_tail_and_determinism(tvg, cfg):
     y1 = to_host(run_dense(tvg, sh, inp, "bf16", relu=False))
     y2 = to_host(run_dense(tvg, sh, inp, "bf16", relu=False))
     assert np.array_equal(y1, y2)
-    assert rel_err(y1, oracle_dense(sh, inp, relu=False)) <= TOL["bf16"]
+    check(y1, oracle_dense(sh, inp, relu=False), "bf16")
     assert (y1 < 0).any()
 
 
@@ -260,18 +249,14 @@ PATCH_WIDE = [
 
 @pytest.mark.parametrize("tile", ["", "64,256", "128,128", "64,128", "64,64"])
 @pytest.mark.parametrize("cfg", PATCH_WIDE)
-def test_bf16_3x3_patch_kernel_many_chunks(tvg, monkeypatch, cfg, tile):
+def test_bf16_3x3_patch_kernel_many_chunks(tvg, cfg, tile):
     """The 3x3 patch kernel with several channel chunks per tile: tiles that straddle images,
     ragged channel and pixel tails, every tile shape."""
     n, ic, h, w, oc, stride = cfg
-    if tile:
-        monkeypatch.setenv("TVG_FORCE_TILE", tile)
-    else:
-        monkeypatch.delenv("TVG_FORCE_TILE", raising=False)
     sh = ti.ConvShape("pw3", n, ic, h, w, oc, 3, 3, stride, 1)
     inp = ti.make_inputs(sh, 9000 + sum(cfg), "bf16", residual=True, bias=True)
-    y = run_dense(tvg, sh, inp, "bf16")
-    assert rel_err(to_host(y), oracle_dense(sh, inp)) <= TOL["bf16"]
+    y = run_dense(tvg, sh, inp, "bf16", tile=tile)
+    check(to_host(y), oracle_dense(sh, inp), "bf16")
 
 
 STEM_SHAPES = [
@@ -290,7 +275,7 @@ def test_bf16_7x7_stem_kernel_shapes(tvg, cfg):
     sh = ti.ConvShape("stem", n, ic, h, w, oc, 7, 7, 2, 3)
     inp = ti.make_inputs(sh, 6000 + sum(cfg), "bf16", residual=True, bias=True)
     y = run_dense(tvg, sh, inp, "bf16")
-    assert rel_err(to_host(y), oracle_dense(sh, inp)) <= TOL["bf16"]
+    check(to_host(y), oracle_dense(sh, inp), "bf16")
 
 
 PW_SHAPES = [
@@ -313,7 +298,7 @@ def test_bf16_1x1_kernel_shapes(tvg, cfg):
     sh = ti.ConvShape("pw", n, ic, h, w, oc, 1, 1, stride, 0)
     inp = ti.make_inputs(sh, 8000 + sum(cfg), "bf16", residual=True, bias=True)
     y = run_dense(tvg, sh, inp, "bf16")
-    assert rel_err(to_host(y), oracle_dense(sh, inp)) <= TOL["bf16"]
+    check(to_host(y), oracle_dense(sh, inp), "bf16")
 
 
 def test_bf16_1x1_kernel_unaligned_input(tvg):
@@ -330,7 +315,7 @@ def test_bf16_1x1_kernel_unaligned_input(tvg):
         x.copy_(d["x"])
         y = tvg.conv2d_fused(x, d["w"], d["scale"], d["shift"], stride=1, pad=0, relu=True)
         torch.cuda.synchronize()
-        assert rel_err(to_host(y), want) <= TOL["bf16"], off
+        check(to_host(y), want, "bf16", off)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -347,7 +332,7 @@ def test_rectangular_filter_and_strides(tvg, dtype):
                          to_dev(shift, "f32"), stride=(2, 3), pad=(2, 1), relu=False)
     torch.cuda.synchronize()
     want = oracle.conv2d_fused(x, w, scale, shift, stride=(2, 3), pad=(2, 1), relu=False)
-    assert rel_err(to_host(y), want) <= TOL[dtype]
+    check(to_host(y), want, dtype)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -394,28 +379,24 @@ def test_output_may_alias_residual(tvg):
     tvg.conv2d_fused(d["x"], d["w"], d["scale"], d["shift"], None, y, stride=1, pad=1, relu=True,
                      out=y)
     torch.cuda.synchronize()
-    assert rel_err(to_host(y), oracle_dense(sh, inp)) <= TOL["bf16"]
+    check(to_host(y), oracle_dense(sh, inp), "bf16")
 
 
 @pytest.mark.parametrize("i", range(12))
-def test_config4_resnet18_shapes_bf16_batch64_sampled(tvg, i):
-    """Full-size launch (the configuration bench.py times); the oracle evaluates a sample of
-    outputs one by one: the first and last tile plus random positions."""
+def test_config4_resnet18_shapes_bf16_batch64_full(tvg, i):
+    """Full-size launch (the configuration bench.py times, store hint included): EVERY output
+    of the layer against the oracle - all 64 images, every tile, image wrap and ragged tail -
+    at the stated 2e-2 and at the tight one-rounding bound."""
     import torch
     sh = ti.resnet18_convs(64)[i]
     inp = ti.make_inputs(sh, ti.layer_seed(4, i), "bf16")
     y = run_dense(tvg, sh, inp, "bf16", stream_out=True)      # as bench.py launches it
     # the store hint changes no value: bit-identical to the plain launch
     assert torch.equal(y.view(torch.int16), run_dense(tvg, sh, inp, "bf16").view(torch.int16))
-    got = to_host(y).reshape(-1)
-    rng = np.random.default_rng(i)
-    total = got.size
-    idx = np.unique(np.concatenate([np.arange(256), total - 1 - np.arange(256),
-                                    rng.integers(0, total, 6000)]))
-    want = oracle_dense(sh, inp, idx=idx)
-    assert rel_err(got[idx], want) <= TOL["bf16"]
-    # property that holds at any size: ReLU output is non-negative and finite everywhere
-    assert np.all(got >= 0) and np.all(np.isfinite(got))
+    got = to_host(y)
+    assert tuple(got.shape) == sh.y_shape()
+    check(got, oracle_dense(sh, inp), "bf16", sh.name)
+    assert np.all(got >= 0)
 
 
 # ------------------------------------------------------------------------------------------
@@ -465,19 +446,35 @@ def body_weights(steps, config=5):
             for s in steps if s.op in ("conv", "dwconv")}
 
 
+def chain_drift(g, r):
+    """(rms, worst element, signed mean in standard errors) of a chain's last tensor against the
+    oracle chain's, all relative to the oracle tensor's RMS."""
+    rho = float(np.sqrt(np.mean(r * r)))
+    d = (g - r) / rho
+    rms = float(np.sqrt(np.mean(d * d)))
+    # Errors of neighbouring outputs share their inputs' flipped roundings, so the elements are
+    # not independent samples: a 3x3 window over the last layers' channels correlates roughly
+    # the 9 positions of a window; the standard error is taken over n / 9 samples.
+    stderr = float(np.std(d)) / np.sqrt(d.size / 9.0)
+    return rms, rel_err(g, r), float(np.mean(d)) / stderr
+
+
 def test_config5_resnet18_body_bf16_small_batch_full(tvg):
     """The whole 21-launch chain at batch 2.
 
-    Gate (per operator, the stated 2e-2): every layer's complete output against the oracle
-    fed with the GPU's own input of that layer.
-    End to end: two correct bf16-storing chains that sum in different orders do not stay
-    within one rounding of each other.  A last-bit difference in one stored activation is a
-    full bf16 ulp (2^-8 relative), and after a few layers most elements differ by an ulp; from
-    then on each layer adds independent rounding noise of about 0.16 % rms, which the next
-    convolution passes on undiminished relative to its output rms.  Over 20 layers the two
-    chains differ by about sqrt(2*20)*0.16 % = 1 % rms and a few sigma at the worst element,
-    so the end-to-end check bounds the rms-normalised error by 2e-2 and the worst element
-    by 8e-2 against the oracle chain (fp64 per layer, outputs rounded to bf16 as stored).
+    THE GATE (per operator, the stated 2e-2, plus the tight one-rounding bound): every layer's
+    complete output against the oracle fed with the GPU's own input of that layer.
+
+    SUPPLEMENTARY, not the stated tolerance: the last tensor against the oracle chain (fp64
+    per layer, outputs rounded to bf16 as stored).  Two correct bf16-storing chains that sum in
+    different orders do not stay within one rounding of each other: a last-bit difference in
+    one stored activation is a full bf16 ulp (2^-8 relative), after a few layers most elements
+    differ by an ulp, and from then on each layer adds independent rounding noise of about
+    0.16 % rms which the next convolution passes on undiminished relative to its output rms.
+    Over 20 layers the two chains differ by about sqrt(2*20)*0.16 % = 1 % rms and a few sigma
+    at the worst element, so this check bounds the rms-normalised error by 2e-2 and the worst
+    element by 8e-2 (this test's own bounds, derived above), and requires the drift to be
+    noise, not bias: the signed mean of (gpu - oracle)/rho within four standard errors of zero.
     """
     from oracle.resnet_body import run_steps
     steps = ti.resnet18_body(2)
@@ -494,15 +491,15 @@ def test_config5_resnet18_body_bf16_small_batch_full(tvg):
         want = oracle.conv2d_fused(host[st.src], p["w"], p["scale"], p["shift"], None, res,
                                    stride=(st.shape.stride,) * 2, pad=(st.shape.pad,) * 2,
                                    relu=st.relu)
-        err = rel_err(host[st.dst], want)
-        assert err <= TOL["bf16"], (st.name, err)
+        check(host[st.dst], want, "bf16", st.name)
     want = run_steps(steps, images, weights)
     final = steps[-1].dst
     assert tuple(got[final].shape) == (2, 512, 7, 7)
-    g, r = to_host(got[final]), want[final].astype(np.float64)
-    rho = float(np.sqrt(np.mean(r * r)))
-    assert float(np.sqrt(np.mean((g - r) ** 2))) / rho <= 2e-2
-    assert rel_err(g, r) <= 8e-2
+    rms, worst, bias_se = chain_drift(to_host(got[final]), want[final].astype(np.float64))
+    print(f"chain drift: rms {rms:.3e} worst {worst:.3e} signed mean {bias_se:+.2f} standard errors")
+    assert rms <= 2e-2
+    assert worst <= 8e-2
+    assert abs(bias_se) <= 4.0
 
 
 def test_tuner_fixes_a_tile_and_results_stay_right(tvg, tmp_path):
@@ -526,7 +523,7 @@ def test_tuner_fixes_a_tile_and_results_stay_right(tvg, tmp_path):
             assert list(plan[1:]) == rep["chosen"]
         out = tvg.conv2d_fused(d["x"], d["w"], d["scale"], d["shift"], stride=1, pad=1, relu=True)
         torch.cuda.synchronize()
-        assert rel_err(to_host(out), oracle_dense(sh, inp)) <= TOL["bf16"]
+        check(to_host(out), oracle_dense(sh, inp), "bf16")
         path = str(tmp_path / "tiles.json")
         tune.save(path)
         tvg.tvg_conv2d_set_tile(desc, 0, 0)
@@ -592,32 +589,25 @@ def test_config5_resnet18_body_hip_graph_replays_match_eager(tvg):
 
 
 def test_config5_resnet18_body_bf16_batch32_teacher_forced(tvg):
-    """Batch 32 (the benchmark's launch configuration).  Every layer is checked on sampled
-    outputs against the oracle fed with the GPU's own input of that layer, which localises
-    a fault to a layer and needs no full-size oracle chain."""
+    """Batch 32 (the benchmark's launch configuration).  Every layer's COMPLETE output against
+    the oracle fed with the GPU's own input of that layer, at the stated 2e-2 and at the tight
+    one-rounding bound; the max-pool bit for bit."""
     steps = ti.resnet18_body(32)
     weights = body_weights(steps)
     images = ti.body_images(32, ti.layer_seed(5, 901))
     got = run_body_gpu(tvg, steps, images, weights)
     host = {k: v.float().cpu().numpy() for k, v in got.items()}
-    rng = np.random.default_rng(5)
+    del got
     for st in steps:
-        out = host[st.dst].astype(np.float64).reshape(-1)
         if st.op == "maxpool":
-            assert np.array_equal(host[st.dst][:1].astype(np.float64),
-                                  oracle.maxpool2d(host[st.src][:1]))
+            assert np.array_equal(host[st.dst].astype(np.float64), oracle.maxpool2d(host[st.src]))
             continue
-        idx = np.unique(np.concatenate([np.arange(128), out.size - 1 - np.arange(128),
-                                        rng.integers(0, out.size, 1500)]))
         p = weights[st.layer_index]
         res = None if st.residual is None else host[st.residual]
-        want = oracle.conv2d_fused_at(host[st.src], p["w"], p["scale"], p["shift"], None, res,
-                                      idx=idx, stride=(st.shape.stride,) * 2,
-                                      pad=(st.shape.pad,) * 2, relu=st.relu)
-        # the sample's own RMS can be small; floor with the whole GPU tensor's RMS
-        rho = float(np.sqrt(np.mean(out * out)))
-        err = np.max(np.abs(out[idx] - want) / np.maximum(np.abs(want), rho))
-        assert err <= TOL["bf16"], (st.name, err)
+        want = oracle.conv2d_fused(host[st.src], p["w"], p["scale"], p["shift"], None, res,
+                                   stride=(st.shape.stride,) * 2, pad=(st.shape.pad,) * 2,
+                                   relu=st.relu)
+        check(host[st.dst], want, "bf16", st.name)
 
 
 def oracle_layer(st, host, weights, idx=None):
@@ -634,10 +624,11 @@ def oracle_layer(st, host, weights, idx=None):
 
 def test_mobilenet_body_bf16_small_batch_full(tvg):
     """The 27-launch MobileNet body (stem, 13 x depthwise 3x3 + 1x1) at batch 2: every layer's
-    complete output against the oracle fed with the GPU's own input of that layer (2e-2), and
-    the last tensor against the oracle chain (fp64 per layer, stored as bf16) with the
-    end-to-end bounds of the ResNet-18 chain test scaled to 27 layers: rms 2.5e-2, worst
-    element 1e-1."""
+    complete output against the oracle fed with the GPU's own input of that layer (the gate:
+    2e-2 and the tight bound), and, as a supplementary check, the last tensor against the
+    oracle chain (fp64 per layer, stored as bf16) with the end-to-end bounds of the ResNet-18
+    chain test scaled to 27 layers: rms 2.5e-2, worst element 1e-1, signed mean within four
+    standard errors."""
     from oracle.resnet_body import run_steps
     steps = ti.mobilenet_body(2)
     weights = body_weights(steps, config=6)
@@ -645,42 +636,27 @@ def test_mobilenet_body_bf16_small_batch_full(tvg):
     got = run_body_gpu(tvg, steps, images, weights)
     host = {k: v.float().cpu().numpy() for k, v in got.items()}
     for st in steps:
-        err = rel_err(host[st.dst], oracle_layer(st, host, weights))
-        assert err <= TOL["bf16"], (st.name, err)
+        check(host[st.dst], oracle_layer(st, host, weights), "bf16", st.name)
     want = run_steps(steps, images, weights)
     final = steps[-1].dst
     assert tuple(got[final].shape) == (2, 1024, 7, 7)
-    g, r = to_host(got[final]), want[final].astype(np.float64)
-    rho = float(np.sqrt(np.mean(r * r)))
-    assert float(np.sqrt(np.mean((g - r) ** 2))) / rho <= 2.5e-2
-    assert rel_err(g, r) <= 1e-1
+    rms, worst, bias_se = chain_drift(to_host(got[final]), want[final].astype(np.float64))
+    print(f"chain drift: rms {rms:.3e} worst {worst:.3e} signed mean {bias_se:+.2f} standard errors")
+    assert rms <= 2.5e-2 and worst <= 1e-1           # supplementary, see the ResNet-18 chain test
+    assert abs(bias_se) <= 4.0
 
 
 def test_mobilenet_body_bf16_batch32_teacher_forced(tvg):
-    """Batch 32, the launch configuration the benchmark times: sampled outputs of every layer
-    against the oracle fed with the GPU's own input of that layer (depthwise layers: the
-    first and the last image in full)."""
+    """Batch 32, the launch configuration the benchmark times: every layer's complete output
+    against the oracle fed with the GPU's own input of that layer."""
     steps = ti.mobilenet_body(32)
     weights = body_weights(steps, config=6)
     images = ti.body_images(32, ti.layer_seed(6, 901))
     got = run_body_gpu(tvg, steps, images, weights)
-    rng = np.random.default_rng(6)
+    host = {k: v.float().cpu().numpy() for k, v in got.items()}
+    del got
     for st in steps:
-        src = got[st.src].float().cpu().numpy()
-        out = got[st.dst].float().cpu().numpy().astype(np.float64)
-        rho = float(np.sqrt(np.mean(out * out)))
-        if st.op == "dwconv":
-            for img in (0, 31):
-                want = oracle_layer(st, {st.src: src[img:img + 1]}, weights)
-                err = np.max(np.abs(out[img:img + 1] - want) / np.maximum(np.abs(want), rho))
-                assert err <= TOL["bf16"], (st.name, img, err)
-            continue
-        flat = out.reshape(-1)
-        idx = np.unique(np.concatenate([np.arange(128), flat.size - 1 - np.arange(128),
-                                        rng.integers(0, flat.size, 1500)]))
-        want = oracle_layer(st, {st.src: src}, weights, idx)
-        err = np.max(np.abs(flat[idx] - want) / np.maximum(np.abs(want), rho))
-        assert err <= TOL["bf16"], (st.name, err)
+        check(host[st.dst], oracle_layer(st, host, weights), "bf16", st.name)
 
 
 # ------------------------------------------------------------------------------------------
@@ -734,13 +710,13 @@ def test_block_one_kernel_form(tvg, cfg):
     want = oracle_block(a, b, "bf16", 1, relu_dw, relu_pw)
     y = run_block(tvg, d, a, b, "bf16", 1, relu_dw, relu_pw, one_kernel=True)
     assert tuple(y.shape) == p.y_shape()
-    assert rel_err(to_host(y), want) <= TOL["bf16"]
+    check(to_host(y), want, "bf16", tight=BLOCK_TIGHT)
     hinted = run_block(tvg, d, a, b, "bf16", 1, relu_dw, relu_pw, hint=True, one_kernel=True)
     import torch
     assert torch.equal(y.view(torch.int16), hinted.view(torch.int16))
     # the same problem as two kernels (a workspace is passed)
     two = run_block(tvg, d, a, b, "bf16", 1, relu_dw, relu_pw)
-    assert rel_err(to_host(two), want) <= TOL["bf16"]
+    check(to_host(two), want, "bf16", tight=BLOCK_TIGHT)
 
 
 @pytest.mark.parametrize("cfg", [(2, 64, 14, 14, 64, 2, "bf16"), (1, 32, 112, 112, 64, 1, "bf16"),
@@ -755,19 +731,17 @@ def test_block_two_kernel_form(tvg, cfg):
     assert not tvg.tvg_dwpw_one_kernel(desc, k)
     y = run_block(tvg, d, a, b, dtype, stride, True, True)
     assert tuple(y.shape) == p.y_shape()
-    assert rel_err(to_host(y), oracle_block(a, b, dtype, stride, True, True)) <= TOL[dtype]
+    check(to_host(y), oracle_block(a, b, dtype, stride, True, True), dtype,
+          tight=BLOCK_TIGHT if dtype == "bf16" else None)
 
 
-def test_block_one_kernel_form_batch32_sampled(tvg):
+def test_block_one_kernel_form_batch32_full(tvg):
     """MobileNet's 14x14 block (512 -> 512) at batch 32, the benchmark's launch configuration:
-    one image in full and the last image's last channels against the oracle."""
+    every output against the block oracle."""
     n, c, hw, k = 32, 512, 14, 512
     d, p, a, b = block_inputs(n, c, hw, hw, k, 1, "bf16", 7401, False, False)
     y = to_host(run_block(tvg, d, a, b, "bf16", 1, True, True, one_kernel=True))
-    for img in (0, 17, 31):
-        a1 = dict(a, x=a["x"][img:img + 1])
-        want = oracle_block(a1, b, "bf16", 1, True, True)
-        assert rel_err(y[img:img + 1], want) <= TOL["bf16"], img
+    check(y, oracle_block(a, b, "bf16", 1, True, True), "bf16", tight=BLOCK_TIGHT)
 
 
 @pytest.mark.parametrize("network", ["resnet18", "mobilenet"])

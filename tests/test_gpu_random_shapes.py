@@ -12,7 +12,7 @@ import pytest
 
 import oracle
 import tvg_inputs as ti
-from _util import TOL, dev_inputs, rel_err, to_host
+from _util import BLOCK_TIGHT, check, dev_inputs, fixed_tile, to_host
 
 pytestmark = pytest.mark.gpu
 
@@ -58,19 +58,18 @@ def cases(seed, count):
 
 
 @pytest.mark.parametrize("case", cases(20260, 300), ids=lambda c: f"{c[0]}")
-def test_random_dense_bf16(tvg, monkeypatch, case):
+def test_random_dense_bf16(tvg, case):
+    import torch
     i, sh, tile, relu, hint, res, bias = case
-    if tile:
-        monkeypatch.setenv("TVG_FORCE_TILE", tile)
-    else:
-        monkeypatch.delenv("TVG_FORCE_TILE", raising=False)
     inp = ti.make_inputs(sh, 52000 + i, "bf16", residual=res, bias=bias)
     d = dev_inputs(inp, "bf16")
-    y = tvg.conv2d_fused(d["x"], d["w"], d["scale"], d["shift"], d["bias"], d["residual"],
-                         stride=sh.stride, pad=sh.pad, relu=relu, stream_out=hint)
+    with fixed_tile(tvg, sh, "bf16", tile):
+        y = tvg.conv2d_fused(d["x"], d["w"], d["scale"], d["shift"], d["bias"], d["residual"],
+                             stride=sh.stride, pad=sh.pad, relu=relu, stream_out=hint)
+        torch.cuda.synchronize()
     want = oracle.conv2d_fused(inp["x"], inp["w"], inp["scale"], inp["shift"], inp["bias"],
                                inp["residual"], stride=(sh.stride,) * 2, pad=(sh.pad,) * 2, relu=relu)
-    assert rel_err(to_host(y), want) <= TOL["bf16"], sh
+    check(to_host(y), want, "bf16", sh)
 
 
 @pytest.mark.parametrize("case", cases(20261, 100), ids=lambda c: f"{c[0]}")
@@ -82,7 +81,7 @@ def test_random_dense_fp32(tvg, case):
                          stride=sh.stride, pad=sh.pad, relu=relu, stream_out=hint)
     want = oracle.conv2d_fused(inp["x"], inp["w"], inp["scale"], inp["shift"], inp["bias"],
                                inp["residual"], stride=(sh.stride,) * 2, pad=(sh.pad,) * 2, relu=relu)
-    assert rel_err(to_host(y), want) <= TOL["f32"], sh
+    check(to_host(y), want, "f32", sh)
 
 
 def dw_cases(seed, count):
@@ -108,7 +107,7 @@ def test_random_depthwise(tvg, case):
                            stride=stride, pad=1, relu=relu, stream_out=hint)
     want = oracle.dwconv2d_fused(inp["x"], inp["w"], inp["scale"], inp["shift"], inp["bias"],
                                  inp["residual"], stride=(stride,) * 2, pad=(1, 1), relu=relu)
-    assert rel_err(to_host(y), want) <= TOL[dtype], sh
+    check(to_host(y), want, dtype, sh)
 
 
 def block_cases(seed, count):
@@ -146,4 +145,4 @@ def test_random_blocks(tvg, case):
         y = tvg.dwpw_fused(da["x"], da["w"], da["scale"], da["shift"], db["w"], db["scale"],
                            db["shift"], db["bias"], db["residual"], stride=stride, relu_dw=relu_dw,
                            relu_pw=relu_pw, stream_out=hint, one_kernel=one)
-        assert rel_err(to_host(y), want) <= TOL["bf16"], (one, d, k)
+        check(to_host(y), want, "bf16", (one, d, k), tight=BLOCK_TIGHT)

@@ -407,3 +407,149 @@ def test_dwpw_block_equals_the_factorised_dense_conv_and_a_matmul(stride):
                             relu_pw=False, store="bf16")
     # the bf16 rounding of t can flip where the fp64 and float32 sums straddle a tie: none here
     np.testing.assert_allclose(got, z, rtol=0, atol=1e-9)
+
+
+# ------------------------------------------------------------------------------------
+# the chain runner (residual wiring, projection shortcut, max-pool, storage rounding) against
+# the same networks composed by hand from torch's float64 CPU routines
+# ------------------------------------------------------------------------------------
+
+def bf16_nearest_even(y64):
+    """fp64 -> nearest bfloat16 (8 significant bits, ties to even) through frexp / rint /
+    ldexp: no bit tricks, independent of the oracle's and the input module's routines."""
+    m, e = np.frexp(np.asarray(y64, dtype=np.float64))          # |m| in [0.5, 1)
+    return np.ldexp(np.rint(m * 256.0) / 256.0, e)
+
+
+def torch_layer(x64, p, stride, pad, residual=None, relu=True, groups=1):
+    """One fused layer as the paper's Section 3 fusion defines it, from library calls:
+    conv2d, per-channel scale and shift, shortcut add, ReLU, storage rounding."""
+    import torch
+    import torch.nn.functional as F
+    y = F.conv2d(torch.from_numpy(x64), torch.from_numpy(p["w"].astype(np.float64)), None, stride,
+                 pad, 1, groups).numpy()
+    y = y * p["scale"].astype(np.float64)[None, :, None, None] \
+        + p["shift"].astype(np.float64)[None, :, None, None]
+    if residual is not None:
+        y = y + residual
+    if relu:
+        y = np.maximum(y, 0.0)
+    return bf16_nearest_even(y)
+
+
+def torch_pool(x64):
+    import torch
+    import torch.nn.functional as F
+    return F.max_pool2d(torch.from_numpy(x64), 3, 2, 1).numpy()
+
+
+def differs(a, b):
+    """Fraction of elements on which two stored tensors disagree."""
+    return float(np.mean(np.asarray(a, np.float64) != np.asarray(b, np.float64)))
+
+
+def test_chain_runner_small_network_against_hand_composition_and_wrong_wirings():
+    """Stem conv, max-pool, an identity-shortcut block and a down-sampling block with a 1x1
+    stride-2 projection: every stored tensor of run_steps equals the network written out by
+    hand.  The same network with the shortcut taken from the wrong tensor, without the pool,
+    with ReLU on the projection or without the storage rounding is far from it, so each of
+    those mistakes in run_steps would fail here."""
+    from oracle.resnet_body import run_steps
+    n, c0, c1, c2, hw = 2, 3, 8, 12, 18
+    S = ti.ConvShape
+    shapes = {"stem": S("stem", n, c0, hw, hw, c1, 3, 3, 1, 1),
+              "a1": S("a1", n, c1, 9, 9, c1, 3, 3, 1, 1), "a2": S("a2", n, c1, 9, 9, c1, 3, 3, 1, 1),
+              "b1": S("b1", n, c1, 9, 9, c2, 3, 3, 2, 1), "bp": S("bp", n, c1, 9, 9, c2, 1, 1, 2, 0),
+              "b2": S("b2", n, c2, 5, 5, c2, 3, 3, 1, 1)}
+    steps = [ti.Step("conv", "stem", 0, 1, shapes["stem"], None, True, 0),
+             ti.Step("maxpool", "pool", 1, 2),
+             ti.Step("conv", "a1", 2, 3, shapes["a1"], None, True, 1),
+             ti.Step("conv", "a2", 3, 4, shapes["a2"], 2, True, 2),
+             ti.Step("conv", "b1", 4, 5, shapes["b1"], None, True, 3),
+             ti.Step("conv", "bp", 4, 6, shapes["bp"], None, False, 4),
+             ti.Step("conv", "b2", 5, 7, shapes["b2"], 6, True, 5)]
+    names = ["stem", "a1", "a2", "b1", "bp", "b2"]
+    W = {i: ti.make_weights(shapes[k], 4100 + i, "bf16") for i, k in enumerate(names)}
+    rng = np.random.default_rng(4099)
+    img = ti.quantize_bf16(rng.uniform(-1, 1, (n, c0, hw, hw)).astype(np.float32))
+    got = run_steps(steps, img, W)
+
+    x = img.astype(np.float64)
+    t1 = torch_layer(x, W[0], 1, 1)
+    t2 = torch_pool(t1)
+    t3 = torch_layer(t2, W[1], 1, 1)
+    t4 = torch_layer(t3, W[2], 1, 1, residual=t2)
+    t5 = torch_layer(t4, W[3], 2, 1)
+    t6 = torch_layer(t4, W[4], 2, 0, relu=False)
+    t7 = torch_layer(t5, W[5], 1, 1, residual=t6)
+    for k, want in {1: t1, 2: t2, 3: t3, 4: t4, 5: t5, 6: t6, 7: t7}.items():
+        assert got[k].shape == want.shape
+        assert np.array_equal(got[k].astype(np.float64), want), k
+    assert (t6 < 0).any()                       # the projection really carries no ReLU
+    assert t2.shape == (n, c1, 9, 9) and t7.shape == (n, c2, 5, 5)
+
+    # planted mistakes, each composed by hand, must NOT reproduce the runner's tensors
+    wrong_identity = torch_layer(t3, W[2], 1, 1, residual=t3)            # shortcut = conv2's own input
+    assert differs(wrong_identity, got[4]) > 0.5
+    no_shortcut = torch_layer(t3, W[2], 1, 1)
+    assert differs(no_shortcut, got[4]) > 0.5
+    wrong_proj = torch_layer(t5, W[5], 1, 1, residual=torch_layer(t4, W[4], 2, 0, relu=True))
+    assert differs(wrong_proj, got[7]) > 0.1                             # ReLU on the projection
+    pool_as_stride = t1[:, :, ::2, ::2]                                  # pool replaced by subsampling
+    assert differs(torch_layer(pool_as_stride, W[1], 1, 1), got[3]) > 0.5
+    unrounded = run_steps(steps, img, W, store_bf16=False)
+    assert differs(unrounded[7], got[7]) > 0.5                           # storage rounding is applied
+
+
+def torch_resnet18_body(img, W):
+    """The ResNet-18 convolutional body (basic blocks, projection shortcuts on the three
+    down-sampling blocks) written as nested code, not from the launch list; the weights of
+    layer i in launch order are W[i]."""
+    it = iter(range(20))
+    x = torch_layer(img.astype(np.float64), W[next(it)], 2, 3)
+    x = torch_pool(x)
+    for stage, down in ((0, False), (1, True), (2, True), (3, True)):
+        for block in range(2):
+            first = block == 0 and down
+            a = torch_layer(x, W[next(it)], 2 if first else 1, 1)
+            shortcut = torch_layer(x, W[next(it)], 2, 0, relu=False) if first else x
+            x = torch_layer(a, W[next(it)], 1, 1, residual=shortcut)
+    return x
+
+
+def test_chain_runner_resnet18_body_against_hand_composition():
+    """The 21-launch list of the ResNet-18 body at batch 1 through run_steps against the network
+    composed by hand from torch float64 calls.  Two fp64 sums in different orders can land on
+    opposite sides of a bf16 tie about once in 10^13 values, so the stored tensors agree bit for
+    bit here; the assertion leaves room for a handful of such flips."""
+    from oracle.resnet_body import run_steps
+    steps = ti.resnet18_body(1)
+    W = {s.layer_index: ti.make_weights(s.shape, ti.layer_seed(5, s.layer_index), "bf16")
+         for s in steps if s.op == "conv"}
+    img = ti.body_images(1, ti.layer_seed(5, 998))
+    got = run_steps(steps, img, W)[steps[-1].dst].astype(np.float64)
+    want = torch_resnet18_body(img, W)
+    assert got.shape == want.shape == (1, 512, 7, 7)
+    assert differs(got, want) < 1e-3
+    rho = float(np.sqrt(np.mean(want * want)))
+    assert rho > 0.1 and np.max(np.abs(got - want)) <= 1e-2 * rho
+
+
+def test_chain_runner_mobilenet_body_against_hand_composition():
+    """The 27-launch MobileNet body at batch 1 against stem + 13 x (depthwise via groups = C, 1x1)
+    written as a loop over the block table."""
+    from oracle.resnet_body import run_steps
+    steps = ti.mobilenet_body(1)
+    W = {s.layer_index: ti.make_weights(s.shape, ti.layer_seed(6, s.layer_index), "bf16")
+         for s in steps}
+    img = ti.body_images(1, ti.layer_seed(6, 998))
+    got = run_steps(steps, img, W)[steps[-1].dst].astype(np.float64)
+    strides = [1, 2, 1, 2, 1, 2, 1, 1, 1, 1, 1, 2, 1]
+    x = torch_layer(img.astype(np.float64), W[0], 2, 1)
+    for b, s in enumerate(strides):
+        x = torch_layer(x, W[1 + 2 * b], s, 1, groups=x.shape[1])
+        x = torch_layer(x, W[2 + 2 * b], 1, 0)
+    assert got.shape == x.shape == (1, 1024, 7, 7)
+    assert differs(got, x) < 1e-3
+    rho = float(np.sqrt(np.mean(x * x)))
+    assert rho > 0.01 and np.max(np.abs(got - x)) <= 1e-2 * rho
