@@ -112,6 +112,28 @@ tvg_status tvg_conv2d_fused(const tvg_conv_desc *desc, const void *x, const void
                             void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * tvg_conv2d_fused for callers that cannot allocate device memory and so have no workspace to
+ * pass: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same operator, same kernels, same results bit for bit; the scratch that a split reduction
+ * needs comes from an array inside the library (tvg_static_scratch_bytes() = 16 MiB per GPU,
+ * held from the library's load to the end of the process) instead of a workspace argument.
+ *   - A problem whose tvg_conv2d_workspace_size() exceeds that is TVG_ERR_WORKSPACE (use
+ *     tvg_conv2d_fused with a workspace); all other arguments and errors as tvg_conv2d_fused.
+ *   - The call allocates and frees nothing and never synchronises.  The device that owns
+ *     hip_stream and the pointers must be the current device: the array's address is looked up
+ *     for the current device on the first call that needs it (TVG_ERR_LAUNCH if the runtime
+ *     cannot resolve it).
+ *   - Every call on a GPU shares that GPU's array.  Calls on one stream are ordered and safe;
+ *     calls that may overlap on one GPU (different streams, concurrent graphs) race on it and
+ *     give wrong results.  Nothing in the array needs clearing between calls: every partial sum
+ *     is written before it is read.
+ */
+tvg_status tvg_conv2d_fused_static(const tvg_conv_desc *desc, const void *x, const void *w,
+                                   const float *scale, const float *shift, const float *bias,
+                                   const void *residual, void *y, void *hip_stream);
+size_t tvg_static_scratch_bytes(void);
+
+/*
  * Depthwise fused 3x3 conv2d, channel multiplier 1 (Table 2, rows D; same fused
  * tail).  Bandwidth kernel on the vector ALUs, no matrix cores.  Arguments as
  * above with w = [c][1][3][3]; desc->k must equal desc->c and r == s == 3;

@@ -76,6 +76,10 @@ def load() -> ctypes.CDLL:
     for f in (lib.tvg_conv2d_fused, lib.tvg_dwconv2d_fused):
         f.restype = ctypes.c_int
         f.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.tvg_conv2d_fused_static.restype = ctypes.c_int
+    lib.tvg_conv2d_fused_static.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.tvg_static_scratch_bytes.restype = sz
+    lib.tvg_static_scratch_bytes.argtypes = []
     lib.tvg_dwpw_workspace_size.restype = ctypes.c_int
     lib.tvg_dwpw_workspace_size.argtypes = [dp, ctypes.c_int32, ctypes.POINTER(sz)]
     lib.tvg_dwpw_one_kernel.restype = ctypes.c_int
@@ -166,6 +170,17 @@ def tvg_conv2d_fused(desc, x, w, scale, shift, bias, residual, y, workspace=None
     return int(load().tvg_conv2d_fused(ctypes.byref(desc), _addr(x), _addr(w), _addr(scale),
                                        _addr(shift), _addr(bias), _addr(residual), _addr(y),
                                        _addr(workspace), workspace_bytes, _stream(stream)))
+
+
+def tvg_conv2d_fused_static(desc, x, w, scale, shift, bias, residual, y, stream=None) -> int:
+    """tvg_conv2d_fused with the library's own static scratch instead of a workspace."""
+    return int(load().tvg_conv2d_fused_static(ctypes.byref(desc), _addr(x), _addr(w), _addr(scale),
+                                              _addr(shift), _addr(bias), _addr(residual), _addr(y),
+                                              _stream(stream)))
+
+
+def tvg_static_scratch_bytes() -> int:
+    return int(load().tvg_static_scratch_bytes())
 
 
 def tvg_dwconv2d_fused(desc, x, w, scale, shift, bias, residual, y, workspace=None,

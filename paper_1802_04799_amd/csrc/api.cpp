@@ -138,6 +138,32 @@ void forget_dispatch()
     g_dispatch.clear();
 }
 
+// Scratch memory of tvg_conv2d_fused_static: the split-reduction partials of the generic kernel
+// live in this array instead of a caller's workspace.  Every GPU that loads the library holds
+// its own copy at its own address until the process ends.  In host code the array's name is
+// only a handle for hipGetSymbolAddress; kernels are given the resolved device address.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices];      // device address of `scratch` per device, once resolved
+
+// The current device's copy of `scratch`; resolved on the first call per device.
+tvg_status static_scratch(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return TVG_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return TVG_ERR_LAUNCH;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return TVG_OK;
+}
+
 }  // namespace
 
 namespace tvg {
@@ -267,6 +293,25 @@ tvg_status tvg_conv2d_fused(const tvg_conv_desc *desc, const void *x, const void
         return TVG_ERR_WORKSPACE;
     return tvg::launch_conv_igemm(p, plan, ptr, stream);
 }
+
+tvg_status tvg_conv2d_fused_static(const tvg_conv_desc *desc, const void *x, const void *w,
+                                   const float *scale, const float *shift, const float *bias,
+                                   const void *residual, void *y, void *hip_stream)
+{
+    size_t need = 0;
+    tvg_status st = tvg_conv2d_workspace_size(desc, &need);       // validates the descriptor
+    if (st != TVG_OK) return st;
+    if (!x || !w || !scale || !shift || !y) return TVG_ERR_NULL;
+    if (need > kStaticScratchBytes) return TVG_ERR_WORKSPACE;     // before any device call
+    void *ws = nullptr;
+    if (need > 0) {
+        st = static_scratch(&ws);
+        if (st != TVG_OK) return st;
+    }
+    return tvg_conv2d_fused(desc, x, w, scale, shift, bias, residual, y, ws, need, hip_stream);
+}
+
+size_t tvg_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
 tvg_status tvg_dwconv2d_fused(const tvg_conv_desc *desc, const void *x, const void *w,
                               const float *scale, const float *shift, const float *bias,

@@ -152,6 +152,19 @@ def test_workspace_query_and_too_small_workspace():
     assert tvg.tvg_dwconv2d_workspace_size(desc(k=8, c=8)) == 0
 
 
+def test_static_scratch_entry_point_validates_on_the_host():
+    """tvg_conv2d_fused_static: descriptor, NULL and size errors come back before any device
+    call (this machine has no GPU)."""
+    assert tvg.tvg_static_scratch_bytes() == 16 << 20
+    assert tvg.tvg_conv2d_fused_static(desc(n=0), FAKE, FAKE, FAKE, FAKE, None, None, FAKE, 0) == 2
+    assert tvg.tvg_conv2d_fused_static(desc(dtype=5), FAKE, FAKE, FAKE, FAKE, None, None, FAKE, 0) == 3
+    assert tvg.tvg_conv2d_fused_static(desc(), FAKE, None, FAKE, FAKE, None, None, FAKE, 0) == 1
+    assert tvg.load().tvg_conv2d_fused_static(None, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, None) == 1
+    big = desc(n=1, c=512, h=28, w=28, k=512)
+    assert tvg.tvg_conv2d_workspace_size(big) > tvg.tvg_static_scratch_bytes()
+    assert tvg.tvg_conv2d_fused_static(big, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, 0) == 4
+
+
 def test_tile_table_sets_overrides_and_forgets():
     """tvg_conv2d_set_tile / tvg_conv2d_get_plan are host-only: the planners' choice, a fixed
     tile, its removal, and what is rejected."""

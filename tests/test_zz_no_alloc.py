@@ -1,0 +1,77 @@
+"""tvg_conv2d_fused_static: the entry point for callers that cannot allocate (no workspace
+argument; split-reduction partials live in an array inside the library).  Through the C ABI,
+against the existing entry point (bit for bit: same kernels) and against the oracle, on two calls
+in a row, the second on a smaller problem that finds the first one's partials in the array."""
+import numpy as np
+import pytest
+
+import oracle
+import tvg_inputs as ti
+from _util import check, dev_inputs, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+def both_entry_points(tvg, sh, inp, dtype):
+    import torch
+    d = dev_inputs(inp, dtype)
+    code = tvg.TVG_BF16 if dtype == "bf16" else tvg.TVG_F32
+    desc = tvg.ConvDesc(sh.n, sh.ic, sh.h, sh.w, sh.oc, sh.r, sh.s, sh.stride, sh.stride, sh.pad,
+                        sh.pad, code, tvg.TVG_RELU)
+    need = tvg.tvg_conv2d_workspace_size(desc)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    y_static = torch.full(sh.y_shape(), float("nan"), dtype=tdt, device="cuda:0")
+    y_ws = torch.full(sh.y_shape(), float("nan"), dtype=tdt, device="cuda:0")
+    ws = torch.empty(max(need, 1), dtype=torch.uint8, device="cuda:0")
+    torch.cuda.synchronize()
+    st = tvg.tvg_conv2d_fused_static(desc, d["x"], d["w"], d["scale"], d["shift"], d["bias"],
+                                     d["residual"], y_static)
+    assert st == 0, tvg.status_string(st)
+    st = tvg.tvg_conv2d_fused(desc, d["x"], d["w"], d["scale"], d["shift"], d["bias"],
+                              d["residual"], y_ws, ws, need)
+    assert st == 0, tvg.status_string(st)
+    torch.cuda.synchronize()
+    return need, y_static, y_ws
+
+
+def test_static_scratch_entry_point_two_calls_in_a_row(tvg):
+    import torch
+    assert tvg.tvg_static_scratch_bytes() == 16 << 20
+    # first call: C2 at batch 1, fp32 (reduction split nine ways, 7.2 MB of partials);
+    # second call: C12 at batch 1 (3.2 MB), then a small ragged problem (a few KB) - each finds
+    # the previous call's partials in the array
+    calls = [(ti.resnet18_convs(1)[1], ti.layer_seed(2, 1), "f32"),
+             (ti.resnet18_convs(1)[11], ti.layer_seed(2, 11), "f32"),
+             (ti.ConvShape("small", 1, 40, 5, 6, 70, 3, 3, 1, 1), 31, "f32"),
+             (ti.ConvShape("small16", 2, 64, 6, 5, 33, 3, 3, 2, 1), 32, "bf16")]
+    needs = []
+    for sh, seed, dtype in calls:
+        inp = ti.make_inputs(sh, seed, dtype, residual=True, bias=True)
+        need, y_static, y_ws = both_entry_points(tvg, sh, inp, dtype)
+        needs.append(need)
+        assert not torch.isnan(y_static.float()).any()
+        assert torch.equal(y_static, y_ws), sh.name            # same kernels, same order: same bits
+        want = oracle.conv2d_fused(inp["x"], inp["w"], inp["scale"], inp["shift"], inp["bias"],
+                                   inp["residual"], stride=(sh.stride,) * 2, pad=(sh.pad,) * 2,
+                                   relu=True)
+        check(to_host(y_static), want, dtype, sh.name)
+    assert needs[0] > needs[1] > needs[2] > 0                  # the scratch really was in use
+
+
+def test_static_scratch_entry_point_without_a_split_and_beyond_the_limit(tvg):
+    import torch
+    # a problem that needs no scratch (bf16 3x3, batch 8): the two entry points agree
+    sh = ti.ConvShape("c6", 8, 128, 28, 28, 128, 3, 3, 1, 1)
+    inp = ti.make_inputs(sh, 77, "bf16")
+    need, y_static, y_ws = both_entry_points(tvg, sh, inp, "bf16")
+    assert need == 0 and torch.equal(y_static, y_ws)
+    # a problem whose partials exceed the array: an error code, nothing launched
+    big = tvg.ConvDesc(1, 512, 28, 28, 512, 3, 3, 1, 1, 1, 1, tvg.TVG_F32, 0)
+    assert tvg.tvg_conv2d_workspace_size(big) > tvg.tvg_static_scratch_bytes()
+    y = torch.full((1, 512, 28, 28), 7.0, device="cuda:0")
+    x = torch.zeros((1, 512, 28, 28), device="cuda:0")
+    w = torch.zeros((512, 512, 3, 3), device="cuda:0")
+    s = torch.ones(512, device="cuda:0")
+    assert tvg.tvg_conv2d_fused_static(big, x, w, s, s, None, None, y) == 4
+    torch.cuda.synchronize()
+    assert bool((y == 7.0).all())
