@@ -7,11 +7,17 @@ One step = one pass over the 12 ResNet-18 conv2d shapes (TVM paper, Table 2, C1.
 batch 64 with bf16 inputs/outputs, fp32 accumulate and the fused scale/shift + ReLU tail:
 12 launches of tvg_conv2d_fused through the C ABI, inputs already resident in HBM.
 Prints ONE JSON line.  ``value`` is the whole step's throughput in TFLOP/s (2*MACs of the
-direct method over the step time).  ``roofline`` describes the layer (= kernel launch)
-that takes the most time inside the timed region; ``layers`` lists all twelve.  The
-depthwise layers (D1..D9), the fp32 batch-1 shapes and the ResNet-18 body are measured
-after the timed region and reported under their own keys.  ``cpu_baseline`` times the fp64
-CPU oracle on a bounded sample of the same workload on this machine's host cores.
+direct method over the step time).  ``roofline`` describes ONE kernel, the one with the
+largest share of the step (conv3x3_dbuf_kernel: the layers the library plans with it are
+launched last and back to back, two HIP events per step bracket exactly them inside the timed
+region); ``layers`` lists all twelve.  ``ceilings`` holds what the GPU sustains in this very run
+(a plain copy, a register-resident matrix-instruction loop per dtype), so every fraction can be
+read against the data-sheet peak and against the achievable rate.  The depthwise layers
+(D1..D9), the fp32 batch-1 shapes and the network bodies are measured after the timed region
+and reported under their own keys; batch-1 layers are timed three ways (eager on warm
+buffers, eager over rotating buffers, and one captured HIP graph of 240 launches over rotating
+buffers), kernel-only durations of the same launches are in profiles/.  ``cpu_baseline`` times
+the fp64 CPU oracle on the same workload on this machine's host cores.
 """
 import argparse
 import json
@@ -53,6 +59,9 @@ def parse():
     ap.add_argument("--body-probe", default="", choices=["", "resnet18", "mobilenet"],
                     help="only run this network body at batch 32 --warmup + --steps times "
                          "(for profiler runs)")
+    ap.add_argument("--batch1-probe", action="store_true",
+                    help="only launch the batch-1 configurations (C1..C12 fp32, D1..D9 fp32) "
+                         "--steps times each over rotating buffers (for profiler runs)")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
                     help="only run a plain device copy of this many MiB --steps times "
                          "(reference for scaling FETCH_SIZE / WRITE_SIZE counters)")
@@ -127,17 +136,69 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / iters
 
+    def time_graph(launch_all, replays=5):
+        """Mean milliseconds per replay of one HIP graph that holds whatever launch_all()
+        enqueues (the library neither allocates nor synchronises, so its calls record as they
+        stand); the capture is warmed up eagerly first and replayed once before timing."""
+        launch_all()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=torch.cuda.Stream()):
+            launch_all()
+        g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(replays):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / replays
+
+    def batch1_three_ways(l, copies, launches=240):
+        """One batch-1 layer: eager on the same (warm) buffers, eager over rotating buffer sets
+        whose footprint exceeds twice the memory-side cache (cold), and the same rotating
+        launches as one captured HIP graph (no host between the launches)."""
+        warm = time_loop(lambda: l.launch(0), 200)
+        state = {"i": 0}
+
+        def cold_call():
+            l.launch(state["i"] % copies)
+            state["i"] += 1
+        cold = time_loop(cold_call, max(2 * copies, 200), warmup=copies)
+        n = max(launches, copies)
+
+        def many():
+            for k in range(n):
+                l.launch(k % copies)
+        graph = time_graph(many) / n
+        return warm, cold, graph
+
     # ---------------------------------------------------------------- the timed region
     if args.copy_probe:
         return copy_probe(torch, args)
     if args.depthwise_probe:
         for i, sh in enumerate(ti.mobilenet_depthwise(64)):
-            l = Layer(sh, ti.layer_seed(3, 100 + i), "f32", depthwise=True, copies=2)
+            copies = rotation(sh.algorithmic_bytes(4))
+            l = Layer(sh, ti.layer_seed(3, 100 + i), "f32", depthwise=True, copies=copies)
             for k in range(args.warmup + args.steps):
-                l.launch(k & 1)
+                l.launch(k % copies)
             torch.cuda.synchronize()
             del l
         print(json.dumps({"depthwise_probe": "D1..D9 batch 64 fp32", "launches_each": args.warmup + args.steps}))
+        return
+    if args.batch1_probe:
+        for name, shapes, cfg, dw in (("C", ti.resnet18_convs(1), 2, False),
+                                      ("D", ti.mobilenet_depthwise(1), 3, True)):
+            for i, sh in enumerate(shapes):
+                copies = rotation(sh.algorithmic_bytes(4), cap=400)
+                l = Layer(sh, ti.layer_seed(cfg, i), "f32", depthwise=dw, copies=copies)
+                for k in range(args.warmup + args.steps):
+                    l.launch(k % copies)
+                torch.cuda.synchronize()
+                del l
+        print(json.dumps({"batch1_probe": "C1..C12, D1..D9, fp32, batch 1, rotating buffers",
+                          "launches_each": args.warmup + args.steps}))
         return
     if args.body_probe:
         r = bench_body(tvg, ti, torch, np, dev, to_dev, time_loop, args.body_probe,
@@ -150,11 +211,20 @@ def main():
     if args.only:
         keep = set(args.only.split(","))
         layers = [l for l in layers if l.sh.name in keep]
-    # The twelve layers are independent; they are launched with the seven 3x3 layers (the
-    # LDS-patch implicit-GEMM kernels conv3x3_patch_kernel and conv3x3_dbuf_kernel, together the
-    # largest share of the step) last and back to back, so that two events per step bracket
-    # exactly those launches.
-    is_dom = lambda l: l.sh.r == 3
+    # The twelve layers are independent.  The launches of ONE kernel, conv3x3_dbuf_kernel (the
+    # software-pipelined bf16 3x3 implicit GEMM, the largest share of the step), come last and
+    # back to back, so that two events per step bracket exactly that kernel's launches.
+    # Which layers it takes is the library's planning decision, read through tvg_conv2d_get_plan.
+    DOM_KERNEL = 2          # TVG_KERNEL_3X3_PIPELINED
+    is_dom = lambda l: tvg.tvg_conv2d_get_plan(l.desc)[0] == DOM_KERNEL
+
+    tuning = None
+    if args.tune:       # the measured per-shape knob search, outside the timed region
+        from paper_1802_04799_amd import tune
+        tuning = [dict(tune.tune_conv2d(l.desc, l.x[0], l.w[0], l.scale, l.shift, l.y[0],
+                                        workspace=l.ws if l.ws_bytes else None), layer=l.sh.name)
+                  for l in layers]
+
     layers = [l for l in layers if not is_dom(l)] + [l for l in layers if is_dom(l)]
     n_dom = sum(1 for l in layers if is_dom(l))
     first_dom = len(layers) - n_dom
@@ -164,13 +234,6 @@ def main():
     def step():
         for l in layers:
             l.launch()
-
-    tuning = None
-    if args.tune:       # a measured per-shape choice of the tile knob, outside the timed region
-        from paper_1802_04799_amd import tune
-        tuning = [dict(tune.tune_conv2d(l.desc, l.x[0], l.w[0], l.scale, l.shift, l.y[0],
-                                        workspace=l.ws if l.ws_bytes else None), layer=l.sh.name)
-                  for l in layers]
 
     for _ in range(args.warmup):
         step()
@@ -207,35 +270,46 @@ def main():
     ms_per_step = wall * 1e3 / K
     value = step_flops / (wall / K) / 1e12
 
+    # ------------------------------------------- what the GPU sustains, in this same run
+    ceilings = measure_ceilings(tvg, torch, dev, time_loop)
+    ach_bf16, ach_hbm = ceilings["mfma_bf16_tflops"], ceilings["copy_gbs"]
+
     layer_rows = []
     for l, ms in zip(layers, per_layer_ms):
         tf = l.sh.flops / (ms * 1e-3) / 1e12
         gbs = l.bytes / (ms * 1e-3) / 1e9
         ai = l.sh.flops / l.bytes
         attainable = min(PEAK_BF16_TFLOPS, ai * PEAK_HBM_GBS / 1e3)
-        layer_rows.append({"name": l.sh.name, "us": round(ms * 1e3, 2), "tflops": round(tf, 1),
+        achievable = min(ach_bf16, ai * ach_hbm / 1e3)
+        layer_rows.append({"name": l.sh.name, "kernel": tvg.KERNEL_NAMES[tvg.tvg_conv2d_get_plan(l.desc)[0]],
+                           "us": round(ms * 1e3, 2), "tflops": round(tf, 1),
                            "gbs": round(gbs, 1), "frac_mfma_peak": round(tf / PEAK_BF16_TFLOPS, 4),
                            "frac_attainable": round(tf / attainable, 4),
+                           "frac_achievable": round(tf / achievable, 4),
                            "bound": "mfma" if ai > PEAK_BF16_TFLOPS * 1e3 / PEAK_HBM_GBS else "hbm"})
     roofline = None
     if n_dom:
         dom_ms = sum(d0[k].elapsed_time(d1[k]) for k in range(K)) / K      # all n_dom launches
-        dom_flops = sum(l.sh.flops for l in layers if is_dom(l))
-        dom_bytes = sum(l.bytes for l in layers if is_dom(l))
+        dom = [l for l in layers if is_dom(l)]
+        dom_flops = sum(l.sh.flops for l in dom)
+        dom_bytes = sum(l.bytes for l in dom)
         dom_tf = dom_flops / (dom_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": round(dom_tf, 2), "peak": PEAK_BF16_TFLOPS,
                     "unit": "TFLOP/s", "frac": round(dom_tf / PEAK_BF16_TFLOPS, 4),
-                    "traffic": measured_traffic("conv3x3_kernels"),
-                    "kernel": "conv3x3_patch_kernel + conv3x3_dbuf_kernel (bf16 3x3 implicit GEMM)",
+                    "traffic": measured_traffic("conv3x3_dbuf_kernel"),
+                    "kernel": "conv3x3_dbuf_kernel",
+                    "frac_of_achievable_mfma": round(dom_tf / ach_bf16, 4),
                     "launches_per_step": n_dom,
-                    "layers": [l.sh.name for l in layers if is_dom(l)],
+                    "layers": [l.sh.name for l in dom],
                     "flops_per_launch": dom_flops / n_dom,
                     "algorithmic_bytes_per_launch": dom_bytes / n_dom,
                     "avg_launch_us": round(dom_ms * 1e3 / n_dom, 2),
                     "share_of_step_time": round(dom_ms / ms_per_step, 3),
-                    "timing": "two HIP events per step around the kernel's back-to-back launches, "
-                              "inside the timed region, on the launch stream"}
+                    "timing": "two HIP events per step around this kernel's back-to-back launches, "
+                              "inside the timed region, on the launch stream; per-unit figures: "
+                              "2*IC*9 flops per output element, (|x|+|w|+|y|)*2 + 8*OC bytes per launch"}
 
+    r3 = [(l, ms) for l, ms in zip(layers, per_layer_ms) if l.sh.r == 3]
     out = {
         "metric": "fused conv2d TFLOP/s (% MFMA peak); depthwise conv GB/s (% HBM peak)",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": K,
@@ -246,8 +320,13 @@ def main():
                                "one step = 12 launches" + (f" (restricted to {args.only})" if args.only else ""),
                    "step_gflop": round(step_flops / 1e9, 2), "step_mbytes": round(step_bytes / 1e6, 1),
                    "frac_mfma_peak": round(value / PEAK_BF16_TFLOPS, 4),
+                   "frac_achievable_mfma": round(value / ach_bf16, 4),
+                   "all_3x3_layers": {"layers": [l.sh.name for l, _ in r3],
+                                      "gflop": round(sum(l.sh.flops for l, _ in r3) / 1e9, 2),
+                                      "us_calibration_pass": round(sum(ms for _, ms in r3) * 1e3, 1)},
                    "stream_out_hint": not args.no_stream_hint},
         "roofline": roofline,
+        "ceilings": ceilings,
         "layers": layer_rows,
         "tuning": tuning,
         "layers_note": "per-launch durations from a calibration pass with an event before every "
@@ -256,38 +335,39 @@ def main():
 
     # ------------------------------------------------------------ extras (not in `value`)
     if not args.skip_extras:
-        # depthwise D1..D9, fp32, batch 1: warm (same buffers) and cold (rotating > 512 MB)
+        # depthwise D1..D9, fp32, batch 1 (configs[2]): three ways
         dw_rows = []
         for i, sh in enumerate(ti.mobilenet_depthwise(1)):
             nbytes = sh.algorithmic_bytes(4)
-            copies = min(1500, max(2, int(640e6 // nbytes) + 1))
+            copies = rotation(nbytes, cap=1500)
             l = Layer(sh, ti.layer_seed(3, i), "f32", depthwise=True, copies=copies)
-            warm = time_loop(lambda: l.launch(0), 200)
-            state = {"i": 0}
-
-            def cold_call():
-                l.launch(state["i"] % copies)
-                state["i"] += 1
-            cold = time_loop(cold_call, 2 * copies, warmup=copies)
+            warm, cold, graph = batch1_three_ways(l, copies)
             dw_rows.append({"name": sh.name, "kbytes": round(nbytes / 1e3, 1),
                             "warm_us": round(warm * 1e3, 2), "cold_us": round(cold * 1e3, 2),
+                            "graph_cold_us": round(graph * 1e3, 2),
                             "warm_gbs": round(nbytes / (warm * 1e-3) / 1e9, 1),
-                            "cold_gbs": round(nbytes / (cold * 1e-3) / 1e9, 1)})
+                            "cold_gbs": round(nbytes / (cold * 1e-3) / 1e9, 1),
+                            "graph_cold_gbs": round(nbytes / (graph * 1e-3) / 1e9, 1),
+                            "graph_cold_frac_hbm_peak": round(nbytes / (graph * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                            "graph_cold_frac_copy": round(nbytes / (graph * 1e-3) / 1e9 / ach_hbm, 4)})
             del l
-        # the same kernel at batch 64: HBM-sized traffic
+        # the same kernel at batch 64: HBM-sized traffic, rotating so that a cycle's reads and
+        # writes exceed twice the memory-side cache
         dw64_rows = []
         for i, sh in enumerate(ti.mobilenet_depthwise(64)):
-            l = Layer(sh, ti.layer_seed(3, 100 + i), "f32", depthwise=True, copies=2)
+            copies = rotation(sh.algorithmic_bytes(4))
+            l = Layer(sh, ti.layer_seed(3, 100 + i), "f32", depthwise=True, copies=copies)
             state = {"i": 0}
 
             def call():
-                l.launch(state["i"] & 1)
+                l.launch(state["i"] % copies)
                 state["i"] += 1
-            ms = time_loop(call, 50)
-            dw64_rows.append({"name": sh.name, "mbytes": round(l.bytes / 1e6, 1),
-                              "us": round(ms * 1e3, 2),
-                              "gbs": round(l.bytes / (ms * 1e-3) / 1e9, 1),
-                              "frac_hbm_peak": round(l.bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)})
+            ms = time_loop(call, max(50, 4 * copies), warmup=copies)
+            gbs = l.bytes / (ms * 1e-3) / 1e9
+            dw64_rows.append({"name": sh.name, "mbytes": round(l.bytes / 1e6, 1), "buffer_sets": copies,
+                              "us": round(ms * 1e3, 2), "gbs": round(gbs, 1),
+                              "frac_hbm_peak": round(gbs / PEAK_HBM_GBS, 4),
+                              "frac_copy": round(gbs / ach_hbm, 4)})
             del l
         tot_b = sum(r["mbytes"] for r in dw64_rows) * 1e6
         tot_t = sum(r["us"] for r in dw64_rows) * 1e-6
@@ -296,23 +376,36 @@ def main():
             "batch64_fp32": dw64_rows,
             "batch64_total_gbs": round(tot_b / tot_t / 1e9, 1),
             "batch64_frac_hbm_peak": round(tot_b / tot_t / 1e9 / PEAK_HBM_GBS, 4),
-            "note": "algorithmic bytes (x, w, y, scale, shift moved once) / event time; batch-1 "
-                    "layers are 0.45-4 MB and launch-bound; cold = rotating disjoint buffers",
+            "batch64_frac_copy": round(tot_b / tot_t / 1e9 / ach_hbm, 4),
+            "note": "algorithmic bytes (x, w, y, scale, shift moved once) / event time.  batch 1: "
+                    "warm = same buffers, cold = rotating disjoint buffer sets (> 640 MB in all), "
+                    "graph_cold = the rotating launches as one captured HIP graph (no host "
+                    "between them); kernel-only durations are in profiles/.  batch 64 "
+                    "(supplementary, not a BASELINE.json configuration) rotates buffer sets too.",
         }
-        # fp32, batch 1 (configs[1]): launch/occupancy-bound, reported for completeness
+        # fp32, batch 1 (configs[0] = C2, configs[1] = C1..C12): three ways
         rows = []
         for i, sh in enumerate(ti.resnet18_convs(1)):
-            l = Layer(sh, ti.layer_seed(2, i), "f32")
-            ms = time_loop(lambda: l.launch(0), 200)
-            rows.append({"name": sh.name, "us": round(ms * 1e3, 2),
-                         "tflops": round(sh.flops / (ms * 1e-3) / 1e12, 2),
+            copies = rotation(sh.algorithmic_bytes(4), cap=400)
+            l = Layer(sh, ti.layer_seed(2, i), "f32", copies=copies)
+            warm, cold, graph = batch1_three_ways(l, copies)
+            rows.append({"name": sh.name, "kernel": tvg.KERNEL_NAMES[tvg.tvg_conv2d_get_plan(l.desc)[0]],
+                         "warm_us": round(warm * 1e3, 2), "cold_us": round(cold * 1e3, 2),
+                         "graph_cold_us": round(graph * 1e3, 2),
+                         "warm_tflops": round(sh.flops / (warm * 1e-3) / 1e12, 2),
+                         "graph_cold_tflops": round(sh.flops / (graph * 1e-3) / 1e12, 2),
                          "splits_ws_bytes": l.ws_bytes})
             del l
-        tot = sum(r["us"] for r in rows) * 1e-6
         fl = sum(s.flops for s in ti.resnet18_convs(1))
-        out["fp32_batch1"] = {"layers": rows, "total_us": round(tot * 1e6, 1),
-                              "tflops": round(fl / tot / 1e12, 2),
-                              "frac_fp32_peak": round(fl / tot / 1e12 / PEAK_FP32_TFLOPS, 4)}
+        tots = {k: sum(r[k] for r in rows) for k in ("warm_us", "cold_us", "graph_cold_us")}
+        out["fp32_batch1"] = {"layers": rows,
+                              "total_warm_us": round(tots["warm_us"], 1),
+                              "total_cold_us": round(tots["cold_us"], 1),
+                              "total_graph_cold_us": round(tots["graph_cold_us"], 1),
+                              "tflops_warm": round(fl / tots["warm_us"] / 1e6, 2),
+                              "frac_fp32_peak_warm": round(fl / tots["warm_us"] / 1e6 / PEAK_FP32_TFLOPS, 4),
+                              "frac_fp32_achievable_warm": round(fl / tots["warm_us"] / 1e6 / ceilings["mfma_fp32_tflops"], 4),
+                              "config1_C2": next(r for r in rows if r["name"] == "C2")}
         # ResNet-18 body, batch 32, bf16 (configs[4]): 20 convs + 1 max-pool, 21 launches
         out["resnet18_body"] = bench_body(tvg, ti, torch, np, dev, to_dev, time_loop, iters=50,
                                           warmup=20, use_arena=not args.no_arena,
@@ -334,6 +427,47 @@ def main():
         out["cpu_baseline"] = cpu_baseline(ti, np)
 
     print(json.dumps(out))
+
+
+def rotation(nbytes, cap=64):
+    """Disjoint buffer sets to rotate through so that one cycle touches more than 640 MB, over
+    twice the 256 MB memory-side cache: every launch then reads from HBM."""
+    return int(min(cap, max(2, 640e6 // nbytes + 1)))
+
+
+def measure_ceilings(tvg, torch, dev, time_loop):
+    """What this GPU sustains, measured in this run: a plain copy (1 GiB each way, far beyond
+    the caches) and a register-resident matrix-instruction loop per dtype, two workgroups per
+    compute unit."""
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device=dev)
+    dst = torch.empty(n, dtype=torch.uint8, device=dev)
+    src.fill_(1)
+
+    def copy():
+        assert tvg.tvg_probe_copy(src, dst, n) == 0
+    ms = time_loop(copy, 10)
+    copy_gbs = 2 * n / (ms * 1e-3) / 1e9
+    ms_t = time_loop(lambda: dst.copy_(src), 10)
+    del src, dst
+    out = torch.empty(512 * 256, dtype=torch.float32, device=dev)
+    res = {"copy_gbs": round(copy_gbs, 1), "copy_frac_hbm_peak": round(copy_gbs / PEAK_HBM_GBS, 4),
+           "runtime_copy_gbs": round(2 * n / (ms_t * 1e-3) / 1e9, 1)}
+    for name, code, iters, peak in (("bf16", tvg.TVG_BF16, 20000, PEAK_BF16_TFLOPS),
+                                    ("fp32", tvg.TVG_F32, 4000, PEAK_FP32_TFLOPS)):
+        fl = {}
+
+        def run():
+            st, fl["v"] = tvg.tvg_probe_mfma(code, iters, 512, out)
+            assert st == 0
+        ms = time_loop(run, 3, warmup=1)
+        tf = fl["v"] / (ms * 1e-3) / 1e12
+        res[f"mfma_{name}_tflops"] = round(tf, 1)
+        res[f"mfma_{name}_frac_peak"] = round(tf / peak, 4)
+    res["note"] = ("copy: 1 GiB read + 1 GiB written by a 16-byte grid-stride copy kernel of the "
+                   "library (runtime_copy: the HIP runtime's own copy of the same buffers); mfma: "
+                   "512 workgroups x 4 waves x 4 independent accumulator tiles, operands in registers")
+    return res
 
 
 def copy_probe(torch, args):

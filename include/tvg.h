@@ -219,7 +219,7 @@ tvg_status tvg_plan_arena(const tvg_tensor_life *tensors, int32_t count, uint64_
  * problem can fix the choice.  Host-only calls, safe to use from several threads.
  *
  * tvg_conv2d_set_tile: from now on plan this exact problem (every descriptor field but flags)
- * with tiles of mt x nt, one of 64x256, 128x128, 64x128, 128x64, 64x64 (anything else:
+ * with tiles of mt x nt (the problem's other knobs, see tvg_conv2d_set_knobs, stay as they are), one of 64x256, 128x128, 64x128, 128x64, 64x64 (anything else:
  * TVG_ERR_UNSUPPORTED); mt = nt = 0 forgets the problem.  A tile shape that the problem's kernel
  * cannot use makes the call fall back to the generic kernel, which is correct but slow: time
  * before you fix.  At most 1024 problems are remembered.
@@ -235,6 +235,54 @@ typedef enum {
 } tvg_kernel;
 tvg_status tvg_conv2d_set_tile(const tvg_conv_desc *desc, int32_t mt, int32_t nt);
 tvg_status tvg_conv2d_get_plan(const tvg_conv_desc *desc, int32_t *kernel, int32_t *mt, int32_t *nt);
+
+/*
+ * The whole schedule space of a problem (TVM paper Section 5.1: a schedule template with knobs
+ * per operator; Section 5.3: the space is explored by measurement).  Every knob is a set of
+ * compiled kernel instances or a launch parameter; 0 leaves a knob to the library's rule.
+ *   mt, nt      workgroup tile, as for tvg_conv2d_set_tile (with it the wave tile: 64x64, 32x64,
+ *               64x32 or 32x32 outputs per wave)
+ *   stages      bf16 3x3: 1 = the single-stage kernel, 2 = the software-pipelined kernel with two
+ *               LDS stages (from 64 input channels on, a multiple of 32; 64-channel tiles)
+ *   split_k     partitions of the reduction.  Generic kernel (fp32, odd shapes): 1..32 partitions
+ *               across workgroups, summed by a second launch - tvg_conv2d_workspace_size follows
+ *               the knob.  Pipelined 3x3: 1 or 2 groups of four waves inside one workgroup that
+ *               take alternate input-channel chunks and add their accumulators through LDS
+ *               (grids of at most one workgroup per CU, stride 1, 128- or 256-pixel tiles, input
+ *               channels a multiple of 64)
+ *   lds_pitch   pipelined 3x3, stride 1: 1 = patch rows of W + 2 words, 2 = rows of W + 16 words
+ *               (operand reads free of bank conflicts across row ends, more LDS)
+ *   row_loads   pipelined 3x3, odd rows of at most 7 pixels: 1 = element loads, 2 = one 16-byte
+ *               load per row and channel from the aligned address below the row, shifted into place
+ * tvg_conv2d_set_knobs: fix the knobs of this exact problem (every descriptor field but flags);
+ * knobs == NULL or all zero forgets the problem.  Values outside the ranges above are
+ * TVG_ERR_UNSUPPORTED.  A combination the problem's kernel cannot use (say, two stages that do
+ * not fit the LDS) makes the call fall back - to the other 3x3 kernel or to the generic kernel,
+ * correct but possibly slow - so time before you fix; tvg_conv2d_get_knobs tells what a call
+ * would really use now (0 where a knob does not apply to the kernel that runs).
+ */
+typedef struct {
+    int32_t mt, nt, stages, split_k, lds_pitch, row_loads;
+} tvg_conv_knobs;
+tvg_status tvg_conv2d_set_knobs(const tvg_conv_desc *desc, const tvg_conv_knobs *knobs);
+tvg_status tvg_conv2d_get_knobs(const tvg_conv_desc *desc, tvg_conv_knobs *knobs);
+
+/*
+ * Measurement probes (not operators): what the GPU sustains, to be timed by the caller beside
+ * the operators in the same run, so that a fraction of the data-sheet peak can be read next to a
+ * fraction of what is achievable (the paper's Section 6 evaluates against measured baselines on
+ * the same device; these are the device's own ceilings).
+ * tvg_probe_copy: dst[0..bytes) = src[0..bytes) with 16-byte accesses; src, dst device pointers,
+ *   16-byte aligned, bytes a positive multiple of 16, the ranges disjoint.  Algorithmic traffic:
+ *   2 * bytes.
+ * tvg_probe_mfma: `workgroups` workgroups of four waves each issue iters * 4 matrix instruction
+ *   groups on register operands (TVG_BF16: v_mfma_f32_32x32x16_bf16; TVG_F32: four
+ *   v_mfma_f32_32x32x2_f32); out is a device buffer of workgroups * 256 floats (written so that the
+ *   loop is live), *flops (host) receives the floating-point operations the launch performs.
+ */
+tvg_status tvg_probe_copy(const void *src, void *dst, size_t bytes, void *hip_stream);
+tvg_status tvg_probe_mfma(int32_t dtype, int32_t iters, int32_t workgroups, float *out,
+                          double *flops, void *hip_stream);
 
 /* Static, NUL-terminated description of a status code (never NULL). */
 const char *tvg_status_string(tvg_status status);

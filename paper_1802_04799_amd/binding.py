@@ -37,6 +37,14 @@ class ConvDesc(ctypes.Structure):
         return (self.w + 2 * self.pad_w - self.s) // self.stride_w + 1
 
 
+class ConvKnobs(ctypes.Structure):
+    """Mirror of tvg_conv_knobs (0 = the library's rule)."""
+    _fields_ = [(n, ctypes.c_int32) for n in ("mt", "nt", "stages", "split_k", "lds_pitch", "row_loads")]
+
+    def as_tuple(self):
+        return tuple(int(getattr(self, n)) for n, _ in self._fields_)
+
+
 class TensorLife(ctypes.Structure):
     """Mirror of tvg_tensor_life."""
     _fields_ = [("bytes", ctypes.c_uint64), ("first_step", ctypes.c_int32),
@@ -80,6 +88,11 @@ def load() -> ctypes.CDLL:
     lib.tvg_conv2d_fused_static.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.tvg_static_scratch_bytes.restype = sz
     lib.tvg_static_scratch_bytes.argtypes = []
+    lib.tvg_probe_copy.restype = ctypes.c_int
+    lib.tvg_probe_copy.argtypes = [vp, vp, sz, vp]
+    lib.tvg_probe_mfma.restype = ctypes.c_int
+    lib.tvg_probe_mfma.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp,
+                                   ctypes.POINTER(ctypes.c_double), vp]
     lib.tvg_dwpw_workspace_size.restype = ctypes.c_int
     lib.tvg_dwpw_workspace_size.argtypes = [dp, ctypes.c_int32, ctypes.POINTER(sz)]
     lib.tvg_dwpw_one_kernel.restype = ctypes.c_int
@@ -96,6 +109,10 @@ def load() -> ctypes.CDLL:
     lib.tvg_version.restype = ctypes.c_int
     lib.tvg_conv2d_set_tile.restype = ctypes.c_int
     lib.tvg_conv2d_set_tile.argtypes = [dp, ctypes.c_int32, ctypes.c_int32]
+    lib.tvg_conv2d_set_knobs.restype = ctypes.c_int
+    lib.tvg_conv2d_set_knobs.argtypes = [dp, ctypes.POINTER(ConvKnobs)]
+    lib.tvg_conv2d_get_knobs.restype = ctypes.c_int
+    lib.tvg_conv2d_get_knobs.argtypes = [dp, ctypes.POINTER(ConvKnobs)]
     i32p = ctypes.POINTER(ctypes.c_int32)
     lib.tvg_conv2d_get_plan.restype = ctypes.c_int
     lib.tvg_conv2d_get_plan.argtypes = [dp, i32p, i32p, i32p]
@@ -117,6 +134,25 @@ KERNEL_NAMES = {0: "generic", 1: "3x3", 2: "3x3-pipelined", 3: "stem", 4: "1x1"}
 def tvg_conv2d_set_tile(desc: "ConvDesc", mt: int, nt: int) -> int:
     """Fix (or, with 0, 0, forget) the tile shape this exact problem is planned with."""
     return int(load().tvg_conv2d_set_tile(ctypes.byref(desc), int(mt), int(nt)))
+
+
+def tvg_conv2d_set_knobs(desc: "ConvDesc", knobs=None) -> int:
+    """Fix the schedule knobs of this exact problem: a ConvKnobs, a 6-tuple
+    (mt, nt, stages, split_k, lds_pitch, row_loads), or None to forget the problem."""
+    if knobs is None:
+        return int(load().tvg_conv2d_set_knobs(ctypes.byref(desc), None))
+    if not isinstance(knobs, ConvKnobs):
+        knobs = ConvKnobs(*[int(v) for v in knobs])
+    return int(load().tvg_conv2d_set_knobs(ctypes.byref(desc), ctypes.byref(knobs)))
+
+
+def tvg_conv2d_get_knobs(desc: "ConvDesc"):
+    """The knobs a call with this descriptor would really use now, as a 6-tuple."""
+    k = ConvKnobs()
+    st = load().tvg_conv2d_get_knobs(ctypes.byref(desc), ctypes.byref(k))
+    if st != TVG_OK:
+        raise TvgError(st, "tvg_conv2d_get_knobs")
+    return k.as_tuple()
 
 
 def tvg_conv2d_get_plan(desc: "ConvDesc"):
@@ -181,6 +217,18 @@ def tvg_conv2d_fused_static(desc, x, w, scale, shift, bias, residual, y, stream=
 
 def tvg_static_scratch_bytes() -> int:
     return int(load().tvg_static_scratch_bytes())
+
+
+def tvg_probe_copy(src, dst, nbytes, stream=None) -> int:
+    return int(load().tvg_probe_copy(_addr(src), _addr(dst), int(nbytes), _stream(stream)))
+
+
+def tvg_probe_mfma(dtype, iters, workgroups, out, stream=None):
+    """Launches the matrix-instruction probe; returns (status, flops of the launch)."""
+    fl = ctypes.c_double(0.0)
+    st = load().tvg_probe_mfma(int(dtype), int(iters), int(workgroups), _addr(out), ctypes.byref(fl),
+                               _stream(stream))
+    return int(st), float(fl.value)
 
 
 def tvg_dwconv2d_fused(desc, x, w, scale, shift, bias, residual, y, workspace=None,

@@ -80,7 +80,7 @@ tvg_status make_problem(const tvg_conv_desc *d, bool depthwise, ConvProblem *out
 // mutex - planning reads it on every call, a tuner writes it a few times per shape.
 struct TileEntry {
     int key[12];
-    int mt, nt;
+    tvg::Knobs knobs;
 };
 std::mutex g_tile_mutex;
 std::vector<TileEntry> g_tiles;
@@ -168,35 +168,24 @@ tvg_status static_scratch(void **out)
 
 namespace tvg {
 
-bool forced_tile(const ConvProblem &p, int *mt, int *nt)
+Knobs forced_knobs(const ConvProblem &p)
 {
     int key[12];
     tile_key(p, key);
-    {
-        std::lock_guard<std::mutex> lock(g_tile_mutex);
-        for (const TileEntry &e : g_tiles)
-            if (memcmp(e.key, key, sizeof(key)) == 0) {
-                *mt = e.mt;
-                *nt = e.nt;
-                return true;
-            }
-    }
-    return false;
+    std::lock_guard<std::mutex> lock(g_tile_mutex);
+    for (const TileEntry &e : g_tiles)
+        if (memcmp(e.key, key, sizeof(key)) == 0) return e.knobs;
+    return Knobs{0, 0, 0, 0, 0, 0};
 }
 
 }  // namespace tvg
 
 extern "C" {
 
-tvg_status tvg_conv2d_set_tile(const tvg_conv_desc *desc, int32_t mt, int32_t nt)
+// Stores, replaces or (knobs all zero) forgets the problem's entry in the knob table.
+static tvg_status store_knobs(const ConvProblem &p, const tvg::Knobs &k)
 {
-    ConvProblem p;
-    tvg_status st = make_problem(desc, false, &p);
-    if (st != TVG_OK) return st;
-    const bool clear = mt == 0 && nt == 0;
-    const bool known = (mt == 64 && (nt == 256 || nt == 128 || nt == 64)) ||
-                       (mt == 128 && (nt == 128 || nt == 64));
-    if (!clear && !known) return TVG_ERR_UNSUPPORTED;
+    const bool clear = !k.mt && !k.nt && !k.stages && !k.split_k && !k.lds_pitch && !k.row_loads;
     int key[12];
     tile_key(p, key);
     forget_dispatch();                     // plans made under the old table are stale
@@ -204,16 +193,80 @@ tvg_status tvg_conv2d_set_tile(const tvg_conv_desc *desc, int32_t mt, int32_t nt
     for (size_t i = 0; i < g_tiles.size(); ++i)
         if (memcmp(g_tiles[i].key, key, sizeof(key)) == 0) {
             if (clear) g_tiles.erase(g_tiles.begin() + (long)i);
-            else { g_tiles[i].mt = mt; g_tiles[i].nt = nt; }
+            else g_tiles[i].knobs = k;
             return TVG_OK;
         }
     if (clear) return TVG_OK;
     if (g_tiles.size() >= kMaxTileEntries) return TVG_ERR_UNSUPPORTED;
     TileEntry e;
     memcpy(e.key, key, sizeof(key));
-    e.mt = mt;
-    e.nt = nt;
+    e.knobs = k;
     g_tiles.push_back(e);
+    return TVG_OK;
+}
+
+static bool known_tile(int mt, int nt)
+{
+    return (mt == 64 && (nt == 256 || nt == 128 || nt == 64)) || (mt == 128 && (nt == 128 || nt == 64));
+}
+
+tvg_status tvg_conv2d_set_tile(const tvg_conv_desc *desc, int32_t mt, int32_t nt)
+{
+    ConvProblem p;
+    tvg_status st = make_problem(desc, false, &p);
+    if (st != TVG_OK) return st;
+    if (!(mt == 0 && nt == 0) && !known_tile(mt, nt)) return TVG_ERR_UNSUPPORTED;
+    tvg::Knobs k = tvg::forced_knobs(p);      // the other knobs stay as they are
+    k.mt = mt;
+    k.nt = nt;
+    return store_knobs(p, k);
+}
+
+tvg_status tvg_conv2d_set_knobs(const tvg_conv_desc *desc, const tvg_conv_knobs *knobs)
+{
+    ConvProblem p;
+    tvg_status st = make_problem(desc, false, &p);
+    if (st != TVG_OK) return st;
+    if (!knobs) return store_knobs(p, tvg::Knobs{0, 0, 0, 0, 0, 0});
+    if (!((knobs->mt == 0 && knobs->nt == 0) || known_tile(knobs->mt, knobs->nt))) return TVG_ERR_UNSUPPORTED;
+    if (knobs->stages < 0 || knobs->stages > 2 || knobs->split_k < 0 || knobs->split_k > 32 ||
+        knobs->lds_pitch < 0 || knobs->lds_pitch > 2 || knobs->row_loads < 0 || knobs->row_loads > 2)
+        return TVG_ERR_UNSUPPORTED;
+    return store_knobs(p, tvg::Knobs{knobs->mt, knobs->nt, knobs->stages, knobs->split_k,
+                                     knobs->lds_pitch, knobs->row_loads});
+}
+
+tvg_status tvg_conv2d_get_knobs(const tvg_conv_desc *desc, tvg_conv_knobs *knobs)
+{
+    if (!knobs) return TVG_ERR_NULL;
+    ConvProblem p;
+    tvg_status st = make_problem(desc, false, &p);
+    if (st != TVG_OK) return st;
+    const Dispatch d = dispatch_for(p);
+    tvg_conv_knobs k = {0, 0, 0, 0, 0, 0};
+    if (d.patch_shape) {
+        k.mt = d.patch.mt;
+        k.nt = d.patch.nt;
+        k.stages = d.patch.dbuf ? 2 : 1;
+        if (d.patch.dbuf) {
+            k.split_k = d.patch.kg;
+            if (p.sh == 1) k.lds_pitch = d.patch.pws == p.W + 2 ? 1 : 2;
+            if (p.W % 2 != 0 && p.W <= 7 && p.sh == 1) k.row_loads = d.patch.px == 8 ? 2 : 1;
+        }
+    } else if (d.stem_shape) {
+        k.mt = 64;
+        k.nt = 256;
+        k.stages = 1;
+    } else if (d.pw_shape) {
+        k.mt = d.pw.mt;
+        k.nt = d.pw.nt;
+    } else {
+        k.mt = d.generic.mt;
+        k.nt = d.generic.nt;
+        k.stages = 2;
+        k.split_k = d.generic.splits;
+    }
+    *knobs = k;
     return TVG_OK;
 }
 

@@ -239,7 +239,11 @@ bool plan_conv1x1(const ConvProblem &p, Pw1x1Plan *plan)
     const auto &cands = (p.OC <= 64 && p.IC < 64) ? shallow : deep;
     bool found = false, fills_best = false;
     int force_mt = 0, force_nt = 0;       // tuning override, as for the 3x3 kernels
-    if (!forced_tile(p, &force_mt, &force_nt)) force_mt = force_nt = 0;
+    {
+        const Knobs knobs = forced_knobs(p);
+        force_mt = knobs.mt;
+        force_nt = knobs.nt;
+    }
     for (const auto &c : cands) {
         const int mt = c[0], nt = c[1];
         if (mt == 128 && p.OC <= 64) continue;

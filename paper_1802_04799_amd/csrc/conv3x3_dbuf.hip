@@ -90,21 +90,47 @@ constexpr int waitcnt_imm(int vm, int lgkm)
 // 64 x NT with NT = (4 / WM) * NJ * 32.  (Tiles of 448 and 832 pixels - one workgroup per CU with
 // 112 or 208 accumulator registers per lane - were measured: slower, a single wave per SIMD
 // issues an MFMA plus its LDS operand read in 27 ns against 16 ns for two waves.)
-template <int WM, int NJ, int STRIDE, int PT, int PX>
-__global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
+//
+// KG = 2: two groups of four waves share one tile and split the reduction - group g takes the
+// chunks 2j + g, with LDS stages of its own - and add their accumulators through LDS at the
+// end, each group finishing half of the tile.  For grids of at most one workgroup per CU: a lone
+// group of four waves is bound by the latency of its own chain (barrier, operand reads, 36
+// matrix instructions: about 1 us per chunk on C9, the matrix pipe busy for 0.58 of it), and
+// no second workgroup is there to fill the gaps; the second group is.
+//
+// UNAL (with PX = 8, stride 1, rows of at most 7 pixels): rows that start at any 2-byte address.
+// A row of an odd-sized map (7x7: 98-byte planes) begins 4-byte aligned or 2 bytes past that,
+// alternating with the row and, when the plane is odd, with the channel.  Element-wise 2-byte
+// loads (16 per thread and chunk on C12 against 18 matrix instructions per wave) kept the CU's
+// address unit busier than its matrix pipes.  Instead a task is one row of one PAIR of channels:
+// it fetches, per channel, the 16 bytes from the aligned address at or just below the row's
+// start - the whole row in one load - and, when it comes to transposing, first moves each
+// channel's four registers down by 16 bits where the row started in the upper half (one funnel
+// shift per register, the amount a per-lane value), then writes pixel k's two channels as one
+// 4-byte piece of the pixel's 16-byte word.  (A task of all eight channels, 16-byte stores, was
+// measured first: the few threads that own a row - 60 of 256 on C12 - became the critical path,
+// 31.4 us against 25.6; pairs spread the same rows over 240 threads.)  Pixels past the end of
+// the row (the eighth element and beyond) go to the dump area.
+template <int WM, int NJ, int STRIDE, int PT, int PX, int KG = 1, bool UNAL = false>
+__global__ __launch_bounds__(256 * KG, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
 {
+    static_assert(!UNAL || (PX == 8 && STRIDE == 1), "unaligned rows: whole rows of at most 7 pixels");
     constexpr int MT = kMT;
     constexpr int WN = 4 / WM;
     constexpr int WTM = MT / WM, WTN = NJ * 32, NT = WN * WTN;
     constexpr int MI = WTM / 32;
     constexpr int PW32 = PX >= 2 ? PX / 2 : 1;        // registers per patch load
     constexpr int kWLoads = 5;                        // a weight task's 72 bytes: 4 x 16 + 8
-    constexpr int kLoads = kWLoads + 8 * PT;          // vector memory loads per thread and chunk
+    constexpr int NCH = UNAL ? 2 : 8;                 // channels per patch task
+    constexpr int kLoads = kWLoads + NCH * PT;        // vector memory loads per thread and chunk
     constexpr int kP0 = 9 + kWLoads;                  // first patch item
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // tid, wave: position within the thread's group of four waves (task lists, tile position)
+    const int tid = threadIdx.x & 255, lane = tid & 63, wave = tid >> 6;
+    const int group = KG == 2 ? __builtin_amdgcn_readfirstlane(threadIdx.x >> 8) : 0;
+    const int gbase = KG == 2 ? group * 2 * a.stage_bytes : 0;      // the group's two stages
     const int wm = wave % WM, wn = wave / WM;
     const int lrow = lane & 31, lhalf = lane >> 5;
 
@@ -132,10 +158,14 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
         2u * (uint32_t)((((m0 + w_ocl) < a.OC ? m0 + w_ocl : 0) * a.IC + w_quad * 4) * 9);
     // LDS byte addresses are kept per stage (index 0 / 1), so that the loop adds nothing to them
     int wbase[2];           // where tap 0 of the weight task goes
-    wbase[0] = (w_quad >> 1) * kAPlane + w_ocl * 16 + (w_quad & 1) * 8;
+    wbase[0] = gbase + (w_quad >> 1) * kAPlane + w_ocl * 16 + (w_quad & 1) * 8;
     wbase[1] = wbase[0] + stage_bytes;
 
     uint32_t goff[PT];      // byte offset of a patch task's first channel within a chunk of x
+    // UNAL: the same for the odd channels of the octet (one channel further, re-aligned), the
+    // funnel shifts (0 or 16 bits) of the even and of the odd channels, and the task's dump words
+    uint32_t goffo[UNAL ? PT : 1];
+    int shift_e[UNAL ? PT : 1], shift_o[UNAL ? PT : 1], pwdump[2][UNAL ? PT : 1];
     int pwbase[2][PT];      // where the first pixel of a patch task goes
     int pwbase2[2][PT];     // stride 2: its second pixel (the even-column half of the row)
     // PX = 4: where pixels 2 and 3 go - behind the first pair, or, for the short last task of a
@@ -143,7 +173,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
     int pwtail[2][PX == 4 ? PT : 1], pwtail2[2][PX == 4 && STRIDE == 2 ? PT : 1];
     // two register sets: while one is transposed into LDS (chunk c+1) the other is still in
     // flight (chunk c+2), so a load has two chunks of MFMA time to arrive
-    uint32_t praw[2][PT][8][PW32];
+    uint32_t praw[2][PT][NCH][PW32];
     uint32_t wraw[2][18];
 
     const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
@@ -160,7 +190,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
     //   then per patch task: PX transposes (one pixel each), 8 loads (one channel each)
     // `set` = which register set the item works on = which stage a transpose writes to;
     // cbase = byte offset of the chunk to load within an image of x.
-    constexpr int kItems = kP0 + PT * (PX + 8);
+    constexpr int kItems = kP0 + PT * (PX + NCH);
     auto work_item = [&](int it, int set, bool do_pack, bool do_load, int c, int cbase) __attribute__((always_inline)) {
         if (it < 9) {
             if (!do_pack) return;
@@ -178,20 +208,39 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
             const int i = it - 9;
             if (i < 4) {
                 const uint4v t4 = __builtin_bit_cast(
-                    uint4v, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, woff + i * 16, c * kChunk * 9 * 2, 0));
+                    uint4v, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, woff + i * 16, (c * KG + group) * kChunk * 9 * 2, 0));
 #pragma unroll
                 for (int d = 0; d < 4; ++d) wraw[set][4 * i + d] = t4[d];
             } else {
                 const uint2v t2 = __builtin_bit_cast(
-                    uint2v, __builtin_amdgcn_raw_buffer_load_b64(wrsrc, woff + 64, c * kChunk * 9 * 2, 0));
+                    uint2v, __builtin_amdgcn_raw_buffer_load_b64(wrsrc, woff + 64, (c * KG + group) * kChunk * 9 * 2, 0));
                 wraw[set][16] = t2[0];
                 wraw[set][17] = t2[1];
             }
         } else {
-            const int j = (it - kP0) / (PX + 8), r = (it - kP0) % (PX + 8);
+            const int j = (it - kP0) / (PX + NCH), r = (it - kP0) % (PX + NCH);
             if (r < PX) {
                 if (!do_pack) return;
                 const int k = r;
+                if constexpr (UNAL) {
+                    if (k == 0) {       // bring both channels' rows down to bit 0 of their registers
+#pragma unroll
+                        for (int q = 0; q < 2; ++q) {
+                            const int sh = q ? shift_o[j] : shift_e[j];
+#pragma unroll
+                            for (int d = 0; d < 3; ++d)
+                                praw[set][j][q][d] = __builtin_amdgcn_alignbit(praw[set][j][q][d + 1],
+                                                                               praw[set][j][q][d], sh);
+                            praw[set][j][q][3] >>= sh;
+                        }
+                    }
+                    const uint32_t o2 = pack_halves(praw[set][j][0][k >> 1], k & 1,
+                                                    praw[set][j][1][k >> 1], k & 1);
+                    // (uniform test: the pixels past the row's end)
+                    *reinterpret_cast<uint32_t *>(smem + (k < W ? pwbase[set][j] + k * 16
+                                                                : pwdump[set][j] + k * 256)) = o2;
+                    return;
+                }
                 uint32_t o[4];
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
@@ -210,7 +259,13 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
                 if (!do_load) return;
                 const int q = r - PX;
                 const int soff = cbase + q * hw2;
-                if constexpr (PX == 8) {
+                if constexpr (UNAL) {
+                    // the odd channel: its channel stride is part of its (re-aligned) lane offset
+                    const uint4v t4 = __builtin_bit_cast(
+                        uint4v, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, q ? goffo[j] : goff[j], cbase, 0));
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) praw[set][j][q][d] = t4[d];
+                } else if constexpr (PX == 8) {
                     const uint4v t4 = __builtin_bit_cast(
                         uint4v, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, goff[j], soff, 0));
 #pragma unroll
@@ -229,7 +284,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
         }
     };
     auto all_items = [&](int first, int last, int set, bool do_pack, bool do_load, int c) __attribute__((always_inline)) {
-        const int cbase = c * kChunk * hw2;
+        const int cbase = (c * KG + group) * kChunk * hw2;
 #pragma unroll
         for (int it = first; it < last; ++it) work_item(it, set, do_pack, do_load, c, cbase);
     };
@@ -239,7 +294,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
     all_items(9, kP0, 0, false, true, 0);
     // likewise the tile's per-channel multiplier and offset, needed only by the fused tail
     float ss_scale = 0.0f, ss_shift = 0.0f, ss_bias = 0.0f;
-    if (tid < MT && m0 + tid < a.OC) {
+    if (group == 0 && tid < MT && m0 + tid < a.OC) {
         ss_scale = a.scale[m0 + tid];
         ss_shift = a.shift[m0 + tid];
         if (a.bias) ss_bias = a.bias[m0 + tid];
@@ -266,7 +321,9 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
         const int pair_step = 16 - PWH * 16;
 #pragma unroll
         for (int j = 0; j < PT; ++j) {
-            const int t = tid + j * 256;
+            // (UNAL: four tasks per row and octet, one per pair of channels)
+            const int pair = UNAL ? (tid & 3) : 0;
+            const int t = UNAL ? (tid + j * 256) >> 2 : tid + j * 256;
             const int octet = t >= per_octet;
             const int rem = t - (octet ? per_octet : 0);
             int iw, vi;
@@ -280,15 +337,32 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
             // tasks with nothing to fetch (padding rows, past the tile) load element 0 and
             // write it to a dump area behind the planes, so that no store needs a predicate
             goff[j] = live ? 2u * (uint32_t)((n * a.IC + octet * 8) * HW + ih * W + iw) : 0u;
-            pwbase[0][j] = live ? 2 * kAPlane + octet * a.pplane + (vrow * PWS + word) * 16 + (n - na) * a.xp16
-                                : 2 * kAPlane + 2 * a.pplane + (tid & 15) * (PX > 1 ? PX * 16 : 32) +
-                                      (STRIDE == 2 && PX > 1 ? 16 - pair_step : 0);
+            if constexpr (UNAL) {
+                // element offsets of the row in the pair's even and odd channel; each load
+                // starts at the 4-byte boundary at or below its row
+                const uint32_t ee = live ? (uint32_t)((n * a.IC + octet * 8 + pair * 2) * HW + ih * W) : 0u;
+                const uint32_t eo = ee + (uint32_t)HW;
+                shift_e[j] = (int)(ee & 1u) * 16;
+                shift_o[j] = (int)(eo & 1u) * 16;
+                goff[j] = 2u * (ee & ~1u);
+                goffo[j] = 2u * (eo & ~1u);
+            }
+            pwbase[0][j] = gbase +
+                           (live ? 2 * kAPlane + octet * a.pplane + (vrow * PWS + word) * 16 + (n - na) * a.xp16
+                                 : 2 * kAPlane + 2 * a.pplane + (tid & 15) * (PX > 1 ? PX * 16 : 32) +
+                                       (STRIDE == 2 && PX > 1 ? 16 - pair_step : 0));
+            if constexpr (UNAL) pwbase[0][j] += pair * 4;     // the pair's 4 bytes of a pixel's word
             pwbase[1][j] = pwbase[0][j] + stage_bytes;
+            if constexpr (UNAL) {
+                // (64 lanes write 256 consecutive bytes: conflict-free)
+                pwdump[0][j] = gbase + 2 * kAPlane + 2 * a.pplane + (tid & 63) * 4;
+                pwdump[1][j] = pwdump[0][j] + stage_bytes;
+            }
             pwbase2[0][j] = pwbase[0][j] + pair_step;
             pwbase2[1][j] = pwbase[1][j] + pair_step;
             if constexpr (PX == 4) {
                 const bool whole = !live || iw + 4 <= W;
-                const int dump = 2 * kAPlane + 2 * a.pplane + (tid & 15) * 64;
+                const int dump = gbase + 2 * kAPlane + 2 * a.pplane + (tid & 15) * 64;
                 pwtail[0][j] = whole ? pwbase[0][j] + (STRIDE == 2 ? 16 : 32) : dump + 32;
                 pwtail[1][j] = pwtail[0][j] + stage_bytes;
                 if constexpr (STRIDE == 2) {
@@ -322,11 +396,11 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
         int rem, ow;
         const int n = fast_div(p, OHW, a.inv_ohw, &rem);
         const int oh = fast_div(rem, a.OW, a.inv_ow, &ow);
-        bpix[j] = 2 * kAPlane + lhalf * a.pplane +
+        bpix[j] = gbase + 2 * kAPlane + lhalf * a.pplane +
                   (p < a.npix ? ((n * VH + oh * STRIDE - vr_lo) * PWS + ow) * 16 + (n - na) * a.xp16 : 0);
     }
     int abase[2];
-    abase[0] = lhalf * kAPlane + (wm * WTM + lrow) * 16;
+    abase[0] = gbase + lhalf * kAPlane + (wm * WTM + lrow) * 16;
     abase[1] = abase[0] + stage_bytes;
     second_chunk_loads(NJ < 4 ? NJ : 4, NJ < 4 ? NJ + 2 : 6);
 
@@ -341,17 +415,17 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
     second_chunk_loads(NJ < 4 ? NJ + 1 : 5, NJ < 4 ? NJ + 2 : 6);
 
-    const int nchunks = a.IC / kChunk;
+    const int nchunks = a.IC / (kChunk * KG);     // chunks of this group
     // zero the patch planes of both stages once (padding rows and columns are never written
     // again) and stage the tile's (scale, offset) pairs
     {
         const int words = 2 * a.pplane / 16;
         for (int s = 0; s < 2; ++s) {
-            uint4v *pz = reinterpret_cast<uint4v *>(smem + s * stage_bytes + 2 * kAPlane);
+            uint4v *pz = reinterpret_cast<uint4v *>(smem + gbase + s * stage_bytes + 2 * kAPlane);
             for (int i = tid; i < words; i += 256) pz[i] = uint4v{0u, 0u, 0u, 0u};
         }
     }
-    if (tid < MT) {
+    if (group == 0 && tid < MT) {
         // (acc + bias)*scale + shift == acc*scale + (bias*scale + shift)
         ss_lds[2 * tid] = ss_scale;
         ss_lds[2 * tid + 1] = fmaf(ss_bias, ss_scale, ss_shift);
@@ -415,7 +489,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
     auto chunk = [&](auto parc, auto modec, int c) __attribute__((always_inline)) {
         constexpr int par = decltype(parc)::value;
         constexpr int mode = decltype(modec)::value;
-        const int cbase = (c + 3) * kChunk * hw2;
+        const int cbase = ((c + 3) * KG + group) * kChunk * hw2;
         // (hidden from loop-invariant code motion, which would spend a register per
         // combination of stage, filter row and pixel block on precomputed addresses)
         int so = par * stage_bytes;
@@ -461,17 +535,59 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
 
     // ---- fused tail: per-wave staging in LDS, vector stores --------------------------------
     __syncthreads();                       // every wave is done reading the operand tiles
-    constexpr int BT = MI * NJ < 4 ? MI * NJ : 4;                 // tiles staged at a time
-    unsigned char *stage = smem + wave * (BT * kStageBytes);      // <= 40 KB < two stages
     const TailArgs tail{a.scale, a.shift, a.bias, a.residual, a.y, a.OC, OHW, a.npix, a.relu};
-    store_acc_tiles_batched<MI, NJ, BT>(acc, stage, lane, m0 + wm * WTM, n0 + wn * WTN, tail,
-                                        a.vmode, ss_lds, wm * WTM);
+    if constexpr (KG == 1) {
+        constexpr int BT = MI * NJ < 4 ? MI * NJ : 4;                 // tiles staged at a time
+        unsigned char *stage = smem + wave * (BT * kStageBytes);      // <= 40 KB < two stages
+        store_acc_tiles_batched<MI, NJ, BT>(acc, stage, lane, m0 + wm * WTM, n0 + wn * WTN, tail,
+                                            a.vmode, ss_lds, wm * WTM);
+    } else {
+        // The two groups hold partial sums of the same tile.  Group g finishes pixel block g of
+        // every wave tile: it hands its partial sums of the other block to its partner wave
+        // through LDS (16-byte words, lane-contiguous: conflict-free) and adds what it receives.
+        static_assert(NJ == 2, "the split-reduction variant halves a wave tile of two pixel blocks");
+        constexpr int kXWave = MI * 16 * 64 * 4;                  // bytes a wave hands over
+        float4v *xout = reinterpret_cast<float4v *>(smem + (wave * 2 + group) * kXWave);
+        const float4v *xin = reinterpret_cast<const float4v *>(smem + (wave * 2 + (group ^ 1)) * kXWave);
+        auto hand_over = [&](auto jc) __attribute__((always_inline)) {
+            constexpr int js = decltype(jc)::value;               // the block this group gives away
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    xout[(i * 4 + q) * 64 + lane] = float4v{acc[i][js][4 * q], acc[i][js][4 * q + 1],
+                                                            acc[i][js][4 * q + 2], acc[i][js][4 * q + 3]};
+        };
+        if (group == 0) hand_over(std::integral_constant<int, 1>{});
+        else hand_over(std::integral_constant<int, 0>{});
+        __syncthreads();
+        float16v mine[MI][1];
+        auto take_in = [&](auto jc) __attribute__((always_inline)) {
+            constexpr int jk = decltype(jc)::value;               // the block this group keeps
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4v o = xin[(i * 4 + q) * 64 + lane];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) mine[i][0][4 * q + e] = acc[i][jk][4 * q + e] + o[e];
+                }
+        };
+        if (group == 0) take_in(std::integral_constant<int, 0>{});
+        else take_in(std::integral_constant<int, 1>{});
+        // the staging areas of the tail lie behind the exchange area (a wave may still be
+        // reading its partner's sums while another has started to store)
+        constexpr int BT = MI;
+        unsigned char *stage = smem + 8 * kXWave + (wave * 2 + group) * (BT * kStageBytes);
+        store_acc_tiles_batched<MI, 1, BT>(mine, stage, lane, m0 + wm * WTM,
+                                           n0 + wn * WTN + group * 32, tail, a.vmode, ss_lds, wm * WTM);
+    }
 }
 
-template <int WM, int NJ, int STRIDE, int PT, int PX>
+template <int WM, int NJ, int STRIDE, int PT, int PX, int KG = 1, bool UNAL = false>
 tvg_status launch_instance(const DbufArgs &a, size_t lds, hipStream_t stream)
 {
-    auto kernel = conv3x3_dbuf_kernel<WM, NJ, STRIDE, PT, PX>;
+    auto kernel = conv3x3_dbuf_kernel<WM, NJ, STRIDE, PT, PX, KG, UNAL>;
     static bool configured = false;      // opt in to > 64 KB of dynamic LDS once per instance
     if (!configured) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
@@ -479,13 +595,40 @@ tvg_status launch_instance(const DbufArgs &a, size_t lds, hipStream_t stream)
             return TVG_ERR_LAUNCH;
         configured = true;
     }
-    hipLaunchKernelGGL(kernel, dim3((unsigned)(a.mtiles * a.ntiles)), dim3(256), lds, stream, a);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(a.mtiles * a.ntiles)), dim3(256 * KG), lds, stream, a);
     return hipGetLastError() == hipSuccess ? TVG_OK : TVG_ERR_LAUNCH;
 }
 
+// The split-reduction variant (two groups of four waves): stride 1, wave tiles of two pixel blocks.
 template <int WM, int NJ>
-tvg_status launch_pt(const DbufArgs &a, size_t lds, int stride, int pt, int px, hipStream_t stream)
+tvg_status launch_pt_kg2(const DbufArgs &a, size_t lds, int pt, int px, hipStream_t stream)
 {
+    if constexpr (NJ == 2) {
+        if (px == 8 && a.W < 8) {
+            if (pt <= 1) return launch_instance<WM, NJ, 1, 1, 8, 2, true>(a, lds, stream);
+            return launch_instance<WM, NJ, 1, 2, 8, 2, true>(a, lds, stream);
+        }
+        switch (px) {
+        case 8: return launch_instance<WM, NJ, 1, 1, 8, 2>(a, lds, stream);
+        case 4:
+            if (pt <= 1) return launch_instance<WM, NJ, 1, 1, 4, 2>(a, lds, stream);
+            return launch_instance<WM, NJ, 1, 2, 4, 2>(a, lds, stream);
+        case 2:
+            if (pt <= 2) return launch_instance<WM, NJ, 1, 2, 2, 2>(a, lds, stream);
+            return launch_instance<WM, NJ, 1, 4, 2, 2>(a, lds, stream);
+        default:
+            if (pt <= 2) return launch_instance<WM, NJ, 1, 2, 1, 2>(a, lds, stream);
+            return launch_instance<WM, NJ, 1, 4, 1, 2>(a, lds, stream);
+        }
+    }
+    return TVG_ERR_UNSUPPORTED;
+}
+
+template <int WM, int NJ>
+tvg_status launch_pt(const DbufArgs &a, size_t lds, int stride, int pt, int px, int kg,
+                     hipStream_t stream)
+{
+    if (kg == 2) return stride == 1 ? launch_pt_kg2<WM, NJ>(a, lds, pt, px, stream) : TVG_ERR_UNSUPPORTED;
     if (stride == 2) {
         // instances exist for the 128- and 256-pixel tiles and even rows (see the plan)
         if constexpr (NJ == 2) {
@@ -500,6 +643,10 @@ tvg_status launch_pt(const DbufArgs &a, size_t lds, int stride, int pt, int px, 
             }
         }
         return TVG_ERR_UNSUPPORTED;
+    }
+    if (px == 8 && a.W < 8) {
+        if (pt <= 1) return launch_instance<WM, NJ, 1, 1, 8, 1, true>(a, lds, stream);
+        return launch_instance<WM, NJ, 1, 2, 8, 1, true>(a, lds, stream);
     }
     switch (px) {
     case 8: return launch_instance<WM, NJ, 1, 1, 8>(a, lds, stream);
@@ -524,8 +671,9 @@ bool plan_conv3x3_dbuf(const ConvProblem &p, Patch3x3Plan *plan)
     if (plan->mt != kMT) return false;
     if (p.IC % (2 * kChunk) != 0) return false;      // the chunk loop runs in pairs
     // Measured at batch 64: with fewer than eight chunks the deeper pipeline's longer start-up
-    // (three chunks in flight before the first MFMA) costs more than the loop gains.
-    if (p.IC < 8 * kChunk || plan->nt > 256) return false;
+    // (three chunks in flight before the first MFMA) costs more than the loop gains.  (A caller
+    // that asks for this kernel by name gets it from four chunks on.)
+    if (p.IC < (plan->want_stages == 2 ? 4 : 8) * kChunk || plan->nt > 256) return false;
     // Stride 2: a patch is four times the output tile, so its two stages fill the LDS of a CU
     // and the kernel pays only where one workgroup per CU covers the problem (instances: the
     // 128- and 256-pixel tiles, even rows).
@@ -544,24 +692,64 @@ bool plan_conv3x3_dbuf(const ConvProblem &p, Patch3x3Plan *plan)
     int pplane = (plan->rows * pws + images * xp) * 16;
     // the widest load that divides a row (and an image plane: every row then starts aligned)
     // (rows of 4m + 2 pixels take 8-byte loads too, 4-byte aligned, the last one of a row short)
-    const int px = p.W % 8 == 0 ? 8 : p.W % 4 == 0 ? 4 : p.W % 2 != 0 ? 1 : p.W >= 6 ? 4 : 2;
-    const int pt = (2 * plan->rows * ((p.W + px - 1) / px) + 255) / 256;
-    if (pt * (px >= 2 ? px / 2 : 1) > 4) return false;       // registers of a task's loads
+    // (odd rows of at most 7 pixels, stride 1, one task per thread: whole rows by one 16-byte load
+    // from the aligned address below the row's start, see the kernel's UNAL)
+    int px = p.W % 8 == 0 ? 8 : p.W % 4 == 0 ? 4 : p.W % 2 != 0 ? 1 : p.W >= 6 ? 4 : 2;
+    // (measured on C12: 27.4 us against 25.6 with element loads - not the default)
+    const bool odd_rows = px == 1;
+    const bool unal = px == 1 && p.W <= 7 && p.sh == 1 && 8 * plan->rows <= 512 && plan->want_rows == 2;
+    if (unal) px = 8;
+    // (unaligned rows: four tasks per row and octet, each two channels)
+    const int pt = unal ? (8 * plan->rows + 255) / 256
+                        : (2 * plan->rows * ((p.W + px - 1) / px) + 255) / 256;
+    if (!unal && pt * (px >= 2 ? px / 2 : 1) > 4) return false;       // registers of a task's loads
     // behind the planes of a stage: 32 bytes for each of 16 lanes, where idle patch tasks store
     // (a stride-2 pair stores its two pixels pwh - 1 words apart)
     const int dump = 16 * (px > 1 ? px * 16 : 32) + (p.sh == 2 ? pwh * 16 : 0);
     int stage = 2 * kAPlane + 2 * pplane + dump;
     size_t lds = 2 * (size_t)stage + (size_t)kMT * 8;
-    if (lds > 80 * 1024 && p.sh == 1) {
+    // (a grid of at most one workgroup per CU may take the whole LDS for the conflict-free pitch:
+    // C9 20.9 -> 19.7 us)
+    const bool lone = plan->tiles <= kComputeUnits;
+    if (p.sh == 1 && (plan->want_pitch == 1 ||
+                      (plan->want_pitch == 0 && lds > (size_t)(lone ? 160 : 80) * 1024))) {
         pws = p.W + 2;
         xp = 0;
         pplane = plan->rows * pws * 16;
         stage = 2 * kAPlane + 2 * pplane + dump;
         lds = 2 * (size_t)stage + (size_t)kMT * 8;
     }
+    // Grids of at most one workgroup per CU (stride 1, wave tiles of two pixel blocks, whole
+    // pairs of chunks for each half of the reduction): two groups of four waves split the
+    // reduction, each with two stages of its own.  Four stages must fit; the conflict-free
+    // pitch is given up for the plain one if that is what it takes.  After the loop the same
+    // memory holds the accumulators the groups exchange and the staging areas of the tail.
+    int kg = 1;
+    // Rule (measured at batch 64, warm): it pays where the rows are odd and fetched element by
+    // element (C12: 28.1 -> 25.6 us), it loses on C9 (20.9 -> 21.4 us, and the four stages cost C9
+    // the conflict-free pitch: 19.7 us with it); tvg_conv2d_set_knobs overrides the rule.
+    const bool kg_rule = plan->want_kg == 2 || (plan->want_kg == 0 && odd_rows);
+    if (p.sh == 1 && plan->tiles <= kComputeUnits && plan->nt >= 128 && p.IC % (4 * kChunk) == 0 &&
+        p.IC >= 8 * kChunk && kg_rule) {
+        const int mi = plan->nt == 256 ? 2 : 1;
+        const size_t after = (size_t)8 * mi * 4096 + (size_t)8 * mi * kStageBytes;
+        auto fits = [&](int st) { return 4 * (size_t)st + (size_t)kMT * 8 <= 160 * 1024; };
+        if (!fits(stage) && plan->want_pitch != 2) {
+            const int pws2 = p.W + 2, pplane2 = plan->rows * pws2 * 16;
+            const int stage2 = 2 * kAPlane + 2 * pplane2 + dump;
+            if (fits(stage2)) { pws = pws2; xp = 0; pplane = pplane2; stage = stage2; }
+        }
+        if (fits(stage)) {
+            kg = 2;
+            lds = 4 * (size_t)stage;
+            if (lds < after) lds = after;
+            lds += (size_t)kMT * 8;
+        }
+    }
     // two workgroups per CU, or one per CU when the whole grid is resident at once anyway
-    if (lds > 80 * 1024 && !(lds <= 160 * 1024 && plan->tiles <= kComputeUnits)) return false;
+    if (kg == 1 && lds > 80 * 1024 && !(lds <= 160 * 1024 && plan->tiles <= kComputeUnits)) return false;
     if (plan->tiles >= (1 << 22)) return false;      // fast_div range of the tile index
+    plan->kg = kg;
     plan->dbuf = 1;
     plan->pt = pt;
     plan->px = px;
@@ -599,9 +787,9 @@ tvg_status launch_conv3x3_dbuf(const ConvProblem &p, const Patch3x3Plan &plan,
     a.inv_vh = 1.0f / (float)(p.H + 2);
     a.inv_wpx = 1.0f / (float)((p.W + plan.px - 1) / plan.px);
     switch (plan.nt) {
-    case 256: return launch_pt<1, 2>(a, plan.lds_bytes, p.sh, plan.pt, plan.px, stream);
-    case 128: return launch_pt<2, 2>(a, plan.lds_bytes, p.sh, plan.pt, plan.px, stream);
-    default: return launch_pt<2, 1>(a, plan.lds_bytes, p.sh, plan.pt, plan.px, stream);
+    case 256: return launch_pt<1, 2>(a, plan.lds_bytes, p.sh, plan.pt, plan.px, plan.kg, stream);
+    case 128: return launch_pt<2, 2>(a, plan.lds_bytes, p.sh, plan.pt, plan.px, plan.kg, stream);
+    default: return launch_pt<2, 1>(a, plan.lds_bytes, p.sh, plan.pt, plan.px, plan.kg, stream);
     }
 }
 

@@ -414,9 +414,9 @@ bool plan_conv3x3_patch(const ConvProblem &p, Patch3x3Plan *plan)
     if (p.sh != p.sw || (p.sh != 1 && p.sh != 2)) return false;
     if (p.IC % kChunk != 0) return false;
     if (p.npix >= (1 << 22) || (long)p.N * (p.H + 2) >= (1 << 22)) return false;   // fast_div range
-    int force_mt = 0, force_nt = 0;
-    if (!forced_tile(p, &force_mt, &force_nt)) force_mt = force_nt = 0;
-    const bool use_dbuf = true;
+    const Knobs knobs = forced_knobs(p);
+    const int force_mt = knobs.mt, force_nt = knobs.nt;
+    const bool use_dbuf = knobs.stages != 1;
     // Tile choice (measured on MI355X at batch 64): take the largest tile that still gives at
     // least 1.5 workgroups per CU, wider in pixels on a tie; if none does, the tile shape with
     // the most workgroups.  A 128-channel tile with more than 4 patch tasks per thread (wide
@@ -449,8 +449,10 @@ bool plan_conv3x3_patch(const ConvProblem &p, Patch3x3Plan *plan)
         const size_t lds = (size_t)9 * mt * kPosBytes + (size_t)rows * (p.W + 2) * kPosBytes +
                            (size_t)mt * 8;      // operands + (scale, offset) pairs
         const long tiles = (long)((p.OC + mt - 1) / mt) * ((p.npix + nt - 1) / nt);
-        Patch3x3Plan cand{mt, nt, pt, px, rows, lds, tiles, 0, 0, 0, 0, 0};
+        Patch3x3Plan cand{mt, nt, pt, px, rows, lds, tiles, 0, 0, 0, 0, 0, 1,
+                          knobs.split_k, knobs.lds_pitch, knobs.row_loads, knobs.stages};
         if (!(use_dbuf && plan_conv3x3_dbuf(p, &cand))) {
+            if (knobs.stages == 2) continue;      // the caller asked for the pipelined kernel
             if (pt > 8 || lds > 80 * 1024) continue;
             if (mt == 128 && pt > 4 && !force_mt) continue;
         }

@@ -329,7 +329,8 @@ ConvPlan plan_conv(const ConvProblem &p, bool allow_split)
 {
     ConvPlan plan;
     const int kt = p.dtype == TVG_BF16 ? 32 : 16;
-    plan.mt = p.OC <= 64 ? 64 : 128;
+    const Knobs knobs = forced_knobs(p);
+    plan.mt = knobs.mt == 64 || knobs.mt == 128 ? knobs.mt : p.OC <= 64 ? 64 : 128;
     plan.nt = kNT;
     const long tiles = (long)((p.OC + plan.mt - 1) / plan.mt) * ((p.npix + kNT - 1) / kNT);
     const int chunks = (p.K + kt - 1) / kt;
@@ -340,6 +341,8 @@ ConvPlan plan_conv(const ConvProblem &p, bool allow_split)
         if (splits > 32) splits = 32;
         if (splits < 1) splits = 1;
     }
+    if (allow_split && knobs.split_k > 0)              // fixed by the caller, at most one per chunk
+        splits = knobs.split_k < chunks ? (knobs.split_k > 32 ? 32 : knobs.split_k) : chunks;
     int per = (chunks + splits - 1) / splits;
     plan.k_per_split = per * kt;
     plan.splits = (p.K + plan.k_per_split - 1) / plan.k_per_split;

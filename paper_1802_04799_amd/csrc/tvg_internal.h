@@ -28,6 +28,14 @@ struct ConvProblem {
     int stream_out; // TVG_STREAM_OUT: y is stored with the non-temporal hint
 };
 
+struct Knobs {
+    int mt, nt;       // workgroup tile
+    int stages;       // bf16 3x3: 1 = single-stage kernel, 2 = software-pipelined kernel
+    int split_k;      // generic kernel: partitions of the reduction; pipelined 3x3: wave groups (1, 2)
+    int lds_pitch;    // pipelined 3x3: 1 = plain patch pitch, 2 = conflict-free padded pitch
+    int row_loads;    // pipelined 3x3, odd rows of at most 7 pixels: 1 = element loads, 2 = whole rows
+};
+
 struct ConvPointers {
     const void *x, *w;
     const float *scale, *shift, *bias;
@@ -45,9 +53,9 @@ struct ConvPlan {
     size_t workspace_bytes;
 };
 
-// Tile shape fixed for this exact problem by tvg_conv2d_set_tile; false when there is none.
-// The planners of the 3x3 and 1x1 kernels then consider that tile shape only.
-bool forced_tile(const ConvProblem &p, int *mt, int *nt);
+// Schedule knobs fixed for this exact problem by tvg_conv2d_set_knobs / tvg_conv2d_set_tile
+// (all zero when there are none; a zero field leaves that choice to the planner's rule).
+Knobs forced_knobs(const ConvProblem &p);
 
 // `allow_split` = false plans a single pass over the reduction (no workspace).
 ConvPlan plan_conv(const ConvProblem &p, bool allow_split = true);
@@ -64,6 +72,10 @@ struct Patch3x3Plan {
     int pplane;         // its bytes per channel-octet plane of the patch
     int stage_bytes;    // its bytes per LDS stage
     int pws, xp16;      // its patch row pitch (16-byte words) and extra bytes between images
+    int kg;             // its groups of four waves that split the reduction (1 or 2)
+    // inputs to plan_conv3x3_dbuf, from the knobs (0 = the planner's rule): wave groups,
+    // pitch (1 plain, 2 padded), row loads (1 element-wise, 2 whole rows)
+    int want_kg, want_pitch, want_rows, want_stages;
 };
 
 // True when the problem is one the patch kernel is built for (bf16, 3x3, pad 1,

@@ -1,22 +1,37 @@
-"""Measured choice of a kernel's tile shape for one problem (TVM paper, Section 5: schedules
-are chosen per operator shape by running candidates on the device; here the space is the handful
-of tile shapes the kernels are built with, so the search is exhaustive and needs no cost model).
+"""Measured search over a problem's schedule knobs (TVM paper, Section 5: Section 5.1's schedule
+space is a template with knobs per operator, Section 5.3 explores it by running candidates on
+the device, with simulated annealing walking the space).  Here the knobs are the compiled kernel
+instances and launch parameters behind ``tvg_conv2d_set_knobs`` - workgroup tile (and with it the
+wave tile), LDS stages, split of the reduction, LDS pitch, row-load strategy - and every
+candidate is timed on the device; there is no cost model.
 
     from paper_1802_04799_amd import tune
-    report = tune.tune_conv2d(desc, x, w, scale, shift, y)      # times, then fixes the best tile
+    report = tune.tune_conv2d(desc, x, w, scale, shift, y)      # walks, then fixes the best point
     tune.save(path)  /  tune.load(path)                          # keep the choices across runs
 
+The walk: start at the library's own plan; a move changes one knob to another of its values; a
+faster point is always accepted, a slower one with probability exp(-(t_new - t_cur) / (T * t_cur))
+with T falling geometrically; after ``restart_after`` moves without a new best the walk jumps to a
+random point (random restart).  Points whose knobs the problem's kernel cannot use (the library
+would fall back to another kernel) are skipped, and every measured point is remembered, so the
+walk never times a point twice.  Small spaces are simply covered completely.
+
 Timing uses HIP events around back-to-back launches on torch's current stream; the library's own
-rule is always one of the candidates, so a tuned problem is never slower than an untuned one by
-more than the noise of the measurement.
+plan is always the first point, so a tuned problem is never slower than an untuned one by more than
+the noise of the measurement.
 """
+import itertools
 import json
+import math
+import random
+import zlib
 from typing import Dict, List, Optional, Tuple
 
 from . import binding as _b
 
 TILES: List[Tuple[int, int]] = [(64, 256), (128, 128), (64, 128), (128, 64), (64, 64)]
-_chosen: Dict[str, Tuple[int, int]] = {}
+KNOBS = ("mt", "nt", "stages", "split_k", "lds_pitch", "row_loads")
+_chosen: Dict[str, Tuple[int, ...]] = {}
 
 
 def _key(desc) -> str:
@@ -41,46 +56,145 @@ def _time_us(call, iters: int, repeats: int) -> float:
     return best
 
 
+def space_for(desc, kernel: int) -> Dict[str, list]:
+    """The values each knob can take for this problem's kernel family (0 = the library's rule is
+    not a value of its own: every point of the space names all its knobs)."""
+    if kernel in (1, 2):                         # bf16 3x3: both kernels, all their knobs
+        s1 = desc.stride_w == 1
+        odd_small = desc.w % 2 == 1 and desc.w <= 7 and s1
+        return {"tile": TILES, "stages": [1, 2], "split_k": [1, 2] if s1 else [1],
+                "lds_pitch": [1, 2] if s1 else [0], "row_loads": [1, 2] if odd_small else [0]}
+    if kernel == 4:                              # bf16 1x1
+        return {"tile": TILES[1:], "stages": [0], "split_k": [0], "lds_pitch": [0], "row_loads": [0]}
+    if kernel == 0:                              # generic kernel: tile rows and the reduction split
+        return {"tile": [(64, 0), (128, 0)], "stages": [0],
+                "split_k": [1, 2, 3, 4, 6, 8, 12, 16, 24, 32], "lds_pitch": [0], "row_loads": [0]}
+    return {"tile": [(0, 0)], "stages": [0], "split_k": [0], "lds_pitch": [0], "row_loads": [0]}
+
+
+def _point(tile, stages, split_k, lds_pitch, row_loads) -> Tuple[int, ...]:
+    return (tile[0], tile[1], stages, split_k, lds_pitch, row_loads)
+
+
+def _normalise(p: Tuple[int, ...]) -> Tuple[int, ...]:
+    """Knobs that only the pipelined kernel has are dropped from a single-stage point, so that
+    equivalent points share one measurement."""
+    mt, nt, stages, split_k, pitch, rows = p
+    if stages == 1:
+        return (mt, nt, 1, 0, 0, 0)
+    return p
+
+
 def tune_conv2d(desc, x, w, scale, shift, y, bias=None, residual=None, workspace=None,
-                iters: int = 30, repeats: int = 3, min_gain: float = 0.03) -> dict:
-    """Times the library's own plan and every tile shape on this problem, fixes the fastest with
-    tvg_conv2d_set_tile when it beats the library's plan by more than `min_gain` (a fraction),
-    and returns what it measured.  y (and the workspace, if the problem needs one) are scratch."""
+                iters: int = 30, repeats: int = 3, min_gain: float = 0.03, max_trials: int = 40,
+                seed: int = 0, t0: float = 0.05, cooling: float = 0.85, restart_after: int = 8) -> dict:
+    """Walks the knob space of this problem by measurement, fixes the fastest point with
+    tvg_conv2d_set_knobs when it beats the library's plan by more than `min_gain` (a fraction),
+    and returns what it measured: the walk (trials, accepted moves, restarts), every point's
+    time, the choice.  y (and a workspace, allocated here as needed) are scratch."""
     import torch
-    _b.tvg_conv2d_set_tile(desc, 0, 0)
-    need = _b.tvg_conv2d_workspace_size(desc)
-    if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
-        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    rng = random.Random(seed ^ zlib.crc32(_key(desc).encode()))
+    _b.tvg_conv2d_set_knobs(desc, None)
+    kernel, mt0, nt0 = _b.tvg_conv2d_get_plan(desc)
+    ws = {"t": workspace}
 
     def call():
-        st = _b.tvg_conv2d_fused(desc, x, w, scale, shift, bias, residual, y, workspace, need, None)
+        need = ws["need"]
+        st = _b.tvg_conv2d_fused(desc, x, w, scale, shift, bias, residual, y, ws["t"], need, None)
         if st != _b.TVG_OK:
             raise _b.TvgError(st, "tvg_conv2d_fused")
 
-    kernel, mt0, nt0 = _b.tvg_conv2d_get_plan(desc)
-    base = _time_us(call, iters, repeats)
+    def measure() -> float:
+        ws["need"] = need = _b.tvg_conv2d_workspace_size(desc)
+        if need and (ws["t"] is None or ws["t"].numel() * ws["t"].element_size() < need):
+            ws["t"] = torch.empty(need, dtype=torch.uint8, device=x.device)
+        return _time_us(call, iters, repeats)
+
+    default_knobs = _b.tvg_conv2d_get_knobs(desc)
+    base = measure()
     report = {"key": _key(desc), "kernel": _b.KERNEL_NAMES[kernel], "default": [mt0, nt0],
-              "default_us": round(base, 2), "candidates": {}}
-    best, best_us = None, base
-    if kernel in (1, 2, 4):                      # the kernels that have a tile knob
-        for mt, nt in TILES:
-            if _b.tvg_conv2d_set_tile(desc, mt, nt) != _b.TVG_OK:
+              "default_knobs": list(default_knobs), "default_us": round(base, 2), "candidates": {}}
+    space = space_for(desc, kernel)
+    axes = ["tile", "stages", "split_k", "lds_pitch", "row_loads"]
+    seen: Dict[Tuple[int, ...], Optional[float]] = {}
+
+    def evaluate(p: Tuple[int, ...]) -> Optional[float]:
+        p = _normalise(p)
+        if p in seen:
+            return seen[p]
+        us = None
+        if _b.tvg_conv2d_set_knobs(desc, p) == _b.TVG_OK:
+            eff = _b.tvg_conv2d_get_knobs(desc)
+            k2 = _b.tvg_conv2d_get_plan(desc)[0]
+            # usable if the library really runs what the point names (no silent fall-back)
+            same_family = (k2 in (1, 2)) if kernel in (1, 2) else k2 == kernel
+            named = all(want == 0 or want == got for want, got in zip(p, eff))
+            if same_family and named:
+                us = measure()
+                report["candidates"]["/".join(map(str, p))] = round(us, 2)
+        seen[p] = us
+        return us
+
+    all_points = [_point(*c) for c in itertools.product(*[space[a] for a in axes])]
+    walk = {"space_points": len({_normalise(p) for p in all_points}), "trials": 0, "accepted": 0,
+            "restarts": 0, "exhaustive": False}
+    best_p, best_us = None, base
+    if len(all_points) <= 1:
+        pass
+    elif walk["space_points"] <= max_trials:      # small space: cover it
+        walk["exhaustive"] = True
+        for p in all_points:
+            us = evaluate(p)
+            if us is not None and us < best_us:
+                best_p, best_us = _normalise(p), us
+        walk["trials"] = sum(v is not None for v in seen.values())
+    else:                                          # simulated annealing with random restarts
+        d = tuple(default_knobs)
+        cur = [(d[0], d[1]), d[2], d[3], d[4], d[5]]
+        # snap the library's plan onto the space (a knob it does not use takes the first value)
+        for i, a in enumerate(axes):
+            if cur[i] not in space[a]:
+                cur[i] = space[a][0]
+        cur_us = evaluate(_point(*cur)) or base
+        temp, stale = t0, 0
+        while walk["trials"] < max_trials:
+            if stale >= restart_after:
+                cand = [rng.choice(space[a]) for a in axes]
+                walk["restarts"] += 1
+                stale = 0
+            else:
+                cand = list(cur)
+                movable = [i for i, a in enumerate(axes) if len(space[a]) > 1]
+                i = rng.choice(movable)
+                cand[i] = rng.choice([v for v in space[axes[i]] if v != cur[i]])
+            fresh = _normalise(_point(*cand)) not in seen
+            us = evaluate(_point(*cand))
+            if fresh:
+                walk["trials"] += 1
+            elif all(_normalise(p) in seen for p in all_points):
+                break                               # everything has been measured
+            if us is None:
+                stale += 1
                 continue
-            k2, mt2, nt2 = _b.tvg_conv2d_get_plan(desc)
-            if k2 == 0 or (mt2, nt2) != (mt, nt):        # this kernel cannot use the tile
-                continue
-            us = _time_us(call, iters, repeats)
-            report["candidates"][f"{mt}x{nt}"] = round(us, 2)
+            if us < cur_us or rng.random() < math.exp(-(us - cur_us) / (temp * cur_us)):
+                cur, cur_us = cand, us
+                walk["accepted"] += 1
             if us < best_us:
-                best, best_us = (mt, nt), us
-    _b.tvg_conv2d_set_tile(desc, 0, 0)
-    if best is not None and best_us < base * (1.0 - min_gain):
-        _b.tvg_conv2d_set_tile(desc, *best)
-        _chosen[report["key"]] = best
-        report["chosen"] = list(best)
+                best_p, best_us, stale = _normalise(_point(*cand)), us, 0
+            else:
+                stale += 1
+            temp *= cooling
+    report["walk"] = walk
+    _b.tvg_conv2d_set_knobs(desc, None)
+    if best_p is not None and best_us < base * (1.0 - min_gain):
+        _b.tvg_conv2d_set_knobs(desc, best_p)
+        _chosen[report["key"]] = tuple(best_p)
+        report["chosen"] = list(best_p[:2])
+        report["chosen_knobs"] = list(best_p)
     else:
         _chosen.pop(report["key"], None)
         report["chosen"] = None                  # the library's rule stands
+        report["chosen_knobs"] = None
     report["tuned_us"] = round(min(best_us, base), 2)
     return report
 
@@ -95,10 +209,11 @@ def load(path: str) -> int:
     with open(path) as f:
         table = json.load(f)
     n = 0
-    for key, (mt, nt) in table.items():
+    for key, knobs in table.items():
         v = [int(t) for t in key.split(",")]
         desc = _b.ConvDesc(*v[:12], 0)
-        if _b.tvg_conv2d_set_tile(desc, mt, nt) == _b.TVG_OK:
-            _chosen[key] = (mt, nt)
+        knobs = tuple(knobs) + (0,) * (6 - len(knobs))      # older files hold (mt, nt) only
+        if _b.tvg_conv2d_set_knobs(desc, knobs) == _b.TVG_OK:
+            _chosen[key] = knobs
             n += 1
     return n

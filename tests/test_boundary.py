@@ -247,3 +247,44 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(b, "_LIB_PATH", str(tmp_path / "libtvg.so"))
     with pytest.raises(ImportError):
         b.load()
+
+
+def test_knob_table_host_side():
+    """tvg_conv2d_set_knobs / tvg_conv2d_get_knobs (host only): what the library's rule picks, what
+    a caller can fix, how the size query follows the reduction split, what is rejected."""
+    c6 = desc(n=64, c=128, h=28, w=28, k=128, dtype=tvg.TVG_BF16)
+    assert tvg.tvg_conv2d_get_knobs(c6) == (64, 256, 2, 1, 2, 0)        # pipelined, padded pitch
+    assert tvg.tvg_conv2d_set_knobs(c6, (64, 128, 1, 0, 0, 0)) == 0
+    assert tvg.tvg_conv2d_get_plan(c6) == (1, 64, 128)                 # the single-stage kernel
+    assert tvg.tvg_conv2d_get_knobs(c6) == (64, 128, 1, 0, 0, 0)
+    assert tvg.tvg_conv2d_set_tile(c6, 64, 64) == 0                    # the tile alone: stages stay
+    assert tvg.tvg_conv2d_get_knobs(c6)[:3] == (64, 64, 1)
+    assert tvg.tvg_conv2d_set_knobs(c6, None) == 0
+    assert tvg.tvg_conv2d_get_knobs(c6) == (64, 256, 2, 1, 2, 0)
+    # C12 at batch 64: odd 7-pixel rows, 200 tiles: two wave groups by rule, element loads
+    c12 = desc(n=64, c=512, h=7, w=7, k=512, dtype=tvg.TVG_BF16)
+    assert tvg.tvg_conv2d_get_knobs(c12) == (64, 128, 2, 2, 2, 1)
+    assert tvg.tvg_conv2d_set_knobs(c12, (0, 0, 2, 1, 0, 2)) == 0
+    assert tvg.tvg_conv2d_get_knobs(c12)[2:] == (2, 1, 2, 2)
+    assert tvg.tvg_conv2d_set_knobs(c12, None) == 0
+    # C9 at batch 64: a lone workgroup per CU keeps the padded pitch (86 KB of LDS), one group
+    c9 = desc(n=64, c=256, h=14, w=14, k=256, dtype=tvg.TVG_BF16)
+    assert tvg.tvg_conv2d_get_knobs(c9) == (64, 256, 2, 1, 2, 0)
+    # the generic kernel: the size query follows the split
+    f = desc(n=1, c=512, h=7, w=7, k=512)
+    auto = tvg.tvg_conv2d_workspace_size(f)
+    k0 = tvg.tvg_conv2d_get_knobs(f)
+    assert k0[2:] == (2, 32, 0, 0) and auto == 32 * 512 * 49 * 4
+    assert tvg.tvg_conv2d_set_knobs(f, (0, 0, 0, 4, 0, 0)) == 0
+    assert tvg.tvg_conv2d_workspace_size(f) == 4 * 512 * 49 * 4 and tvg.tvg_conv2d_get_knobs(f)[3] == 4
+    assert tvg.tvg_conv2d_set_knobs(f, (0, 0, 0, 1, 0, 0)) == 0
+    assert tvg.tvg_conv2d_workspace_size(f) == 0
+    assert tvg.tvg_conv2d_set_knobs(f, None) == 0
+    assert tvg.tvg_conv2d_workspace_size(f) == auto
+    for bad in [(64, 100, 0, 0, 0, 0), (0, 0, 3, 0, 0, 0), (0, 0, 0, 33, 0, 0), (0, 0, 0, -1, 0, 0),
+                (0, 0, 0, 0, 3, 0), (0, 0, 0, 0, 0, 3)]:
+        assert tvg.tvg_conv2d_set_knobs(c6, bad) == 3
+    assert tvg.tvg_conv2d_set_knobs(desc(n=0), (0, 0, 1, 0, 0, 0)) == 2
+    lib = tvg.load()
+    assert lib.tvg_conv2d_set_knobs(None, None) == 1
+    assert lib.tvg_conv2d_get_knobs(ctypes.byref(c6), None) == 1

@@ -226,6 +226,48 @@ def test_bf16_3x3_pipelined_kernel_stride2(tvg, cfg, tile):
     check(to_host(y), oracle_dense(sh, inp), "bf16")
 
 
+KNOB_SHAPES = [
+    # bf16 3x3 stride-1 problems for the pipelined kernel's knobs (input channels a multiple of
+    # 64 so that two wave groups can split the reduction): n, ic, h, w, oc
+    (3, 128, 7, 7, 130), (40, 128, 7, 7, 64), (1, 512, 7, 7, 64), (70, 128, 3, 3, 64),
+    (2, 128, 3, 1, 64), (9, 192, 5, 5, 96), (2, 256, 14, 14, 72), (1, 128, 30, 70, 16),
+    (5, 192, 12, 12, 96), (2, 128, 9, 11, 40), (1, 64, 7, 7, 64), (33, 256, 7, 5, 200),
+]
+KNOB_POINTS = [
+    # (tile, split_k, lds_pitch, row_loads); stages = 2 throughout
+    ("64,128", 2, 1, 1), ("64,128", 2, 2, 1), ("64,256", 2, 1, 1), ("64,256", 1, 2, 1),
+    ("64,128", 1, 1, 2), ("64,128", 2, 1, 2), ("64,256", 2, 2, 2), ("64,64", 1, 2, 2),
+]
+
+
+@pytest.mark.parametrize("point", KNOB_POINTS, ids=lambda p: f"{p[0]}-k{p[1]}-p{p[2]}-r{p[3]}")
+@pytest.mark.parametrize("cfg", KNOB_SHAPES, ids=lambda c: "x".join(map(str, c)))
+def test_bf16_3x3_pipelined_kernel_knobs(tvg, cfg, point):
+    """The pipelined kernel under its knobs, fixed through tvg_conv2d_set_knobs: two wave groups
+    splitting the reduction, both LDS pitches, whole-row loads of odd rows (start addresses of
+    both parities, rows of 1 to 7 pixels).  A point the problem cannot use (the library would run
+    something else) is skipped; what runs is checked against the oracle with bias, residual, ReLU."""
+    import torch
+    n, ic, h, w, oc = cfg
+    tile, split_k, pitch, rows = point
+    mt, nt = (int(v) for v in tile.split(","))
+    sh = ti.ConvShape("kn", n, ic, h, w, oc, 3, 3, 1, 1)
+    desc = tvg.ConvDesc(n, ic, h, w, oc, 3, 3, 1, 1, 1, 1, tvg.TVG_BF16, 0)
+    want_knobs = (mt, nt, 2, split_k, pitch, rows if (w % 2 == 1 and w <= 7) else 0)
+    assert tvg.tvg_conv2d_set_knobs(desc, want_knobs) == 0
+    try:
+        got_knobs = tvg.tvg_conv2d_get_knobs(desc)
+        if tvg.tvg_conv2d_get_plan(desc)[0] != 2 or any(a and a != b for a, b in zip(want_knobs, got_knobs)):
+            pytest.skip(f"point not usable here: asked {want_knobs}, would run {got_knobs}")
+        inp = ti.make_inputs(sh, 15000 + sum(cfg) + split_k + 2 * pitch + 4 * rows, "bf16", residual=True, bias=True)
+        y1 = run_dense(tvg, sh, inp, "bf16")
+        y2 = run_dense(tvg, sh, inp, "bf16")
+        assert torch.equal(y1.view(torch.int16), y2.view(torch.int16))      # deterministic
+        check(to_host(y1), oracle_dense(sh, inp), "bf16", (cfg, got_knobs))
+    finally:
+        tvg.tvg_conv2d_set_knobs(desc, None)
+
+
 @pytest.mark.parametrize("cfg", [(2, 128, 8, 8, 64), (3, 128, 7, 7, 130), (1, 256, 33, 40, 72)])
 def test_bf16_3x3_pipelined_kernel_plain_tail_and_determinism(tvg, cfg):
     """No bias, no residual, no ReLU (negative outputs survive), and bit-identical reruns."""
@@ -515,22 +557,26 @@ def test_tuner_fixes_a_tile_and_results_stay_right(tvg, tmp_path):
     y = torch.empty(sh.y_shape(), dtype=torch.bfloat16, device="cuda:0")
     try:
         rep = tune.tune_conv2d(desc, d["x"], d["w"], d["scale"], d["shift"], y, iters=10, repeats=2,
-                               min_gain=0.0)
+                               min_gain=0.0, max_trials=12)
         assert rep["kernel"] == "3x3" and len(rep["candidates"]) >= 3
         assert rep["tuned_us"] <= rep["default_us"]
+        walk = rep["walk"]
+        assert 3 <= walk["trials"] <= 12 and walk["space_points"] > 12 and not walk["exhaustive"]
         plan = tvg.tvg_conv2d_get_plan(desc)
         if rep["chosen"]:
             assert list(plan[1:]) == rep["chosen"]
+            assert all(w == 0 or w == g for w, g in zip(rep["chosen_knobs"], tvg.tvg_conv2d_get_knobs(desc)))
         out = tvg.conv2d_fused(d["x"], d["w"], d["scale"], d["shift"], stride=1, pad=1, relu=True)
         torch.cuda.synchronize()
         check(to_host(out), oracle_dense(sh, inp), "bf16")
         path = str(tmp_path / "tiles.json")
         tune.save(path)
-        tvg.tvg_conv2d_set_tile(desc, 0, 0)
+        knobs = tvg.tvg_conv2d_get_knobs(desc)
+        tvg.tvg_conv2d_set_knobs(desc, None)
         assert tune.load(path) == (1 if rep["chosen"] else 0)
-        assert tvg.tvg_conv2d_get_plan(desc) == plan
+        assert tvg.tvg_conv2d_get_plan(desc) == plan and tvg.tvg_conv2d_get_knobs(desc) == knobs
     finally:
-        tvg.tvg_conv2d_set_tile(desc, 0, 0)
+        tvg.tvg_conv2d_set_knobs(desc, None)
 
 
 def test_config5_resnet18_body_hip_graph_replays_match_eager(tvg):
