@@ -231,7 +231,8 @@ typedef enum {
     TVG_KERNEL_3X3 = 1,            /* bf16 3x3, input patch in LDS, one stage              */
     TVG_KERNEL_3X3_PIPELINED = 2,  /* bf16 3x3, two LDS stages, software-pipelined         */
     TVG_KERNEL_STEM = 3,           /* bf16 7x7 stride 2, few input channels                */
-    TVG_KERNEL_1X1 = 4             /* bf16 1x1                                             */
+    TVG_KERNEL_1X1 = 4,            /* bf16 1x1                                             */
+    TVG_KERNEL_F32_SMALL = 5       /* fp32 1x1 / 3x3 of launch-bound problems, one launch  */
 } tvg_kernel;
 tvg_status tvg_conv2d_set_tile(const tvg_conv_desc *desc, int32_t mt, int32_t nt);
 tvg_status tvg_conv2d_get_plan(const tvg_conv_desc *desc, int32_t *kernel, int32_t *mt, int32_t *nt);

@@ -98,10 +98,11 @@ void tile_key(const ConvProblem &p, int (&key)[12])
 // it.  The launch-bound batch-1 layers spend 1-5 us per call in planning otherwise.
 struct Dispatch {
     int key[12];
-    bool patch_shape, stem_shape, pw_shape;
+    bool patch_shape, stem_shape, pw_shape, f32_shape;
     tvg::Patch3x3Plan patch;
     tvg::StemPlan stem;
     tvg::Pw1x1Plan pw;
+    tvg::F32SmallPlan f32;
     tvg::ConvPlan generic;          // the generic kernel's plan, reduction split allowed
     tvg::ConvPlan generic_single;   // the same in a single pass (no workspace)
 };
@@ -124,6 +125,7 @@ Dispatch dispatch_for(const ConvProblem &p)
     d.patch_shape = tvg::plan_conv3x3_patch(p, &d.patch);
     d.stem_shape = !d.patch_shape && tvg::plan_conv7x7s2_stem(p, &d.stem);
     d.pw_shape = !d.patch_shape && !d.stem_shape && tvg::plan_conv1x1(p, &d.pw);
+    d.f32_shape = tvg::plan_conv_f32_small(p, &d.f32);
     d.generic = tvg::plan_conv(p, true);
     d.generic_single = tvg::plan_conv(p, false);
     std::lock_guard<std::mutex> lock(g_dispatch_mutex);
@@ -260,6 +262,9 @@ tvg_status tvg_conv2d_get_knobs(const tvg_conv_desc *desc, tvg_conv_knobs *knobs
     } else if (d.pw_shape) {
         k.mt = d.pw.mt;
         k.nt = d.pw.nt;
+    } else if (d.f32_shape) {
+        k.stages = 1;
+        k.split_k = d.f32.nw * d.f32.ksplit;     // waves of a workgroup x slices across workgroups
     } else {
         k.mt = d.generic.mt;
         k.nt = d.generic.nt;
@@ -289,6 +294,10 @@ tvg_status tvg_conv2d_get_plan(const tvg_conv_desc *desc, int32_t *kernel, int32
         *kernel = TVG_KERNEL_1X1;
         *mt = d.pw.mt;
         *nt = d.pw.nt;
+    } else if (d.f32_shape) {
+        *kernel = TVG_KERNEL_F32_SMALL;
+        *mt = 32;
+        *nt = 32;
     } else {
         *kernel = TVG_KERNEL_GENERIC;
         *mt = d.generic.mt;
@@ -306,7 +315,7 @@ tvg_status tvg_conv2d_workspace_size(const tvg_conv_desc *desc, size_t *bytes)
     if (st != TVG_OK) return st;
     const Dispatch d = dispatch_for(p);
     const bool single_pass = d.patch_shape || d.stem_shape || d.pw_shape;
-    *bytes = single_pass ? 0 : d.generic.workspace_bytes;
+    *bytes = single_pass ? 0 : d.f32_shape ? d.f32.workspace_bytes : d.generic.workspace_bytes;
     return TVG_OK;
 }
 
@@ -337,13 +346,22 @@ tvg_status tvg_conv2d_fused(const tvg_conv_desc *desc, const void *x, const void
     if (d.stem_shape && tvg::conv7x7s2_stem_pointers_ok(ptr))
         return tvg::launch_conv7x7s2_stem(p, d.stem, ptr, stream);
     if (d.pw_shape && tvg::conv1x1_pointers_ok(ptr)) return tvg::launch_conv1x1(p, d.pw, ptr, stream);
+    const auto workspace_short = [&](size_t need) {
+        return need > 0 && (!workspace || workspace_bytes < need ||
+                            reinterpret_cast<uintptr_t>(workspace) % 256 != 0);
+    };
+    if (d.f32_shape && tvg::conv_f32_small_pointers_ok(ptr)) {
+        if (workspace_short(d.f32.workspace_bytes)) return TVG_ERR_WORKSPACE;
+        return tvg::launch_conv_f32_small(p, d.f32, ptr, stream);
+    }
     // A problem shaped for a specialised kernel reported a zero workspace; if its pointers
     // rule that kernel out, the generic kernel runs it in a single pass over the reduction.
-    const tvg::ConvPlan &plan = (d.patch_shape || d.stem_shape || d.pw_shape) ? d.generic_single
-                                                                               : d.generic;
-    if (plan.workspace_bytes > 0 && (!workspace || workspace_bytes < plan.workspace_bytes ||
-                                     reinterpret_cast<uintptr_t>(workspace) % 256 != 0))
-        return TVG_ERR_WORKSPACE;
+    // (an fp32 problem whose x is not 16-byte aligned: the generic kernel, within the workspace
+    // that the query reported for the fp32 kernel if that is all the caller has)
+    const tvg::ConvPlan &plan =
+        (d.patch_shape || d.stem_shape || d.pw_shape ||
+         (d.f32_shape && workspace_short(d.generic.workspace_bytes))) ? d.generic_single : d.generic;
+    if (workspace_short(plan.workspace_bytes)) return TVG_ERR_WORKSPACE;
     return tvg::launch_conv_igemm(p, plan, ptr, stream);
 }
 

@@ -1,0 +1,357 @@
+// fp32 fused conv2d for launch-bound problems (batch 1: the ResNet-18 shapes of Table 2 have
+// roofline times of 0.1 - 1.5 us, far below the cost of a launch): 1x1 and 3x3 filters, stride 1
+// or 2, "same" padding.  One launch, nothing but y written (TVM paper Section 4.2 cooperative
+// fetch, Section 4.3 tensorization; Section 3 fusion for the tail).
+//
+// What makes fp32 different from the bf16 kernels: v_mfma_f32_32x32x2_f32 takes ONE k value per
+// lane (lanes 0-31: k, lanes 32-63: k + 1), so nothing has to be transposed.
+//   - The pixel operand of tap (r, s) is the fp32 input itself at a shifted address: the input
+//     rows a tile needs are copied into LDS in their natural [channel][row][column] layout with
+//     zero borders, and 32 consecutive pixels are 32 consecutive words.
+//   - The weight operand of lane (oc, half) over a run of k values is a CONTIGUOUS run of floats
+//     of the OIHW tensor (k = (ic, r, s) is its innermost order).  A wave copies the 32 runs of
+//     a pass (32 output channels x 8 input channels x taps) into LDS with 16-byte loads whose
+//     lanes walk along the runs, and every lane then reads its own run's floats one by one.
+//     (The first version loaded each lane's run straight into registers: every lane then touches
+//     cache lines of its own, a wave's load instruction 64 of them, and with 8 to 16 waves per CU
+//     the lines are evicted and fetched again for each of a run's nine loads - C12 at batch 1
+//     took 28 us, C9 18 us, bound by the CU's address unit.)
+// A workgroup owns 32 output channels x 32 consecutive pixels of one image; its NW waves (1 to
+// 16) split the reduction: in every pass wave w takes 8 input channels (4 per half-wave), copies
+// their rows into LDS of its own, and needs no barrier to use them.  At the end the waves add
+// their accumulators through LDS (one barrier pair) and 256 threads apply the fused tail and
+// store rows of 4 consecutive pixels.  The reduction order is fixed, results are deterministic.
+#include "tvg_device.h"
+#include "tvg_internal.h"
+
+namespace tvg {
+
+namespace {
+
+constexpr int kCPH = 4;              // input channels per half-wave and pass
+// patch loads per lane and pass (16-, 8- or 4-byte loads for rows of 4n, 2n, other pixel counts);
+// workgroups of 16 waves (4 per SIMD, 128 registers each) hold fewer
+constexpr int kMaxSlots = 16, kMaxBig = 8;
+constexpr int kPartPitch = 65;       // floats per (wave, register) row of the partial sums
+constexpr int kWRegion = 32 * 73 + 0;  // floats of a wave's weight runs in LDS (3x3: 32 x (72 + 1)); 16-byte multiple
+constexpr int kRsrc = 0x00020000;
+
+struct F32Args {
+    const float *x, *w, *scale, *shift, *bias, *residual;
+    float *y;
+    int N, IC, H, W, OC, OH, OW, relu;
+    int mtiles, tpi;        // channel tiles, pixel tiles per image
+    int nw, passes;         // waves per workgroup, passes over the channels (per slice)
+    int ksplit;             // slices of the reduction across workgroups (blockIdx.y); > 1: raw sums to ws
+    float *ws;              // [ksplit][N][OC][OH][OW] partial sums
+    int pitch, region;      // LDS row pitch and floats per wave region
+    int vec_out;            // y (and residual) rows of 4 pixels are aligned 16-byte pieces
+    uint32_t x_bytes, w_bytes;
+};
+
+template <int R, int STRIDE, int VEC, bool BIG>
+__global__ __launch_bounds__(BIG ? 1024 : 512) void conv_f32_small_kernel(const F32Args a)
+{
+    constexpr int RS = R * R, PAD = R / 2;
+    constexpr int WROW = 2 * kCPH * RS;            // floats of one output channel's run per pass
+    constexpr int WPITCH = WROW + 1;               // its pitch in LDS (odd: conflict-free reads)
+    constexpr int WPIECES = 32 * WROW / 4;         // 16-byte pieces of the 32 runs
+    constexpr int WSLOTS = (WPIECES + 63) / 64;    // per lane
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lp = lane & 31, half = lane >> 5;
+    int b = blockIdx.x;
+    const int mt = b % a.mtiles;
+    b /= a.mtiles;
+    const int pt = b % a.tpi, n = b / a.tpi;
+    const int m0 = mt * 32, p0 = pt * 32;
+    const int OHW = a.OH * a.OW, W = a.W, H = a.H;
+    const int npx = min(32, OHW - p0);
+    const int oh_lo = p0 / a.OW, oh_hi = (p0 + npx - 1) / a.OW;
+    const int ih_lo = oh_lo * STRIDE - PAD;
+    const int nr = (oh_hi - oh_lo) * STRIDE + R;          // input rows of the tile (with padding rows)
+    const int pitch = a.pitch, plane = nr * pitch;
+    // rows that exist in the image: one contiguous run per channel
+    const int ih_first = max(ih_lo, 0), ih_last = min(ih_lo + nr - 1, H - 1);
+    const int E = (ih_last - ih_first + 1) * W;           // floats per channel to copy
+    const int row_shift = ih_first - ih_lo;
+
+    float *reg = smem + wave * (a.region + kWRegion);
+    float *wl = reg + a.region;                            // the wave's 32 weight runs
+    // zero the wave's region once: border columns and rows outside the image stay zero, the
+    // interior is overwritten by every pass
+    for (int i = lane * 4; i < a.region; i += 256)
+        *reinterpret_cast<float4v *>(reg + i) = float4v{0.0f, 0.0f, 0.0f, 0.0f};
+
+    const __amdgpu_buffer_rsrc_t xrsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.x), 0, a.x_bytes, kRsrc);
+    const __amdgpu_buffer_rsrc_t wrsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.w), 0, a.w_bytes, kRsrc);
+
+    // this lane's pixel (lanes past the tile's end shadow pixel 0; their results are dropped)
+    const int pp = lp < npx ? lp : 0;
+    const int oh = (p0 + pp) / a.OW, ow = (p0 + pp) - oh * a.OW;
+    const int bbase = half * kCPH * plane + (oh - oh_lo) * STRIDE * pitch + ow * STRIDE;
+    // weight copy slots: piece q of the 32 runs -> (run, part); runs past OC shadow the last one
+    uint32_t wsrc[WSLOTS];
+    int wdst[WSLOTS];
+#pragma unroll
+    for (int k = 0; k < WSLOTS; ++k) {
+        const int q = lane + 64 * k;
+        const int run = q / (WROW / 4), part = q - run * (WROW / 4);
+        wdst[k] = q < WPIECES ? run * WPITCH + part * 4 : -1;
+        wsrc[k] = 4u * (uint32_t)(min(m0 + run, a.OC - 1) * a.IC * RS) + 16u * (uint32_t)part;
+    }
+    const int abase = lp * WPITCH + half * kCPH * RS;
+
+    // copy slots of this lane: element i of the wave's 8 x E floats -> (channel, row, column)
+    const float inv_e = 1.0f / (float)E, inv_w = 1.0f / (float)W;
+    constexpr int NSLOT = BIG ? kMaxBig : kMaxSlots;
+    constexpr int STEP = VEC;                      // floats per copy: 4, 2 or 1
+    uint32_t src_off[NSLOT];      // byte offset within channel block 0 of the image (per pass: + channels)
+    int dst_off[NSLOT];           // float offset in the wave's region, -1 = no element
+#pragma unroll
+    for (int k = 0; k < NSLOT; ++k) {
+        const int i = (lane + 64 * k) * STEP;
+        dst_off[k] = -1;
+        src_off[k] = 0;
+        if (i < 2 * kCPH * E) {
+            int e, col;
+            const int ch = fast_div(i, E, inv_e, &e);
+            const int row = fast_div(e, W, inv_w, &col);
+            src_off[k] = 4u * (uint32_t)((ch * H + ih_first) * W + e);
+            dst_off[k] = ch * plane + (row + row_shift) * pitch + col + PAD;
+        }
+    }
+
+    float16v acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+
+    for (int pass = 0; pass < a.passes; ++pass) {
+        // this wave's 8 channels (slice blockIdx.y of the reduction takes a.passes passes)
+        const int ic0 = (((int)blockIdx.y * a.passes + pass) * a.nw + wave) * 2 * kCPH;
+        // weights: the runs of channels ic0 .. ic0 + 7 (WROW contiguous floats per output channel)
+        uint4v wv[WSLOTS];
+#pragma unroll
+        for (int k = 0; k < WSLOTS; ++k)
+            if (wdst[k] >= 0)
+                wv[k] = __builtin_bit_cast(
+                    uint4v, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, wsrc[k], ic0 * RS * 4, 0));
+        // the patch rows of the 8 channels
+        const int cbase = 4 * ((n * a.IC + ic0) * H * W);
+        float pv[NSLOT][STEP];
+#pragma unroll
+        for (int k = 0; k < NSLOT; ++k) {
+            if (dst_off[k] >= 0) {                       // (the same lanes in every pass)
+                if constexpr (VEC == 4) {
+                    const uint4v t4 = __builtin_bit_cast(
+                        uint4v, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, src_off[k], cbase, 0));
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) pv[k][d] = __uint_as_float(t4[d]);
+                } else if constexpr (VEC == 2) {
+                    const uint2v t2 = __builtin_bit_cast(
+                        uint2v, __builtin_amdgcn_raw_buffer_load_b64(xrsrc, src_off[k], cbase, 0));
+                    pv[k][0] = __uint_as_float(t2[0]);
+                    pv[k][1] = __uint_as_float(t2[1]);
+                } else {
+                    pv[k][0] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(xrsrc, src_off[k], cbase, 0));
+                }
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < WSLOTS; ++k)
+            if (wdst[k] >= 0) {
+#pragma unroll
+                for (int d = 0; d < 4; ++d) wl[wdst[k] + d] = __uint_as_float(wv[k][d]);
+            }
+#pragma unroll
+        for (int k = 0; k < NSLOT; ++k)
+            if (dst_off[k] >= 0) {
+#pragma unroll
+                for (int d = 0; d < STEP; ++d) reg[dst_off[k] + d] = pv[k][d];
+            }
+        // a wave reads only what it wrote itself: LDS operations of a wave complete in order
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int c = 0; c < kCPH; ++c)
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int s = 0; s < R; ++s) {
+                    const float bv = reg[bbase + c * plane + r * pitch + s];
+                    const float av = wl[abase + c * RS + r * R + s];
+                    // pixel operand first: the accumulator tile is D[pixel][channel]
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av, acc, 0, 0, 0);
+                }
+        __builtin_amdgcn_wave_barrier();      // the next pass overwrites the rows just read
+    }
+
+    // ---- the waves' partial sums meet in LDS (over the patch regions, which are done with) ----
+    __syncthreads();
+    float *part = smem;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) part[(wave * 16 + v) * kPartPitch + lane] = acc[v];
+    __syncthreads();
+    // value v of lane l: channel l % 32, pixel 8*(v/4) + 4*(l/32) + v%4.  Thread t of the first
+    // 256 takes channel t / 8 and the 4 consecutive pixels from 4 * (t % 8) on.
+    for (int t = tid; t < 256; t += (int)blockDim.x) {
+        const int cc = t >> 3, pb = (t & 7) * 4;
+        const int src_lane = cc + 32 * ((pb >> 2) & 1), v0 = 4 * (pb >> 3);
+        float sum[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        for (int s = 0; s < a.nw; ++s)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) sum[q] += part[(s * 16 + v0 + q) * kPartPitch + src_lane];
+        const int oc = m0 + cc;
+        if (oc >= a.OC || pb >= npx) continue;
+        if (a.ksplit > 1) {       // a slice of the reduction: raw sums, the reduce launch finishes
+            float *dst = a.ws + (size_t)blockIdx.y * ((size_t)a.N * a.OC * OHW) +
+                         (size_t)(n * a.OC + oc) * OHW + p0 + pb;
+            if (OHW % 4 == 0) *reinterpret_cast<float4v *>(dst) = float4v{sum[0], sum[1], sum[2], sum[3]};
+            else
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (pb + q < npx) dst[q] = sum[q];
+            continue;
+        }
+        const float sc = a.scale[oc];
+        const float sf = a.bias ? fmaf(a.bias[oc], sc, a.shift[oc]) : a.shift[oc];
+        const float floor_v = a.relu ? 0.0f : -INFINITY;
+        const int idx = (n * a.OC + oc) * OHW + p0 + pb;
+        if (a.vec_out) {                               // OHW % 4 == 0: the whole group is inside
+            float4v r4 = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (a.residual) r4 = *reinterpret_cast<const float4v *>(a.residual + idx);
+            float4v o;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) o[q] = fmaxf(fmaf(sum[q], sc, sf) + r4[q], floor_v);
+            *reinterpret_cast<float4v *>(a.y + idx) = o;
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (pb + q < npx) {
+                    float o = fmaf(sum[q], sc, sf);
+                    if (a.residual) o += a.residual[idx + q];
+                    a.y[idx + q] = fmaxf(o, floor_v);
+                }
+        }
+    }
+}
+
+template <int R, int STRIDE>
+tvg_status launch_rs(const F32Args &a, int vec, dim3 grid, size_t lds, hipStream_t stream)
+{
+    // opt in to > 64 KB of dynamic LDS (a cheap host call, made before every launch: the four
+    // instances below would each need a flag of their own)
+    auto set = [&](auto kernel) {
+        return hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) == hipSuccess;
+    };
+#define TVG_F32_LAUNCH(VEC_, BIG_)                                                             \
+    do {                                                                                       \
+        auto kernel = conv_f32_small_kernel<R, STRIDE, VEC_, BIG_>;                            \
+        if (!set(kernel)) return TVG_ERR_LAUNCH;                                               \
+        hipLaunchKernelGGL(kernel, grid, dim3(64 * a.nw), lds, stream, a);                     \
+    } while (0)
+    if (a.nw == 16) {
+        if (vec == 4) TVG_F32_LAUNCH(4, true);
+        else if (vec == 2) TVG_F32_LAUNCH(2, true);
+        else TVG_F32_LAUNCH(1, true);
+    } else {
+        if (vec == 4) TVG_F32_LAUNCH(4, false);
+        else if (vec == 2) TVG_F32_LAUNCH(2, false);
+        else TVG_F32_LAUNCH(1, false);
+    }
+#undef TVG_F32_LAUNCH
+    return hipGetLastError() == hipSuccess ? TVG_OK : TVG_ERR_LAUNCH;
+}
+
+}  // namespace
+
+bool plan_conv_f32_small(const ConvProblem &p, F32SmallPlan *plan)
+{
+    if (p.dtype != TVG_F32 || p.R != p.S || (p.R != 1 && p.R != 3)) return false;
+    if (p.ph != p.R / 2 || p.pw != p.R / 2 || p.sh != p.sw || (p.sh != 1 && p.sh != 2)) return false;
+    if (p.IC % (2 * kCPH) != 0) return false;
+    const Knobs knobs = forced_knobs(p);
+    if (knobs.split_k > 0 || knobs.mt > 0) return false;     // the caller shapes the generic kernel
+    // launch-bound problems only: those the generic kernel cannot fill the chip with in one pass
+    const long gtiles = (long)((p.OC + 127) / 128) * ((p.npix + 127) / 128);
+    if (gtiles >= kComputeUnits) return false;
+    const int OHW = p.OH * p.OW;
+    const int orows = std::min(p.OH, (std::min(32, OHW) + p.OW - 2) / p.OW + 1);   // rows 32 pixels can touch
+    const int nr = (orows - 1) * p.sh + p.R;
+    const int pitch = p.W + 2 * (p.R / 2);
+    const int region = (2 * kCPH * nr * pitch + 3) / 4 * 4;
+    const int vec = p.W % 4 == 0 ? 4 : p.W % 2 == 0 ? 2 : 1;
+    const long elems = (long)2 * kCPH * std::min(nr, p.H) * p.W;
+    const long slots = (elems / vec + 63) / 64;
+    if (slots > kMaxSlots) return false;
+    if (elems >= (1 << 22)) return false;                    // fast_div range
+    if ((size_t)p.N * p.IC * p.H * p.W >= ((size_t)1 << 30) || (size_t)p.OC * p.K >= ((size_t)1 << 30))
+        return false;                                        // 32-bit byte offsets
+    int nw = slots <= kMaxBig ? 16 : 8;
+    auto lds_for = [&](int w) {
+        return std::max((size_t)w * (region + kWRegion) * 4, (size_t)w * 16 * kPartPitch * 4);
+    };
+    while (nw > 1 && (p.IC % (2 * kCPH * nw) != 0 || lds_for(nw) > 160 * 1024)) nw >>= 1;
+    const size_t lds = lds_for(nw);
+    if (lds > 160 * 1024) return false;
+    if ((long)p.N * ((OHW + 31) / 32) * ((p.OC + 31) / 32) >= (1L << 31)) return false;
+    // Deep reductions on few tiles (C9, C10, C12 at batch 1: 32 to 56 tiles, 4 to 8 passes of
+    // about 3.6 us each, the matrix pipes of a few CUs doing all the work): slices of the
+    // reduction go to different workgroups, their sums to the workspace, and the reduce launch of
+    // the generic kernel adds them in a fixed order.  A second launch costs about 4 us, so only
+    // from three passes on.
+    const int passes = p.IC / (2 * kCPH * nw);
+    const long wgs = (long)p.N * ((OHW + 31) / 32) * ((p.OC + 31) / 32);
+    int ksplit = 1;
+    if (passes >= 3 && wgs < kComputeUnits) {
+        ksplit = passes;
+        while (ksplit > 1 && (passes % ksplit != 0 || wgs * (ksplit / 2) >= 2 * kComputeUnits)) --ksplit;
+    }
+    plan->nw = nw;
+    plan->ksplit = ksplit;
+    plan->passes = passes / ksplit;
+    plan->workspace_bytes = ksplit > 1 ? (size_t)ksplit * p.npix * p.OC * sizeof(float) : 0;
+    plan->pitch = pitch;
+    plan->region = region;
+    plan->vec = vec;
+    plan->lds_bytes = lds;
+    return true;
+}
+
+bool conv_f32_small_pointers_ok(const ConvPointers &ptr)
+{
+    return reinterpret_cast<uintptr_t>(ptr.x) % 16 == 0 && reinterpret_cast<uintptr_t>(ptr.w) % 4 == 0;
+}
+
+tvg_status launch_conv_f32_small(const ConvProblem &p, const F32SmallPlan &plan, const ConvPointers &ptr,
+                                 hipStream_t stream)
+{
+    F32Args a;
+    a.x = static_cast<const float *>(ptr.x); a.w = static_cast<const float *>(ptr.w);
+    a.scale = ptr.scale; a.shift = ptr.shift; a.bias = ptr.bias;
+    a.residual = static_cast<const float *>(ptr.residual); a.y = static_cast<float *>(ptr.y);
+    a.N = p.N; a.IC = p.IC; a.H = p.H; a.W = p.W; a.OC = p.OC; a.OH = p.OH; a.OW = p.OW;
+    a.relu = p.relu;
+    a.mtiles = (p.OC + 31) / 32;
+    a.tpi = (p.OH * p.OW + 31) / 32;
+    a.nw = plan.nw; a.passes = plan.passes; a.pitch = plan.pitch; a.region = plan.region;
+    a.ksplit = plan.ksplit; a.ws = ptr.workspace;
+    a.vec_out = (p.OH * p.OW) % 4 == 0 && reinterpret_cast<uintptr_t>(ptr.y) % 16 == 0 &&
+                reinterpret_cast<uintptr_t>(ptr.residual) % 16 == 0;
+    a.x_bytes = (uint32_t)((size_t)p.N * p.IC * p.H * p.W * 4);
+    a.w_bytes = (uint32_t)((size_t)p.OC * p.IC * p.R * p.S * 4);
+    const dim3 grid((unsigned)((long)a.mtiles * a.tpi * p.N), (unsigned)plan.ksplit);
+    const int vec = plan.vec;
+    tvg_status st;
+    if (p.R == 3) st = p.sh == 1 ? launch_rs<3, 1>(a, vec, grid, plan.lds_bytes, stream)
+                                 : launch_rs<3, 2>(a, vec, grid, plan.lds_bytes, stream);
+    else st = p.sh == 1 ? launch_rs<1, 1>(a, vec, grid, plan.lds_bytes, stream)
+                        : launch_rs<1, 2>(a, vec, grid, plan.lds_bytes, stream);
+    if (st != TVG_OK || plan.ksplit == 1) return st;
+    return launch_splitk_reduce(p, plan.ksplit, ptr, stream);
+}
+
+}  // namespace tvg

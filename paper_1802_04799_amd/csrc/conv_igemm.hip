@@ -351,6 +351,22 @@ ConvPlan plan_conv(const ConvProblem &p, bool allow_split)
     return plan;
 }
 
+tvg_status launch_splitk_reduce(const ConvProblem &p, int splits, const ConvPointers &ptr,
+                                hipStream_t stream)
+{
+    IgemmArgs a{};
+    a.scale = ptr.scale; a.shift = ptr.shift; a.bias = ptr.bias;
+    a.residual = ptr.residual; a.y = ptr.y; a.ws = ptr.workspace;
+    a.OC = p.OC; a.OH = p.OH; a.OW = p.OW; a.npix = p.npix; a.relu = p.relu;
+    a.splits = splits;
+    const int total = p.npix * p.OC;
+    if (p.dtype == TVG_BF16)
+        hipLaunchKernelGGL((splitk_reduce_kernel<bf16_t>), dim3((total + 255) / 256), dim3(256), 0, stream, a);
+    else
+        hipLaunchKernelGGL((splitk_reduce_kernel<float>), dim3((total + 255) / 256), dim3(256), 0, stream, a);
+    return hipGetLastError() == hipSuccess ? TVG_OK : TVG_ERR_LAUNCH;
+}
+
 tvg_status launch_conv_igemm(const ConvProblem &p, const ConvPlan &plan, const ConvPointers &ptr,
                              hipStream_t stream)
 {

@@ -128,6 +128,24 @@ bool plan_dwpw(const ConvProblem &dw, int OC, DwPwPlan *plan);
 tvg_status launch_dwpw(const ConvProblem &dw, int OC, int pw_relu, int pw_stream_out,
                        const DwPwPlan &plan, const DwPwPointers &ptr, hipStream_t stream);
 
+// fp32 1x1 / 3x3 kernel for launch-bound problems: one launch, the waves of a workgroup split the
+// reduction and add their accumulators through LDS.
+struct F32SmallPlan {
+    int nw, passes;     // waves per workgroup, passes over the input channels
+    int pitch, region;  // LDS row pitch and floats per wave
+    int vec;            // floats per patch load: 4, 2 or 1 (rows of 4n, 2n, other pixel counts)
+    int ksplit;         // slices of the reduction across workgroups (1 = none, else a reduce launch follows)
+    size_t lds_bytes, workspace_bytes;
+};
+// Adds `splits` partial results [splits][N][OC][OH][OW] in ptr.workspace in a fixed order and
+// applies the fused tail (the second launch of every reduction that is split across workgroups).
+tvg_status launch_splitk_reduce(const ConvProblem &p, int splits, const ConvPointers &ptr,
+                                hipStream_t stream);
+bool plan_conv_f32_small(const ConvProblem &p, F32SmallPlan *plan);
+bool conv_f32_small_pointers_ok(const ConvPointers &ptr);
+tvg_status launch_conv_f32_small(const ConvProblem &p, const F32SmallPlan &plan, const ConvPointers &ptr,
+                                 hipStream_t stream);
+
 tvg_status launch_conv_igemm(const ConvProblem &p, const ConvPlan &plan, const ConvPointers &ptr,
                              hipStream_t stream);
 tvg_status launch_dwconv3x3(const ConvProblem &p, const ConvPointers &ptr, hipStream_t stream);

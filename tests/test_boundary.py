@@ -139,8 +139,9 @@ def test_workspace_query_and_too_small_workspace():
     # a large-batch problem fills the chip without splitting the reduction
     big = desc(n=64, c=64, h=56, w=56, k=64, dtype=tvg.TVG_BF16)
     assert tvg.tvg_conv2d_workspace_size(big) == 0
-    # the last ResNet-18 shape at batch 1 has 49 pixels: the reduction is partitioned
-    small = desc(n=1, c=512, h=7, w=7, k=512)
+    # 49 pixels at batch 1, and input channels that are no multiple of 8 (so that the generic
+    # kernel runs the problem, not the one-launch fp32 kernel): the reduction is partitioned
+    small = desc(n=1, c=508, h=7, w=7, k=512)
     need = tvg.tvg_conv2d_workspace_size(small)
     assert need > 0 and need % (512 * 49 * 4) == 0
     assert tvg.tvg_conv2d_fused(small, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, None, 0, 0) == 4
@@ -160,7 +161,7 @@ def test_static_scratch_entry_point_validates_on_the_host():
     assert tvg.tvg_conv2d_fused_static(desc(dtype=5), FAKE, FAKE, FAKE, FAKE, None, None, FAKE, 0) == 3
     assert tvg.tvg_conv2d_fused_static(desc(), FAKE, None, FAKE, FAKE, None, None, FAKE, 0) == 1
     assert tvg.load().tvg_conv2d_fused_static(None, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, None) == 1
-    big = desc(n=1, c=512, h=28, w=28, k=512)
+    big = desc(n=1, c=516, h=28, w=28, k=512)
     assert tvg.tvg_conv2d_workspace_size(big) > tvg.tvg_static_scratch_bytes()
     assert tvg.tvg_conv2d_fused_static(big, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, 0) == 4
 
@@ -191,7 +192,10 @@ def test_tile_table_sets_overrides_and_forgets():
                                         stride_w=2, pad_h=3, pad_w=3, dtype=tvg.TVG_BF16))[0] == 3
     assert tvg.tvg_conv2d_get_plan(desc(n=64, c=128, h=28, w=28, k=256, r=1, s=1, stride_h=2,
                                         stride_w=2, pad_h=0, pad_w=0, dtype=tvg.TVG_BF16)) == (4, 128, 64)
-    assert tvg.tvg_conv2d_get_plan(desc(n=1, c=64, h=56, w=56, k=64))[0] == 0
+    assert tvg.tvg_conv2d_get_plan(desc(n=1, c=64, h=56, w=56, k=64)) == (5, 32, 32)     # fp32, launch-bound
+    assert tvg.tvg_conv2d_get_plan(desc(n=1, c=60, h=56, w=56, k=64))[0] == 0            # channels not 8n
+    assert tvg.tvg_conv2d_get_plan(desc(n=64, c=64, h=56, w=56, k=64))[0] == 0           # fills the chip
+    assert tvg.tvg_conv2d_get_plan(desc(n=1, c=64, h=56, w=56, k=64, r=5, s=5, pad_h=2, pad_w=2))[0] == 0
 
 
 def test_block_entry_point_validates_on_the_host():
@@ -271,7 +275,7 @@ def test_knob_table_host_side():
     c9 = desc(n=64, c=256, h=14, w=14, k=256, dtype=tvg.TVG_BF16)
     assert tvg.tvg_conv2d_get_knobs(c9) == (64, 256, 2, 1, 2, 0)
     # the generic kernel: the size query follows the split
-    f = desc(n=1, c=512, h=7, w=7, k=512)
+    f = desc(n=1, c=508, h=7, w=7, k=512)
     auto = tvg.tvg_conv2d_workspace_size(f)
     k0 = tvg.tvg_conv2d_get_knobs(f)
     assert k0[2:] == (2, 32, 0, 0) and auto == 32 * 512 * 49 * 4
@@ -281,6 +285,17 @@ def test_knob_table_host_side():
     assert tvg.tvg_conv2d_workspace_size(f) == 0
     assert tvg.tvg_conv2d_set_knobs(f, None) == 0
     assert tvg.tvg_conv2d_workspace_size(f) == auto
+    # the one-launch fp32 kernel: its waves split the reduction; a caller who fixes the generic
+    # kernel's knobs gets the generic kernel
+    g = desc(n=1, c=512, h=7, w=7, k=512)
+    # (8 waves per workgroup x 8 slices across workgroups, the slices' sums in the workspace)
+    assert tvg.tvg_conv2d_get_plan(g)[0] == 5 and tvg.tvg_conv2d_get_knobs(g) == (0, 0, 1, 64, 0, 0)
+    assert tvg.tvg_conv2d_workspace_size(g) == 8 * 512 * 49 * 4
+    c2 = desc(n=1, c=64, h=56, w=56, k=64)           # one pass: one launch, no workspace
+    assert tvg.tvg_conv2d_get_knobs(c2) == (0, 0, 1, 8, 0, 0) and tvg.tvg_conv2d_workspace_size(c2) == 0
+    assert tvg.tvg_conv2d_set_knobs(g, (0, 0, 0, 4, 0, 0)) == 0
+    assert tvg.tvg_conv2d_get_plan(g)[0] == 0 and tvg.tvg_conv2d_workspace_size(g) == 4 * 512 * 49 * 4
+    assert tvg.tvg_conv2d_set_knobs(g, None) == 0
     for bad in [(64, 100, 0, 0, 0, 0), (0, 0, 3, 0, 0, 0), (0, 0, 0, 33, 0, 0), (0, 0, 0, -1, 0, 0),
                 (0, 0, 0, 0, 3, 0), (0, 0, 0, 0, 0, 3)]:
         assert tvg.tvg_conv2d_set_knobs(c6, bad) == 3

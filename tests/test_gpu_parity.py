@@ -360,6 +360,37 @@ def test_bf16_1x1_kernel_unaligned_input(tvg):
         check(to_host(y), want, "bf16", off)
 
 
+F32_SMALL = [
+    # fp32 launch-bound problems for the one-launch kernel (1x1 / 3x3, "same" padding, input
+    # channels a multiple of 8): n, ic, h, w, oc, k, stride.  Rows of 4n pixels (16-byte copies)
+    # and others, 1 to 16 waves per workgroup, one and several passes, ragged channel and pixel
+    # tails, tiles at the top and bottom image borders, several images.
+    (1, 64, 56, 56, 64, 3, 1), (1, 64, 56, 56, 128, 3, 2), (1, 128, 28, 28, 128, 3, 1),
+    (1, 256, 14, 14, 512, 3, 2), (1, 512, 7, 7, 512, 3, 1), (1, 64, 56, 56, 64, 1, 1),
+    (1, 256, 14, 14, 512, 1, 2), (2, 8, 9, 11, 33, 3, 1), (3, 24, 5, 6, 70, 3, 2),
+    (1, 40, 1, 1, 5, 3, 1), (2, 16, 12, 8, 40, 1, 1), (1, 136, 7, 9, 64, 3, 1),
+    (2, 1024, 7, 7, 48, 1, 1), (1, 32, 30, 64, 16, 3, 1), (3, 48, 13, 16, 130, 3, 2),
+    (1, 8, 2, 3, 1, 1, 2), (4, 64, 4, 4, 96, 3, 1), (1, 16, 33, 4, 8, 3, 1),
+]
+
+
+@pytest.mark.parametrize("cfg", F32_SMALL, ids=lambda c: "x".join(map(str, c)))
+def test_fp32_small_kernel_shapes(tvg, cfg):
+    n, ic, h, w, oc, k, stride = cfg
+    sh = ti.ConvShape("f32s", n, ic, h, w, oc, k, k, stride, k // 2)
+    desc = tvg.ConvDesc(n, ic, h, w, oc, k, k, stride, stride, k // 2, k // 2, tvg.TVG_F32, 0)
+    assert tvg.tvg_conv2d_get_plan(desc)[0] == 5, "expected the fp32 kernel for launch-bound problems"
+    inp = ti.make_inputs(sh, 17000 + sum(cfg), "f32", residual=True, bias=True)
+    y1 = to_host(run_dense(tvg, sh, inp, "f32"))
+    y2 = to_host(run_dense(tvg, sh, inp, "f32"))
+    assert np.array_equal(y1, y2)                                # deterministic
+    check(y1, oracle_dense(sh, inp), "f32", cfg)
+    plain = ti.make_inputs(sh, 17500 + sum(cfg), "f32")
+    y3 = to_host(run_dense(tvg, sh, plain, "f32", relu=False))
+    check(y3, oracle_dense(sh, plain, relu=False), "f32", cfg)
+    assert (y3 < 0).any()
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_rectangular_filter_and_strides(tvg, dtype):
     import torch

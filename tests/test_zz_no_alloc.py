@@ -37,12 +37,14 @@ def both_entry_points(tvg, sh, inp, dtype):
 def test_static_scratch_entry_point_two_calls_in_a_row(tvg):
     import torch
     assert tvg.tvg_static_scratch_bytes() == 16 << 20
-    # first call: C2 at batch 1, fp32 (reduction split nine ways, 7.2 MB of partials);
-    # second call: C12 at batch 1 (3.2 MB), then a small ragged problem (a few KB) - each finds
-    # the previous call's partials in the array
-    calls = [(ti.resnet18_convs(1)[1], ti.layer_seed(2, 1), "f32"),
-             (ti.resnet18_convs(1)[11], ti.layer_seed(2, 11), "f32"),
-             (ti.ConvShape("small", 1, 40, 5, 6, 70, 3, 3, 1, 1), 31, "f32"),
+    # Problems whose reduction the generic kernel splits across workgroups (fp32 shapes the
+    # one-launch fp32 kernel does not take: a 7x7 filter, input channels no multiple of 8).
+    # first call: C1 at batch 1 (6.4 MB of partials); then 512 x 100 channels on a 7x7 map
+    # (1.4 MB), then a small ragged problem (42 KB) - each finds the previous call's partials in
+    # the array; last a bf16 problem that needs none
+    calls = [(ti.resnet18_convs(1)[0], ti.layer_seed(2, 0), "f32"),
+             (ti.ConvShape("mid", 1, 100, 7, 7, 512, 3, 3, 1, 1), 30, "f32"),
+             (ti.ConvShape("small", 1, 36, 5, 6, 70, 3, 3, 1, 1), 31, "f32"),
              (ti.ConvShape("small16", 2, 64, 6, 5, 33, 3, 3, 2, 1), 32, "bf16")]
     needs = []
     for sh, seed, dtype in calls:
@@ -66,11 +68,11 @@ def test_static_scratch_entry_point_without_a_split_and_beyond_the_limit(tvg):
     need, y_static, y_ws = both_entry_points(tvg, sh, inp, "bf16")
     assert need == 0 and torch.equal(y_static, y_ws)
     # a problem whose partials exceed the array: an error code, nothing launched
-    big = tvg.ConvDesc(1, 512, 28, 28, 512, 3, 3, 1, 1, 1, 1, tvg.TVG_F32, 0)
+    big = tvg.ConvDesc(1, 516, 28, 28, 512, 3, 3, 1, 1, 1, 1, tvg.TVG_F32, 0)
     assert tvg.tvg_conv2d_workspace_size(big) > tvg.tvg_static_scratch_bytes()
     y = torch.full((1, 512, 28, 28), 7.0, device="cuda:0")
-    x = torch.zeros((1, 512, 28, 28), device="cuda:0")
-    w = torch.zeros((512, 512, 3, 3), device="cuda:0")
+    x = torch.zeros((1, 516, 28, 28), device="cuda:0")
+    w = torch.zeros((512, 516, 3, 3), device="cuda:0")
     s = torch.ones(512, device="cuda:0")
     assert tvg.tvg_conv2d_fused_static(big, x, w, s, s, None, None, y) == 4
     torch.cuda.synchronize()
