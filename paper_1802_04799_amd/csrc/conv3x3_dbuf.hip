@@ -695,9 +695,11 @@ bool plan_conv3x3_dbuf(const ConvProblem &p, Patch3x3Plan *plan)
     // (odd rows of at most 7 pixels, stride 1, one task per thread: whole rows by one 16-byte load
     // from the aligned address below the row's start, see the kernel's UNAL)
     int px = p.W % 8 == 0 ? 8 : p.W % 4 == 0 ? 4 : p.W % 2 != 0 ? 1 : p.W >= 6 ? 4 : 2;
-    // (measured on C12: 27.4 us against 25.6 with element loads - not the default)
+    // (C12 at batch 64, found by the knob search: whole rows + one wave group + padded pitch 23.1 us;
+    // element loads + two wave groups 25.9; element loads + one group 28.1; whole rows with the
+    // plain pitch 28.1 - the 4-byte stores of a row's pieces then collide)
     const bool odd_rows = px == 1;
-    const bool unal = px == 1 && p.W <= 7 && p.sh == 1 && 8 * plan->rows <= 512 && plan->want_rows == 2;
+    const bool unal = px == 1 && p.W <= 7 && p.sh == 1 && 8 * plan->rows <= 512 && plan->want_rows != 1;
     if (unal) px = 8;
     // (unaligned rows: four tasks per row and octet, each two channels)
     const int pt = unal ? (8 * plan->rows + 255) / 256
@@ -728,7 +730,7 @@ bool plan_conv3x3_dbuf(const ConvProblem &p, Patch3x3Plan *plan)
     // Rule (measured at batch 64, warm): it pays where the rows are odd and fetched element by
     // element (C12: 28.1 -> 25.6 us), it loses on C9 (20.9 -> 21.4 us, and the four stages cost C9
     // the conflict-free pitch: 19.7 us with it); tvg_conv2d_set_knobs overrides the rule.
-    const bool kg_rule = plan->want_kg == 2 || (plan->want_kg == 0 && odd_rows);
+    const bool kg_rule = plan->want_kg == 2 || (plan->want_kg == 0 && odd_rows && !unal);
     if (p.sh == 1 && plan->tiles <= kComputeUnits && plan->nt >= 128 && p.IC % (4 * kChunk) == 0 &&
         p.IC >= 8 * kChunk && kg_rule) {
         const int mi = plan->nt == 256 ? 2 : 1;

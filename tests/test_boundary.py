@@ -265,11 +265,11 @@ def test_knob_table_host_side():
     assert tvg.tvg_conv2d_get_knobs(c6)[:3] == (64, 64, 1)
     assert tvg.tvg_conv2d_set_knobs(c6, None) == 0
     assert tvg.tvg_conv2d_get_knobs(c6) == (64, 256, 2, 1, 2, 0)
-    # C12 at batch 64: odd 7-pixel rows, 200 tiles: two wave groups by rule, element loads
+    # C12 at batch 64: odd 7-pixel rows, 200 tiles: by rule whole-row loads, one wave group, padded pitch
     c12 = desc(n=64, c=512, h=7, w=7, k=512, dtype=tvg.TVG_BF16)
-    assert tvg.tvg_conv2d_get_knobs(c12) == (64, 128, 2, 2, 2, 1)
-    assert tvg.tvg_conv2d_set_knobs(c12, (0, 0, 2, 1, 0, 2)) == 0
-    assert tvg.tvg_conv2d_get_knobs(c12)[2:] == (2, 1, 2, 2)
+    assert tvg.tvg_conv2d_get_knobs(c12) == (64, 128, 2, 1, 2, 2)
+    assert tvg.tvg_conv2d_set_knobs(c12, (0, 0, 2, 0, 0, 1)) == 0       # element loads: two wave groups
+    assert tvg.tvg_conv2d_get_knobs(c12)[2:] == (2, 2, 2, 1)
     assert tvg.tvg_conv2d_set_knobs(c12, None) == 0
     # C9 at batch 64: a lone workgroup per CU keeps the padded pitch (86 KB of LDS), one group
     c9 = desc(n=64, c=256, h=14, w=14, k=256, dtype=tvg.TVG_BF16)
