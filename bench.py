@@ -414,6 +414,12 @@ def main():
             out["resnet18_body"]["ms_separate_tensors"] = bench_body(
                 tvg, ti, torch, np, dev, to_dev, time_loop, iters=50, warmup=20, graph=False,
                 use_arena=False)["ms"]
+        # the same body with every down-sampling block's first conv and projection shortcut as
+        # one two-head launch: 18 launches (FLOPs counted as for the 21-launch chain)
+        fused = bench_body(tvg, ti, torch, np, dev, to_dev, time_loop, iters=50, warmup=20,
+                           use_arena=not args.no_arena, fuse_projection=True)
+        out["resnet18_body"]["two_head_blocks"] = {k: fused[k] for k in
+                                                   ("launches", "ms", "graph_replay_ms", "images_per_s", "tflops")}
         # MobileNet body, batch 32, bf16: stem + 13 x (depthwise 3x3, 1x1), 27 launches
         out["mobilenet_body"] = bench_body(tvg, ti, torch, np, dev, to_dev, time_loop, "mobilenet",
                                            iters=50, warmup=20, use_arena=not args.no_arena,
@@ -493,12 +499,13 @@ def measured_traffic(kernel):
 
 
 def bench_body(tvg, ti, torch, np, dev, to_dev, time_loop, network="resnet18", iters=10, warmup=3,
-               graph=True, use_arena=True, tune_tiles=False):
+               graph=True, use_arena=True, tune_tiles=False, fuse_projection=False):
     n = 32
     config = 5 if network == "resnet18" else 6
-    steps = ti.resnet18_body(n) if network == "resnet18" else ti.mobilenet_body(n)
+    steps = ti.resnet18_body(n, fuse_projection) if network == "resnet18" else ti.mobilenet_body(n)
+    plain = ti.resnet18_body(n) if network == "resnet18" else steps
     weights = {s.layer_index: ti.make_weights(s.shape, ti.layer_seed(config, s.layer_index), "bf16")
-               for s in steps if s.op != "maxpool"}
+               for s in plain if s.op != "maxpool"}
     dw = {k: {"w": to_dev(p["w"], True), "scale": to_dev(p["scale"], False),
               "shift": to_dev(p["shift"], False)} for k, p in weights.items()}
     images = to_dev(ti.body_images(n, ti.layer_seed(config, 901)), True)
@@ -529,6 +536,23 @@ def bench_body(tvg, ti, torch, np, dev, to_dev, time_loop, network="resnet18", i
             p = dw[st.layer_index]
             calls.append((tvg.tvg_dwconv2d_fused, (desc, src, p["w"], p["scale"], p["shift"], None,
                                                    None, y, None, 0, None)))
+        elif st.op == "conv_dual":
+            # a down-sampling block's first conv and its 1x1 projection (the centre tap of a 3x3
+            # filter, weights joined once up front: constant folding) as one two-head launch
+            sh, s2 = st.shape, st.shape2
+            p1, p2 = weights[st.layer_index], weights[st.layer_index2]
+            emb = np.zeros((s2.oc, s2.ic, 3, 3), np.float32)
+            emb[:, :, 1, 1] = p2["w"][:, :, 0, 0]
+            wj = to_dev(np.concatenate([p1["w"], emb]), True)
+            scj = to_dev(np.concatenate([p1["scale"], p2["scale"]]), False)
+            sfj = to_dev(np.concatenate([p1["shift"], p2["shift"]]), False)
+            desc = tvg.ConvDesc(sh.n, sh.ic, sh.h, sh.w, sh.oc + s2.oc, 3, 3, sh.stride, sh.stride, 1, 1,
+                                tvg.TVG_BF16, tvg.TVG_RELU if st.relu else 0)
+            y = planned(st.dst, sh.y_shape())
+            tensors[st.dst2] = planned(st.dst2, s2.y_shape())
+            calls.append((tvg.tvg_conv2d_fused_dual,
+                          (desc, sh.oc, (tvg.TVG_RELU if st.relu2 else 0) | tvg.TVG_CENTRE_TAP_ONLY, src,
+                           wj, scj, sfj, None, None, y, tensors[st.dst2], None)))
         elif st.op == "conv":
             sh = st.shape
             desc = tvg.ConvDesc(sh.n, sh.ic, sh.h, sh.w, sh.oc, sh.r, sh.s, sh.stride, sh.stride,
@@ -570,7 +594,7 @@ def bench_body(tvg, ti, torch, np, dev, to_dev, time_loop, network="resnet18", i
         with torch.cuda.graph(g, stream=torch.cuda.Stream()):
             forward()
         graph_ms = time_loop(g.replay, 10)
-    flops = sum(s.shape.flops for s in steps if s.op != "maxpool")
+    flops = sum(s.shape.flops for s in plain if s.op != "maxpool")
     return {"batch": n, "launches": len(calls), "tiles_changed_by_tuning": tuned, "arena": use_arena, "arena_mb": round(arena_bytes / 1e6, 1),
             "unplanned_mb": round(sum(lives[t][0] for t in ids) / 1e6, 1), "ms": round(ms, 4), "graph_replay_ms": round(graph_ms, 4) if graph else None,
             "tflops": round(flops / (ms * 1e-3) / 1e12, 1),

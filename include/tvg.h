@@ -72,6 +72,8 @@ typedef enum { TVG_F32 = 0, TVG_BF16 = 1 } tvg_dtype;
  *                 stores (the generic kernel that takes fp32 and odd shapes, the element-wise
  *                 tail of unaligned maps) ignore it. */
 enum { TVG_RELU = 1u, TVG_STREAM_OUT = 2u };
+/* Only in the flags2 argument of tvg_conv2d_fused_dual: see there. */
+enum { TVG_CENTRE_TAP_ONLY = 4u };
 
 typedef struct {
     int32_t n, c, h, w;        /* input N, C (= IC), H, W                                   */
@@ -110,6 +112,33 @@ tvg_status tvg_conv2d_fused(const tvg_conv_desc *desc, const void *x, const void
                             const float *scale, const float *shift, const float *bias,
                             const void *residual, void *y,
                             void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Two fused convolutions of the SAME input in one launch (Section 3, operator fusion, applied to
+ * sibling operators that share their input): bf16, 3x3, pad 1, stride 1 or 2, c a multiple of 16.
+ * desc describes both together, desc->k = k1 + k2 output channels with weights [k1 + k2][c][3][3]
+ * and scale, shift, bias of k1 + k2 entries:
+ *   head 1   channels [0, k1): y1 [n][k1][oh][ow], tail with desc->flags and residual1
+ *            ([n][k1][oh][ow] or NULL)
+ *   head 2   channels [k1, k1 + k2): y2 [n][k2][oh][ow], tail with flags2 (TVG_RELU,
+ *            TVG_STREAM_OUT), no residual
+ * What it is for: the down-sampling block of a residual network, whose first 3x3 stride-2
+ * convolution and whose 1x1 stride-2 projection shortcut read the same tensor.  A 1x1 convolution
+ * with stride s and no padding is the centre tap of a 3x3 convolution with stride s and pad 1, so
+ * the projection rides along as head 2 with filters that are zero outside their centre tap
+ * (w[k1 + j][i][1][1] = the 1x1 weight, the caller builds the tensor once); TVG_CENTRE_TAP_ONLY in
+ * flags2 is the caller's promise of exactly that, and head 2's tiles then skip the other eight
+ * taps.  Without the flag head 2 is a full 3x3 convolution.  One launch and one pass over x
+ * instead of two.
+ * Errors: TVG_ERR_BAD_SHAPE unless 0 < k1 < desc->k; TVG_ERR_UNSUPPORTED for problems outside the
+ * single-stage 3x3 kernel (other dtype, filter, padding; k1 no multiple of 64; x or w not
+ * 16-byte aligned) - run the two convolutions separately then.  y1, y2 must not overlap x, w or
+ * each other.  No workspace.
+ */
+tvg_status tvg_conv2d_fused_dual(const tvg_conv_desc *desc, int32_t k1, uint32_t flags2,
+                                 const void *x, const void *w, const float *scale,
+                                 const float *shift, const float *bias, const void *residual1,
+                                 void *y1, void *y2, void *hip_stream);
 
 /*
  * tvg_conv2d_fused for callers that cannot allocate device memory and so have no workspace to

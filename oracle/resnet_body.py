@@ -36,6 +36,18 @@ def run_steps(steps, images: np.ndarray, weights: Dict[int, dict], store_bf16: b
             sh = st.shape
             y64 = dwconv2d_fused(src, p["w"], p["scale"], p["shift"], None, None,
                                  stride=(sh.stride, sh.stride), pad=(sh.pad, sh.pad), relu=st.relu)
+        elif st.op == "conv_dual":
+            # two convolutions of the same input recorded as one launch: by definition the two
+            # operators evaluated separately (the 1x1 one with no padding), each stored on its own
+            p2, s2 = weights[st.layer_index2], st.shape2
+            y2 = conv2d_fused(src, p2["w"], p2["scale"], p2["shift"], None, None,
+                              stride=(s2.stride, s2.stride), pad=(s2.pad, s2.pad), relu=st.relu2)
+            tensors[st.dst2] = round_to_bf16(y2) if store_bf16 else y2.astype(np.float32)
+            if on_step is not None:
+                on_step(st, y2)
+            p, sh = weights[st.layer_index], st.shape
+            y64 = conv2d_fused(src, p["w"], p["scale"], p["shift"], None, None,
+                               stride=(sh.stride, sh.stride), pad=(sh.pad, sh.pad), relu=st.relu)
         elif st.op == "maxpool":
             y64 = maxpool2d(src, k=3, stride=2, pad=1)
         else:

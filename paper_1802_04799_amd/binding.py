@@ -11,6 +11,7 @@ _LIB_PATH = os.path.join(HERE, "libtvg.so")
 TVG_F32, TVG_BF16 = 0, 1
 TVG_RELU = 1
 TVG_STREAM_OUT = 2      # hint: nothing reads y soon, store it past the caches
+TVG_CENTRE_TAP_ONLY = 4  # flags2 of tvg_conv2d_fused_dual: head 2's filters are zero off the centre tap
 TVG_OK = 0
 
 
@@ -84,6 +85,8 @@ def load() -> ctypes.CDLL:
     for f in (lib.tvg_conv2d_fused, lib.tvg_dwconv2d_fused):
         f.restype = ctypes.c_int
         f.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.tvg_conv2d_fused_dual.restype = ctypes.c_int
+    lib.tvg_conv2d_fused_dual.argtypes = [dp, ctypes.c_int32, ctypes.c_uint32] + [vp] * 9
     lib.tvg_conv2d_fused_static.restype = ctypes.c_int
     lib.tvg_conv2d_fused_static.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.tvg_static_scratch_bytes.restype = sz
@@ -206,6 +209,13 @@ def tvg_conv2d_fused(desc, x, w, scale, shift, bias, residual, y, workspace=None
     return int(load().tvg_conv2d_fused(ctypes.byref(desc), _addr(x), _addr(w), _addr(scale),
                                        _addr(shift), _addr(bias), _addr(residual), _addr(y),
                                        _addr(workspace), workspace_bytes, _stream(stream)))
+
+
+def tvg_conv2d_fused_dual(desc, k1, flags2, x, w, scale, shift, bias, residual1, y1, y2, stream=None) -> int:
+    """Two fused 3x3 convolutions of the same input in one launch (see include/tvg.h)."""
+    return int(load().tvg_conv2d_fused_dual(ctypes.byref(desc), int(k1), int(flags2), _addr(x), _addr(w),
+                                            _addr(scale), _addr(shift), _addr(bias), _addr(residual1),
+                                            _addr(y1), _addr(y2), _stream(stream)))
 
 
 def tvg_conv2d_fused_static(desc, x, w, scale, shift, bias, residual, y, stream=None) -> int:

@@ -365,6 +365,26 @@ tvg_status tvg_conv2d_fused(const tvg_conv_desc *desc, const void *x, const void
     return tvg::launch_conv_igemm(p, plan, ptr, stream);
 }
 
+tvg_status tvg_conv2d_fused_dual(const tvg_conv_desc *desc, int32_t k1, uint32_t flags2,
+                                 const void *x, const void *w, const float *scale,
+                                 const float *shift, const float *bias, const void *residual1,
+                                 void *y1, void *y2, void *hip_stream)
+{
+    ConvProblem p;
+    tvg_status st = make_problem(desc, false, &p);
+    if (st != TVG_OK) return st;
+    if (k1 < 1 || k1 >= p.OC) return TVG_ERR_BAD_SHAPE;
+    if (flags2 & ~(uint32_t)(TVG_RELU | TVG_STREAM_OUT | TVG_CENTRE_TAP_ONLY)) return TVG_ERR_UNSUPPORTED;
+    if (!x || !w || !scale || !shift || !y1 || !y2) return TVG_ERR_NULL;
+    tvg::Patch3x3Plan plan;
+    if (!tvg::plan_conv3x3_patch(p, &plan, k1)) return TVG_ERR_UNSUPPORTED;
+    const tvg::ConvPointers ptr{x, w, scale, shift, bias, residual1, y1, nullptr};
+    if (!tvg::conv3x3_patch_pointers_ok(ptr)) return TVG_ERR_UNSUPPORTED;
+    const tvg::DualHead dual{k1, (int)((flags2 & TVG_RELU ? 1 : 0) | (flags2 & TVG_STREAM_OUT ? 2 : 0)),
+                             (flags2 & TVG_CENTRE_TAP_ONLY) ? 1 : 0, y2};
+    return tvg::launch_conv3x3_patch(p, plan, ptr, static_cast<hipStream_t>(hip_stream), &dual);
+}
+
 tvg_status tvg_conv2d_fused_static(const tvg_conv_desc *desc, const void *x, const void *w,
                                    const float *scale, const float *shift, const float *bias,
                                    const void *residual, void *y, void *hip_stream)

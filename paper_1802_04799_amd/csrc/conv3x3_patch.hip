@@ -47,6 +47,12 @@ struct PatchArgs {
     uint32_t x_bytes, w_bytes;
     int ss_offset;    // byte offset in LDS of the staged (scale, offset) pairs
     int ntiles, m_major;
+    // Two heads (tvg_conv2d_fused_dual): output channels [0, oc1) go to y with `relu` and the
+    // residual, channels [oc1, OC) to y2 with relu2; oc1 = 0: one head.  centre2: the filters of
+    // head 2 are zero outside their centre tap (a 1x1 convolution of the same input), its tiles
+    // skip the other eight taps.  A tile lies within one head (oc1 is a multiple of MT).
+    int oc1, relu2, centre2;
+    bf16_t *y2;
 };
 
 constexpr int kPosBytes = 48;    // 16 channels (32 B) + 16 B padding: conflict-free 16-byte reads
@@ -65,7 +71,8 @@ __device__ __forceinline__ uint32_t half_of(uint32_t d, int hi) { return hi ? d 
 // MT x NT output tile per workgroup of 256 threads; PT = patch load tasks per thread; PX =
 // horizontally adjacent pixels fetched per load (2, 4 or 8 need W to be a multiple: 32-, 64- or
 // 128-bit loads, a half to an eighth of the vector memory instructions).
-template <int MT, int NT, int STRIDE, int PT, int PX>
+// DUAL = the two-head variant (instances exist for the 64-channel tiles of 128 and 256 pixels).
+template <int MT, int NT, int STRIDE, int PT, int PX, bool DUAL = false>
 __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a)
 {
     // four waves as 2 x 2, or 1 x 4 for the wide 64 x 256 tile (the weights of a chunk weigh
@@ -281,6 +288,8 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
     store_chunk();
     __syncthreads();
 
+    const bool head2 = DUAL && m0 >= a.oc1;                 // (uniform)
+    const bool centre_only = head2 && a.centre2 != 0;
     const unsigned char *Abase = As + (wm * WTM + lrow) * kPosBytes + lhalf * 16;
     for (int c = 0; c < nchunks; ++c) {
         // All of the next chunk's loads are issued before this chunk's MFMAs: measured, issuing
@@ -300,6 +309,17 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
             for (int j = 0; j < NJ; ++j)
                 bf[slot][j] = *reinterpret_cast<const uint4v *>(Ps + pb[j] + toff);
         };
+        if (centre_only) {
+            // a 1x1 convolution riding in a 3x3 launch: the centre tap alone
+            fetch(4, 0);
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        __builtin_bit_cast(bf16x8v, bf[0][j]),
+                        __builtin_bit_cast(bf16x8v, af[0][i]), acc[i][j], 0, 0, 0);
+        } else {
         fetch(0, 0);
 #pragma unroll
         for (int tap = 0; tap < 9; ++tap) {
@@ -317,6 +337,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
             if (tap + 1 < 9) __builtin_amdgcn_sched_group_barrier(0x100, MI + NJ, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, MI * NJ, 0);
         }
+        }
 
         if (c + 1 < nchunks) {
             __syncthreads();
@@ -330,7 +351,15 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
     // up to two tiles per wave are staged at a time: 20 KB, less than any instance's operands
     constexpr int BT = MI * NJ >= 2 ? 2 : 1;
     unsigned char *stage = smem + wave * (BT * kStageBytes);
-    const TailArgs tail{a.scale, a.shift, a.bias, a.residual, a.y, a.OC, OHW, a.npix, a.relu};
+    if (head2) {
+        // head 2: its own tensor of OC - oc1 channels, no residual, its own ReLU and store hint
+        const TailArgs tail2{a.scale, a.shift, a.bias, nullptr, a.y2, a.OC - a.oc1, OHW, a.npix, a.relu2};
+        store_acc_tiles_batched<MI, NJ, BT>(acc, stage, lane, m0 - a.oc1 + wm * WTM, n0 + wn * WTN,
+                                            tail2, a.vmode, ss_lds, wm * WTM);
+        return;
+    }
+    const TailArgs tail{a.scale, a.shift, a.bias, a.residual, a.y, DUAL ? a.oc1 : a.OC, OHW,
+                        a.npix, a.relu};
     store_acc_tiles_batched<MI, NJ, BT>(acc, stage, lane, m0 + wm * WTM, n0 + wn * WTN, tail,
                                         a.vmode, ss_lds, wm * WTM);
 }
@@ -353,10 +382,10 @@ int max_patch_rows(const ConvProblem &p, int nt)
     return best;
 }
 
-template <int MT, int NT, int STRIDE, int PT, int PX>
-tvg_status launch_instance(const PatchArgs &a, int ntiles, size_t lds, hipStream_t stream)
+template <int MT, int NT, int STRIDE, int PT, int PX, bool DUAL = false>
+tvg_status launch_instance_d(const PatchArgs &a, int ntiles, size_t lds, hipStream_t stream)
 {
-    auto kernel = conv3x3_patch_kernel<MT, NT, STRIDE, PT, PX>;
+    auto kernel = conv3x3_patch_kernel<MT, NT, STRIDE, PT, PX, DUAL>;
     static bool configured = false;      // opt in to > 64 KB of dynamic LDS once per instance
     if (!configured) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
@@ -366,6 +395,16 @@ tvg_status launch_instance(const PatchArgs &a, int ntiles, size_t lds, hipStream
     }
     hipLaunchKernelGGL(kernel, dim3((unsigned)(a.mtiles * ntiles)), dim3(256), lds, stream, a);
     return hipGetLastError() == hipSuccess ? TVG_OK : TVG_ERR_LAUNCH;
+}
+
+template <int MT, int NT, int STRIDE, int PT, int PX>
+tvg_status launch_instance(const PatchArgs &a, int ntiles, size_t lds, hipStream_t stream)
+{
+    if (a.oc1 > 0) {
+        if constexpr (MT == 64 && NT >= 128) return launch_instance_d<MT, NT, STRIDE, PT, PX, true>(a, ntiles, lds, stream);
+        else return TVG_ERR_UNSUPPORTED;
+    }
+    return launch_instance_d<MT, NT, STRIDE, PT, PX, false>(a, ntiles, lds, stream);
 }
 
 template <int MT, int NT, int STRIDE>
@@ -408,13 +447,15 @@ bool conv3x3_patch_pointers_ok(const ConvPointers &ptr)
     return reinterpret_cast<uintptr_t>(ptr.w) % 16 == 0 && reinterpret_cast<uintptr_t>(ptr.x) % 16 == 0;
 }
 
-bool plan_conv3x3_patch(const ConvProblem &p, Patch3x3Plan *plan)
+bool plan_conv3x3_patch(const ConvProblem &p, Patch3x3Plan *plan, int single_stage_mt_divides)
 {
     if (p.dtype != TVG_BF16 || p.R != 3 || p.S != 3 || p.ph != 1 || p.pw != 1) return false;
     if (p.sh != p.sw || (p.sh != 1 && p.sh != 2)) return false;
     if (p.IC % kChunk != 0) return false;
     if (p.npix >= (1 << 22) || (long)p.N * (p.H + 2) >= (1 << 22)) return false;   // fast_div range
-    const Knobs knobs = forced_knobs(p);
+    // (two-head launches: the single-stage kernel only, channel tiles that divide head 1)
+    const bool dual = single_stage_mt_divides > 0;
+    const Knobs knobs = dual ? Knobs{0, 0, 1, 0, 0, 0} : forced_knobs(p);
     const int force_mt = knobs.mt, force_nt = knobs.nt;
     const bool use_dbuf = knobs.stages != 1;
     // Tile choice (measured on MI355X at batch 64): take the largest tile that still gives at
@@ -427,6 +468,7 @@ bool plan_conv3x3_patch(const ConvProblem &p, Patch3x3Plan *plan)
     for (const auto &c : cands) {
         const int mt = c[0], nt = c[1];
         if (mt == 128 && p.OC <= 64) continue;
+        if (dual && (mt != 64 || nt < 128 || single_stage_mt_divides % mt != 0)) continue;
         if (force_mt && mt != force_mt) continue;
         if (force_nt && nt != force_nt) continue;
         const int rows = max_patch_rows(p, nt);
@@ -451,6 +493,7 @@ bool plan_conv3x3_patch(const ConvProblem &p, Patch3x3Plan *plan)
         const long tiles = (long)((p.OC + mt - 1) / mt) * ((p.npix + nt - 1) / nt);
         Patch3x3Plan cand{mt, nt, pt, px, rows, lds, tiles, 0, 0, 0, 0, 0, 1,
                           knobs.split_k, knobs.lds_pitch, knobs.row_loads, knobs.stages};
+        if (dual && nt == 256 && pt > 1) continue;    // (those two-head instances run out of registers)
         if (!(use_dbuf && plan_conv3x3_dbuf(p, &cand))) {
             if (knobs.stages == 2) continue;      // the caller asked for the pipelined kernel
             if (pt > 8 || lds > 80 * 1024) continue;
@@ -471,10 +514,14 @@ bool plan_conv3x3_patch(const ConvProblem &p, Patch3x3Plan *plan)
 }
 
 tvg_status launch_conv3x3_patch(const ConvProblem &p, const Patch3x3Plan &plan,
-                                const ConvPointers &ptr, hipStream_t stream)
+                                const ConvPointers &ptr, hipStream_t stream, const DualHead *dual)
 {
-    if (plan.dbuf) return launch_conv3x3_dbuf(p, plan, ptr, stream);
+    if (plan.dbuf) return dual ? TVG_ERR_UNSUPPORTED : launch_conv3x3_dbuf(p, plan, ptr, stream);
     PatchArgs a;
+    a.oc1 = dual ? dual->oc1 : 0;
+    a.relu2 = dual ? dual->relu2 : 0;
+    a.centre2 = dual ? dual->centre2 : 0;
+    a.y2 = dual ? static_cast<bf16_t *>(dual->y2) : nullptr;
     a.x = static_cast<const bf16_t *>(ptr.x); a.w = static_cast<const bf16_t *>(ptr.w);
     a.scale = ptr.scale; a.shift = ptr.shift; a.bias = ptr.bias;
     a.residual = static_cast<const bf16_t *>(ptr.residual); a.y = static_cast<bf16_t *>(ptr.y);
@@ -482,6 +529,8 @@ tvg_status launch_conv3x3_patch(const ConvProblem &p, const Patch3x3Plan &plan,
     a.npix = p.npix; a.relu = p.relu | (p.stream_out << 1);
     a.mtiles = (p.OC + plan.mt - 1) / plan.mt;
     a.vmode = pick_store_vmode(p.dtype, p.OH * p.OW, ptr.y, ptr.residual);
+    if (dual && pick_store_vmode(p.dtype, p.OH * p.OW, dual->y2, nullptr) < a.vmode)
+        a.vmode = pick_store_vmode(p.dtype, p.OH * p.OW, dual->y2, nullptr);
     a.ss_offset = (int)(plan.lds_bytes - (size_t)plan.mt * 8);
     a.x_bytes = (uint32_t)((size_t)p.N * p.IC * p.H * p.W * 2);
     a.w_bytes = (uint32_t)((size_t)p.OC * p.IC * 9 * 2);

@@ -80,10 +80,18 @@ struct Patch3x3Plan {
 
 // True when the problem is one the patch kernel is built for (bf16, 3x3, pad 1,
 // stride 1 or 2, IC a multiple of 16).  Pointer alignment is checked at launch.
-bool plan_conv3x3_patch(const ConvProblem &p, Patch3x3Plan *plan);
+// single_stage_mt_divides > 0 (two-head launches): plan the single-stage kernel only, with a
+// channel tile that divides this number (the channels of head 1).
+bool plan_conv3x3_patch(const ConvProblem &p, Patch3x3Plan *plan, int single_stage_mt_divides = 0);
 bool conv3x3_patch_pointers_ok(const ConvPointers &ptr);
+// The second head of a two-head launch: output channels [oc1, OC) go to y2 with their own flags.
+struct DualHead {
+    int oc1, relu2, centre2;     // relu2: bit 0 ReLU, bit 1 store hint
+    void *y2;
+};
 tvg_status launch_conv3x3_patch(const ConvProblem &p, const Patch3x3Plan &plan,
-                                const ConvPointers &ptr, hipStream_t stream);
+                                const ConvPointers &ptr, hipStream_t stream,
+                                const DualHead *dual = nullptr);
 // Two-stage variant (64-channel tiles): completes a plan whose mt, nt and rows are set.
 bool plan_conv3x3_dbuf(const ConvProblem &p, Patch3x3Plan *plan);
 tvg_status launch_conv3x3_dbuf(const ConvProblem &p, const Patch3x3Plan &plan,

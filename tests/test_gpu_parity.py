@@ -490,6 +490,31 @@ def test_maxpool_is_exact(tvg, dtype, shape):
     assert np.array_equal(to_host(y), oracle.maxpool2d(x))
 
 
+def dual_params(weights, st):
+    """Constant folding for a two-head step: the 3x3 filters of head 1 and the 1x1 filters of head 2
+    (placed at the centre tap of zero 3x3 filters) as one weight tensor, scale and shift joined."""
+    p1, p2 = weights[st.layer_index], weights[st.layer_index2]
+    k2, c = p2["w"].shape[:2]
+    emb = np.zeros((k2, c, 3, 3), np.float32)
+    emb[:, :, 1, 1] = p2["w"][:, :, 0, 0]
+    return {"w": np.concatenate([p1["w"], emb]), "scale": np.concatenate([p1["scale"], p2["scale"]]),
+            "shift": np.concatenate([p1["shift"], p2["shift"]])}
+
+
+def run_dual(tvg, st, src, p):
+    """One tvg_conv2d_fused_dual launch for a "conv_dual" step; p = device tensors of dual_params."""
+    import torch
+    sh, s2 = st.shape, st.shape2
+    desc = tvg.ConvDesc(sh.n, sh.ic, sh.h, sh.w, sh.oc + s2.oc, 3, 3, sh.stride, sh.stride, 1, 1,
+                        tvg.TVG_BF16, tvg.TVG_RELU if st.relu else 0)
+    y1 = torch.empty(sh.y_shape(), dtype=torch.bfloat16, device="cuda:0")
+    y2 = torch.empty(s2.y_shape(), dtype=torch.bfloat16, device="cuda:0")
+    flags2 = (tvg.TVG_RELU if st.relu2 else 0) | tvg.TVG_CENTRE_TAP_ONLY
+    rc = tvg.tvg_conv2d_fused_dual(desc, sh.oc, flags2, src, p["w"], p["scale"], p["shift"], None, None, y1, y2)
+    assert rc == 0, tvg.status_string(rc)
+    return y1, y2
+
+
 def run_body_gpu(tvg, steps, images, weights):
     import torch
     tensors = {0: to_dev(images, "bf16")}
@@ -497,7 +522,10 @@ def run_body_gpu(tvg, steps, images, weights):
              for k, p in weights.items()}
     for st in steps:
         src = tensors[st.src]
-        if st.op == "conv":
+        if st.op == "conv_dual":
+            p = {n: to_dev(v, "bf16" if n == "w" else "f32") for n, v in dual_params(weights, st).items()}
+            tensors[st.dst], tensors[st.dst2] = run_dual(tvg, st, src, p)
+        elif st.op == "conv":
             p = dev_w[st.layer_index]
             res = None if st.residual is None else tensors[st.residual]
             tensors[st.dst] = tvg.conv2d_fused(src, p["w"], p["scale"], p["shift"], None, res,
@@ -573,6 +601,85 @@ def test_config5_resnet18_body_bf16_small_batch_full(tvg):
     assert rms <= 2e-2
     assert worst <= 8e-2
     assert abs(bias_se) <= 4.0
+
+
+DUAL_SHAPES = [
+    # n, c, h, w, k1, k2, stride: the ResNet-18 down-sampling blocks (C4+C5, C7+C8, C10+C11) and
+    # ragged cases: pixel tails, a head 2 that is no multiple of the tile, odd maps, stride 1
+    (2, 64, 56, 56, 128, 128, 2), (2, 128, 28, 28, 256, 256, 2), (3, 256, 14, 14, 512, 512, 2),
+    (3, 16, 9, 11, 64, 40, 1), (2, 32, 10, 13, 128, 70, 2), (5, 48, 7, 7, 64, 1, 1),
+    (1, 16, 30, 70, 192, 33, 2), (7, 32, 7, 7, 64, 64, 2), (2, 16, 2, 3, 64, 16, 2),
+]
+
+
+@pytest.mark.parametrize("centre_only", [True, False])
+@pytest.mark.parametrize("cfg", DUAL_SHAPES, ids=lambda c: "x".join(map(str, c)))
+def test_two_head_conv(tvg, cfg, centre_only):
+    """tvg_conv2d_fused_dual: head 1 against the oracle's 3x3 convolution (bias, residual, ReLU),
+    head 2 against the oracle's 1x1 convolution of the same input with the same stride (centre
+    tap only) or against a full 3x3 convolution (no promise about the filters); bit-identical
+    reruns."""
+    import torch
+    n, c, h, w, k1, k2, stride = cfg
+    s1 = ti.ConvShape("h1", n, c, h, w, k1, 3, 3, stride, 1)
+    s2 = ti.ConvShape("h2", n, c, h, w, k2, 1, 1, stride, 0) if centre_only else \
+        ti.ConvShape("h2", n, c, h, w, k2, 3, 3, stride, 1)
+    a = ti.make_inputs(s1, 19000 + sum(cfg), "bf16", residual=True, bias=True)
+    b = ti.make_inputs(s2, 19500 + sum(cfg), "bf16", bias=True)
+    w2 = b["w"]
+    if centre_only:
+        w2 = np.zeros((k2, c, 3, 3), np.float32)
+        w2[:, :, 1, 1] = b["w"][:, :, 0, 0]
+    cat = lambda u, v: np.concatenate([u, v])
+    x = to_dev(a["x"], "bf16")
+    dw, dsc, dsf, dbi = (to_dev(cat(a["w"], w2), "bf16"), to_dev(cat(a["scale"], b["scale"]), "f32"),
+                         to_dev(cat(a["shift"], b["shift"]), "f32"), to_dev(cat(a["bias"], b["bias"]), "f32"))
+    res = to_dev(a["residual"], "bf16")
+    desc = tvg.ConvDesc(n, c, h, w, k1 + k2, 3, 3, stride, stride, 1, 1, tvg.TVG_BF16, tvg.TVG_RELU)
+    outs = []
+    for rep in range(2):
+        y1 = torch.full(s1.y_shape(), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+        y2 = torch.full(s2.y_shape(), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+        rc = tvg.tvg_conv2d_fused_dual(desc, k1, tvg.TVG_CENTRE_TAP_ONLY if centre_only else 0, x, dw,
+                                       dsc, dsf, dbi, res, y1, y2)
+        assert rc == 0, tvg.status_string(rc)
+        torch.cuda.synchronize()
+        outs.append((y1, y2))
+    assert torch.equal(outs[0][0].view(torch.int16), outs[1][0].view(torch.int16))
+    assert torch.equal(outs[0][1].view(torch.int16), outs[1][1].view(torch.int16))
+    a["x"] = b["x"] = a["x"]
+    check(to_host(outs[0][0]), oracle_dense(s1, a), "bf16", ("head 1", cfg))
+    b["x"] = a["x"]
+    check(to_host(outs[0][1]), oracle_dense(s2, b, relu=False), "bf16", ("head 2", cfg))
+    assert (to_host(outs[0][1]) < 0).any()
+
+
+@pytest.mark.parametrize("batch", [2, 32])
+def test_config5_resnet18_body_with_two_head_blocks(tvg, batch):
+    """The ResNet-18 chain with each down-sampling block's first conv and projection shortcut as
+    ONE two-head launch (18 launches): every tensor bit-identical to the 21-launch chain (the
+    same products are summed in the same order), and, at the stated tolerance and the tight
+    bound, every layer against the oracle fed with the GPU's own input of that layer."""
+    import torch
+    plain, fused = ti.resnet18_body(batch), ti.resnet18_body(batch, fuse_projection=True)
+    weights = body_weights(plain)
+    images = ti.body_images(batch, ti.layer_seed(5, 903))
+    want = run_body_gpu(tvg, plain, images, weights)
+    got = run_body_gpu(tvg, fused, images, weights)
+    for k in want:
+        same = torch.equal(got[k].view(torch.int16), want[k].view(torch.int16))
+        assert same, f"tensor {k} differs between the fused and the plain chain"
+    host = {k: v.float().cpu().numpy() for k, v in got.items()}
+    del got, want
+    for st in fused:
+        if st.op != "conv_dual":
+            continue
+        for shape, lidx, dst, relu in ((st.shape, st.layer_index, st.dst, st.relu),
+                                       (st.shape2, st.layer_index2, st.dst2, st.relu2)):
+            p = weights[lidx]
+            ref = oracle.conv2d_fused(host[st.src], p["w"], p["scale"], p["shift"], None, None,
+                                      stride=(shape.stride,) * 2, pad=(shape.pad,) * 2, relu=relu)
+            check(host[dst], ref, "bf16", (st.name, shape.name))
 
 
 def test_tuner_fixes_a_tile_and_results_stay_right(tvg, tmp_path):

@@ -553,3 +553,26 @@ def test_chain_runner_mobilenet_body_against_hand_composition():
     assert differs(got, x) < 1e-3
     rho = float(np.sqrt(np.mean(x * x)))
     assert rho > 0.01 and np.max(np.abs(got - x)) <= 1e-2 * rho
+
+
+def test_chain_runner_two_head_steps_equal_the_separate_steps():
+    """The ResNet-18 launch list with the down-sampling blocks' first conv and projection recorded
+    as one two-head step (18 launches) yields, tensor by tensor, what the 21-launch list yields:
+    the two-head step is by definition the two operators evaluated separately."""
+    from oracle.resnet_body import run_steps
+    plain, fused = ti.resnet18_body(1), ti.resnet18_body(1, fuse_projection=True)
+    assert len(plain) == 21 and len(fused) == 18
+    assert sum(s.op == "conv_dual" for s in fused) == 3
+    for s in fused:
+        if s.op == "conv_dual":          # a 3x3 and a 1x1 of the same input, same stride and outputs
+            assert (s.shape.r, s.shape2.r, s.shape2.pad) == (3, 1, 0) and s.shape.stride == s.shape2.stride == 2
+            assert s.shape.x_shape() == s.shape2.x_shape() and s.shape.y_shape() == s.shape2.y_shape()
+            assert s.relu and not s.relu2
+    W = {s.layer_index: ti.make_weights(s.shape, ti.layer_seed(5, s.layer_index), "bf16")
+         for s in plain if s.op == "conv"}
+    img = ti.body_images(1, ti.layer_seed(5, 997))
+    a, b = run_steps(plain, img, W), run_steps(fused, img, W)
+    assert sorted(a) == sorted(b)
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k
+    assert ti.tensor_lives(plain).keys() == ti.tensor_lives(fused).keys()

@@ -184,7 +184,7 @@ def config1_shape() -> ConvShape:
 @dataclass(frozen=True)
 class Step:
     """One launch of a network body: tensors are named by small integer ids."""
-    op: str                      # "conv", "dwconv" or "maxpool"
+    op: str                      # "conv", "dwconv", "maxpool" or "conv_dual"
     name: str
     src: int
     dst: int
@@ -192,10 +192,20 @@ class Step:
     residual: Optional[int] = None
     relu: bool = True
     layer_index: int = 0         # index used for the layer's weight seed
+    # "conv_dual": a 3x3 conv (shape, relu, layer_index -> dst) and a 1x1 conv of the same input
+    # with the same stride (shape2, relu2, layer_index2 -> dst2) as one launch
+    dst2: Optional[int] = None
+    shape2: Optional[ConvShape] = None
+    relu2: bool = False
+    layer_index2: int = 0
 
 
-def resnet18_body(n: int = 32) -> List[Step]:
+def resnet18_body(n: int = 32, fuse_projection: bool = False) -> List[Step]:
     """ResNet-18 convolutional body as a flat launch list (tensor 0 = the images).
+
+    fuse_projection: a down-sampling block's first conv and its projection shortcut, which read
+    the same tensor, become ONE "conv_dual" step (18 launches instead of 21); tensor ids, layer
+    indices and therefore every weight stay those of the unfused list.
 
     Stem conv (C1) + ReLU, 3x3 stride-2 pad-1 max-pool, then 8 basic blocks:
     conv-scale/shift-ReLU, conv-scale/shift + shortcut, ReLU.  Down-sampling
@@ -223,6 +233,12 @@ def resnet18_body(n: int = 32) -> List[Step]:
     t = pooled
 
     def basic_block(tag, t_in, first, second, proj=None) -> int:
+        if proj is not None and fuse_projection:
+            a, shortcut = new_tensor(), new_tensor()
+            steps.append(Step("conv_dual", f"{tag}.conv1+proj", t_in, a, first, None, True, counter["l"],
+                              shortcut, proj, False, counter["l"] + 1))
+            counter["l"] += 2
+            return conv(f"{tag}.conv2", second, a, residual=shortcut)
         a = conv(f"{tag}.conv1", first, t_in)
         shortcut = t_in if proj is None else conv(f"{tag}.proj", proj, t_in, relu=False)
         return conv(f"{tag}.conv2", second, a, residual=shortcut)
@@ -278,6 +294,9 @@ def tensor_lives(steps: List[Step], elem_bytes: int = 2):
         else:
             shapes[st.dst] = st.shape.y_shape()
         first[st.dst] = last[st.dst] = i
+        if st.op == "conv_dual":
+            shapes[st.dst2] = st.shape2.y_shape()
+            first[st.dst2] = last[st.dst2] = i
         for t in (st.src, st.residual):
             if t is not None:
                 last[t] = i
