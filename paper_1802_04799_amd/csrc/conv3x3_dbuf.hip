@@ -682,10 +682,29 @@ bool plan_conv3x3_dbuf(const ConvProblem &p, Patch3x3Plan *plan)
     // consecutive pixels; they are conflict-free when those words are consecutive modulo 16,
     // also across the end of an image row and of an image.  Stride 1: a pitch of W + 16 words
     // makes the step at a row end 1 (mod 16), and xp extra words between images do the same
-    // for the step from an image's last pixel to the next image's first.  Stride 2 keeps the
-    // plain pitch (even columns, then odd columns); so does stride 1 when the padded planes
-    // would cost the second workgroup per CU.
-    const int pwh = (p.W + 3) / 2;
+    // for the step from an image's last pixel to the next image's first.  Stride 1 keeps the
+    // plain pitch when the padded planes would cost the second workgroup per CU.
+    // Stride 2: the 16 lanes of an access read word (output row * 4 * pwh + output column) of one
+    // column half, so the step at the end of an output row is 4 * pwh - OW words; up to three
+    // spare words per half row are added where they make more of those 16 words fall into
+    // different banks (counted over the first four groups of 16 pixels of an image).
+    int pwh = (p.W + 3) / 2;
+    if (p.sh == 2 && plan->want_pitch != 1) {
+        int best_d = 0, best_n = -1;
+        for (int d = 0; d < 4; ++d) {
+            int distinct = 0;
+            for (int g = 0; g < 4; ++g) {
+                unsigned seen = 0;
+                for (int l = 0; l < 16; ++l) {
+                    const int pix = g * 16 + l, row = pix / p.OW, col = pix % p.OW;
+                    seen |= 1u << ((row * 4 * (pwh + d) + col) & 15);
+                }
+                distinct += __builtin_popcount(seen);
+            }
+            if (distinct > best_n) { best_n = distinct; best_d = d; }
+        }
+        pwh += best_d;
+    }
     const int images = (plan->nt - 1) / (p.OH * p.OW) + 1;     // image ends a tile can span
     int pws = p.sh == 2 ? 2 * pwh : p.W + 16;
     int xp = p.sh == 2 ? 0 : ((p.H * p.W - (p.H + 2) * pws) % 16 + 16) % 16;
