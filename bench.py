@@ -406,6 +406,44 @@ def main():
                               "frac_fp32_peak_warm": round(fl / tots["warm_us"] / 1e6 / PEAK_FP32_TFLOPS, 4),
                               "frac_fp32_achievable_warm": round(fl / tots["warm_us"] / 1e6 / ceilings["mfma_fp32_tflops"], 4),
                               "config1_C2": next(r for r in rows if r["name"] == "C2")}
+        # The pre-transformed-weights path (Winograd F(2x2,3x3); the paper's "TVM PT") beside the
+        # direct kernels on the 3x3 stride-1 layers at batch 64.  FLOPs are counted by the direct
+        # method for both (no discount for the multiplications Winograd saves); the weight
+        # transform runs once, outside the timed loop, as the paper's pre-transformation does.
+        wino_rows = []
+        for i, sh in enumerate(ti.resnet18_convs(64)):
+            if sh.r != 3 or sh.stride != 1:
+                continue
+            l = Layer(sh, ti.layer_seed(4, i), "bf16")
+            pb, wb = tvg.tvg_conv2d_prepack_size(l.desc)
+            packed = torch.empty(pb, dtype=torch.uint8, device=dev)
+            wws = torch.empty(wb, dtype=torch.uint8, device=dev)
+            if tvg.tvg_conv2d_prepack(l.desc, l.w[0], packed, pb) != 0:
+                raise RuntimeError("tvg_conv2d_prepack")
+            y2 = torch.empty_like(l.y[0])
+
+            def wino():
+                st = tvg.tvg_conv2d_fused_prepacked(l.desc, l.x[0], packed, l.scale, l.shift, None, None,
+                                                    y2, wws, wb, None)
+                if st != 0:
+                    raise RuntimeError(tvg.status_string(st))
+            t_direct = time_loop(l.launch, 200, warmup=200)
+            t_wino = time_loop(wino, 200, warmup=200)
+            diff = (l.y[0].float() - y2.float()).abs()
+            rho = l.y[0].float().pow(2).mean().sqrt()
+            rel = (diff / torch.maximum(l.y[0].float().abs(), rho)).max().item()
+            wino_rows.append({"name": sh.name, "direct_us": round(t_direct * 1e3, 2),
+                              "prepacked_us": round(t_wino * 1e3, 2),
+                              "direct_tflops": round(sh.flops / (t_direct * 1e-3) / 1e12, 1),
+                              "prepacked_tflops_direct_flop_count": round(sh.flops / (t_wino * 1e-3) / 1e12, 1),
+                              "packed_weights_mb": round(pb / 1e6, 2), "workspace_mb": round(wb / 1e6, 1),
+                              "max_rel_diff_to_direct": round(rel, 5)})
+            del l, packed, wws, y2
+        out["pretransformed_winograd"] = {
+            "layers": wino_rows,
+            "note": "tvg_conv2d_fused_prepacked (input transform + contraction with the inverse transform "
+                    "and the fused tail in registers) against tvg_conv2d_fused, same buffers back to back, "
+                    "warm; FLOPs by the direct count for both"}
         # ResNet-18 body, batch 32, bf16 (configs[4]): 20 convs + 1 max-pool, 21 launches
         out["resnet18_body"] = bench_body(tvg, ti, torch, np, dev, to_dev, time_loop, iters=50,
                                           warmup=20, use_arena=not args.no_arena,

@@ -141,6 +141,37 @@ tvg_status tvg_conv2d_fused_dual(const tvg_conv_desc *desc, int32_t k1, uint32_t
                                  void *y1, void *y2, void *hip_stream);
 
 /*
+ * Convolution with pre-transformed weights (Section 6.1: the "TVM PT" rows of the GPU operator
+ * benchmark - Winograd convolution whose weight transform is done once, ahead of time).
+ * bf16, 3x3, stride 1, pad 1, c and k multiples of 64: a 2x2 block of outputs is computed from a
+ * 4x4 block of inputs by Winograd's minimal filtering F(2x2, 3x3), 16 multiplications per input
+ * channel instead of 36.  Three calls:
+ *   tvg_conv2d_prepack_size     bytes of the packed weights and of the per-call workspace
+ *   tvg_conv2d_prepack          w [k][c][3][3] (device, bf16, 16-byte aligned) -> packed (device,
+ *                               16-byte aligned, at least packed_bytes): G g G^T of every filter in
+ *                               fp16, laid out as the contraction reads it.  Once per weight tensor.
+ *   tvg_conv2d_fused_prepacked  tvg_conv2d_fused with `packed` in place of w.  workspace: device,
+ *                               256-byte aligned, at least the queried size; it receives the
+ *                               transformed input (16 values per 2x2 output block and channel).
+ * Same definition of the operator as tvg_conv2d_fused (the fused tail included), different
+ * arithmetic: the transformed operands are fp16 (the sums of four bf16 inputs do not fit bf16's 8
+ * bits; fp16 keeps 11), accumulation, inverse transform and tail are fp32.  Results agree with
+ * the direct kernels within 1e-2 of the output's RMS instead of one bf16 rounding; inputs must
+ * satisfy 4 max|x| < 65504 (fp16's range), which the caller guarantees.
+ * Errors: TVG_ERR_UNSUPPORTED for every other problem (and for tensors beyond 2 GiB of
+ * transformed input); TVG_ERR_WORKSPACE for a short or misaligned packed / workspace buffer;
+ * otherwise as tvg_conv2d_fused.  The calls allocate nothing and never synchronise.
+ */
+tvg_status tvg_conv2d_prepack_size(const tvg_conv_desc *desc, size_t *packed_bytes,
+                                   size_t *workspace_bytes);
+tvg_status tvg_conv2d_prepack(const tvg_conv_desc *desc, const void *w, void *packed,
+                              size_t packed_bytes, void *hip_stream);
+tvg_status tvg_conv2d_fused_prepacked(const tvg_conv_desc *desc, const void *x, const void *packed,
+                                      const float *scale, const float *shift, const float *bias,
+                                      const void *residual, void *y, void *workspace,
+                                      size_t workspace_bytes, void *hip_stream);
+
+/*
  * tvg_conv2d_fused for callers that cannot allocate device memory and so have no workspace to
  * pass: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
  * Same operator, same kernels, same results bit for bit; the scratch that a split reduction

@@ -89,6 +89,12 @@ def load() -> ctypes.CDLL:
     lib.tvg_conv2d_fused_dual.argtypes = [dp, ctypes.c_int32, ctypes.c_uint32] + [vp] * 9
     lib.tvg_conv2d_fused_static.restype = ctypes.c_int
     lib.tvg_conv2d_fused_static.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.tvg_conv2d_prepack_size.restype = ctypes.c_int
+    lib.tvg_conv2d_prepack_size.argtypes = [dp, ctypes.POINTER(sz), ctypes.POINTER(sz)]
+    lib.tvg_conv2d_prepack.restype = ctypes.c_int
+    lib.tvg_conv2d_prepack.argtypes = [dp, vp, vp, sz, vp]
+    lib.tvg_conv2d_fused_prepacked.restype = ctypes.c_int
+    lib.tvg_conv2d_fused_prepacked.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.tvg_static_scratch_bytes.restype = sz
     lib.tvg_static_scratch_bytes.argtypes = []
     lib.tvg_probe_copy.restype = ctypes.c_int
@@ -223,6 +229,27 @@ def tvg_conv2d_fused_static(desc, x, w, scale, shift, bias, residual, y, stream=
     return int(load().tvg_conv2d_fused_static(ctypes.byref(desc), _addr(x), _addr(w), _addr(scale),
                                               _addr(shift), _addr(bias), _addr(residual), _addr(y),
                                               _stream(stream)))
+
+
+def tvg_conv2d_prepack_size(desc):
+    """Returns (packed_bytes, workspace_bytes) of the pre-transformed-weights path; raises on error."""
+    pb, wb = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    st = load().tvg_conv2d_prepack_size(ctypes.byref(desc), ctypes.byref(pb), ctypes.byref(wb))
+    if st != TVG_OK:
+        raise TvgError(st, "tvg_conv2d_prepack_size")
+    return int(pb.value), int(wb.value)
+
+
+def tvg_conv2d_prepack(desc, w, packed, packed_bytes, stream=None) -> int:
+    return int(load().tvg_conv2d_prepack(ctypes.byref(desc), _addr(w), _addr(packed), int(packed_bytes),
+                                         _stream(stream)))
+
+
+def tvg_conv2d_fused_prepacked(desc, x, packed, scale, shift, bias, residual, y, workspace,
+                               workspace_bytes, stream=None) -> int:
+    return int(load().tvg_conv2d_fused_prepacked(ctypes.byref(desc), _addr(x), _addr(packed), _addr(scale),
+                                                 _addr(shift), _addr(bias), _addr(residual), _addr(y),
+                                                 _addr(workspace), int(workspace_bytes), _stream(stream)))
 
 
 def tvg_static_scratch_bytes() -> int:

@@ -404,6 +404,53 @@ tvg_status tvg_conv2d_fused_static(const tvg_conv_desc *desc, const void *x, con
 
 size_t tvg_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
+tvg_status tvg_conv2d_prepack_size(const tvg_conv_desc *desc, size_t *packed_bytes, size_t *workspace_bytes)
+{
+    if (!packed_bytes || !workspace_bytes) return TVG_ERR_NULL;
+    ConvProblem p;
+    tvg_status st = make_problem(desc, false, &p);
+    if (st != TVG_OK) return st;
+    tvg::WinoPlan plan;
+    if (!tvg::plan_conv3x3_winograd(p, &plan)) return TVG_ERR_UNSUPPORTED;
+    *packed_bytes = plan.u_bytes;
+    *workspace_bytes = plan.v_bytes;
+    return TVG_OK;
+}
+
+tvg_status tvg_conv2d_prepack(const tvg_conv_desc *desc, const void *w, void *packed,
+                              size_t packed_bytes, void *hip_stream)
+{
+    ConvProblem p;
+    tvg_status st = make_problem(desc, false, &p);
+    if (st != TVG_OK) return st;
+    tvg::WinoPlan plan;
+    if (!tvg::plan_conv3x3_winograd(p, &plan)) return TVG_ERR_UNSUPPORTED;
+    if (!w || !packed) return TVG_ERR_NULL;
+    if (packed_bytes < plan.u_bytes || reinterpret_cast<uintptr_t>(packed) % 16 != 0) return TVG_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(w) % 16 != 0) return TVG_ERR_UNSUPPORTED;
+    return tvg::launch_winograd_prepack(p, w, packed, static_cast<hipStream_t>(hip_stream));
+}
+
+tvg_status tvg_conv2d_fused_prepacked(const tvg_conv_desc *desc, const void *x, const void *packed,
+                                      const float *scale, const float *shift, const float *bias,
+                                      const void *residual, void *y, void *workspace,
+                                      size_t workspace_bytes, void *hip_stream)
+{
+    ConvProblem p;
+    tvg_status st = make_problem(desc, false, &p);
+    if (st != TVG_OK) return st;
+    tvg::WinoPlan plan;
+    if (!tvg::plan_conv3x3_winograd(p, &plan)) return TVG_ERR_UNSUPPORTED;
+    if (!x || !packed || !scale || !shift || !y) return TVG_ERR_NULL;
+    if (!workspace || workspace_bytes < plan.v_bytes || reinterpret_cast<uintptr_t>(workspace) % 256 != 0)
+        return TVG_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(packed) % 16 != 0 || reinterpret_cast<uintptr_t>(x) % 2 != 0 ||
+        reinterpret_cast<uintptr_t>(y) % 2 != 0 || reinterpret_cast<uintptr_t>(residual) % 2 != 0)
+        return TVG_ERR_UNSUPPORTED;
+    const tvg::ConvPointers ptr{x, nullptr, scale, shift, bias, residual, y, static_cast<float *>(workspace)};
+    return tvg::launch_conv3x3_winograd(p, plan, packed, ptr, static_cast<hipStream_t>(hip_stream));
+}
+
 tvg_status tvg_dwconv2d_fused(const tvg_conv_desc *desc, const void *x, const void *w,
                               const float *scale, const float *shift, const float *bias,
                               const void *residual, void *y, void *workspace,

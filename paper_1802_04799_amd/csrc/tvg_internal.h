@@ -154,6 +154,21 @@ bool conv_f32_small_pointers_ok(const ConvPointers &ptr);
 tvg_status launch_conv_f32_small(const ConvProblem &p, const F32SmallPlan &plan, const ConvPointers &ptr,
                                  hipStream_t stream);
 
+// bf16 3x3 stride-1 pad-1 convolution by Winograd F(2x2, 3x3) with pre-transformed weights
+// (IC and OC multiples of 64).  The packed weights are u_bytes of fp16, the per-call workspace
+// (the transformed input) v_bytes.
+struct WinoPlan {
+    int TH, TW, T;      // 2x2 output tiles per image column, row, and in all
+    int nb;             // 32-tile blocks per wave (1: the workgroup covers 64 channels x 64 tiles)
+    long tiles;
+    size_t u_bytes, v_bytes;
+};
+bool plan_conv3x3_winograd(const ConvProblem &p, WinoPlan *plan);
+tvg_status launch_winograd_prepack(const ConvProblem &p, const void *w, void *packed, hipStream_t stream);
+// ptr.w is unused (the weights come packed), ptr.workspace is the transformed-input area.
+tvg_status launch_conv3x3_winograd(const ConvProblem &p, const WinoPlan &plan, const void *packed,
+                                   const ConvPointers &ptr, hipStream_t stream);
+
 tvg_status launch_conv_igemm(const ConvProblem &p, const ConvPlan &plan, const ConvPointers &ptr,
                              hipStream_t stream);
 tvg_status launch_dwconv3x3(const ConvProblem &p, const ConvPointers &ptr, hipStream_t stream);

@@ -166,6 +166,40 @@ def test_static_scratch_entry_point_validates_on_the_host():
     assert tvg.tvg_conv2d_fused_static(big, FAKE, FAKE, FAKE, FAKE, None, None, FAKE, 0) == 4
 
 
+def test_prepacked_entry_points_validate_on_the_host():
+    """tvg_conv2d_prepack_size / prepack / fused_prepacked: sizes are a pure function of the
+    descriptor, everything else is rejected before any device call (this machine has no GPU)."""
+    d = desc(n=2, c=128, h=9, w=7, k=64, dtype=tvg.TVG_BF16)
+    pb, wb = tvg.tvg_conv2d_prepack_size(d)
+    assert pb == 16 * 128 * 64 * 2                         # [16 positions][c][k] fp16
+    assert wb == 16 * 128 * (2 * 5 * 4) * 2                # [16 positions][c][2x2 output tiles] fp16
+    for kw in (dict(stride_h=2, stride_w=2), dict(c=32), dict(k=96), dict(dtype=tvg.TVG_F32),
+               dict(r=1, s=1, pad_h=0, pad_w=0), dict(pad_h=0, pad_w=0), dict(n=8192, h=512, w=512)):
+        f = dict(n=2, c=128, h=9, w=7, k=64, dtype=tvg.TVG_BF16)
+        f.update(kw)
+        with pytest.raises(tvg.TvgError) as e:
+            tvg.tvg_conv2d_prepack_size(desc(**f))
+        assert e.value.status == 3, kw
+        assert tvg.tvg_conv2d_prepack(desc(**f), FAKE, FAKE, 1 << 30, 0) == 3
+        assert tvg.tvg_conv2d_fused_prepacked(desc(**f), FAKE, FAKE, FAKE, FAKE, None, None, FAKE,
+                                              FAKE * 16, 1 << 40, 0) == 3
+    with pytest.raises(tvg.TvgError) as e:
+        tvg.tvg_conv2d_prepack_size(desc(n=0, dtype=tvg.TVG_BF16))
+    assert e.value.status == 2
+    lib = tvg.load()
+    assert lib.tvg_conv2d_prepack_size(ctypes.byref(d), None, None) == 1
+    A = 0x10000                                             # 256-byte aligned fake pointer
+    assert tvg.tvg_conv2d_prepack(d, None, A, pb, 0) == 1
+    assert tvg.tvg_conv2d_prepack(d, A, A, pb - 1, 0) == 4
+    assert tvg.tvg_conv2d_prepack(d, A, A + 8, pb, 0) == 4
+    assert tvg.tvg_conv2d_prepack(d, A + 8, A, pb, 0) == 3          # w must be 16-byte aligned
+    assert tvg.tvg_conv2d_fused_prepacked(d, A, A, A, A, None, None, None, A, wb, 0) == 1
+    assert tvg.tvg_conv2d_fused_prepacked(d, A, A, A, A, None, None, A, None, 0, 0) == 4
+    assert tvg.tvg_conv2d_fused_prepacked(d, A, A, A, A, None, None, A, A, wb - 1, 0) == 4
+    assert tvg.tvg_conv2d_fused_prepacked(d, A, A, A, A, None, None, A, A + 128, wb, 0) == 4
+    assert tvg.tvg_conv2d_fused_prepacked(d, A, A + 8, A, A, None, None, A, A, wb, 0) == 3
+
+
 def test_tile_table_sets_overrides_and_forgets():
     """tvg_conv2d_set_tile / tvg_conv2d_get_plan are host-only: the planners' choice, a fixed
     tile, its removal, and what is rejected."""
