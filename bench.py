@@ -62,6 +62,9 @@ def parse():
     ap.add_argument("--batch1-probe", action="store_true",
                     help="only launch the batch-1 configurations (C1..C12 fp32, D1..D9 fp32) "
                          "--steps times each over rotating buffers (for profiler runs)")
+    ap.add_argument("--winograd-probe", action="store_true",
+                    help="only launch the pre-transformed-weights path on C2, C6, C9, C12 at batch 64 "
+                         "--warmup + --steps times each (for profiler runs)")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
                     help="only run a plain device copy of this many MiB --steps times "
                          "(reference for scaling FETCH_SIZE / WRITE_SIZE counters)")
@@ -199,6 +202,24 @@ def main():
                 del l
         print(json.dumps({"batch1_probe": "C1..C12, D1..D9, fp32, batch 1, rotating buffers",
                           "launches_each": args.warmup + args.steps}))
+        return
+    if args.winograd_probe:
+        for i, sh in enumerate(ti.resnet18_convs(64)):
+            if sh.r != 3 or sh.stride != 1:
+                continue
+            l = Layer(sh, ti.layer_seed(4, i), "bf16")
+            pb, wb = tvg.tvg_conv2d_prepack_size(l.desc)
+            packed = torch.empty(pb, dtype=torch.uint8, device=dev)
+            wws = torch.empty(wb, dtype=torch.uint8, device=dev)
+            tvg.tvg_conv2d_prepack(l.desc, l.w[0], packed, pb)
+            for k in range(args.warmup + args.steps):
+                st = tvg.tvg_conv2d_fused_prepacked(l.desc, l.x[0], packed, l.scale, l.shift, None, None,
+                                                    l.y[0], wws, wb, None)
+                if st != 0:
+                    raise RuntimeError(tvg.status_string(st))
+            torch.cuda.synchronize()
+            del l, packed, wws
+        print(json.dumps({"winograd_probe": "C2, C6, C9, C12 batch 64 bf16", "launches_each": args.warmup + args.steps}))
         return
     if args.body_probe:
         r = bench_body(tvg, ti, torch, np, dev, to_dev, time_loop, args.body_probe,

@@ -207,8 +207,14 @@ __global__ __launch_bounds__(256, 2) void wino_gemm_kernel(const WinoArgs a)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave & 1, wn = wave >> 1;
     const int lrow = lane & 31, lhalf = lane >> 5;
-    const int m0 = (blockIdx.x % a.mtiles) * kMT;
-    const int t0 = (blockIdx.x / a.mtiles) * NT;
+    // Workgroups are dealt to the eight XCDs in turn; renumbered so that one XCD gets a contiguous
+    // run of tiles, the channel tiles of one tile range (which read the same transformed input)
+    // share that XCD's L2 instead of each fetching it from HBM (C6: 105 -> 57 MB fetched).
+    const int nbk = gridDim.x, bid = blockIdx.x;
+    const int xq = nbk >> 3, xr = nbk & 7, xcd = bid & 7, local = bid >> 3;
+    const int tile = xcd < xr ? xcd * (xq + 1) + local : xr * (xq + 1) + (xcd - xr) * xq + local;
+    const int m0 = (tile % a.mtiles) * kMT;
+    const int t0 = (tile / a.mtiles) * NT;
 
     stage_scale_shift(ss_lds, m0, kMT, a.scale, a.shift, a.bias, a.OC, tid, 256);
 
