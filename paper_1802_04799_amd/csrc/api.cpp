@@ -209,7 +209,7 @@ static tvg_status store_knobs(const ConvProblem &p, const tvg::Knobs &k)
 
 static bool known_tile(int mt, int nt)
 {
-    return (mt == 64 && (nt == 256 || nt == 128 || nt == 64)) || (mt == 128 && (nt == 128 || nt == 64));
+    return (mt == 64 && (nt == 256 || nt == 128 || nt == 64)) || (mt == 128 && (nt == 256 || nt == 128 || nt == 64));
 }
 
 tvg_status tvg_conv2d_set_tile(const tvg_conv_desc *desc, int32_t mt, int32_t nt)
@@ -251,7 +251,7 @@ tvg_status tvg_conv2d_get_knobs(const tvg_conv_desc *desc, tvg_conv_knobs *knobs
         k.nt = d.patch.nt;
         k.stages = d.patch.dbuf ? 2 : 1;
         if (d.patch.dbuf) {
-            k.split_k = d.patch.kg;
+            k.split_k = d.patch.kg == 2 ? 2 : 1;       // (kg 3 names the channel split: mt = 128)
             if (p.sh == 1) k.lds_pitch = d.patch.pws == p.W + 2 ? 1 : 2;
             if (p.W % 2 != 0 && p.W <= 7 && p.sh == 1) k.row_loads = d.patch.px == 8 ? 2 : 1;
         }

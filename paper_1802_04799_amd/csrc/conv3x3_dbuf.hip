@@ -23,6 +23,7 @@
 #include <stdio.h>
 #include <stdlib.h>
 
+#include <algorithm>
 #include <type_traits>
 
 #include "tvg_device.h"
@@ -111,10 +112,19 @@ constexpr int waitcnt_imm(int vm, int lgkm)
 // measured first: the few threads that own a row - 60 of 256 on C12 - became the critical path,
 // 31.4 us against 25.6; pairs spread the same rows over 240 threads.)  Pixels past the end of
 // the row (the eighth element and beyond) go to the dump area.
-template <int WM, int NJ, int STRIDE, int PT, int PX, int KG = 1, bool UNAL = false>
-__global__ __launch_bounds__(256 * KG, 2) void conv3x3_dbuf_kernel(const DbufArgs a)
+//
+// MG: two groups of four waves split the OUTPUT CHANNELS of a 128-channel tile - group g owns
+// channels 64 g .. 64 g + 63 with weight planes of its own - and share one patch: the 512 threads
+// stage it together (half the patch tasks per thread), every patch word feeds twice the matrix
+// instructions, and a CU holds two waves per SIMD that run the same chunk.  For grids that fit
+// the chip at one such workgroup per CU: stride-2 layers, whose patch is four times the output
+// tile (their two stages then fit one workgroup per CU only), and stride-1 grids that would
+// otherwise put two workgroups on some CUs and one on the rest.
+template <int WM, int NJ, int STRIDE, int PT, int PX, int KG = 1, bool UNAL = false, bool MG = false>
+__global__ __launch_bounds__(256 * (MG ? 2 : KG), 2) void conv3x3_dbuf_kernel(const DbufArgs a)
 {
     static_assert(!UNAL || (PX == 8 && STRIDE == 1), "unaligned rows: whole rows of at most 7 pixels");
+    static_assert(!(MG && (KG != 1 || UNAL)), "the channel-split variant has one reduction group and aligned rows");
     constexpr int MT = kMT;
     constexpr int WN = 4 / WM;
     constexpr int WTM = MT / WM, WTN = NJ * 32, NT = WN * WTN;
@@ -129,8 +139,15 @@ __global__ __launch_bounds__(256 * KG, 2) void conv3x3_dbuf_kernel(const DbufArg
 
     // tid, wave: position within the thread's group of four waves (task lists, tile position)
     const int tid = threadIdx.x & 255, lane = tid & 63, wave = tid >> 6;
-    const int group = KG == 2 ? __builtin_amdgcn_readfirstlane(threadIdx.x >> 8) : 0;
+    const int group = (KG == 2 || MG) ? __builtin_amdgcn_readfirstlane(threadIdx.x >> 8) : 0;
     const int gbase = KG == 2 ? group * 2 * a.stage_bytes : 0;      // the group's two stages
+    const int kgroup = KG == 2 ? group : 0;                          // which chunks the group takes
+    // MG: the group's pair of weight planes within a stage; the patch planes follow all of them
+    constexpr int kWAll = (MG ? 4 : 2) * kAPlane;
+    const int agrp = MG ? group * 2 * kAPlane : 0;
+    // the patch is staged by all threads of the workgroup
+    constexpr int PTH = MG ? 512 : 256;
+    const int ptid = MG ? (int)threadIdx.x : tid;
     const int wm = wave % WM, wn = wave / WM;
     const int lrow = lane & 31, lhalf = lane >> 5;
 
@@ -147,7 +164,7 @@ __global__ __launch_bounds__(256 * KG, 2) void conv3x3_dbuf_kernel(const DbufArg
         const int tile = xcd_remap(blockIdx.x, gridDim.x);
         int r;
         const int q = fast_div(tile, a.m_major ? a.ntiles : a.mtiles, a.inv_tdiv, &r);
-        m0 = (a.m_major ? q : r) * MT;
+        m0 = (a.m_major ? q : r) * (MG ? 2 * MT : MT) + (MG ? group * MT : 0);
         n0 = (a.m_major ? r : q) * NT;
     }
 
@@ -158,7 +175,7 @@ __global__ __launch_bounds__(256 * KG, 2) void conv3x3_dbuf_kernel(const DbufArg
         2u * (uint32_t)((((m0 + w_ocl) < a.OC ? m0 + w_ocl : 0) * a.IC + w_quad * 4) * 9);
     // LDS byte addresses are kept per stage (index 0 / 1), so that the loop adds nothing to them
     int wbase[2];           // where tap 0 of the weight task goes
-    wbase[0] = gbase + (w_quad >> 1) * kAPlane + w_ocl * 16 + (w_quad & 1) * 8;
+    wbase[0] = gbase + agrp + (w_quad >> 1) * kAPlane + w_ocl * 16 + (w_quad & 1) * 8;
     wbase[1] = wbase[0] + stage_bytes;
 
     uint32_t goff[PT];      // byte offset of a patch task's first channel within a chunk of x
@@ -208,12 +225,12 @@ __global__ __launch_bounds__(256 * KG, 2) void conv3x3_dbuf_kernel(const DbufArg
             const int i = it - 9;
             if (i < 4) {
                 const uint4v t4 = __builtin_bit_cast(
-                    uint4v, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, woff + i * 16, (c * KG + group) * kChunk * 9 * 2, 0));
+                    uint4v, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, woff + i * 16, (c * KG + kgroup) * kChunk * 9 * 2, 0));
 #pragma unroll
                 for (int d = 0; d < 4; ++d) wraw[set][4 * i + d] = t4[d];
             } else {
                 const uint2v t2 = __builtin_bit_cast(
-                    uint2v, __builtin_amdgcn_raw_buffer_load_b64(wrsrc, woff + 64, (c * KG + group) * kChunk * 9 * 2, 0));
+                    uint2v, __builtin_amdgcn_raw_buffer_load_b64(wrsrc, woff + 64, (c * KG + kgroup) * kChunk * 9 * 2, 0));
                 wraw[set][16] = t2[0];
                 wraw[set][17] = t2[1];
             }
@@ -284,7 +301,7 @@ __global__ __launch_bounds__(256 * KG, 2) void conv3x3_dbuf_kernel(const DbufArg
         }
     };
     auto all_items = [&](int first, int last, int set, bool do_pack, bool do_load, int c) __attribute__((always_inline)) {
-        const int cbase = (c * KG + group) * kChunk * hw2;
+        const int cbase = (c * KG + kgroup) * kChunk * hw2;
 #pragma unroll
         for (int it = first; it < last; ++it) work_item(it, set, do_pack, do_load, c, cbase);
     };
@@ -294,7 +311,7 @@ __global__ __launch_bounds__(256 * KG, 2) void conv3x3_dbuf_kernel(const DbufArg
     all_items(9, kP0, 0, false, true, 0);
     // likewise the tile's per-channel multiplier and offset, needed only by the fused tail
     float ss_scale = 0.0f, ss_shift = 0.0f, ss_bias = 0.0f;
-    if (group == 0 && tid < MT && m0 + tid < a.OC) {
+    if ((MG || group == 0) && tid < MT && m0 + tid < a.OC) {
         ss_scale = a.scale[m0 + tid];
         ss_shift = a.shift[m0 + tid];
         if (a.bias) ss_bias = a.bias[m0 + tid];
@@ -323,7 +340,7 @@ __global__ __launch_bounds__(256 * KG, 2) void conv3x3_dbuf_kernel(const DbufArg
         for (int j = 0; j < PT; ++j) {
             // (UNAL: four tasks per row and octet, one per pair of channels)
             const int pair = UNAL ? (tid & 3) : 0;
-            const int t = UNAL ? (tid + j * 256) >> 2 : tid + j * 256;
+            const int t = UNAL ? (tid + j * 256) >> 2 : ptid + j * PTH;
             const int octet = t >= per_octet;
             const int rem = t - (octet ? per_octet : 0);
             int iw, vi;
@@ -348,21 +365,21 @@ __global__ __launch_bounds__(256 * KG, 2) void conv3x3_dbuf_kernel(const DbufArg
                 goffo[j] = 2u * (eo & ~1u);
             }
             pwbase[0][j] = gbase +
-                           (live ? 2 * kAPlane + octet * a.pplane + (vrow * PWS + word) * 16 + (n - na) * a.xp16
-                                 : 2 * kAPlane + 2 * a.pplane + (tid & 15) * (PX > 1 ? PX * 16 : 32) +
+                           (live ? kWAll + octet * a.pplane + (vrow * PWS + word) * 16 + (n - na) * a.xp16
+                                 : kWAll + 2 * a.pplane + (tid & 15) * (PX > 1 ? PX * 16 : 32) +
                                        (STRIDE == 2 && PX > 1 ? 16 - pair_step : 0));
             if constexpr (UNAL) pwbase[0][j] += pair * 4;     // the pair's 4 bytes of a pixel's word
             pwbase[1][j] = pwbase[0][j] + stage_bytes;
             if constexpr (UNAL) {
                 // (64 lanes write 256 consecutive bytes: conflict-free)
-                pwdump[0][j] = gbase + 2 * kAPlane + 2 * a.pplane + (tid & 63) * 4;
+                pwdump[0][j] = gbase + kWAll + 2 * a.pplane + (tid & 63) * 4;
                 pwdump[1][j] = pwdump[0][j] + stage_bytes;
             }
             pwbase2[0][j] = pwbase[0][j] + pair_step;
             pwbase2[1][j] = pwbase[1][j] + pair_step;
             if constexpr (PX == 4) {
                 const bool whole = !live || iw + 4 <= W;
-                const int dump = gbase + 2 * kAPlane + 2 * a.pplane + (tid & 15) * 64;
+                const int dump = gbase + kWAll + 2 * a.pplane + (tid & 15) * 64;
                 pwtail[0][j] = whole ? pwbase[0][j] + (STRIDE == 2 ? 16 : 32) : dump + 32;
                 pwtail[1][j] = pwtail[0][j] + stage_bytes;
                 if constexpr (STRIDE == 2) {
@@ -396,11 +413,11 @@ __global__ __launch_bounds__(256 * KG, 2) void conv3x3_dbuf_kernel(const DbufArg
         int rem, ow;
         const int n = fast_div(p, OHW, a.inv_ohw, &rem);
         const int oh = fast_div(rem, a.OW, a.inv_ow, &ow);
-        bpix[j] = gbase + 2 * kAPlane + lhalf * a.pplane +
+        bpix[j] = gbase + kWAll + lhalf * a.pplane +
                   (p < a.npix ? ((n * VH + oh * STRIDE - vr_lo) * PWS + ow) * 16 + (n - na) * a.xp16 : 0);
     }
     int abase[2];
-    abase[0] = gbase + lhalf * kAPlane + (wm * WTM + lrow) * 16;
+    abase[0] = gbase + agrp + lhalf * kAPlane + (wm * WTM + lrow) * 16;
     abase[1] = abase[0] + stage_bytes;
     second_chunk_loads(NJ < 4 ? NJ : 4, NJ < 4 ? NJ + 2 : 6);
 
@@ -421,11 +438,12 @@ __global__ __launch_bounds__(256 * KG, 2) void conv3x3_dbuf_kernel(const DbufArg
     {
         const int words = 2 * a.pplane / 16;
         for (int s = 0; s < 2; ++s) {
-            uint4v *pz = reinterpret_cast<uint4v *>(smem + gbase + s * stage_bytes + 2 * kAPlane);
-            for (int i = tid; i < words; i += 256) pz[i] = uint4v{0u, 0u, 0u, 0u};
+            uint4v *pz = reinterpret_cast<uint4v *>(smem + gbase + s * stage_bytes + kWAll);
+            for (int i = ptid; i < words; i += PTH) pz[i] = uint4v{0u, 0u, 0u, 0u};
         }
     }
-    if (group == 0 && tid < MT) {
+    if constexpr (MG) ss_lds += group * 2 * MT;          // each group's 64 channels
+    if ((MG || group == 0) && tid < MT) {
         // (acc + bias)*scale + shift == acc*scale + (bias*scale + shift)
         ss_lds[2 * tid] = ss_scale;
         ss_lds[2 * tid + 1] = fmaf(ss_bias, ss_scale, ss_shift);
@@ -489,7 +507,7 @@ __global__ __launch_bounds__(256 * KG, 2) void conv3x3_dbuf_kernel(const DbufArg
     auto chunk = [&](auto parc, auto modec, int c) __attribute__((always_inline)) {
         constexpr int par = decltype(parc)::value;
         constexpr int mode = decltype(modec)::value;
-        const int cbase = ((c + 3) * KG + group) * kChunk * hw2;
+        const int cbase = ((c + 3) * KG + kgroup) * kChunk * hw2;
         // (hidden from loop-invariant code motion, which would spend a register per
         // combination of stage, filter row and pixel block on precomputed addresses)
         int so = par * stage_bytes;
@@ -538,7 +556,8 @@ __global__ __launch_bounds__(256 * KG, 2) void conv3x3_dbuf_kernel(const DbufArg
     const TailArgs tail{a.scale, a.shift, a.bias, a.residual, a.y, a.OC, OHW, a.npix, a.relu};
     if constexpr (KG == 1) {
         constexpr int BT = MI * NJ < 4 ? MI * NJ : 4;                 // tiles staged at a time
-        unsigned char *stage = smem + wave * (BT * kStageBytes);      // <= 40 KB < two stages
+        // (four waves: <= 40 KB < two stages; MG: eight waves, the host sizes the LDS for them)
+        unsigned char *stage = smem + ((MG ? group * 4 : 0) + wave) * (BT * kStageBytes);
         store_acc_tiles_batched<MI, NJ, BT>(acc, stage, lane, m0 + wm * WTM, n0 + wn * WTN, tail,
                                             a.vmode, ss_lds, wm * WTM);
     } else {
@@ -584,10 +603,10 @@ __global__ __launch_bounds__(256 * KG, 2) void conv3x3_dbuf_kernel(const DbufArg
     }
 }
 
-template <int WM, int NJ, int STRIDE, int PT, int PX, int KG = 1, bool UNAL = false>
+template <int WM, int NJ, int STRIDE, int PT, int PX, int KG = 1, bool UNAL = false, bool MG = false>
 tvg_status launch_instance(const DbufArgs &a, size_t lds, hipStream_t stream)
 {
-    auto kernel = conv3x3_dbuf_kernel<WM, NJ, STRIDE, PT, PX, KG, UNAL>;
+    auto kernel = conv3x3_dbuf_kernel<WM, NJ, STRIDE, PT, PX, KG, UNAL, MG>;
     static bool configured = false;      // opt in to > 64 KB of dynamic LDS once per instance
     if (!configured) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
@@ -595,7 +614,7 @@ tvg_status launch_instance(const DbufArgs &a, size_t lds, hipStream_t stream)
             return TVG_ERR_LAUNCH;
         configured = true;
     }
-    hipLaunchKernelGGL(kernel, dim3((unsigned)(a.mtiles * a.ntiles)), dim3(256 * KG), lds, stream, a);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(a.mtiles * a.ntiles)), dim3(256 * (MG ? 2 : KG)), lds, stream, a);
     return hipGetLastError() == hipSuccess ? TVG_OK : TVG_ERR_LAUNCH;
 }
 
@@ -624,10 +643,40 @@ tvg_status launch_pt_kg2(const DbufArgs &a, size_t lds, int pt, int px, hipStrea
     return TVG_ERR_UNSUPPORTED;
 }
 
+// The channel-split variant (two groups of four waves, 128 output channels): wave tiles of two
+// pixel blocks, aligned rows, one or two patch tasks per thread.
+template <int WM, int NJ>
+tvg_status launch_pt_mg(const DbufArgs &a, size_t lds, int stride, int pt, int px, hipStream_t stream)
+{
+    if constexpr (NJ == 2) {
+        if (pt > 2) return TVG_ERR_UNSUPPORTED;
+#define TVG_MG(S_, PX_)                                                                              \
+    (pt <= 1 ? launch_instance<WM, NJ, S_, 1, PX_, 1, false, true>(a, lds, stream)                    \
+             : launch_instance<WM, NJ, S_, 2, PX_, 1, false, true>(a, lds, stream))
+        // (the host admits 16-byte loads with one task per thread only: registers)
+        if (px == 8 && pt > 1) return TVG_ERR_UNSUPPORTED;
+        if (stride == 2) {
+            if (px == 8) return launch_instance<WM, NJ, 2, 1, 8, 1, false, true>(a, lds, stream);
+            if (px == 4) return TVG_MG(2, 4);
+            if (px == 2) return TVG_MG(2, 2);
+            return TVG_ERR_UNSUPPORTED;
+        }
+        switch (px) {
+        case 8: return launch_instance<WM, NJ, 1, 1, 8, 1, false, true>(a, lds, stream);
+        case 4: return TVG_MG(1, 4);
+        case 2: return TVG_MG(1, 2);
+        default: return TVG_MG(1, 1);
+        }
+#undef TVG_MG
+    }
+    return TVG_ERR_UNSUPPORTED;
+}
+
 template <int WM, int NJ>
 tvg_status launch_pt(const DbufArgs &a, size_t lds, int stride, int pt, int px, int kg,
                      hipStream_t stream)
 {
+    if (kg == 3) return launch_pt_mg<WM, NJ>(a, lds, stride, pt, px, stream);
     if (kg == 2) return stride == 1 ? launch_pt_kg2<WM, NJ>(a, lds, pt, px, stream) : TVG_ERR_UNSUPPORTED;
     if (stride == 2) {
         // instances exist for the 128- and 256-pixel tiles and even rows (see the plan)
@@ -668,7 +717,15 @@ tvg_status launch_pt(const DbufArgs &a, size_t lds, int stride, int pt, int px, 
 // stages do not fit or the tile shape has no instance.
 bool plan_conv3x3_dbuf(const ConvProblem &p, Patch3x3Plan *plan)
 {
-    if (plan->mt != kMT) return false;
+    // 128-channel tiles: the channel-split variant (two wave groups, one workgroup per CU)
+    const bool mg = plan->mt == 2 * kMT;
+    if (plan->mt != kMT && !mg) return false;
+    // Measured at batch 64: C6 21.4 us against 21.7 with 64 x 256 tiles, C7 18.7 against 18.9 in the
+    // single-stage kernel, C10 30.0 against 21.7 (100 workgroups instead of 200) - the operand reads
+    // of a 32 x 64 or 64 x 64 wave tile keep the LDS as busy as before, whoever stages the patch.
+    // Not a rule, then: the variant runs where a caller names it (tile 128 x nt, two stages).
+    if (mg && (plan->want_stages != 2 || plan->tiles > kComputeUnits || plan->nt < 128 || p.OC <= kMT))
+        return false;
     if (p.IC % (2 * kChunk) != 0) return false;      // the chunk loop runs in pairs
     // Measured at batch 64: with fewer than eight chunks the deeper pipeline's longer start-up
     // (three chunks in flight before the first MFMA) costs more than the loop gains.  (A caller
@@ -718,17 +775,23 @@ bool plan_conv3x3_dbuf(const ConvProblem &p, Patch3x3Plan *plan)
     // element loads + two wave groups 25.9; element loads + one group 28.1; whole rows with the
     // plain pitch 28.1 - the 4-byte stores of a row's pieces then collide)
     const bool odd_rows = px == 1;
-    const bool unal = px == 1 && p.W <= 7 && p.sh == 1 && 8 * plan->rows <= 512 && plan->want_rows != 1;
+    const bool unal = px == 1 && p.W <= 7 && p.sh == 1 && 8 * plan->rows <= 512 && plan->want_rows != 1 && !mg;
     if (unal) px = 8;
     // (unaligned rows: four tasks per row and octet, each two channels)
+    const int pth = mg ? 512 : 256;                   // threads that share the patch tasks
     const int pt = unal ? (8 * plan->rows + 255) / 256
-                        : (2 * plan->rows * ((p.W + px - 1) / px) + 255) / 256;
+                        : (2 * plan->rows * ((p.W + px - 1) / px) + pth - 1) / pth;
     if (!unal && pt * (px >= 2 ? px / 2 : 1) > 4) return false;       // registers of a task's loads
+    if (mg && pt > 2) return false;                                    // instances built
     // behind the planes of a stage: 32 bytes for each of 16 lanes, where idle patch tasks store
     // (a stride-2 pair stores its two pixels pwh - 1 words apart)
     const int dump = 16 * (px > 1 ? px * 16 : 32) + (p.sh == 2 ? pwh * 16 : 0);
-    int stage = 2 * kAPlane + 2 * pplane + dump;
-    size_t lds = 2 * (size_t)stage + (size_t)kMT * 8;
+    const int wplanes = (mg ? 4 : 2) * kAPlane;
+    const size_t ss_bytes = (size_t)plan->mt * 8;
+    // (the tail's staging areas, one per wave, reuse the stages; eight waves need 80 KB)
+    const size_t tail_bytes = mg ? (size_t)8 * 4 * kStageBytes : 0;
+    int stage = wplanes + 2 * pplane + dump;
+    size_t lds = std::max(2 * (size_t)stage, tail_bytes) + ss_bytes;
     // (a grid of at most one workgroup per CU may take the whole LDS for the conflict-free pitch:
     // C9 20.9 -> 19.7 us)
     const bool lone = plan->tiles <= kComputeUnits;
@@ -737,8 +800,8 @@ bool plan_conv3x3_dbuf(const ConvProblem &p, Patch3x3Plan *plan)
         pws = p.W + 2;
         xp = 0;
         pplane = plan->rows * pws * 16;
-        stage = 2 * kAPlane + 2 * pplane + dump;
-        lds = 2 * (size_t)stage + (size_t)kMT * 8;
+        stage = wplanes + 2 * pplane + dump;
+        lds = std::max(2 * (size_t)stage, tail_bytes) + ss_bytes;
     }
     // Grids of at most one workgroup per CU (stride 1, wave tiles of two pixel blocks, whole
     // pairs of chunks for each half of the reduction): two groups of four waves split the
@@ -750,7 +813,7 @@ bool plan_conv3x3_dbuf(const ConvProblem &p, Patch3x3Plan *plan)
     // element (C12: 28.1 -> 25.6 us), it loses on C9 (20.9 -> 21.4 us, and the four stages cost C9
     // the conflict-free pitch: 19.7 us with it); tvg_conv2d_set_knobs overrides the rule.
     const bool kg_rule = plan->want_kg == 2 || (plan->want_kg == 0 && odd_rows && !unal);
-    if (p.sh == 1 && plan->tiles <= kComputeUnits && plan->nt >= 128 && p.IC % (4 * kChunk) == 0 &&
+    if (!mg && p.sh == 1 && plan->tiles <= kComputeUnits && plan->nt >= 128 && p.IC % (4 * kChunk) == 0 &&
         p.IC >= 8 * kChunk && kg_rule) {
         const int mi = plan->nt == 256 ? 2 : 1;
         const size_t after = (size_t)8 * mi * 4096 + (size_t)8 * mi * kStageBytes;
@@ -770,6 +833,7 @@ bool plan_conv3x3_dbuf(const ConvProblem &p, Patch3x3Plan *plan)
     // two workgroups per CU, or one per CU when the whole grid is resident at once anyway
     if (kg == 1 && lds > 80 * 1024 && !(lds <= 160 * 1024 && plan->tiles <= kComputeUnits)) return false;
     if (plan->tiles >= (1 << 22)) return false;      // fast_div range of the tile index
+    if (mg) kg = 3;                                   // (the launch's name for the channel split)
     plan->kg = kg;
     plan->dbuf = 1;
     plan->pt = pt;
@@ -791,13 +855,13 @@ tvg_status launch_conv3x3_dbuf(const ConvProblem &p, const Patch3x3Plan &plan,
     a.residual = static_cast<const bf16_t *>(ptr.residual); a.y = static_cast<bf16_t *>(ptr.y);
     a.N = p.N; a.IC = p.IC; a.H = p.H; a.W = p.W; a.OC = p.OC; a.OH = p.OH; a.OW = p.OW;
     a.npix = p.npix; a.relu = p.relu | (p.stream_out << 1);
-    a.mtiles = (p.OC + kMT - 1) / kMT;
+    a.mtiles = (p.OC + plan.mt - 1) / plan.mt;
     a.vmode = pick_store_vmode(p.dtype, p.OH * p.OW, ptr.y, ptr.residual);
     a.pplane = plan.pplane;
     a.pws = plan.pws;
     a.xp16 = plan.xp16;
     a.stage_bytes = plan.stage_bytes;
-    a.ss_offset = (int)(plan.lds_bytes - (size_t)kMT * 8);
+    a.ss_offset = (int)(plan.lds_bytes - (size_t)plan.mt * 8);
     a.x_bytes = (uint32_t)((size_t)p.N * p.IC * p.H * p.W * 2);
     a.w_bytes = (uint32_t)((size_t)p.OC * p.IC * 9 * 2);
     a.ntiles = (p.npix + plan.nt - 1) / plan.nt;

@@ -462,7 +462,9 @@ bool plan_conv3x3_patch(const ConvProblem &p, Patch3x3Plan *plan, int single_sta
     // least 1.5 workgroups per CU, wider in pixels on a tie; if none does, the tile shape with
     // the most workgroups.  A 128-channel tile with more than 4 patch tasks per thread (wide
     // stride-2 patches) runs out of registers and is skipped.
-    const int cands[5][2] = {{64, 256}, {128, 128}, {64, 128}, {128, 64}, {64, 64}};
+    // (128 x 256 exists in the pipelined kernel only, as its channel-split variant, and is taken
+    // when a caller names it)
+    const int cands[6][2] = {{64, 256}, {128, 128}, {64, 128}, {128, 64}, {64, 64}, {128, 256}};
     Patch3x3Plan best{};
     bool found = false, best_fills = false;
     for (const auto &c : cands) {
@@ -471,6 +473,7 @@ bool plan_conv3x3_patch(const ConvProblem &p, Patch3x3Plan *plan, int single_sta
         if (dual && (mt != 64 || nt < 128 || single_stage_mt_divides % mt != 0)) continue;
         if (force_mt && mt != force_mt) continue;
         if (force_nt && nt != force_nt) continue;
+        if (mt == 128 && nt == 256 && !(force_mt == 128 && force_nt == 256)) continue;
         const int rows = max_patch_rows(p, nt);
         // two pixels per load when the rows are even (32-bit aligned pairs) and that keeps the
         // task count within the instances built for it
@@ -496,6 +499,7 @@ bool plan_conv3x3_patch(const ConvProblem &p, Patch3x3Plan *plan, int single_sta
         if (dual && nt == 256 && pt > 1) continue;    // (those two-head instances run out of registers)
         if (!(use_dbuf && plan_conv3x3_dbuf(p, &cand))) {
             if (knobs.stages == 2) continue;      // the caller asked for the pipelined kernel
+            if (mt == 128 && nt == 256) continue; // (no single-stage instance of that tile)
             if (pt > 8 || lds > 80 * 1024) continue;
             if (mt == 128 && pt > 4 && !force_mt) continue;
         }

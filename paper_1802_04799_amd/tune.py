@@ -30,6 +30,8 @@ from typing import Dict, List, Optional, Tuple
 from . import binding as _b
 
 TILES: List[Tuple[int, int]] = [(64, 256), (128, 128), (64, 128), (128, 64), (64, 64)]
+# the pipelined 3x3 kernel also has 128 x 256 (its channel-split variant: two wave groups share a patch)
+TILES_3X3: List[Tuple[int, int]] = TILES + [(128, 256)]
 KNOBS = ("mt", "nt", "stages", "split_k", "lds_pitch", "row_loads")
 _chosen: Dict[str, Tuple[int, ...]] = {}
 
@@ -62,7 +64,7 @@ def space_for(desc, kernel: int) -> Dict[str, list]:
     if kernel in (1, 2):                         # bf16 3x3: both kernels, all their knobs
         s1 = desc.stride_w == 1
         odd_small = desc.w % 2 == 1 and desc.w <= 7 and s1
-        return {"tile": TILES, "stages": [1, 2], "split_k": [1, 2] if s1 else [1],
+        return {"tile": TILES_3X3, "stages": [1, 2], "split_k": [1, 2] if s1 else [1],
                 "lds_pitch": [1, 2] if s1 else [0], "row_loads": [1, 2] if odd_small else [0]}
     if kernel == 4:                              # bf16 1x1
         return {"tile": TILES[1:], "stages": [0], "split_k": [0], "lds_pitch": [0], "row_loads": [0]}

@@ -215,7 +215,11 @@ def test_tile_table_sets_overrides_and_forgets():
     assert tvg.tvg_conv2d_set_tile(c6, 0, 0) == 0
     assert tvg.tvg_conv2d_get_plan(c6) == (2, 64, 256)
     assert tvg.tvg_conv2d_set_tile(c6, 0, 0) == 0                    # forgetting twice is fine
-    for mt, nt in [(64, 100), (256, 64), (128, 256), (-64, 64), (64, 0)]:
+    # 128 x 256 is the pipelined kernel's channel-split variant: it runs when named with its stages
+    assert tvg.tvg_conv2d_set_knobs(c6, (128, 256, 2, 0, 0, 0)) == 0
+    assert tvg.tvg_conv2d_get_plan(c6) == (2, 128, 256)
+    assert tvg.tvg_conv2d_set_knobs(c6, None) == 0
+    for mt, nt in [(64, 100), (256, 64), (256, 256), (-64, 64), (64, 0)]:
         assert tvg.tvg_conv2d_set_tile(c6, mt, nt) == 3
     assert tvg.tvg_conv2d_set_tile(desc(n=0), 64, 64) == 2
     lib = tvg.load()

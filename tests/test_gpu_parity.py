@@ -268,6 +268,47 @@ def test_bf16_3x3_pipelined_kernel_knobs(tvg, cfg, point):
         tvg.tvg_conv2d_set_knobs(desc, None)
 
 
+MG_SHAPES = [
+    # the pipelined kernel's channel-split variant (128-channel tiles, two wave groups that share
+    # one patch): n, ic, h, w, oc, stride.  More than 64 output channels, at most 256 tiles; ragged
+    # channel tails in the second group (130, 72, 200), several images per tile, every load width,
+    # both strides, the full C6, C7 and C10 launches of the benchmark.
+    (2, 128, 8, 8, 128, 1), (3, 128, 7, 7, 130, 1), (1, 256, 33, 40, 72, 1), (5, 192, 12, 12, 96, 1),
+    (2, 128, 56, 56, 128, 1), (1, 128, 30, 70, 200, 1), (40, 128, 7, 7, 128, 1), (2, 128, 14, 14, 256, 1),
+    (1, 128, 2, 64, 200, 1), (2, 128, 3, 1, 128, 1), (3, 128, 10, 10, 96, 1), (64, 128, 28, 28, 128, 1),
+    (2, 128, 14, 14, 128, 2), (3, 128, 9, 10, 130, 2), (1, 256, 28, 28, 72, 2), (2, 128, 16, 16, 128, 2),
+    (5, 160, 7, 8, 72, 2), (4, 128, 6, 12, 128, 2), (64, 128, 28, 28, 256, 2), (64, 256, 14, 14, 512, 2),
+]
+
+
+@pytest.mark.parametrize("pitch", [1, 2])
+@pytest.mark.parametrize("nt", [256, 128])
+@pytest.mark.parametrize("cfg", MG_SHAPES, ids=lambda c: "x".join(map(str, c)))
+def test_bf16_3x3_pipelined_kernel_channel_split(tvg, cfg, nt, pitch):
+    """128 x nt tiles of the pipelined kernel, fixed through tvg_conv2d_set_knobs; skipped where the
+    library would not run that variant (too many tiles, a patch that does not fit); what runs is
+    checked against the oracle with bias, residual and ReLU, and is deterministic."""
+    import torch
+    n, ic, h, w, oc, stride = cfg
+    if stride == 2 and pitch == 1:
+        pytest.skip("stride 2 has one pitch rule")
+    sh = ti.ConvShape("mg", n, ic, h, w, oc, 3, 3, stride, 1)
+    desc = tvg.ConvDesc(n, ic, h, w, oc, 3, 3, stride, stride, 1, 1, tvg.TVG_BF16, 0)
+    want = (128, nt, 2, 0, pitch if stride == 1 else 0, 0)
+    assert tvg.tvg_conv2d_set_knobs(desc, want) == 0
+    try:
+        got = tvg.tvg_conv2d_get_knobs(desc)
+        if tvg.tvg_conv2d_get_plan(desc) != (2, 128, nt) or any(a and a != b for a, b in zip(want, got)):
+            pytest.skip(f"variant not usable here: asked {want}, would run {got}")
+        inp = ti.make_inputs(sh, 16000 + sum(cfg) + nt + pitch, "bf16", residual=True, bias=True)
+        y1 = run_dense(tvg, sh, inp, "bf16")
+        y2 = run_dense(tvg, sh, inp, "bf16", stream_out=True)
+        assert torch.equal(y1.view(torch.int16), y2.view(torch.int16))
+        check(to_host(y1), oracle_dense(sh, inp), "bf16", (cfg, got))
+    finally:
+        tvg.tvg_conv2d_set_knobs(desc, None)
+
+
 @pytest.mark.parametrize("cfg", [(2, 128, 8, 8, 64), (3, 128, 7, 7, 130), (1, 256, 33, 40, 72)])
 def test_bf16_3x3_pipelined_kernel_plain_tail_and_determinism(tvg, cfg):
     """No bias, no residual, no ReLU (negative outputs survive), and bit-identical reruns."""
