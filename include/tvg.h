@@ -292,7 +292,8 @@ typedef enum {
     TVG_KERNEL_3X3_PIPELINED = 2,  /* bf16 3x3, two LDS stages, software-pipelined         */
     TVG_KERNEL_STEM = 3,           /* bf16 7x7 stride 2, few input channels                */
     TVG_KERNEL_1X1 = 4,            /* bf16 1x1                                             */
-    TVG_KERNEL_F32_SMALL = 5       /* fp32 1x1 / 3x3 of launch-bound problems, one launch  */
+    TVG_KERNEL_F32_SMALL = 5,      /* fp32 1x1 / 3x3 of launch-bound problems, one launch  */
+    TVG_KERNEL_1X1_DEEP = 6        /* bf16 1x1 stride 1, reductions of 128 n channels       */
 } tvg_kernel;
 tvg_status tvg_conv2d_set_tile(const tvg_conv_desc *desc, int32_t mt, int32_t nt);
 tvg_status tvg_conv2d_get_plan(const tvg_conv_desc *desc, int32_t *kernel, int32_t *mt, int32_t *nt);
@@ -303,8 +304,13 @@ tvg_status tvg_conv2d_get_plan(const tvg_conv_desc *desc, int32_t *kernel, int32
  * compiled kernel instances or a launch parameter; 0 leaves a knob to the library's rule.
  *   mt, nt      workgroup tile, as for tvg_conv2d_set_tile (with it the wave tile: 64x64, 32x64,
  *               64x32 or 32x32 outputs per wave)
+ *               128 x 256 (and 128 x 128 with stages = 2) name the pipelined 3x3 kernel's
+ *               channel-split variant: two groups of four waves own 64 output channels each and
+ *               share one patch (at most one workgroup per CU, more than 64 output channels)
  *   stages      bf16 3x3: 1 = the single-stage kernel, 2 = the software-pipelined kernel with two
  *               LDS stages (from 64 input channels on, a multiple of 32; 64-channel tiles)
+ *               bf16 1x1, stride 1: 2 = the kernel for deep reductions (c a multiple of 128, maps
+ *               of 4n pixels: wide pixel loads, two steps of 64 channels in flight)
  *   split_k     partitions of the reduction.  Generic kernel (fp32, odd shapes): 1..32 partitions
  *               across workgroups, summed by a second launch - tvg_conv2d_workspace_size follows
  *               the knob.  Pipelined 3x3: 1 or 2 groups of four waves inside one workgroup that

@@ -137,7 +137,7 @@ def tvg_version() -> int:
     return int(load().tvg_version())
 
 
-KERNEL_NAMES = {0: "generic", 1: "3x3", 2: "3x3-pipelined", 3: "stem", 4: "1x1", 5: "fp32-small"}
+KERNEL_NAMES = {0: "generic", 1: "3x3", 2: "3x3-pipelined", 3: "stem", 4: "1x1", 5: "fp32-small", 6: "1x1-deep"}
 
 
 def tvg_conv2d_set_tile(desc: "ConvDesc", mt: int, nt: int) -> int:

@@ -16,7 +16,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtvg.so")
-SOURCES = ["api.cpp", "conv_igemm.hip", "conv3x3_patch.hip", "conv3x3_dbuf.hip", "conv7x7s2_stem.hip", "conv1x1.hip", "dwconv.hip", "dwpw.hip", "pool.hip", "probe.hip", "conv_f32_small.hip", "conv3x3_winograd.hip"]
+SOURCES = ["api.cpp", "conv_igemm.hip", "conv3x3_patch.hip", "conv3x3_dbuf.hip", "conv7x7s2_stem.hip", "conv1x1.hip", "dwconv.hip", "dwpw.hip", "pool.hip", "probe.hip", "conv_f32_small.hip", "conv3x3_winograd.hip", "conv1x1_deep.hip"]
 HEADERS = [os.path.join(CSRC, "tvg_internal.h"), os.path.join(CSRC, "tvg_device.h"),
            os.path.join(ROOT, "include", "tvg.h")]
 

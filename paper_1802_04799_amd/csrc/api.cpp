@@ -98,10 +98,11 @@ void tile_key(const ConvProblem &p, int (&key)[12])
 // it.  The launch-bound batch-1 layers spend 1-5 us per call in planning otherwise.
 struct Dispatch {
     int key[12];
-    bool patch_shape, stem_shape, pw_shape, f32_shape;
+    bool patch_shape, stem_shape, pw_shape, pwd_shape, f32_shape;
     tvg::Patch3x3Plan patch;
     tvg::StemPlan stem;
     tvg::Pw1x1Plan pw;
+    tvg::PwDeepPlan pwd;            // the deep-reduction 1x1 kernel, where its rule (or a knob) picks it
     tvg::F32SmallPlan f32;
     tvg::ConvPlan generic;          // the generic kernel's plan, reduction split allowed
     tvg::ConvPlan generic_single;   // the same in a single pass (no workspace)
@@ -125,6 +126,13 @@ Dispatch dispatch_for(const ConvProblem &p)
     d.patch_shape = tvg::plan_conv3x3_patch(p, &d.patch);
     d.stem_shape = !d.patch_shape && tvg::plan_conv7x7s2_stem(p, &d.stem);
     d.pw_shape = !d.patch_shape && !d.stem_shape && tvg::plan_conv1x1(p, &d.pw);
+    {
+        // stages knob of a 1x1 problem: 2 = the deep-reduction kernel.  No rule picks it: measured at
+        // batch 32 / 64 over thirteen MobileNet and ResNet-50 pointwise shapes it takes 1.15-1.5 times
+        // as long as the general kernel (512 -> 512 at 14x14: 15.7 against 12.5 us).
+        const int want = tvg::forced_knobs(p).stages;
+        d.pwd_shape = d.pw_shape && want == 2 && tvg::plan_conv1x1_deep(p, &d.pwd);
+    }
     d.f32_shape = tvg::plan_conv_f32_small(p, &d.f32);
     d.generic = tvg::plan_conv(p, true);
     d.generic_single = tvg::plan_conv(p, false);
@@ -259,9 +267,14 @@ tvg_status tvg_conv2d_get_knobs(const tvg_conv_desc *desc, tvg_conv_knobs *knobs
         k.mt = 64;
         k.nt = 256;
         k.stages = 1;
+    } else if (d.pwd_shape) {
+        k.mt = 64;
+        k.nt = 128;
+        k.stages = 2;
     } else if (d.pw_shape) {
         k.mt = d.pw.mt;
         k.nt = d.pw.nt;
+        k.stages = 1;
     } else if (d.f32_shape) {
         k.stages = 1;
         k.split_k = d.f32.nw * d.f32.ksplit;     // waves of a workgroup x slices across workgroups
@@ -290,6 +303,10 @@ tvg_status tvg_conv2d_get_plan(const tvg_conv_desc *desc, int32_t *kernel, int32
         *kernel = TVG_KERNEL_STEM;
         *mt = 64;
         *nt = 256;
+    } else if (d.pwd_shape) {
+        *kernel = TVG_KERNEL_1X1_DEEP;
+        *mt = 64;
+        *nt = 128;
     } else if (d.pw_shape) {
         *kernel = TVG_KERNEL_1X1;
         *mt = d.pw.mt;
@@ -345,6 +362,7 @@ tvg_status tvg_conv2d_fused(const tvg_conv_desc *desc, const void *x, const void
         return tvg::launch_conv3x3_patch(p, d.patch, ptr, stream);
     if (d.stem_shape && tvg::conv7x7s2_stem_pointers_ok(ptr))
         return tvg::launch_conv7x7s2_stem(p, d.stem, ptr, stream);
+    if (d.pwd_shape && tvg::conv1x1_deep_pointers_ok(ptr)) return tvg::launch_conv1x1_deep(p, d.pwd, ptr, stream);
     if (d.pw_shape && tvg::conv1x1_pointers_ok(ptr)) return tvg::launch_conv1x1(p, d.pw, ptr, stream);
     const auto workspace_short = [&](size_t need) {
         return need > 0 && (!workspace || workspace_bytes < need ||

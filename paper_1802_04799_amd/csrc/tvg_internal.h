@@ -118,6 +118,17 @@ bool conv1x1_pointers_ok(const ConvPointers &ptr);
 tvg_status launch_conv1x1(const ConvProblem &p, const Pw1x1Plan &plan, const ConvPointers &ptr,
                           hipStream_t stream);
 
+// bf16 1x1 stride-1 kernel for deep reductions (IC a multiple of 128, maps of 4n pixels): wide
+// pixel loads transposed in registers, two steps of 64 channels in flight.
+struct PwDeepPlan {
+    int px;             // pixels per load: 8 or 4
+    long tiles;
+};
+bool plan_conv1x1_deep(const ConvProblem &p, PwDeepPlan *plan);
+bool conv1x1_deep_pointers_ok(const ConvPointers &ptr);
+tvg_status launch_conv1x1_deep(const ConvProblem &p, const PwDeepPlan &plan, const ConvPointers &ptr,
+                               hipStream_t stream);
+
 // bf16 MobileNet block in one kernel: depthwise 3x3 (pad 1, stride 1) computed in LDS as the
 // pixel operand of the 1x1 stage.  `dw` is the depthwise problem, OC the 1x1 stage's channels.
 struct DwPwPlan {

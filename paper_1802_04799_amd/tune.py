@@ -66,8 +66,10 @@ def space_for(desc, kernel: int) -> Dict[str, list]:
         odd_small = desc.w % 2 == 1 and desc.w <= 7 and s1
         return {"tile": TILES_3X3, "stages": [1, 2], "split_k": [1, 2] if s1 else [1],
                 "lds_pitch": [1, 2] if s1 else [0], "row_loads": [1, 2] if odd_small else [0]}
-    if kernel == 4:                              # bf16 1x1
-        return {"tile": TILES[1:], "stages": [0], "split_k": [0], "lds_pitch": [0], "row_loads": [0]}
+    if kernel in (4, 6):                         # bf16 1x1: its tiles, or the deep-reduction kernel
+        deep = desc.stride_w == 1 and desc.c % 128 == 0 and (desc.h * desc.w) % 4 == 0
+        return {"tile": TILES[1:], "stages": [1, 2] if deep else [1], "split_k": [0], "lds_pitch": [0],
+                "row_loads": [0]}
     if kernel == 0:                              # generic kernel: tile rows and the reduction split
         return {"tile": [(64, 0), (128, 0)], "stages": [0],
                 "split_k": [1, 2, 3, 4, 6, 8, 12, 16, 24, 32], "lds_pitch": [0], "row_loads": [0]}
@@ -129,7 +131,7 @@ def tune_conv2d(desc, x, w, scale, shift, y, bias=None, residual=None, workspace
             eff = _b.tvg_conv2d_get_knobs(desc)
             k2 = _b.tvg_conv2d_get_plan(desc)[0]
             # usable if the library really runs what the point names (no silent fall-back)
-            same_family = (k2 in (1, 2)) if kernel in (1, 2) else k2 == kernel
+            same_family = (k2 in (1, 2)) if kernel in (1, 2) else (k2 in (4, 6)) if kernel in (4, 6) else k2 == kernel
             named = all(want == 0 or want == got for want, got in zip(p, eff))
             if same_family and named:
                 us = measure()

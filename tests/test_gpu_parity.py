@@ -384,6 +384,45 @@ def test_bf16_1x1_kernel_shapes(tvg, cfg):
     check(to_host(y), oracle_dense(sh, inp), "bf16")
 
 
+DEEP_PW_SHAPES = [
+    # bf16 1x1 stride-1 problems with IC % 128 == 0 and maps of 4n pixels (the deep-reduction
+    # pointwise kernel): n, ic, h, w, oc.  16- and 8-byte pixel loads (HW % 8 == 0 or not), 2 to 16
+    # steps, ragged channel and pixel tails, tiles that span several images, the MobileNet layers.
+    (2, 512, 14, 14, 512), (3, 128, 4, 4, 64), (1, 256, 6, 6, 72), (2, 1024, 2, 2, 130),
+    (5, 256, 28, 28, 256), (1, 384, 10, 10, 200), (2, 128, 56, 56, 128), (3, 256, 2, 2, 64),
+    (1, 128, 4, 1, 64), (70, 256, 2, 2, 64), (32, 512, 14, 14, 512), (2, 2048, 2, 6, 96),
+    (1, 640, 8, 9, 40),
+]
+
+
+@pytest.mark.parametrize("variant", ["plain", "bias+residual", "no-relu"])
+@pytest.mark.parametrize("cfg", DEEP_PW_SHAPES, ids=lambda c: "x".join(map(str, c)))
+def test_bf16_1x1_deep_kernel_shapes(tvg, cfg, variant):
+    """The deep-reduction pointwise kernel, named through the stages knob (no rule picks it): every
+    output against the oracle, deterministic, hint-independent."""
+    import torch
+    n, ic, h, w, oc = cfg
+    sh = ti.ConvShape("pwd", n, ic, h, w, oc, 1, 1, 1, 0)
+    desc = tvg.ConvDesc(n, ic, h, w, oc, 1, 1, 1, 1, 0, 0, tvg.TVG_BF16, 0)
+    assert tvg.tvg_conv2d_set_knobs(desc, (0, 0, 2, 0, 0, 0)) == 0
+    try:
+        assert tvg.tvg_conv2d_get_plan(desc) == (6, 64, 128)
+        inp = ti.make_inputs(sh, 17000 + sum(cfg) + len(variant), "bf16", residual="residual" in variant,
+                             bias="bias" in variant)
+        relu = "no-relu" not in variant
+        y1 = run_dense(tvg, sh, inp, "bf16", relu=relu)
+        y2 = run_dense(tvg, sh, inp, "bf16", relu=relu, stream_out=True)
+        assert torch.equal(y1.view(torch.int16), y2.view(torch.int16))
+        check(to_host(y1), oracle_dense(sh, inp, relu=relu), "bf16", (cfg, variant))
+        # the general pointwise kernel on the same problem (stages = 1): same operator
+        assert tvg.tvg_conv2d_set_knobs(desc, (0, 0, 1, 0, 0, 0)) == 0
+        assert tvg.tvg_conv2d_get_plan(desc)[0] == 4
+        y3 = run_dense(tvg, sh, inp, "bf16", relu=relu)
+        check(to_host(y3), oracle_dense(sh, inp, relu=relu), "bf16", (cfg, variant, "general"))
+    finally:
+        tvg.tvg_conv2d_set_knobs(desc, None)
+
+
 def test_bf16_1x1_kernel_unaligned_input(tvg):
     """x at an 8-byte and at a 2-byte offset from an aligned address (the kernel needs 2-byte
     alignment only)."""
