@@ -30,6 +30,8 @@
 #include <stdlib.h>
 
 #include <numeric>
+#include <algorithm>
+
 #include "tvg_device.h"
 #include "tvg_internal.h"
 
@@ -55,7 +57,11 @@ struct PatchArgs {
     bf16_t *y2;
 };
 
-constexpr int kPosBytes = 48;    // 16 channels (32 B) + 16 B padding: conflict-free 16-byte reads
+// LDS layout: the two channel octets of a chunk live in separate PLANES of dense 16-byte words
+// (position-major), so the 16-byte reads of 16 consecutive lanes are 256 consecutive bytes:
+// conflict-free without padding (a 48-byte position stride did the same with half as much again
+// of LDS, which cost the 64-channel layers their third workgroup per CU).
+constexpr int kWordBytes = 16;
 constexpr int kChunk = 16;       // input channels per chunk = K of one 32x32x16 MFMA
 constexpr int kRsrcFlags = 0x00020000;   // raw buffer descriptor word 3 on gfx9-family targets
 
@@ -73,6 +79,8 @@ __device__ __forceinline__ uint32_t half_of(uint32_t d, int hi) { return hi ? d 
 // 128-bit loads, a half to an eighth of the vector memory instructions).
 // DUAL = the two-head variant (instances exist for the 64-channel tiles of 128 and 256 pixels).
 template <int MT, int NT, int STRIDE, int PT, int PX, bool DUAL = false>
+// (Three workgroups per CU were measured on C2 once the plane layout had made room in LDS: the
+// compiler then keeps the 64 x 256 tile in 168 registers with 16 spilled, 33.2 us against 23.6.)
 __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a)
 {
     // four waves as 2 x 2, or 1 x 4 for the wide 64 x 256 tile (the weights of a chunk weigh
@@ -81,11 +89,12 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
     constexpr int WM = NT == 256 ? 1 : 2, WN = 4 / WM;
     constexpr int WTM = MT / WM, WTN = NT / WN;
     constexpr int MI = WTM / 32, NJ = WTN / 32;
-    constexpr int ABYTES = 9 * MT * kPosBytes;
+    constexpr int APLANE = 9 * MT * kWordBytes + 128;     // (+128: the two planes' stores fall on different banks)
+    constexpr int ABYTES = 2 * APLANE;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    unsigned char *As = smem;              // [tap][oc][48 B]
-    unsigned char *Ps = smem + ABYTES;     // [virtual row][W + 2][48 B]
+    unsigned char *As = smem;              // [octet][tap][oc] 16-byte words
+    unsigned char *Ps = smem + ABYTES;     // [octet][virtual row][W + 2] 16-byte words
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WM, wn = wave / WM;
@@ -118,6 +127,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
     const int vr_lo = na * VH + oha * STRIDE;
     const int nrows = nb * VH + ohb * STRIDE + 2 - vr_lo + 1;
     const int npos = nrows * PW;
+    const int pplane = npos * kWordBytes;          // one octet plane of this tile's patch
 
     float *ss_lds = reinterpret_cast<float *>(smem + a.ss_offset);
 
@@ -149,7 +159,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
                     goff[j] = 2u * (uint32_t)((n * a.IC + octet * 8) * HW + ih * W + iw);
                     const int col = iw + 1;       // patch column (0 = left padding)
                     const int pos = STRIDE == 2 ? ((col & 1) ? HALF + (col >> 1) : (col >> 1)) : col;
-                    loff[j] = (vrow * PW + pos) * kPosBytes + octet * 16;
+                    loff[j] = octet * pplane + (vrow * PW + pos) * kWordBytes;
                     nvalid[j] = min(PX, W - iw);
                 }
             }
@@ -161,13 +171,13 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
         const int p = n0 + wn * WTN + j * 32 + lrow;
-        pb[j] = lhalf * 16;
+        pb[j] = lhalf * pplane;
         if (p < a.npix) {
             int rem, ow;
             const int n = fast_div(p, OHW, inv_ohw, &rem);
             const int oh = fast_div(rem, a.OW, inv_ow, &ow);
             // (stride 2: column 2*ow is even, at position ow of its row)
-            pb[j] += ((n * VH + oh * STRIDE - vr_lo) * PW + ow) * kPosBytes;
+            pb[j] += ((n * VH + oh * STRIDE - vr_lo) * PW + ow) * kWordBytes;
         }
     }
 
@@ -240,8 +250,8 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
                                    (half_of(praw[j][2 * q + 1][k >> 1], k & 1) << 16);
                         // stride 2 (PX > 1: the task starts on an odd patch column): pixels
                         // alternate between the odd and the even half of the row
-                        const int koff = STRIDE == 2 ? ((k & 1) ? (1 - HALF) * kPosBytes : 0) + (k >> 1) * kPosBytes
-                                                     : k * kPosBytes;
+                        const int koff = STRIDE == 2 ? ((k & 1) ? (1 - HALF) * kWordBytes : 0) + (k >> 1) * kWordBytes
+                                                     : k * kWordBytes;
                         *reinterpret_cast<uint4v *>(Ps + loff[j] + koff) = uint4v{o[0], o[1], o[2], o[3]};
                     }
                 }
@@ -262,7 +272,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
                     const int e0 = (2 * q) * 9 + tap, e1 = (2 * q + 1) * 9 + tap;
                     o[q] = half_of(d[e0 >> 1], e0 & 1) | (half_of(d[e1 >> 1], e1 & 1) << 16);
                 }
-                *reinterpret_cast<uint4v *>(As + (tap * MT + w_ocl) * kPosBytes + w_oct * 16) =
+                *reinterpret_cast<uint4v *>(As + w_oct * APLANE + (tap * MT + w_ocl) * kWordBytes) =
                     uint4v{o[0], o[1], o[2], o[3]};
             }
         }
@@ -281,7 +291,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
     // their latency: zero the patch once (padding rows and columns are never written
     // again) and stage the tile's (scale, offset) pairs.
     load_chunk(0);
-    for (int i = tid; i < npos * (kPosBytes / 16); i += 256)
+    for (int i = tid; i < 2 * npos; i += 256)
         reinterpret_cast<uint4v *>(Ps)[i] = uint4v{0u, 0u, 0u, 0u};
     stage_scale_shift(ss_lds, m0, MT, a.scale, a.shift, a.bias, a.OC, tid, 256);
     __syncthreads();          // patch zeroing complete before the first real data lands
@@ -290,7 +300,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
 
     const bool head2 = DUAL && m0 >= a.oc1;                 // (uniform)
     const bool centre_only = head2 && a.centre2 != 0;
-    const unsigned char *Abase = As + (wm * WTM + lrow) * kPosBytes + lhalf * 16;
+    const unsigned char *Abase = As + lhalf * APLANE + (wm * WTM + lrow) * kWordBytes;
     for (int c = 0; c < nchunks; ++c) {
         // All of the next chunk's loads are issued before this chunk's MFMAs: measured, issuing
         // them in slices between the taps leaves them too little time to arrive.
@@ -300,11 +310,11 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
         uint4v af[2][MI], bf[2][NJ];
         auto fetch = [&](int tap, int slot) {
             const int r = tap / 3, s = tap - r * 3;
-            const int toff = (r * PW + (STRIDE == 2 ? (s == 1 ? HALF : (s >> 1)) : s)) * kPosBytes;
+            const int toff = (r * PW + (STRIDE == 2 ? (s == 1 ? HALF : (s >> 1)) : s)) * kWordBytes;
 #pragma unroll
             for (int i = 0; i < MI; ++i)
                 af[slot][i] =
-                    *reinterpret_cast<const uint4v *>(Abase + (tap * MT + i * 32) * kPosBytes);
+                    *reinterpret_cast<const uint4v *>(Abase + (tap * MT + i * 32) * kWordBytes);
 #pragma unroll
             for (int j = 0; j < NJ; ++j)
                 bf[slot][j] = *reinterpret_cast<const uint4v *>(Ps + pb[j] + toff);
@@ -348,7 +358,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
 
     // ---- fused tail: transpose each 32x32 tile through LDS, vector stores -----------------
     __syncthreads();                       // every wave is done reading the operand tiles
-    // up to two tiles per wave are staged at a time: 20 KB, less than any instance's operands
+    // up to two tiles per wave are staged at a time: 20 KB (the host sizes the LDS for it)
     constexpr int BT = MI * NJ >= 2 ? 2 : 1;
     unsigned char *stage = smem + wave * (BT * kStageBytes);
     if (head2) {
@@ -491,8 +501,9 @@ bool plan_conv3x3_patch(const ConvProblem &p, Patch3x3Plan *plan, int single_sta
         }
         int pt = (2 * rows * ((p.W + px - 1) / px) + 255) / 256;
         if (px == 2 && pt > 4) { px = 1; pt = (2 * rows * p.W + 255) / 256; }
-        const size_t lds = (size_t)9 * mt * kPosBytes + (size_t)rows * (p.W + 2) * kPosBytes +
-                           (size_t)mt * 8;      // operands + (scale, offset) pairs
+        // operand planes (the tail's staging areas, 20 KB, reuse them) + (scale, offset) pairs
+        const size_t lds = std::max(2 * ((size_t)9 * mt * kWordBytes + 128) + 2 * (size_t)rows * (p.W + 2) * kWordBytes,
+                                    (size_t)4 * 2 * kStageBytes) + (size_t)mt * 8;
         const long tiles = (long)((p.OC + mt - 1) / mt) * ((p.npix + nt - 1) / nt);
         Patch3x3Plan cand{mt, nt, pt, px, rows, lds, tiles, 0, 0, 0, 0, 0, 1,
                           knobs.split_k, knobs.lds_pitch, knobs.row_loads, knobs.stages};
