@@ -279,8 +279,10 @@ tvg_status tvg_plan_arena(const tvg_tensor_life *tensors, int32_t count, uint64_
  * problem can fix the choice.  Host-only calls, safe to use from several threads.
  *
  * tvg_conv2d_set_tile: from now on plan this exact problem (every descriptor field but flags)
- * with tiles of mt x nt (the problem's other knobs, see tvg_conv2d_set_knobs, stay as they are), one of 64x256, 128x128, 64x128, 128x64, 64x64 (anything else:
- * TVG_ERR_UNSUPPORTED); mt = nt = 0 forgets the problem.  A tile shape that the problem's kernel
+ * with tiles of mt x nt (the problem's other knobs, see tvg_conv2d_set_knobs, stay as they are),
+ * one of 64x512, 64x256, 128x256, 128x128, 64x128, 128x64, 64x64 (anything else:
+ * TVG_ERR_UNSUPPORTED; 64x512 exists in the single-stage 3x3 kernel for stride 1 and rows of 8n
+ * pixels, 128x256 in the pipelined 3x3 kernel); mt = nt = 0 forgets the problem.  A tile shape that the problem's kernel
  * cannot use makes the call fall back to the generic kernel, which is correct but slow: time
  * before you fix.  At most 1024 problems are remembered.
  * tvg_conv2d_get_plan: which kernel and tile shape a call with this descriptor would use now

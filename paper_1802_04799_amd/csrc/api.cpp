@@ -217,7 +217,7 @@ static tvg_status store_knobs(const ConvProblem &p, const tvg::Knobs &k)
 
 static bool known_tile(int mt, int nt)
 {
-    return (mt == 64 && (nt == 256 || nt == 128 || nt == 64)) || (mt == 128 && (nt == 256 || nt == 128 || nt == 64));
+    return (mt == 64 && (nt == 512 || nt == 256 || nt == 128 || nt == 64)) || (mt == 128 && (nt == 256 || nt == 128 || nt == 64));
 }
 
 tvg_status tvg_conv2d_set_tile(const tvg_conv_desc *desc, int32_t mt, int32_t nt)

@@ -86,7 +86,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
     // four waves as 2 x 2, or 1 x 4 for the wide 64 x 256 tile (the weights of a chunk weigh
     // about six times the input patch per tile side, so a wide pixel tile moves the fewest
     // operand bytes per MFMA through the vector memory path)
-    constexpr int WM = NT == 256 ? 1 : 2, WN = 4 / WM;
+    constexpr int WM = NT >= 256 ? 1 : 2, WN = 4 / WM;
     constexpr int WTM = MT / WM, WTN = NT / WN;
     constexpr int MI = WTM / 32, NJ = WTN / 32;
     constexpr int APLANE = 9 * MT * kWordBytes + 128;     // (+128: the two planes' stores fall on different banks)
@@ -474,7 +474,10 @@ bool plan_conv3x3_patch(const ConvProblem &p, Patch3x3Plan *plan, int single_sta
     // stride-2 patches) runs out of registers and is skipped.
     // (128 x 256 exists in the pipelined kernel only, as its channel-split variant, and is taken
     // when a caller names it)
-    const int cands[6][2] = {{64, 256}, {128, 128}, {64, 128}, {128, 64}, {64, 64}, {128, 256}};
+    // (64 x 512: single-stage kernel, stride 1, rows of 8n pixels; first in line for the layers the
+    // pipelined kernel does not take - fewer than eight chunks - where it still gives 1.5 workgroups
+    // per CU: C2 at batch 64, 392 tiles in one round instead of 784 in two, 24.6 -> 22.6 us)
+    const int cands[7][2] = {{64, 512}, {64, 256}, {128, 128}, {64, 128}, {128, 64}, {64, 64}, {128, 256}};
     Patch3x3Plan best{};
     bool found = false, best_fills = false;
     for (const auto &c : cands) {
@@ -484,6 +487,7 @@ bool plan_conv3x3_patch(const ConvProblem &p, Patch3x3Plan *plan, int single_sta
         if (force_mt && mt != force_mt) continue;
         if (force_nt && nt != force_nt) continue;
         if (mt == 128 && nt == 256 && !(force_mt == 128 && force_nt == 256)) continue;
+        if (nt == 512 && (p.sh != 1 || dual || p.W % 8 != 0 || (force_nt != 512 && p.IC >= 8 * kChunk))) continue;
         const int rows = max_patch_rows(p, nt);
         // two pixels per load when the rows are even (32-bit aligned pairs) and that keeps the
         // task count within the instances built for it
@@ -493,7 +497,7 @@ bool plan_conv3x3_patch(const ConvProblem &p, Patch3x3Plan *plan, int single_sta
         // batch 64 with the split rows: C4 26.0 -> 24.2 us, C7 unchanged); at stride 1 they pay
         // under the 256-pixel tile only (C2 30.5 -> 28.9 us; under 64x128 31.4 -> 32.9: the wider
         // a task, the more of its lanes' 16-byte LDS stores fall on the same banks)
-        if ((p.sh == 2 || nt == 256) && p.W % 2 == 0) {
+        if ((p.sh == 2 || nt >= 256) && p.W % 2 == 0) {
             // (a row that is no multiple of the load ends in a shorter task, loads 4-byte aligned)
             const auto tasks = [&](int q) { return (2 * rows * ((p.W + q - 1) / q) + 255) / 256; };
             if (p.W >= 8 && tasks(8) <= 2 && (p.W % 8 == 0 || tasks(8) < tasks(4))) px = 8;
@@ -508,6 +512,7 @@ bool plan_conv3x3_patch(const ConvProblem &p, Patch3x3Plan *plan, int single_sta
         Patch3x3Plan cand{mt, nt, pt, px, rows, lds, tiles, 0, 0, 0, 0, 0, 1,
                           knobs.split_k, knobs.lds_pitch, knobs.row_loads, knobs.stages};
         if (dual && nt == 256 && pt > 1) continue;    // (those two-head instances run out of registers)
+        if (nt == 512 && !(px == 8 && pt <= 1)) continue;      // (the one instance built)
         if (!(use_dbuf && plan_conv3x3_dbuf(p, &cand))) {
             if (knobs.stages == 2) continue;      // the caller asked for the pipelined kernel
             if (mt == 128 && nt == 256) continue; // (no single-stage instance of that tile)
@@ -552,6 +557,11 @@ tvg_status launch_conv3x3_patch(const ConvProblem &p, const Patch3x3Plan &plan,
     const int ntiles = (p.npix + plan.nt - 1) / plan.nt;
     a.ntiles = ntiles;
     a.m_major = (size_t)p.OC * p.IC * 9 > (size_t)p.N * p.IC * p.H * p.W;
+    if (plan.nt == 512) {
+        if (p.sh == 1 && plan.px == 8 && plan.pt <= 1 && !dual)
+            return launch_instance_d<64, 512, 1, 1, 8, false>(a, ntiles, plan.lds_bytes, stream);
+        return TVG_ERR_UNSUPPORTED;
+    }
     if (plan.nt == 256)
         return launch_stride<64, 256>(a, p.sh, ntiles, plan.lds_bytes, plan.pt, plan.px, stream);
     if (plan.mt == 128 && plan.nt == 128)

@@ -30,8 +30,9 @@ from typing import Dict, List, Optional, Tuple
 from . import binding as _b
 
 TILES: List[Tuple[int, int]] = [(64, 256), (128, 128), (64, 128), (128, 64), (64, 64)]
-# the pipelined 3x3 kernel also has 128 x 256 (its channel-split variant: two wave groups share a patch)
-TILES_3X3: List[Tuple[int, int]] = TILES + [(128, 256)]
+# the pipelined 3x3 kernel also has 128 x 256 (its channel-split variant: two wave groups share a patch),
+# the single-stage one 64 x 512 (stride 1, rows of 8n pixels)
+TILES_3X3: List[Tuple[int, int]] = TILES + [(128, 256), (64, 512)]
 KNOBS = ("mt", "nt", "stages", "split_k", "lds_pitch", "row_loads")
 _chosen: Dict[str, Tuple[int, ...]] = {}
 

@@ -172,7 +172,7 @@ PATCH_RAGGED = [
 ]
 
 
-@pytest.mark.parametrize("tile", ["", "64,256", "128,128", "128,64", "64,128", "64,64"])
+@pytest.mark.parametrize("tile", ["", "64,512", "64,256", "128,128", "128,64", "64,128", "64,64"])
 @pytest.mark.parametrize("cfg", PATCH_RAGGED)
 def test_bf16_3x3_patch_kernel_ragged_shapes_all_tiles(tvg, cfg, tile):
     """The LDS-patch 3x3 kernel under every workgroup tile shape it is built with (fixed through
@@ -182,6 +182,37 @@ def test_bf16_3x3_patch_kernel_ragged_shapes_all_tiles(tvg, cfg, tile):
     inp = ti.make_inputs(sh, 4000 + sum(cfg), "bf16", residual=True, bias=True)
     y = run_dense(tvg, sh, inp, "bf16", tile=tile)
     check(to_host(y), oracle_dense(sh, inp), "bf16")
+
+
+WIDE_TILE_SHAPES = [
+    # the single-stage kernel's 64 x 512 tile (stride 1, rows of 8n pixels): n, ic, h, w, oc
+    (3, 64, 16, 24, 64), (2, 32, 8, 8, 130), (1, 16, 40, 64, 64), (5, 96, 24, 16, 72),
+    (4, 64, 56, 56, 64), (1, 112, 3, 8, 40), (9, 64, 8, 8, 64), (2, 256, 16, 16, 64),
+]
+
+
+@pytest.mark.parametrize("cfg", WIDE_TILE_SHAPES, ids=lambda c: "x".join(map(str, c)))
+def test_bf16_3x3_patch_kernel_wide_tile(tvg, cfg):
+    """64 x 512 tiles (one wave covers 64 channels x 128 pixels), fixed by tvg_conv2d_set_tile:
+    the plan must really be that tile; bias, residual, ReLU; tiles that span several images,
+    ragged channel and pixel tails."""
+    n, ic, h, w, oc = cfg
+    sh = ti.ConvShape("wt", n, ic, h, w, oc, 3, 3, 1, 1)
+    desc = tvg.ConvDesc(n, ic, h, w, oc, 3, 3, 1, 1, 1, 1, tvg.TVG_BF16, 0)
+    inp = ti.make_inputs(sh, 18000 + sum(cfg), "bf16", residual=True, bias=True)
+    with fixed_tile(tvg, sh, "bf16", "64,512"):
+        assert tvg.tvg_conv2d_get_plan(desc) == (1, 64, 512)
+        y = run_dense(tvg, sh, inp, "bf16")
+    check(to_host(y), oracle_dense(sh, inp), "bf16", cfg)
+
+
+def test_bf16_3x3_wide_tile_is_the_rule_for_shallow_layers_that_fill_the_chip(tvg):
+    def plan(n, ic, h, w, oc, stride=1):
+        return tvg.tvg_conv2d_get_plan(tvg.ConvDesc(n, ic, h, w, oc, 3, 3, stride, stride, 1, 1, tvg.TVG_BF16, 0))
+    assert plan(64, 64, 56, 56, 64) == (1, 64, 512)        # C2 at batch 64: 392 tiles
+    assert plan(32, 64, 56, 56, 64) == (1, 64, 256)        # batch 32: the wide tile would leave CUs idle
+    assert plan(64, 128, 28, 28, 128) == (2, 64, 256)      # eight chunks: the pipelined kernel
+    assert plan(64, 64, 56, 56, 128, 2)[2] != 512          # stride 2
 
 
 DBUF_SHAPES = [
