@@ -1,5 +1,8 @@
-// bf16 7x7 stride-2 pad-3 fused conv2d for very few input channels (the ResNet
-// stem, Table 2's C1: 3 -> 64 channels on 224x224), on MFMA.
+// bf16 stride-2 fused conv2d for very few input channels - 7x7 pad 3 (the ResNet stem, Table 2's
+// C1: 3 -> 64 channels on 224x224) and 3x3 pad 1 (the MobileNet stem, 3 -> 32) - on MFMA.  The
+// text below describes the 7x7 case; R is a template parameter, and a 3x3 filter row sits in
+// slots 3..5 of the same 8-slot window (the window of pixel (oh, ow) covers input columns
+// 2*ow - 4 .. 2*ow + 3 whatever R is).
 //
 // With IC = 3 the reduction (147) is too short and too ragged for the channel-
 // chunked kernels, and at batch 64 the layer is bound by writing its output
@@ -49,14 +52,15 @@ constexpr uint32_t kOutOfRange = 0xFFFFFFF0u;
 // IC = input channels (compile time, so the reduction loop unrolls completely and the LDS
 // reads of one MFMA step overlap the previous step's MFMAs); LT = 16-byte copy tasks per
 // thread per tile.
-template <int IC, int LT>
-__global__ __launch_bounds__(256, 2) void conv7x7s2_stem_kernel(const StemArgs a)
+template <int R, int IC, int LT>
+__global__ __launch_bounds__(256, 2) void conv_stem_s2_kernel(const StemArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    constexpr int npairs = IC * 7;
+    constexpr int PAD = R / 2;
+    constexpr int npairs = IC * R;
     constexpr int NM = (npairs + 1) / 2;                 // MFMAs over the reduction
     const int H = a.H, W = a.W, OHW = a.OH * a.OW;
-    const int VH = H + 6;                                // virtual rows per image (3 + H + 3)
+    const int VH = H + 2 * PAD;                          // virtual rows per image (pad + H + pad)
     const int pitch = (W + 8) * 2;                       // bytes per staged row
     const int nrows = a.nrows;
     const int a_bytes = 2 * NM * kMT * 16;
@@ -83,7 +87,7 @@ __global__ __launch_bounds__(256, 2) void conv7x7s2_stem_kernel(const StemArgs a
     // as 16-byte vectors that are all in flight together, then scattered element by element
     // into [pair = (ic, r)][oc][slot = s + 1] (slot 0, the odd pair and absent channels stay 0)
     {
-        constexpr int KW = IC * 49;                      // weights per output channel
+        constexpr int KW = IC * R * R;                   // weights per output channel
         constexpr int WV = (kMT * KW + 7) / 8;           // vectors per full tile
         constexpr int WT = (WV + 255) / 256;             // vectors per thread
         const int count = min(kMT, a.OC - m0) * KW;
@@ -105,7 +109,7 @@ __global__ __launch_bounds__(256, 2) void conv7x7s2_stem_kernel(const StemArgs a
             for (int k = 0; k < 8; ++k) {
                 const int f = f0 + k;
                 const int ocl = f / KW, rem = f - ocl * KW;
-                const int pair = rem / 7, sp = rem - pair * 7 + 1;
+                const int pair = rem / R, sp = rem - pair * R + (4 - PAD);
                 const bf16_t v = (bf16_t)(k & 1 ? wv[j][k >> 1] >> 16 : wv[j][k >> 1] & 0xffffu);
                 if (f < count) reinterpret_cast<bf16_t *>(As)[(pair * kMT + ocl) * 8 + sp] = v;
             }
@@ -148,7 +152,7 @@ __global__ __launch_bounds__(256, 2) void conv7x7s2_stem_kernel(const StemArgs a
         for (int j = 0; j < LT; ++j) {
             int vi = vi_lo + rslot[j], n = n_lo;
             if (vi >= VH) { vi -= VH; n += 1; }
-            const int ih = vi - 3;
+            const int ih = vi - PAD;
             const bool ok = rslot[j] >= 0 && ih >= 0 && ih < H && n < a.N;
             const uint32_t voff = ok ? cgoff[j] + (uint32_t)((n * IC * H + ih) * W) * 2u : kOutOfRange;
             lreg[j] = __builtin_bit_cast(uint4v, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, voff, 0, 0));
@@ -202,8 +206,8 @@ __global__ __launch_bounds__(256, 2) void conv7x7s2_stem_kernel(const StemArgs a
         for (int m = 0; m < NM; ++m) {
             // the two half-waves hold pairs 2m and 2m+1; both offsets are uniform values
             const int pa = 2 * m, pq = 2 * m + 1 < npairs ? 2 * m + 1 : 0;
-            const int offa = ((pa / 7) * nrows + pa % 7) * pitch;
-            const int offq = ((pq / 7) * nrows + pq % 7) * pitch;
+            const int offa = ((pa / R) * nrows + pa % R) * pitch;
+            const int offq = ((pq / R) * nrows + pq % R) * pitch;
             const int poff = lhalf ? offq : offa;
             uint4v af[2], bf[2];
 #pragma unroll
@@ -235,7 +239,7 @@ __global__ __launch_bounds__(256, 2) void conv7x7s2_stem_kernel(const StemArgs a
 
 int max_stem_rows(const ConvProblem &p)
 {
-    const int OHW = p.OH * p.OW, VH = p.H + 6;
+    const int OHW = p.OH * p.OW, VH = p.H + 2 * p.ph;
     int best = 0;
     // the row count of a tile depends only on where in an image it starts, which repeats after
     // OHW / gcd(OHW, kNT) tiles: one period covers every case (this runs on every call)
@@ -244,16 +248,16 @@ int max_stem_rows(const ConvProblem &p)
         const long last = (p0 + kNT < p.npix ? p0 + kNT : p.npix) - 1;
         const int na = (int)(p0 / OHW), oha = (int)((p0 - (long)na * OHW) / p.OW);
         const int nb = (int)(last / OHW), ohb = (int)((last - (long)nb * OHW) / p.OW);
-        const int rows = nb * VH + ohb * 2 + 6 - (na * VH + oha * 2) + 1;
+        const int rows = nb * VH + ohb * 2 + (p.R - 1) - (na * VH + oha * 2) + 1;
         if (rows > best) best = rows;
     }
     return best;
 }
 
-template <int IC, int LT>
+template <int R, int IC, int LT>
 tvg_status launch_lt(const StemArgs &a, unsigned grid, size_t lds, hipStream_t stream)
 {
-    auto kernel = conv7x7s2_stem_kernel<IC, LT>;
+    auto kernel = conv_stem_s2_kernel<R, IC, LT>;
     static bool configured = false;
     if (!configured) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
@@ -269,15 +273,15 @@ tvg_status launch_lt(const StemArgs &a, unsigned grid, size_t lds, hipStream_t s
 
 bool plan_conv7x7s2_stem(const ConvProblem &p, StemPlan *plan)
 {
-    if (p.dtype != TVG_BF16 || p.R != 7 || p.S != 7 || p.sh != 2 || p.sw != 2 || p.ph != 3 ||
-        p.pw != 3)
+    if (p.dtype != TVG_BF16 || (p.R != 7 && p.R != 3) || p.S != p.R || p.sh != 2 || p.sw != 2 ||
+        p.ph != p.R / 2 || p.pw != p.R / 2)
         return false;
     if (p.IC > 4 || p.W % 8 != 0) return false;
-    if (p.npix >= (1 << 22) || (long)p.N * (p.H + 6) >= (1 << 22)) return false;   // fast_div range
+    if (p.npix >= (1 << 22) || (long)p.N * (p.H + 2 * p.ph) >= (1 << 22)) return false;   // fast_div range
     if ((size_t)p.N * p.IC * p.H * p.W * 2 > (size_t)kOutOfRange) return false;
     const int rows = max_stem_rows(p);
-    if (rows > p.H + 6) return false;                   // a tile may wrap into the next image once
-    const int nm = (p.IC * 7 + 1) / 2;
+    if (rows > p.H + 2 * p.ph) return false;            // a tile may wrap into the next image once
+    const int nm = (p.IC * p.R + 1) / 2;
     const size_t lds = (size_t)2 * nm * kMT * 16 + (size_t)2 * p.IC * rows * (p.W + 8) * 2 +
                        (size_t)8 * kStageBytes + (size_t)kMT * 8;
     const int lt = (p.IC * rows * (p.W / 8) + 255) / 256;
@@ -316,14 +320,23 @@ tvg_status launch_conv7x7s2_stem(const ConvProblem &p, const StemPlan &plan, con
     // Buffer loads are range-checked per 4-byte word: an odd number of weights (odd OC x IC)
     // would leave the last one unreadable, so the size is rounded up to whole words (the two
     // bytes past the tensor lie in the same aligned word as its last element).
-    a.w_bytes = ((uint32_t)((size_t)p.OC * p.IC * 49 * 2) + 3u) & ~3u;
+    a.w_bytes = ((uint32_t)((size_t)p.OC * p.IC * p.R * p.R * 2) + 3u) & ~3u;
     const unsigned grid = (unsigned)(per * a.mtiles);
-    if (p.IC == 3 && plan.lt <= 5) return launch_lt<3, 5>(a, grid, plan.lds_bytes, stream);
+    if (p.R == 3) {
+        if (p.IC == 3 && plan.lt <= 5) return launch_lt<3, 3, 5>(a, grid, plan.lds_bytes, stream);
+        switch (p.IC) {
+        case 1: return launch_lt<3, 1, 8>(a, grid, plan.lds_bytes, stream);
+        case 2: return launch_lt<3, 2, 8>(a, grid, plan.lds_bytes, stream);
+        case 3: return launch_lt<3, 3, 8>(a, grid, plan.lds_bytes, stream);
+        default: return launch_lt<3, 4, 8>(a, grid, plan.lds_bytes, stream);
+        }
+    }
+    if (p.IC == 3 && plan.lt <= 5) return launch_lt<7, 3, 5>(a, grid, plan.lds_bytes, stream);
     switch (p.IC) {
-    case 1: return launch_lt<1, 8>(a, grid, plan.lds_bytes, stream);
-    case 2: return launch_lt<2, 8>(a, grid, plan.lds_bytes, stream);
-    case 3: return launch_lt<3, 8>(a, grid, plan.lds_bytes, stream);
-    default: return launch_lt<4, 8>(a, grid, plan.lds_bytes, stream);
+    case 1: return launch_lt<7, 1, 8>(a, grid, plan.lds_bytes, stream);
+    case 2: return launch_lt<7, 2, 8>(a, grid, plan.lds_bytes, stream);
+    case 3: return launch_lt<7, 3, 8>(a, grid, plan.lds_bytes, stream);
+    default: return launch_lt<7, 4, 8>(a, grid, plan.lds_bytes, stream);
     }
 }
 
