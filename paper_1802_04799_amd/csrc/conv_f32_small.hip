@@ -266,10 +266,204 @@ tvg_status launch_rs(const F32Args &a, int vec, dim3 grid, size_t lds, hipStream
     return hipGetLastError() == hipSuccess ? TVG_OK : TVG_ERR_LAUNCH;
 }
 
+// ---------------------------------------------------------------------------------------------
+// The same idea for the 7x7 stride-2 pad-3 stem with up to four input channels (C1 of Table 2 at
+// batch 1: K = 147, too short and too ragged to split by channels).  A workgroup owns 32 output
+// channels x 64 consecutive pixels of one image and has SEVEN waves, one per filter row: wave r
+// multiplies filter row r of every input channel - 8 tap slots per (channel, row), slot 0 a zero
+// weight, so that the window of pixel (oh, ow) starts at the even padded column 2 ow - into its
+// own accumulators; the seven partial tiles are added through LDS and the fused tail stores rows
+// of four pixels.  The input rows of the tile are staged once, shared by all waves, in their
+// natural layout with four zero columns on either side; the 32 x IC x 49 weights of the tile
+// are one contiguous run of the OIHW tensor, copied with coalesced loads into [row][channel]
+// [slot][oc] order, so that the 32 lanes of an operand read are 32 consecutive words.
+struct F32StemArgs {
+    const float *x, *w, *scale, *shift, *bias, *residual;
+    float *y;
+    int N, H, W, OC, OH, OW, relu;
+    int mtiles, tpi, nr, pw4;          // channel tiles, pixel tiles per image, staged rows, 16-byte words per staged row
+    float inv_rowwords, inv_pw4;       // reciprocals of nr * pw4 and pw4
+    int vec_out;
+    uint32_t x_bytes, w_bytes;
+};
+
+constexpr int kStemWaves = 7, kStemThreads = 64 * kStemWaves, kStemPix = 64;
+
+template <int IC>
+__global__ __launch_bounds__(kStemThreads) void conv_f32_stem_kernel(const F32StemArgs a)
+{
+    constexpr int R = 7, KW = IC * 49;
+    constexpr int WFLOATS = R * IC * 8 * 32;                 // staged weights
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lp = lane & 31, half = lane >> 5;
+    int b = blockIdx.x;
+    const int mt = b % a.mtiles;
+    b /= a.mtiles;
+    const int pt = b % a.tpi, n = b / a.tpi;
+    const int m0 = mt * 32, p0 = pt * kStemPix;
+    const int OHW = a.OH * a.OW, W = a.W, H = a.H;
+    const int npx = min(kStemPix, OHW - p0);
+    const int oh_lo = p0 / a.OW;
+    const int ih_lo = oh_lo * 2 - 3;
+    const int PW = a.pw4 * 4, nr = a.nr, plane = nr * PW;
+    float *wl = smem;                                        // [r][ic][slot][oc]
+    float *patch = smem + WFLOATS;                           // [ic][row][PW]
+
+    const __amdgpu_buffer_rsrc_t xrsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.x), 0, a.x_bytes, kRsrc);
+    const __amdgpu_buffer_rsrc_t wrsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.w), 0, a.w_bytes, kRsrc);
+
+    // ---- weights: element e of the tile's contiguous run -> (oc, ic, r, s); rows past OC read zeros
+    constexpr int WN = (32 * KW + kStemThreads - 1) / kStemThreads;
+    float wv[WN];
+#pragma unroll
+    for (int j = 0; j < WN; ++j) {
+        const int e = tid + j * kStemThreads;
+        const uint32_t off = e < 32 * KW ? 4u * (uint32_t)(m0 * KW + e) : 0xFFFFFFFCu;
+        wv[j] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(wrsrc, off, 0, 0));
+    }
+    // ---- patch: task = one 16-byte word of a staged row; the first and last word of a row are
+    // padding, rows outside the image come back as zeros (out-of-range offset)
+    const int ntask = IC * nr * a.pw4;
+    for (int t = tid; t < ntask; t += kStemThreads) {
+        int rem, j;
+        const int ic = fast_div(t, nr * a.pw4, a.inv_rowwords, &rem);
+        const int row = fast_div(rem, a.pw4, a.inv_pw4, &j);
+        const int ih = ih_lo + row;
+        const bool ok = j > 0 && j < a.pw4 - 1 && ih >= 0 && ih < H;
+        const uint32_t off = ok ? 4u * (uint32_t)(((n * IC + ic) * H + ih) * W + 4 * (j - 1)) : 0xFFFFFFF0u;
+        const uint4v v = __builtin_bit_cast(uint4v, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, off, 0, 0));
+        *reinterpret_cast<uint4v *>(patch + (ic * nr + row) * PW + 4 * j) = v;
+    }
+#pragma unroll
+    for (int j = 0; j < WN; ++j) {
+        const int e = tid + j * kStemThreads;
+        if (e < 32 * KW) {
+            const int oc = e / KW, rem = e - oc * KW;
+            const int ic = rem / 49, t = rem - ic * 49;
+            const int r = t / 7, s = t - r * 7;
+            wl[((r * IC + ic) * 8 + s + 1) * 32 + oc] = wv[j];
+        }
+    }
+    for (int i = tid; i < R * IC * 32; i += kStemThreads)   // slot 0 of every (row, channel)
+        wl[(i >> 5) * 8 * 32 + (i & 31)] = 0.0f;
+    __syncthreads();
+
+    // ---- wave r: filter row r of every channel, two blocks of 32 pixels ---------------------
+    int bbase[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int q = j * 32 + lp;
+        const int pp = q < npx ? q : 0;                      // lanes past the end shadow pixel 0
+        const int oh = (p0 + pp) / a.OW, ow = (p0 + pp) - oh * a.OW;
+        bbase[j] = ((oh - oh_lo) * 2 + wave) * PW + 2 * ow + half;
+    }
+    const int abase = (wave * IC * 8 + half) * 32 + lp;
+    float16v acc[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[j][v] = 0.0f;
+#pragma unroll
+    for (int ic = 0; ic < IC; ++ic)
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+            const float av = wl[abase + (ic * 8 + 2 * st) * 32];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const float bv = patch[bbase[j] + ic * plane + 2 * st];
+                // pixel operand first: the accumulator tile is D[pixel][channel]
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av, acc[j], 0, 0, 0);
+            }
+        }
+
+    // ---- the seven partial tiles meet in LDS (over the operands, which are done with) --------
+    __syncthreads();
+    float *part = smem;                                      // [block][wave][16][kPartPitch]
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) part[((j * kStemWaves + wave) * 16 + v) * kPartPitch + lane] = acc[j][v];
+    __syncthreads();
+    for (int g = tid; g < 512; g += kStemThreads) {
+        const int j = g >> 8, t = g & 255;
+        const int cc = t >> 3, pb = (t & 7) * 4;
+        const int src_lane = cc + 32 * ((pb >> 2) & 1), v0 = 4 * (pb >> 3);
+        float sum[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int s = 0; s < kStemWaves; ++s)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) sum[q] += part[((j * kStemWaves + s) * 16 + v0 + q) * kPartPitch + src_lane];
+        const int oc = m0 + cc, px = j * 32 + pb;
+        if (oc >= a.OC || px >= npx) continue;
+        const float sc = a.scale[oc];
+        const float sf = a.bias ? fmaf(a.bias[oc], sc, a.shift[oc]) : a.shift[oc];
+        const float floor_v = a.relu ? 0.0f : -INFINITY;
+        const int idx = (n * a.OC + oc) * OHW + p0 + px;
+        if (a.vec_out) {                                     // OHW % 4 == 0: the whole group is inside
+            float4v r4 = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (a.residual) r4 = *reinterpret_cast<const float4v *>(a.residual + idx);
+            float4v o;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) o[q] = fmaxf(fmaf(sum[q], sc, sf) + r4[q], floor_v);
+            *reinterpret_cast<float4v *>(a.y + idx) = o;
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (px + q < npx) {
+                    float o = fmaf(sum[q], sc, sf);
+                    if (a.residual) o += a.residual[idx + q];
+                    a.y[idx + q] = fmaxf(o, floor_v);
+                }
+        }
+    }
+}
+
+// Rows of input a tile of 64 consecutive pixels can touch, and the LDS it needs.
+static bool f32_stem_geometry(const ConvProblem &p, int *nr, int *pw4, size_t *lds)
+{
+    const int OHW = p.OH * p.OW;
+    const int orows = std::min(p.OH, (std::min(kStemPix, OHW) + p.OW - 2) / p.OW + 1);
+    *nr = (orows - 1) * 2 + 7;
+    *pw4 = p.W / 4 + 2;
+    const size_t operands = ((size_t)7 * p.IC * 8 * 32 + (size_t)p.IC * *nr * *pw4 * 4) * 4;
+    const size_t partials = (size_t)2 * kStemWaves * 16 * kPartPitch * 4;
+    *lds = std::max(operands, partials);
+    return *lds <= 80 * 1024;
+}
+
 }  // namespace
 
 bool plan_conv_f32_small(const ConvProblem &p, F32SmallPlan *plan)
 {
+    plan->stem = 0;
+    if (p.dtype == TVG_F32 && p.R == 7 && p.S == 7 && p.sh == 2 && p.sw == 2 && p.ph == 3 && p.pw == 3 &&
+        p.IC <= 4 && p.W % 4 == 0) {
+        // the 7x7 stem of launch-bound problems: one launch, seven waves split the filter rows
+        const Knobs knobs = forced_knobs(p);
+        if (knobs.split_k > 0 || knobs.mt > 0) return false;
+        const long gtiles = (long)((p.OC + 127) / 128) * ((p.npix + 127) / 128);
+        if (gtiles >= kComputeUnits) return false;
+        int nr, pw4;
+        size_t lds;
+        if (!f32_stem_geometry(p, &nr, &pw4, &lds)) return false;
+        if ((long)p.IC * nr * pw4 >= (1 << 22)) return false;                  // fast_div range
+        if ((size_t)p.N * p.IC * p.H * p.W >= ((size_t)1 << 30) || (size_t)p.OC * p.K >= ((size_t)1 << 30))
+            return false;                                                      // 32-bit byte offsets
+        if ((long)p.N * ((p.OH * p.OW + kStemPix - 1) / kStemPix) * ((p.OC + 31) / 32) >= (1L << 31)) return false;
+        plan->stem = 1;
+        plan->nw = kStemWaves;
+        plan->passes = 1;
+        plan->ksplit = 1;
+        plan->workspace_bytes = 0;
+        plan->pitch = pw4 * 4;
+        plan->region = nr;
+        plan->vec = 4;
+        plan->lds_bytes = lds;
+        return true;
+    }
     if (p.dtype != TVG_F32 || p.R != p.S || (p.R != 1 && p.R != 3)) return false;
     if (p.ph != p.R / 2 || p.pw != p.R / 2 || p.sh != p.sw || (p.sh != 1 && p.sh != 2)) return false;
     if (p.IC % (2 * kCPH) != 0) return false;
@@ -326,9 +520,45 @@ bool conv_f32_small_pointers_ok(const ConvPointers &ptr)
     return reinterpret_cast<uintptr_t>(ptr.x) % 16 == 0 && reinterpret_cast<uintptr_t>(ptr.w) % 4 == 0;
 }
 
+static tvg_status launch_conv_f32_stem(const ConvProblem &p, const F32SmallPlan &plan, const ConvPointers &ptr,
+                                       hipStream_t stream)
+{
+    F32StemArgs a;
+    a.x = static_cast<const float *>(ptr.x); a.w = static_cast<const float *>(ptr.w);
+    a.scale = ptr.scale; a.shift = ptr.shift; a.bias = ptr.bias;
+    a.residual = static_cast<const float *>(ptr.residual); a.y = static_cast<float *>(ptr.y);
+    a.N = p.N; a.H = p.H; a.W = p.W; a.OC = p.OC; a.OH = p.OH; a.OW = p.OW;
+    a.relu = p.relu;
+    a.mtiles = (p.OC + 31) / 32;
+    a.tpi = (p.OH * p.OW + kStemPix - 1) / kStemPix;
+    a.nr = plan.region;
+    a.pw4 = plan.pitch / 4;
+    a.inv_rowwords = 1.0f / (float)(a.nr * a.pw4);
+    a.inv_pw4 = 1.0f / (float)a.pw4;
+    a.vec_out = (p.OH * p.OW) % 4 == 0 && reinterpret_cast<uintptr_t>(ptr.y) % 16 == 0 &&
+                reinterpret_cast<uintptr_t>(ptr.residual) % 16 == 0;
+    a.x_bytes = (uint32_t)((size_t)p.N * p.IC * p.H * p.W * 4);
+    a.w_bytes = (uint32_t)((size_t)p.OC * p.IC * 49 * 4);
+    const dim3 grid((unsigned)((long)a.mtiles * a.tpi * p.N));
+    auto go = [&](auto kernel) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+            return TVG_ERR_LAUNCH;
+        hipLaunchKernelGGL(kernel, grid, dim3(kStemThreads), plan.lds_bytes, stream, a);
+        return hipGetLastError() == hipSuccess ? TVG_OK : TVG_ERR_LAUNCH;
+    };
+    switch (p.IC) {
+    case 1: return go(conv_f32_stem_kernel<1>);
+    case 2: return go(conv_f32_stem_kernel<2>);
+    case 3: return go(conv_f32_stem_kernel<3>);
+    default: return go(conv_f32_stem_kernel<4>);
+    }
+}
+
 tvg_status launch_conv_f32_small(const ConvProblem &p, const F32SmallPlan &plan, const ConvPointers &ptr,
                                  hipStream_t stream)
 {
+    if (plan.stem) return launch_conv_f32_stem(p, plan, ptr, stream);
     F32Args a;
     a.x = static_cast<const float *>(ptr.x); a.w = static_cast<const float *>(ptr.w);
     a.scale = ptr.scale; a.shift = ptr.shift; a.bias = ptr.bias;

@@ -154,6 +154,7 @@ struct F32SmallPlan {
     int pitch, region;  // LDS row pitch and floats per wave
     int vec;            // floats per patch load: 4, 2 or 1 (rows of 4n, 2n, other pixel counts)
     int ksplit;         // slices of the reduction across workgroups (1 = none, else a reduce launch follows)
+    int stem;           // 1 = the 7x7 stride-2 variant (seven waves, one per filter row; region = staged rows)
     size_t lds_bytes, workspace_bytes;
 };
 // Adds `splits` partial results [splits][N][OC][OH][OW] in ptr.workspace in a fixed order and

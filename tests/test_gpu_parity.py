@@ -516,6 +516,31 @@ def test_fp32_small_kernel_shapes(tvg, cfg):
     assert (y3 < 0).any()
 
 
+F32_STEM = [
+    # fp32 7x7 stride-2 pad-3 problems with at most four input channels and rows of 4n pixels (the
+    # one-launch stem kernel of launch-bound problems): n, ic, h, w, oc
+    (1, 3, 224, 224, 64), (2, 3, 32, 32, 64), (3, 1, 40, 24, 70), (1, 4, 16, 16, 8), (5, 3, 18, 8, 33),
+    (2, 2, 50, 48, 100), (1, 3, 9, 12, 40), (2, 3, 64, 4, 32), (1, 3, 2, 4, 5), (1, 4, 31, 132, 64),
+]
+
+
+@pytest.mark.parametrize("variant", ["plain", "bias+residual", "no-relu"])
+@pytest.mark.parametrize("cfg", F32_STEM, ids=lambda c: "x".join(map(str, c)))
+def test_fp32_stem_kernel_shapes(tvg, cfg, variant):
+    """Seven waves, one per filter row, partial tiles added through LDS: full fused tail, tiles that
+    end in the middle of a row, maps smaller than a tile, channel tails."""
+    n, ic, h, w, oc = cfg
+    sh = ti.ConvShape("f32stem", n, ic, h, w, oc, 7, 7, 2, 3)
+    desc = tvg.ConvDesc(n, ic, h, w, oc, 7, 7, 2, 2, 3, 3, tvg.TVG_F32, 0)
+    assert tvg.tvg_conv2d_get_plan(desc)[0] == 5
+    assert tvg.tvg_conv2d_workspace_size(desc) == 0
+    inp = ti.make_inputs(sh, 19000 + sum(cfg) + len(variant), "f32", residual="residual" in variant,
+                         bias="bias" in variant)
+    relu = "no-relu" not in variant
+    y = run_dense(tvg, sh, inp, "f32", relu=relu)
+    check(to_host(y), oracle_dense(sh, inp, relu=relu), "f32", (cfg, variant))
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_rectangular_filter_and_strides(tvg, dtype):
     import torch

@@ -38,11 +38,11 @@ def test_static_scratch_entry_point_two_calls_in_a_row(tvg):
     import torch
     assert tvg.tvg_static_scratch_bytes() == 16 << 20
     # Problems whose reduction the generic kernel splits across workgroups (fp32 shapes the
-    # one-launch fp32 kernel does not take: a 7x7 filter, input channels no multiple of 8).
-    # first call: C1 at batch 1 (6.4 MB of partials); then 512 x 100 channels on a 7x7 map
+    # one-launch fp32 kernels do not take: a 5x5 filter, input channels no multiple of 8).
+    # first call: a 5x5 stride-2 layer on a 224x224 map (6.4 MB of partials); then 512 x 100 channels on a 7x7 map
     # (1.4 MB), then a small ragged problem (42 KB) - each finds the previous call's partials in
     # the array; last a bf16 problem that needs none
-    calls = [(ti.resnet18_convs(1)[0], ti.layer_seed(2, 0), "f32"),
+    calls = [(ti.ConvShape("five", 1, 5, 224, 224, 64, 5, 5, 2, 2), 29, "f32"),
              (ti.ConvShape("mid", 1, 100, 7, 7, 512, 3, 3, 1, 1), 30, "f32"),
              (ti.ConvShape("small", 1, 36, 5, 6, 70, 3, 3, 1, 1), 31, "f32"),
              (ti.ConvShape("small16", 2, 64, 6, 5, 33, 3, 3, 2, 1), 32, "bf16")]
