@@ -184,9 +184,12 @@ __global__ __launch_bounds__(256) void dwconv3x3_direct_kernel(const DwDirectArg
     const int iw0 = ow0 * STRIDE;                     // first in-image column of the vectors
 #pragma unroll
     for (int rr = 0; rr < IR; ++rr) {
+        // A padding row is read from the nearest image row and replaced by zeros: with no
+        // branch around the loads all rows of the block are in flight at once (one memory round
+        // trip per lane instead of one per row, which is what a launch of few waves waits for).
         const int ih = oh0 * STRIDE - 1 + rr;
-        if (ih < 0 || ih >= H) continue;              // a padding row contributes nothing
-        const float *row = xp + ih * W + iw0;
+        const bool rowok = ih >= 0 && ih < H;
+        const float *row = xp + min(max(ih, 0), H - 1) * W + iw0;
         float v[NV];                                  // columns iw0 - 1 .. iw0 + NV - 2
         v[0] = iw0 > 0 ? row[-1] : 0.0f;
         const float4v m0 = *reinterpret_cast<const float4v *>(row);
@@ -197,6 +200,8 @@ __global__ __launch_bounds__(256) void dwconv3x3_direct_kernel(const DwDirectArg
             const float4v m1 = *reinterpret_cast<const float4v *>(row + 4);
             v[5] = m1[0]; v[6] = m1[1]; v[7] = m1[2]; v[8] = m1[3];
         }
+#pragma unroll
+        for (int e = 0; e < NV; ++e) v[e] = rowok ? v[e] : 0.0f;
 #pragma unroll
         for (int o = 0; o < kRB; ++o) {
             const int r = rr - o * STRIDE;
@@ -272,6 +277,9 @@ __global__ __launch_bounds__(256) void dwconv3x3_direct_bf16_kernel(const DwDire
     const int iw0 = ow0 * STRIDE;
 #pragma unroll
     for (int rr = 0; rr < IR; ++rr) {
+        // (the branch stays here: hoisting all rows of a block, up to 9 x 18 pixels, costs this
+        // kernel more in occupancy than the serial round trips do - 14 -> 18 us on the 112x112
+        // MobileNet layers at batch 32 - where the fp32 kernel above gains 12-20 %)
         const int ih = oh0 * STRIDE - 1 + rr;
         if (ih < 0 || ih >= H) continue;              // a padding row contributes nothing
         const bf16_t *row = xp + ih * W + iw0;
@@ -446,6 +454,183 @@ void launch_smallplane(const DwSmallArgs &d, bool nt, unsigned blocks, size_t ld
                            stream, d);
 }
 
+// Variant for the narrow maps of the late layers (output rows of 14 or 7 pixels: D6..D9 of Table 2
+// and the MobileNet body behind them) when there are enough planes to fill the chip.  A lane owns
+// ONE output row of one plane: it reads its three input rows whole (rows of 14 or 28 pixels are 28
+// to 112 contiguous bytes, fetched as dword-aligned 16-byte vectors plus a remainder), keeps them
+// in registers with a zero column on either side, and writes the output row as one contiguous run.
+// There is no LDS, no barrier and no per-element index arithmetic: the small-plane kernel above
+// spends some 60 vector instructions per output (offsets, masks, LDS reads of taps that change with
+// every plane) and was bound by instruction issue, not by memory - 11.1 us against 4.9 us here on
+// the 14x14x512 bf16 layer at batch 32; a lane per output-row PAIR or per plane is slower again
+// (5.9, 11.2 us: fewer, fatter waves).  Neighbouring lanes re-read two of the three rows; the
+// caches serve that.  With few planes (batch 1) the small-plane kernel's finer split wins.
+typedef uint32_t uint4a __attribute__((ext_vector_type(4), aligned(4)));
+typedef uint32_t uint3a __attribute__((ext_vector_type(3), aligned(4)));
+typedef uint32_t uint2a __attribute__((ext_vector_type(2), aligned(4)));
+
+template <int NW>
+__device__ __forceinline__ void load_words(const uint32_t *p, uint32_t (&w)[NW])
+{
+#pragma unroll
+    for (int k = 0; k + 4 <= NW; k += 4) {
+        const uint4a m = *reinterpret_cast<const uint4a *>(p + k);
+        w[k] = m[0]; w[k + 1] = m[1]; w[k + 2] = m[2]; w[k + 3] = m[3];
+    }
+    constexpr int B = NW / 4 * 4;
+    if constexpr (NW % 4 == 3) {
+        const uint3a m = *reinterpret_cast<const uint3a *>(p + B);
+        w[B] = m[0]; w[B + 1] = m[1]; w[B + 2] = m[2];
+    }
+    if constexpr (NW % 4 == 2) {
+        const uint2a m = *reinterpret_cast<const uint2a *>(p + B);
+        w[B] = m[0]; w[B + 1] = m[1];
+    }
+    if constexpr (NW % 4 == 1) w[B] = p[B];
+}
+
+template <bool NT, int NW>
+__device__ __forceinline__ void store_words(uint32_t *p, const uint32_t (&w)[NW])
+{
+#pragma unroll
+    for (int k = 0; k + 4 <= NW; k += 4) {
+        uint4a m;
+        m[0] = w[k]; m[1] = w[k + 1]; m[2] = w[k + 2]; m[3] = w[k + 3];
+        if constexpr (NT) __builtin_nontemporal_store(m, reinterpret_cast<uint4a *>(p + k));
+        else *reinterpret_cast<uint4a *>(p + k) = m;
+    }
+    constexpr int B = NW / 4 * 4;
+    if constexpr (NW % 4 == 3) {
+        uint3a m;
+        m[0] = w[B]; m[1] = w[B + 1]; m[2] = w[B + 2];
+        if constexpr (NT) __builtin_nontemporal_store(m, reinterpret_cast<uint3a *>(p + B));
+        else *reinterpret_cast<uint3a *>(p + B) = m;
+    }
+    if constexpr (NW % 4 == 2) {
+        uint2a m;
+        m[0] = w[B]; m[1] = w[B + 1];
+        if constexpr (NT) __builtin_nontemporal_store(m, reinterpret_cast<uint2a *>(p + B));
+        else *reinterpret_cast<uint2a *>(p + B) = m;
+    }
+    if constexpr (NW % 4 == 1) stream_store<NT>(p + B, w[B]);
+}
+
+struct DwRowsArgs {
+    const void *x, *w;
+    const float *scale, *shift, *bias;
+    const void *residual;
+    void *y;
+    int C, H, OH;
+    int total;         // lanes with work: planes x OH
+    float inv_oh;
+    int relu;
+};
+
+template <typename T, int STRIDE, int OW, bool NT>
+__global__ __launch_bounds__(256) void dwconv3x3_rows_kernel(const DwRowsArgs a)
+{
+    constexpr int W = OW * STRIDE;                  // input row, pixels
+    constexpr int EW = 4 / sizeof(T);               // pixels per 32-bit word
+    static_assert(W % EW == 0, "input rows are whole words");
+    constexpr int NW = W / EW;
+    const int g = blockIdx.x * 256 + threadIdx.x;
+    if (g >= a.total) return;
+    int oh;
+    const int plane = fast_div(g, a.OH, a.inv_oh, &oh);
+    const int c = plane % a.C;
+    const T *__restrict__ wg = static_cast<const T *>(a.w);
+    float wt[9];
+#pragma unroll
+    for (int e = 0; e < 9; ++e) wt[e] = Elem<T>::load(wg, c * 9 + e);
+    const float sc = a.scale[c];
+    const float sf = a.bias ? fmaf(a.bias[c], sc, a.shift[c]) : a.shift[c];
+
+    // the three input rows; a padding row is read from the nearest image row and zeroed, so that
+    // all loads are in flight together
+    const T *xp = static_cast<const T *>(a.x) + (size_t)plane * a.H * W;
+    float v[3][W + 2];
+#pragma unroll
+    for (int r = 0; r < 3; ++r) {
+        const int ih = oh * STRIDE - 1 + r;
+        const bool ok = ih >= 0 && ih < a.H;
+        uint32_t wd[NW];
+        load_words<NW>(reinterpret_cast<const uint32_t *>(xp + min(max(ih, 0), a.H - 1) * W), wd);
+        v[r][0] = 0.0f;
+        v[r][W + 1] = 0.0f;
+#pragma unroll
+        for (int k = 0; k < NW; ++k) {
+            if constexpr (sizeof(T) == 4) {
+                v[r][1 + k] = ok ? __uint_as_float(wd[k]) : 0.0f;
+            } else {
+                v[r][1 + 2 * k] = ok ? __uint_as_float(wd[k] << 16) : 0.0f;
+                v[r][2 + 2 * k] = ok ? __uint_as_float(wd[k] & 0xFFFF0000u) : 0.0f;
+            }
+        }
+    }
+
+    float out[OW];
+#pragma unroll
+    for (int q = 0; q < OW; ++q) {
+        float acc = 0.0f;
+#pragma unroll
+        for (int r = 0; r < 3; ++r)
+#pragma unroll
+            for (int t = 0; t < 3; ++t) acc += v[r][q * STRIDE + t] * wt[r * 3 + t];
+        out[q] = fmaf(acc, sc, sf);
+    }
+
+    const size_t idx = ((size_t)plane * a.OH + oh) * OW;
+    const float floor_v = a.relu ? 0.0f : -INFINITY;
+    T *yp = static_cast<T *>(a.y) + idx;
+    const T *rp = static_cast<const T *>(a.residual) + idx;
+    constexpr bool kWords = (OW * sizeof(T)) % 4 == 0;      // the output row is whole words
+    if constexpr (kWords) {
+        constexpr int NO = OW * sizeof(T) / 4;
+        uint32_t ow_[NO];
+        if (a.residual) {
+            load_words<NO>(reinterpret_cast<const uint32_t *>(rp), ow_);
+#pragma unroll
+            for (int k = 0; k < NO; ++k) {
+                if constexpr (sizeof(T) == 4) {
+                    out[k] += __uint_as_float(ow_[k]);
+                } else {
+                    out[2 * k] += __uint_as_float(ow_[k] << 16);
+                    out[2 * k + 1] += __uint_as_float(ow_[k] & 0xFFFF0000u);
+                }
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < NO; ++k) {
+            if constexpr (sizeof(T) == 4) ow_[k] = __float_as_uint(fmaxf(out[k], floor_v));
+            else ow_[k] = f32x2_to_bf16x2(fmaxf(out[2 * k], floor_v), fmaxf(out[2 * k + 1], floor_v));
+        }
+        store_words<NT, NO>(reinterpret_cast<uint32_t *>(yp), ow_);
+    } else {
+        // rows of an odd number of bf16 pixels start on any 2-byte boundary: element by element
+#pragma unroll
+        for (int q = 0; q < OW; ++q) {
+            float o = out[q];
+            if (a.residual) o += Elem<T>::load(rp, q);
+            Elem<T>::store(yp, q, fmaxf(o, floor_v));
+        }
+    }
+}
+
+template <typename T, int STRIDE, int OW>
+void launch_rows(const DwRowsArgs &d, bool nt, hipStream_t stream)
+{
+    const unsigned blocks = (unsigned)((d.total + 255) / 256);
+    // (the non-temporal hint pays on the 4-byte type's wide stores only, as in the kernels above)
+    if (nt && sizeof(T) == 4)
+        hipLaunchKernelGGL((dwconv3x3_rows_kernel<T, STRIDE, OW, true>), dim3(blocks), dim3(256), 0, stream, d);
+    else
+        hipLaunchKernelGGL((dwconv3x3_rows_kernel<T, STRIDE, OW, false>), dim3(blocks), dim3(256), 0, stream, d);
+}
+
+// Lanes below which the rows kernel leaves a launch to the small-plane kernel (a batch-1 layer has
+// 3.5 to 7 thousand output rows: too few waves to hide a lane's three-row fetch).
+constexpr long kRowsMinLanes = 16384;
+
 int ceil_log2(int v)
 {
     int l = 0;
@@ -512,6 +697,30 @@ tvg_status launch_dwconv3x3(const ConvProblem &p, const ConvPointers &ptr, hipSt
         return hipGetLastError() == hipSuccess ? TVG_OK : TVG_ERR_LAUNCH;
     }
 
+    // narrow output rows, many planes: one lane per output row
+    const long rows_total = (long)p.N * p.IC * p.OH;
+    const int esz = p.dtype == TVG_BF16 ? 2 : 4;
+    if ((p.OW == 14 || p.OW == 7) && p.W == p.OW * stride0 && (p.W * esz) % 4 == 0 &&
+        rows_total >= kRowsMinLanes && rows_total < (1L << 22) &&
+        reinterpret_cast<uintptr_t>(ptr.x) % 4 == 0 && reinterpret_cast<uintptr_t>(ptr.y) % 4 == 0 &&
+        reinterpret_cast<uintptr_t>(ptr.residual) % 4 == 0 && reinterpret_cast<uintptr_t>(ptr.w) % esz == 0) {
+        DwRowsArgs d;
+        d.x = ptr.x; d.w = ptr.w;
+        d.scale = ptr.scale; d.shift = ptr.shift; d.bias = ptr.bias;
+        d.residual = ptr.residual; d.y = ptr.y;
+        d.C = p.IC; d.H = p.H; d.OH = p.OH;
+        d.total = (int)rows_total;
+        d.inv_oh = 1.0f / (float)p.OH;
+        d.relu = p.relu;
+        const bool nt = p.stream_out != 0;
+        const bool f32 = p.dtype == TVG_F32;
+        if (p.OW == 14 && stride0 == 1) f32 ? launch_rows<float, 1, 14>(d, nt, stream) : launch_rows<bf16_t, 1, 14>(d, nt, stream);
+        else if (p.OW == 14) f32 ? launch_rows<float, 2, 14>(d, nt, stream) : launch_rows<bf16_t, 2, 14>(d, nt, stream);
+        else if (stride0 == 2) f32 ? launch_rows<float, 2, 7>(d, nt, stream) : launch_rows<bf16_t, 2, 7>(d, nt, stream);
+        else launch_rows<float, 1, 7>(d, nt, stream);       // (bf16 rows of 7 pixels are not whole words)
+        return hipGetLastError() == hipSuccess ? TVG_OK : TVG_ERR_LAUNCH;
+    }
+
     if (p.OH * p.OW <= 256 && reinterpret_cast<uintptr_t>(ptr.x) % 16 == 0) {
         DwSmallArgs d;
         d.x = ptr.x; d.w = ptr.w;
@@ -519,16 +728,21 @@ tvg_status launch_dwconv3x3(const ConvProblem &p, const ConvPointers &ptr, hipSt
         d.residual = ptr.residual; d.y = ptr.y;
         d.planes = p.N * p.IC; d.C = p.IC; d.H = p.H; d.W = p.W; d.OH = p.OH; d.OW = p.OW;
         d.relu = p.relu;
-        // planes per workgroup: a multiple of 4 (fp32) or 8 (bf16) so that every group starts
-        // on a 16-byte boundary, about 2048 outputs, at most 40 KB of LDS, and no larger than
-        // leaves about four workgroups per CU
-        const int unit = p.dtype == TVG_BF16 ? 8 : 4;
+        // planes per workgroup: a multiple of the unit that makes every group start on a 16-byte
+        // boundary (1 when a plane is itself a multiple of 16 bytes, else 4 for fp32 and 8 for
+        // bf16), about 2048 outputs, at most 40 KB of LDS, and no larger than leaves about four
+        // workgroups per CU - or, with so few planes that this is below the unit (batch 1), one
+        // workgroup per CU: D6 at batch 1 used to run 32 workgroups of 8 planes on 256 CUs
         const int hw = p.H * p.W, ohw = p.OH * p.OW;
+        const int esize = p.dtype == TVG_BF16 ? 2 : 4;
+        const int unit = (hw * esize) % 16 == 0 ? 1 : 16 / esize;
         int pg = 2048 / ohw;
         const int cap_lds = (40 * 1024 / 4) / (hw + 12);
         if (pg > cap_lds) pg = cap_lds;
-        const int cap_fill = d.planes / (4 * kComputeUnits);
-        if (cap_fill >= unit && pg > cap_fill) pg = cap_fill;
+        int cap_fill = d.planes / (4 * kComputeUnits);
+        if (cap_fill < unit) cap_fill = d.planes / kComputeUnits;
+        if (cap_fill < unit) cap_fill = unit;
+        if (pg > cap_fill) pg = cap_fill;
         pg = pg / unit * unit;
         if (pg >= unit) {
             d.PG = pg;

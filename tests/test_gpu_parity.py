@@ -92,9 +92,49 @@ def test_depthwise_ragged_shapes_full_tail(tvg, dtype, n, c, h, w, stride):
     check(to_host(y), want, dtype)
 
 
-@pytest.mark.parametrize("i", [0, 2, 3, 8])
+# (n, c, h, w, stride): narrow output rows (14 or 7 pixels) on enough planes for the kernel that
+# gives a lane one output row - square and oblong maps, an odd height under stride 2
+ROWS_SHAPES = [(8, 256, 14, 14, 1), (4, 512, 9, 14, 1), (8, 300, 7, 7, 1), (8, 256, 28, 28, 2),
+               (8, 256, 20, 28, 2), (8, 320, 14, 14, 2), (8, 400, 13, 14, 2), (3, 800, 7, 7, 1)]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("variant", ["plain", "bias+residual", "no-relu+residual", "offset"])
+@pytest.mark.parametrize("cfg", ROWS_SHAPES, ids=lambda c: "x".join(map(str, c)))
+def test_depthwise_row_per_lane_kernel_shapes(tvg, cfg, variant, dtype):
+    """Every output of the row-per-lane depthwise kernel; "offset" places x, y and the residual
+    4 bytes (and, for bf16, also 2 bytes: the fallback) past a 16-byte boundary."""
+    import torch
+    n, c, h, w, stride = cfg
+    sh = ti.ConvShape("dw", n, c, h, w, c, 3, 3, stride, 1, depthwise=True)
+    res = variant != "plain"
+    inp = ti.make_inputs(sh, 5100 + sum(cfg) + len(variant), dtype, residual=res, bias="bias" in variant)
+    relu = "no-relu" not in variant
+    want = oracle.dwconv2d_fused(inp["x"], inp["w"], inp["scale"], inp["shift"], inp["bias"],
+                                 inp["residual"], stride=(stride,) * 2, pad=(1, 1), relu=relu)
+    d = dev_inputs(inp, dtype)
+    shifts = [0] if variant != "offset" else ([1] if dtype == "f32" else [2, 1])
+    for off in shifts:
+        def place(t):
+            base = torch.empty(t.numel() + 16, dtype=t.dtype, device=t.device)
+            v = base[off:off + t.numel()].view(t.shape)
+            v.copy_(t)
+            return v
+        x, r = (place(d["x"]), place(d["residual"])) if off else (d["x"], d["residual"])
+        y = torch.full(sh.y_shape(), float("nan"), dtype=x.dtype, device=x.device)
+        y = place(y) if off else y
+        for hint in (False, True):
+            y.fill_(float("nan"))
+            out = tvg.dwconv2d_fused(x, d["w"], d["scale"], d["shift"], d["bias"], r, stride=stride,
+                                     pad=1, relu=relu, stream_out=hint, out=y)
+            torch.cuda.synchronize()
+            assert out.data_ptr() == y.data_ptr()
+            check(to_host(y), want, dtype, (cfg, variant, off, hint))
+
+
+@pytest.mark.parametrize("i", [0, 2, 3, 5, 6, 7, 8])
 def test_depthwise_batch64_full(tvg, i):
-    """D1, D3, D4, D9 at batch 64 (HBM-sized traffic): the launch configuration of the
+    """D1, D3, D4, D6..D9 at batch 64 (HBM-sized traffic): the launch configuration of the
     supplementary bandwidth measurement, every output against the oracle."""
     import torch
     sh = ti.mobilenet_depthwise(64)[i]
