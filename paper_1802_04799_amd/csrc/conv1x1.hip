@@ -46,15 +46,17 @@ __device__ __forceinline__ int xcd_remap(int bid, int nb)
 // NCH > 0: the reduction is exactly NCH chunks and all of them are fetched before the first is
 // used, each into registers of its own.  These layers do 4 to 16 MFMAs per wave and chunk, so
 // with one chunk in flight at a time every chunk costs a full memory latency (measured: 8
-// chunks, 12 us); with all in flight the latency is paid once.  NCH = 0: any channel count,
-// one chunk ahead.
+// chunks, 12 us); with all in flight the latency is paid once.  NCH = 0: any number of whole
+// chunks, a rolling window of them ahead (see PF below).  NCH < 0: any channel count, the last
+// chunk ragged, one chunk ahead.
 template <int MT, int NT, int NCH>
 __global__ __launch_bounds__(256) void conv1x1_kernel(const PwArgs a)
 {
     constexpr int WTM = MT / 2, WTN = NT / 2;
     constexpr int MI = WTM / 32, NJ = WTN / 32;
     constexpr int BT = NT * 4 / 256;          // (pixel, octet) slots per thread
-    constexpr int AT = (MT * 4 + 255) / 256;  // weight vectors per thread
+    constexpr int AT = MT * 4 / 256;          // weight vectors per thread
+    static_assert(MT % 64 == 0 && NT % 64 == 0, "whole load slots per thread");
     constexpr int OPER = (MT + NT) * kRow;
     constexpr int STAGE = 4 * MI * NJ * kStageBytes;    // the epilogue stages all of a wave's tiles
     __shared__ __attribute__((aligned(16))) unsigned char lds[OPER > STAGE ? OPER : STAGE];
@@ -99,9 +101,9 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const PwArgs a)
         const int v = tid + i * 256;
         const int row = v >> 2, kv = v & 3;
         akv[i] = kv;
-        adst[i] = v < MT * 4 ? row * kRow + kv * 16 : -1;
+        adst[i] = row * kRow + kv * 16;
         // rows past OC read row 0; their accumulators are never stored
-        aoff[i] = 2u * (uint32_t)(((v < MT * 4 && m0 + row < a.OC) ? m0 + row : 0) * a.IC + kv * 8);
+        aoff[i] = 2u * (uint32_t)((m0 + row < a.OC ? m0 + row : 0) * a.IC + kv * 8);
     }
 
     const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
@@ -109,7 +111,13 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const PwArgs a)
     const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<bf16_t *>(a.w), 0, a.w_bytes, kRsrcFlags);
 
-    constexpr int NS = NCH > 0 ? NCH : 1;      // register sets
+    // NCH = 0: PF chunks ahead, each in a register set of its own that is refilled as soon as its
+    // chunk has gone to LDS.  With one chunk ahead every chunk cost a memory latency, because the
+    // 4 to 8 MFMAs of a chunk are over long before its successor arrives, and a layer that leaves
+    // a CU one or two workgroups has nothing else to run meanwhile (512 -> 512 channels on 6272
+    // pixels: 16 chunks, 17.4 us, 190 TFLOP/s).
+    constexpr int PF = (MT == 128 && NT == 128) ? 2 : 4;
+    constexpr int NS = NCH > 0 ? NCH : NCH == 0 ? PF : 1;     // register sets
     uint32_t braw[NS][BT][8];
     uint4v areg[NS][AT];
     // Full chunks (all 32 channels below IC) use the scalar offset operand for the channel
@@ -117,7 +125,7 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const PwArgs a)
     // are unambiguously out of range of the descriptor and read as zeros.
     auto load_chunk = [&](int c, int set) __attribute__((always_inline)) {
         const int c0 = c * kKC;
-        if (NCH > 0 || c0 + kKC <= a.IC) {
+        if (NCH >= 0 || c0 + kKC <= a.IC) {
 #pragma unroll
             for (int j = 0; j < BT; ++j)
 #pragma unroll
@@ -154,7 +162,7 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const PwArgs a)
                 braw[set][j][4] | (braw[set][j][5] << 16), braw[set][j][6] | (braw[set][j][7] << 16)};
 #pragma unroll
         for (int i = 0; i < AT; ++i)
-            if (adst[i] >= 0) *reinterpret_cast<uint4v *>(As + adst[i]) = areg[set][i];
+            *reinterpret_cast<uint4v *>(As + adst[i]) = areg[set][i];
     };
 
     float16v acc[MI][NJ];
@@ -198,7 +206,7 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const PwArgs a)
             mfma_chunk();
             __syncthreads();          // (the last one frees the operand tiles for the tail)
         }
-    } else {
+    } else if constexpr (NCH < 0) {
         const int nchunks = (a.IC + kKC - 1) / kKC;
         load_chunk(0, 0);
         store_chunk(0);
@@ -210,6 +218,29 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const PwArgs a)
             if (c + 1 < nchunks) {
                 store_chunk(0);
                 __syncthreads();
+            }
+        }
+    } else {
+        // (a multiple of PF chunks, the launcher sees to that.  Every load below is issued
+        // unconditionally - past the end, the last chunk again, into a set nobody reads - because a
+        // wait on the memory counter can leave the younger loads in flight only if they are
+        // certain to have been issued: behind a branch they force a wait for everything.)
+        const int nchunks = a.IC / kKC;
+#pragma unroll
+        for (int s = 0; s < PF; ++s) {
+            load_chunk(s, s);
+            __builtin_amdgcn_sched_barrier(0);    // (issue order = consumption order)
+        }
+        for (int c0 = 0; c0 < nchunks; c0 += PF) {
+#pragma unroll
+            for (int s = 0; s < PF; ++s) {
+                store_chunk(s);
+                __syncthreads();
+                __builtin_amdgcn_sched_barrier(0);
+                load_chunk(min(c0 + s + PF, nchunks - 1), s);
+                __builtin_amdgcn_sched_barrier(0);
+                mfma_chunk();
+                __syncthreads();          // (the last one frees the operand tiles for the tail)
             }
         }
     }
@@ -282,8 +313,12 @@ tvg_status launch_conv1x1(const ConvProblem &p, const Pw1x1Plan &plan, const Con
     const unsigned grid = (unsigned)plan.tiles;
     // whole reduction in flight at once when it is 2 or 8 full chunks and the registers fit
     // (measured at batch 64: C11, 8 chunks, 13.0 -> 11.5 us; 4 chunks: no gain)
-    int nch = p.IC % kKC == 0 ? p.IC / kKC : 0;
-    if ((nch != 2 && nch != 8) || (nch == 8 && plan.mt == 128 && plan.nt == 128)) nch = 0;
+    int nch = p.IC % kKC == 0 ? p.IC / kKC : -1;
+    if (nch > 0 && ((nch != 2 && nch != 8) || (nch == 8 && plan.mt == 128 && plan.nt == 128))) {
+        // the rolling window takes whole groups of PF chunks (4, or 2 under the 128 x 128 tile)
+        const int pf = (plan.mt == 128 && plan.nt == 128) ? 2 : 4;
+        nch = nch % pf == 0 ? 0 : -1;
+    }
 #define TVG_PW_LAUNCH(MT_, NT_)                                                                     \
     do {                                                                                           \
         if (nch == 2)                                                                              \
@@ -291,8 +326,10 @@ tvg_status launch_conv1x1(const ConvProblem &p, const Pw1x1Plan &plan, const Con
         else if (nch == 8)                                                                         \
             hipLaunchKernelGGL((conv1x1_kernel<MT_, NT_, (MT_ == 128 && NT_ == 128) ? 2 : 8>),       \
                                dim3(grid), dim3(256), 0, stream, a);                               \
-        else                                                                                       \
+        else if (nch == 0)                                                                         \
             hipLaunchKernelGGL((conv1x1_kernel<MT_, NT_, 0>), dim3(grid), dim3(256), 0, stream, a);   \
+        else                                                                                       \
+            hipLaunchKernelGGL((conv1x1_kernel<MT_, NT_, -1>), dim3(grid), dim3(256), 0, stream, a);  \
     } while (0)
     if (plan.mt == 128 && plan.nt == 128) TVG_PW_LAUNCH(128, 128);
     else if (plan.mt == 128) TVG_PW_LAUNCH(128, 64);
