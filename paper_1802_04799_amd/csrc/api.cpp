@@ -264,7 +264,7 @@ tvg_status tvg_conv2d_get_knobs(const tvg_conv_desc *desc, tvg_conv_knobs *knobs
             if (p.W % 2 != 0 && p.W <= 7 && p.sh == 1) k.row_loads = d.patch.px == 8 ? 2 : 1;
         }
     } else if (d.stem_shape) {
-        k.mt = 64;
+        k.mt = d.stem.mt;
         k.nt = 256;
         k.stages = 1;
     } else if (d.pwd_shape) {
@@ -301,7 +301,7 @@ tvg_status tvg_conv2d_get_plan(const tvg_conv_desc *desc, int32_t *kernel, int32
         *nt = d.patch.nt;
     } else if (d.stem_shape) {
         *kernel = TVG_KERNEL_STEM;
-        *mt = 64;
+        *mt = d.stem.mt;
         *nt = 256;
     } else if (d.pwd_shape) {
         *kernel = TVG_KERNEL_1X1_DEEP;

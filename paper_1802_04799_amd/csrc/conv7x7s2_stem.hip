@@ -45,16 +45,18 @@ struct StemArgs {
 };
 
 constexpr int kNT = 256;                 // pixels per tile
-constexpr int kMT = 64;                  // output channels per tile
+// (output channels per tile: MT = 64, or 32 for layers of at most 32 channels - the MobileNet
+// stem - which would otherwise run half of their MFMAs and half of the tail on rows nobody stores)
 constexpr int kRsrcFlags = 0x00020000;   // raw buffer descriptor word 3 on gfx9-family targets
 constexpr uint32_t kOutOfRange = 0xFFFFFFF0u;
 
 // IC = input channels (compile time, so the reduction loop unrolls completely and the LDS
 // reads of one MFMA step overlap the previous step's MFMAs); LT = 16-byte copy tasks per
 // thread per tile.
-template <int R, int IC, int LT>
+template <int R, int IC, int LT, int MT>
 __global__ __launch_bounds__(256, 2) void conv_stem_s2_kernel(const StemArgs a)
 {
+    constexpr int kMT = MT, MI = MT / 32;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     constexpr int PAD = R / 2;
     constexpr int npairs = IC * R;
@@ -194,9 +196,9 @@ __global__ __launch_bounds__(256, 2) void conv_stem_s2_kernel(const StemArgs a)
                 pb[j] = (n * VH + oh * 2 - vr_lo) * pitch + ow * 4;
             }
         }
-        float16v acc[2][2];
+        float16v acc[MI][2];
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < MI; ++i)
 #pragma unroll
             for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -209,9 +211,9 @@ __global__ __launch_bounds__(256, 2) void conv_stem_s2_kernel(const StemArgs a)
             const int offa = ((pa / R) * nrows + pa % R) * pitch;
             const int offq = ((pq / R) * nrows + pq % R) * pitch;
             const int poff = lhalf ? offq : offa;
-            uint4v af[2], bf[2];
+            uint4v af[MI], bf[2];
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < MI; ++i)
                 af[i] = *reinterpret_cast<const uint4v *>(As + ((2 * m + lhalf) * kMT + i * 32 + lrow) * 16);
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
@@ -219,7 +221,7 @@ __global__ __launch_bounds__(256, 2) void conv_stem_s2_kernel(const StemArgs a)
                 bf[j] = uint4v{src[0], src[1], src[2], src[3]};
             }
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < MI; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j)
                     // pixel operand first: the accumulator tile is D[pixel][channel]
@@ -232,7 +234,7 @@ __global__ __launch_bounds__(256, 2) void conv_stem_s2_kernel(const StemArgs a)
         // now, so that waiting for those loads does not also wait for this tile's stores.
         if (next < a.ntiles) store_tile_rows((it + 1) & 1);
 
-        store_acc_tiles_batched<2, 2, 2>(acc, stage, lane, m0, p0 + wave * 64, tail, a.vmode, ss_lds, 0);
+        store_acc_tiles_batched<MI, 2, 2>(acc, stage, lane, m0, p0 + wave * 64, tail, a.vmode, ss_lds, 0);
         __syncthreads();
     }
 }
@@ -254,10 +256,10 @@ int max_stem_rows(const ConvProblem &p)
     return best;
 }
 
-template <int R, int IC, int LT>
+template <int R, int IC, int LT, int MT = 64>
 tvg_status launch_lt(const StemArgs &a, unsigned grid, size_t lds, hipStream_t stream)
 {
-    auto kernel = conv_stem_s2_kernel<R, IC, LT>;
+    auto kernel = conv_stem_s2_kernel<R, IC, LT, MT>;
     static bool configured = false;
     if (!configured) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
@@ -282,11 +284,14 @@ bool plan_conv7x7s2_stem(const ConvProblem &p, StemPlan *plan)
     const int rows = max_stem_rows(p);
     if (rows > p.H + 2 * p.ph) return false;            // a tile may wrap into the next image once
     const int nm = (p.IC * p.R + 1) / 2;
-    const size_t lds = (size_t)2 * nm * kMT * 16 + (size_t)2 * p.IC * rows * (p.W + 8) * 2 +
-                       (size_t)8 * kStageBytes + (size_t)kMT * 8;
+    // (the narrow channel tile exists for the case that needs it, the 3x3 three-channel stem)
+    const int mt = (p.OC <= 32 && p.R == 3 && p.IC == 3) ? 32 : 64;
+    const size_t lds = (size_t)2 * nm * mt * 16 + (size_t)2 * p.IC * rows * (p.W + 8) * 2 +
+                       (size_t)8 * kStageBytes + (size_t)mt * 8;
     const int lt = (p.IC * rows * (p.W / 8) + 255) / 256;
     if (lds > 80 * 1024 || lt > 8) return false;
     plan->rows = rows;
+    plan->mt = mt;
     plan->lt = lt;
     plan->lds_bytes = lds;
     return true;
@@ -310,7 +315,7 @@ tvg_status launch_conv7x7s2_stem(const ConvProblem &p, const StemPlan &plan, con
     a.vmode = pick_store_vmode(p.dtype, p.OH * p.OW, ptr.y, ptr.residual);
     a.nrows = plan.rows;
     a.ntiles = (p.npix + kNT - 1) / kNT;
-    a.mtiles = (p.OC + kMT - 1) / kMT;
+    a.mtiles = (p.OC + plan.mt - 1) / plan.mt;
     // persistent workgroups: two per CU, shared between the output-channel tiles
     int per = 2 * kComputeUnits / a.mtiles;
     if (per < 1) per = 1;
@@ -323,6 +328,9 @@ tvg_status launch_conv7x7s2_stem(const ConvProblem &p, const StemPlan &plan, con
     a.w_bytes = ((uint32_t)((size_t)p.OC * p.IC * p.R * p.R * 2) + 3u) & ~3u;
     const unsigned grid = (unsigned)(per * a.mtiles);
     if (p.R == 3) {
+        if (plan.mt == 32)
+            return plan.lt <= 5 ? launch_lt<3, 3, 5, 32>(a, grid, plan.lds_bytes, stream)
+                                : launch_lt<3, 3, 8, 32>(a, grid, plan.lds_bytes, stream);
         if (p.IC == 3 && plan.lt <= 5) return launch_lt<3, 3, 5>(a, grid, plan.lds_bytes, stream);
         switch (p.IC) {
         case 1: return launch_lt<3, 1, 8>(a, grid, plan.lds_bytes, stream);

@@ -100,6 +100,7 @@ tvg_status launch_conv3x3_dbuf(const ConvProblem &p, const Patch3x3Plan &plan,
 // bf16 7x7 stride-2 pad-3 kernel for IC <= 4 (the ResNet stem).
 struct StemPlan {
     int rows;           // virtual input rows staged per tile
+    int mt;             // output channels per tile (64, or 32 for narrow layers)
     int lt;             // 16-byte copy tasks per thread per tile
     size_t lds_bytes;
 };

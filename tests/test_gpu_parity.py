@@ -432,15 +432,19 @@ def test_bf16_7x7_stem_kernel_shapes(tvg, cfg):
     check(to_host(y), oracle_dense(sh, inp), "bf16")
 
 
-@pytest.mark.parametrize("cfg", STEM_SHAPES + [(32, 3, 224, 224, 32), (2, 3, 16, 16, 32), (4, 4, 10, 8, 40)])
+@pytest.mark.parametrize("cfg", STEM_SHAPES + [(32, 3, 224, 224, 32), (2, 3, 16, 16, 32), (4, 4, 10, 8, 40),
+                                               # the 32-channel tile: ragged and tiny channel counts
+                                               (3, 3, 64, 96, 24), (2, 3, 48, 40, 17), (1, 3, 224, 224, 1)])
 def test_bf16_3x3_stride2_stem_kernel_shapes(tvg, cfg):
     """The same kernel with a 3x3 filter (pad 1): the MobileNet stem, 3 -> 32 channels, and the
     7x7 list's shapes; full fused tail; the plan must name the stem kernel for the large maps."""
     n, ic, h, w, oc = cfg
     sh = ti.ConvShape("stem3", n, ic, h, w, oc, 3, 3, 2, 1)
     desc = tvg.ConvDesc(n, ic, h, w, oc, 3, 3, 2, 2, 1, 1, tvg.TVG_BF16, 0)
-    if cfg in ((32, 3, 224, 224, 32), (1, 3, 224, 224, 64), (2, 3, 32, 32, 64), (2, 1, 64, 64, 16)):
+    if cfg in ((32, 3, 224, 224, 32), (1, 3, 224, 224, 64), (2, 3, 32, 32, 64), (2, 1, 64, 64, 16),
+               (3, 3, 64, 96, 24)):
         assert tvg.tvg_conv2d_get_plan(desc)[0] == 3      # (small maps may be declined: tiles that span images)
+        assert tvg.tvg_conv2d_get_plan(desc)[1] == (32 if ic == 3 and oc <= 32 else 64)
     inp = ti.make_inputs(sh, 6500 + sum(cfg), "bf16", residual=True, bias=True)
     y = run_dense(tvg, sh, inp, "bf16")
     check(to_host(y), oracle_dense(sh, inp), "bf16", cfg)
