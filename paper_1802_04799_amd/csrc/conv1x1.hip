@@ -315,7 +315,9 @@ tvg_status launch_conv1x1(const ConvProblem &p, const Pw1x1Plan &plan, const Con
     // (measured at batch 64: C11, 8 chunks, 13.0 -> 11.5 us; 4 chunks: no gain)
     int nch = p.IC % kKC == 0 ? p.IC / kKC : -1;
     if (nch > 0 && ((nch != 2 && nch != 8) || (nch == 8 && plan.mt == 128 && plan.nt == 128))) {
-        // the rolling window takes whole groups of PF chunks (4, or 2 under the 128 x 128 tile)
+        // the rolling window takes whole groups of PF chunks (4, or 2 under the 128 x 128 tile;
+        // eight sets under the 64-pixel tiles, refilled one by one or four at a time, were slower:
+        // 512 -> 512 at 14x14 14.6 and 15.4 us against 13.1)
         const int pf = (plan.mt == 128 && plan.nt == 128) ? 2 : 4;
         nch = nch % pf == 0 ? 0 : -1;
     }
