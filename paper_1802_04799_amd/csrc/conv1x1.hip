@@ -222,26 +222,33 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const PwArgs a)
         }
     } else {
         // (a multiple of PF chunks, the launcher sees to that.  Every load below is issued
-        // unconditionally - past the end, the last chunk again, into a set nobody reads - because a
-        // wait on the memory counter can leave the younger loads in flight only if they are
-        // certain to have been issued: behind a branch they force a wait for everything.)
+        // unconditionally - the last group of PF chunks is peeled off for that - because a wait on
+        // the memory counter can leave the younger loads in flight only if they are certain to
+        // have been issued: behind a branch they force a wait for everything.)
         const int nchunks = a.IC / kKC;
 #pragma unroll
         for (int s = 0; s < PF; ++s) {
             load_chunk(s, s);
             __builtin_amdgcn_sched_barrier(0);    // (issue order = consumption order)
         }
-        for (int c0 = 0; c0 < nchunks; c0 += PF) {
+        for (int c0 = 0; c0 + PF < nchunks; c0 += PF) {
 #pragma unroll
             for (int s = 0; s < PF; ++s) {
                 store_chunk(s);
                 __syncthreads();
                 __builtin_amdgcn_sched_barrier(0);
-                load_chunk(min(c0 + s + PF, nchunks - 1), s);
+                load_chunk(c0 + s + PF, s);
                 __builtin_amdgcn_sched_barrier(0);
                 mfma_chunk();
-                __syncthreads();          // (the last one frees the operand tiles for the tail)
+                __syncthreads();
             }
+        }
+#pragma unroll
+        for (int s = 0; s < PF; ++s) {    // the last group: nothing left to fetch
+            store_chunk(s);
+            __syncthreads();
+            mfma_chunk();
+            __syncthreads();              // (the last one frees the operand tiles for the tail)
         }
     }
 
@@ -311,10 +318,10 @@ tvg_status launch_conv1x1(const ConvProblem &p, const Pw1x1Plan &plan, const Con
     a.x_bytes = (uint32_t)((size_t)p.N * p.IC * p.H * p.W * 2);
     a.w_bytes = (uint32_t)((size_t)p.OC * p.IC * 2);
     const unsigned grid = (unsigned)plan.tiles;
-    // whole reduction in flight at once when it is 2 or 8 full chunks and the registers fit
-    // (measured at batch 64: C11, 8 chunks, 13.0 -> 11.5 us; 4 chunks: no gain)
+    // whole reduction in flight at once when it is 2, 4 or 8 full chunks and the registers fit
+    // (measured at batch 64: C11, 8 chunks, 13.0 -> 11.5 us)
     int nch = p.IC % kKC == 0 ? p.IC / kKC : -1;
-    if (nch > 0 && ((nch != 2 && nch != 8) || (nch == 8 && plan.mt == 128 && plan.nt == 128))) {
+    if (nch > 0 && ((nch != 2 && nch != 4 && nch != 8) || (nch == 8 && plan.mt == 128 && plan.nt == 128))) {
         // the rolling window takes whole groups of PF chunks (4, or 2 under the 128 x 128 tile;
         // eight sets under the 64-pixel tiles, refilled one by one or four at a time, were slower:
         // 512 -> 512 at 14x14 14.6 and 15.4 us against 13.1)
@@ -325,6 +332,8 @@ tvg_status launch_conv1x1(const ConvProblem &p, const Pw1x1Plan &plan, const Con
     do {                                                                                           \
         if (nch == 2)                                                                              \
             hipLaunchKernelGGL((conv1x1_kernel<MT_, NT_, 2>), dim3(grid), dim3(256), 0, stream, a);   \
+        else if (nch == 4)                                                                         \
+            hipLaunchKernelGGL((conv1x1_kernel<MT_, NT_, 4>), dim3(grid), dim3(256), 0, stream, a);   \
         else if (nch == 8)                                                                         \
             hipLaunchKernelGGL((conv1x1_kernel<MT_, NT_, (MT_ == 128 && NT_ == 128) ? 2 : 8>),       \
                                dim3(grid), dim3(256), 0, stream, a);                               \
