@@ -646,6 +646,35 @@ tvg_status launch_dwconv3x3(const ConvProblem &p, const ConvPointers &ptr, hipSt
     const bool ptr16 = reinterpret_cast<uintptr_t>(ptr.x) % 16 == 0 &&
                        reinterpret_cast<uintptr_t>(ptr.y) % 16 == 0 &&
                        reinterpret_cast<uintptr_t>(ptr.residual) % 16 == 0;
+    // narrow output rows, many planes: one lane per output row
+    const long rows_total = (long)p.N * p.IC * p.OH;
+    const int esz = p.dtype == TVG_BF16 ? 2 : 4;
+    // (rows of 28 pixels: bf16 only, 11.1 -> 9.3 us on the 256-channel layer at batch 32; in fp32 a
+    // lane's three rows are 90 registers and 112-byte strides, and D5 at batch 64 took 73 us against
+    // the register-blocked kernel's 33)
+    if ((p.OW == 14 || p.OW == 7 || (p.OW == 28 && stride0 == 1 && p.dtype == TVG_BF16)) &&
+        p.W == p.OW * stride0 && (p.W * esz) % 4 == 0 &&
+        rows_total >= kRowsMinLanes && rows_total < (1L << 22) &&
+        reinterpret_cast<uintptr_t>(ptr.x) % 4 == 0 && reinterpret_cast<uintptr_t>(ptr.y) % 4 == 0 &&
+        reinterpret_cast<uintptr_t>(ptr.residual) % 4 == 0 && reinterpret_cast<uintptr_t>(ptr.w) % esz == 0) {
+        DwRowsArgs d;
+        d.x = ptr.x; d.w = ptr.w;
+        d.scale = ptr.scale; d.shift = ptr.shift; d.bias = ptr.bias;
+        d.residual = ptr.residual; d.y = ptr.y;
+        d.C = p.IC; d.H = p.H; d.OH = p.OH;
+        d.total = (int)rows_total;
+        d.inv_oh = 1.0f / (float)p.OH;
+        d.relu = p.relu;
+        const bool nt = p.stream_out != 0;
+        const bool f32 = p.dtype == TVG_F32;
+        if (p.OW == 28) launch_rows<bf16_t, 1, 28>(d, nt, stream);
+        else if (p.OW == 14 && stride0 == 1) f32 ? launch_rows<float, 1, 14>(d, nt, stream) : launch_rows<bf16_t, 1, 14>(d, nt, stream);
+        else if (p.OW == 14) f32 ? launch_rows<float, 2, 14>(d, nt, stream) : launch_rows<bf16_t, 2, 14>(d, nt, stream);
+        else if (stride0 == 2) f32 ? launch_rows<float, 2, 7>(d, nt, stream) : launch_rows<bf16_t, 2, 7>(d, nt, stream);
+        else launch_rows<float, 1, 7>(d, nt, stream);       // (bf16 rows of 7 pixels are not whole words)
+        return hipGetLastError() == hipSuccess ? TVG_OK : TVG_ERR_LAUNCH;
+    }
+
     const long tasks = (long)p.N * p.IC * ((p.OH + kRB - 1) / kRB) * (p.OW / 4);
     if (p.dtype == TVG_F32 && ptr16 && p.W % 4 == 0 && p.OW % 4 == 0 && p.W >= 8 &&
         tasks < (1L << 31) && (p.OH + kRB - 1) / kRB * (p.OW / 4) < (1 << 22)) {
@@ -694,30 +723,6 @@ tvg_status launch_dwconv3x3(const ConvProblem &p, const ConvPointers &ptr, hipSt
         else if (stride0 == 1) launch_direct_bf16<1, 4>(d, nt, blocks, stream);
         else if (cw == 8) launch_direct_bf16<2, 8>(d, nt, blocks, stream);
         else launch_direct_bf16<2, 4>(d, nt, blocks, stream);
-        return hipGetLastError() == hipSuccess ? TVG_OK : TVG_ERR_LAUNCH;
-    }
-
-    // narrow output rows, many planes: one lane per output row
-    const long rows_total = (long)p.N * p.IC * p.OH;
-    const int esz = p.dtype == TVG_BF16 ? 2 : 4;
-    if ((p.OW == 14 || p.OW == 7) && p.W == p.OW * stride0 && (p.W * esz) % 4 == 0 &&
-        rows_total >= kRowsMinLanes && rows_total < (1L << 22) &&
-        reinterpret_cast<uintptr_t>(ptr.x) % 4 == 0 && reinterpret_cast<uintptr_t>(ptr.y) % 4 == 0 &&
-        reinterpret_cast<uintptr_t>(ptr.residual) % 4 == 0 && reinterpret_cast<uintptr_t>(ptr.w) % esz == 0) {
-        DwRowsArgs d;
-        d.x = ptr.x; d.w = ptr.w;
-        d.scale = ptr.scale; d.shift = ptr.shift; d.bias = ptr.bias;
-        d.residual = ptr.residual; d.y = ptr.y;
-        d.C = p.IC; d.H = p.H; d.OH = p.OH;
-        d.total = (int)rows_total;
-        d.inv_oh = 1.0f / (float)p.OH;
-        d.relu = p.relu;
-        const bool nt = p.stream_out != 0;
-        const bool f32 = p.dtype == TVG_F32;
-        if (p.OW == 14 && stride0 == 1) f32 ? launch_rows<float, 1, 14>(d, nt, stream) : launch_rows<bf16_t, 1, 14>(d, nt, stream);
-        else if (p.OW == 14) f32 ? launch_rows<float, 2, 14>(d, nt, stream) : launch_rows<bf16_t, 2, 14>(d, nt, stream);
-        else if (stride0 == 2) f32 ? launch_rows<float, 2, 7>(d, nt, stream) : launch_rows<bf16_t, 2, 7>(d, nt, stream);
-        else launch_rows<float, 1, 7>(d, nt, stream);       // (bf16 rows of 7 pixels are not whole words)
         return hipGetLastError() == hipSuccess ? TVG_OK : TVG_ERR_LAUNCH;
     }
 

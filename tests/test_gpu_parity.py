@@ -95,7 +95,8 @@ def test_depthwise_ragged_shapes_full_tail(tvg, dtype, n, c, h, w, stride):
 # (n, c, h, w, stride): narrow output rows (14 or 7 pixels) on enough planes for the kernel that
 # gives a lane one output row - square and oblong maps, an odd height under stride 2
 ROWS_SHAPES = [(8, 256, 14, 14, 1), (4, 512, 9, 14, 1), (8, 300, 7, 7, 1), (8, 256, 28, 28, 2),
-               (8, 256, 20, 28, 2), (8, 320, 14, 14, 2), (8, 400, 13, 14, 2), (3, 800, 7, 7, 1)]
+               (8, 256, 20, 28, 2), (8, 320, 14, 14, 2), (8, 400, 13, 14, 2), (3, 800, 7, 7, 1),
+               (4, 200, 28, 28, 1), (3, 256, 25, 28, 1)]      # 28-pixel rows: this kernel in bf16 only
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
