@@ -134,7 +134,7 @@ __global__ __launch_bounds__(256) void dwconv3x3_kernel(const DwArgs a)
 }
 
 // Register-blocked variant for fp32 planes whose rows are multiples of four: no LDS.
-// A lane computes a block of 4 output rows x 4 output columns of one plane; every input
+// A lane computes a block of RB (4, 2 or 1) output rows x 4 output columns of one plane; every input
 // row of the block is read as 16-byte vectors plus the halo scalars, re-used in registers
 // by the (up to three) output rows that need it, and each output row leaves as one 16-byte
 // store.  Neighbouring lanes read neighbouring vectors of the same row; the overlap
@@ -152,9 +152,9 @@ struct DwDirectArgs {
     int relu;
 };
 
-constexpr int kRB = 4;        // output rows per lane
+constexpr int kRB = 4;        // output rows per lane (bf16 kernel; the fp32 kernel's RB is chosen per launch)
 
-template <int STRIDE, bool NT>
+template <int STRIDE, bool NT, int RB = 4>
 __global__ __launch_bounds__(256) void dwconv3x3_direct_kernel(const DwDirectArgs a)
 {
     const int g = blockIdx.x * 256 + threadIdx.x;
@@ -163,7 +163,7 @@ __global__ __launch_bounds__(256) void dwconv3x3_direct_kernel(const DwDirectArg
     int cb;
     const int rb = fast_div(g - plane * a.tpp, a.CB, a.inv_cb, &cb);
     const int c = plane % a.C;
-    const int oh0 = rb * kRB, ow0 = cb * 4;
+    const int oh0 = rb * RB, ow0 = cb * 4;
     const int H = a.H, W = a.W;
     const float *__restrict__ xp = a.x + (size_t)plane * H * W;
 
@@ -173,11 +173,11 @@ __global__ __launch_bounds__(256) void dwconv3x3_direct_kernel(const DwDirectArg
     const float sc = a.scale[c];
     const float sf = a.bias ? fmaf(a.bias[c], sc, a.shift[c]) : a.shift[c];
 
-    constexpr int IR = (kRB - 1) * STRIDE + 3;        // input rows of the block
+    constexpr int IR = (RB - 1) * STRIDE + 3;        // input rows of the block
     constexpr int NV = 3 * STRIDE + 3;                // input columns of the block
-    float acc[kRB][4];
+    float acc[RB][4];
 #pragma unroll
-    for (int o = 0; o < kRB; ++o)
+    for (int o = 0; o < RB; ++o)
 #pragma unroll
         for (int q = 0; q < 4; ++q) acc[o][q] = 0.0f;
 
@@ -203,7 +203,7 @@ __global__ __launch_bounds__(256) void dwconv3x3_direct_kernel(const DwDirectArg
 #pragma unroll
         for (int e = 0; e < NV; ++e) v[e] = rowok ? v[e] : 0.0f;
 #pragma unroll
-        for (int o = 0; o < kRB; ++o) {
+        for (int o = 0; o < RB; ++o) {
             const int r = rr - o * STRIDE;
             if (r < 0 || r > 2) continue;
 #pragma unroll
@@ -215,7 +215,7 @@ __global__ __launch_bounds__(256) void dwconv3x3_direct_kernel(const DwDirectArg
 
     const float floor_v = a.relu ? 0.0f : -INFINITY;
 #pragma unroll
-    for (int o = 0; o < kRB; ++o) {
+    for (int o = 0; o < RB; ++o) {
         const int oh = oh0 + o;
         if (oh >= a.OH) continue;
         const size_t idx = ((size_t)plane * a.OH + oh) * a.OW + ow0;
@@ -675,28 +675,42 @@ tvg_status launch_dwconv3x3(const ConvProblem &p, const ConvPointers &ptr, hipSt
         return hipGetLastError() == hipSuccess ? TVG_OK : TVG_ERR_LAUNCH;
     }
 
-    const long tasks = (long)p.N * p.IC * ((p.OH + kRB - 1) / kRB) * (p.OW / 4);
+    // output rows per lane (measured at batch 64 and batch 1, us with 4 / 2 / 1 rows): stride 2 wants
+    // one (D2 49.6 / 48.7 / 45.1, D4 31.4 / 29.9 / 25.0: a block of 4 rows is 9 input rows of
+    // registers), stride 1 four on the wide maps (D1 42.9 / 50.3 / 65.8) and two on 28-pixel rows
+    // (D5 33.4 / 31.5 / 33.5); a launch of few lanes wants the finest split (batch 1: 4.4-5.4 /
+    // 3.8-4.4 / 3.3-3.8)
+    const long tasks4 = (long)p.N * p.IC * ((p.OH + 3) / 4) * (p.OW / 4);
+    const int frb = (stride0 == 2 || tasks4 < 131072) ? 1 : p.W <= 28 ? 2 : 4;
+    const long tasks = (long)p.N * p.IC * ((p.OH + frb - 1) / frb) * (p.OW / 4);
     if (p.dtype == TVG_F32 && ptr16 && p.W % 4 == 0 && p.OW % 4 == 0 && p.W >= 8 &&
-        tasks < (1L << 31) && (p.OH + kRB - 1) / kRB * (p.OW / 4) < (1 << 22)) {
+        tasks < (1L << 31) && (p.OH + frb - 1) / frb * (p.OW / 4) < (1 << 22)) {
         DwDirectArgs d;
         d.x = static_cast<const float *>(ptr.x); d.w = static_cast<const float *>(ptr.w);
         d.scale = ptr.scale; d.shift = ptr.shift; d.bias = ptr.bias;
         d.residual = static_cast<const float *>(ptr.residual); d.y = static_cast<float *>(ptr.y);
         d.C = p.IC; d.H = p.H; d.W = p.W; d.OH = p.OH; d.OW = p.OW;
         d.CB = p.OW / 4;
-        d.tpp = (p.OH + kRB - 1) / kRB * d.CB;
+        d.tpp = (p.OH + frb - 1) / frb * d.CB;
         d.total = (int)tasks;
         d.inv_cb = 1.0f / (float)d.CB;
         d.relu = p.relu;
         const unsigned blocks = (unsigned)((tasks + 255) / 256);
-        if (stride0 == 1 && p.stream_out)
-            hipLaunchKernelGGL((dwconv3x3_direct_kernel<1, true>), dim3(blocks), dim3(256), 0, stream, d);
-        else if (stride0 == 1)
-            hipLaunchKernelGGL((dwconv3x3_direct_kernel<1, false>), dim3(blocks), dim3(256), 0, stream, d);
-        else if (p.stream_out)
-            hipLaunchKernelGGL((dwconv3x3_direct_kernel<2, true>), dim3(blocks), dim3(256), 0, stream, d);
-        else
-            hipLaunchKernelGGL((dwconv3x3_direct_kernel<2, false>), dim3(blocks), dim3(256), 0, stream, d);
+#define TVG_DW_LAUNCH(RB_)                                                                           \
+        do {                                                                                         \
+            if (stride0 == 1 && p.stream_out)                                                         \
+                hipLaunchKernelGGL((dwconv3x3_direct_kernel<1, true, RB_>), dim3(blocks), dim3(256), 0, stream, d);  \
+            else if (stride0 == 1)                                                                    \
+                hipLaunchKernelGGL((dwconv3x3_direct_kernel<1, false, RB_>), dim3(blocks), dim3(256), 0, stream, d); \
+            else if (p.stream_out)                                                                    \
+                hipLaunchKernelGGL((dwconv3x3_direct_kernel<2, true, RB_>), dim3(blocks), dim3(256), 0, stream, d);  \
+            else                                                                                      \
+                hipLaunchKernelGGL((dwconv3x3_direct_kernel<2, false, RB_>), dim3(blocks), dim3(256), 0, stream, d); \
+        } while (0)
+        if (frb == 1) TVG_DW_LAUNCH(1);
+        else if (frb == 2) TVG_DW_LAUNCH(2);
+        else TVG_DW_LAUNCH(4);
+#undef TVG_DW_LAUNCH
         return hipGetLastError() == hipSuccess ? TVG_OK : TVG_ERR_LAUNCH;
     }
 
