@@ -152,7 +152,7 @@ struct DwDirectArgs {
     int relu;
 };
 
-constexpr int kRB = 4;        // output rows per lane (bf16 kernel; the fp32 kernel's RB is chosen per launch)
+
 
 template <int STRIDE, bool NT, int RB = 4>
 __global__ __launch_bounds__(256) void dwconv3x3_direct_kernel(const DwDirectArgs a)
@@ -245,7 +245,7 @@ struct DwDirectBf16Args {
     int relu;
 };
 
-template <int STRIDE, int CW, bool NT>
+template <int STRIDE, int CW, bool NT, int RB = 4>
 __global__ __launch_bounds__(256) void dwconv3x3_direct_bf16_kernel(const DwDirectBf16Args a)
 {
     const int g = blockIdx.x * 256 + threadIdx.x;
@@ -254,7 +254,7 @@ __global__ __launch_bounds__(256) void dwconv3x3_direct_bf16_kernel(const DwDire
     int cb;
     const int rb = fast_div(g - plane * a.tpp, a.CB, a.inv_cb, &cb);
     const int c = plane % a.C;
-    const int oh0 = rb * kRB, ow0 = cb * CW;
+    const int oh0 = rb * RB, ow0 = cb * CW;
     const int H = a.H, W = a.W;
     const bf16_t *__restrict__ xp = a.x + (size_t)plane * H * W;
 
@@ -264,13 +264,13 @@ __global__ __launch_bounds__(256) void dwconv3x3_direct_bf16_kernel(const DwDire
     const float sc = a.scale[c];
     const float sf = a.bias ? fmaf(a.bias[c], sc, a.shift[c]) : a.shift[c];
 
-    constexpr int IR = (kRB - 1) * STRIDE + 3;        // input rows of the block
+    constexpr int IR = (RB - 1) * STRIDE + 3;        // input rows of the block
     constexpr int NIN = CW * STRIDE;                  // input pixels fetched as vectors
     constexpr int NW = NIN / 2;                       // ... in 4-byte words
     constexpr int NV = NIN + 2;                       // columns iw0 - 1 .. iw0 + NIN
-    float acc[kRB][CW];
+    float acc[RB][CW];
 #pragma unroll
-    for (int o = 0; o < kRB; ++o)
+    for (int o = 0; o < RB; ++o)
 #pragma unroll
         for (int q = 0; q < CW; ++q) acc[o][q] = 0.0f;
 
@@ -304,7 +304,7 @@ __global__ __launch_bounds__(256) void dwconv3x3_direct_bf16_kernel(const DwDire
         }
         if (STRIDE == 1) v[NV - 1] = iw0 + NIN < W ? bf16_to_f32(row[NIN]) : 0.0f;
 #pragma unroll
-        for (int o = 0; o < kRB; ++o) {
+        for (int o = 0; o < RB; ++o) {
             const int r = rr - o * STRIDE;
             if (r < 0 || r > 2) continue;
 #pragma unroll
@@ -317,7 +317,7 @@ __global__ __launch_bounds__(256) void dwconv3x3_direct_bf16_kernel(const DwDire
     typedef uint32_t outv __attribute__((ext_vector_type(CW / 2)));
     const float floor_v = a.relu ? 0.0f : -INFINITY;
 #pragma unroll
-    for (int o = 0; o < kRB; ++o) {
+    for (int o = 0; o < RB; ++o) {
         const int oh = oh0 + o;
         if (oh >= a.OH) continue;
         const size_t idx = ((size_t)plane * a.OH + oh) * a.OW + ow0;
@@ -337,15 +337,22 @@ __global__ __launch_bounds__(256) void dwconv3x3_direct_bf16_kernel(const DwDire
     }
 }
 
-template <int STRIDE, int CW>
-void launch_direct_bf16(const DwDirectBf16Args &d, bool nt, unsigned blocks, hipStream_t stream)
+template <int STRIDE, int CW, int RB>
+void launch_direct_bf16_rb(const DwDirectBf16Args &d, bool nt, unsigned blocks, hipStream_t stream)
 {
     if (nt)
-        hipLaunchKernelGGL((dwconv3x3_direct_bf16_kernel<STRIDE, CW, true>), dim3(blocks), dim3(256), 0,
+        hipLaunchKernelGGL((dwconv3x3_direct_bf16_kernel<STRIDE, CW, true, RB>), dim3(blocks), dim3(256), 0,
                            stream, d);
     else
-        hipLaunchKernelGGL((dwconv3x3_direct_bf16_kernel<STRIDE, CW, false>), dim3(blocks), dim3(256), 0,
+        hipLaunchKernelGGL((dwconv3x3_direct_bf16_kernel<STRIDE, CW, false, RB>), dim3(blocks), dim3(256), 0,
                            stream, d);
+}
+
+template <int STRIDE, int CW>
+void launch_direct_bf16(const DwDirectBf16Args &d, int rb, bool nt, unsigned blocks, hipStream_t stream)
+{
+    if (rb == 2) launch_direct_bf16_rb<STRIDE, CW, 2>(d, nt, blocks, stream);
+    else launch_direct_bf16_rb<STRIDE, CW, 4>(d, nt, blocks, stream);
 }
 
 // Variant for small planes (at most 256 outputs per plane: 14x14 and 7x7 maps).  A
@@ -717,26 +724,30 @@ tvg_status launch_dwconv3x3(const ConvProblem &p, const ConvPointers &ptr, hipSt
     // bf16: 8 output columns per lane where the row allows, else 4; planes of at most 256
     // outputs whose rows allow neither go to the small-plane kernel below
     const int cw = p.OW % 8 == 0 ? 8 : p.OW % 4 == 0 ? 4 : 0;
-    const long btasks = cw ? (long)p.N * p.IC * ((p.OH + kRB - 1) / kRB) * (p.OW / cw) : 0;
+    // output rows per lane: 4, under stride 2 two (a block of 4 is 9 input rows; the 112 -> 56 and
+    // 56 -> 28 MobileNet layers at batch 32: 14.2 -> 13.7 and 9.2 -> 8.5 us; one row: 14.0, 9.0, and
+    // 40 % slower under stride 1)
+    const int brb = stride0 == 2 ? 2 : 4;
+    const long btasks = cw ? (long)p.N * p.IC * ((p.OH + brb - 1) / brb) * (p.OW / cw) : 0;
     if (p.dtype == TVG_BF16 && ptr16 && cw && (stride0 == 1 || p.W == 2 * p.OW) &&
         reinterpret_cast<uintptr_t>(ptr.w) % 2 == 0 && btasks < (1L << 31) &&
-        (p.OH + kRB - 1) / kRB * (p.OW / cw) < (1 << 22)) {
+        (p.OH + brb - 1) / brb * (p.OW / cw) < (1 << 22)) {
         DwDirectBf16Args d;
         d.x = static_cast<const bf16_t *>(ptr.x); d.w = static_cast<const bf16_t *>(ptr.w);
         d.scale = ptr.scale; d.shift = ptr.shift; d.bias = ptr.bias;
         d.residual = static_cast<const bf16_t *>(ptr.residual); d.y = static_cast<bf16_t *>(ptr.y);
         d.C = p.IC; d.H = p.H; d.W = p.W; d.OH = p.OH; d.OW = p.OW;
         d.CB = p.OW / cw;
-        d.tpp = (p.OH + kRB - 1) / kRB * d.CB;
+        d.tpp = (p.OH + brb - 1) / brb * d.CB;
         d.total = (int)btasks;
         d.inv_cb = 1.0f / (float)d.CB;
         d.relu = p.relu;
         const unsigned blocks = (unsigned)((btasks + 255) / 256);
         const bool nt = p.stream_out != 0;
-        if (stride0 == 1 && cw == 8) launch_direct_bf16<1, 8>(d, nt, blocks, stream);
-        else if (stride0 == 1) launch_direct_bf16<1, 4>(d, nt, blocks, stream);
-        else if (cw == 8) launch_direct_bf16<2, 8>(d, nt, blocks, stream);
-        else launch_direct_bf16<2, 4>(d, nt, blocks, stream);
+        if (stride0 == 1 && cw == 8) launch_direct_bf16<1, 8>(d, brb, nt, blocks, stream);
+        else if (stride0 == 1) launch_direct_bf16<1, 4>(d, brb, nt, blocks, stream);
+        else if (cw == 8) launch_direct_bf16<2, 8>(d, brb, nt, blocks, stream);
+        else launch_direct_bf16<2, 4>(d, brb, nt, blocks, stream);
         return hipGetLastError() == hipSuccess ? TVG_OK : TVG_ERR_LAUNCH;
     }
 
