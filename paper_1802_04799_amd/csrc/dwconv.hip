@@ -531,6 +531,7 @@ struct DwRowsArgs {
     int total;         // lanes with work: planes x OH
     float inv_oh;
     int relu;
+    uint32_t x_bytes;  // size of x rounded up to a whole word (odd rows only)
 };
 
 template <typename T, int STRIDE, int OW, bool NT>
@@ -538,8 +539,14 @@ __global__ __launch_bounds__(256) void dwconv3x3_rows_kernel(const DwRowsArgs a)
 {
     constexpr int W = OW * STRIDE;                  // input row, pixels
     constexpr int EW = 4 / sizeof(T);               // pixels per 32-bit word
-    static_assert(W % EW == 0, "input rows are whole words");
-    constexpr int NW = W / EW;
+    // Rows of an odd number of bf16 pixels (7: 14 bytes) start on any 2-byte boundary.  Such a row
+    // is fetched as the four aligned words from the one that holds its first pixel - through a
+    // buffer descriptor whose size is the tensor's rounded up to a whole word, so that the last
+    // word of the tensor is readable - and moved down by 16 bits where it started in a word's
+    // upper half (one funnel shift per word).
+    constexpr bool kOdd = W % EW != 0;
+    static_assert(!kOdd || (sizeof(T) == 2 && W == 7), "odd rows: seven bf16 pixels");
+    constexpr int NW = (W + EW - 1) / EW;
     const int g = blockIdx.x * 256 + threadIdx.x;
     if (g >= a.total) return;
     int oh;
@@ -561,18 +568,32 @@ __global__ __launch_bounds__(256) void dwconv3x3_rows_kernel(const DwRowsArgs a)
         const int ih = oh * STRIDE - 1 + r;
         const bool ok = ih >= 0 && ih < a.H;
         uint32_t wd[NW];
-        load_words<NW>(reinterpret_cast<const uint32_t *>(xp + min(max(ih, 0), a.H - 1) * W), wd);
+        const int ihc = min(max(ih, 0), a.H - 1);
+        if constexpr (kOdd) {
+            const uint32_t start = ((uint32_t)plane * a.H + ihc) * (uint32_t)(W * 2);   // byte offset in x
+            const uint4v m = __builtin_bit_cast(
+                uint4v, __builtin_amdgcn_raw_buffer_load_b128(
+                            __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.x), 0, a.x_bytes, 0x00020000),
+                            start & ~3u, 0, 0));
+            const uint32_t sh = (start & 2u) * 8u;
+            wd[0] = __builtin_amdgcn_alignbit(m[1], m[0], sh);
+            wd[1] = __builtin_amdgcn_alignbit(m[2], m[1], sh);
+            wd[2] = __builtin_amdgcn_alignbit(m[3], m[2], sh);
+            wd[3] = m[3] >> sh;
+        } else {
+            load_words<NW>(reinterpret_cast<const uint32_t *>(xp + ihc * W), wd);
+        }
         v[r][0] = 0.0f;
-        v[r][W + 1] = 0.0f;
 #pragma unroll
         for (int k = 0; k < NW; ++k) {
             if constexpr (sizeof(T) == 4) {
                 v[r][1 + k] = ok ? __uint_as_float(wd[k]) : 0.0f;
             } else {
                 v[r][1 + 2 * k] = ok ? __uint_as_float(wd[k] << 16) : 0.0f;
-                v[r][2 + 2 * k] = ok ? __uint_as_float(wd[k] & 0xFFFF0000u) : 0.0f;
+                if (2 + 2 * k <= W) v[r][2 + 2 * k] = ok ? __uint_as_float(wd[k] & 0xFFFF0000u) : 0.0f;
             }
         }
+        v[r][W + 1] = 0.0f;
     }
 
     float out[OW];
@@ -660,7 +681,7 @@ tvg_status launch_dwconv3x3(const ConvProblem &p, const ConvPointers &ptr, hipSt
     // lane's three rows are 90 registers and 112-byte strides, and D5 at batch 64 took 73 us against
     // the register-blocked kernel's 33)
     if ((p.OW == 14 || p.OW == 7 || (p.OW == 28 && stride0 == 1 && p.dtype == TVG_BF16)) &&
-        p.W == p.OW * stride0 && (p.W * esz) % 4 == 0 &&
+        p.W == p.OW * stride0 && ((p.W * esz) % 4 == 0 || (p.dtype == TVG_BF16 && p.W == 7)) &&
         rows_total >= kRowsMinLanes && rows_total < (1L << 22) &&
         reinterpret_cast<uintptr_t>(ptr.x) % 4 == 0 && reinterpret_cast<uintptr_t>(ptr.y) % 4 == 0 &&
         reinterpret_cast<uintptr_t>(ptr.residual) % 4 == 0 && reinterpret_cast<uintptr_t>(ptr.w) % esz == 0) {
@@ -671,6 +692,8 @@ tvg_status launch_dwconv3x3(const ConvProblem &p, const ConvPointers &ptr, hipSt
         d.C = p.IC; d.H = p.H; d.OH = p.OH;
         d.total = (int)rows_total;
         d.inv_oh = 1.0f / (float)p.OH;
+        // (a depthwise problem has fewer than 2^31 elements, so the byte count fits)
+        d.x_bytes = (uint32_t)(((size_t)p.N * p.IC * p.H * p.W * esz + 3) & ~(size_t)3);
         d.relu = p.relu;
         const bool nt = p.stream_out != 0;
         const bool f32 = p.dtype == TVG_F32;
@@ -678,7 +701,7 @@ tvg_status launch_dwconv3x3(const ConvProblem &p, const ConvPointers &ptr, hipSt
         else if (p.OW == 14 && stride0 == 1) f32 ? launch_rows<float, 1, 14>(d, nt, stream) : launch_rows<bf16_t, 1, 14>(d, nt, stream);
         else if (p.OW == 14) f32 ? launch_rows<float, 2, 14>(d, nt, stream) : launch_rows<bf16_t, 2, 14>(d, nt, stream);
         else if (stride0 == 2) f32 ? launch_rows<float, 2, 7>(d, nt, stream) : launch_rows<bf16_t, 2, 7>(d, nt, stream);
-        else launch_rows<float, 1, 7>(d, nt, stream);       // (bf16 rows of 7 pixels are not whole words)
+        else f32 ? launch_rows<float, 1, 7>(d, nt, stream) : launch_rows<bf16_t, 1, 7>(d, nt, stream);
         return hipGetLastError() == hipSuccess ? TVG_OK : TVG_ERR_LAUNCH;
     }
 

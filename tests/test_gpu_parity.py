@@ -99,7 +99,8 @@ def test_depthwise_ragged_shapes_full_tail(tvg, dtype, n, c, h, w, stride):
 # gives a lane one output row - square and oblong maps, an odd height under stride 2
 ROWS_SHAPES = [(8, 256, 14, 14, 1), (4, 512, 9, 14, 1), (8, 300, 7, 7, 1), (8, 256, 28, 28, 2),
                (8, 256, 20, 28, 2), (8, 320, 14, 14, 2), (8, 400, 13, 14, 2), (3, 800, 7, 7, 1),
-               (4, 200, 28, 28, 1), (3, 256, 25, 28, 1)]      # 28-pixel rows: this kernel in bf16 only
+               (4, 200, 28, 28, 1), (3, 256, 25, 28, 1),      # 28-pixel rows: this kernel in bf16 only
+               (3, 801, 7, 7, 1)]      # bf16: 14-byte rows, and a tensor that ends in half a word
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
