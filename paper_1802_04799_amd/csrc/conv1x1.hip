@@ -59,11 +59,9 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const PwArgs a)
     static_assert(MT % 64 == 0 && NT % 64 == 0, "whole load slots per thread");
     constexpr int OPER = (MT + NT) * kRow;
     constexpr int STAGE = 4 * MI * NJ * kStageBytes;    // the epilogue stages all of a wave's tiles
-    // two operand stages: chunk c + 1 is written while chunk c is read, one barrier per chunk
-    // (NCH < 0, the ragged loop, uses one)
-    constexpr int NST = NCH < 0 ? 1 : 2;
-    __shared__ __attribute__((aligned(16))) unsigned char lds[NST * OPER > STAGE ? NST * OPER : STAGE];
+    __shared__ __attribute__((aligned(16))) unsigned char lds[OPER > STAGE ? OPER : STAGE];
     __shared__ float ss_lds[2 * MT];
+    unsigned char *As = lds, *Bs = lds + MT * kRow;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave & 1, wn = wave >> 1;
@@ -156,8 +154,7 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const PwArgs a)
             }
         }
     };
-    auto store_chunk = [&](int set, int st = 0) __attribute__((always_inline)) {
-        unsigned char *As = lds + st * OPER, *Bs = As + MT * kRow;
+    auto store_chunk = [&](int set) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < BT; ++j)
             *reinterpret_cast<uint4v *>(Bs + bdst[j]) = uint4v{
@@ -176,8 +173,7 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const PwArgs a)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    auto mfma_chunk = [&](int st = 0) __attribute__((always_inline)) {
-        const unsigned char *As = lds + st * OPER, *Bs = As + MT * kRow;
+    auto mfma_chunk = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
             uint4v af[MI], bf[NJ];
@@ -203,12 +199,11 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const PwArgs a)
     if constexpr (NCH > 0) {
 #pragma unroll
         for (int c = 0; c < NCH; ++c) load_chunk(c, c);
-        store_chunk(0, 0);
-        __syncthreads();
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
-            if (c + 1 < NCH) store_chunk(c + 1, (c + 1) & 1);
-            mfma_chunk(c & 1);
+            store_chunk(c);
+            __syncthreads();
+            mfma_chunk();
             __syncthreads();          // (the last one frees the operand tiles for the tail)
         }
     } else if constexpr (NCH < 0) {
@@ -226,8 +221,8 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const PwArgs a)
             }
         }
     } else {
-        // (a multiple of PF chunks, at least 2 PF: the launcher sees to that.  Every load below is
-        // issued unconditionally - the last two groups are peeled off for that - because a wait on
+        // (a multiple of PF chunks, the launcher sees to that.  Every load below is issued
+        // unconditionally - the last group of PF chunks is peeled off for that - because a wait on
         // the memory counter can leave the younger loads in flight only if they are certain to
         // have been issued: behind a branch they force a wait for everything.)
         const int nchunks = a.IC / kKC;
@@ -236,39 +231,23 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const PwArgs a)
             load_chunk(s, s);
             __builtin_amdgcn_sched_barrier(0);    // (issue order = consumption order)
         }
-        // chunk c is read from stage c & 1 while chunk c + 1 goes from set (c + 1) % PF into the
-        // other stage, and that set is refilled with chunk c + 1 + PF (PF is even: set and stage of
-        // a position in the unrolled group are compile-time values)
-        static_assert(PF % 2 == 0, "stage parity is fixed within a group");
-        store_chunk(0, 0);
-        __syncthreads();
-        __builtin_amdgcn_sched_barrier(0);
-        load_chunk(PF, 0);                    // (there are at least 2 PF chunks)
-        __builtin_amdgcn_sched_barrier(0);
-        for (int c0 = 0; c0 + 2 * PF < nchunks; c0 += PF) {
+        for (int c0 = 0; c0 + PF < nchunks; c0 += PF) {
 #pragma unroll
             for (int s = 0; s < PF; ++s) {
-                // position c = c0 + s: store chunk c + 1, fetch chunk c + 1 + PF into its set
-                store_chunk((s + 1) % PF, (s + 1) & 1);
+                store_chunk(s);
+                __syncthreads();
                 __builtin_amdgcn_sched_barrier(0);
-                load_chunk(c0 + s + 1 + PF, (s + 1) % PF);
+                load_chunk(c0 + s + PF, s);
                 __builtin_amdgcn_sched_barrier(0);
-                mfma_chunk(s & 1);
+                mfma_chunk();
                 __syncthreads();
             }
         }
-        // the last two groups, where the fetches and then the stores run out: position t stands
-        // for chunk nchunks - 2 PF + t, so every condition is a compile-time one
-        const int cl = nchunks - 2 * PF;
 #pragma unroll
-        for (int t = 0; t < 2 * PF; ++t) {
-            if (t + 1 < 2 * PF) store_chunk((t + 1) % PF, (t + 1) & 1);
-            if (t + 1 < PF) {
-                __builtin_amdgcn_sched_barrier(0);
-                load_chunk(cl + t + 1 + PF, (t + 1) % PF);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            mfma_chunk(t & 1);
+        for (int s = 0; s < PF; ++s) {    // the last group: nothing left to fetch
+            store_chunk(s);
+            __syncthreads();
+            mfma_chunk();
             __syncthreads();              // (the last one frees the operand tiles for the tail)
         }
     }
@@ -345,9 +324,11 @@ tvg_status launch_conv1x1(const ConvProblem &p, const Pw1x1Plan &plan, const Con
     if (nch > 0 && ((nch != 2 && nch != 4 && nch != 8) || (nch == 8 && plan.mt == 128 && plan.nt == 128))) {
         // the rolling window takes whole groups of PF chunks (4, or 2 under the 128 x 128 tile;
         // eight sets under the 64-pixel tiles, refilled one by one or four at a time, were slower:
-        // 512 -> 512 at 14x14 14.6 and 15.4 us against 13.1)
+        // 512 -> 512 at 14x14 14.6 and 15.4 us against 13.1; two LDS stages with one barrier per
+        // chunk made single layers 3-10 % faster in a warm loop and changed the chains and the
+        // step by less than 1 % either way on one box: not kept)
         const int pf = (plan.mt == 128 && plan.nt == 128) ? 2 : 4;
-        nch = (nch % pf == 0 && nch >= 2 * pf) ? 0 : -1;
+        nch = nch % pf == 0 ? 0 : -1;
     }
 #define TVG_PW_LAUNCH(MT_, NT_)                                                                     \
     do {                                                                                           \
