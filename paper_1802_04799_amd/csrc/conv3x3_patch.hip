@@ -72,7 +72,15 @@ __device__ __forceinline__ int xcd_remap(int bid, int nb)
     return xcd < rem ? xcd * (q + 1) + local : rem * (q + 1) + (xcd - rem) * q + local;
 }
 
-__device__ __forceinline__ uint32_t half_of(uint32_t d, int hi) { return hi ? d >> 16 : d & 0xFFFFu; }
+// (half `ha` of a) | (half `hb` of b) << 16 in one byte permute (v_perm_b32 takes its selector
+// bytes 0-3 from the second source, 4-7 from the first); written as shifts and masks the same
+// pair costs two to three instructions, and the staging of a chunk was a third of the loop's
+// instruction stream, which is what bounds the layers of this kernel
+__device__ __forceinline__ uint32_t pack_halves(uint32_t a, int ha, uint32_t b, int hb)
+{
+    const uint32_t sel = (ha ? 0x0302u : 0x0100u) | ((hb ? 0x0706u : 0x0504u) << 16);
+    return __builtin_amdgcn_perm(b, a, sel);
+}
 
 // MT x NT output tile per workgroup of 256 threads; PT = patch load tasks per thread; PX =
 // horizontally adjacent pixels fetched per load (2, 4 or 8 need W to be a multiple: 32-, 64- or
@@ -246,8 +254,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
                         uint32_t o[4];
 #pragma unroll
                         for (int q = 0; q < 4; ++q)
-                            o[q] = half_of(praw[j][2 * q][k >> 1], k & 1) |
-                                   (half_of(praw[j][2 * q + 1][k >> 1], k & 1) << 16);
+                            o[q] = pack_halves(praw[j][2 * q][k >> 1], k & 1, praw[j][2 * q + 1][k >> 1], k & 1);
                         // stride 2 (PX > 1: the task starts on an odd patch column): pixels
                         // alternate between the odd and the even half of the row
                         const int koff = STRIDE == 2 ? ((k & 1) ? (1 - HALF) * kWordBytes : 0) + (k >> 1) * kWordBytes
@@ -270,7 +277,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int e0 = (2 * q) * 9 + tap, e1 = (2 * q + 1) * 9 + tap;
-                    o[q] = half_of(d[e0 >> 1], e0 & 1) | (half_of(d[e1 >> 1], e1 & 1) << 16);
+                    o[q] = pack_halves(d[e0 >> 1], e0 & 1, d[e1 >> 1], e1 & 1);
                 }
                 *reinterpret_cast<uint4v *>(As + w_oct * APLANE + (tap * MT + w_ocl) * kWordBytes) =
                     uint4v{o[0], o[1], o[2], o[3]};
