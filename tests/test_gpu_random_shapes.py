@@ -110,6 +110,41 @@ def test_random_depthwise(tvg, case):
     check(to_host(y), want, dtype, sh)
 
 
+def dw_many_plane_cases(seed, count):
+    """Launches with thousands of planes: what the row-per-lane kernel (output rows of 7, 14 and,
+    in bf16, 28 pixels) and the taller row blocks of the fp32 register-blocked kernel take."""
+    rng = random.Random(seed)
+    out = []
+    for i in range(count):
+        stride = rng.choice([1, 2])
+        if rng.random() < 0.6:
+            w = rng.choice([7, 14, 28]) * stride              # the row kernel's widths
+        else:
+            w = 4 * rng.randint(2, 16)                        # rows of whole 16-byte vectors
+        h = rng.randint(2, 30)
+        oh = (h - 1) // stride + 1
+        planes = max(1, rng.choice([17000, 20000, 140000]) // max(1, oh) + rng.randint(0, 7))
+        planes = min(planes, 3_000_000 // (h * w))            # keep the oracle's work small
+        c = rng.choice([c for c in (64, 96, 256, 500, 1000) if c <= planes] or [planes])
+        n = -(-planes // c)
+        out.append((i, n, c, h, w, stride, rng.choice(["f32", "bf16"]), rng.random() < 0.7,
+                    rng.random() < 0.5, rng.random() < 0.5))
+    return out
+
+
+@pytest.mark.parametrize("case", dw_many_plane_cases(31337, 48), ids=lambda c: f"{c[0]}")
+def test_random_depthwise_many_planes(tvg, case):
+    i, n, c, h, w, stride, dtype, relu, hint, res = case
+    sh = ti.ConvShape("rp", n, c, h, w, c, 3, 3, stride, 1, depthwise=True)
+    inp = ti.make_inputs(sh, 58000 + i, dtype, residual=res, bias=True)
+    d = dev_inputs(inp, dtype)
+    y = tvg.dwconv2d_fused(d["x"], d["w"], d["scale"], d["shift"], d["bias"], d["residual"],
+                           stride=stride, pad=1, relu=relu, stream_out=hint)
+    want = oracle.dwconv2d_fused(inp["x"], inp["w"], inp["scale"], inp["shift"], inp["bias"],
+                                 inp["residual"], stride=(stride,) * 2, pad=(1, 1), relu=relu)
+    check(to_host(y), want, dtype, sh)
+
+
 def block_cases(seed, count):
     rng = random.Random(seed)
     out = []
