@@ -478,6 +478,32 @@ def test_bf16_1x1_kernel_shapes(tvg, cfg):
     check(to_host(y), oracle_dense(sh, inp), "bf16")
 
 
+# n, ic, h, w, oc, stride: reductions of 4, 6, 8, 12, 16, 20 and 32 chunks of 32 channels (whole
+# reduction fetched up front: 4 and 8; the rolling window of four - two under the 128 x 128 tile -
+# otherwise), ragged channel and pixel tails, 7x7 maps, under each of the four tiles
+PW_WINDOW_SHAPES = [(2, 128, 9, 9, 70, 1), (3, 192, 7, 7, 130, 1), (2, 256, 10, 6, 96, 2),
+                    (1, 384, 14, 14, 200, 1), (2, 512, 14, 14, 512, 1), (3, 512, 7, 7, 72, 2),
+                    (1, 640, 8, 9, 40, 1), (2, 1024, 7, 7, 130, 1), (33, 512, 2, 2, 64, 1)]
+
+
+@pytest.mark.parametrize("tile", [(64, 64), (128, 64), (64, 128), (128, 128)], ids=lambda t: f"{t[0]}x{t[1]}")
+@pytest.mark.parametrize("cfg", PW_WINDOW_SHAPES, ids=lambda c: "x".join(map(str, c)))
+def test_bf16_1x1_kernel_chunk_windows_all_tiles(tvg, cfg, tile):
+    n, ic, h, w, oc, stride = cfg
+    sh = ti.ConvShape("pw", n, ic, h, w, oc, 1, 1, stride, 0)
+    desc = tvg.ConvDesc(n, ic, h, w, oc, 1, 1, stride, stride, 0, 0, tvg.TVG_BF16, 0)
+    if tile[0] == 128 and oc <= 64:
+        pytest.skip("no 128-channel tile for layers of at most 64 channels")
+    assert tvg.tvg_conv2d_set_knobs(desc, (tile[0], tile[1], 0, 0, 0, 0)) == 0
+    try:
+        assert tvg.tvg_conv2d_get_plan(desc) == (4, tile[0], tile[1])
+        inp = ti.make_inputs(sh, 8800 + sum(cfg) + tile[0] + tile[1], "bf16", residual=True, bias=True)
+        y = run_dense(tvg, sh, inp, "bf16")
+        check(to_host(y), oracle_dense(sh, inp), "bf16", (cfg, tile))
+    finally:
+        tvg.tvg_conv2d_set_knobs(desc, None)
+
+
 DEEP_PW_SHAPES = [
     # bf16 1x1 stride-1 problems with IC % 128 == 0 and maps of 4n pixels (the deep-reduction
     # pointwise kernel): n, ic, h, w, oc.  16- and 8-byte pixel loads (HW % 8 == 0 or not), 2 to 16
