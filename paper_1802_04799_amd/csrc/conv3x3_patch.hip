@@ -94,7 +94,10 @@ __global__ __launch_bounds__(256, 2) void conv3x3_patch_kernel(const PatchArgs a
     // four waves as 2 x 2, or 1 x 4 for the wide 64 x 256 tile (the weights of a chunk weigh
     // about six times the input patch per tile side, so a wide pixel tile moves the fewest
     // operand bytes per MFMA through the vector memory path)
-    constexpr int WM = NT >= 256 ? 1 : 2, WN = 4 / WM;
+    // wave layout: under a 64-channel tile the four waves sit side by side, each all 64 channels x
+    // NT / 4 pixels (for 128 pixels that is two weight reads and one pixel read per pair of
+    // MFMAs instead of one and two: C7 19.0 -> 18.4 us); a 128-channel tile is 2 x 2 waves
+    constexpr int WM = (NT >= 256 || (MT == 64 && NT == 128)) ? 1 : 2, WN = 4 / WM;
     constexpr int WTM = MT / WM, WTN = NT / WN;
     constexpr int MI = WTM / 32, NJ = WTN / 32;
     constexpr int APLANE = 9 * MT * kWordBytes + 128;     // (+128: the two planes' stores fall on different banks)
