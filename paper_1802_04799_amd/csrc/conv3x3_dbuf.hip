@@ -874,13 +874,13 @@ tvg_status launch_conv3x3_dbuf(const ConvProblem &p, const Patch3x3Plan &plan,
     switch (plan.nt) {
     case 256: return launch_pt<1, 2>(a, plan.lds_bytes, p.sh, plan.pt, plan.px, plan.kg, stream);
     case 128:
-        // whole rows of at most 7 pixels (C12): four waves side by side, each all 64 channels x 32
-        // pixels - two weight reads and one pixel read per pair of MFMAs instead of one and two,
-        // and it is the pixel reads of 7-pixel rows that collide (23.1 -> 22.4 us at batch 64)
+        // one group of four waves: side by side, each all 64 channels x 32 pixels - two weight
+        // reads and one pixel read per pair of MFMAs instead of one and two (the weight reads never
+        // collide, the pixel reads of short or strided rows do): C12 23.1 -> 22.4 us, C10 21.7 ->
+        // 20.6 us at batch 64, the 256-channel 14x14 layer at batch 32 16.0 -> 15.5 us
         if (p.sh == 1 && plan.kg == 1 && plan.px == 8 && p.W < 8 && plan.pt <= 1)
             return launch_instance<1, 1, 1, 1, 8, 1, true>(a, plan.lds_bytes, stream);
-        // (stride 2 likewise: C10 21.7 -> 20.6 us)
-        if (p.sh == 2 && plan.kg == 1)
+        if (plan.kg == 1)
             return launch_pt<1, 1>(a, plan.lds_bytes, p.sh, plan.pt, plan.px, plan.kg, stream);
         return launch_pt<2, 2>(a, plan.lds_bytes, p.sh, plan.pt, plan.px, plan.kg, stream);
     default: return launch_pt<2, 1>(a, plan.lds_bytes, p.sh, plan.pt, plan.px, plan.kg, stream);
