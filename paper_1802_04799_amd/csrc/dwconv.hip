@@ -610,7 +610,7 @@ __global__ __launch_bounds__(256) void dwconv3x3_rows_kernel(const DwRowsArgs a)
     const size_t idx = ((size_t)plane * a.OH + oh) * OW;
     const float floor_v = a.relu ? 0.0f : -INFINITY;
     T *yp = static_cast<T *>(a.y) + idx;
-    const T *rp = static_cast<const T *>(a.residual) + idx;
+    const T *rp = a.residual ? static_cast<const T *>(a.residual) + idx : nullptr;
     constexpr bool kWords = (OW * sizeof(T)) % 4 == 0;      // the output row is whole words
     if constexpr (kWords) {
         constexpr int NO = OW * sizeof(T) / 4;
