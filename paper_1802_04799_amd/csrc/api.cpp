@@ -313,8 +313,8 @@ tvg_status tvg_conv2d_get_plan(const tvg_conv_desc *desc, int32_t *kernel, int32
         *nt = d.pw.nt;
     } else if (d.f32_shape) {
         *kernel = TVG_KERNEL_F32_SMALL;
-        *mt = 32;
-        *nt = 32;
+        *mt = d.f32.stem ? 32 : d.f32.tile;
+        *nt = d.f32.stem ? 64 : d.f32.tile;
     } else {
         *kernel = TVG_KERNEL_GENERIC;
         *mt = d.generic.mt;

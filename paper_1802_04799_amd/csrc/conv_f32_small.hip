@@ -33,7 +33,7 @@ constexpr int kCPH = 4;              // input channels per half-wave and pass
 // workgroups of 16 waves (4 per SIMD, 128 registers each) hold fewer
 constexpr int kMaxSlots = 16, kMaxBig = 8;
 constexpr int kPartPitch = 65;       // floats per (wave, register) row of the partial sums
-constexpr int kWRegion = 32 * 73 + 0;  // floats of a wave's weight runs in LDS (3x3: 32 x (72 + 1)); 16-byte multiple
+constexpr int kWRow = 73;            // floats of one weight run in LDS (3x3: 72 + 1); a tile's runs: T x 73, a 16-byte multiple
 constexpr int kRsrc = 0x00020000;
 
 struct F32Args {
@@ -49,25 +49,35 @@ struct F32Args {
     uint32_t x_bytes, w_bytes;
 };
 
-template <int R, int STRIDE, int VEC, bool BIG>
+// T = tile edge: 32 (v_mfma_f32_32x32x2_f32: the two half-waves hold k and k + 1) or 16
+// (v_mfma_f32_16x16x4_f32: four quarter-waves, four k values).  The small tile is for layers that
+// leave most CUs without a 32 x 32 tile: every wave of a workgroup issues its MFMAs to the matrix
+// pipe of its SIMD, 36 of 64 cycles each per pass of a 3x3 layer, and with 16 waves on a CU that
+// is 9200 cycles (4.4 us) while three quarters of the chip idle; a quarter of the tile is a quarter
+// of that on four times the CUs.
+template <int R, int STRIDE, int VEC, bool BIG, int T>
 __global__ __launch_bounds__(BIG ? 1024 : 512) void conv_f32_small_kernel(const F32Args a)
 {
+    constexpr int KG = 64 / T;                     // k values per MFMA = groups of T lanes
+    constexpr int CPG = 2 * kCPH / KG;             // input channels per group and pass
+    constexpr int NV = T * T / 64;                 // accumulator registers
+    constexpr int kWRegion = T * kWRow;
     constexpr int RS = R * R, PAD = R / 2;
     constexpr int WROW = 2 * kCPH * RS;            // floats of one output channel's run per pass
     constexpr int WPITCH = WROW + 1;               // its pitch in LDS (odd: conflict-free reads)
-    constexpr int WPIECES = 32 * WROW / 4;         // 16-byte pieces of the 32 runs
+    constexpr int WPIECES = T * WROW / 4;          // 16-byte pieces of the T runs
     constexpr int WSLOTS = (WPIECES + 63) / 64;    // per lane
     extern __shared__ __attribute__((aligned(16))) float smem[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int lp = lane & 31, half = lane >> 5;
+    const int lp = lane & (T - 1), half = lane / T;        // (half: the lane's k group)
     int b = blockIdx.x;
     const int mt = b % a.mtiles;
     b /= a.mtiles;
     const int pt = b % a.tpi, n = b / a.tpi;
-    const int m0 = mt * 32, p0 = pt * 32;
+    const int m0 = mt * T, p0 = pt * T;
     const int OHW = a.OH * a.OW, W = a.W, H = a.H;
-    const int npx = min(32, OHW - p0);
+    const int npx = min(T, OHW - p0);
     const int oh_lo = p0 / a.OW, oh_hi = (p0 + npx - 1) / a.OW;
     const int ih_lo = oh_lo * STRIDE - PAD;
     const int nr = (oh_hi - oh_lo) * STRIDE + R;          // input rows of the tile (with padding rows)
@@ -92,7 +102,7 @@ __global__ __launch_bounds__(BIG ? 1024 : 512) void conv_f32_small_kernel(const 
     // this lane's pixel (lanes past the tile's end shadow pixel 0; their results are dropped)
     const int pp = lp < npx ? lp : 0;
     const int oh = (p0 + pp) / a.OW, ow = (p0 + pp) - oh * a.OW;
-    const int bbase = half * kCPH * plane + (oh - oh_lo) * STRIDE * pitch + ow * STRIDE;
+    const int bbase = half * CPG * plane + (oh - oh_lo) * STRIDE * pitch + ow * STRIDE;
     // weight copy slots: piece q of the 32 runs -> (run, part); runs past OC shadow the last one
     uint32_t wsrc[WSLOTS];
     int wdst[WSLOTS];
@@ -103,7 +113,7 @@ __global__ __launch_bounds__(BIG ? 1024 : 512) void conv_f32_small_kernel(const 
         wdst[k] = q < WPIECES ? run * WPITCH + part * 4 : -1;
         wsrc[k] = 4u * (uint32_t)(min(m0 + run, a.OC - 1) * a.IC * RS) + 16u * (uint32_t)part;
     }
-    const int abase = lp * WPITCH + half * kCPH * RS;
+    const int abase = lp * WPITCH + half * CPG * RS;
 
     // copy slots of this lane: element i of the wave's 8 x E floats -> (channel, row, column)
     const float inv_e = 1.0f / (float)E, inv_w = 1.0f / (float)W;
@@ -125,9 +135,10 @@ __global__ __launch_bounds__(BIG ? 1024 : 512) void conv_f32_small_kernel(const 
         }
     }
 
-    float16v acc;
+    typedef float accv __attribute__((ext_vector_type(NV)));
+    accv acc;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+    for (int v = 0; v < NV; ++v) acc[v] = 0.0f;
 
     for (int pass = 0; pass < a.passes; ++pass) {
         // this wave's 8 channels (slice blockIdx.y of the reduction takes a.passes passes)
@@ -175,7 +186,7 @@ __global__ __launch_bounds__(BIG ? 1024 : 512) void conv_f32_small_kernel(const 
         // a wave reads only what it wrote itself: LDS operations of a wave complete in order
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
-        for (int c = 0; c < kCPH; ++c)
+        for (int c = 0; c < CPG; ++c)
 #pragma unroll
             for (int r = 0; r < R; ++r)
 #pragma unroll
@@ -183,7 +194,8 @@ __global__ __launch_bounds__(BIG ? 1024 : 512) void conv_f32_small_kernel(const 
                     const float bv = reg[bbase + c * plane + r * pitch + s];
                     const float av = wl[abase + c * RS + r * R + s];
                     // pixel operand first: the accumulator tile is D[pixel][channel]
-                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av, acc, 0, 0, 0);
+                    if constexpr (T == 32) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av, acc, 0, 0, 0);
+                    else acc = __builtin_amdgcn_mfma_f32_16x16x4f32(bv, av, acc, 0, 0, 0);
                 }
         __builtin_amdgcn_wave_barrier();      // the next pass overwrites the rows just read
     }
@@ -192,17 +204,19 @@ __global__ __launch_bounds__(BIG ? 1024 : 512) void conv_f32_small_kernel(const 
     __syncthreads();
     float *part = smem;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) part[(wave * 16 + v) * kPartPitch + lane] = acc[v];
+    for (int v = 0; v < NV; ++v) part[(wave * NV + v) * kPartPitch + lane] = acc[v];
     __syncthreads();
-    // value v of lane l: channel l % 32, pixel 8*(v/4) + 4*(l/32) + v%4.  Thread t of the first
-    // 256 takes channel t / 8 and the 4 consecutive pixels from 4 * (t % 8) on.
-    for (int t = tid; t < 256; t += (int)blockDim.x) {
-        const int cc = t >> 3, pb = (t & 7) * 4;
-        const int src_lane = cc + 32 * ((pb >> 2) & 1), v0 = 4 * (pb >> 3);
+    // T = 32: value v of lane l is channel l % 32, pixel 8*(v/4) + 4*(l/32) + v%4; T = 16: channel
+    // l % 16, pixel 4*(l/16) + v.  Thread t of the first T*T/4 takes channel t / (T/4) and the 4
+    // consecutive pixels from 4 * (t % (T/4)) on.
+    for (int t = tid; t < T * T / 4; t += (int)blockDim.x) {
+        const int cc = t / (T / 4), pb = (t % (T / 4)) * 4;
+        const int src_lane = T == 32 ? cc + 32 * ((pb >> 2) & 1) : cc + 16 * (pb >> 2);
+        const int v0 = T == 32 ? 4 * (pb >> 3) : 0;
         float sum[4] = {0.0f, 0.0f, 0.0f, 0.0f};
         for (int s = 0; s < a.nw; ++s)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) sum[q] += part[(s * 16 + v0 + q) * kPartPitch + src_lane];
+            for (int q = 0; q < 4; ++q) sum[q] += part[(s * NV + v0 + q) * kPartPitch + src_lane];
         const int oc = m0 + cc;
         if (oc >= a.OC || pb >= npx) continue;
         if (a.ksplit > 1) {       // a slice of the reduction: raw sums, the reduce launch finishes
@@ -238,7 +252,7 @@ __global__ __launch_bounds__(BIG ? 1024 : 512) void conv_f32_small_kernel(const 
     }
 }
 
-template <int R, int STRIDE>
+template <int R, int STRIDE, int T>
 tvg_status launch_rs(const F32Args &a, int vec, dim3 grid, size_t lds, hipStream_t stream)
 {
     // opt in to > 64 KB of dynamic LDS (a cheap host call, made before every launch: the four
@@ -249,7 +263,7 @@ tvg_status launch_rs(const F32Args &a, int vec, dim3 grid, size_t lds, hipStream
     };
 #define TVG_F32_LAUNCH(VEC_, BIG_)                                                             \
     do {                                                                                       \
-        auto kernel = conv_f32_small_kernel<R, STRIDE, VEC_, BIG_>;                            \
+        auto kernel = conv_f32_small_kernel<R, STRIDE, VEC_, BIG_, T>;                         \
         if (!set(kernel)) return TVG_ERR_LAUNCH;                                               \
         hipLaunchKernelGGL(kernel, grid, dim3(64 * a.nw), lds, stream, a);                     \
     } while (0)
@@ -454,6 +468,7 @@ bool plan_conv_f32_small(const ConvProblem &p, F32SmallPlan *plan)
             return false;                                                      // 32-bit byte offsets
         if ((long)p.N * ((p.OH * p.OW + kStemPix - 1) / kStemPix) * ((p.OC + 31) / 32) >= (1L << 31)) return false;
         plan->stem = 1;
+        plan->tile = 32;
         plan->nw = kStemWaves;
         plan->passes = 1;
         plan->ksplit = 1;
@@ -473,46 +488,66 @@ bool plan_conv_f32_small(const ConvProblem &p, F32SmallPlan *plan)
     const long gtiles = (long)((p.OC + 127) / 128) * ((p.npix + 127) / 128);
     if (gtiles >= kComputeUnits) return false;
     const int OHW = p.OH * p.OW;
-    const int orows = std::min(p.OH, (std::min(32, OHW) + p.OW - 2) / p.OW + 1);   // rows 32 pixels can touch
-    const int nr = (orows - 1) * p.sh + p.R;
     const int pitch = p.W + 2 * (p.R / 2);
-    const int region = (2 * kCPH * nr * pitch + 3) / 4 * 4;
     const int vec = p.W % 4 == 0 ? 4 : p.W % 2 == 0 ? 2 : 1;
-    const long elems = (long)2 * kCPH * std::min(nr, p.H) * p.W;
-    const long slots = (elems / vec + 63) / 64;
-    if (slots > kMaxSlots) return false;
-    if (elems >= (1 << 22)) return false;                    // fast_div range
     if ((size_t)p.N * p.IC * p.H * p.W >= ((size_t)1 << 30) || (size_t)p.OC * p.K >= ((size_t)1 << 30))
         return false;                                        // 32-bit byte offsets
-    int nw = slots <= kMaxBig ? 16 : 8;
-    auto lds_for = [&](int w) {
-        return std::max((size_t)w * (region + kWRegion) * 4, (size_t)w * 16 * kPartPitch * 4);
+    // the geometry of a plan with tiles of T x T outputs
+    auto geometry = [&](int T, F32SmallPlan *g) {
+        const int orows = std::min(p.OH, (std::min(T, OHW) + p.OW - 2) / p.OW + 1);   // rows T pixels can touch
+        const int nr = (orows - 1) * p.sh + p.R;
+        const int region = (2 * kCPH * nr * pitch + 3) / 4 * 4;
+        const long elems = (long)2 * kCPH * std::min(nr, p.H) * p.W;
+        const long slots = (elems / vec + 63) / 64;
+        if (slots > kMaxSlots) return false;
+        if (elems >= (1 << 22)) return false;                    // fast_div range
+        int nw = slots <= kMaxBig ? 16 : 8;
+        auto lds_for = [&](int w) {
+            return std::max((size_t)w * (region + T * kWRow) * 4, (size_t)w * (T * T / 64) * kPartPitch * 4);
+        };
+        while (nw > 1 && (p.IC % (2 * kCPH * nw) != 0 || lds_for(nw) > 160 * 1024)) nw >>= 1;
+        const size_t lds = lds_for(nw);
+        if (lds > 160 * 1024) return false;
+        const long wgs = (long)p.N * ((OHW + T - 1) / T) * ((p.OC + T - 1) / T);
+        if (wgs >= (1L << 31)) return false;
+        // Deep reductions on few tiles (C9, C10, C12 at batch 1: 4 to 8 passes of about 3.6 us each
+        // under the large tile, the matrix pipes of a few CUs doing all the work): slices of the
+        // reduction go to different workgroups, their sums to the workspace, and the reduce launch
+        // of the generic kernel adds them in a fixed order.  A second launch costs about 4 us, so
+        // only from three passes on.
+        const int passes = p.IC / (2 * kCPH * nw);
+        int ksplit = 1;
+        if (passes >= 3 && wgs < kComputeUnits) {
+            ksplit = passes;
+            while (ksplit > 1 && (passes % ksplit != 0 || wgs * (ksplit / 2) >= 2 * kComputeUnits)) --ksplit;
+        }
+        g->tile = T;
+        g->nw = nw;
+        g->ksplit = ksplit;
+        g->passes = passes / ksplit;
+        g->workspace_bytes = ksplit > 1 ? (size_t)ksplit * p.npix * p.OC * sizeof(float) : 0;
+        g->pitch = pitch;
+        g->region = region;
+        g->vec = vec;
+        g->lds_bytes = lds;
+        g->stem = 0;
+        return true;
     };
-    while (nw > 1 && (p.IC % (2 * kCPH * nw) != 0 || lds_for(nw) > 160 * 1024)) nw >>= 1;
-    const size_t lds = lds_for(nw);
-    if (lds > 160 * 1024) return false;
-    if ((long)p.N * ((OHW + 31) / 32) * ((p.OC + 31) / 32) >= (1L << 31)) return false;
-    // Deep reductions on few tiles (C9, C10, C12 at batch 1: 32 to 56 tiles, 4 to 8 passes of
-    // about 3.6 us each, the matrix pipes of a few CUs doing all the work): slices of the
-    // reduction go to different workgroups, their sums to the workspace, and the reduce launch of
-    // the generic kernel adds them in a fixed order.  A second launch costs about 4 us, so only
-    // from three passes on.
-    const int passes = p.IC / (2 * kCPH * nw);
-    const long wgs = (long)p.N * ((OHW + 31) / 32) * ((p.OC + 31) / 32);
-    int ksplit = 1;
-    if (passes >= 3 && wgs < kComputeUnits) {
-        ksplit = passes;
-        while (ksplit > 1 && (passes % ksplit != 0 || wgs * (ksplit / 2) >= 2 * kComputeUnits)) --ksplit;
+    // 16 x 16 tiles where 32 x 32 ones would leave three quarters of the CUs without a workgroup,
+    // provided the small tiles then need no second launch (measured at batch 1, us with 32 / 16:
+    // C7 12.0 / 7.9, C9 11.3 / 9.1, C11 10.9 / 7.9, C10 12.1 / 11.6, C8 7.9 / 7.9; with more tiles
+    // the small ones lose - C2 8.3 / 20.2, C4 9.8 / 11.8, C6 11.0 / 12.3 - as does C12, 12.5 / 16.2,
+    // whose reduction stays split either way and whose 49 pixels make four tiles of 16, one of them
+    // a single pixel)
+    const long wgs32 = (long)p.N * ((OHW + 31) / 32) * ((p.OC + 31) / 32);
+    if (wgs32 <= kComputeUnits / 4) {
+        F32SmallPlan small;
+        if (geometry(16, &small) && small.ksplit == 1) {
+            *plan = small;
+            return true;
+        }
     }
-    plan->nw = nw;
-    plan->ksplit = ksplit;
-    plan->passes = passes / ksplit;
-    plan->workspace_bytes = ksplit > 1 ? (size_t)ksplit * p.npix * p.OC * sizeof(float) : 0;
-    plan->pitch = pitch;
-    plan->region = region;
-    plan->vec = vec;
-    plan->lds_bytes = lds;
-    return true;
+    return geometry(32, plan);
 }
 
 bool conv_f32_small_pointers_ok(const ConvPointers &ptr)
@@ -565,8 +600,8 @@ tvg_status launch_conv_f32_small(const ConvProblem &p, const F32SmallPlan &plan,
     a.residual = static_cast<const float *>(ptr.residual); a.y = static_cast<float *>(ptr.y);
     a.N = p.N; a.IC = p.IC; a.H = p.H; a.W = p.W; a.OC = p.OC; a.OH = p.OH; a.OW = p.OW;
     a.relu = p.relu;
-    a.mtiles = (p.OC + 31) / 32;
-    a.tpi = (p.OH * p.OW + 31) / 32;
+    a.mtiles = (p.OC + plan.tile - 1) / plan.tile;
+    a.tpi = (p.OH * p.OW + plan.tile - 1) / plan.tile;
     a.nw = plan.nw; a.passes = plan.passes; a.pitch = plan.pitch; a.region = plan.region;
     a.ksplit = plan.ksplit; a.ws = ptr.workspace;
     a.vec_out = (p.OH * p.OW) % 4 == 0 && reinterpret_cast<uintptr_t>(ptr.y) % 16 == 0 &&
@@ -576,10 +611,17 @@ tvg_status launch_conv_f32_small(const ConvProblem &p, const F32SmallPlan &plan,
     const dim3 grid((unsigned)((long)a.mtiles * a.tpi * p.N), (unsigned)plan.ksplit);
     const int vec = plan.vec;
     tvg_status st;
-    if (p.R == 3) st = p.sh == 1 ? launch_rs<3, 1>(a, vec, grid, plan.lds_bytes, stream)
-                                 : launch_rs<3, 2>(a, vec, grid, plan.lds_bytes, stream);
-    else st = p.sh == 1 ? launch_rs<1, 1>(a, vec, grid, plan.lds_bytes, stream)
-                        : launch_rs<1, 2>(a, vec, grid, plan.lds_bytes, stream);
+    if (plan.tile == 16) {
+        if (p.R == 3) st = p.sh == 1 ? launch_rs<3, 1, 16>(a, vec, grid, plan.lds_bytes, stream)
+                                     : launch_rs<3, 2, 16>(a, vec, grid, plan.lds_bytes, stream);
+        else st = p.sh == 1 ? launch_rs<1, 1, 16>(a, vec, grid, plan.lds_bytes, stream)
+                            : launch_rs<1, 2, 16>(a, vec, grid, plan.lds_bytes, stream);
+    } else {
+        if (p.R == 3) st = p.sh == 1 ? launch_rs<3, 1, 32>(a, vec, grid, plan.lds_bytes, stream)
+                                     : launch_rs<3, 2, 32>(a, vec, grid, plan.lds_bytes, stream);
+        else st = p.sh == 1 ? launch_rs<1, 1, 32>(a, vec, grid, plan.lds_bytes, stream)
+                            : launch_rs<1, 2, 32>(a, vec, grid, plan.lds_bytes, stream);
+    }
     if (st != TVG_OK || plan.ksplit == 1) return st;
     return launch_splitk_reduce(p, plan.ksplit, ptr, stream);
 }

@@ -151,6 +151,7 @@ tvg_status launch_dwpw(const ConvProblem &dw, int OC, int pw_relu, int pw_stream
 // fp32 1x1 / 3x3 kernel for launch-bound problems: one launch, the waves of a workgroup split the
 // reduction and add their accumulators through LDS.
 struct F32SmallPlan {
+    int tile;           // output tile edge: 32 or 16
     int nw, passes;     // waves per workgroup, passes over the input channels
     int pitch, region;  // LDS row pitch and floats per wave
     int vec;            // floats per patch load: 4, 2 or 1 (rows of 4n, 2n, other pixel counts)

@@ -231,6 +231,10 @@ def test_tile_table_sets_overrides_and_forgets():
     assert tvg.tvg_conv2d_get_plan(desc(n=64, c=128, h=28, w=28, k=256, r=1, s=1, stride_h=2,
                                         stride_w=2, pad_h=0, pad_w=0, dtype=tvg.TVG_BF16)) == (4, 128, 64)
     assert tvg.tvg_conv2d_get_plan(desc(n=1, c=64, h=56, w=56, k=64)) == (5, 32, 32)     # fp32, launch-bound
+    # ... with 16 x 16 tiles where 32 x 32 ones are at most 64 and the small ones need no second launch
+    assert tvg.tvg_conv2d_get_plan(desc(n=1, c=128, h=28, w=28, k=256, stride_h=2, stride_w=2)) == (5, 16, 16)
+    assert tvg.tvg_conv2d_get_plan(desc(n=1, c=256, h=14, w=14, k=256)) == (5, 16, 16)
+    assert tvg.tvg_conv2d_get_plan(desc(n=1, c=512, h=7, w=7, k=512)) == (5, 32, 32)     # (split either way)
     assert tvg.tvg_conv2d_get_plan(desc(n=1, c=60, h=56, w=56, k=64))[0] == 0            # channels not 8n
     assert tvg.tvg_conv2d_get_plan(desc(n=64, c=64, h=56, w=56, k=64))[0] == 0           # fills the chip
     assert tvg.tvg_conv2d_get_plan(desc(n=1, c=64, h=56, w=56, k=64, r=5, s=5, pad_h=2, pad_w=2))[0] == 0
