@@ -292,9 +292,9 @@ typedef enum {
     TVG_KERNEL_GENERIC = 0,        /* implicit GEMM with gathered operands, any shape      */
     TVG_KERNEL_3X3 = 1,            /* bf16 3x3, input patch in LDS, one stage              */
     TVG_KERNEL_3X3_PIPELINED = 2,  /* bf16 3x3, two LDS stages, software-pipelined         */
-    TVG_KERNEL_STEM = 3,           /* bf16 7x7 stride 2, few input channels                */
+    TVG_KERNEL_STEM = 3,           /* bf16 7x7 or 3x3 stride 2, few input channels (mt 64|32) */
     TVG_KERNEL_1X1 = 4,            /* bf16 1x1                                             */
-    TVG_KERNEL_F32_SMALL = 5,      /* fp32 1x1 / 3x3 of launch-bound problems, one launch  */
+    TVG_KERNEL_F32_SMALL = 5,      /* fp32 1x1 / 3x3 / 7x7 stem of launch-bound problems (mt = nt = 32 or 16; stem 32 x 64) */
     TVG_KERNEL_1X1_DEEP = 6        /* bf16 1x1 stride 1, reductions of 128 n channels       */
 } tvg_kernel;
 tvg_status tvg_conv2d_set_tile(const tvg_conv_desc *desc, int32_t mt, int32_t nt);
